@@ -1,0 +1,85 @@
+"""Feature tables, Glorot weights, target batches and the harness's upstream gradient."""
+import math
+import numpy as np
+import torch
+
+from .rmat import mix64, _s64
+
+
+def feature_table(V: int, d: int, dtype: str = "f32", seed: int = 2, device="cpu",
+                  rows_per_chunk: int = 1 << 22) -> torch.Tensor:
+    """[V x d] N(0,1) table, row-major.  Drawn from torch's generator of `device`, so a
+    table made on the GPU is not the table made on the host: consumers on the other side
+    read the rows they need from this tensor."""
+    tdtype = {"f32": torch.float32, "bf16": torch.bfloat16}[dtype]
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    out = torch.empty((V, d), dtype=tdtype, device=device)
+    for lo in range(0, V, rows_per_chunk):
+        hi = min(V, lo + rows_per_chunk)
+        blk = torch.randn((hi - lo, d), generator=gen, device=device, dtype=torch.float32)
+        out[lo:hi] = blk.to(tdtype)
+        del blk
+    return out
+
+
+def glorot_weights(dims, seed: int = 3, bias_scale: float = 0.0):
+    """Per layer i (1..k): W_self, W_nbr as float32 [d_{i-1} x d_i] drawn U(-a, a) with
+    a = sqrt(6 / (d_in + d_out)), and a bias vector (zero unless bias_scale > 0)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    w_self, w_nbr, bias = [], [], []
+    for d_in, d_out in zip(dims[:-1], dims[1:]):
+        a = math.sqrt(6.0 / (d_in + d_out))
+        w_self.append(rng.uniform(-a, a, size=(d_in, d_out)).astype(np.float32))
+        w_nbr.append(rng.uniform(-a, a, size=(d_in, d_out)).astype(np.float32))
+        bias.append((bias_scale * rng.standard_normal(d_out)).astype(np.float32))
+    return w_self, w_nbr, bias
+
+
+def training_subset(V: int, fraction: float, seed: int = 4, device="cpu", chunk: int = 1 << 26) -> torch.Tensor:
+    """Ascending ids of the nodes whose hash falls below `fraction` (all nodes if fraction >= 1)."""
+    if fraction >= 1.0:
+        return torch.arange(V, dtype=torch.int64, device=device)
+    thresh = int(fraction * (1 << 32))
+    key = _s64(seed * 0xA24BAED4963EE407)
+    parts = []
+    for lo in range(0, V, chunk):
+        hi = min(V, lo + chunk)
+        ids = torch.arange(lo, hi, dtype=torch.int64, device=device)
+        h = mix64(ids ^ key) & 0xFFFFFFFF
+        parts.append(ids[h < thresh])
+    return torch.cat(parts)
+
+
+def target_batch(pool_size: int, batch: int, batch_index: int, seed: int = 4, pool: torch.Tensor = None) -> np.ndarray:
+    """`batch` pairwise-distinct target node ids (int32), uniform over the pool, for mini-batch `batch_index`.
+
+    Distinctness by construction: positions i*stride + offset_i with offset_i < stride are
+    distinct, then shuffled; for a pool much larger than the batch this is a stratified
+    uniform draw."""
+    if batch > pool_size:
+        raise ValueError("batch larger than pool")
+    rng = np.random.Generator(np.random.PCG64([seed, batch_index]))
+    stride = pool_size // batch
+    pos = np.arange(batch, dtype=np.int64) * stride + rng.integers(0, stride, size=batch)
+    rng.shuffle(pos)
+    if pool is not None:
+        ids = pool[torch.from_numpy(pos).to(pool.device)].cpu().numpy()
+    else:
+        ids = pos
+    return ids.astype(np.int32)
+
+
+def class_labels(n: int, num_classes: int, seed: int = 5) -> np.ndarray:
+    rng = np.random.Generator(np.random.PCG64(seed))
+    return rng.integers(0, num_classes, size=n).astype(np.int64)
+
+
+def softmax_xent_grad(logits: np.ndarray, labels: np.ndarray) -> np.ndarray:
+    """Upstream gradient fed to the backward pass of both sides: d(mean cross-entropy)/d(logits)."""
+    z = logits.astype(np.float64)
+    z = z - z.max(axis=1, keepdims=True)
+    p = np.exp(z)
+    p /= p.sum(axis=1, keepdims=True)
+    p[np.arange(len(labels)), labels] -= 1.0
+    return (p / len(labels)).astype(np.float32)
