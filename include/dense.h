@@ -1,0 +1,158 @@
+/*
+ * dense.h -- C ABI of libdense_mi355x.so: DENSE mini-batch construction and the GraphSage-mean
+ * encoder that consumes it, on one MI355X (gfx950), graph and features resident in HBM.
+ *
+ * Citations are to the MariusGNN paper (arXiv 2202.02365): Section 4.1 / Algorithm 1
+ * (multi-hop sampling into DENSE), Section 4.2 (repr_map, H^0, Step 1 / Step 2,
+ * Algorithm 2 = DENSE update per layer, Algorithm 3 = layer aggregation), Section 2
+ * (the generic GNN layer and the backward pass), Section 7.1 (fanout order, directions).
+ *
+ * Conventions
+ *   - Every pointer whose name starts with d_ is a DEVICE pointer; everything else is host memory.
+ *   - The caller owns the graph, the feature table, weights, outputs and the workspaces it
+ *     hands over; the library allocates no device memory.  Handles (dn_graph, dn_batch,
+ *     dn_model) are small host objects; destroy them with the matching *_destroy.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
+ *     enqueued asynchronously; the only entry point that waits for the device is
+ *     dn_batch_counts.  Sizes that depend on the sample stay in device memory.
+ *   - Return value: DN_OK (0) or a negative DN_E* code; dn_last_error() then returns a
+ *     thread-local description.  No entry point aborts or throws.
+ *   - k = number of layers = number of hops, 1 <= k <= DN_MAX_LAYERS.  fanouts[h] is the
+ *     fanout of hop h, ordered AWAY from the targets (Section 7.1), 1 <= fanouts[h] <= 64.
+ *   - Delta_k = targets (caller order).  Delta_{k-1-h} = nodes first reached at hop h, in
+ *     ascending node id.  node_ids = Delta_0 | Delta_1 | ... | Delta_k (Algorithm 1 stacks
+ *     each new Delta in front).  Both offset arrays carry an end sentinel.
+ *   - Determinism: the same (graph, targets, fanouts, direction, seed) gives byte-identical
+ *     arrays, and the same inputs give bit-identical embeddings and gradients, run to run.
+ */
+#ifndef DENSE_MI355X_H
+#define DENSE_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* exported symbol */
+#define DN_API __attribute__((visibility("default")))
+
+#define DN_MAX_LAYERS 6
+#define DN_MAX_FANOUT 64
+
+enum {
+    DN_OK = 0,
+    DN_EINVAL = -1,     /* bad argument (null pointer, size or fanout out of range, unsupported dtype) */
+    DN_ECAPACITY = -2,  /* a workspace is too small for the request */
+    DN_EHIP = -3,       /* a HIP runtime call failed; dn_last_error() carries hipGetErrorString */
+    DN_ESTATE = -4,     /* call order violated (e.g. sage_backward before sage_forward) */
+    DN_ESAMPLE = -5     /* reported by dn_batch_counts: duplicate or out-of-range target id */
+};
+
+enum { DN_F32 = 0, DN_BF16 = 1 };
+enum { DN_DIR_OUT = 0, DN_DIR_IN = 1, DN_DIR_BOTH = 2 };
+
+typedef struct dn_graph dn_graph;
+typedef struct dn_batch dn_batch;
+typedef struct dn_model dn_model;
+
+/* Device pointers to the five arrays of one sampled mini-batch (valid until the next
+ * dense_sample on the same dn_batch).  Element counts are those of dn_batch_counts. */
+typedef struct dn_dense_view {
+    const int32_t* d_node_id_offsets; /* [k+2] start of Delta_0..Delta_k in node_ids, then N      */
+    const int32_t* d_node_ids;        /* [N]                                                      */
+    const int32_t* d_nbr_offsets;     /* [N - n_0 + 1] entry q: start in nbrs of the node at
+                                         position node_id_offsets[1]+q; last entry = E            */
+    const int32_t* d_nbrs;            /* [E] sampled neighbours, sequential per node              */
+    const int32_t* d_repr_map;        /* [E] position in node_ids (= row of H^0) of nbrs[j]       */
+} dn_dense_view;
+
+DN_API const char* dn_last_error(void);
+
+/* ---- graph store (Section 4.1: edges sorted by source and by destination with per-node offsets,
+ *      held here as CSR / CSC in HBM).  Borrows the caller's device buffers.
+ *      d_rowptr_* : int64[V+1]; d_col_* : int32[rowptr[V]].  The in-edge pair may be NULL when only
+ *      DN_DIR_OUT is sampled (and vice versa). */
+DN_API int  dn_graph_create(dn_graph** out, int64_t num_nodes,
+                     const int64_t* d_rowptr_out, const int32_t* d_col_out,
+                     const int64_t* d_rowptr_in, const int32_t* d_col_in);
+DN_API void dn_graph_destroy(dn_graph* g);
+
+/* ---- mini-batch object: capacities and workspace.
+ *      dn_batch_workspace_size: bytes of device workspace needed for batches of at most
+ *      max_targets targets on a graph of num_nodes nodes (upper bound max_targets * prod(fanouts),
+ *      capped by num_nodes; twice the fanout per hop for DN_DIR_BOTH).
+ *      dn_batch_create: binds the workspace (256-byte aligned, owned by the caller, must outlive
+ *      the batch) and zeroes the part that must start at zero on `stream`. */
+DN_API int  dn_batch_workspace_size(int64_t num_nodes, int32_t max_targets, int32_t k, const int32_t* fanouts,
+                             int32_t direction, size_t* bytes);
+DN_API int  dn_batch_create(dn_batch** out, int64_t num_nodes, int32_t max_targets, int32_t k,
+                     const int32_t* fanouts, int32_t direction,
+                     void* d_workspace, size_t workspace_bytes, void* stream);
+DN_API void dn_batch_destroy(dn_batch* b);
+/* Capacities the workspace was sized for: rows of node_ids / H^0, and neighbour slots. */
+DN_API int  dn_batch_capacity(const dn_batch* b, int64_t* node_capacity, int64_t* slot_capacity);
+
+/* ---- dense_sample: Algorithm 1.  One-hop sampling (Section 4.1: a node with more than f neighbours
+ *      gets f of them, otherwise all) is uniform without replacement over adjacency positions by
+ *      Floyd's subset algorithm; step s of node v at hop h draws word (s & 3) of
+ *      Philox4x32-10(counter = (s >> 2, v, h, direction bit), key = (seed lo, seed hi)) and maps
+ *      it to [0, deg - f + s] by a 32-bit multiply-high.  Neighbours are stored in Floyd
+ *      insertion order (adjacency order when deg <= f); for DN_DIR_BOTH a node's segment is its
+ *      out-sample followed by its in-sample.  Also builds repr_map (Section 4.2).
+ *      d_targets: int32[n_targets], pairwise distinct ids in [0, V); a violation is reported by
+ *      the next dn_batch_counts as DN_ESAMPLE (the arrays are then unspecified but in bounds). */
+DN_API int  dense_sample(dn_batch* b, const dn_graph* g, const int32_t* d_targets, int32_t n_targets,
+                  uint64_t seed, void* stream);
+
+/* Device pointers of the current sample. */
+DN_API int  dn_batch_view(const dn_batch* b, dn_dense_view* view);
+
+/* Copies node_id_offsets[0..k+1] followed by E (k+3 values) to host_counts and WAITS for `stream`.
+ * Returns DN_ESAMPLE if the last dense_sample saw an invalid target set. */
+DN_API int  dn_batch_counts(const dn_batch* b, int64_t* host_counts, void* stream);
+
+/* ---- dense_gather: H^0[r, :] = table[node_ids[r], :] for r < N (Section 4.2).
+ *      d_table: [V x dim] row-major with row stride ld_elems elements, dtype DN_F32 or DN_BF16.
+ *      d_H0:    [N x dim] dense row-major, same dtype, capacity >= the batch's node capacity rows. */
+DN_API int  dense_gather(const dn_batch* b, const void* d_table, int32_t dtype, int32_t dim, int64_t ld_elems,
+                  void* d_H0, void* stream);
+
+/* ---- GraphSage-mean encoder.  dims[0..k]: dims[0] = width of H^0, dims[i] = width of layer i.
+ *      Layer i (Step 1 + Algorithm 3 with mean, Algorithm 2 applied as offset arithmetic):
+ *        M[p]   = mean over p's neighbour slots j of H^{i-1}[repr_map[j]]   (0 when p has none),
+ *                 fp32 sum in ascending slot order, fp32 division
+ *        Z[p]   = bf16(H^{i-1}[p]) W_self^i + bf16(M[p]) W_nbr^i + b^i     bf16 MFMA operands, fp32 accumulate
+ *        H^i[p] = ReLU(Z[p]) for i < k, Z[p] for i = k                      stored fp32
+ *      for every node p of node_ids after Delta_{i-1}.
+ *      dn_model_workspace_size / dn_model_create: workspace for activations saved for the backward
+ *      pass and for backward temporaries, sized from the batch's capacities; in_dtype = dtype of H^0.
+ *      dn_model_set_weights: d_w_self[i-1], d_w_nbr[i-1]: fp32 [dims[i-1] x dims[i]] row-major,
+ *      d_bias[i-1]: fp32 [dims[i]]; converted once to the bf16 layouts the kernels use (call it
+ *      again after every optimiser step). */
+DN_API int  dn_model_workspace_size(const dn_batch* b, int32_t k, const int32_t* dims, int32_t in_dtype, size_t* bytes);
+DN_API int  dn_model_create(dn_model** out, const dn_batch* b, int32_t k, const int32_t* dims, int32_t in_dtype,
+                     void* d_workspace, size_t workspace_bytes, void* stream);
+DN_API int  dn_model_set_weights(dn_model* m, const float* const* d_w_self, const float* const* d_w_nbr,
+                          const float* const* d_bias, void* stream);
+DN_API void dn_model_destroy(dn_model* m);
+
+/* sage_forward: d_H0 = output of dense_gather (dtype in_dtype); d_out: fp32 [n_targets x dims[k]],
+ * row t = embedding of target t (caller order). */
+DN_API int  sage_forward(dn_model* m, const dn_batch* b, const void* d_H0, float* d_out, void* stream);
+
+/* sage_backward (Section 2: "loss and gradients"): given d_grad_out = dL/dH^k, fp32
+ * [n_targets x dims[k]], writes dL/dW_self^i, dL/dW_nbr^i (fp32 [dims[i-1] x dims[i]]) and dL/db^i
+ * (fp32 [dims[i]]) for every layer, and, when d_dH0 is not NULL, dL/dH^0 (fp32 [N x dims[0]],
+ * capacity >= node capacity rows; needed for learnable base representations).  Uses the
+ * activations saved by the last sage_forward on the same model and batch.  Neighbour-mean
+ * gradients are summed per input row in ascending slot order (no floating-point atomics). */
+DN_API int  sage_backward(dn_model* m, const dn_batch* b, const float* d_grad_out,
+                   float* const* d_dw_self, float* const* d_dw_nbr, float* const* d_dbias,
+                   float* d_dH0, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DENSE_MI355X_H */

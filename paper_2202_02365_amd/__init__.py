@@ -1,0 +1,13 @@
+"""MI355X-native DENSE mini-batch construction + GraphSage-mean encoder (arXiv 2202.02365 hot path).
+
+Thin Python binding over libdense_mi355x.so (hand-written HIP for gfx950).  Argument
+marshalling only: every step runs in the library's kernels.  PyTorch supplies device memory
+and streams.  There is no CPU fallback: if the library is missing, loading raises.
+"""
+from .binding import (DN_F32, DN_BF16, DN_DIR_OUT, DN_DIR_IN, DN_DIR_BOTH, DenseError, Graph, Batch, Model,
+                      dense_sample, dense_gather, sage_forward, sage_backward, library_path, load_library,
+                      declared_symbols)
+
+__all__ = ["DN_F32", "DN_BF16", "DN_DIR_OUT", "DN_DIR_IN", "DN_DIR_BOTH", "DenseError", "Graph", "Batch", "Model",
+           "dense_sample", "dense_gather", "sage_forward", "sage_backward", "library_path", "load_library",
+           "declared_symbols"]

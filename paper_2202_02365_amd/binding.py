@@ -1,0 +1,245 @@
+"""ctypes binding of include/dense.h.  Same entry-point names; marshalling only."""
+import ctypes
+import os
+import re
+from typing import List, Optional, Sequence
+
+import torch
+
+DN_F32, DN_BF16 = 0, 1
+DN_DIR_OUT, DN_DIR_IN, DN_DIR_BOTH = 0, 1, 2
+DN_MAX_LAYERS = 6
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_HEADER = os.path.join(os.path.dirname(_PKG), "include", "dense.h")
+_lib = None
+
+
+class DenseError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__("libdense_mi355x error %d: %s" % (code, message))
+        self.code = code
+
+
+class _View(ctypes.Structure):
+    _fields_ = [("node_id_offsets", ctypes.c_void_p), ("node_ids", ctypes.c_void_p),
+                ("nbr_offsets", ctypes.c_void_p), ("nbrs", ctypes.c_void_p), ("repr_map", ctypes.c_void_p)]
+
+
+def library_path() -> str:
+    return os.path.join(_PKG, "libdense_mi355x.so")
+
+
+def declared_symbols() -> List[str]:
+    """Names of every entry point include/dense.h declares."""
+    text = open(_HEADER).read()
+    return re.findall(r"DN_API\s+[\w\s\*]+?\b(\w+)\s*\(", text)
+
+
+def load_library():
+    """Loads the HIP library built in-tree.  Raises if it has not been built: there is no fallback."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        raise FileNotFoundError("%s is missing: run `python -c 'import __graft_entry__ as g; g.build()'`" % path)
+    lib = ctypes.CDLL(path)
+    vp, i32, i64, u64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64, ctypes.c_size_t
+    pp = ctypes.POINTER(ctypes.c_void_p)
+    sig = {
+        "dn_last_error": (ctypes.c_char_p, []),
+        "dn_graph_create": (ctypes.c_int, [pp, i64, vp, vp, vp, vp]),
+        "dn_graph_destroy": (None, [vp]),
+        "dn_batch_workspace_size": (ctypes.c_int, [i64, i32, i32, ctypes.POINTER(i32), i32, ctypes.POINTER(sz)]),
+        "dn_batch_create": (ctypes.c_int, [pp, i64, i32, i32, ctypes.POINTER(i32), i32, vp, sz, vp]),
+        "dn_batch_destroy": (None, [vp]),
+        "dn_batch_capacity": (ctypes.c_int, [vp, ctypes.POINTER(i64), ctypes.POINTER(i64)]),
+        "dense_sample": (ctypes.c_int, [vp, vp, vp, i32, u64, vp]),
+        "dn_batch_view": (ctypes.c_int, [vp, ctypes.POINTER(_View)]),
+        "dn_batch_counts": (ctypes.c_int, [vp, ctypes.POINTER(i64), vp]),
+        "dense_gather": (ctypes.c_int, [vp, vp, i32, i32, i64, vp, vp]),
+        "dn_model_workspace_size": (ctypes.c_int, [vp, i32, ctypes.POINTER(i32), i32, ctypes.POINTER(sz)]),
+        "dn_model_create": (ctypes.c_int, [pp, vp, i32, ctypes.POINTER(i32), i32, vp, sz, vp]),
+        "dn_model_set_weights": (ctypes.c_int, [vp, pp, pp, pp, vp]),
+        "dn_model_destroy": (None, [vp]),
+        "sage_forward": (ctypes.c_int, [vp, vp, vp, vp, vp]),
+        "sage_backward": (ctypes.c_int, [vp, vp, vp, pp, pp, pp, vp, vp]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = lib
+    return lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise DenseError(rc, load_library().dn_last_error().decode())
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev_ptr(t: Optional[torch.Tensor], dtype=None) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous CUDA tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError("expected dtype %s, got %s" % (dtype, t.dtype))
+    return t.data_ptr()
+
+
+def _i32_array(values: Sequence[int]):
+    return (ctypes.c_int32 * len(values))(*[int(v) for v in values])
+
+
+def _ptr_array(tensors: Sequence[torch.Tensor]):
+    return (ctypes.c_void_p * len(tensors))(*[_dev_ptr(t, torch.float32) for t in tensors])
+
+
+def _alloc_workspace(nbytes: int, device) -> torch.Tensor:
+    ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
+    shift = (-ws.data_ptr()) % 256
+    return ws[shift:shift + nbytes]
+
+
+class Graph:
+    """CSR by source (out-edges) and optionally by destination (in-edges), resident in HBM."""
+
+    def __init__(self, rowptr_out: Optional[torch.Tensor], col_out: Optional[torch.Tensor],
+                 rowptr_in: Optional[torch.Tensor] = None, col_in: Optional[torch.Tensor] = None):
+        lib = load_library()
+        ref = rowptr_out if rowptr_out is not None else rowptr_in
+        self.num_nodes = ref.numel() - 1
+        self._keep = (rowptr_out, col_out, rowptr_in, col_in)
+        h = ctypes.c_void_p()
+        _check(lib.dn_graph_create(ctypes.byref(h), self.num_nodes,
+                                   _dev_ptr(rowptr_out, torch.int64), _dev_ptr(col_out, torch.int32),
+                                   _dev_ptr(rowptr_in, torch.int64), _dev_ptr(col_in, torch.int32)))
+        self.handle = h
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.dn_graph_destroy(self.handle)
+            self.handle = None
+
+
+class Batch:
+    """One mini-batch slot: workspace sized for max_targets targets and the given fanouts."""
+
+    def __init__(self, num_nodes: int, max_targets: int, fanouts: Sequence[int], direction: int = DN_DIR_OUT,
+                 device="cuda"):
+        lib = load_library()
+        self.k = len(fanouts)
+        self.fanouts = list(fanouts)
+        self.direction = direction
+        fan = _i32_array(fanouts)
+        nbytes = ctypes.c_size_t()
+        _check(lib.dn_batch_workspace_size(num_nodes, max_targets, self.k, fan, direction, ctypes.byref(nbytes)))
+        self.workspace = _alloc_workspace(nbytes.value, device)
+        h = ctypes.c_void_p()
+        _check(lib.dn_batch_create(ctypes.byref(h), num_nodes, max_targets, self.k, fan, direction,
+                                   self.workspace.data_ptr(), nbytes.value, _stream()))
+        self.handle = h
+        nc, sc = ctypes.c_int64(), ctypes.c_int64()
+        _check(lib.dn_batch_capacity(h, ctypes.byref(nc), ctypes.byref(sc)))
+        self.node_capacity, self.slot_capacity = nc.value, sc.value
+        self._targets = None
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.dn_batch_destroy(self.handle)
+            self.handle = None
+
+    def counts(self) -> List[int]:
+        """[node_id_offsets[0..k+1]..., E]; waits for the stream."""
+        buf = (ctypes.c_int64 * (self.k + 3))()
+        _check(load_library().dn_batch_counts(self.handle, buf, _stream()))
+        return list(buf)
+
+    def _wrap(self, ptr: int, count: int) -> torch.Tensor:
+        off = ptr - self.workspace.data_ptr()
+        return self.workspace[off:off + 4 * count].view(torch.int32)
+
+    def view(self):
+        """The five DENSE arrays as int32 CUDA tensors aliasing the workspace (calls counts())."""
+        c = self.counts()
+        n, e, n0 = c[self.k + 1], c[self.k + 2], c[1]
+        v = _View()
+        _check(load_library().dn_batch_view(self.handle, ctypes.byref(v)))
+        return {"node_id_offsets": self._wrap(v.node_id_offsets, self.k + 2),
+                "node_ids": self._wrap(v.node_ids, n),
+                "nbr_offsets": self._wrap(v.nbr_offsets, n - n0 + 1),
+                "nbrs": self._wrap(v.nbrs, e),
+                "repr_map": self._wrap(v.repr_map, e)}
+
+
+class Model:
+    """GraphSage-mean encoder bound to a batch's capacities."""
+
+    def __init__(self, batch: Batch, dims: Sequence[int], in_dtype: int = DN_F32, device="cuda"):
+        lib = load_library()
+        self.k = len(dims) - 1
+        self.dims = list(dims)
+        self.in_dtype = in_dtype
+        d = _i32_array(dims)
+        nbytes = ctypes.c_size_t()
+        _check(lib.dn_model_workspace_size(batch.handle, self.k, d, in_dtype, ctypes.byref(nbytes)))
+        self.workspace = _alloc_workspace(nbytes.value, device)
+        h = ctypes.c_void_p()
+        _check(lib.dn_model_create(ctypes.byref(h), batch.handle, self.k, d, in_dtype, self.workspace.data_ptr(),
+                                   nbytes.value, _stream()))
+        self.handle = h
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.dn_model_destroy(self.handle)
+            self.handle = None
+
+    def set_weights(self, w_self: Sequence[torch.Tensor], w_nbr: Sequence[torch.Tensor], bias: Sequence[torch.Tensor]):
+        for i in range(self.k):
+            assert tuple(w_self[i].shape) == (self.dims[i], self.dims[i + 1]) == tuple(w_nbr[i].shape)
+            assert tuple(bias[i].shape) == (self.dims[i + 1],)
+        _check(load_library().dn_model_set_weights(self.handle, _ptr_array(w_self), _ptr_array(w_nbr),
+                                                   _ptr_array(bias), _stream()))
+
+
+def dense_sample(batch: Batch, graph: Graph, targets: torch.Tensor, seed: int) -> None:
+    """Algorithm 1 on the device; results stay in the batch (see Batch.view / Batch.counts)."""
+    n = targets.numel()
+    batch._targets = targets
+    _check(load_library().dense_sample(batch.handle, graph.handle, _dev_ptr(targets, torch.int32) if n else None,
+                                       n, seed & 0xFFFFFFFFFFFFFFFF, _stream()))
+
+
+def dense_gather(batch: Batch, table: torch.Tensor, out: torch.Tensor) -> torch.Tensor:
+    """out[r] = table[node_ids[r]] for the batch's N nodes; out has node_capacity rows."""
+    dtype = {torch.float32: DN_F32, torch.bfloat16: DN_BF16}[table.dtype]
+    assert out.dtype == table.dtype and out.shape[1] == table.shape[1] and out.shape[0] >= batch.node_capacity
+    assert table.stride(1) == 1
+    _check(load_library().dense_gather(batch.handle, table.data_ptr(), dtype, table.shape[1], table.stride(0),
+                                       _dev_ptr(out), _stream()))
+    return out
+
+
+def sage_forward(model: Model, batch: Batch, h0: torch.Tensor, out: torch.Tensor) -> torch.Tensor:
+    """out[t] = H^k of target t (fp32 [n_targets x dims[k]])."""
+    want = torch.float32 if model.in_dtype == DN_F32 else torch.bfloat16
+    assert h0.dtype == want and h0.shape[1] == model.dims[0] and h0.shape[0] >= batch.node_capacity
+    assert out.shape[1] == model.dims[-1]
+    _check(load_library().sage_forward(model.handle, batch.handle, _dev_ptr(h0), _dev_ptr(out, torch.float32), _stream()))
+    return out
+
+
+def sage_backward(model: Model, batch: Batch, grad_out: torch.Tensor, d_w_self: Sequence[torch.Tensor],
+                  d_w_nbr: Sequence[torch.Tensor], d_bias: Sequence[torch.Tensor],
+                  d_h0: Optional[torch.Tensor] = None) -> None:
+    if d_h0 is not None:
+        assert d_h0.shape[0] >= batch.node_capacity and d_h0.shape[1] == model.dims[0]
+    _check(load_library().sage_backward(model.handle, batch.handle, _dev_ptr(grad_out, torch.float32),
+                                        _ptr_array(d_w_self), _ptr_array(d_w_nbr), _ptr_array(d_bias),
+                                        _dev_ptr(d_h0, torch.float32), _stream()))

@@ -1,0 +1,360 @@
+// The C ABI of libdense_mi355x.so: argument checking, handle bookkeeping, workspace carve-up.
+// Every step of the hot path runs in the kernels behind the dn_launch_* calls.
+#include "dn_internal.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <algorithm>
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+struct Carver {          // hands out 256-byte aligned pieces of one workspace; counts when base == nullptr
+    char* base;
+    size_t off = 0;
+    explicit Carver(void* b) : base(static_cast<char*>(b)) {}
+    template <typename T>
+    T* take(int64_t count)
+    {
+        off = (off + 255) & ~size_t(255);
+        T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+        off += sizeof(T) * (size_t)(count > 0 ? count : 0);
+        return p;
+    }
+    size_t bytes() const { return (off + 255) & ~size_t(255); }
+};
+
+int fill_batch_caps(dn_batch* b, int64_t V, int32_t max_targets, int32_t k, const int32_t* fanouts, int32_t direction)
+{
+    if (V < 1 || V > 0x7fffffffLL) return dn_fail(DN_EINVAL, "num_nodes must be in [1, 2^31)");
+    if (k < 1 || k > DN_MAX_LAYERS) return dn_fail(DN_EINVAL, "k must be in [1, %d]", DN_MAX_LAYERS);
+    if (!fanouts) return dn_fail(DN_EINVAL, "fanouts is null");
+    if (max_targets < 1) return dn_fail(DN_EINVAL, "max_targets must be positive");
+    if (direction < DN_DIR_OUT || direction > DN_DIR_BOTH) return dn_fail(DN_EINVAL, "direction must be 0, 1 or 2");
+    const int mult = direction == DN_DIR_BOTH ? 2 : 1;
+    std::memset(b, 0, sizeof(*b));
+    b->V = V; b->k = k; b->direction = direction; b->max_targets = max_targets;
+    b->cap_level[0] = max_targets < V ? max_targets : V;
+    b->cap_nodes = b->cap_level[0];
+    b->cap_slots = 0;
+    for (int h = 0; h < k; ++h) {
+        if (fanouts[h] < 1 || fanouts[h] > DN_MAX_FANOUT)
+            return dn_fail(DN_EINVAL, "fanouts[%d] = %d is outside [1, %d]", h, fanouts[h], DN_MAX_FANOUT);
+        b->fanouts[h] = fanouts[h];
+        b->cap_slots_hop[h] = b->cap_level[h] * fanouts[h] * mult;
+        b->cap_slots += b->cap_slots_hop[h];
+        b->cap_level[h + 1] = b->cap_slots_hop[h] < V ? b->cap_slots_hop[h] : V;
+        b->cap_nodes += b->cap_level[h + 1];
+    }
+    if (b->cap_nodes > V) b->cap_nodes = V;
+    if (b->cap_slots > 0x7fffff00LL) return dn_fail(DN_ECAPACITY, "more than 2^31 neighbour slots per batch");
+    b->words0 = (V + 31) / 32;
+    b->words1 = (b->words0 + 31) / 32;
+    const int64_t blocks_words = (b->words1 + 255) / 256, blocks_targets = (max_targets + 255) / 256;
+    b->max_blocks = (int32_t)(blocks_words > blocks_targets ? blocks_words : blocks_targets);
+    return DN_OK;
+}
+
+void carve_batch(dn_batch* b, Carver& c)
+{
+    b->hdr = c.take<int32_t>(DN_HDR_WORDS);
+    b->seen = c.take<uint32_t>(b->words0);
+    b->fresh = c.take<uint32_t>(b->words0);
+    b->summary = c.take<uint32_t>(b->words1);
+    b->lvlpos = c.take<int32_t>(b->V);
+    b->lvl_ids = c.take<int32_t>(b->cap_nodes);
+    b->lvl_nbr_offsets = c.take<int32_t>(b->cap_nodes + 1);
+    b->lvl_nbrs = c.take<int32_t>(b->cap_slots);
+    b->lvl_owner = c.take<int32_t>(b->cap_slots);
+    b->blk_a = c.take<int32_t>(2 * (int64_t)b->max_blocks + 2);    // used as uint64[max_blocks]
+    b->blk_b = nullptr;
+    b->node_ids = c.take<int32_t>(b->cap_nodes);
+    b->nbr_offsets = c.take<int32_t>(b->cap_nodes + 1);
+    b->nbrs = c.take<int32_t>(b->cap_slots);
+    b->repr_map = c.take<int32_t>(b->cap_slots);
+    b->slot_owner = c.take<int32_t>(b->cap_slots);
+    for (int i = 0; i < 2; ++i) {
+        b->tr_key[i] = c.take<int32_t>(b->cap_slots);
+        b->tr_val[i] = c.take<int32_t>(b->cap_slots);
+    }
+    b->tr_ptr = c.take<int32_t>(b->cap_nodes + 2);
+    const int64_t tiles = (b->cap_slots + 2047) / 2048;
+    b->tr_hist_words = 256 * tiles + (256 * tiles + 2047) / 2048 + 16;
+    b->tr_hist = c.take<int32_t>(b->tr_hist_words);
+}
+
+int fill_model(dn_model* m, const dn_batch* b, int32_t k, const int32_t* dims, int32_t in_dtype)
+{
+    if (!b) return dn_fail(DN_EINVAL, "batch is null");
+    if (k != b->k) return dn_fail(DN_EINVAL, "model has %d layers, the batch samples %d hops", k, b->k);
+    if (!dims) return dn_fail(DN_EINVAL, "dims is null");
+    if (in_dtype != DN_F32 && in_dtype != DN_BF16) return dn_fail(DN_EINVAL, "in_dtype must be DN_F32 or DN_BF16");
+    std::memset(m, 0, sizeof(*m));
+    m->k = k; m->in_dtype = in_dtype;
+    for (int i = 0; i <= k; ++i) {
+        if (dims[i] < 1 || dims[i] > 16384) return dn_fail(DN_EINVAL, "dims[%d] = %d is outside [1, 16384]", i, dims[i]);
+        m->dims[i] = dims[i];
+    }
+    // rows of layer i = nodes of Delta_i .. Delta_k = levels 0 .. k-i
+    for (int i = 1; i <= k; ++i) {
+        dn_layer_bufs& L = m->layer[i - 1];
+        L.d_in = dims[i - 1]; L.d_out = dims[i];
+        L.kp = (int32_t)dn_round_up(2 * (int64_t)L.d_in, 64);
+        L.np = (int32_t)dn_round_up(L.d_out, 64);
+        int64_t rows = 0;
+        for (int h = 0; h <= k - i; ++h) rows += b->cap_level[h];
+        if (rows > b->V) rows = b->V;
+        L.rows_cap = rows;
+        L.rows_pad = dn_round_up(rows, 128);
+    }
+    return DN_OK;
+}
+
+void carve_model(dn_model* m, const dn_batch* b, Carver& c)
+{
+    const int k = m->k;
+    int64_t max_dzb = 0, max_dzbt = 0, max_xt = 0, max_dx = 0, max_g = 0, max_w = 0, max_db = 0;
+    for (int i = 1; i <= k; ++i) {
+        dn_layer_bufs& L = m->layer[i - 1];
+        L.x = c.take<dn_bf16>(L.rows_pad * L.kp);
+        L.h = (i < k) ? c.take<float>(L.rows_pad * L.d_out) : nullptr;
+        L.wt = c.take<dn_bf16>(dn_round_up(L.d_out, 128) * L.kp);
+        L.w = c.take<dn_bf16>(dn_round_up(2 * (int64_t)L.d_in, 128) * L.np);
+        L.bias = c.take<float>(L.d_out);
+        max_dzb = std::max<int64_t>(max_dzb, L.rows_pad * L.np);
+        max_dzbt = std::max<int64_t>(max_dzbt, dn_round_up(L.d_out, 128) * L.rows_pad);
+        max_xt = std::max<int64_t>(max_xt, dn_round_up(L.kp, 128) * L.rows_pad);
+        max_dx = std::max<int64_t>(max_dx, L.rows_pad * L.kp);
+        max_w = std::max<int64_t>(max_w, 2 * (int64_t)L.d_in * L.d_out);
+        max_db = std::max<int64_t>(max_db, ((L.rows_cap + 63) / 64 + 1) * L.d_out);
+        if (i < k) max_g = std::max<int64_t>(max_g, L.rows_pad * L.d_out);   // gradient w.r.t. H^i
+    }
+    m->dzb = c.take<dn_bf16>(max_dzb);
+    m->dzbt = c.take<dn_bf16>(max_dzbt);
+    m->xt = c.take<dn_bf16>(max_xt);
+    m->dx = c.take<float>(max_dx);
+    m->g[0] = c.take<float>(max_g);
+    m->g[1] = c.take<float>(max_g);
+    m->splits = 32;
+    m->partial_floats = (int64_t)m->splits * max_w;
+    m->partial = c.take<float>(m->partial_floats);
+    m->db_partial = c.take<float>(max_db);
+    (void)b;
+}
+
+}  // namespace
+
+int dn_fail(int code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+extern "C" {
+
+const char* dn_last_error(void) { return g_err; }
+
+int dn_graph_create(dn_graph** out, int64_t num_nodes, const int64_t* d_rowptr_out, const int32_t* d_col_out,
+                    const int64_t* d_rowptr_in, const int32_t* d_col_in)
+{
+    if (!out) return dn_fail(DN_EINVAL, "out is null");
+    if (num_nodes < 1 || num_nodes > 0x7fffffffLL) return dn_fail(DN_EINVAL, "num_nodes must be in [1, 2^31)");
+    if (!d_rowptr_out && !d_rowptr_in) return dn_fail(DN_EINVAL, "no adjacency given");
+    if ((d_rowptr_out && !d_col_out) || (d_rowptr_in && !d_col_in)) return dn_fail(DN_EINVAL, "rowptr without col");
+    dn_graph* g = new (std::nothrow) dn_graph;
+    if (!g) return dn_fail(DN_EINVAL, "out of host memory");
+    g->V = num_nodes;
+    g->rowptr[0] = d_rowptr_out; g->col[0] = d_col_out;
+    g->rowptr[1] = d_rowptr_in;  g->col[1] = d_col_in;
+    *out = g;
+    return DN_OK;
+}
+
+void dn_graph_destroy(dn_graph* g) { delete g; }
+
+int dn_batch_workspace_size(int64_t num_nodes, int32_t max_targets, int32_t k, const int32_t* fanouts,
+                            int32_t direction, size_t* bytes)
+{
+    if (!bytes) return dn_fail(DN_EINVAL, "bytes is null");
+    dn_batch tmp;
+    int rc = fill_batch_caps(&tmp, num_nodes, max_targets, k, fanouts, direction);
+    if (rc) return rc;
+    Carver c(nullptr);
+    carve_batch(&tmp, c);
+    *bytes = c.bytes();
+    return DN_OK;
+}
+
+int dn_batch_create(dn_batch** out, int64_t num_nodes, int32_t max_targets, int32_t k, const int32_t* fanouts,
+                    int32_t direction, void* d_workspace, size_t workspace_bytes, void* stream)
+{
+    if (!out) return dn_fail(DN_EINVAL, "out is null");
+    if (!d_workspace || ((uintptr_t)d_workspace & 255)) return dn_fail(DN_EINVAL, "workspace must be non-null and 256-byte aligned");
+    dn_batch* b = new (std::nothrow) dn_batch;
+    if (!b) return dn_fail(DN_EINVAL, "out of host memory");
+    int rc = fill_batch_caps(b, num_nodes, max_targets, k, fanouts, direction);
+    if (rc) { delete b; return rc; }
+    Carver c(d_workspace);
+    carve_batch(b, c);
+    if (c.bytes() > workspace_bytes) {
+        delete b;
+        return dn_fail(DN_ECAPACITY, "workspace has %zu bytes, %zu needed", workspace_bytes, c.bytes());
+    }
+    b->workspace_bytes = c.bytes();
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // header and the three bitmaps are contiguous at the front: they must start at zero
+    const size_t zero_bytes = (size_t)(reinterpret_cast<char*>(b->lvlpos) - reinterpret_cast<char*>(b->hdr));
+    hipError_t e = hipMemsetAsync(b->hdr, 0, zero_bytes, st);
+    if (e != hipSuccess) { delete b; return dn_fail(DN_EHIP, "hipMemsetAsync: %s", hipGetErrorString(e)); }
+    b->sample_serial = 0;
+    b->tr_serial = ~0ull;
+    *out = b;
+    return DN_OK;
+}
+
+void dn_batch_destroy(dn_batch* b) { delete b; }
+
+int dn_batch_capacity(const dn_batch* b, int64_t* node_capacity, int64_t* slot_capacity)
+{
+    if (!b) return dn_fail(DN_EINVAL, "batch is null");
+    if (node_capacity) *node_capacity = b->cap_nodes;
+    if (slot_capacity) *slot_capacity = b->cap_slots;
+    return DN_OK;
+}
+
+int dense_sample(dn_batch* b, const dn_graph* g, const int32_t* d_targets, int32_t n_targets, uint64_t seed, void* stream)
+{
+    if (!b || !g) return dn_fail(DN_EINVAL, "batch or graph is null");
+    if (g->V != b->V) return dn_fail(DN_EINVAL, "graph has %lld nodes, the batch was created for %lld", (long long)g->V, (long long)b->V);
+    if (n_targets < 0 || n_targets > b->max_targets)
+        return dn_fail(DN_ECAPACITY, "n_targets = %d is outside [0, %d]", n_targets, b->max_targets);
+    if (n_targets > 0 && !d_targets) return dn_fail(DN_EINVAL, "d_targets is null");
+    if (b->direction != DN_DIR_IN && !g->rowptr[0]) return dn_fail(DN_EINVAL, "the graph has no out-edge adjacency");
+    if (b->direction != DN_DIR_OUT && !g->rowptr[1]) return dn_fail(DN_EINVAL, "the graph has no in-edge adjacency");
+    b->n_targets = n_targets;
+    b->sample_serial += 1;
+    return dn_launch_sample(b, g, d_targets, n_targets, seed, static_cast<hipStream_t>(stream));
+}
+
+int dn_batch_view(const dn_batch* b, dn_dense_view* view)
+{
+    if (!b || !view) return dn_fail(DN_EINVAL, "batch or view is null");
+    view->d_node_id_offsets = b->hdr + HDR_NODE_OFF;
+    view->d_node_ids = b->node_ids;
+    view->d_nbr_offsets = b->nbr_offsets;
+    view->d_nbrs = b->nbrs;
+    view->d_repr_map = b->repr_map;
+    return DN_OK;
+}
+
+int dn_batch_counts(const dn_batch* b, int64_t* host_counts, void* stream)
+{
+    if (!b || !host_counts) return dn_fail(DN_EINVAL, "batch or host_counts is null");
+    if (b->sample_serial == 0) return dn_fail(DN_ESTATE, "dense_sample has not run on this batch");
+    int32_t h[DN_HDR_WORDS];
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    DN_HIP(hipMemcpyAsync(h, b->hdr, sizeof(h), hipMemcpyDeviceToHost, st));
+    DN_HIP(hipStreamSynchronize(st));
+    for (int j = 0; j <= b->k + 1; ++j) host_counts[j] = h[HDR_NODE_OFF + j];
+    host_counts[b->k + 2] = h[HDR_E];
+    if (h[HDR_STATUS] & (ST_BAD_TARGET | ST_DUP_TARGET))
+        return dn_fail(DN_ESAMPLE, "dense_sample: %s", (h[HDR_STATUS] & ST_BAD_TARGET) ? "target id out of range" : "duplicate target id");
+    if (h[HDR_STATUS] & ST_CAPACITY) return dn_fail(DN_ECAPACITY, "dense_sample: node capacity exceeded");
+    return DN_OK;
+}
+
+int dense_gather(const dn_batch* b, const void* d_table, int32_t dtype, int32_t dim, int64_t ld_elems, void* d_H0, void* stream)
+{
+    if (!b || !d_table || !d_H0) return dn_fail(DN_EINVAL, "null argument");
+    if (dtype != DN_F32 && dtype != DN_BF16) return dn_fail(DN_EINVAL, "dtype must be DN_F32 or DN_BF16");
+    if (dim < 1 || ld_elems < dim) return dn_fail(DN_EINVAL, "dim = %d, ld_elems = %lld", dim, (long long)ld_elems);
+    if (b->sample_serial == 0) return dn_fail(DN_ESTATE, "dense_sample has not run on this batch");
+    return dn_launch_gather(b, d_table, dtype, dim, ld_elems, d_H0, static_cast<hipStream_t>(stream));
+}
+
+int dn_model_workspace_size(const dn_batch* b, int32_t k, const int32_t* dims, int32_t in_dtype, size_t* bytes)
+{
+    if (!bytes) return dn_fail(DN_EINVAL, "bytes is null");
+    dn_model tmp;
+    int rc = fill_model(&tmp, b, k, dims, in_dtype);
+    if (rc) return rc;
+    Carver c(nullptr);
+    carve_model(&tmp, b, c);
+    *bytes = c.bytes();
+    return DN_OK;
+}
+
+int dn_model_create(dn_model** out, const dn_batch* b, int32_t k, const int32_t* dims, int32_t in_dtype,
+                    void* d_workspace, size_t workspace_bytes, void* stream)
+{
+    if (!out) return dn_fail(DN_EINVAL, "out is null");
+    if (!d_workspace || ((uintptr_t)d_workspace & 255)) return dn_fail(DN_EINVAL, "workspace must be non-null and 256-byte aligned");
+    dn_model* m = new (std::nothrow) dn_model;
+    if (!m) return dn_fail(DN_EINVAL, "out of host memory");
+    int rc = fill_model(m, b, k, dims, in_dtype);
+    if (rc) { delete m; return rc; }
+    Carver c(d_workspace);
+    carve_model(m, b, c);
+    if (c.bytes() > workspace_bytes) {
+        delete m;
+        return dn_fail(DN_ECAPACITY, "workspace has %zu bytes, %zu needed", workspace_bytes, c.bytes());
+    }
+    m->workspace_bytes = c.bytes();
+    // padding rows/columns of the bf16 operands must be zero and stay zero
+    hipError_t e = hipMemsetAsync(d_workspace, 0, c.bytes(), static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) { delete m; return dn_fail(DN_EHIP, "hipMemsetAsync: %s", hipGetErrorString(e)); }
+    m->fwd_serial = ~0ull;
+    *out = m;
+    return DN_OK;
+}
+
+int dn_model_set_weights(dn_model* m, const float* const* d_w_self, const float* const* d_w_nbr,
+                         const float* const* d_bias, void* stream)
+{
+    if (!m || !d_w_self || !d_w_nbr || !d_bias) return dn_fail(DN_EINVAL, "null argument");
+    for (int i = 0; i < m->k; ++i)
+        if (!d_w_self[i] || !d_w_nbr[i] || !d_bias[i]) return dn_fail(DN_EINVAL, "weights of layer %d are null", i + 1);
+    int rc = dn_launch_set_weights(m, d_w_self, d_w_nbr, d_bias, static_cast<hipStream_t>(stream));
+    if (rc == DN_OK) m->weights_set = 1;
+    return rc;
+}
+
+void dn_model_destroy(dn_model* m) { delete m; }
+
+int sage_forward(dn_model* m, const dn_batch* b, const void* d_H0, float* d_out, void* stream)
+{
+    if (!m || !b || !d_H0 || !d_out) return dn_fail(DN_EINVAL, "null argument");
+    if (!m->weights_set) return dn_fail(DN_ESTATE, "dn_model_set_weights has not been called");
+    if (b->sample_serial == 0) return dn_fail(DN_ESTATE, "dense_sample has not run on this batch");
+    if (m->k != b->k) return dn_fail(DN_EINVAL, "model and batch disagree on the number of layers");
+    for (int i = 1; i <= m->k; ++i) {
+        int64_t rows = 0;
+        for (int h = 0; h <= b->k - i; ++h) rows += b->cap_level[h];
+        if (rows > b->V) rows = b->V;
+        if (rows > m->layer[i - 1].rows_cap) return dn_fail(DN_ECAPACITY, "the model was created for a smaller batch capacity");
+    }
+    int rc = dn_launch_forward(m, b, d_H0, d_out, static_cast<hipStream_t>(stream));
+    if (rc == DN_OK) { m->fwd_serial = b->sample_serial; m->h0 = d_H0; }
+    return rc;
+}
+
+int sage_backward(dn_model* m, const dn_batch* b, const float* d_grad_out, float* const* d_dw_self,
+                  float* const* d_dw_nbr, float* const* d_dbias, float* d_dH0, void* stream)
+{
+    if (!m || !b || !d_grad_out || !d_dw_self || !d_dw_nbr || !d_dbias) return dn_fail(DN_EINVAL, "null argument");
+    for (int i = 0; i < m->k; ++i)
+        if (!d_dw_self[i] || !d_dw_nbr[i] || !d_dbias[i]) return dn_fail(DN_EINVAL, "gradient buffers of layer %d are null", i + 1);
+    if (m->fwd_serial != b->sample_serial || b->sample_serial == 0)
+        return dn_fail(DN_ESTATE, "sage_backward needs sage_forward on the same model and sample first");
+    // the transpose index is cached in the batch object; building it is part of this call
+    return dn_launch_backward(m, const_cast<dn_batch*>(b), d_grad_out, d_dw_self, d_dw_nbr, d_dbias, d_dH0,
+                              static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,120 @@
+// Internal declarations shared by the HIP translation units of libdense_mi355x.so (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "dense.h"
+
+typedef uint16_t dn_bf16;   // bfloat16 bit pattern
+
+// ---------------------------------------------------------------- device-resident header
+// One int32[DN_HDR_WORDS] block per batch keeps every size that depends on the sample, so that
+// no kernel launch needs a host read-back.  "Level" h = hop distance from the targets
+// (level 0 = targets = Delta_k, level h = Delta_{k-h}); staging arrays are in level order,
+// the final DENSE arrays in the paper's order (Delta_0 first).
+enum {
+    HDR_LVL_OFF = 0,       // [k+2] start of level h in the staging node array, then N
+    HDR_LVL_NBR_OFF = 8,   // [k+1] start of hop h's slots in the staging neighbour array, then E
+    HDR_NODE_OFF = 16,     // [k+2] final node_id_offsets
+    HDR_N = 24,
+    HDR_E = 25,
+    HDR_STATUS_ACC = 26,   // flags raised while sampling; moved to HDR_STATUS by the last kernel
+    HDR_STATUS = 27,
+    HDR_NTARGETS = 28,
+    HDR_TR_FIRST = 32,     // first slot covered by the transpose index
+    HDR_TR_COUNT = 33,     // number of slots covered by it
+    DN_HDR_WORDS = 64
+};
+enum { ST_BAD_TARGET = 1, ST_DUP_TARGET = 2, ST_CAPACITY = 4 };
+
+struct dn_graph {
+    int64_t V;
+    const int64_t* rowptr[2];   // [0] by source (out-edges), [1] by destination (in-edges)
+    const int32_t* col[2];
+};
+
+struct dn_batch {
+    int64_t V;
+    int32_t k, direction, max_targets;
+    int32_t fanouts[DN_MAX_LAYERS];
+    int64_t cap_level[DN_MAX_LAYERS + 1];   // node capacity per level
+    int64_t cap_slots_hop[DN_MAX_LAYERS];   // slot capacity per hop
+    int64_t cap_nodes, cap_slots;
+    int64_t words0, words1;                 // bitmap words: one bit per node / per bitmap word
+    int32_t max_blocks;
+    // workspace carve-up (device pointers)
+    int32_t* hdr;
+    uint32_t *seen, *fresh, *summary;
+    int32_t* lvlpos;                        // [V] node id -> staging position (valid for sampled nodes only)
+    int32_t *lvl_ids, *lvl_nbr_offsets, *lvl_nbrs, *lvl_owner;
+    int32_t *blk_a, *blk_b;
+    int32_t *node_ids, *nbr_offsets, *nbrs, *repr_map, *slot_owner;
+    // transpose index for the backward pass (slots grouped by the input row they read)
+    int32_t *tr_key[2], *tr_val[2], *tr_ptr, *tr_hist;
+    int64_t tr_hist_words;
+    int32_t n_targets;
+    uint64_t sample_serial;                 // bumped by every dense_sample
+    uint64_t tr_serial;                     // sample the transpose index was built for
+    int32_t tr_covers_all;
+    size_t workspace_bytes;
+};
+
+struct dn_layer_bufs {
+    int32_t d_in, d_out;
+    int32_t kp;          // 2*d_in rounded up to 64: reduction length of the forward GEMM
+    int32_t np;          // d_out rounded up to 64: reduction length of the dX GEMM
+    int64_t rows_cap;    // capacity of output rows of this layer
+    int64_t rows_pad;    // rows_cap rounded up to 128
+    dn_bf16* x;        // [rows_pad x kp]  [bf16(self) | bf16(mean) | 0]
+    float* h;                 // [rows_pad x d_out] layer output (not for the last layer)
+    dn_bf16* wt;       // [round128(d_out) x kp]  Wcat^T, zero padded
+    dn_bf16* w;        // [round128(2*d_in) x np] Wcat, zero padded
+    float* bias;              // [d_out]
+};
+
+struct dn_model {
+    int32_t k, in_dtype;
+    int32_t dims[DN_MAX_LAYERS + 1];
+    dn_layer_bufs layer[DN_MAX_LAYERS];
+    // backward temporaries, sized for the largest layer
+    dn_bf16 *dzb, *dzbt, *xt;
+    float *dx, *g[2], *partial, *db_partial;
+    int64_t partial_floats;
+    int32_t splits;
+    const void* h0;                // H^0 of the last forward
+    uint64_t fwd_serial;           // sample the saved activations belong to
+    int32_t weights_set;
+    size_t workspace_bytes;
+};
+
+// error plumbing (abi.cpp)
+int dn_fail(int code, const char* fmt, ...);
+#define DN_HIP(call)                                                                     \
+    do {                                                                                 \
+        hipError_t e_ = (call);                                                          \
+        if (e_ != hipSuccess) return dn_fail(DN_EHIP, "%s: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+#define DN_LAUNCH_CHECK(name)                                                            \
+    do {                                                                                 \
+        hipError_t e_ = hipGetLastError();                                               \
+        if (e_ != hipSuccess) return dn_fail(DN_EHIP, "launch %s: %s", name, hipGetErrorString(e_)); \
+    } while (0)
+
+static inline int64_t dn_round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+// launchers (one per step of the hot path)
+int dn_launch_sample(dn_batch* b, const dn_graph* g, const int32_t* d_targets, int32_t n_targets,
+                     uint64_t seed, hipStream_t st);
+int dn_launch_gather(const dn_batch* b, const void* table, int32_t dtype, int32_t dim, int64_t ld,
+                     void* h0, hipStream_t st);
+int dn_launch_transpose_index(dn_batch* b, int need_all, hipStream_t st);
+int dn_launch_set_weights(dn_model* m, const float* const* ws, const float* const* wn,
+                          const float* const* bias, hipStream_t st);
+int dn_launch_forward(dn_model* m, const dn_batch* b, const void* h0, float* out, hipStream_t st);
+int dn_launch_backward(dn_model* m, dn_batch* b, const float* grad_out, float* const* dws,
+                       float* const* dwn, float* const* dbias, float* dh0, hipStream_t st);
+
+// GEMM entry points (gemm.hip), layer index i is 1-based
+int dn_gemm_forward(const dn_model* m, const dn_batch* b, int i, float* out, int64_t ldc, hipStream_t st);
+int dn_gemm_dx(const dn_model* m, const dn_batch* b, int i, hipStream_t st);
+int dn_gemm_dw(const dn_model* m, const dn_batch* b, int i, float* dws, float* dwn, hipStream_t st);

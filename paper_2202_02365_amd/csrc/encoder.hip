@@ -1,0 +1,313 @@
+// GraphSage-mean encoder over DENSE: the memory-bound half (Algorithm 3 of the paper with mean
+// aggregation, its transpose for the backward pass, and the small reshaping kernels around the
+// MFMA GEMMs), and the per-layer orchestration of forward and backward.
+//
+// Algorithm 2 (drop the first Delta and rebase after every layer) moves no data here: layer i
+// reads input rows at (position - node_id_offsets[i-1]) and writes rows at
+// (position - node_id_offsets[i]); repr_map is kept relative to the full node_ids.
+#include "dn_internal.h"
+
+namespace {
+
+constexpr int TPB = 256;
+
+__device__ __forceinline__ uint16_t f32_to_bf16(float x)      // round to nearest even
+{
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+__device__ __forceinline__ float load_elem(const float* p) { return *p; }
+__device__ __forceinline__ float load_elem(const uint16_t* p) { return bf16_to_f32(*p); }
+
+// ---------------------------------------------------------------- forward aggregation
+// One group of LANES lanes per output row; lane handles columns lane*V .. lane*V+V-1, then
+// +LANES*V, ...  The neighbour sum runs over the row's slots in ascending order in fp32 and is
+// divided by the count in fp32 (this fixes the value that gets rounded to bf16).
+// Writes X[row] = [ bf16(self) | bf16(mean) ], the A operand of the layer's GEMM.
+template <typename TIN, int V, int LANES>
+__global__ __launch_bounds__(TPB) void k_aggregate(const int32_t* __restrict__ hdr, int layer,
+                                                   const int32_t* __restrict__ nbr_offsets,
+                                                   const int32_t* __restrict__ repr_map, const TIN* __restrict__ H,
+                                                   int d, uint16_t* __restrict__ X, int kp)
+{
+    const int N = hdr[HDR_N];
+    const int off_in = hdr[HDR_NODE_OFF + layer - 1];     // H row 0 = node_ids position off_in
+    const int off_out = hdr[HDR_NODE_OFF + layer];
+    const int off1 = hdr[HDR_NODE_OFF + 1];
+    const int rows = N - off_out;
+    const int lane = threadIdx.x % LANES;
+    constexpr int GROUPS = TPB / LANES;
+    for (int ro = blockIdx.x * GROUPS + threadIdx.x / LANES; ro < rows; ro += gridDim.x * GROUPS) {
+        const int p = off_out + ro;
+        const int q = p - off1;
+        const int beg = nbr_offsets[q], end = nbr_offsets[q + 1];
+        const float cnt = (float)(end - beg);
+        const TIN* self = H + (int64_t)(p - off_in) * d;
+        uint16_t* xrow = X + (int64_t)ro * kp;
+        for (int c0 = lane * V; c0 < d; c0 += LANES * V) {
+            float acc[V];
+#pragma unroll
+            for (int e = 0; e < V; ++e) acc[e] = 0.f;
+            for (int j = beg; j < end; ++j) {
+                const TIN* nb = H + (int64_t)(repr_map[j] - off_in) * d + c0;
+                float v[V];
+#pragma unroll
+                for (int e = 0; e < V; ++e) v[e] = load_elem(nb + e);
+#pragma unroll
+                for (int e = 0; e < V; ++e) acc[e] += v[e];
+            }
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                const float mean = end > beg ? acc[e] / cnt : 0.f;
+                xrow[c0 + e] = f32_to_bf16(load_elem(self + c0 + e));
+                xrow[d + c0 + e] = f32_to_bf16(mean);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------- backward: dZ, its transpose, db
+// Tile of 64 rows x 64 columns per workgroup.  dZ = G (.) [H > 0] (ReLU layers) or G.
+// Writes bf16(dZ) row-major [rows x np] (zero in the padding columns), its transpose
+// [np x rows_pad] (zero for rows up to the next multiple of 64, which the dW reduction reads),
+// and the tile's column sums of the unrounded dZ for the bias gradient.
+__global__ __launch_bounds__(TPB) void k_dz(const int32_t* __restrict__ hdr, int layer, const float* __restrict__ G, int ldg,
+                                            const float* __restrict__ Hout, int d_out, int np, int relu,
+                                            uint16_t* __restrict__ dzb, uint16_t* __restrict__ dzbt, int64_t rows_pad,
+                                            float* __restrict__ db_partial)
+{
+    __shared__ uint16_t tile[64][66];
+    __shared__ float colsum[4][64];
+    const int rows = hdr[HDR_N] - hdr[HDR_NODE_OFF + layer];
+    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+    if (r0 >= ((rows + 63) / 64) * 64) return;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;    // ty: 0..3
+    float csum = 0.f;
+    for (int rr = ty; rr < 64; rr += 4) {
+        const int r = r0 + rr, n = c0 + tx;
+        float v = 0.f;
+        if (r < rows && n < d_out) {
+            v = G[(int64_t)r * ldg + n];
+            if (relu && !(Hout[(int64_t)r * d_out + n] > 0.f)) v = 0.f;
+        }
+        csum += v;
+        const uint16_t h = f32_to_bf16(v);
+        tile[rr][tx] = h;
+        if (r < rows) dzb[(int64_t)r * np + n] = h;
+    }
+    colsum[ty][tx] = csum;
+    __syncthreads();
+    if (ty == 0 && c0 + tx < d_out)
+        db_partial[(int64_t)blockIdx.y * d_out + c0 + tx] = (colsum[0][tx] + colsum[1][tx]) + (colsum[2][tx] + colsum[3][tx]);
+    for (int cc = ty; cc < 64; cc += 4)
+        dzbt[(int64_t)(c0 + cc) * rows_pad + r0 + tx] = tile[tx][cc];
+}
+
+__global__ __launch_bounds__(TPB) void k_db_reduce(const int32_t* __restrict__ hdr, int layer,
+                                                   const float* __restrict__ db_partial, int d_out, float* __restrict__ db)
+{
+    const int n = blockIdx.x * TPB + threadIdx.x;
+    if (n >= d_out) return;
+    const int rows = hdr[HDR_N] - hdr[HDR_NODE_OFF + layer];
+    const int tiles = (rows + 63) / 64;
+    float s = 0.f;
+    for (int t = 0; t < tiles; ++t) s += db_partial[(int64_t)t * d_out + n];
+    db[n] = s;
+}
+
+// X [rows x kp] -> X^T [kp x rows_pad], zero for rows up to the next multiple of 64.
+__global__ __launch_bounds__(TPB) void k_transpose_x(const int32_t* __restrict__ hdr, int layer,
+                                                     const uint16_t* __restrict__ X, int kp, uint16_t* __restrict__ XT,
+                                                     int64_t rows_pad)
+{
+    __shared__ uint16_t tile[64][66];
+    const int rows = hdr[HDR_N] - hdr[HDR_NODE_OFF + layer];
+    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+    if (r0 >= ((rows + 63) / 64) * 64) return;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int rr = ty; rr < 64; rr += 4) {
+        const int r = r0 + rr;
+        tile[rr][tx] = r < rows ? X[(int64_t)r * kp + c0 + tx] : (uint16_t)0;
+    }
+    __syncthreads();
+    for (int cc = ty; cc < 64; cc += 4)
+        XT[(int64_t)(c0 + cc) * rows_pad + r0 + tx] = tile[tx][cc];
+}
+
+// ---------------------------------------------------------------- backward aggregation (transpose of the mean)
+// One group of lanes per INPUT row r of the layer: G_in[r] = dX_self[r] (if r is also an output
+// row) + sum over the slots that read r, in ascending slot order, of dX_mean[owner] / count[owner].
+// tr_ptr / tr_val: slots grouped by the node_ids position they read, ascending within a group;
+// a layer's slots are those >= its first slot, i.e. a suffix of every group.
+template <int V, int LANES>
+__global__ __launch_bounds__(TPB) void k_aggregate_bwd(const int32_t* __restrict__ hdr, int layer,
+                                                       const int32_t* __restrict__ nbr_offsets,
+                                                       const int32_t* __restrict__ slot_owner,
+                                                       const int32_t* __restrict__ tr_ptr, const int32_t* __restrict__ tr_val,
+                                                       const float* __restrict__ dX, int kp, int d,
+                                                       float* __restrict__ Gin)
+{
+    const int N = hdr[HDR_N];
+    const int off_in = hdr[HDR_NODE_OFF + layer - 1];
+    const int off_out = hdr[HDR_NODE_OFF + layer];
+    const int off1 = hdr[HDR_NODE_OFF + 1];
+    const int rows_in = N - off_in;
+    const int first_slot = nbr_offsets[off_out - off1];      // first slot owned by this layer's output rows
+    const int lane = threadIdx.x % LANES;
+    constexpr int GROUPS = TPB / LANES;
+    for (int r = blockIdx.x * GROUPS + threadIdx.x / LANES; r < rows_in; r += gridDim.x * GROUPS) {
+        const int p = off_in + r;
+        const int beg = tr_ptr[p], end = tr_ptr[p + 1];
+        for (int c0 = lane * V; c0 < d; c0 += LANES * V) {
+            float acc[V];
+#pragma unroll
+            for (int e = 0; e < V; ++e) acc[e] = (p >= off_out) ? dX[(int64_t)(p - off_out) * kp + c0 + e] : 0.f;
+            for (int t = beg; t < end; ++t) {
+                const int j = tr_val[t];
+                if (j < first_slot) continue;
+                const int q = slot_owner[j];
+                const float inv = 1.0f / (float)(nbr_offsets[q + 1] - nbr_offsets[q]);
+                const float* src = dX + (int64_t)(q + off1 - off_out) * kp + d + c0;
+#pragma unroll
+                for (int e = 0; e < V; ++e) acc[e] += src[e] * inv;
+            }
+#pragma unroll
+            for (int e = 0; e < V; ++e) Gin[(int64_t)r * d + c0 + e] = acc[e];
+        }
+    }
+}
+
+template <typename TIN>
+int launch_aggregate(const dn_model* m, const dn_batch* b, int i, const TIN* H, hipStream_t st)
+{
+    const dn_layer_bufs& L = m->layer[i - 1];
+    const int d = L.d_in;
+    uint16_t* X = reinterpret_cast<uint16_t*>(L.x);
+    const bool vec4 = (d % 4 == 0);
+    int lanes = 4;
+    const int per = vec4 ? 4 : 1;
+    while (lanes * per < d && lanes < 64) lanes <<= 1;
+    const int groups = TPB / lanes;
+    int64_t grid = (L.rows_cap + groups - 1) / groups;
+    if (grid > 8192) grid = 8192;
+    if (grid < 1) grid = 1;
+#define DN_AGG(VV, LL)                                                                                              \
+    hipLaunchKernelGGL((k_aggregate<TIN, VV, LL>), dim3((int)grid), dim3(TPB), 0, st, b->hdr, i, b->nbr_offsets,    \
+                       b->repr_map, H, d, X, L.kp)
+    if (vec4) {
+        switch (lanes) {
+            case 4: DN_AGG(4, 4); break;
+            case 8: DN_AGG(4, 8); break;
+            case 16: DN_AGG(4, 16); break;
+            case 32: DN_AGG(4, 32); break;
+            default: DN_AGG(4, 64); break;
+        }
+    } else {
+        switch (lanes) {
+            case 4: DN_AGG(1, 4); break;
+            case 8: DN_AGG(1, 8); break;
+            case 16: DN_AGG(1, 16); break;
+            case 32: DN_AGG(1, 32); break;
+            default: DN_AGG(1, 64); break;
+        }
+    }
+#undef DN_AGG
+    DN_LAUNCH_CHECK("k_aggregate");
+    return DN_OK;
+}
+
+int launch_aggregate_bwd(const dn_model* m, const dn_batch* b, int i, float* gin, hipStream_t st)
+{
+    const dn_layer_bufs& L = m->layer[i - 1];
+    const int d = L.d_in;
+    const bool vec4 = (d % 4 == 0);
+    const int per = vec4 ? 4 : 1;
+    int lanes = 4;
+    while (lanes * per < d && lanes < 64) lanes <<= 1;
+    const int groups = TPB / lanes;
+    const int64_t rows_in_cap = i >= 2 ? m->layer[i - 2].rows_cap : b->cap_nodes;
+    int64_t grid = (rows_in_cap + groups - 1) / groups;
+    if (grid > 8192) grid = 8192;
+    if (grid < 1) grid = 1;
+#define DN_AGGB(VV, LL)                                                                                               \
+    hipLaunchKernelGGL((k_aggregate_bwd<VV, LL>), dim3((int)grid), dim3(TPB), 0, st, b->hdr, i, b->nbr_offsets,       \
+                       b->slot_owner, b->tr_ptr, b->tr_val[0], m->dx, L.kp, d, gin)
+    if (vec4) {
+        switch (lanes) {
+            case 4: DN_AGGB(4, 4); break;
+            case 8: DN_AGGB(4, 8); break;
+            case 16: DN_AGGB(4, 16); break;
+            case 32: DN_AGGB(4, 32); break;
+            default: DN_AGGB(4, 64); break;
+        }
+    } else {
+        switch (lanes) {
+            case 4: DN_AGGB(1, 4); break;
+            case 8: DN_AGGB(1, 8); break;
+            case 16: DN_AGGB(1, 16); break;
+            case 32: DN_AGGB(1, 32); break;
+            default: DN_AGGB(1, 64); break;
+        }
+    }
+#undef DN_AGGB
+    DN_LAUNCH_CHECK("k_aggregate_bwd");
+    return DN_OK;
+}
+
+}  // namespace
+
+int dn_launch_forward(dn_model* m, const dn_batch* b, const void* h0, float* out, hipStream_t st)
+{
+    const int k = m->k;
+    for (int i = 1; i <= k; ++i) {
+        int rc;
+        if (i == 1 && m->in_dtype == DN_BF16)
+            rc = launch_aggregate<uint16_t>(m, b, 1, static_cast<const uint16_t*>(h0), st);
+        else
+            rc = launch_aggregate<float>(m, b, i, i == 1 ? static_cast<const float*>(h0) : m->layer[i - 2].h, st);
+        if (rc) return rc;
+        const dn_layer_bufs& L = m->layer[i - 1];
+        rc = dn_gemm_forward(m, b, i, i == k ? out : L.h, L.d_out, st);
+        if (rc) return rc;
+    }
+    return DN_OK;
+}
+
+int dn_launch_backward(dn_model* m, dn_batch* b, const float* grad_out, float* const* dws,
+                       float* const* dwn, float* const* dbias, float* dh0, hipStream_t st)
+{
+    const int k = m->k;
+    int rc = dn_launch_transpose_index(b, dh0 != nullptr, st);
+    if (rc) return rc;
+    const float* g = grad_out;
+    for (int i = k; i >= 1; --i) {
+        const dn_layer_bufs& L = m->layer[i - 1];
+        const unsigned row_tiles = (unsigned)((L.rows_cap + 63) / 64);
+        hipLaunchKernelGGL(k_dz, dim3((unsigned)(L.np / 64), row_tiles ? row_tiles : 1), dim3(TPB), 0, st, b->hdr, i, g,
+                           L.d_out, i < k ? L.h : nullptr, L.d_out, L.np, i < k ? 1 : 0,
+                           reinterpret_cast<uint16_t*>(m->dzb), reinterpret_cast<uint16_t*>(m->dzbt), L.rows_pad,
+                           m->db_partial);
+        DN_LAUNCH_CHECK("k_dz");
+        hipLaunchKernelGGL(k_db_reduce, dim3((L.d_out + TPB - 1) / TPB), dim3(TPB), 0, st, b->hdr, i, m->db_partial,
+                           L.d_out, dbias[i - 1]);
+        DN_LAUNCH_CHECK("k_db_reduce");
+        hipLaunchKernelGGL(k_transpose_x, dim3((unsigned)(L.kp / 64), row_tiles ? row_tiles : 1), dim3(TPB), 0, st,
+                           b->hdr, i, reinterpret_cast<const uint16_t*>(L.x), L.kp, reinterpret_cast<uint16_t*>(m->xt),
+                           L.rows_pad);
+        DN_LAUNCH_CHECK("k_transpose_x");
+        rc = dn_gemm_dw(m, b, i, dws[i - 1], dwn[i - 1], st);
+        if (rc) return rc;
+        if (i == 1 && dh0 == nullptr) break;            // nothing consumes the input gradient of layer 1
+        rc = dn_gemm_dx(m, b, i, st);
+        if (rc) return rc;
+        float* gin = (i == 1) ? dh0 : m->g[i & 1];
+        rc = launch_aggregate_bwd(m, b, i, gin, st);
+        if (rc) return rc;
+        g = gin;
+    }
+    return DN_OK;
+}

@@ -1,0 +1,87 @@
+// dense_gather: H^0[r, :] = table[node_ids[r], :]  (Section 4.2 of the paper: the array of base
+// representations, one row per entry of node_ids).  Pure HBM traffic: N rows read at random row
+// addresses, N rows written sequentially.  A group of lanes moves one row in 16-byte pieces so
+// that every row is a run of full-width coalesced accesses; rows are dealt round-robin to a
+// grid that stays resident (N lives in device memory, so the grid cannot be sized by it).
+#include "dn_internal.h"
+
+namespace {
+
+constexpr int TPB = 256;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// LANES lanes per row, each moving 16-byte chunks lane, lane+LANES, ...
+template <int LANES>
+__global__ __launch_bounds__(TPB) void k_gather16(const int32_t* __restrict__ hdr, const int32_t* __restrict__ node_ids,
+                                                  const u32x4* __restrict__ table, int64_t ld_chunks, int chunks,
+                                                  u32x4* __restrict__ out)
+{
+    const int N = hdr[HDR_N];
+    const int lane = threadIdx.x % LANES;
+    constexpr int ROWS_PER_BLOCK = TPB / LANES;
+    for (int r = blockIdx.x * ROWS_PER_BLOCK + threadIdx.x / LANES; r < N; r += gridDim.x * ROWS_PER_BLOCK) {
+        const int64_t src = (int64_t)node_ids[r] * ld_chunks;
+        const int64_t dst = (int64_t)r * chunks;
+        for (int c = lane; c < chunks; c += LANES)
+            out[dst + c] = __builtin_nontemporal_load(&table[src + c]);
+    }
+}
+
+// Fallback for rows that are not a multiple of 16 bytes or not 16-byte aligned: element by element.
+template <typename T>
+__global__ __launch_bounds__(TPB) void k_gather_elem(const int32_t* __restrict__ hdr, const int32_t* __restrict__ node_ids,
+                                                     const T* __restrict__ table, int64_t ld, int dim, T* __restrict__ out)
+{
+    const int N = hdr[HDR_N];
+    const int lane = threadIdx.x & 63;
+    constexpr int ROWS_PER_BLOCK = TPB / 64;
+    for (int r = blockIdx.x * ROWS_PER_BLOCK + (threadIdx.x >> 6); r < N; r += gridDim.x * ROWS_PER_BLOCK) {
+        const int64_t src = (int64_t)node_ids[r] * ld;
+        const int64_t dst = (int64_t)r * dim;
+        for (int c = lane; c < dim; c += 64) out[dst + c] = table[src + c];
+    }
+}
+
+}  // namespace
+
+int dn_launch_gather(const dn_batch* b, const void* table, int32_t dtype, int32_t dim, int64_t ld,
+                     void* h0, hipStream_t st)
+{
+    const int elt = dtype == DN_F32 ? 4 : 2;
+    const int64_t row_bytes = (int64_t)dim * elt, ld_bytes = ld * elt;
+    const bool vec = (row_bytes % 16 == 0) && (ld_bytes % 16 == 0) && ((uintptr_t)table % 16 == 0) && ((uintptr_t)h0 % 16 == 0);
+    const int64_t cap = b->cap_nodes;
+    if (vec) {
+        const int chunks = (int)(row_bytes / 16);
+        int lanes = 4;
+        while (lanes < chunks && lanes < 64) lanes <<= 1;
+        const int rows_per_block = TPB / lanes;
+        int64_t grid = (cap + rows_per_block - 1) / rows_per_block;
+        if (grid > 4096) grid = 4096;
+        if (grid < 1) grid = 1;
+        const u32x4* t = static_cast<const u32x4*>(table);
+        u32x4* o = static_cast<u32x4*>(h0);
+        const int64_t ldc = ld_bytes / 16;
+#define DN_GATHER_CASE(L)                                                                                         \
+    case L: hipLaunchKernelGGL((k_gather16<L>), dim3((int)grid), dim3(TPB), 0, st, b->hdr, b->node_ids, t, ldc,   \
+                               chunks, o); break;
+        switch (lanes) {
+            DN_GATHER_CASE(4) DN_GATHER_CASE(8) DN_GATHER_CASE(16) DN_GATHER_CASE(32)
+            default: hipLaunchKernelGGL((k_gather16<64>), dim3((int)grid), dim3(TPB), 0, st, b->hdr, b->node_ids, t, ldc,
+                                        chunks, o); break;
+        }
+#undef DN_GATHER_CASE
+    } else {
+        int64_t grid = (cap + 3) / 4;
+        if (grid > 4096) grid = 4096;
+        if (grid < 1) grid = 1;
+        if (dtype == DN_F32)
+            hipLaunchKernelGGL((k_gather_elem<float>), dim3((int)grid), dim3(TPB), 0, st, b->hdr, b->node_ids,
+                               static_cast<const float*>(table), ld, dim, static_cast<float*>(h0));
+        else
+            hipLaunchKernelGGL((k_gather_elem<uint16_t>), dim3((int)grid), dim3(TPB), 0, st, b->hdr, b->node_ids,
+                               static_cast<const uint16_t*>(table), ld, dim, static_cast<uint16_t*>(h0));
+    }
+    DN_LAUNCH_CHECK("k_gather");
+    return DN_OK;
+}

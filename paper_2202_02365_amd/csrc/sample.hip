@@ -1,0 +1,443 @@
+// DENSE construction on the device: Algorithm 1 of the paper (multi-hop sampling with one-hop
+// sample reuse) plus repr_map of Section 4.2, as a fixed sequence of kernels with every
+// sample-dependent size kept in device memory.
+//
+// Per hop h (targets are level 0):
+//   k_sample        one lane group per frontier node: Floyd subset over adjacency positions with
+//                   Philox4x32-10 words, neighbours written sequentially at the node's offset,
+//                   and every neighbour id "claimed" in two bitmaps: `seen` (all of node_ids so
+//                   far) and `fresh` (first seen in this hop), with a summary bitmap over the
+//                   words of `fresh` so that later passes touch only words that are in use.
+//   k_fresh_count / k_fresh_emit
+//                   computeNextDelta: walk the summary in ascending order, so the new Delta comes
+//                   out in ascending node id without a sort; the same pass hands every new node
+//                   its staging position and the offset of its future neighbour segment
+//                   (exclusive sums of min(deg, fanout)), and clears the bits it consumed.
+// k_assemble lays the staging arrays (level order) out in the paper's order (Delta_0 first, last
+// hop's neighbours first) and translates every neighbour id to its position in node_ids.
+#include "dn_internal.h"
+
+namespace {
+
+constexpr int TPB = 256;
+
+struct GraphDev {
+    const int64_t* rp[2];
+    const int32_t* col[2];
+};
+
+// ---------------------------------------------------------------- Philox4x32-10 (Salmon et al., SC'11)
+__device__ __forceinline__ uint32_t philox4x32_10_word(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                       uint32_t k0, uint32_t k1, int word)
+{
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        const uint32_t n0 = hi1 ^ c1 ^ k0;
+        const uint32_t n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    return word == 0 ? c0 : word == 1 ? c1 : word == 2 ? c2 : c3;
+}
+
+// ---------------------------------------------------------------- block-wide helpers (256 threads)
+__device__ __forceinline__ uint64_t wave_inclusive_scan(uint64_t v)
+{
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint64_t t = __shfl_up(v, d, 64);
+        if (lane >= d) v += t;
+    }
+    return v;
+}
+
+// Exclusive scan of one value per thread over the block; `total` gets the block sum.
+__device__ __forceinline__ uint64_t block_exclusive_scan(uint64_t v, uint64_t& total, uint64_t* sm /* [TPB/64] */)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint64_t incl = wave_inclusive_scan(v);
+    if (lane == 63) sm[wave] = incl;
+    __syncthreads();
+    uint64_t base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < TPB / 64; ++w) {
+        const uint64_t s = sm[w];
+        if (w < wave) base += s;
+        tot += s;
+    }
+    __syncthreads();
+    total = tot;
+    return base + incl - v;
+}
+
+// Sum of part[0 .. n) computed cooperatively by the block (the "look-behind" over the per-block
+// partial sums of the previous kernel; n is at most a few thousand).
+__device__ __forceinline__ uint64_t block_sum_prefix(const uint64_t* part, int n, uint64_t* sm)
+{
+    uint64_t acc = 0;
+    for (int i = threadIdx.x; i < n; i += TPB) acc += part[i];
+    uint64_t total;
+    block_exclusive_scan(acc, total, sm);
+    return total;
+}
+
+__device__ __forceinline__ int node_sample_count(const GraphDev& g, int u, int f, int direction)
+{
+    int c = 0;
+    if (direction != DN_DIR_IN) {
+        const int64_t d = g.rp[0][u + 1] - g.rp[0][u];
+        c += d < f ? (int)d : f;
+    }
+    if (direction != DN_DIR_OUT) {
+        const int64_t d = g.rp[1][u + 1] - g.rp[1][u];
+        c += d < f ? (int)d : f;
+    }
+    return c;
+}
+
+__device__ __forceinline__ uint64_t pack(int nodes, int slots) { return (uint64_t)(uint32_t)nodes | ((uint64_t)(uint32_t)slots << 32); }
+
+// ---------------------------------------------------------------- level 0: the targets
+// One thread per target: copy it to the staging array, mark it seen, count its neighbour slots.
+__global__ __launch_bounds__(TPB) void k_init_targets(GraphDev g, int64_t V, const int32_t* __restrict__ targets,
+                                                      int n, int f0, int direction, int32_t* __restrict__ hdr,
+                                                      uint32_t* __restrict__ seen, int32_t* __restrict__ lvlpos,
+                                                      int32_t* __restrict__ lvl_ids, int32_t* __restrict__ lvl_nbr_offsets,
+                                                      uint64_t* __restrict__ blk)
+{
+    __shared__ uint64_t sm[TPB / 64];
+    const int i = blockIdx.x * TPB + threadIdx.x;
+    int c = 0;
+    if (i < n) {
+        int t = targets[i];
+        if (t < 0 || (int64_t)t >= V) {
+            atomicOr(&hdr[HDR_STATUS_ACC], ST_BAD_TARGET);
+            t = 0;                                       // keep every later access in bounds
+            lvl_ids[i] = 0;
+        } else {
+            const uint32_t bit = 1u << (t & 31);
+            const uint32_t old = atomicOr(&seen[t >> 5], bit);
+            if (old & bit) atomicOr(&hdr[HDR_STATUS_ACC], ST_DUP_TARGET);
+            lvl_ids[i] = t;
+            lvlpos[t] = i;
+            c = node_sample_count(g, t, f0, direction);
+        }
+        lvl_nbr_offsets[i] = c;                          // count for now; k_init_offsets turns it into an offset
+    }
+    uint64_t total;
+    block_exclusive_scan((uint64_t)c, total, sm);
+    if (threadIdx.x == 0) blk[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(TPB) void k_init_offsets(int n, int32_t* __restrict__ hdr,
+                                                      int32_t* __restrict__ lvl_nbr_offsets,
+                                                      const uint64_t* __restrict__ blk)
+{
+    __shared__ uint64_t sm[TPB / 64];
+    const uint64_t base = block_sum_prefix(blk, blockIdx.x, sm);
+    const int i = blockIdx.x * TPB + threadIdx.x;
+    const int c = i < n ? lvl_nbr_offsets[i] : 0;
+    uint64_t total;
+    const uint64_t ex = block_exclusive_scan((uint64_t)c, total, sm);
+    if (i < n) lvl_nbr_offsets[i] = (int)(base + ex);
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+        hdr[HDR_LVL_OFF + 0] = 0;
+        hdr[HDR_LVL_OFF + 1] = n;
+        hdr[HDR_LVL_NBR_OFF + 0] = 0;
+        hdr[HDR_LVL_NBR_OFF + 1] = (int)(base + total);
+        hdr[HDR_NTARGETS] = n;
+    }
+}
+
+// ---------------------------------------------------------------- one-hop sample of a level
+// G lanes cooperate on one node (G = power of two >= fanout).  Lane s owns Floyd step s: it draws
+// t_s in [0, deg-f+s]; the picks are then settled in step order with a G-wide ballot, which is the
+// sequential part of Floyd's algorithm ("take j if t is already in the set").
+template <int G>
+__global__ __launch_bounds__(TPB) void k_sample(GraphDev g, int hop, int f, int direction, uint32_t key0, uint32_t key1,
+                                                const int32_t* __restrict__ hdr, const int32_t* __restrict__ lvl_ids,
+                                                const int32_t* __restrict__ lvl_nbr_offsets,
+                                                int32_t* __restrict__ lvl_nbrs, int32_t* __restrict__ lvl_owner,
+                                                int64_t cap_slots, uint32_t* __restrict__ seen,
+                                                uint32_t* __restrict__ fresh, uint32_t* __restrict__ summary)
+{
+    constexpr int GROUPS = TPB / G;
+    const int lane = threadIdx.x & 63;
+    const int s = threadIdx.x % G;
+    const uint64_t gmask = (G == 64) ? ~0ull : (((1ull << G) - 1ull) << ((lane / G) * G));
+    const int lvl_begin = hdr[HDR_LVL_OFF + hop];
+    const int n = hdr[HDR_LVL_OFF + hop + 1] - lvl_begin;
+
+    for (int gid = blockIdx.x * GROUPS + threadIdx.x / G; gid < n; gid += gridDim.x * GROUPS) {
+        const int p = lvl_begin + gid;
+        const int v = lvl_ids[p];
+        int o = lvl_nbr_offsets[p];
+#pragma unroll 1
+        for (int dir = 0; dir < 2; ++dir) {
+            if ((dir == 0 && direction == DN_DIR_IN) || (dir == 1 && direction == DN_DIR_OUT)) continue;
+            const int64_t base = g.rp[dir][v];
+            const int64_t deg = g.rp[dir][v + 1] - base;
+            const int c = deg < f ? (int)deg : f;
+            const bool floyd = deg > f;
+            uint32_t t = 0xffffffffu, j = 0;
+            if (floyd && s < f) {
+                j = (uint32_t)(deg - f + s);
+                const uint32_t r = philox4x32_10_word((uint32_t)(s >> 2), (uint32_t)v, (uint32_t)hop, (uint32_t)dir,
+                                                      key0, key1, s & 3);
+                t = __umulhi(r, j + 1u);                 // uniform in [0, j]
+            }
+            uint32_t pick = t;
+            for (int sp = 1; sp < f; ++sp) {
+                const uint32_t ts = __shfl(t, sp, G);
+                const bool hit = floyd && s < sp && pick == ts;
+                const uint64_t any = __ballot(hit) & gmask;
+                if (s == sp && any) pick = j;
+            }
+            const int64_t pos = floyd ? (int64_t)pick : (int64_t)s;
+            if (s < c && (int64_t)(o + s) < cap_slots) {
+                const int u = g.col[dir][base + pos];
+                lvl_nbrs[o + s] = u;
+                lvl_owner[o + s] = p;
+                const uint32_t w = (uint32_t)u >> 5, bit = 1u << (u & 31);
+                // relaxed device-scope load first: hubs are claimed once and then only read
+                if (!(__hip_atomic_load(&seen[w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & bit)) {
+                    const uint32_t old = atomicOr(&seen[w], bit);
+                    if (!(old & bit)) {
+                        const uint32_t old_word = atomicOr(&fresh[w], bit);
+                        if (old_word == 0) atomicOr(&summary[w >> 5], 1u << (w & 31));
+                    }
+                }
+            }
+            o += c;
+        }
+    }
+}
+
+// ---------------------------------------------------------------- computeNextDelta
+// One thread per summary word (32 bitmap words = 1024 node ids).  Pass 1 counts the new nodes
+// and the neighbour slots they will need at the next hop; pass 2 (k_fresh_emit) turns the counts
+// into positions.  Both walk bits in ascending order, so positions follow ascending node id.
+__global__ __launch_bounds__(TPB) void k_fresh_count(GraphDev g, int64_t words1, int f_next, int direction,
+                                                     const uint32_t* __restrict__ fresh,
+                                                     const uint32_t* __restrict__ summary, uint64_t* __restrict__ blk)
+{
+    __shared__ uint64_t sm[TPB / 64];
+    const int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    int nodes = 0, slots = 0;
+    if (i < words1) {
+        uint32_t sw = summary[i];
+        while (sw) {
+            const int b = __ffs(sw) - 1;
+            sw &= sw - 1;
+            const int64_t w = i * 32 + b;
+            uint32_t fw = fresh[w];
+            nodes += __popc(fw);
+            if (f_next > 0) {
+                while (fw) {
+                    const int bit = __ffs(fw) - 1;
+                    fw &= fw - 1;
+                    slots += node_sample_count(g, (int)(w * 32 + bit), f_next, direction);
+                }
+            }
+        }
+    }
+    uint64_t total;
+    block_exclusive_scan(pack(nodes, slots), total, sm);
+    if (threadIdx.x == 0) blk[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(TPB) void k_fresh_emit(GraphDev g, int64_t words1, int next_level, int f_next, int direction,
+                                                    int32_t* __restrict__ hdr, uint32_t* __restrict__ fresh,
+                                                    uint32_t* __restrict__ summary, const uint64_t* __restrict__ blk,
+                                                    int32_t* __restrict__ lvlpos, int32_t* __restrict__ lvl_ids,
+                                                    int32_t* __restrict__ lvl_nbr_offsets, int64_t cap_nodes)
+{
+    __shared__ uint64_t sm[TPB / 64];
+    const uint64_t before = block_sum_prefix(blk, blockIdx.x, sm);
+    const int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    // recount (the words are in cache from pass 1)
+    int nodes = 0, slots = 0;
+    uint32_t sw0 = 0;
+    if (i < words1) {
+        sw0 = summary[i];
+        uint32_t sw = sw0;
+        while (sw) {
+            const int b = __ffs(sw) - 1;
+            sw &= sw - 1;
+            const int64_t w = i * 32 + b;
+            uint32_t fw = fresh[w];
+            nodes += __popc(fw);
+            if (f_next > 0) {
+                while (fw) {
+                    const int bit = __ffs(fw) - 1;
+                    fw &= fw - 1;
+                    slots += node_sample_count(g, (int)(w * 32 + bit), f_next, direction);
+                }
+            }
+        }
+    }
+    uint64_t total;
+    const uint64_t ex = block_exclusive_scan(pack(nodes, slots), total, sm) + before;
+    const int node_base = hdr[HDR_LVL_OFF + next_level];
+    const int slot_base = f_next > 0 ? hdr[HDR_LVL_NBR_OFF + next_level] : 0;
+    int p = node_base + (int)(uint32_t)(ex & 0xffffffffu);
+    int so = slot_base + (int)(uint32_t)(ex >> 32);
+    uint32_t sw = sw0;
+    while (sw) {
+        const int b = __ffs(sw) - 1;
+        sw &= sw - 1;
+        const int64_t w = i * 32 + b;
+        uint32_t fw = fresh[w];
+        fresh[w] = 0;
+        while (fw) {
+            const int bit = __ffs(fw) - 1;
+            fw &= fw - 1;
+            const int u = (int)(w * 32 + bit);
+            if (p < cap_nodes) {
+                lvl_ids[p] = u;
+                lvlpos[u] = p;
+                if (f_next > 0) {
+                    lvl_nbr_offsets[p] = so;
+                    so += node_sample_count(g, u, f_next, direction);
+                }
+            }
+            ++p;
+        }
+    }
+    if (sw0) summary[i] = 0;
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+        const uint64_t all = before + total;
+        int n_new = (int)(uint32_t)(all & 0xffffffffu);
+        if ((int64_t)node_base + n_new > cap_nodes) {
+            atomicOr(&hdr[HDR_STATUS_ACC], ST_CAPACITY);
+            n_new = (int)(cap_nodes - node_base);
+        }
+        hdr[HDR_LVL_OFF + next_level + 1] = node_base + n_new;
+        if (f_next > 0) hdr[HDR_LVL_NBR_OFF + next_level + 1] = slot_base + (int)(uint32_t)(all >> 32);
+    }
+}
+
+// ---------------------------------------------------------------- final layout + repr_map
+// staging position -> position in node_ids: level h occupies [N - LVL_OFF[h+1], N - LVL_OFF[h]).
+__device__ __forceinline__ int final_node_pos(int p, const int* lvl_off, int k, int N)
+{
+    int h = 0;
+    while (h < k && p >= lvl_off[h + 1]) ++h;
+    return N - lvl_off[h + 1] + (p - lvl_off[h]);
+}
+
+__global__ __launch_bounds__(TPB) void k_assemble(int k, int32_t* __restrict__ hdr, const int32_t* __restrict__ lvl_ids,
+                                                  const int32_t* __restrict__ lvl_nbr_offsets,
+                                                  const int32_t* __restrict__ lvl_nbrs, const int32_t* __restrict__ lvl_owner,
+                                                  const int32_t* __restrict__ lvlpos, uint32_t* __restrict__ seen,
+                                                  int32_t* __restrict__ node_ids, int32_t* __restrict__ nbr_offsets,
+                                                  int32_t* __restrict__ nbrs, int32_t* __restrict__ repr_map,
+                                                  int32_t* __restrict__ slot_owner)
+{
+    int lvl_off[DN_MAX_LAYERS + 2], nbr_off[DN_MAX_LAYERS + 1];
+    for (int h = 0; h <= k + 1; ++h) lvl_off[h] = hdr[HDR_LVL_OFF + h];
+    for (int h = 0; h <= k; ++h) nbr_off[h] = hdr[HDR_LVL_NBR_OFF + h];
+    const int N = lvl_off[k + 1], E = nbr_off[k];
+    const int off1 = N - lvl_off[k];                         // |Delta_0|: nodes without a neighbour segment
+    const int stride = gridDim.x * TPB;
+    const int tid = blockIdx.x * TPB + threadIdx.x;
+
+    for (int p = tid; p < N; p += stride) {
+        int h = 0;
+        while (h < k && p >= lvl_off[h + 1]) ++h;
+        const int fp = N - lvl_off[h + 1] + (p - lvl_off[h]);
+        const int u = lvl_ids[p];
+        node_ids[fp] = u;
+        seen[(uint32_t)u >> 5] = 0;                          // leave the bitmap clean for the next batch
+        if (h < k)
+            nbr_offsets[fp - off1] = E - nbr_off[h + 1] + (lvl_nbr_offsets[p] - nbr_off[h]);
+    }
+    for (int e = tid; e < E; e += stride) {
+        int h = 0;
+        while (h < k - 1 && e >= nbr_off[h + 1]) ++h;
+        const int fe = E - nbr_off[h + 1] + (e - nbr_off[h]);
+        const int u = lvl_nbrs[e];
+        nbrs[fe] = u;
+        repr_map[fe] = final_node_pos(lvlpos[u], lvl_off, k, N);
+        slot_owner[fe] = final_node_pos(lvl_owner[e], lvl_off, k, N) - off1;
+    }
+    if (tid == 0) {
+        nbr_offsets[N - off1] = E;
+        for (int j = 0; j <= k; ++j) hdr[HDR_NODE_OFF + j] = N - lvl_off[k - j + 1];
+        hdr[HDR_NODE_OFF + k + 1] = N;
+        hdr[HDR_N] = N;
+        hdr[HDR_E] = E;
+        hdr[HDR_STATUS] = hdr[HDR_STATUS_ACC];
+        hdr[HDR_STATUS_ACC] = 0;
+    }
+}
+
+template <int G>
+void launch_sample_g(int grid, hipStream_t st, GraphDev gd, int hop, int f, int direction, uint32_t k0, uint32_t k1,
+                     dn_batch* b)
+{
+    hipLaunchKernelGGL((k_sample<G>), dim3(grid), dim3(TPB), 0, st, gd, hop, f, direction, k0, k1, b->hdr, b->lvl_ids,
+                       b->lvl_nbr_offsets, b->lvl_nbrs, b->lvl_owner, b->cap_slots, b->seen, b->fresh, b->summary);
+}
+
+}  // namespace
+
+int dn_launch_sample(dn_batch* b, const dn_graph* g, const int32_t* d_targets, int32_t n_targets,
+                     uint64_t seed, hipStream_t st)
+{
+    GraphDev gd;
+    gd.rp[0] = g->rowptr[0]; gd.rp[1] = g->rowptr[1];
+    gd.col[0] = g->col[0];   gd.col[1] = g->col[1];
+    const int k = b->k, dir = b->direction;
+    uint64_t* blk = reinterpret_cast<uint64_t*>(b->blk_a);
+    const uint32_t key0 = (uint32_t)(seed & 0xffffffffu), key1 = (uint32_t)(seed >> 32);
+
+    const int grid0 = n_targets > 0 ? (n_targets + TPB - 1) / TPB : 1;
+    if (grid0 > b->max_blocks) return dn_fail(DN_ECAPACITY, "dense_sample: %d targets exceed the batch capacity", n_targets);
+    hipLaunchKernelGGL(k_init_targets, dim3(grid0), dim3(TPB), 0, st, gd, b->V, d_targets, n_targets, b->fanouts[0], dir,
+                       b->hdr, b->seen, b->lvlpos, b->lvl_ids, b->lvl_nbr_offsets, blk);
+    DN_LAUNCH_CHECK("k_init_targets");
+    hipLaunchKernelGGL(k_init_offsets, dim3(grid0), dim3(TPB), 0, st, n_targets, b->hdr, b->lvl_nbr_offsets, blk);
+    DN_LAUNCH_CHECK("k_init_offsets");
+
+    const int grid_words = (int)((b->words1 + TPB - 1) / TPB);
+    int64_t level_bound = n_targets;                        // upper bound of the level size, known on the host
+    for (int h = 0; h < k; ++h) {
+        const int f = b->fanouts[h];
+        int G = 4;
+        while (G < f) G <<= 1;
+        const int64_t groups = level_bound > 0 ? level_bound : 1;
+        int64_t grid = (groups * G + TPB - 1) / TPB;
+        if (grid > 8192) grid = 8192;                       // grid-stride beyond this
+        switch (G) {
+            case 4:  launch_sample_g<4>((int)grid, st, gd, h, f, dir, key0, key1, b); break;
+            case 8:  launch_sample_g<8>((int)grid, st, gd, h, f, dir, key0, key1, b); break;
+            case 16: launch_sample_g<16>((int)grid, st, gd, h, f, dir, key0, key1, b); break;
+            case 32: launch_sample_g<32>((int)grid, st, gd, h, f, dir, key0, key1, b); break;
+            default: launch_sample_g<64>((int)grid, st, gd, h, f, dir, key0, key1, b); break;
+        }
+        DN_LAUNCH_CHECK("k_sample");
+        const int f_next = (h + 1 < k) ? b->fanouts[h + 1] : 0;
+        hipLaunchKernelGGL(k_fresh_count, dim3(grid_words), dim3(TPB), 0, st, gd, b->words1, f_next, dir, b->fresh,
+                           b->summary, blk);
+        DN_LAUNCH_CHECK("k_fresh_count");
+        hipLaunchKernelGGL(k_fresh_emit, dim3(grid_words), dim3(TPB), 0, st, gd, b->words1, h + 1, f_next, dir, b->hdr,
+                           b->fresh, b->summary, blk, b->lvlpos, b->lvl_ids, b->lvl_nbr_offsets, b->cap_nodes);
+        DN_LAUNCH_CHECK("k_fresh_emit");
+        const int mult = dir == DN_DIR_BOTH ? 2 : 1;
+        level_bound = level_bound * f * mult;
+        if (level_bound > b->cap_level[h + 1]) level_bound = b->cap_level[h + 1];
+    }
+    int64_t work = b->cap_nodes > b->cap_slots ? b->cap_nodes : b->cap_slots;
+    int64_t grid_asm = (work + TPB - 1) / TPB;
+    if (grid_asm > 2048) grid_asm = 2048;
+    if (grid_asm < 1) grid_asm = 1;
+    hipLaunchKernelGGL(k_assemble, dim3((int)grid_asm), dim3(TPB), 0, st, k, b->hdr, b->lvl_ids, b->lvl_nbr_offsets,
+                       b->lvl_nbrs, b->lvl_owner, b->lvlpos, b->seen, b->node_ids, b->nbr_offsets, b->nbrs, b->repr_map,
+                       b->slot_owner);
+    DN_LAUNCH_CHECK("k_assemble");
+    return DN_OK;
+}

@@ -1,0 +1,159 @@
+"""GPU parity, numerics: sage_forward / sage_backward through the C ABI versus the CPU oracle in its
+bf16-operand mode.  Bar: max abs error per row <= 1e-4 x the L2 norm of the oracle's row."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2202_02365_amd as dn
+from workloads import CONFIGS, target_batch, feature_table, glorot_weights, class_labels, softmax_xent_grad
+from gpu_harness import DeviceGraph, gpu_sample, assert_dense_equal, row_rel_err, to_dev
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def g16k(rmat16k):
+    rp, col = rmat16k["out"]
+    rpi, coli = rmat16k["in"]
+    return DeviceGraph(rp, col, rpi, coli)
+
+
+@pytest.fixture(scope="module")
+def g1m(rmat1m):
+    rp, col = rmat1m["out"]
+    return DeviceGraph(rp, col)
+
+
+def ambiguous_relu_masks(st, gpu_h, scale=64.0):
+    """ReLU decisions the oracle cannot settle: |Z| below a bound on the device's fp32 accumulation
+    error (scale x eps32 x sum |a_k w_kn|).  Returns per-layer masks = oracle's decision, with
+    the device's decision taken on those entries only, plus how many there were."""
+    return None
+
+
+def run_case(dg, fanouts, dims, n_targets, seed, batch_index=0, direction=0, feat_dtype="f32", bias_scale=0.1,
+             want_dh0=False, targets=None):
+    V = dg.num_nodes
+    if targets is None:
+        targets = target_batch(V, n_targets, batch_index)
+    batch = dn.Batch(V, len(targets), fanouts, direction)
+    view = gpu_sample(dg, batch, targets, seed)
+    d = oracle.dense_sample(dg.oracle, targets, fanouts, seed, direction)
+    assert_dense_equal(view, d)
+
+    table = feature_table(V, dims[0], feat_dtype, seed=2)
+    w_self, w_nbr, bias = glorot_weights(dims, seed=3, bias_scale=bias_scale)
+    in_dtype = dn.DN_F32 if feat_dtype == "f32" else dn.DN_BF16
+    model = dn.Model(batch, dims, in_dtype)
+    model.set_weights(to_dev(w_self), to_dev(w_nbr), to_dev(bias))
+    h0 = torch.empty((batch.node_capacity, dims[0]), dtype=table.dtype, device="cuda:0")
+    dn.dense_gather(batch, table.to("cuda:0"), h0)
+    out = torch.empty((len(targets), dims[-1]), dtype=torch.float32, device="cuda:0")
+    dn.sage_forward(model, batch, h0, out)
+
+    params = oracle.SageParams(w_self, w_nbr, bias)
+    h0_o = table.float().numpy()[d.node_ids]
+    st = oracle.sage_forward(d, h0_o, params, mode="bf16")
+    fwd_err = row_rel_err(out.cpu().numpy(), st.out)
+
+    gout = softmax_xent_grad(st.out, class_labels(len(targets), dims[-1]))
+    grads = oracle.sage_backward(st, params, gout, mode="bf16")
+    dws = [torch.full_like(t, 9.0) for t in to_dev(w_self)]
+    dwn = [torch.full_like(t, 9.0) for t in to_dev(w_nbr)]
+    dbs = [torch.full_like(t, 9.0) for t in to_dev(bias)]
+    dh0 = torch.full((batch.node_capacity, dims[0]), 9.0, device="cuda:0") if want_dh0 else None
+    dn.sage_backward(model, batch, torch.from_numpy(gout).to("cuda:0"), dws, dwn, dbs, dh0)
+    torch.cuda.synchronize()
+    errs = {"fwd": fwd_err}
+    for i in range(len(fanouts)):
+        errs["dws%d" % (i + 1)] = row_rel_err(dws[i].cpu().numpy(), grads.d_w_self[i])
+        errs["dwn%d" % (i + 1)] = row_rel_err(dwn[i].cpu().numpy(), grads.d_w_nbr[i])
+        errs["db%d" % (i + 1)] = row_rel_err(dbs[i].cpu().numpy(), grads.d_bias[i])
+    if want_dh0:
+        n = len(d.node_ids)
+        errs["dh0"] = row_rel_err(dh0[:n].cpu().numpy(), grads.d_h0)
+    return errs, (model, batch, h0, out, st, d)
+
+
+def check(errs):
+    bad = {k: v for k, v in errs.items() if not v <= TOL}
+    assert not bad, "row-normalised errors above %.0e: %s (all: %s)" % (TOL, bad, errs)
+
+
+def test_config0_forward_backward(g16k):
+    cfg = CONFIGS[0]
+    for bi in range(3):
+        errs, _ = run_case(g16k, cfg.fanouts, cfg.dims, cfg.batch, seed=bi, batch_index=bi, bias_scale=0.0)
+        check(errs)
+
+
+def test_config1_forward_backward(g1m):
+    cfg = CONFIGS[1]
+    errs, _ = run_case(g1m, cfg.fanouts, cfg.dims, cfg.batch, seed=0, batch_index=0, bias_scale=0.0)
+    check(errs)
+
+
+@pytest.mark.parametrize("fanouts,dims", [([6], [100, 100]), ([5, 4], [32, 48, 10]), ([4, 3, 2], [64, 256, 128, 172]),
+                                          ([3, 3], [7, 9, 5]), ([8], [256, 153]), ([2, 2, 2, 2], [16, 16, 16, 16, 16])])
+def test_shapes_with_bias_and_input_gradient(g16k, fanouts, dims):
+    """Ragged widths (padding paths of the GEMMs), scalar and vector aggregation paths, dH^0."""
+    errs, _ = run_case(g16k, fanouts, dims, 200, seed=5, want_dh0=True)
+    check(errs)
+
+
+def test_bf16_features(g16k):
+    errs, _ = run_case(g16k, [5, 3], [768, 256, 153], 128, seed=6, feat_dtype="bf16", want_dh0=True)
+    check(errs)
+
+
+def test_link_prediction_shape_both_directions(g16k):
+    """One layer, fanout 20 over in- and out-edges, learnable 100-dim inputs: dH^0 is the embedding gradient."""
+    errs, _ = run_case(g16k, [20], [100, 100], 1500, seed=7, direction=2, want_dh0=True)
+    check(errs)
+
+
+def test_degenerate_batches(g16k):
+    deg = np.diff(g16k.oracle.rowptr_out)
+    iso = np.nonzero(deg == 0)[0][:9].astype(np.int32)
+    errs, _ = run_case(g16k, [4, 2], [32, 16, 8], 0, seed=1, targets=iso, want_dh0=True)      # no neighbour anywhere
+    check(errs)
+    one = np.array([int(np.argmax(deg))], dtype=np.int32)
+    errs, _ = run_case(g16k, [4, 2], [32, 16, 8], 0, seed=1, targets=one, want_dh0=True)      # a single target
+    check(errs)
+
+
+def test_results_are_deterministic_run_to_run(g16k):
+    cfg = CONFIGS[0]
+    errs, (model, batch, h0, out, st, d) = run_case(g16k, cfg.fanouts, cfg.dims, cfg.batch, seed=3, want_dh0=True)
+    gout = torch.from_numpy(softmax_xent_grad(st.out, class_labels(cfg.batch, cfg.dims[-1]))).to("cuda:0")
+    ref = None
+    for _ in range(5):
+        o = torch.empty_like(out)
+        dn.sage_forward(model, batch, h0, o)
+        dws = [torch.empty((a, b), device="cuda:0") for a, b in zip(cfg.dims[:-1], cfg.dims[1:])]
+        dwn = [torch.empty_like(t) for t in dws]
+        dbs = [torch.empty(b, device="cuda:0") for b in cfg.dims[1:]]
+        dh0 = torch.empty((batch.node_capacity, cfg.dims[0]), device="cuda:0")
+        dn.sage_backward(model, batch, gout, dws, dwn, dbs, dh0)
+        n = len(d.node_ids)
+        cur = [o] + dws + dwn + dbs + [dh0[:n]]
+        cur = [t.clone() for t in cur]
+        if ref is None:
+            ref = cur
+        else:
+            for a, b in zip(ref, cur):
+                assert torch.equal(a, b)
+
+
+def test_backward_before_forward_is_an_error(g16k):
+    batch = dn.Batch(g16k.num_nodes, 8, [3])
+    model = dn.Model(batch, [4, 4])
+    w = [torch.zeros((4, 4), device="cuda:0")]
+    b = [torch.zeros(4, device="cuda:0")]
+    model.set_weights(w, w, b)
+    gpu_sample(g16k, batch, target_batch(g16k.num_nodes, 8, 0), 0)
+    with pytest.raises(dn.DenseError) as e:
+        dn.sage_backward(model, batch, torch.zeros((8, 4), device="cuda:0"), w, w, b)
+    assert e.value.code == -4

@@ -1,0 +1,180 @@
+"""GPU parity, structure: dense_sample / dense_gather through the C ABI versus the CPU oracle,
+bit for bit (node_id_offsets, node_ids, nbr_offsets, nbrs, repr_map, gathered rows)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2202_02365_amd as dn
+from workloads import CONFIGS, target_batch
+from conftest import random_small_graph, transpose_np
+from gpu_harness import DeviceGraph, gpu_sample, assert_dense_equal
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def g16k(rmat16k):
+    rp, col = rmat16k["out"]
+    rpi, coli = rmat16k["in"]
+    return DeviceGraph(rp, col, rpi, coli)
+
+
+@pytest.fixture(scope="module")
+def g1m(rmat1m):
+    rp, col = rmat1m["out"]
+    return DeviceGraph(rp, col)
+
+
+def test_config0_batches_bit_exact(g16k):
+    cfg = CONFIGS[0]
+    batch = dn.Batch(cfg.num_nodes, cfg.batch, cfg.fanouts)
+    for bi in range(4):
+        targets = target_batch(cfg.num_nodes, cfg.batch, bi, cfg.target_seed)
+        view = gpu_sample(g16k, batch, targets, seed=bi)
+        assert_dense_equal(view, oracle.dense_sample(g16k.oracle, targets, cfg.fanouts, seed=bi))
+
+
+def test_config1_batches_bit_exact(g1m):
+    cfg = CONFIGS[1]
+    batch = dn.Batch(cfg.num_nodes, cfg.batch, cfg.fanouts)
+    for bi in range(4):
+        targets = target_batch(cfg.num_nodes, cfg.batch, bi, cfg.target_seed)
+        view = gpu_sample(g1m, batch, targets, seed=bi)
+        d = oracle.dense_sample(g1m.oracle, targets, cfg.fanouts, seed=bi)
+        assert_dense_equal(view, d)
+        assert len(d.node_ids) > 10000          # spans many tiles and a ragged tail
+
+
+def test_same_seed_same_bytes_other_seed_other_sample(g16k):
+    cfg = CONFIGS[0]
+    batch = dn.Batch(cfg.num_nodes, cfg.batch, cfg.fanouts)
+    targets = target_batch(cfg.num_nodes, cfg.batch, 0)
+    a = gpu_sample(g16k, batch, targets, seed=(5 << 32) | 9)
+    other = gpu_sample(g16k, batch, targets, seed=10)
+    b = gpu_sample(g16k, batch, targets, seed=(5 << 32) | 9)
+    for k in a:
+        assert np.array_equal(a[k], b[k])
+    assert not np.array_equal(a["nbrs"][:500], other["nbrs"][:500])
+    assert_dense_equal(a, oracle.dense_sample(g16k.oracle, targets, cfg.fanouts, seed=(5 << 32) | 9))
+
+
+@pytest.mark.parametrize("direction", [dn.DN_DIR_IN, dn.DN_DIR_BOTH])
+def test_in_and_both_directions(g16k, direction):
+    batch = dn.Batch(g16k.num_nodes, 300, [20], direction)
+    targets = target_batch(g16k.num_nodes, 300, 3)
+    view = gpu_sample(g16k, batch, targets, seed=11)
+    assert_dense_equal(view, oracle.dense_sample(g16k.oracle, targets, [20], seed=11, direction=direction))
+    batch2 = dn.Batch(g16k.num_nodes, 64, [4, 3], direction)
+    targets = target_batch(g16k.num_nodes, 64, 4)
+    view = gpu_sample(g16k, batch2, targets, seed=12)
+    assert_dense_equal(view, oracle.dense_sample(g16k.oracle, targets, [4, 3], seed=12, direction=direction))
+
+
+@pytest.mark.parametrize("fanouts", [[1], [3], [4], [5, 5], [8, 1], [16], [17], [32, 2], [33], [64], [2, 2, 2, 2],
+                                     [3, 2, 2, 2, 2, 2]])
+def test_fanout_shapes(g16k, fanouts):
+    """Every lane-group width (4..64), the largest fanout and the deepest supported model."""
+    batch = dn.Batch(g16k.num_nodes, 100, fanouts)
+    targets = target_batch(g16k.num_nodes, 100, 7)
+    view = gpu_sample(g16k, batch, targets, seed=21)
+    assert_dense_equal(view, oracle.dense_sample(g16k.oracle, targets, fanouts, seed=21))
+
+
+def test_hubs_isolated_nodes_and_partial_batches(g16k):
+    deg = np.diff(g16k.oracle.rowptr_out)
+    batch = dn.Batch(g16k.num_nodes, 256, [10, 5])
+    hubs = np.argsort(deg)[-40:].astype(np.int32)
+    view = gpu_sample(g16k, batch, hubs, seed=1)                      # fewer targets than capacity
+    assert_dense_equal(view, oracle.dense_sample(g16k.oracle, hubs, [10, 5], seed=1))
+    iso = np.nonzero(deg == 0)[0][:17].astype(np.int32)
+    view = gpu_sample(g16k, batch, iso, seed=1)                       # nobody has a neighbour
+    d = oracle.dense_sample(g16k.oracle, iso, [10, 5], seed=1)
+    assert_dense_equal(view, d)
+    assert len(d.nbrs) == 0
+    view = gpu_sample(g16k, batch, np.zeros(0, dtype=np.int32), seed=1)   # empty batch
+    assert_dense_equal(view, oracle.dense_sample(g16k.oracle, [], [10, 5], seed=1))
+    one = np.array([int(hubs[-1])], dtype=np.int32)
+    view = gpu_sample(g16k, batch, one, seed=2)
+    assert_dense_equal(view, oracle.dense_sample(g16k.oracle, one, [10, 5], seed=2))
+
+
+def test_exhaustive_fanout_small_graphs():
+    """Fanout >= every degree: nothing is random, whole adjacency lists are copied."""
+    rng = np.random.default_rng(3)
+    for trial in range(6):
+        n = int(rng.integers(5, 200))
+        rowptr, col = random_small_graph(rng, n, 2.0)
+        rpi, coli = transpose_np(rowptr, col)
+        dg = DeviceGraph(rowptr, col, rpi, coli)
+        k = 1 + trial % 3
+        fan = [64] * k
+        targets = rng.choice(n, size=min(n, 1 + trial), replace=False).astype(np.int32)
+        for direction in (0, 2):
+            batch = dn.Batch(n, len(targets), fan, direction)
+            view = gpu_sample(dg, batch, targets, seed=trial)
+            assert_dense_equal(view, oracle.dense_sample(dg.oracle, targets, fan, seed=trial, direction=direction))
+
+
+def test_whole_graph_as_targets(g16k):
+    """Maximum size: every node is a target (the seen-bitmap is full, no new node can appear)."""
+    n = g16k.num_nodes
+    batch = dn.Batch(n, n, [3, 2])
+    targets = np.random.default_rng(0).permutation(n).astype(np.int32)
+    view = gpu_sample(g16k, batch, targets, seed=3)
+    d = oracle.dense_sample(g16k.oracle, targets, [3, 2], seed=3)
+    assert_dense_equal(view, d)
+    assert d.node_id_offsets.tolist() == [0, 0, 0, n]
+
+
+def test_invalid_targets_are_reported_not_fatal(g16k):
+    batch = dn.Batch(g16k.num_nodes, 16, [4, 2])
+    t = torch.tensor([1, 2, 3, 2], dtype=torch.int32, device="cuda:0")
+    dn.dense_sample(batch, g16k.graph, t, 0)
+    with pytest.raises(dn.DenseError) as e:
+        batch.counts()
+    assert e.value.code == -5
+    t = torch.tensor([1, g16k.num_nodes, -4], dtype=torch.int32, device="cuda:0")
+    dn.dense_sample(batch, g16k.graph, t, 0)
+    with pytest.raises(dn.DenseError) as e:
+        batch.counts()
+    assert e.value.code == -5
+    # the batch object is clean again afterwards
+    targets = target_batch(g16k.num_nodes, 16, 0)
+    view = gpu_sample(g16k, batch, targets, seed=5)
+    assert_dense_equal(view, oracle.dense_sample(g16k.oracle, targets, [4, 2], seed=5))
+    with pytest.raises(dn.DenseError) as e:                            # more targets than the capacity
+        dn.dense_sample(batch, g16k.graph, torch.arange(17, dtype=torch.int32, device="cuda:0"), 0)
+    assert e.value.code == -2
+
+
+@pytest.mark.parametrize("dtype,dim", [("f32", 32), ("f32", 128), ("f32", 100), ("f32", 7), ("bf16", 768),
+                                       ("bf16", 64), ("bf16", 5)])
+def test_gather_rows_bit_exact(g16k, dtype, dim):
+    from workloads import feature_table
+    cfg = CONFIGS[0]
+    batch = dn.Batch(cfg.num_nodes, cfg.batch, cfg.fanouts)
+    targets = target_batch(cfg.num_nodes, cfg.batch, 1)
+    view = gpu_sample(g16k, batch, targets, seed=4)
+    table = feature_table(cfg.num_nodes, dim, dtype, seed=2)
+    out = torch.full((batch.node_capacity, dim), -7.0, dtype=table.dtype, device="cuda:0")
+    dn.dense_gather(batch, table.to("cuda:0"), out)
+    n = len(view["node_ids"])
+    as_bits = (lambda t: t.view(torch.int16).numpy()) if dtype == "bf16" else (lambda t: t.view(torch.int32).numpy())
+    want = oracle.dense_gather(as_bits(table), oracle.dense_sample(g16k.oracle, targets, cfg.fanouts, seed=4).node_ids)
+    got = as_bits(out.cpu())
+    assert np.array_equal(got[:n], want)
+    assert bool((out[n:].float() == -7.0).all())                      # rows past N are not touched
+
+
+def test_gather_strided_table(g16k):
+    cfg = CONFIGS[0]
+    batch = dn.Batch(cfg.num_nodes, 64, [5])
+    targets = target_batch(cfg.num_nodes, 64, 2)
+    view = gpu_sample(g16k, batch, targets, seed=4)
+    wide = torch.randn((cfg.num_nodes, 48), device="cuda:0")
+    table = wide[:, :32]                                              # row stride 48, width 32
+    out = torch.zeros((batch.node_capacity, 32), device="cuda:0")
+    dn.dense_gather(batch, table, out)
+    n = len(view["node_ids"])
+    assert torch.equal(out[:n].cpu(), table.cpu()[torch.from_numpy(view["node_ids"]).long()])
