@@ -17,11 +17,18 @@ Readings of points the paper leaves open:
     an empty neighbourhood contributes a zero mean; no dropout, no output normalisation.
     aggregation="sum" with identity weights reproduces Algorithm 3 as printed.
   - precision: mode "exact" is fp64 throughout.  Mode "bf16" models matrix-core operands:
-    both GEMM operands are rounded to bfloat16 (round-to-nearest-even), products and sums
-    stay fp64.  The value that gets rounded is produced in the arithmetic the device
-    uses at that point, because a rounding decision must be taken in one precision on
-    both sides: the neighbour mean is an fp32 sum in ascending slot order followed by an
-    fp32 division, activations and upstream gradients are stored as fp32.
+    every GEMM operand is a sum of bfloat16 terms (round-to-nearest-even), products and
+    sums stay fp64.  Operands that derive from the caller's inputs by arithmetic both
+    sides can repeat bit for bit (H^0 rows, the layer-1 neighbour mean, weights, the
+    upstream gradient dL/dH^k) are ONE term, bf16(x).  Operands computed on the device
+    through a matrix-core accumulation, whose last bits depend on the accumulation order
+    (activations H^i for i >= 1, neighbour means of them, back-propagated dZ^i for i < k),
+    are TWO terms, bf16(x) + bf16(x - bf16(x)): a rounding decision has to be taken in one
+    precision on both sides, and with a second term the sum no longer depends on which
+    way the first one was rounded.  The value that gets split is produced in the
+    arithmetic the device uses at that point: the neighbour mean is an fp32 sum in
+    ascending slot order followed by an fp32 division, activations and gradients are
+    stored as fp32.
   - backward: the gradient of the layer above with respect to Z passes where Z > 0;
     dW = operand^T dZ, db = column sums of dZ, and the gradient with respect to the input
     rows is the self part plus, for every neighbour slot, dM[owner] / count[owner].
@@ -30,6 +37,16 @@ from dataclasses import dataclass, field
 from typing import List, Optional
 
 import numpy as np
+
+
+def bf16_terms(x: np.ndarray, terms: int) -> np.ndarray:
+    """x as a sum of `terms` bfloat16 values (1 or 2), returned in fp64."""
+    x32 = np.ascontiguousarray(x, dtype=np.float32)
+    hi = round_bf16(x32)
+    if terms == 1:
+        return hi.astype(np.float64)
+    lo = round_bf16(x32 - hi)            # x32 - hi is exact in fp32
+    return hi.astype(np.float64) + lo.astype(np.float64)
 
 
 def round_bf16(x: np.ndarray) -> np.ndarray:
@@ -126,6 +143,12 @@ def sage_forward(dense, h0: np.ndarray, params: SageParams, mode: str = "exact")
     k = len(params.w_self)
     rb = round_bf16 if mode == "bf16" else (lambda a: a)
     store = (lambda a: a.astype(np.float32)) if mode == "bf16" else (lambda a: a.astype(np.float64))
+
+    def operand(a, layer):
+        if mode != "bf16":
+            return a.astype(np.float64)
+        return bf16_terms(a, 1 if layer == 1 else 2)
+
     view = dense_layer_view(dense, 1)
     h = store(np.asarray(h0))
     st = ForwardState()
@@ -135,8 +158,8 @@ def sage_forward(dense, h0: np.ndarray, params: SageParams, mode: str = "exact")
         counts = np.diff(view.nbr_offsets)
         nbr_aggr = _segment_reduce(h, view, params.aggregation, np.float32 if mode == "bf16" else np.float64)
         self_repr = h[n_prev:]
-        a_self = rb(self_repr).astype(np.float64)
-        a_nbr = rb(nbr_aggr).astype(np.float64)
+        a_self = operand(self_repr, i)
+        a_nbr = operand(nbr_aggr, i)
         w_s = rb(params.w_self[i - 1]).astype(np.float64)
         w_n = rb(params.w_nbr[i - 1]).astype(np.float64)
         z = a_self @ w_s + a_nbr @ w_n + params.bias[i - 1].astype(np.float64)[None, :]
@@ -178,7 +201,7 @@ def sage_backward(st: ForwardState, params: SageParams, grad_out: np.ndarray, mo
         else:
             d_z = g
         d_zs[i - 1] = d_z
-        d_zb = rb(d_z).astype(np.float64)
+        d_zb = d_z if mode != "bf16" else bf16_terms(d_z, 1 if i == k else 2)
         w_s = rb(params.w_self[i - 1]).astype(np.float64)
         w_n = rb(params.w_nbr[i - 1]).astype(np.float64)
         d_ws[i - 1] = ls.self_op.T @ d_zb

@@ -63,6 +63,7 @@ def load_library():
         "dn_model_create": (ctypes.c_int, [pp, vp, i32, ctypes.POINTER(i32), i32, vp, sz, vp]),
         "dn_model_set_weights": (ctypes.c_int, [vp, pp, pp, pp, vp]),
         "dn_model_destroy": (None, [vp]),
+        "dn_model_status": (ctypes.c_int, [vp, ctypes.POINTER(i32), vp]),
         "sage_forward": (ctypes.c_int, [vp, vp, vp, vp, vp]),
         "sage_backward": (ctypes.c_int, [vp, vp, vp, pp, pp, pp, vp, vp]),
     }
@@ -199,6 +200,12 @@ class Model:
         if getattr(self, "handle", None) and _lib is not None:
             _lib.dn_model_destroy(self.handle)
             self.handle = None
+
+    def status(self):
+        """(sign fix-ups of the last ReLU layer, queue-overflow flag); waits for the stream."""
+        buf = (ctypes.c_int32 * 2)()
+        _check(load_library().dn_model_status(self.handle, buf, _stream()))
+        return int(buf[0]), int(buf[1])
 
     def set_weights(self, w_self: Sequence[torch.Tensor], w_nbr: Sequence[torch.Tensor], bias: Sequence[torch.Tensor]):
         for i in range(self.k):

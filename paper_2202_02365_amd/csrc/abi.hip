@@ -36,8 +36,9 @@ int fill_batch_caps(dn_batch* b, int64_t V, int32_t max_targets, int32_t k, cons
     if (direction < DN_DIR_OUT || direction > DN_DIR_BOTH) return dn_fail(DN_EINVAL, "direction must be 0, 1 or 2");
     const int mult = direction == DN_DIR_BOTH ? 2 : 1;
     std::memset(b, 0, sizeof(*b));
+    if (max_targets > V) max_targets = (int32_t)V;          // targets are pairwise distinct
     b->V = V; b->k = k; b->direction = direction; b->max_targets = max_targets;
-    b->cap_level[0] = max_targets < V ? max_targets : V;
+    b->cap_level[0] = max_targets;
     b->cap_nodes = b->cap_level[0];
     b->cap_slots = 0;
     for (int h = 0; h < k; ++h) {
@@ -102,8 +103,12 @@ int fill_model(dn_model* m, const dn_batch* b, int32_t k, const int32_t* dims, i
     for (int i = 1; i <= k; ++i) {
         dn_layer_bufs& L = m->layer[i - 1];
         L.d_in = dims[i - 1]; L.d_out = dims[i];
-        L.kp = (int32_t)dn_round_up(2 * (int64_t)L.d_in, 64);
+        L.xterms = i == 1 ? 1 : 2;
+        L.zterms = i == k ? 1 : 2;
+        L.kx = 2 * L.d_in * L.xterms;
+        L.kp = (int32_t)dn_round_up(L.kx, 64);
         L.np = (int32_t)dn_round_up(L.d_out, 64);
+        L.nz = L.np * L.zterms;
         int64_t rows = 0;
         for (int h = 0; h <= k - i; ++h) rows += b->cap_level[h];
         if (rows > b->V) rows = b->V;
@@ -116,24 +121,30 @@ int fill_model(dn_model* m, const dn_batch* b, int32_t k, const int32_t* dims, i
 void carve_model(dn_model* m, const dn_batch* b, Carver& c)
 {
     const int k = m->k;
-    int64_t max_dzb = 0, max_dzbt = 0, max_xt = 0, max_dx = 0, max_g = 0, max_w = 0, max_db = 0;
+    int64_t max_dzb = 0, max_dzbt = 0, max_xt = 0, max_dx = 0, max_g = 0, max_w = 0, max_db = 0, max_fix = 4096;
     for (int i = 1; i <= k; ++i) {
         dn_layer_bufs& L = m->layer[i - 1];
         L.x = c.take<dn_bf16>(L.rows_pad * L.kp);
         L.h = (i < k) ? c.take<float>(L.rows_pad * L.d_out) : nullptr;
         L.wt = c.take<dn_bf16>(dn_round_up(L.d_out, 128) * L.kp);
-        L.w = c.take<dn_bf16>(dn_round_up(2 * (int64_t)L.d_in, 128) * L.np);
+        L.w = c.take<dn_bf16>(dn_round_up(2 * (int64_t)L.d_in, 128) * L.nz);
         L.bias = c.take<float>(L.d_out);
-        max_dzb = std::max<int64_t>(max_dzb, L.rows_pad * L.np);
+        L.rownorm = c.take<float>(L.rows_pad);
+        L.colnorm = c.take<float>(L.d_out);
+        max_dzb = std::max<int64_t>(max_dzb, L.rows_pad * L.nz);
         max_dzbt = std::max<int64_t>(max_dzbt, dn_round_up(L.d_out, 128) * L.rows_pad);
         max_xt = std::max<int64_t>(max_xt, dn_round_up(L.kp, 128) * L.rows_pad);
-        max_dx = std::max<int64_t>(max_dx, L.rows_pad * L.kp);
-        max_w = std::max<int64_t>(max_w, 2 * (int64_t)L.d_in * L.d_out);
+        max_dx = std::max<int64_t>(max_dx, L.rows_pad * 2 * L.d_in);
+        max_w = std::max<int64_t>(max_w, (int64_t)L.kx * L.d_out * L.zterms);
         max_db = std::max<int64_t>(max_db, ((L.rows_cap + 63) / 64 + 1) * L.d_out);
-        if (i < k) max_g = std::max<int64_t>(max_g, L.rows_pad * L.d_out);   // gradient w.r.t. H^i
+        if (i < k) {
+            max_g = std::max<int64_t>(max_g, L.rows_pad * L.d_out);   // gradient w.r.t. H^i
+            max_fix = std::max<int64_t>(max_fix, L.rows_cap * L.d_out / 16);
+        }
     }
     m->dzb = c.take<dn_bf16>(max_dzb);
-    m->dzbt = c.take<dn_bf16>(max_dzbt);
+    m->dzbt_term_stride = max_dzbt;
+    m->dzbt = c.take<dn_bf16>(2 * max_dzbt);
     m->xt = c.take<dn_bf16>(max_xt);
     m->dx = c.take<float>(max_dx);
     m->g[0] = c.take<float>(max_g);
@@ -142,6 +153,9 @@ void carve_model(dn_model* m, const dn_batch* b, Carver& c)
     m->partial_floats = (int64_t)m->splits * max_w;
     m->partial = c.take<float>(m->partial_floats);
     m->db_partial = c.take<float>(max_db);
+    m->fix_cap = max_fix;
+    m->fix_list = c.take<int64_t>(max_fix);
+    m->fix_count = c.take<int32_t>(64);
     (void)b;
 }
 
@@ -326,6 +340,15 @@ int dn_model_set_weights(dn_model* m, const float* const* d_w_self, const float*
 }
 
 void dn_model_destroy(dn_model* m) { delete m; }
+
+int dn_model_status(const dn_model* m, int32_t* status, void* stream)
+{
+    if (!m || !status) return dn_fail(DN_EINVAL, "null argument");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    DN_HIP(hipMemcpyAsync(status, m->fix_count, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    DN_HIP(hipStreamSynchronize(st));
+    return DN_OK;
+}
 
 int sage_forward(dn_model* m, const dn_batch* b, const void* d_H0, float* d_out, void* stream)
 {

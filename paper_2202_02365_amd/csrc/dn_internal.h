@@ -61,15 +61,21 @@ struct dn_batch {
 
 struct dn_layer_bufs {
     int32_t d_in, d_out;
-    int32_t kp;          // 2*d_in rounded up to 64: reduction length of the forward GEMM
-    int32_t np;          // d_out rounded up to 64: reduction length of the dX GEMM
+    int32_t xterms;      // bf16 terms per activation operand: 1 for layer 1 (derived from inputs), 2 above
+    int32_t zterms;      // bf16 terms of dZ in the backward GEMMs: 1 for the last layer (caller's gradient), 2 below
+    int32_t kx;          // valid columns of X: 2*d_in*xterms  = [self | mean] per term
+    int32_t kp;          // kx rounded up to 64: reduction length of the forward GEMM
+    int32_t np;          // d_out rounded up to 64
+    int32_t nz;          // np*zterms: row length of bf16(dZ) = reduction length of the dX GEMM
     int64_t rows_cap;    // capacity of output rows of this layer
     int64_t rows_pad;    // rows_cap rounded up to 128
-    dn_bf16* x;        // [rows_pad x kp]  [bf16(self) | bf16(mean) | 0]
-    float* h;                 // [rows_pad x d_out] layer output (not for the last layer)
-    dn_bf16* wt;       // [round128(d_out) x kp]  Wcat^T, zero padded
-    dn_bf16* w;        // [round128(2*d_in) x np] Wcat, zero padded
-    float* bias;              // [d_out]
+    dn_bf16* x;          // [rows_pad x kp]
+    float* h;            // [rows_pad x d_out] layer output (not for the last layer)
+    dn_bf16* wt;         // [round128(d_out) x kp]   Wcat^T repeated per X term, zero padded
+    dn_bf16* w;          // [round128(2*d_in) x nz]  Wcat repeated per dZ term, zero padded
+    float* bias;         // [d_out]
+    float* rownorm;      // [rows_pad] L2 norm of each X row (bounds the accumulation error of Z)
+    float* colnorm;      // [d_out]    L2 norm of each Wcat^T row
 };
 
 struct dn_model {
@@ -78,9 +84,14 @@ struct dn_model {
     dn_layer_bufs layer[DN_MAX_LAYERS];
     // backward temporaries, sized for the largest layer
     dn_bf16 *dzb, *dzbt, *xt;
+    int64_t dzbt_term_stride;      // elements between the hi and lo transposes of dZ
     float *dx, *g[2], *partial, *db_partial;
     int64_t partial_floats;
     int32_t splits;
+    // pre-activations too close to zero for the fp32 accumulation to settle their sign
+    int64_t* fix_list;             // entries (row << 16 | column)
+    int32_t* fix_count;            // [0] entries pushed, [1] sticky overflow flag
+    int64_t fix_cap;
     const void* h0;                // H^0 of the last forward
     uint64_t fwd_serial;           // sample the saved activations belong to
     int32_t weights_set;

@@ -27,12 +27,15 @@ __device__ __forceinline__ float load_elem(const uint16_t* p) { return bf16_to_f
 // One group of LANES lanes per output row; lane handles columns lane*V .. lane*V+V-1, then
 // +LANES*V, ...  The neighbour sum runs over the row's slots in ascending order in fp32 and is
 // divided by the count in fp32 (this fixes the value that gets rounded to bf16).
-// Writes X[row] = [ bf16(self) | bf16(mean) ], the A operand of the layer's GEMM.
-template <typename TIN, int V, int LANES>
+// Writes the A operand of the layer's GEMM, X[row] = [ self | mean ] as bf16, followed for
+// TERMS == 2 by the bf16 of what the first rounding left over, [ self_lo | mean_lo ]; and the
+// L2 norm of the row (bound of the accumulation error of its dot products).
+template <typename TIN, int V, int LANES, int TERMS>
 __global__ __launch_bounds__(TPB) void k_aggregate(const int32_t* __restrict__ hdr, int layer,
                                                    const int32_t* __restrict__ nbr_offsets,
                                                    const int32_t* __restrict__ repr_map, const TIN* __restrict__ H,
-                                                   int d, uint16_t* __restrict__ X, int kp)
+                                                   int d, uint16_t* __restrict__ X, int kp, float* __restrict__ rownorm,
+                                                   int32_t* __restrict__ fix_count)
 {
     const int N = hdr[HDR_N];
     const int off_in = hdr[HDR_NODE_OFF + layer - 1];     // H row 0 = node_ids position off_in
@@ -41,6 +44,7 @@ __global__ __launch_bounds__(TPB) void k_aggregate(const int32_t* __restrict__ h
     const int rows = N - off_out;
     const int lane = threadIdx.x % LANES;
     constexpr int GROUPS = TPB / LANES;
+    if (blockIdx.x == 0 && threadIdx.x == 0) fix_count[0] = 0;    // the GEMM that follows fills the queue
     for (int ro = blockIdx.x * GROUPS + threadIdx.x / LANES; ro < rows; ro += gridDim.x * GROUPS) {
         const int p = off_out + ro;
         const int q = p - off1;
@@ -48,6 +52,7 @@ __global__ __launch_bounds__(TPB) void k_aggregate(const int32_t* __restrict__ h
         const float cnt = (float)(end - beg);
         const TIN* self = H + (int64_t)(p - off_in) * d;
         uint16_t* xrow = X + (int64_t)ro * kp;
+        float sq = 0.f;
         for (int c0 = lane * V; c0 < d; c0 += LANES * V) {
             float acc[V];
 #pragma unroll
@@ -63,29 +68,46 @@ __global__ __launch_bounds__(TPB) void k_aggregate(const int32_t* __restrict__ h
 #pragma unroll
             for (int e = 0; e < V; ++e) {
                 const float mean = end > beg ? acc[e] / cnt : 0.f;
-                xrow[c0 + e] = f32_to_bf16(load_elem(self + c0 + e));
-                xrow[d + c0 + e] = f32_to_bf16(mean);
+                const float sv = load_elem(self + c0 + e);
+                const uint16_t s_hi = f32_to_bf16(sv), m_hi = f32_to_bf16(mean);
+                xrow[c0 + e] = s_hi;
+                xrow[d + c0 + e] = m_hi;
+                const float s_hf = bf16_to_f32(s_hi), m_hf = bf16_to_f32(m_hi);
+                sq += s_hf * s_hf + m_hf * m_hf;
+                if (TERMS == 2) {
+                    const uint16_t s_lo = f32_to_bf16(sv - s_hf), m_lo = f32_to_bf16(mean - m_hf);
+                    xrow[2 * d + c0 + e] = s_lo;
+                    xrow[3 * d + c0 + e] = m_lo;
+                    const float s_lf = bf16_to_f32(s_lo), m_lf = bf16_to_f32(m_lo);
+                    sq += s_lf * s_lf + m_lf * m_lf;
+                }
             }
         }
+#pragma unroll
+        for (int o = LANES / 2; o > 0; o >>= 1) sq += __shfl_xor(sq, o, LANES);
+        if (lane == 0) rownorm[ro] = sqrtf(sq) * 1.0001f;
     }
 }
 
 // ---------------------------------------------------------------- backward: dZ, its transpose, db
 // Tile of 64 rows x 64 columns per workgroup.  dZ = G (.) [H > 0] (ReLU layers) or G.
-// Writes bf16(dZ) row-major [rows x np] (zero in the padding columns), its transpose
-// [np x rows_pad] (zero for rows up to the next multiple of 64, which the dW reduction reads),
-// and the tile's column sums of the unrounded dZ for the bias gradient.
+// Writes bf16 terms of dZ row-major [rows x TERMS*np] (hi block, then lo block; zero in the
+// padding columns), their transposes [np x rows_pad] per term (zero for rows up to the next
+// multiple of 64, which the dW reduction reads), and the tile's column sums of the unrounded dZ
+// for the bias gradient.
+template <int TERMS>
 __global__ __launch_bounds__(TPB) void k_dz(const int32_t* __restrict__ hdr, int layer, const float* __restrict__ G, int ldg,
                                             const float* __restrict__ Hout, int d_out, int np, int relu,
                                             uint16_t* __restrict__ dzb, uint16_t* __restrict__ dzbt, int64_t rows_pad,
-                                            float* __restrict__ db_partial)
+                                            int64_t term_stride, float* __restrict__ db_partial)
 {
-    __shared__ uint16_t tile[64][66];
+    __shared__ uint16_t tile[TERMS][64][66];
     __shared__ float colsum[4][64];
     const int rows = hdr[HDR_N] - hdr[HDR_NODE_OFF + layer];
     const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
     if (r0 >= ((rows + 63) / 64) * 64) return;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;    // ty: 0..3
+    const int nz = TERMS * np;
     float csum = 0.f;
     for (int rr = ty; rr < 64; rr += 4) {
         const int r = r0 + rr, n = c0 + tx;
@@ -95,16 +117,22 @@ __global__ __launch_bounds__(TPB) void k_dz(const int32_t* __restrict__ hdr, int
             if (relu && !(Hout[(int64_t)r * d_out + n] > 0.f)) v = 0.f;
         }
         csum += v;
-        const uint16_t h = f32_to_bf16(v);
-        tile[rr][tx] = h;
-        if (r < rows) dzb[(int64_t)r * np + n] = h;
+        const uint16_t hi = f32_to_bf16(v);
+        tile[0][rr][tx] = hi;
+        if (r < rows) dzb[(int64_t)r * nz + n] = hi;
+        if (TERMS == 2) {
+            const uint16_t lo = f32_to_bf16(v - bf16_to_f32(hi));
+            tile[TERMS - 1][rr][tx] = lo;
+            if (r < rows) dzb[(int64_t)r * nz + np + n] = lo;
+        }
     }
     colsum[ty][tx] = csum;
     __syncthreads();
     if (ty == 0 && c0 + tx < d_out)
         db_partial[(int64_t)blockIdx.y * d_out + c0 + tx] = (colsum[0][tx] + colsum[1][tx]) + (colsum[2][tx] + colsum[3][tx]);
-    for (int cc = ty; cc < 64; cc += 4)
-        dzbt[(int64_t)(c0 + cc) * rows_pad + r0 + tx] = tile[tx][cc];
+    for (int t = 0; t < TERMS; ++t)
+        for (int cc = ty; cc < 64; cc += 4)
+            dzbt[t * term_stride + (int64_t)(c0 + cc) * rows_pad + r0 + tx] = tile[t][tx][cc];
 }
 
 __global__ __launch_bounds__(TPB) void k_db_reduce(const int32_t* __restrict__ hdr, int layer,
@@ -148,7 +176,7 @@ __global__ __launch_bounds__(TPB) void k_aggregate_bwd(const int32_t* __restrict
                                                        const int32_t* __restrict__ nbr_offsets,
                                                        const int32_t* __restrict__ slot_owner,
                                                        const int32_t* __restrict__ tr_ptr, const int32_t* __restrict__ tr_val,
-                                                       const float* __restrict__ dX, int kp, int d,
+                                                       const float* __restrict__ dX, int ldx, int d,
                                                        float* __restrict__ Gin)
 {
     const int N = hdr[HDR_N];
@@ -165,13 +193,13 @@ __global__ __launch_bounds__(TPB) void k_aggregate_bwd(const int32_t* __restrict
         for (int c0 = lane * V; c0 < d; c0 += LANES * V) {
             float acc[V];
 #pragma unroll
-            for (int e = 0; e < V; ++e) acc[e] = (p >= off_out) ? dX[(int64_t)(p - off_out) * kp + c0 + e] : 0.f;
+            for (int e = 0; e < V; ++e) acc[e] = (p >= off_out) ? dX[(int64_t)(p - off_out) * ldx + c0 + e] : 0.f;
             for (int t = beg; t < end; ++t) {
                 const int j = tr_val[t];
                 if (j < first_slot) continue;
                 const int q = slot_owner[j];
                 const float inv = 1.0f / (float)(nbr_offsets[q + 1] - nbr_offsets[q]);
-                const float* src = dX + (int64_t)(q + off1 - off_out) * kp + d + c0;
+                const float* src = dX + (int64_t)(q + off1 - off_out) * ldx + d + c0;
 #pragma unroll
                 for (int e = 0; e < V; ++e) acc[e] += src[e] * inv;
             }
@@ -181,8 +209,8 @@ __global__ __launch_bounds__(TPB) void k_aggregate_bwd(const int32_t* __restrict
     }
 }
 
-template <typename TIN>
-int launch_aggregate(const dn_model* m, const dn_batch* b, int i, const TIN* H, hipStream_t st)
+template <typename TIN, int TERMS>
+int launch_aggregate_t(const dn_model* m, const dn_batch* b, int i, const TIN* H, hipStream_t st)
 {
     const dn_layer_bufs& L = m->layer[i - 1];
     const int d = L.d_in;
@@ -195,9 +223,9 @@ int launch_aggregate(const dn_model* m, const dn_batch* b, int i, const TIN* H, 
     int64_t grid = (L.rows_cap + groups - 1) / groups;
     if (grid > 8192) grid = 8192;
     if (grid < 1) grid = 1;
-#define DN_AGG(VV, LL)                                                                                              \
-    hipLaunchKernelGGL((k_aggregate<TIN, VV, LL>), dim3((int)grid), dim3(TPB), 0, st, b->hdr, i, b->nbr_offsets,    \
-                       b->repr_map, H, d, X, L.kp)
+#define DN_AGG(VV, LL)                                                                                                 \
+    hipLaunchKernelGGL((k_aggregate<TIN, VV, LL, TERMS>), dim3((int)grid), dim3(TPB), 0, st, b->hdr, i, b->nbr_offsets, \
+                       b->repr_map, H, d, X, L.kp, L.rownorm, m->fix_count)
     if (vec4) {
         switch (lanes) {
             case 4: DN_AGG(4, 4); break;
@@ -235,7 +263,7 @@ int launch_aggregate_bwd(const dn_model* m, const dn_batch* b, int i, float* gin
     if (grid < 1) grid = 1;
 #define DN_AGGB(VV, LL)                                                                                               \
     hipLaunchKernelGGL((k_aggregate_bwd<VV, LL>), dim3((int)grid), dim3(TPB), 0, st, b->hdr, i, b->nbr_offsets,       \
-                       b->slot_owner, b->tr_ptr, b->tr_val[0], m->dx, L.kp, d, gin)
+                       b->slot_owner, b->tr_ptr, b->tr_val[0], m->dx, 2 * d, d, gin)
     if (vec4) {
         switch (lanes) {
             case 4: DN_AGGB(4, 4); break;
@@ -266,9 +294,11 @@ int dn_launch_forward(dn_model* m, const dn_batch* b, const void* h0, float* out
     for (int i = 1; i <= k; ++i) {
         int rc;
         if (i == 1 && m->in_dtype == DN_BF16)
-            rc = launch_aggregate<uint16_t>(m, b, 1, static_cast<const uint16_t*>(h0), st);
+            rc = launch_aggregate_t<uint16_t, 1>(m, b, 1, static_cast<const uint16_t*>(h0), st);
+        else if (i == 1)
+            rc = launch_aggregate_t<float, 1>(m, b, 1, static_cast<const float*>(h0), st);
         else
-            rc = launch_aggregate<float>(m, b, i, i == 1 ? static_cast<const float*>(h0) : m->layer[i - 2].h, st);
+            rc = launch_aggregate_t<float, 2>(m, b, i, m->layer[i - 2].h, st);
         if (rc) return rc;
         const dn_layer_bufs& L = m->layer[i - 1];
         rc = dn_gemm_forward(m, b, i, i == k ? out : L.h, L.d_out, st);
@@ -287,10 +317,14 @@ int dn_launch_backward(dn_model* m, dn_batch* b, const float* grad_out, float* c
     for (int i = k; i >= 1; --i) {
         const dn_layer_bufs& L = m->layer[i - 1];
         const unsigned row_tiles = (unsigned)((L.rows_cap + 63) / 64);
-        hipLaunchKernelGGL(k_dz, dim3((unsigned)(L.np / 64), row_tiles ? row_tiles : 1), dim3(TPB), 0, st, b->hdr, i, g,
-                           L.d_out, i < k ? L.h : nullptr, L.d_out, L.np, i < k ? 1 : 0,
-                           reinterpret_cast<uint16_t*>(m->dzb), reinterpret_cast<uint16_t*>(m->dzbt), L.rows_pad,
-                           m->db_partial);
+        if (L.zterms == 2)
+            hipLaunchKernelGGL((k_dz<2>), dim3((unsigned)(L.np / 64), row_tiles ? row_tiles : 1), dim3(TPB), 0, st, b->hdr,
+                               i, g, L.d_out, L.h, L.d_out, L.np, 1, reinterpret_cast<uint16_t*>(m->dzb),
+                               reinterpret_cast<uint16_t*>(m->dzbt), L.rows_pad, m->dzbt_term_stride, m->db_partial);
+        else
+            hipLaunchKernelGGL((k_dz<1>), dim3((unsigned)(L.np / 64), row_tiles ? row_tiles : 1), dim3(TPB), 0, st, b->hdr,
+                               i, g, L.d_out, nullptr, L.d_out, L.np, 0, reinterpret_cast<uint16_t*>(m->dzb),
+                               reinterpret_cast<uint16_t*>(m->dzbt), L.rows_pad, m->dzbt_term_stride, m->db_partial);
         DN_LAUNCH_CHECK("k_dz");
         hipLaunchKernelGGL(k_db_reduce, dim3((L.d_out + TPB - 1) / TPB), dim3(TPB), 0, st, b->hdr, i, m->db_partial,
                            L.d_out, dbias[i - 1]);

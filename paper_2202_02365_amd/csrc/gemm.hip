@@ -13,6 +13,14 @@
 // are in flight while the current one is multiplied.  M and the dW reduction length live in
 // device memory (they depend on the sample); the grid is sized by capacity and surplus
 // workgroups leave at once.
+//
+// Operand terms: an operand the device computed through an MFMA accumulation is carried as two
+// bf16 terms (hi + lo), laid side by side along the reduction index, with the other operand
+// repeated; an operand that derives from the caller's inputs is one term.
+//
+// ReLU sign: where |Z| is below a bound on the fp32 accumulation error (2 K 2^-24 |x| |w|), the
+// epilogue queues the element and k_relu_fixup recomputes that dot product in fp64, so that the
+// stored activation and the mask [Z > 0] used by the backward pass are those of the exact sum.
 #include "dn_internal.h"
 
 namespace {
@@ -36,6 +44,11 @@ struct GemmArgs {
     const float* bias;
     int relu;
     int64_t split_stride;   // floats between consecutive split partials
+    int terms;              // dW: reduction terms (hi, lo) of B; split index z = term * (gridDim.z / terms) + chunk group
+    int64_t b_term_stride;  // dW: elements between B's terms
+    // ReLU sign fix-up (EPI_BIAS_ACT with relu)
+    const float* rownorm; const float* colnorm; float gamma;
+    long long* fix_list; int* fix_count; long long fix_cap;
 };
 
 __device__ __forceinline__ int slot(int row, int c) { return row * 8 + (c ^ (row & 7)); }
@@ -52,11 +65,15 @@ __global__ __launch_bounds__(TPB) void k_gemm_nt(GemmArgs a)
     const int row0 = blockIdx.y * BM, col0 = blockIdx.x * BN;
     if (row0 >= M) return;
 
-    // reduction range of this split
+    // reduction range of this split (dW: the splits of every term cover the whole range)
     const int chunks = red / BK;
-    const int per = (chunks + gridDim.z - 1) / gridDim.z;
-    const int kc_begin = blockIdx.z * per;
+    const int groups = (EPI == EPI_SPLIT) ? (int)gridDim.z / a.terms : 1;
+    const int term = (EPI == EPI_SPLIT) ? (int)blockIdx.z / groups : 0;
+    const int grp = (EPI == EPI_SPLIT) ? (int)blockIdx.z % groups : 0;
+    const int per = (chunks + groups - 1) / groups;
+    const int kc_begin = grp * per;
     const int kc_end = min(chunks, kc_begin + per);
+    const uint16_t* Bbase = a.B + (int64_t)term * a.b_term_stride;
 
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -76,7 +93,7 @@ __global__ __launch_bounds__(TPB) void k_gemm_nt(GemmArgs a)
         for (int i = 0; i < 4; ++i) {
             const int id = t + TPB * i, row = id >> 3, c = id & 7;
             ra[i] = *reinterpret_cast<const u32x4*>(a.A + (int64_t)(row0 + row) * a.lda + k0 + c * 8);
-            rb[i] = *reinterpret_cast<const u32x4*>(a.B + (int64_t)(col0 + row) * a.ldb + k0 + c * 8);
+            rb[i] = *reinterpret_cast<const u32x4*>(Bbase + (int64_t)(col0 + row) * a.ldb + k0 + c * 8);
         }
     };
     auto store_tiles = [&]() {
@@ -121,6 +138,8 @@ __global__ __launch_bounds__(TPB) void k_gemm_nt(GemmArgs a)
             const int n = col0 + wn * 64 + j * 32 + (lane & 31);
             if (n >= a.ncols) continue;
             const float bv = (EPI == EPI_BIAS_ACT) ? a.bias[n] : 0.f;
+            const float cn = (EPI == EPI_BIAS_ACT && a.relu) ? a.gamma * a.colnorm[n] : 0.f;
+            const float bt = fabsf(bv) * 4.76837158e-7f;          // 2^-21 |b|: rounding of the bias add
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int m = row0 + wm * 64 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
@@ -128,7 +147,14 @@ __global__ __launch_bounds__(TPB) void k_gemm_nt(GemmArgs a)
                     float v = acc[i][j][e];
                     if (EPI == EPI_BIAS_ACT) {
                         v += bv;
-                        if (a.relu) v = fmaxf(v, 0.f);
+                        if (a.relu) {
+                            if (fabsf(v) <= cn * a.rownorm[m] + bt) {
+                                const int pos = atomicAdd(&a.fix_count[0], 1);
+                                if (pos < a.fix_cap) a.fix_list[pos] = ((long long)m << 16) | (long long)n;
+                                else a.fix_count[1] = 1;
+                            }
+                            v = fmaxf(v, 0.f);
+                        }
                     }
                     C[(int64_t)m * a.ldc + n] = v;
                 }
@@ -136,17 +162,47 @@ __global__ __launch_bounds__(TPB) void k_gemm_nt(GemmArgs a)
         }
 }
 
-// dW[kk][n] = sum over splits, in split order; rows kk < d go to dW_self, d <= kk < 2d to dW_nbr.
+// dW[kk][n] = sum over the X terms (rows kk + t*2d) and over the splits, in a fixed order;
+// rows kk < d go to dW_self, d <= kk < 2d to dW_nbr.
 __global__ __launch_bounds__(TPB) void k_dw_reduce(const float* __restrict__ partial, int64_t split_stride, int splits,
-                                                   int d_in, int d_out, float* __restrict__ dws, float* __restrict__ dwn)
+                                                   int xterms, int d_in, int d_out, float* __restrict__ dws,
+                                                   float* __restrict__ dwn)
 {
     const int idx = blockIdx.x * TPB + threadIdx.x;
     if (idx >= 2 * d_in * d_out) return;
     const int kk = idx / d_out, n = idx - kk * d_out;
     float s = 0.f;
-    for (int z = 0; z < splits; ++z) s += partial[(int64_t)z * split_stride + (int64_t)kk * d_out + n];
+    for (int t = 0; t < xterms; ++t)
+        for (int z = 0; z < splits; ++z)
+            s += partial[(int64_t)z * split_stride + (int64_t)(kk + t * 2 * d_in) * d_out + n];
     if (kk < d_in) dws[(int64_t)kk * d_out + n] = s;
     else dwn[(int64_t)(kk - d_in) * d_out + n] = s;
+}
+
+// One wave per queued element: Z = sum_k X[m][k] * Wt[n][k] + b[n] in fp64 (bf16 products are
+// exact in fp64, the sum is good to 2^-53 of the magnitudes), H[m][n] = fp32(max(Z, 0)).
+__global__ __launch_bounds__(TPB) void k_relu_fixup(const long long* __restrict__ fix_list, const int* __restrict__ fix_count,
+                                                    long long fix_cap, const uint16_t* __restrict__ X,
+                                                    const uint16_t* __restrict__ Wt, int kp, const float* __restrict__ bias,
+                                                    float* __restrict__ H, int ldh)
+{
+    const int lane = threadIdx.x & 63;
+    const long long total = min((long long)fix_count[0], fix_cap);
+    const int waves = gridDim.x * (TPB / 64);
+    for (long long it = (long long)blockIdx.x * (TPB / 64) + (threadIdx.x >> 6); it < total; it += waves) {
+        const long long ent = fix_list[it];
+        const int m = (int)(ent >> 16), n = (int)(ent & 0xffff);
+        const uint16_t* xr = X + (int64_t)m * kp;
+        const uint16_t* wr = Wt + (int64_t)n * kp;
+        double s = 0.0;
+        for (int kk = lane; kk < kp; kk += 64)
+            s += (double)__uint_as_float((uint32_t)xr[kk] << 16) * (double)__uint_as_float((uint32_t)wr[kk] << 16);
+        for (int d = 32; d > 0; d >>= 1) s += __shfl_down(s, d, 64);
+        if (lane == 0) {
+            const double z = s + (double)bias[n];
+            H[(int64_t)m * ldh + n] = (float)(z > 0.0 ? z : 0.0);
+        }
+    }
 }
 
 // fp32 weights -> the two zero-padded bf16 layouts (round to nearest even).
@@ -160,8 +216,8 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float x)
 
 __global__ __launch_bounds__(TPB) void k_pack_weights(const float* __restrict__ ws, const float* __restrict__ wn,
                                                       const float* __restrict__ bias, int d_in, int d_out, int kp, int np,
-                                                      uint16_t* __restrict__ wt, uint16_t* __restrict__ w,
-                                                      float* __restrict__ bias_out)
+                                                      int nz, int xterms, int zterms, uint16_t* __restrict__ wt,
+                                                      uint16_t* __restrict__ w, float* __restrict__ bias_out)
 {
     const int idx = blockIdx.x * TPB + threadIdx.x;
     if (idx < d_out) bias_out[idx] = bias[idx];
@@ -169,8 +225,21 @@ __global__ __launch_bounds__(TPB) void k_pack_weights(const float* __restrict__ 
     const int kk = idx / d_out, n = idx - kk * d_out;
     const float v = kk < d_in ? ws[(int64_t)kk * d_out + n] : wn[(int64_t)(kk - d_in) * d_out + n];
     const uint16_t h = f32_to_bf16(v);
-    wt[(int64_t)n * kp + kk] = h;
-    w[(int64_t)kk * np + n] = h;
+    for (int t = 0; t < xterms; ++t) wt[(int64_t)n * kp + t * 2 * d_in + kk] = h;
+    for (int t = 0; t < zterms; ++t) w[(int64_t)kk * nz + t * np + n] = h;
+}
+
+// colnorm[n] = L2 norm of row n of Wcat^T (all terms), one thread per row
+__global__ __launch_bounds__(TPB) void k_col_norms(const uint16_t* __restrict__ wt, int d_out, int kp, float* __restrict__ colnorm)
+{
+    const int n = blockIdx.x * TPB + threadIdx.x;
+    if (n >= d_out) return;
+    float s = 0.f;
+    for (int kk = 0; kk < kp; ++kk) {
+        const float v = __uint_as_float((uint32_t)wt[(int64_t)n * kp + kk] << 16);
+        s += v * v;
+    }
+    colnorm[n] = sqrtf(s) * 1.0001f;
 }
 
 template <int EPI>
@@ -194,8 +263,16 @@ int dn_gemm_forward(const dn_model* m, const dn_batch* b, int i, float* out, int
     a.B = reinterpret_cast<const uint16_t*>(L.wt); a.ldb = L.kp;
     a.C = out; a.ldc = ldc;
     a.hdr = b->hdr; a.layer = i; a.m_const = -1; a.ncols = L.d_out; a.red_const = L.kp;
-    a.bias = L.bias; a.relu = (i < m->k) ? 1 : 0; a.split_stride = 0;
-    return launch<EPI_BIAS_ACT>(a, L.rows_cap, 1, st);
+    a.bias = L.bias; a.relu = (i < m->k) ? 1 : 0; a.split_stride = 0; a.terms = 1; a.b_term_stride = 0;
+    a.rownorm = L.rownorm; a.colnorm = L.colnorm;
+    a.gamma = (float)L.kp * 1.1920929e-7f;                 // 2 K 2^-24: worst case of K fp32 additions, doubled
+    a.fix_list = reinterpret_cast<long long*>(m->fix_list); a.fix_count = m->fix_count; a.fix_cap = m->fix_cap;
+    int rc = launch<EPI_BIAS_ACT>(a, L.rows_cap, 1, st);
+    if (rc || !a.relu) return rc;
+    hipLaunchKernelGGL(k_relu_fixup, dim3(128), dim3(TPB), 0, st, a.fix_list, a.fix_count, a.fix_cap, a.A, a.B, L.kp,
+                       L.bias, out, (int)ldc);
+    DN_LAUNCH_CHECK("k_relu_fixup");
+    return DN_OK;
 }
 
 // dX = bf16(dZ) * Wcat^T   -> m->dx [rows x kp], columns [0, 2*d_in) valid.
@@ -203,11 +280,11 @@ int dn_gemm_dx(const dn_model* m, const dn_batch* b, int i, hipStream_t st)
 {
     const dn_layer_bufs& L = m->layer[i - 1];
     GemmArgs a{};
-    a.A = reinterpret_cast<const uint16_t*>(m->dzb); a.lda = L.np;
-    a.B = reinterpret_cast<const uint16_t*>(L.w); a.ldb = L.np;
-    a.C = m->dx; a.ldc = L.kp;
-    a.hdr = b->hdr; a.layer = i; a.m_const = -1; a.ncols = 2 * L.d_in; a.red_const = L.np;
-    a.bias = nullptr; a.relu = 0; a.split_stride = 0;
+    a.A = reinterpret_cast<const uint16_t*>(m->dzb); a.lda = L.nz;
+    a.B = reinterpret_cast<const uint16_t*>(L.w); a.ldb = L.nz;
+    a.C = m->dx; a.ldc = 2 * L.d_in;
+    a.hdr = b->hdr; a.layer = i; a.m_const = -1; a.ncols = 2 * L.d_in; a.red_const = L.nz;
+    a.bias = nullptr; a.relu = 0; a.split_stride = 0; a.terms = 1; a.b_term_stride = 0;
     return launch<EPI_PLAIN>(a, L.rows_cap, 1, st);
 }
 
@@ -222,15 +299,17 @@ int dn_gemm_dw(const dn_model* m, const dn_batch* b, int i, float* dws, float* d
     a.A = reinterpret_cast<const uint16_t*>(m->xt); a.lda = L.rows_pad;
     a.B = reinterpret_cast<const uint16_t*>(m->dzbt); a.ldb = L.rows_pad;
     a.C = m->partial; a.ldc = L.d_out;
-    a.hdr = b->hdr; a.layer = i; a.m_const = 2 * L.d_in; a.ncols = L.d_out; a.red_const = -1;
-    a.bias = nullptr; a.relu = 0; a.split_stride = (int64_t)2 * L.d_in * L.d_out;
-    if ((int64_t)splits * a.split_stride > m->partial_floats)
+    a.hdr = b->hdr; a.layer = i; a.m_const = L.kx; a.ncols = L.d_out; a.red_const = -1;
+    a.bias = nullptr; a.relu = 0; a.split_stride = (int64_t)L.kx * L.d_out;
+    a.terms = L.zterms; a.b_term_stride = m->dzbt_term_stride;
+    const int zsplits = splits * L.zterms;
+    if ((int64_t)zsplits * a.split_stride > m->partial_floats)
         return dn_fail(DN_ECAPACITY, "dW partial buffer too small");
-    int rc = launch<EPI_SPLIT>(a, 2 * L.d_in, splits, st);
+    int rc = launch<EPI_SPLIT>(a, L.kx, zsplits, st);
     if (rc) return rc;
     const int total = 2 * L.d_in * L.d_out;
-    hipLaunchKernelGGL(k_dw_reduce, dim3((total + TPB - 1) / TPB), dim3(TPB), 0, st, m->partial, a.split_stride, splits,
-                       L.d_in, L.d_out, dws, dwn);
+    hipLaunchKernelGGL(k_dw_reduce, dim3((total + TPB - 1) / TPB), dim3(TPB), 0, st, m->partial, a.split_stride, zsplits,
+                       L.xterms, L.d_in, L.d_out, dws, dwn);
     DN_LAUNCH_CHECK("k_dw_reduce");
     return DN_OK;
 }
@@ -243,9 +322,12 @@ int dn_launch_set_weights(dn_model* m, const float* const* ws, const float* cons
         const int total = 2 * L.d_in * L.d_out;
         const int n = total > L.d_out ? total : L.d_out;
         hipLaunchKernelGGL(k_pack_weights, dim3((n + TPB - 1) / TPB), dim3(TPB), 0, st, ws[i], wn[i], bias[i], L.d_in,
-                           L.d_out, L.kp, L.np, reinterpret_cast<uint16_t*>(L.wt), reinterpret_cast<uint16_t*>(L.w),
-                           L.bias);
+                           L.d_out, L.kp, L.np, L.nz, L.xterms, L.zterms, reinterpret_cast<uint16_t*>(L.wt),
+                           reinterpret_cast<uint16_t*>(L.w), L.bias);
         DN_LAUNCH_CHECK("k_pack_weights");
+        hipLaunchKernelGGL(k_col_norms, dim3((L.d_out + TPB - 1) / TPB), dim3(TPB), 0, st,
+                           reinterpret_cast<const uint16_t*>(L.wt), L.d_out, L.kp, L.colnorm);
+        DN_LAUNCH_CHECK("k_col_norms");
     }
     return DN_OK;
 }
