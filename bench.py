@@ -1,0 +1,272 @@
+#!/usr/bin/env python3
+"""Benchmark of the DENSE hot path on one MI355X.
+
+One step = one mini-batch through every step of the path: dense_sample (3-hop DENSE
+construction) -> dense_gather (H^0) -> sage_forward -> sage_backward, on synthetic inputs that
+are resident in HBM before the clock starts.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload rmat111m|rmat1m|rmat16k|...]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+N_BATCHES = 64                  # distinct target batches cycled through, sampling seed = batch index
+
+
+def log(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+def build_inputs(cfg, dev):
+    import torch
+    from workloads import rmat_csr, transpose_csr, feature_table, glorot_weights, training_subset, target_batch
+    t0 = time.time()
+    big = cfg.num_nodes > (1 << 22)
+    gen_dev = dev if big else "cpu"
+    rowptr, col = rmat_csr(cfg.num_nodes, cfg.num_edges, cfg.graph_seed, device=gen_dev)
+    rowptr_in = col_in = None
+    if cfg.direction != 0:
+        rowptr_in, col_in = transpose_csr(rowptr, col)
+    log("graph: V=%d E=%d (nominal %d) on %s in %.1fs" % (cfg.num_nodes, col.numel(), cfg.num_edges, gen_dev, time.time() - t0))
+    t0 = time.time()
+    table = feature_table(cfg.num_nodes, cfg.feat_dim, cfg.feat_dtype, cfg.feat_seed, device=gen_dev)
+    log("features: %d x %d %s in %.1fs" % (cfg.num_nodes, cfg.feat_dim, cfg.feat_dtype, time.time() - t0))
+    pool = training_subset(cfg.num_nodes, cfg.train_fraction, cfg.target_seed, device=gen_dev)
+    targets = [target_batch(pool.numel(), cfg.batch, bi, cfg.target_seed, pool=pool if cfg.train_fraction < 1 else None)
+               for bi in range(N_BATCHES)]
+    weights = glorot_weights(cfg.dims, cfg.weight_seed)
+    to = lambda t: None if t is None else t.to(dev)
+    return dict(rowptr=to(rowptr), col=to(col), rowptr_in=to(rowptr_in), col_in=to(col_in), table=to(table),
+                targets=targets, weights=weights)
+
+
+def algorithmic_work(tag, sizes, cfg, dims):
+    """Algorithmic bytes (HBM-bound kernels) or flops (GEMMs) of ONE launch of the kernel `tag`,
+    averaged over the batches; sizes = per-batch (node_id_offsets[0..k+1], E)."""
+    import numpy as np
+    k = cfg.num_layers
+    elt0 = 4 if cfg.feat_dtype == "f32" else 2
+    off = np.array([s[:k + 2] for s in sizes], dtype=np.float64)      # [batches, k+2]
+    E = np.array([s[k + 2] for s in sizes], dtype=np.float64)
+    N = off[:, k + 1]
+    out = {}
+    if tag == "gather":
+        return "hbm", float(np.mean(2 * N * dims[0] * elt0))
+    if tag.startswith("aggregate_L"):
+        i = int(tag.split("_L")[1])
+        rows = N - off[:, i]
+        # slots owned by Delta_i..Delta_k: unknown per layer on the host without the arrays; bounded by E, exact for layer 1
+        slots = np.array([s[k + 2 + i] for s in sizes], dtype=np.float64)
+        elt = elt0 if i == 1 else 4
+        d = dims[i - 1]
+        terms = 1 if i == 1 else 2
+        return "hbm", float(np.mean((slots + rows) * d * elt + slots * 4 + rows * 2 * d * terms * 2))
+    if tag.startswith("gemm_fwd_L"):
+        i = int(tag.split("_L")[1])
+        rows = N - off[:, i]
+        terms = 1 if i == 1 else 2
+        return "mfma", float(np.mean(2 * rows * (2 * dims[i - 1] * terms) * dims[i]))
+    if tag.startswith("gemm_dw_L"):
+        i = int(tag.split("_L")[1])
+        rows = N - off[:, i]
+        xt = 1 if i == 1 else 2
+        zt = 1 if i == k else 2
+        return "mfma", float(np.mean(2 * rows * (2 * dims[i - 1] * xt) * dims[i] * zt))
+    if tag.startswith("gemm_dx_L"):
+        i = int(tag.split("_L")[1])
+        rows = N - off[:, i]
+        zt = 1 if i == k else 2
+        return "mfma", float(np.mean(2 * rows * (2 * dims[i - 1]) * dims[i] * zt))
+    return "hbm", None
+
+
+def cpu_baseline(cfg, inputs, sizes, budget_s=20.0):
+    """The oracle as it stands, timed on the host: sample + gather + forward + backward per batch."""
+    import numpy as np
+    import torch
+    import oracle
+    from workloads import class_labels, softmax_xent_grad
+    t0 = time.time()
+    g = oracle.Graph(cfg.num_nodes, inputs["rowptr"].cpu().numpy(), inputs["col"].cpu().numpy(),
+                     None if inputs["rowptr_in"] is None else inputs["rowptr_in"].cpu().numpy(),
+                     None if inputs["col_in"] is None else inputs["col_in"].cpu().numpy())
+    log("cpu_baseline: graph copied to the host in %.1fs" % (time.time() - t0))
+    w_self, w_nbr, bias = inputs["weights"]
+    params = oracle.SageParams(w_self, w_nbr, bias)
+    table = inputs["table"]
+    labels = class_labels(cfg.batch, cfg.dims[-1])
+    done, edges, spent = 0, 0, 0.0
+    while done < N_BATCHES and (done < 2 or spent < budget_s):
+        targets = inputs["targets"][done]
+        t0 = time.time()
+        d = oracle.dense_sample(g, targets, cfg.fanouts, seed=done, direction=cfg.direction)
+        t_fetch = time.time()
+        rows = table[torch.from_numpy(d.node_ids.astype(np.int64)).to(table.device)].float().cpu().numpy()
+        fetch = time.time() - t_fetch                    # device->host row fetch stands in for the host-side gather
+        st = oracle.sage_forward(d, rows, params, mode="bf16")
+        gout = softmax_xent_grad(st.out, labels[:len(targets)])
+        oracle.sage_backward(st, params, gout, mode="bf16")
+        spent += time.time() - t0
+        edges += len(d.nbrs)
+        done += 1
+        log("cpu_baseline: batch %d, %.2fs so far" % (done, spent))
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    return {"value": edges / spent, "unit": "sampled edges/s", "cores": int(threads), "kind": "oracle",
+            "sample": "%d mini-batches of the same workload (sample+gather+forward+backward, %.1f s; C sampler is "
+                      "single-threaded, NumPy GEMMs use the BLAS threads counted in cores; feature rows fetched "
+                      "from the device table)" % (done, spent),
+            "mini_batches_per_s": done / spent}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=64)
+    ap.add_argument("--workload", default="rmat111m")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-times", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2202_02365_amd as dn
+    from workloads import get_config
+
+    cfg = get_config(args.workload)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    inputs = build_inputs(cfg, dev)
+    k, dims = cfg.num_layers, cfg.dims
+
+    graph = dn.Graph(inputs["rowptr"], inputs["col"], inputs["rowptr_in"], inputs["col_in"])
+    batch = dn.Batch(cfg.num_nodes, cfg.batch, cfg.fanouts, cfg.direction)
+    in_dtype = dn.DN_F32 if cfg.feat_dtype == "f32" else dn.DN_BF16
+    model = dn.Model(batch, dims, in_dtype)
+    w_self, w_nbr, bias = [[torch.from_numpy(a).to(dev) for a in group] for group in inputs["weights"]]
+    model.set_weights(w_self, w_nbr, bias)
+    table = inputs["table"]
+    targets = [torch.from_numpy(t).to(dev) for t in inputs["targets"]]
+    h0 = torch.empty((batch.node_capacity, dims[0]), dtype=table.dtype, device=dev)
+    out = torch.empty((cfg.batch, dims[-1]), dtype=torch.float32, device=dev)
+    gen = torch.Generator(device="cpu").manual_seed(11)
+    grad_out = (torch.randn((cfg.batch, dims[-1]), generator=gen) / cfg.batch).to(dev)   # synthetic dL/dH^k
+    dws = [torch.empty_like(w) for w in w_self]
+    dwn = [torch.empty_like(w) for w in w_nbr]
+    dbs = [torch.empty_like(b) for b in bias]
+    need_dh0 = cfg.name.endswith("_lp")            # learnable base representations need dL/dH^0
+    dh0 = torch.empty((batch.node_capacity, dims[0]), dtype=torch.float32, device=dev) if need_dh0 else None
+
+    def step(bi, backward=True):
+        dn.dense_sample(batch, graph, targets[bi], bi)
+        dn.dense_gather(batch, table, h0)
+        dn.sage_forward(model, batch, h0, out)
+        if backward:
+            dn.sage_backward(model, batch, grad_out, dws, dwn, dbs, dh0)
+
+    # sizes of every batch (untimed; counts() waits for the device)
+    sizes = []
+    for bi in range(N_BATCHES):
+        dn.dense_sample(batch, graph, targets[bi], bi)
+        c = batch.counts()
+        nbr_offsets = batch.view()["nbr_offsets"]
+        # slots owned by Delta_i .. Delta_k (what layer i aggregates over), i = 1..k
+        c += [int(c[k + 2] - int(nbr_offsets[c[i] - c[1]])) for i in range(1, k + 1)]
+        sizes.append(c)
+    mean_n = float(np.mean([s[k + 1] for s in sizes]))
+    mean_e = float(np.mean([s[k + 2] for s in sizes]))
+    log("mini-batch sizes: mean N=%.0f, mean E=%.0f" % (mean_n, mean_e))
+
+    def timed(n_steps, backward=True):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(n_steps):
+            step(s % N_BATCHES, backward)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    timed(args.warmup)
+    total_s = timed(args.steps)
+    edges = sum(sizes[s % N_BATCHES][k + 2] for s in range(args.steps))
+    fwd_only_s = timed(args.steps, backward=False)
+    log("timed %d steps: %.3f ms/step (sample+gather+fwd only: %.3f ms)" %
+        (args.steps, 1e3 * total_s / args.steps, 1e3 * fwd_only_s / args.steps))
+
+    # per-kernel durations: the same K steps again, every launch bracketed by HIP events on its stream
+    roofline, kernels = None, {}
+    if not args.no_kernel_times:
+        dn.profile_enable(True)
+        timed(args.steps)
+        prof = dn.profile_collect()
+        dn.profile_enable(False)
+        kernels = {tag: {"avg_us": 1e3 * ms / n, "launches_per_step": n / args.steps} for tag, (ms, n) in prof.items()}
+        step_sum_us = sum(v["avg_us"] * v["launches_per_step"] for v in kernels.values())
+        used = [sizes[s % N_BATCHES] for s in range(args.steps)]
+        best = None
+        for tag, v in kernels.items():
+            bound, work = algorithmic_work(tag, used, cfg, dims)
+            if work is None:
+                continue
+            per_step_us = v["avg_us"] * v["launches_per_step"]
+            if best is None or per_step_us > best[0]:
+                best = (per_step_us, tag, bound, work, v["avg_us"])
+        if best is not None:
+            _, tag, bound, work, avg_us = best
+            if bound == "hbm":
+                achieved, peak, unit = work / (avg_us * 1e-6) / 1e9, HBM_PEAK_GBS, "GB/s"
+            else:
+                achieved, peak, unit = work / (avg_us * 1e-6) / 1e12, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s"
+            roofline = {"kernel": tag, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
+                        "frac": achieved / peak, "traffic": None, "avg_us": avg_us,
+                        "algorithmic_per_launch": work, "kernel_time_share_of_step": best[0] / step_sum_us}
+
+    baseline = None
+    if not args.no_cpu_baseline:
+        baseline = cpu_baseline(cfg, inputs, sizes)
+
+    result = {
+        "metric": "sampled edges/s through sample+gather+forward+backward (3-hop DENSE + GraphSage)",
+        "value": edges / total_s,
+        "unit": "sampled edges/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": 1e3 * total_s / args.steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "num_nodes": cfg.num_nodes, "num_edges_nominal": cfg.num_edges,
+                   "num_edges": int(inputs["col"].numel()), "feat_dim": cfg.feat_dim, "feat_dtype": cfg.feat_dtype,
+                   "dims": dims, "fanouts": list(cfg.fanouts), "batch": cfg.batch,
+                   "mean_nodes_per_batch": mean_n, "mean_sampled_edges_per_batch": mean_e},
+        "mini_batches_per_s": args.steps / total_s,
+        "sample_gather_fwd": {"ms_per_step": 1e3 * fwd_only_s / args.steps,
+                              "mini_batches_per_s": args.steps / fwd_only_s,
+                              "sampled_edges_per_s": edges / fwd_only_s},
+        "roofline": roofline,
+        "kernels": kernels,
+        "cpu_baseline": baseline,
+    }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -156,6 +156,19 @@ DN_API int  sage_backward(dn_model* m, const dn_batch* b, const float* d_grad_ou
                    float* const* d_dw_self, float* const* d_dw_nbr, float* const* d_dbias,
                    float* d_dH0, void* stream);
 
+/* ---- per-kernel timing for benchmarks (off by default; not a step of the path).
+ *      dn_profile_enable(1): from now on every kernel launch of this library is bracketed by a pair of
+ *      HIP events on the stream it is launched on; dn_profile_enable(0) stops that.  Enabling also
+ *      discards earlier records.  dn_profile_collect WAITS for the device, adds up the elapsed time per
+ *      kernel tag and writes up to `max_entries` entries; *n_entries = number of distinct tags. */
+typedef struct dn_kernel_time {
+    char    tag[48];     /* e.g. "gather", "aggregate_L1", "gemm_fwd_L1" */
+    double  total_ms;
+    int64_t launches;
+} dn_kernel_time;
+DN_API int  dn_profile_enable(int32_t enable);
+DN_API int  dn_profile_collect(dn_kernel_time* out, int32_t max_entries, int32_t* n_entries);
+
 #ifdef __cplusplus
 }
 #endif

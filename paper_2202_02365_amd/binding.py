@@ -21,6 +21,10 @@ class DenseError(RuntimeError):
         self.code = code
 
 
+class _KernelTime(ctypes.Structure):
+    _fields_ = [("tag", ctypes.c_char * 48), ("total_ms", ctypes.c_double), ("launches", ctypes.c_int64)]
+
+
 class _View(ctypes.Structure):
     _fields_ = [("node_id_offsets", ctypes.c_void_p), ("node_ids", ctypes.c_void_p),
                 ("nbr_offsets", ctypes.c_void_p), ("nbrs", ctypes.c_void_p), ("repr_map", ctypes.c_void_p)]
@@ -64,6 +68,8 @@ def load_library():
         "dn_model_set_weights": (ctypes.c_int, [vp, pp, pp, pp, vp]),
         "dn_model_destroy": (None, [vp]),
         "dn_model_status": (ctypes.c_int, [vp, ctypes.POINTER(i32), vp]),
+        "dn_profile_enable": (ctypes.c_int, [i32]),
+        "dn_profile_collect": (ctypes.c_int, [ctypes.POINTER(_KernelTime), i32, ctypes.POINTER(i32)]),
         "sage_forward": (ctypes.c_int, [vp, vp, vp, vp, vp]),
         "sage_backward": (ctypes.c_int, [vp, vp, vp, pp, pp, pp, vp, vp]),
     }
@@ -213,6 +219,19 @@ class Model:
             assert tuple(bias[i].shape) == (self.dims[i + 1],)
         _check(load_library().dn_model_set_weights(self.handle, _ptr_array(w_self), _ptr_array(w_nbr),
                                                    _ptr_array(bias), _stream()))
+
+
+def profile_enable(on: bool) -> None:
+    """Bracket every kernel launch of the library with HIP events (benchmark use)."""
+    _check(load_library().dn_profile_enable(1 if on else 0))
+
+
+def profile_collect():
+    """{tag: (total_ms, launches)} since profile_enable(True); waits for the device."""
+    buf = (_KernelTime * 128)()
+    n = ctypes.c_int32()
+    _check(load_library().dn_profile_collect(buf, 128, ctypes.byref(n)))
+    return {buf[i].tag.decode(): (buf[i].total_ms, int(buf[i].launches)) for i in range(min(n.value, 128))}
 
 
 def dense_sample(batch: Batch, graph: Graph, targets: torch.Tensor, seed: int) -> None:

@@ -7,6 +7,10 @@
 #include <cstring>
 #include <new>
 #include <algorithm>
+#include <map>
+#include <mutex>
+#include <string>
+#include <vector>
 
 namespace {
 
@@ -160,6 +164,49 @@ void carve_model(dn_model* m, const dn_batch* b, Carver& c)
 }
 
 }  // namespace
+
+namespace {
+struct ProfRecord { std::string tag; hipEvent_t start, stop; };
+std::mutex g_prof_mutex;
+bool g_prof_on = false;
+std::vector<ProfRecord> g_prof_records;
+std::vector<hipEvent_t> g_prof_pool;
+
+hipEvent_t prof_event()
+{
+    if (!g_prof_pool.empty()) { hipEvent_t e = g_prof_pool.back(); g_prof_pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+void prof_clear()
+{
+    for (auto& r : g_prof_records) { g_prof_pool.push_back(r.start); g_prof_pool.push_back(r.stop); }
+    g_prof_records.clear();
+}
+}  // namespace
+
+dn_prof_scope::dn_prof_scope(const char* tag, int layer, hipStream_t stream) : idx(-1), st(stream)
+{
+    if (!g_prof_on) return;
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    ProfRecord r;
+    r.tag = tag;
+    if (layer > 0) r.tag += "_L" + std::to_string(layer);
+    r.start = prof_event();
+    r.stop = prof_event();
+    if (!r.start || !r.stop) return;
+    if (hipEventRecord(r.start, st) != hipSuccess) return;
+    idx = (int)g_prof_records.size();
+    g_prof_records.push_back(r);
+}
+
+dn_prof_scope::~dn_prof_scope()
+{
+    if (idx < 0) return;
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    if (idx < (int)g_prof_records.size()) (void)hipEventRecord(g_prof_records[idx].stop, st);
+}
 
 int dn_fail(int code, const char* fmt, ...)
 {
@@ -378,6 +425,43 @@ int sage_backward(dn_model* m, const dn_batch* b, const float* d_grad_out, float
     // the transpose index is cached in the batch object; building it is part of this call
     return dn_launch_backward(m, const_cast<dn_batch*>(b), d_grad_out, d_dw_self, d_dw_nbr, d_dbias, d_dH0,
                               static_cast<hipStream_t>(stream));
+}
+
+int dn_profile_enable(int32_t enable)
+{
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    if (enable) prof_clear();
+    g_prof_on = enable != 0;
+    return DN_OK;
+}
+
+int dn_profile_collect(dn_kernel_time* out, int32_t max_entries, int32_t* n_entries)
+{
+    if (!n_entries || (max_entries > 0 && !out)) return dn_fail(DN_EINVAL, "null argument");
+    DN_HIP(hipDeviceSynchronize());
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    std::map<std::string, std::pair<double, int64_t>> acc;
+    std::vector<std::string> order;
+    for (auto& r : g_prof_records) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess) continue;
+        auto it = acc.find(r.tag);
+        if (it == acc.end()) { acc[r.tag] = {0.0, 0}; order.push_back(r.tag); it = acc.find(r.tag); }
+        it->second.first += ms;
+        it->second.second += 1;
+    }
+    int32_t n = 0;
+    for (auto& tag : order) {
+        if (n < max_entries) {
+            std::memset(&out[n], 0, sizeof(out[n]));
+            std::strncpy(out[n].tag, tag.c_str(), sizeof(out[n].tag) - 1);
+            out[n].total_ms = acc[tag].first;
+            out[n].launches = acc[tag].second;
+        }
+        ++n;
+    }
+    *n_entries = n;
+    return DN_OK;
 }
 
 }  // extern "C"

@@ -111,6 +111,14 @@ int dn_fail(int code, const char* fmt, ...);
         if (e_ != hipSuccess) return dn_fail(DN_EHIP, "launch %s: %s", name, hipGetErrorString(e_)); \
     } while (0)
 
+// Optional per-launch event pair (see dn_profile_enable); a no-op unless profiling is on.
+struct dn_prof_scope {
+    int idx;
+    hipStream_t st;
+    dn_prof_scope(const char* tag, int layer, hipStream_t stream);
+    ~dn_prof_scope();
+};
+
 static inline int64_t dn_round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
 // launchers (one per step of the hot path)

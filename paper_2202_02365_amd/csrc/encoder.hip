@@ -223,6 +223,7 @@ int launch_aggregate_t(const dn_model* m, const dn_batch* b, int i, const TIN* H
     int64_t grid = (L.rows_cap + groups - 1) / groups;
     if (grid > 8192) grid = 8192;
     if (grid < 1) grid = 1;
+    dn_prof_scope ps("aggregate", i, st);
 #define DN_AGG(VV, LL)                                                                                                 \
     hipLaunchKernelGGL((k_aggregate<TIN, VV, LL, TERMS>), dim3((int)grid), dim3(TPB), 0, st, b->hdr, i, b->nbr_offsets, \
                        b->repr_map, H, d, X, L.kp, L.rownorm, m->fix_count)
@@ -261,6 +262,7 @@ int launch_aggregate_bwd(const dn_model* m, const dn_batch* b, int i, float* gin
     int64_t grid = (rows_in_cap + groups - 1) / groups;
     if (grid > 8192) grid = 8192;
     if (grid < 1) grid = 1;
+    dn_prof_scope ps("aggregate_bwd", i, st);
 #define DN_AGGB(VV, LL)                                                                                               \
     hipLaunchKernelGGL((k_aggregate_bwd<VV, LL>), dim3((int)grid), dim3(TPB), 0, st, b->hdr, i, b->nbr_offsets,       \
                        b->slot_owner, b->tr_ptr, b->tr_val[0], m->dx, 2 * d, d, gin)
@@ -317,6 +319,7 @@ int dn_launch_backward(dn_model* m, dn_batch* b, const float* grad_out, float* c
     for (int i = k; i >= 1; --i) {
         const dn_layer_bufs& L = m->layer[i - 1];
         const unsigned row_tiles = (unsigned)((L.rows_cap + 63) / 64);
+        { dn_prof_scope ps("dz", i, st);
         if (L.zterms == 2)
             hipLaunchKernelGGL((k_dz<2>), dim3((unsigned)(L.np / 64), row_tiles ? row_tiles : 1), dim3(TPB), 0, st, b->hdr,
                                i, g, L.d_out, L.h, L.d_out, L.np, 1, reinterpret_cast<uint16_t*>(m->dzb),
@@ -325,13 +328,18 @@ int dn_launch_backward(dn_model* m, dn_batch* b, const float* grad_out, float* c
             hipLaunchKernelGGL((k_dz<1>), dim3((unsigned)(L.np / 64), row_tiles ? row_tiles : 1), dim3(TPB), 0, st, b->hdr,
                                i, g, L.d_out, nullptr, L.d_out, L.np, 0, reinterpret_cast<uint16_t*>(m->dzb),
                                reinterpret_cast<uint16_t*>(m->dzbt), L.rows_pad, m->dzbt_term_stride, m->db_partial);
+        }
         DN_LAUNCH_CHECK("k_dz");
+        { dn_prof_scope ps("db_reduce", i, st);
         hipLaunchKernelGGL(k_db_reduce, dim3((L.d_out + TPB - 1) / TPB), dim3(TPB), 0, st, b->hdr, i, m->db_partial,
                            L.d_out, dbias[i - 1]);
+        }
         DN_LAUNCH_CHECK("k_db_reduce");
+        { dn_prof_scope ps("transpose_x", i, st);
         hipLaunchKernelGGL(k_transpose_x, dim3((unsigned)(L.kp / 64), row_tiles ? row_tiles : 1), dim3(TPB), 0, st,
                            b->hdr, i, reinterpret_cast<const uint16_t*>(L.x), L.kp, reinterpret_cast<uint16_t*>(m->xt),
                            L.rows_pad);
+        }
         DN_LAUNCH_CHECK("k_transpose_x");
         rc = dn_gemm_dw(m, b, i, dws[i - 1], dwn[i - 1], st);
         if (rc) return rc;

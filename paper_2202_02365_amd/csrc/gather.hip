@@ -51,6 +51,7 @@ int dn_launch_gather(const dn_batch* b, const void* table, int32_t dtype, int32_
     const int64_t row_bytes = (int64_t)dim * elt, ld_bytes = ld * elt;
     const bool vec = (row_bytes % 16 == 0) && (ld_bytes % 16 == 0) && ((uintptr_t)table % 16 == 0) && ((uintptr_t)h0 % 16 == 0);
     const int64_t cap = b->cap_nodes;
+    dn_prof_scope ps("gather", 0, st);
     if (vec) {
         const int chunks = (int)(row_bytes / 16);
         int lanes = 4;

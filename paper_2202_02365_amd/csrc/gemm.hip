@@ -243,8 +243,9 @@ __global__ __launch_bounds__(TPB) void k_col_norms(const uint16_t* __restrict__ 
 }
 
 template <int EPI>
-int launch(const GemmArgs& a, int64_t m_cap, int splits, hipStream_t st)
+int launch(const GemmArgs& a, int64_t m_cap, int splits, hipStream_t st, const char* tag)
 {
+    dn_prof_scope ps(tag, a.layer, st);
     dim3 grid((unsigned)((a.ncols + BN - 1) / BN), (unsigned)((m_cap + BM - 1) / BM), (unsigned)splits);
     if (grid.y == 0) grid.y = 1;
     hipLaunchKernelGGL((k_gemm_nt<EPI>), grid, dim3(TPB), 0, st, a);
@@ -267,8 +268,9 @@ int dn_gemm_forward(const dn_model* m, const dn_batch* b, int i, float* out, int
     a.rownorm = L.rownorm; a.colnorm = L.colnorm;
     a.gamma = (float)L.kp * 1.1920929e-7f;                 // 2 K 2^-24: worst case of K fp32 additions, doubled
     a.fix_list = reinterpret_cast<long long*>(m->fix_list); a.fix_count = m->fix_count; a.fix_cap = m->fix_cap;
-    int rc = launch<EPI_BIAS_ACT>(a, L.rows_cap, 1, st);
+    int rc = launch<EPI_BIAS_ACT>(a, L.rows_cap, 1, st, "gemm_fwd");
     if (rc || !a.relu) return rc;
+    dn_prof_scope ps("relu_fixup", i, st);
     hipLaunchKernelGGL(k_relu_fixup, dim3(128), dim3(TPB), 0, st, a.fix_list, a.fix_count, a.fix_cap, a.A, a.B, L.kp,
                        L.bias, out, (int)ldc);
     DN_LAUNCH_CHECK("k_relu_fixup");
@@ -285,7 +287,7 @@ int dn_gemm_dx(const dn_model* m, const dn_batch* b, int i, hipStream_t st)
     a.C = m->dx; a.ldc = 2 * L.d_in;
     a.hdr = b->hdr; a.layer = i; a.m_const = -1; a.ncols = 2 * L.d_in; a.red_const = L.nz;
     a.bias = nullptr; a.relu = 0; a.split_stride = 0; a.terms = 1; a.b_term_stride = 0;
-    return launch<EPI_PLAIN>(a, L.rows_cap, 1, st);
+    return launch<EPI_PLAIN>(a, L.rows_cap, 1, st, "gemm_dx");
 }
 
 // dWcat = X^T * bf16(dZ), reduction over the layer's rows split `splits` ways, then reduced in order.
@@ -305,9 +307,10 @@ int dn_gemm_dw(const dn_model* m, const dn_batch* b, int i, float* dws, float* d
     const int zsplits = splits * L.zterms;
     if ((int64_t)zsplits * a.split_stride > m->partial_floats)
         return dn_fail(DN_ECAPACITY, "dW partial buffer too small");
-    int rc = launch<EPI_SPLIT>(a, L.kx, zsplits, st);
+    int rc = launch<EPI_SPLIT>(a, L.kx, zsplits, st, "gemm_dw");
     if (rc) return rc;
     const int total = 2 * L.d_in * L.d_out;
+    dn_prof_scope ps("dw_reduce", i, st);
     hipLaunchKernelGGL(k_dw_reduce, dim3((total + TPB - 1) / TPB), dim3(TPB), 0, st, m->partial, a.split_stride, zsplits,
                        L.xterms, L.d_in, L.d_out, dws, dwn);
     DN_LAUNCH_CHECK("k_dw_reduce");

@@ -397,10 +397,14 @@ int dn_launch_sample(dn_batch* b, const dn_graph* g, const int32_t* d_targets, i
 
     const int grid0 = n_targets > 0 ? (n_targets + TPB - 1) / TPB : 1;
     if (grid0 > b->max_blocks) return dn_fail(DN_ECAPACITY, "dense_sample: %d targets exceed the batch capacity", n_targets);
+    { dn_prof_scope ps("init_targets", 0, st);
     hipLaunchKernelGGL(k_init_targets, dim3(grid0), dim3(TPB), 0, st, gd, b->V, d_targets, n_targets, b->fanouts[0], dir,
                        b->hdr, b->seen, b->lvlpos, b->lvl_ids, b->lvl_nbr_offsets, blk);
+    }
     DN_LAUNCH_CHECK("k_init_targets");
+    { dn_prof_scope ps("init_offsets", 0, st);
     hipLaunchKernelGGL(k_init_offsets, dim3(grid0), dim3(TPB), 0, st, n_targets, b->hdr, b->lvl_nbr_offsets, blk);
+    }
     DN_LAUNCH_CHECK("k_init_offsets");
 
     const int grid_words = (int)((b->words1 + TPB - 1) / TPB);
@@ -412,6 +416,7 @@ int dn_launch_sample(dn_batch* b, const dn_graph* g, const int32_t* d_targets, i
         const int64_t groups = level_bound > 0 ? level_bound : 1;
         int64_t grid = (groups * G + TPB - 1) / TPB;
         if (grid > 8192) grid = 8192;                       // grid-stride beyond this
+        { dn_prof_scope ps("sample_hop", h + 1, st);
         switch (G) {
             case 4:  launch_sample_g<4>((int)grid, st, gd, h, f, dir, key0, key1, b); break;
             case 8:  launch_sample_g<8>((int)grid, st, gd, h, f, dir, key0, key1, b); break;
@@ -419,13 +424,18 @@ int dn_launch_sample(dn_batch* b, const dn_graph* g, const int32_t* d_targets, i
             case 32: launch_sample_g<32>((int)grid, st, gd, h, f, dir, key0, key1, b); break;
             default: launch_sample_g<64>((int)grid, st, gd, h, f, dir, key0, key1, b); break;
         }
+        }
         DN_LAUNCH_CHECK("k_sample");
         const int f_next = (h + 1 < k) ? b->fanouts[h + 1] : 0;
+        { dn_prof_scope ps("fresh_count_hop", h + 1, st);
         hipLaunchKernelGGL(k_fresh_count, dim3(grid_words), dim3(TPB), 0, st, gd, b->words1, f_next, dir, b->fresh,
                            b->summary, blk);
+        }
         DN_LAUNCH_CHECK("k_fresh_count");
+        { dn_prof_scope ps("fresh_emit_hop", h + 1, st);
         hipLaunchKernelGGL(k_fresh_emit, dim3(grid_words), dim3(TPB), 0, st, gd, b->words1, h + 1, f_next, dir, b->hdr,
                            b->fresh, b->summary, blk, b->lvlpos, b->lvl_ids, b->lvl_nbr_offsets, b->cap_nodes);
+        }
         DN_LAUNCH_CHECK("k_fresh_emit");
         const int mult = dir == DN_DIR_BOTH ? 2 : 1;
         level_bound = level_bound * f * mult;
@@ -435,9 +445,11 @@ int dn_launch_sample(dn_batch* b, const dn_graph* g, const int32_t* d_targets, i
     int64_t grid_asm = (work + TPB - 1) / TPB;
     if (grid_asm > 2048) grid_asm = 2048;
     if (grid_asm < 1) grid_asm = 1;
+    { dn_prof_scope ps("assemble", 0, st);
     hipLaunchKernelGGL(k_assemble, dim3((int)grid_asm), dim3(TPB), 0, st, k, b->hdr, b->lvl_ids, b->lvl_nbr_offsets,
                        b->lvl_nbrs, b->lvl_owner, b->lvlpos, b->seen, b->node_ids, b->nbr_offsets, b->nbrs, b->repr_map,
                        b->slot_owner);
+    }
     DN_LAUNCH_CHECK("k_assemble");
     return DN_OK;
 }

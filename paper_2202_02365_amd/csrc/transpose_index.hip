@@ -184,6 +184,7 @@ int dn_launch_transpose_index(dn_batch* b, int need_all, hipStream_t st)
     int64_t g = (cap + TPB - 1) / TPB;
     if (g > 2048) g = 2048;
     if (g < 1) g = 1;
+    dn_prof_scope ps("transpose_index", 0, st);       // the whole sort counts as one step
     hipLaunchKernelGGL(k_tr_init, dim3((int)g), dim3(TPB), 0, st, b->hdr, need_all, b->k, b->nbr_offsets, b->repr_map,
                        b->tr_key[src], b->tr_val[src]);
     DN_LAUNCH_CHECK("k_tr_init");
