@@ -135,16 +135,28 @@ __global__ __launch_bounds__(TPB) void k_dz(const int32_t* __restrict__ hdr, int
             dzbt[t * term_stride + (int64_t)(c0 + cc) * rows_pad + r0 + tx] = tile[t][tx][cc];
 }
 
+// db[n] = sum over the row tiles of k_dz.  64 columns per workgroup; each of its 4 waves takes every
+// fourth tile (lanes = columns, coalesced), the four partial sums are combined in a fixed order.
 __global__ __launch_bounds__(TPB) void k_db_reduce(const int32_t* __restrict__ hdr, int layer,
                                                    const float* __restrict__ db_partial, int d_out, float* __restrict__ db)
 {
-    const int n = blockIdx.x * TPB + threadIdx.x;
-    if (n >= d_out) return;
+    __shared__ float part[4][64];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int n = blockIdx.x * 64 + tx;
     const int rows = hdr[HDR_N] - hdr[HDR_NODE_OFF + layer];
     const int tiles = (rows + 63) / 64;
-    float s = 0.f;
-    for (int t = 0; t < tiles; ++t) s += db_partial[(int64_t)t * d_out + n];
-    db[n] = s;
+    float s0 = 0.f, s1 = 0.f;
+    if (n < d_out) {
+        int t = ty;
+        for (; t + 4 < tiles; t += 8) {
+            s0 += db_partial[(int64_t)t * d_out + n];
+            s1 += db_partial[(int64_t)(t + 4) * d_out + n];
+        }
+        if (t < tiles) s0 += db_partial[(int64_t)t * d_out + n];
+    }
+    part[ty][tx] = s0 + s1;
+    __syncthreads();
+    if (ty == 0 && n < d_out) db[n] = (part[0][tx] + part[1][tx]) + (part[2][tx] + part[3][tx]);
 }
 
 // X [rows x kp] -> X^T [kp x rows_pad], zero for rows up to the next multiple of 64.
@@ -331,7 +343,7 @@ int dn_launch_backward(dn_model* m, dn_batch* b, const float* grad_out, float* c
         }
         DN_LAUNCH_CHECK("k_dz");
         { dn_prof_scope ps("db_reduce", i, st);
-        hipLaunchKernelGGL(k_db_reduce, dim3((L.d_out + TPB - 1) / TPB), dim3(TPB), 0, st, b->hdr, i, m->db_partial,
+        hipLaunchKernelGGL(k_db_reduce, dim3((L.d_out + 63) / 64), dim3(TPB), 0, st, b->hdr, i, m->db_partial,
                            L.d_out, dbias[i - 1]);
         }
         DN_LAUNCH_CHECK("k_db_reduce");

@@ -131,6 +131,21 @@ __global__ __launch_bounds__(TPB) void k_gemm_nt(GemmArgs a)
     // epilogue: lane holds column (lane & 31); register e holds row 8*(e/4) + 4*(lane/32) + e%4
     float* C = a.C;
     if (EPI == EPI_SPLIT) C += (int64_t)blockIdx.z * a.split_stride;
+    float rn[2][16];                       // row norms of this lane's 32 rows, fetched in one batch
+    __shared__ int s_fix_n, s_fix_base;
+    long long* local_fix = reinterpret_cast<long long*>(As);     // the operand tiles are no longer needed
+    constexpr int LOCAL_FIX_CAP = BM * BK / 8 * 16 / 8;
+    if (EPI == EPI_BIAS_ACT && a.relu) {
+        if (t == 0) s_fix_n = 0;
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int m = row0 + wm * 64 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                rn[i][e] = m < M ? a.rownorm[m] : 0.f;
+            }
+    }
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -148,10 +163,16 @@ __global__ __launch_bounds__(TPB) void k_gemm_nt(GemmArgs a)
                     if (EPI == EPI_BIAS_ACT) {
                         v += bv;
                         if (a.relu) {
-                            if (fabsf(v) <= cn * a.rownorm[m] + bt) {
-                                const int pos = atomicAdd(&a.fix_count[0], 1);
-                                if (pos < a.fix_cap) a.fix_list[pos] = ((long long)m << 16) | (long long)n;
-                                else a.fix_count[1] = 1;
+                            if (fabsf(v) <= cn * rn[i][e] + bt) {
+                                // queue in LDS first: one global atomic per workgroup instead of one per element
+                                const long long ent = ((long long)m << 16) | (long long)n;
+                                const int lp = atomicAdd(&s_fix_n, 1);
+                                if (lp < LOCAL_FIX_CAP) local_fix[lp] = ent;
+                                else {
+                                    const int pos = atomicAdd(&a.fix_count[0], 1);
+                                    if (pos < a.fix_cap) a.fix_list[pos] = ent;
+                                    else a.fix_count[1] = 1;
+                                }
                             }
                             v = fmaxf(v, 0.f);
                         }
@@ -160,6 +181,17 @@ __global__ __launch_bounds__(TPB) void k_gemm_nt(GemmArgs a)
                 }
             }
         }
+    if (EPI == EPI_BIAS_ACT && a.relu) {
+        __syncthreads();
+        const int n_local = min(s_fix_n, LOCAL_FIX_CAP);
+        if (t == 0 && n_local > 0) s_fix_base = atomicAdd(&a.fix_count[0], n_local);
+        __syncthreads();
+        for (int q = t; q < n_local; q += TPB) {
+            const long long pos = (long long)s_fix_base + q;
+            if (pos < a.fix_cap) a.fix_list[pos] = local_fix[q];
+            else a.fix_count[1] = 1;
+        }
+    }
 }
 
 // dW[kk][n] = sum over the X terms (rows kk + t*2d) and over the splits, in a fixed order;
@@ -172,9 +204,19 @@ __global__ __launch_bounds__(TPB) void k_dw_reduce(const float* __restrict__ par
     if (idx >= 2 * d_in * d_out) return;
     const int kk = idx / d_out, n = idx - kk * d_out;
     float s = 0.f;
-    for (int t = 0; t < xterms; ++t)
-        for (int z = 0; z < splits; ++z)
-            s += partial[(int64_t)z * split_stride + (int64_t)(kk + t * 2 * d_in) * d_out + n];
+    for (int t = 0; t < xterms; ++t) {
+        const float* src = partial + (int64_t)(kk + t * 2 * d_in) * d_out + n;
+        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;       // four chains: loads overlap, order stays fixed
+        int z = 0;
+        for (; z + 4 <= splits; z += 4) {
+            s0 += src[(int64_t)(z + 0) * split_stride];
+            s1 += src[(int64_t)(z + 1) * split_stride];
+            s2 += src[(int64_t)(z + 2) * split_stride];
+            s3 += src[(int64_t)(z + 3) * split_stride];
+        }
+        for (; z < splits; ++z) s0 += src[(int64_t)z * split_stride];
+        s += (s0 + s1) + (s2 + s3);
+    }
     if (kk < d_in) dws[(int64_t)kk * d_out + n] = s;
     else dwn[(int64_t)(kk - d_in) * d_out + n] = s;
 }
@@ -195,8 +237,15 @@ __global__ __launch_bounds__(TPB) void k_relu_fixup(const long long* __restrict_
         const uint16_t* xr = X + (int64_t)m * kp;
         const uint16_t* wr = Wt + (int64_t)n * kp;
         double s = 0.0;
-        for (int kk = lane; kk < kp; kk += 64)
-            s += (double)__uint_as_float((uint32_t)xr[kk] << 16) * (double)__uint_as_float((uint32_t)wr[kk] << 16);
+        for (int c = lane; c < kp / 8; c += 64) {             // kp is a multiple of 64, rows are 16-byte aligned
+            const u32x4 xv = *reinterpret_cast<const u32x4*>(xr + c * 8);
+            const u32x4 wv = *reinterpret_cast<const u32x4*>(wr + c * 8);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                s += (double)__uint_as_float(xv[e] << 16) * (double)__uint_as_float(wv[e] << 16);
+                s += (double)__uint_as_float(xv[e] & 0xffff0000u) * (double)__uint_as_float(wv[e] & 0xffff0000u);
+            }
+        }
         for (int d = 32; d > 0; d >>= 1) s += __shfl_down(s, d, 64);
         if (lane == 0) {
             const double z = s + (double)bias[n];
@@ -271,7 +320,7 @@ int dn_gemm_forward(const dn_model* m, const dn_batch* b, int i, float* out, int
     int rc = launch<EPI_BIAS_ACT>(a, L.rows_cap, 1, st, "gemm_fwd");
     if (rc || !a.relu) return rc;
     dn_prof_scope ps("relu_fixup", i, st);
-    hipLaunchKernelGGL(k_relu_fixup, dim3(128), dim3(TPB), 0, st, a.fix_list, a.fix_count, a.fix_cap, a.A, a.B, L.kp,
+    hipLaunchKernelGGL(k_relu_fixup, dim3(1024), dim3(TPB), 0, st, a.fix_list, a.fix_count, a.fix_cap, a.A, a.B, L.kp,
                        L.bias, out, (int)ldc);
     DN_LAUNCH_CHECK("k_relu_fixup");
     return DN_OK;
@@ -295,8 +344,12 @@ int dn_gemm_dw(const dn_model* m, const dn_batch* b, int i, float* dws, float* d
 {
     const dn_layer_bufs& L = m->layer[i - 1];
     int64_t chunks_cap = (L.rows_cap + BK - 1) / BK;
-    int splits = m->splits;
+    // enough workgroups to fill the chip, no more: every split costs a partial tile to write and re-read
+    const int tiles = ((L.kx + BM - 1) / BM) * ((L.d_out + BN - 1) / BN) * L.zterms;
+    int splits = (512 + tiles - 1) / tiles;
+    if (splits > m->splits) splits = m->splits;
     if (splits > chunks_cap) splits = (int)(chunks_cap > 0 ? chunks_cap : 1);
+    if (splits < 1) splits = 1;
     GemmArgs a{};
     a.A = reinterpret_cast<const uint16_t*>(m->xt); a.lda = L.rows_pad;
     a.B = reinterpret_cast<const uint16_t*>(m->dzbt); a.ldb = L.rows_pad;
