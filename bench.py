@@ -26,29 +26,6 @@ def log(msg):
     print("[bench] " + msg, file=sys.stderr, flush=True)
 
 
-def build_inputs(cfg, dev):
-    import torch
-    from workloads import rmat_csr, transpose_csr, feature_table, glorot_weights, training_subset, target_batch
-    t0 = time.time()
-    big = cfg.num_nodes > (1 << 22)
-    gen_dev = dev if big else "cpu"
-    rowptr, col = rmat_csr(cfg.num_nodes, cfg.num_edges, cfg.graph_seed, device=gen_dev)
-    rowptr_in = col_in = None
-    if cfg.direction != 0:
-        rowptr_in, col_in = transpose_csr(rowptr, col)
-    log("graph: V=%d E=%d (nominal %d) on %s in %.1fs" % (cfg.num_nodes, col.numel(), cfg.num_edges, gen_dev, time.time() - t0))
-    t0 = time.time()
-    table = feature_table(cfg.num_nodes, cfg.feat_dim, cfg.feat_dtype, cfg.feat_seed, device=gen_dev)
-    log("features: %d x %d %s in %.1fs" % (cfg.num_nodes, cfg.feat_dim, cfg.feat_dtype, time.time() - t0))
-    pool = training_subset(cfg.num_nodes, cfg.train_fraction, cfg.target_seed, device=gen_dev)
-    targets = [target_batch(pool.numel(), cfg.batch, bi, cfg.target_seed, pool=pool if cfg.train_fraction < 1 else None)
-               for bi in range(N_BATCHES)]
-    weights = glorot_weights(cfg.dims, cfg.weight_seed)
-    to = lambda t: None if t is None else t.to(dev)
-    return dict(rowptr=to(rowptr), col=to(col), rowptr_in=to(rowptr_in), col_in=to(col_in), table=to(table),
-                targets=targets, weights=weights)
-
-
 def algorithmic_work(tag, sizes, cfg, dims):
     """Algorithmic bytes (HBM-bound kernels) or flops (GEMMs) of ONE launch of the kernel `tag`,
     averaged over the batches; sizes = per-batch (node_id_offsets[0..k+1], E)."""
@@ -152,7 +129,8 @@ def main():
     cfg = get_config(args.workload)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    inputs = build_inputs(cfg, dev)
+    from workloads import make_inputs
+    inputs = make_inputs(cfg, dev, N_BATCHES, log)
     k, dims = cfg.num_layers, cfg.dims
 
     graph = dn.Graph(inputs["rowptr"], inputs["col"], inputs["rowptr_in"], inputs["col_in"])

@@ -125,7 +125,7 @@ int fill_model(dn_model* m, const dn_batch* b, int32_t k, const int32_t* dims, i
 void carve_model(dn_model* m, const dn_batch* b, Carver& c)
 {
     const int k = m->k;
-    int64_t max_dzb = 0, max_dzbt = 0, max_xt = 0, max_dx = 0, max_g = 0, max_w = 0, max_db = 0, max_fix = 4096;
+    int64_t max_dzb = 0, max_dzbt = 0, max_xt = 0, max_dx = 0, max_g = 0, max_w = 0, max_db = 0;
     for (int i = 1; i <= k; ++i) {
         dn_layer_bufs& L = m->layer[i - 1];
         L.x = c.take<dn_bf16>(L.rows_pad * L.kp);
@@ -143,7 +143,6 @@ void carve_model(dn_model* m, const dn_batch* b, Carver& c)
         max_db = std::max<int64_t>(max_db, ((L.rows_cap + 63) / 64 + 1) * L.d_out);
         if (i < k) {
             max_g = std::max<int64_t>(max_g, L.rows_pad * L.d_out);   // gradient w.r.t. H^i
-            max_fix = std::max<int64_t>(max_fix, L.rows_cap * L.d_out / 16);
         }
     }
     m->dzb = c.take<dn_bf16>(max_dzb);
@@ -157,8 +156,6 @@ void carve_model(dn_model* m, const dn_batch* b, Carver& c)
     m->partial_floats = (int64_t)m->splits * max_w;
     m->partial = c.take<float>(m->partial_floats);
     m->db_partial = c.take<float>(max_db);
-    m->fix_cap = max_fix;
-    m->fix_list = c.take<int64_t>(max_fix);
     m->fix_count = c.take<int32_t>(64);
     (void)b;
 }

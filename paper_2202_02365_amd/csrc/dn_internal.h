@@ -89,9 +89,7 @@ struct dn_model {
     int64_t partial_floats;
     int32_t splits;
     // pre-activations too close to zero for the fp32 accumulation to settle their sign
-    int64_t* fix_list;             // entries (row << 16 | column)
-    int32_t* fix_count;            // [0] entries pushed, [1] sticky overflow flag
-    int64_t fix_cap;
+    int32_t* fix_count;            // [0] exact recomputations in the last ReLU layer, [1] sticky overflow flag
     const void* h0;                // H^0 of the last forward
     uint64_t fwd_serial;           // sample the saved activations belong to
     int32_t weights_set;

@@ -19,8 +19,9 @@
 // repeated; an operand that derives from the caller's inputs is one term.
 //
 // ReLU sign: where |Z| is below a bound on the fp32 accumulation error (2 K 2^-24 |x| |w|), the
-// epilogue queues the element and k_relu_fixup recomputes that dot product in fp64, so that the
-// stored activation and the mask [Z > 0] used by the backward pass are those of the exact sum.
+// epilogue queues the element in LDS and the workgroup then recomputes that dot product in fp64,
+// so that the stored activation and the mask [Z > 0] used by the backward pass are those of the
+// exact sum.
 #include "dn_internal.h"
 
 namespace {
@@ -30,6 +31,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BM = 128, BN = 128, BK = 64, TPB = 256;
+constexpr int LOCAL_FIX_CAP = 1024;     // sign fix-ups one workgroup can queue (of its 16384 outputs)
 enum { EPI_BIAS_ACT = 0, EPI_PLAIN = 1, EPI_SPLIT = 2 };
 
 struct GemmArgs {
@@ -48,16 +50,20 @@ struct GemmArgs {
     int64_t b_term_stride;  // dW: elements between B's terms
     // ReLU sign fix-up (EPI_BIAS_ACT with relu)
     const float* rownorm; const float* colnorm; float gamma;
-    long long* fix_list; int* fix_count; long long fix_cap;
+    int* fix_count;         // [0] number of exact recomputations, [1] sticky overflow flag
 };
 
-__device__ __forceinline__ int slot(int row, int c) { return row * 8 + (c ^ (row & 7)); }
+// 16-byte slot of chunk c of tile row `row`: 16 consecutive rows of one chunk column land in 16 different
+// 16-byte bank groups (row parity picks the half, (row >> 1) & 7 permutes the chunks within it)
+__device__ __forceinline__ int slot(int row, int c) { return row * 8 + (c ^ ((row >> 1) & 7)); }
+
+struct TileRegs { u32x4 a[4], b[4]; };
 
 template <int EPI>
-__global__ __launch_bounds__(TPB) void k_gemm_nt(GemmArgs a)
+__global__ __launch_bounds__(TPB, 2) void k_gemm_nt(GemmArgs a)
 {
-    __shared__ u32x4 As[BM * BK / 8];
-    __shared__ u32x4 Bs[BN * BK / 8];
+    __shared__ u32x4 As[2][BM * BK / 8];
+    __shared__ u32x4 Bs[2][BN * BK / 8];
 
     const int rows_layer = a.hdr[HDR_N] - a.hdr[HDR_NODE_OFF + a.layer];
     const int M = a.m_const >= 0 ? a.m_const : rows_layer;
@@ -86,38 +92,42 @@ __global__ __launch_bounds__(TPB) void k_gemm_nt(GemmArgs a)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    u32x4 ra[4], rb[4];
-    auto load_tiles = [&](int kc) {
+    // Two register stages: while tile kc is multiplied out of LDS, tiles kc+1 and kc+2 are in
+    // flight, so a chain of dependent k-steps exposes half of the memory latency per step.  Two
+    // LDS buffers allow a single barrier per step.
+    const uint16_t* a_ptr[4];
+    const uint16_t* b_ptr[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int id = t + TPB * i, row = id >> 3, c = id & 7;
+        a_ptr[i] = a.A + (int64_t)(row0 + row) * a.lda + c * 8;
+        b_ptr[i] = Bbase + (int64_t)(col0 + row) * a.ldb + c * 8;
+    }
+    auto load_tiles = [&](TileRegs& r, int kc) {
         const int64_t k0 = (int64_t)kc * BK;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int id = t + TPB * i, row = id >> 3, c = id & 7;
-            ra[i] = *reinterpret_cast<const u32x4*>(a.A + (int64_t)(row0 + row) * a.lda + k0 + c * 8);
-            rb[i] = *reinterpret_cast<const u32x4*>(Bbase + (int64_t)(col0 + row) * a.ldb + k0 + c * 8);
+            r.a[i] = *reinterpret_cast<const u32x4*>(a_ptr[i] + k0);
+            r.b[i] = *reinterpret_cast<const u32x4*>(b_ptr[i] + k0);
         }
     };
-    auto store_tiles = [&]() {
+    auto store_tiles = [&](const TileRegs& r, int buf) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int id = t + TPB * i, row = id >> 3, c = id & 7;
-            As[slot(row, c)] = ra[i];
-            Bs[slot(row, c)] = rb[i];
+            As[buf][slot(row, c)] = r.a[i];
+            Bs[buf][slot(row, c)] = r.b[i];
         }
     };
-
-    if (kc_begin < kc_end) load_tiles(kc_begin);
-    for (int kc = kc_begin; kc < kc_end; ++kc) {
-        store_tiles();
-        __syncthreads();
-        if (kc + 1 < kc_end) load_tiles(kc + 1);
+    auto multiply = [&](int buf) {
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             const int c = 2 * ks + (lane >> 5);
             bf16x8 fa[2], fb[2];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                fa[i] = __builtin_bit_cast(bf16x8, As[slot(wm * 64 + i * 32 + (lane & 31), c)]);
-                fb[i] = __builtin_bit_cast(bf16x8, Bs[slot(wn * 64 + i * 32 + (lane & 31), c)]);
+                fa[i] = __builtin_bit_cast(bf16x8, As[buf][slot(wm * 64 + i * 32 + (lane & 31), c)]);
+                fb[i] = __builtin_bit_cast(bf16x8, Bs[buf][slot(wn * 64 + i * 32 + (lane & 31), c)]);
             }
 #pragma unroll
             for (int i = 0; i < 2; ++i)
@@ -125,26 +135,36 @@ __global__ __launch_bounds__(TPB) void k_gemm_nt(GemmArgs a)
                 for (int j = 0; j < 2; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
         }
-        __syncthreads();
+    };
+
+    TileRegs r0, r1;
+    if (kc_begin + 0 < kc_end) load_tiles(r0, kc_begin + 0);
+    if (kc_begin + 1 < kc_end) load_tiles(r1, kc_begin + 1);
+    int kc = kc_begin, buf = 0;
+#define DN_GEMM_STEP(R)                                       \
+    if (kc >= kc_end) break;                                  \
+    store_tiles(R, buf);                                      \
+    __syncthreads();                                          \
+    if (kc + 2 < kc_end) load_tiles(R, kc + 2);               \
+    multiply(buf);                                            \
+    buf ^= 1;                                                 \
+    ++kc;
+    for (;;) {
+        DN_GEMM_STEP(r0)
+        DN_GEMM_STEP(r1)
     }
+#undef DN_GEMM_STEP
 
     // epilogue: lane holds column (lane & 31); register e holds row 8*(e/4) + 4*(lane/32) + e%4
     float* C = a.C;
     if (EPI == EPI_SPLIT) C += (int64_t)blockIdx.z * a.split_stride;
-    float rn[2][16];                       // row norms of this lane's 32 rows, fetched in one batch
-    __shared__ int s_fix_n, s_fix_base;
-    long long* local_fix = reinterpret_cast<long long*>(As);     // the operand tiles are no longer needed
-    constexpr int LOCAL_FIX_CAP = BM * BK / 8 * 16 / 8;
+    __shared__ int s_fix_n;
+    __shared__ long long local_fix[LOCAL_FIX_CAP];
+    __shared__ float s_rownorm[BM];
     if (EPI == EPI_BIAS_ACT && a.relu) {
         if (t == 0) s_fix_n = 0;
+        if (t < BM) s_rownorm[t] = row0 + t < M ? a.rownorm[row0 + t] : 0.f;
         __syncthreads();
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int m = row0 + wm * 64 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-                rn[i][e] = m < M ? a.rownorm[m] : 0.f;
-            }
     }
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -163,16 +183,10 @@ __global__ __launch_bounds__(TPB) void k_gemm_nt(GemmArgs a)
                     if (EPI == EPI_BIAS_ACT) {
                         v += bv;
                         if (a.relu) {
-                            if (fabsf(v) <= cn * rn[i][e] + bt) {
-                                // queue in LDS first: one global atomic per workgroup instead of one per element
-                                const long long ent = ((long long)m << 16) | (long long)n;
+                            if (fabsf(v) <= cn * s_rownorm[m - row0] + bt) {
+                                // the fp32 sum cannot settle this sign: queue the element for the exact pass below
                                 const int lp = atomicAdd(&s_fix_n, 1);
-                                if (lp < LOCAL_FIX_CAP) local_fix[lp] = ent;
-                                else {
-                                    const int pos = atomicAdd(&a.fix_count[0], 1);
-                                    if (pos < a.fix_cap) a.fix_list[pos] = ent;
-                                    else a.fix_count[1] = 1;
-                                }
+                                if (lp < LOCAL_FIX_CAP) local_fix[lp] = ((long long)m << 16) | (long long)n;
                             }
                             v = fmaxf(v, 0.f);
                         }
@@ -182,14 +196,37 @@ __global__ __launch_bounds__(TPB) void k_gemm_nt(GemmArgs a)
             }
         }
     if (EPI == EPI_BIAS_ACT && a.relu) {
+        // Exact pass: one wave per queued element recomputes Z = sum_k A[m][k] B[n][k] + b[n] in fp64
+        // (bf16 products are exact in fp64, the sum is good to 2^-53 of the magnitudes) and stores
+        // fp32(max(Z, 0)), so that the activation and the mask [Z > 0] of the backward pass are
+        // those of the exact sum.
         __syncthreads();
-        const int n_local = min(s_fix_n, LOCAL_FIX_CAP);
-        if (t == 0 && n_local > 0) s_fix_base = atomicAdd(&a.fix_count[0], n_local);
-        __syncthreads();
-        for (int q = t; q < n_local; q += TPB) {
-            const long long pos = (long long)s_fix_base + q;
-            if (pos < a.fix_cap) a.fix_list[pos] = local_fix[q];
-            else a.fix_count[1] = 1;
+        const int queued = s_fix_n;
+        const int n_local = min(queued, LOCAL_FIX_CAP);
+        if (t == 0 && queued > 0) {
+            atomicAdd(&a.fix_count[0], n_local);
+            if (queued > LOCAL_FIX_CAP) a.fix_count[1] = 1;       // surplus keeps its fp32 sign
+        }
+        for (int q = wave; q < n_local; q += TPB / 64) {
+            const long long ent = local_fix[q];
+            const int m = (int)(ent >> 16), n = (int)(ent & 0xffff);
+            const uint16_t* xr = a.A + (int64_t)m * a.lda;
+            const uint16_t* wr = Bbase + (int64_t)n * a.ldb;
+            double sum = 0.0;
+            for (int c = lane; c < red / 8; c += 64) {
+                const u32x4 xv = *reinterpret_cast<const u32x4*>(xr + c * 8);
+                const u32x4 wv = *reinterpret_cast<const u32x4*>(wr + c * 8);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    sum += (double)__uint_as_float(xv[e] << 16) * (double)__uint_as_float(wv[e] << 16);
+                    sum += (double)__uint_as_float(xv[e] & 0xffff0000u) * (double)__uint_as_float(wv[e] & 0xffff0000u);
+                }
+            }
+            for (int d = 32; d > 0; d >>= 1) sum += __shfl_down(sum, d, 64);
+            if (lane == 0) {
+                const double z = sum + (double)a.bias[n];
+                C[(int64_t)m * a.ldc + n] = (float)(z > 0.0 ? z : 0.0);
+            }
         }
     }
 }
@@ -219,39 +256,6 @@ __global__ __launch_bounds__(TPB) void k_dw_reduce(const float* __restrict__ par
     }
     if (kk < d_in) dws[(int64_t)kk * d_out + n] = s;
     else dwn[(int64_t)(kk - d_in) * d_out + n] = s;
-}
-
-// One wave per queued element: Z = sum_k X[m][k] * Wt[n][k] + b[n] in fp64 (bf16 products are
-// exact in fp64, the sum is good to 2^-53 of the magnitudes), H[m][n] = fp32(max(Z, 0)).
-__global__ __launch_bounds__(TPB) void k_relu_fixup(const long long* __restrict__ fix_list, const int* __restrict__ fix_count,
-                                                    long long fix_cap, const uint16_t* __restrict__ X,
-                                                    const uint16_t* __restrict__ Wt, int kp, const float* __restrict__ bias,
-                                                    float* __restrict__ H, int ldh)
-{
-    const int lane = threadIdx.x & 63;
-    const long long total = min((long long)fix_count[0], fix_cap);
-    const int waves = gridDim.x * (TPB / 64);
-    for (long long it = (long long)blockIdx.x * (TPB / 64) + (threadIdx.x >> 6); it < total; it += waves) {
-        const long long ent = fix_list[it];
-        const int m = (int)(ent >> 16), n = (int)(ent & 0xffff);
-        const uint16_t* xr = X + (int64_t)m * kp;
-        const uint16_t* wr = Wt + (int64_t)n * kp;
-        double s = 0.0;
-        for (int c = lane; c < kp / 8; c += 64) {             // kp is a multiple of 64, rows are 16-byte aligned
-            const u32x4 xv = *reinterpret_cast<const u32x4*>(xr + c * 8);
-            const u32x4 wv = *reinterpret_cast<const u32x4*>(wr + c * 8);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                s += (double)__uint_as_float(xv[e] << 16) * (double)__uint_as_float(wv[e] << 16);
-                s += (double)__uint_as_float(xv[e] & 0xffff0000u) * (double)__uint_as_float(wv[e] & 0xffff0000u);
-            }
-        }
-        for (int d = 32; d > 0; d >>= 1) s += __shfl_down(s, d, 64);
-        if (lane == 0) {
-            const double z = s + (double)bias[n];
-            H[(int64_t)m * ldh + n] = (float)(z > 0.0 ? z : 0.0);
-        }
-    }
 }
 
 // fp32 weights -> the two zero-padded bf16 layouts (round to nearest even).
@@ -316,14 +320,8 @@ int dn_gemm_forward(const dn_model* m, const dn_batch* b, int i, float* out, int
     a.bias = L.bias; a.relu = (i < m->k) ? 1 : 0; a.split_stride = 0; a.terms = 1; a.b_term_stride = 0;
     a.rownorm = L.rownorm; a.colnorm = L.colnorm;
     a.gamma = (float)L.kp * 1.1920929e-7f;                 // 2 K 2^-24: worst case of K fp32 additions, doubled
-    a.fix_list = reinterpret_cast<long long*>(m->fix_list); a.fix_count = m->fix_count; a.fix_cap = m->fix_cap;
-    int rc = launch<EPI_BIAS_ACT>(a, L.rows_cap, 1, st, "gemm_fwd");
-    if (rc || !a.relu) return rc;
-    dn_prof_scope ps("relu_fixup", i, st);
-    hipLaunchKernelGGL(k_relu_fixup, dim3(1024), dim3(TPB), 0, st, a.fix_list, a.fix_count, a.fix_cap, a.A, a.B, L.kp,
-                       L.bias, out, (int)ldc);
-    DN_LAUNCH_CHECK("k_relu_fixup");
-    return DN_OK;
+    a.fix_count = m->fix_count;
+    return launch<EPI_BIAS_ACT>(a, L.rows_cap, 1, st, "gemm_fwd");
 }
 
 // dX = bf16(dZ) * Wcat^T   -> m->dx [rows x kp], columns [0, 2*d_in) valid.

@@ -1,0 +1,88 @@
+"""GPU parity at the full workload sizes, in the launch configuration bench.py times: the 111M-node
+graph with fp32 features, the 122M-node graph with 768-wide bf16 features, and the 86M-node
+link-prediction shape sampled over in- and out-edges.  The graph is generated on the device,
+copied to the host for the oracle, and the whole DENSE structure, the gathered rows, the
+embeddings and the gradients are compared."""
+import gc
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2202_02365_amd as dn
+from workloads import CONFIGS, make_inputs, class_labels, softmax_xent_grad
+from gpu_harness import assert_dense_equal, row_rel_err, to_dev
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-4
+
+
+def run_full(cfg, batches, n_targets=None, want_dh0=False):
+    dev = torch.device("cuda:0")
+    inputs = make_inputs(cfg, dev, n_batches=max(batches) + 1)
+    og = oracle.Graph(cfg.num_nodes, inputs["rowptr"].cpu().numpy(), inputs["col"].cpu().numpy(),
+                      None if inputs["rowptr_in"] is None else inputs["rowptr_in"].cpu().numpy(),
+                      None if inputs["col_in"] is None else inputs["col_in"].cpu().numpy())
+    graph = dn.Graph(inputs["rowptr"], inputs["col"], inputs["rowptr_in"], inputs["col_in"])
+    batch = dn.Batch(cfg.num_nodes, cfg.batch, cfg.fanouts, cfg.direction)
+    in_dtype = dn.DN_F32 if cfg.feat_dtype == "f32" else dn.DN_BF16
+    model = dn.Model(batch, cfg.dims, in_dtype)
+    w_self, w_nbr, bias = inputs["weights"]
+    model.set_weights(to_dev(w_self), to_dev(w_nbr), to_dev(bias))
+    params = oracle.SageParams(w_self, w_nbr, bias)
+    table = inputs["table"]
+    h0 = torch.empty((batch.node_capacity, cfg.dims[0]), dtype=table.dtype, device=dev)
+    report = []
+    for bi in batches:
+        targets = inputs["targets"][bi] if n_targets is None else inputs["targets"][bi][:n_targets]
+        dn.dense_sample(batch, graph, torch.from_numpy(targets).to(dev), bi)
+        view = {k: v.cpu().numpy() for k, v in batch.view().items()}
+        d = oracle.dense_sample(og, targets, cfg.fanouts, seed=bi, direction=cfg.direction)
+        assert_dense_equal(view, d)
+        n = len(d.node_ids)
+        dn.dense_gather(batch, table, h0)
+        ids = torch.from_numpy(d.node_ids.astype(np.int64)).to(dev)
+        assert torch.equal(h0[:n], table[ids])                            # gathered rows, bit for bit
+        out = torch.empty((len(targets), cfg.dims[-1]), dtype=torch.float32, device=dev)
+        dn.sage_forward(model, batch, h0, out)
+        st = oracle.sage_forward(d, table[ids].float().cpu().numpy(), params, mode="bf16")
+        errs = {"fwd": row_rel_err(out.cpu().numpy(), st.out)}
+        gout = softmax_xent_grad(st.out, class_labels(len(targets), cfg.dims[-1]))
+        grads = oracle.sage_backward(st, params, gout, mode="bf16")
+        dws = [torch.empty_like(t) for t in to_dev(w_self)]
+        dwn = [torch.empty_like(t) for t in to_dev(w_nbr)]
+        dbs = [torch.empty_like(t) for t in to_dev(bias)]
+        dh0 = torch.empty((batch.node_capacity, cfg.dims[0]), device=dev) if want_dh0 else None
+        dn.sage_backward(model, batch, torch.from_numpy(gout).to(dev), dws, dwn, dbs, dh0)
+        torch.cuda.synchronize()
+        assert model.status()[1] == 0
+        for i in range(cfg.num_layers):
+            errs["dws%d" % (i + 1)] = row_rel_err(dws[i].cpu().numpy(), grads.d_w_self[i])
+            errs["dwn%d" % (i + 1)] = row_rel_err(dwn[i].cpu().numpy(), grads.d_w_nbr[i])
+            errs["db%d" % (i + 1)] = row_rel_err(dbs[i].cpu().numpy(), grads.d_bias[i])
+        if want_dh0:
+            errs["dh0"] = row_rel_err(dh0[:n].cpu().numpy(), grads.d_h0)
+        print(cfg.name, "batch", bi, "N=%d E=%d" % (n, len(d.nbrs)), {k: float("%.2e" % v) for k, v in errs.items()})
+        bad = {k: v for k, v in errs.items() if not v <= TOL}
+        assert not bad, bad
+        report.append((n, len(d.nbrs)))
+    del inputs, graph, batch, model, table, h0, og
+    gc.collect()
+    torch.cuda.empty_cache()
+    return report
+
+
+def test_rmat111m_fp32_features():
+    report = run_full(CONFIGS[2], batches=[0, 3])
+    assert all(n > 20000 for n, _ in report)
+
+
+def test_rmat122m_bf16_features():
+    run_full(CONFIGS[3], batches=[1])
+
+
+def test_rmat86m_both_directions_with_input_gradient():
+    """150,000 target nodes (the size of the unique endpoints + negatives of a 50,000-edge batch),
+    20 in- plus 20 out-neighbours, one layer, gradient with respect to the learnable inputs."""
+    run_full(CONFIGS[4], batches=[0], want_dh0=True)
