@@ -116,6 +116,7 @@ def main():
     ap.add_argument("--workload", default="rmat111m")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-times", action="store_true")
+    ap.add_argument("--no-graphs", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -158,6 +159,39 @@ def main():
         if backward:
             dn.sage_backward(model, batch, grad_out, dws, dwn, dbs, dh0)
 
+    # Two mini-batches in flight: batch t+1 is sampled and gathered on one stream while batch t runs
+    # forward/backward on another (mini-batch construction does not read the weights; this is the
+    # paper's pipelining of construction with compute, Section 3, on two HIP streams of one GPU).
+    slots = [(batch, h0), (dn.Batch(cfg.num_nodes, cfg.batch, cfg.fanouts, cfg.direction), torch.empty_like(h0))]
+    s_build, s_compute = torch.cuda.Stream(), torch.cuda.Stream()
+    ev_built = [torch.cuda.Event(), torch.cuda.Event()]
+    ev_free = [torch.cuda.Event(), torch.cuda.Event()]
+
+    def timed_pipelined(n_steps, backward=True):
+        torch.cuda.synchronize()
+        for e in ev_free:
+            e.record()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(n_steps):
+            b_s, h0_s = slots[s & 1]
+            bi = s % N_BATCHES
+            with torch.cuda.stream(s_build):
+                s_build.wait_event(ev_free[s & 1])
+                dn.dense_sample(b_s, graph, targets[bi], bi)
+                dn.dense_gather(b_s, table, h0_s)
+                if backward:
+                    b_s.prepare_backward(need_dh0)
+                ev_built[s & 1].record(s_build)
+            with torch.cuda.stream(s_compute):
+                s_compute.wait_event(ev_built[s & 1])
+                dn.sage_forward(model, b_s, h0_s, out)
+                if backward:
+                    dn.sage_backward(model, b_s, grad_out, dws, dwn, dbs, dh0)
+                ev_free[s & 1].record(s_compute)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
     # sizes of every batch (untimed; counts() waits for the device)
     sizes = []
     for bi in range(N_BATCHES):
@@ -179,12 +213,78 @@ def main():
         torch.cuda.synchronize()
         return time.perf_counter() - t0
 
-    timed(args.warmup)
-    total_s = timed(args.steps)
+    # The same pipeline replayed from HIP graphs, one graph per batch index, captured once, so that
+    # the host submits 1 graph launch per step instead of ~40 kernel launches (the step is a chain of small kernels and the host would otherwise
+    # be the bottleneck).  Replays launch exactly the kernels of the eager path; one replay is compared
+    # with an eager step below.
+    graphs = {}
+
+    def capture_graphs(backward):
+        # graph bi: forward(+backward) of batch bi on the capture stream, and, forked onto a second
+        # stream inside the same graph, sampling + gather of batch bi+1 into the other slot
+        for bi in range(N_BATCHES):
+            nxt = (bi + 1) % N_BATCHES
+            b_cur, h0_cur = slots[bi & 1]
+            b_nxt, h0_nxt = slots[nxt & 1]
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=s_compute):
+                s_build.wait_stream(s_compute)
+                with torch.cuda.stream(s_build):
+                    dn.dense_sample(b_nxt, graph, targets[nxt], nxt)
+                    dn.dense_gather(b_nxt, table, h0_nxt)
+                    if backward:
+                        b_nxt.prepare_backward(need_dh0)
+                dn.sage_forward(model, b_cur, h0_cur, out)
+                if backward:
+                    dn.sage_backward(model, b_cur, grad_out, dws, dwn, dbs, dh0)
+                s_compute.wait_stream(s_build)
+            graphs[(bi, backward)] = g
+        torch.cuda.synchronize()
+
+    def timed_graphs(n_steps, backward=True):
+        # prologue (untimed): construct batch 0 so that the first graph finds its inputs
+        with torch.cuda.stream(s_compute):
+            dn.dense_sample(slots[0][0], graph, targets[0], 0)
+            dn.dense_gather(slots[0][0], table, slots[0][1])
+            if backward:
+                slots[0][0].prepare_backward(need_dh0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        with torch.cuda.stream(s_compute):
+            for s in range(n_steps):
+                graphs[(s % N_BATCHES, backward)].replay()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
     edges = sum(sizes[s % N_BATCHES][k + 2] for s in range(args.steps))
-    fwd_only_s = timed(args.steps, backward=False)
-    log("timed %d steps: %.3f ms/step (sample+gather+fwd only: %.3f ms)" %
-        (args.steps, 1e3 * total_s / args.steps, 1e3 * fwd_only_s / args.steps))
+    timed(args.warmup)
+    serial_s = timed(args.steps)
+    serial_fwd_s = timed(args.steps, backward=False)
+    if args.no_graphs:
+        timed_pipelined(args.warmup)
+        total_s = timed_pipelined(args.steps)
+        fwd_only_s = timed_pipelined(args.steps, backward=False)
+    else:
+        assert N_BATCHES % 2 == 0
+        # eager reference for batch 5, to compare one replay with
+        step(5)
+        torch.cuda.synchronize()
+        eager = [t.clone() for t in dws + dwn + dbs + [out]]
+        capture_graphs(True)
+        capture_graphs(False)
+        timed_graphs(args.warmup)
+        total_s = timed_graphs(args.steps)
+        fwd_only_s = timed_graphs(args.steps, backward=False)
+        with torch.cuda.stream(s_compute):
+            graphs[(4, True)].replay()           # constructs batch 5
+            graphs[(5, True)].replay()           # forward + backward of batch 5
+        torch.cuda.synchronize()
+        if not all(torch.equal(a, b) for a, b in zip(eager, dws + dwn + dbs + [out])):
+            raise RuntimeError("a graph replay differs from the eager step")
+    log("timed %d steps, two mini-batches in flight: %.3f ms/step (sample+gather+fwd only: %.3f ms); "
+        "one in flight: %.3f ms/step (%.3f ms)" %
+        (args.steps, 1e3 * total_s / args.steps, 1e3 * fwd_only_s / args.steps,
+         1e3 * serial_s / args.steps, 1e3 * serial_fwd_s / args.steps))
 
     # per-kernel durations: the same K steps again, every launch bracketed by HIP events on its stream
     roofline, kernels = None, {}
@@ -236,9 +336,14 @@ def main():
                    "dims": dims, "fanouts": list(cfg.fanouts), "batch": cfg.batch,
                    "mean_nodes_per_batch": mean_n, "mean_sampled_edges_per_batch": mean_e},
         "mini_batches_per_s": args.steps / total_s,
+        "in_flight": "2 mini-batches: sample+gather of batch t+1 on one stream, forward+backward of batch t on another",
+        "launch": "eager" if args.no_graphs else "hipGraph replay (1 graph per step, construction forked onto a second stream)",
         "sample_gather_fwd": {"ms_per_step": 1e3 * fwd_only_s / args.steps,
                               "mini_batches_per_s": args.steps / fwd_only_s,
                               "sampled_edges_per_s": edges / fwd_only_s},
+        "one_in_flight": {"ms_per_step": 1e3 * serial_s / args.steps, "mini_batches_per_s": args.steps / serial_s,
+                          "sampled_edges_per_s": edges / serial_s,
+                          "sample_gather_fwd_ms_per_step": 1e3 * serial_fwd_s / args.steps},
         "roofline": roofline,
         "kernels": kernels,
         "cpu_baseline": baseline,

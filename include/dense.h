@@ -106,6 +106,13 @@ DN_API int  dn_batch_capacity(const dn_batch* b, int64_t* node_capacity, int64_t
 DN_API int  dense_sample(dn_batch* b, const dn_graph* g, const int32_t* d_targets, int32_t n_targets,
                   uint64_t seed, void* stream);
 
+/* Optional: builds, on `stream`, the index sage_backward needs for the transpose of the neighbour mean
+ * (neighbour slots grouped by the row of H they read; with need_input_grad = 0 only the slots of layers
+ * 2..k).  sage_backward builds it itself when this was not called for the current sample; calling it
+ * right after dense_sample moves that work off the forward/backward chain, e.g. onto the stream
+ * that constructs mini-batches. */
+DN_API int  dn_batch_prepare_backward(dn_batch* b, int32_t need_input_grad, void* stream);
+
 /* Device pointers of the current sample. */
 DN_API int  dn_batch_view(const dn_batch* b, dn_dense_view* view);
 
@@ -151,7 +158,9 @@ DN_API int  sage_forward(dn_model* m, const dn_batch* b, const void* d_H0, float
  * (fp32 [dims[i]]) for every layer, and, when d_dH0 is not NULL, dL/dH^0 (fp32 [N x dims[0]],
  * capacity >= node capacity rows; needed for learnable base representations).  Uses the
  * activations saved by the last sage_forward on the same model and batch.  Neighbour-mean
- * gradients are summed per input row in ascending slot order (no floating-point atomics). */
+ * gradients are summed per input row in ascending slot order (no floating-point atomics).
+ * The weight-gradient kernels run on a second stream the model owns (forked from and joined back to
+ * `stream` with events, so the call is still ordered on `stream` as a whole). */
 DN_API int  sage_backward(dn_model* m, const dn_batch* b, const float* d_grad_out,
                    float* const* d_dw_self, float* const* d_dw_nbr, float* const* d_dbias,
                    float* d_dH0, void* stream);

@@ -61,6 +61,7 @@ def load_library():
         "dn_batch_capacity": (ctypes.c_int, [vp, ctypes.POINTER(i64), ctypes.POINTER(i64)]),
         "dense_sample": (ctypes.c_int, [vp, vp, vp, i32, u64, vp]),
         "dn_batch_view": (ctypes.c_int, [vp, ctypes.POINTER(_View)]),
+        "dn_batch_prepare_backward": (ctypes.c_int, [vp, i32, vp]),
         "dn_batch_counts": (ctypes.c_int, [vp, ctypes.POINTER(i64), vp]),
         "dense_gather": (ctypes.c_int, [vp, vp, i32, i32, i64, vp, vp]),
         "dn_model_workspace_size": (ctypes.c_int, [vp, i32, ctypes.POINTER(i32), i32, ctypes.POINTER(sz)]),
@@ -161,6 +162,10 @@ class Batch:
         if getattr(self, "handle", None) and _lib is not None:
             _lib.dn_batch_destroy(self.handle)
             self.handle = None
+
+    def prepare_backward(self, need_input_grad: bool = False) -> None:
+        """Build the transpose index of the current sample now (on the current stream)."""
+        _check(load_library().dn_batch_prepare_backward(self.handle, 1 if need_input_grad else 0, _stream()))
 
     def counts(self) -> List[int]:
         """[node_id_offsets[0..k+1]..., E]; waits for the stream."""

@@ -125,7 +125,8 @@ int fill_model(dn_model* m, const dn_batch* b, int32_t k, const int32_t* dims, i
 void carve_model(dn_model* m, const dn_batch* b, Carver& c)
 {
     const int k = m->k;
-    int64_t max_dzb = 0, max_dzbt = 0, max_xt = 0, max_dx = 0, max_g = 0, max_w = 0, max_db = 0;
+    int64_t max_dzb = 0, max_dx = 0, max_g = 0;
+    m->splits = 32;
     for (int i = 1; i <= k; ++i) {
         dn_layer_bufs& L = m->layer[i - 1];
         L.x = c.take<dn_bf16>(L.rows_pad * L.kp);
@@ -135,27 +136,20 @@ void carve_model(dn_model* m, const dn_batch* b, Carver& c)
         L.bias = c.take<float>(L.d_out);
         L.rownorm = c.take<float>(L.rows_pad);
         L.colnorm = c.take<float>(L.d_out);
+        L.xt = c.take<dn_bf16>(dn_round_up(L.kp, 128) * L.rows_pad);
+        L.dzbt_term_stride = dn_round_up(L.d_out, 128) * L.rows_pad;
+        L.dzbt = c.take<dn_bf16>(L.zterms * L.dzbt_term_stride);
+        L.partial_floats = (int64_t)m->splits * L.kx * L.d_out * L.zterms;
+        L.partial = c.take<float>(L.partial_floats);
+        L.db_partial = c.take<float>(((L.rows_cap + 63) / 64 + 1) * L.d_out);
         max_dzb = std::max<int64_t>(max_dzb, L.rows_pad * L.nz);
-        max_dzbt = std::max<int64_t>(max_dzbt, dn_round_up(L.d_out, 128) * L.rows_pad);
-        max_xt = std::max<int64_t>(max_xt, dn_round_up(L.kp, 128) * L.rows_pad);
         max_dx = std::max<int64_t>(max_dx, L.rows_pad * 2 * L.d_in);
-        max_w = std::max<int64_t>(max_w, (int64_t)L.kx * L.d_out * L.zterms);
-        max_db = std::max<int64_t>(max_db, ((L.rows_cap + 63) / 64 + 1) * L.d_out);
-        if (i < k) {
-            max_g = std::max<int64_t>(max_g, L.rows_pad * L.d_out);   // gradient w.r.t. H^i
-        }
+        if (i < k) max_g = std::max<int64_t>(max_g, L.rows_pad * L.d_out);   // gradient w.r.t. H^i
     }
     m->dzb = c.take<dn_bf16>(max_dzb);
-    m->dzbt_term_stride = max_dzbt;
-    m->dzbt = c.take<dn_bf16>(2 * max_dzbt);
-    m->xt = c.take<dn_bf16>(max_xt);
     m->dx = c.take<float>(max_dx);
     m->g[0] = c.take<float>(max_g);
     m->g[1] = c.take<float>(max_g);
-    m->splits = 32;
-    m->partial_floats = (int64_t)m->splits * max_w;
-    m->partial = c.take<float>(m->partial_floats);
-    m->db_partial = c.take<float>(max_db);
     m->fix_count = c.take<int32_t>(64);
     (void)b;
 }
@@ -300,6 +294,13 @@ int dense_sample(dn_batch* b, const dn_graph* g, const int32_t* d_targets, int32
     return dn_launch_sample(b, g, d_targets, n_targets, seed, static_cast<hipStream_t>(stream));
 }
 
+int dn_batch_prepare_backward(dn_batch* b, int32_t need_input_grad, void* stream)
+{
+    if (!b) return dn_fail(DN_EINVAL, "batch is null");
+    if (b->sample_serial == 0) return dn_fail(DN_ESTATE, "dense_sample has not run on this batch");
+    return dn_launch_transpose_index(b, need_input_grad != 0, static_cast<hipStream_t>(stream));
+}
+
 int dn_batch_view(const dn_batch* b, dn_dense_view* view)
 {
     if (!b || !view) return dn_fail(DN_EINVAL, "batch or view is null");
@@ -368,6 +369,18 @@ int dn_model_create(dn_model** out, const dn_batch* b, int32_t k, const int32_t*
     hipError_t e = hipMemsetAsync(d_workspace, 0, c.bytes(), static_cast<hipStream_t>(stream));
     if (e != hipSuccess) { delete m; return dn_fail(DN_EHIP, "hipMemsetAsync: %s", hipGetErrorString(e)); }
     m->fwd_serial = ~0ull;
+    // second stream for the weight-gradient chain (default priority); without it everything stays on the caller's stream
+    m->side = nullptr;
+    m->ev_fork = m->ev_join = nullptr;
+    for (int i = 0; i < DN_MAX_LAYERS; ++i) m->ev_dz[i] = nullptr;
+    bool ok = hipStreamCreateWithFlags(&m->side, hipStreamNonBlocking) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&m->ev_fork, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&m->ev_join, hipEventDisableTiming) == hipSuccess;
+    for (int i = 0; ok && i < k; ++i) ok = hipEventCreateWithFlags(&m->ev_dz[i], hipEventDisableTiming) == hipSuccess;
+    if (!ok) {
+        (void)hipGetLastError();
+        if (m->side) { (void)hipStreamDestroy(m->side); m->side = nullptr; }
+    }
     *out = m;
     return DN_OK;
 }
@@ -383,7 +396,15 @@ int dn_model_set_weights(dn_model* m, const float* const* d_w_self, const float*
     return rc;
 }
 
-void dn_model_destroy(dn_model* m) { delete m; }
+void dn_model_destroy(dn_model* m)
+{
+    if (!m) return;
+    if (m->side) (void)hipStreamDestroy(m->side);
+    if (m->ev_fork) (void)hipEventDestroy(m->ev_fork);
+    if (m->ev_join) (void)hipEventDestroy(m->ev_join);
+    for (int i = 0; i < DN_MAX_LAYERS; ++i) if (m->ev_dz[i]) (void)hipEventDestroy(m->ev_dz[i]);
+    delete m;
+}
 
 int dn_model_status(const dn_model* m, int32_t* status, void* stream)
 {

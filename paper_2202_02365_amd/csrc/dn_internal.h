@@ -76,6 +76,13 @@ struct dn_layer_bufs {
     float* bias;         // [d_out]
     float* rownorm;      // [rows_pad] L2 norm of each X row (bounds the accumulation error of Z)
     float* colnorm;      // [d_out]    L2 norm of each Wcat^T row
+    // backward operands of the weight-gradient chain, per layer so that the chains of different layers overlap
+    dn_bf16* xt;         // [round128(kp) x rows_pad]  X^T
+    dn_bf16* dzbt;       // zterms x [round128(d_out) x rows_pad]  bf16 terms of dZ^T
+    int64_t dzbt_term_stride;
+    float* partial;      // split-K partials of dWcat
+    int64_t partial_floats;
+    float* db_partial;   // per row-tile column sums of dZ
 };
 
 struct dn_model {
@@ -83,11 +90,13 @@ struct dn_model {
     int32_t dims[DN_MAX_LAYERS + 1];
     dn_layer_bufs layer[DN_MAX_LAYERS];
     // backward temporaries, sized for the largest layer
-    dn_bf16 *dzb, *dzbt, *xt;
-    int64_t dzbt_term_stride;      // elements between the hi and lo transposes of dZ
-    float *dx, *g[2], *partial, *db_partial;
-    int64_t partial_floats;
+    dn_bf16* dzb;                  // bf16 terms of dZ, row-major (A operand of the dX GEMM)
+    float *dx, *g[2];
     int32_t splits;
+    // weight gradients (X^T, dW GEMM, reductions) run on a second stream beside the chain that
+    // carries the gradient down the layers; host objects only, no device memory
+    hipStream_t side;
+    hipEvent_t ev_fork, ev_dz[DN_MAX_LAYERS], ev_join;
     // pre-activations too close to zero for the fp32 accumulation to settle their sign
     int32_t* fix_count;            // [0] exact recomputations in the last ReLU layer, [1] sticky overflow flag
     const void* h0;                // H^0 of the last forward

@@ -104,10 +104,12 @@ __global__ __launch_bounds__(TPB) void k_dz(const int32_t* __restrict__ hdr, int
     __shared__ uint16_t tile[TERMS][64][66];
     __shared__ float colsum[4][64];
     const int rows = hdr[HDR_N] - hdr[HDR_NODE_OFF + layer];
-    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-    if (r0 >= ((rows + 63) / 64) * 64) return;
+    const int c0 = blockIdx.x * 64;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;    // ty: 0..3
     const int nz = TERMS * np;
+  for (int rt = blockIdx.y; rt * 64 < rows; rt += gridDim.y) {
+    const int r0 = rt * 64;
+    __syncthreads();
     float csum = 0.f;
     for (int rr = ty; rr < 64; rr += 4) {
         const int r = r0 + rr, n = c0 + tx;
@@ -129,10 +131,11 @@ __global__ __launch_bounds__(TPB) void k_dz(const int32_t* __restrict__ hdr, int
     colsum[ty][tx] = csum;
     __syncthreads();
     if (ty == 0 && c0 + tx < d_out)
-        db_partial[(int64_t)blockIdx.y * d_out + c0 + tx] = (colsum[0][tx] + colsum[1][tx]) + (colsum[2][tx] + colsum[3][tx]);
+        db_partial[(int64_t)rt * d_out + c0 + tx] = (colsum[0][tx] + colsum[1][tx]) + (colsum[2][tx] + colsum[3][tx]);
     for (int t = 0; t < TERMS; ++t)
         for (int cc = ty; cc < 64; cc += 4)
             dzbt[t * term_stride + (int64_t)(c0 + cc) * rows_pad + r0 + tx] = tile[t][tx][cc];
+  }
 }
 
 // db[n] = sum over the row tiles of k_dz.  64 columns per workgroup; each of its 4 waves takes every
@@ -166,16 +169,19 @@ __global__ __launch_bounds__(TPB) void k_transpose_x(const int32_t* __restrict__
 {
     __shared__ uint16_t tile[64][66];
     const int rows = hdr[HDR_N] - hdr[HDR_NODE_OFF + layer];
-    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-    if (r0 >= ((rows + 63) / 64) * 64) return;
+    const int c0 = blockIdx.x * 64;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int rr = ty; rr < 64; rr += 4) {
-        const int r = r0 + rr;
-        tile[rr][tx] = r < rows ? X[(int64_t)r * kp + c0 + tx] : (uint16_t)0;
+    for (int rt = blockIdx.y; rt * 64 < rows; rt += gridDim.y) {
+        const int r0 = rt * 64;
+        __syncthreads();
+        for (int rr = ty; rr < 64; rr += 4) {
+            const int r = r0 + rr;
+            tile[rr][tx] = r < rows ? X[(int64_t)r * kp + c0 + tx] : (uint16_t)0;
+        }
+        __syncthreads();
+        for (int cc = ty; cc < 64; cc += 4)
+            XT[(int64_t)(c0 + cc) * rows_pad + r0 + tx] = tile[tx][cc];
     }
-    __syncthreads();
-    for (int cc = ty; cc < 64; cc += 4)
-        XT[(int64_t)(c0 + cc) * rows_pad + r0 + tx] = tile[tx][cc];
 }
 
 // ---------------------------------------------------------------- backward aggregation (transpose of the mean)
@@ -325,35 +331,53 @@ int dn_launch_backward(dn_model* m, dn_batch* b, const float* grad_out, float* c
                        float* const* dwn, float* const* dbias, float* dh0, hipStream_t st)
 {
     const int k = m->k;
-    int rc = dn_launch_transpose_index(b, dh0 != nullptr, st);
+    int rc = dn_launch_transpose_index(b, dh0 != nullptr, st);     // no-op when prepared for this sample
     if (rc) return rc;
+    // Two chains.  `st` carries the gradient down the layers: dZ^i -> dX^i -> transpose of the mean
+    // -> dZ^{i-1}.  `side` computes what nothing downstream waits for: X^T, the dW GEMM and the
+    // reductions of dW and db.  Fork and join with events; every layer has its own operands.
+    hipStream_t side = m->side ? m->side : st;
+    if (side != st) {
+        DN_HIP(hipEventRecord(m->ev_fork, st));
+        DN_HIP(hipStreamWaitEvent(side, m->ev_fork, 0));
+    }
+    for (int i = k; i >= 1; --i) {                                  // X^T needs only the forward pass
+        const dn_layer_bufs& L = m->layer[i - 1];
+        unsigned row_tiles = (unsigned)((L.rows_cap + 63) / 64);
+        if (row_tiles > 65535) row_tiles = 65535;
+        { dn_prof_scope ps("transpose_x", i, side);
+        hipLaunchKernelGGL(k_transpose_x, dim3((unsigned)(L.kp / 64), row_tiles ? row_tiles : 1), dim3(TPB), 0, side,
+                           b->hdr, i, reinterpret_cast<const uint16_t*>(L.x), L.kp, reinterpret_cast<uint16_t*>(L.xt),
+                           L.rows_pad);
+        }
+        DN_LAUNCH_CHECK("k_transpose_x");
+    }
     const float* g = grad_out;
     for (int i = k; i >= 1; --i) {
         const dn_layer_bufs& L = m->layer[i - 1];
-        const unsigned row_tiles = (unsigned)((L.rows_cap + 63) / 64);
+        unsigned row_tiles = (unsigned)((L.rows_cap + 63) / 64);
+        if (row_tiles > 65535) row_tiles = 65535;           // the kernels stride over the row tiles beyond the grid
         { dn_prof_scope ps("dz", i, st);
         if (L.zterms == 2)
             hipLaunchKernelGGL((k_dz<2>), dim3((unsigned)(L.np / 64), row_tiles ? row_tiles : 1), dim3(TPB), 0, st, b->hdr,
                                i, g, L.d_out, L.h, L.d_out, L.np, 1, reinterpret_cast<uint16_t*>(m->dzb),
-                               reinterpret_cast<uint16_t*>(m->dzbt), L.rows_pad, m->dzbt_term_stride, m->db_partial);
+                               reinterpret_cast<uint16_t*>(L.dzbt), L.rows_pad, L.dzbt_term_stride, L.db_partial);
         else
             hipLaunchKernelGGL((k_dz<1>), dim3((unsigned)(L.np / 64), row_tiles ? row_tiles : 1), dim3(TPB), 0, st, b->hdr,
                                i, g, L.d_out, nullptr, L.d_out, L.np, 0, reinterpret_cast<uint16_t*>(m->dzb),
-                               reinterpret_cast<uint16_t*>(m->dzbt), L.rows_pad, m->dzbt_term_stride, m->db_partial);
+                               reinterpret_cast<uint16_t*>(L.dzbt), L.rows_pad, L.dzbt_term_stride, L.db_partial);
         }
         DN_LAUNCH_CHECK("k_dz");
-        { dn_prof_scope ps("db_reduce", i, st);
-        hipLaunchKernelGGL(k_db_reduce, dim3((L.d_out + 63) / 64), dim3(TPB), 0, st, b->hdr, i, m->db_partial,
+        if (side != st) {
+            DN_HIP(hipEventRecord(m->ev_dz[i - 1], st));
+            DN_HIP(hipStreamWaitEvent(side, m->ev_dz[i - 1], 0));
+        }
+        { dn_prof_scope ps("db_reduce", i, side);
+        hipLaunchKernelGGL(k_db_reduce, dim3((L.d_out + 63) / 64), dim3(TPB), 0, side, b->hdr, i, L.db_partial,
                            L.d_out, dbias[i - 1]);
         }
         DN_LAUNCH_CHECK("k_db_reduce");
-        { dn_prof_scope ps("transpose_x", i, st);
-        hipLaunchKernelGGL(k_transpose_x, dim3((unsigned)(L.kp / 64), row_tiles ? row_tiles : 1), dim3(TPB), 0, st,
-                           b->hdr, i, reinterpret_cast<const uint16_t*>(L.x), L.kp, reinterpret_cast<uint16_t*>(m->xt),
-                           L.rows_pad);
-        }
-        DN_LAUNCH_CHECK("k_transpose_x");
-        rc = dn_gemm_dw(m, b, i, dws[i - 1], dwn[i - 1], st);
+        rc = dn_gemm_dw(m, b, i, dws[i - 1], dwn[i - 1], side);
         if (rc) return rc;
         if (i == 1 && dh0 == nullptr) break;            // nothing consumes the input gradient of layer 1
         rc = dn_gemm_dx(m, b, i, st);
@@ -362,6 +386,10 @@ int dn_launch_backward(dn_model* m, dn_batch* b, const float* grad_out, float* c
         rc = launch_aggregate_bwd(m, b, i, gin, st);
         if (rc) return rc;
         g = gin;
+    }
+    if (side != st) {
+        DN_HIP(hipEventRecord(m->ev_join, side));
+        DN_HIP(hipStreamWaitEvent(st, m->ev_join, 0));
     }
     return DN_OK;
 }

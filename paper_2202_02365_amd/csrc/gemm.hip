@@ -196,7 +196,7 @@ __global__ __launch_bounds__(TPB, 2) void k_gemm_nt(GemmArgs a)
             }
         }
     if (EPI == EPI_BIAS_ACT && a.relu) {
-        // Exact pass: one wave per queued element recomputes Z = sum_k A[m][k] B[n][k] + b[n] in fp64
+        // Exact pass: 16 lanes per queued element recompute Z = sum_k A[m][k] B[n][k] + b[n] in fp64
         // (bf16 products are exact in fp64, the sum is good to 2^-53 of the magnitudes) and stores
         // fp32(max(Z, 0)), so that the activation and the mask [Z > 0] of the backward pass are
         // those of the exact sum.
@@ -207,13 +207,15 @@ __global__ __launch_bounds__(TPB, 2) void k_gemm_nt(GemmArgs a)
             atomicAdd(&a.fix_count[0], n_local);
             if (queued > LOCAL_FIX_CAP) a.fix_count[1] = 1;       // surplus keeps its fp32 sign
         }
-        for (int q = wave; q < n_local; q += TPB / 64) {
+        // 16 lanes per queued element, 16 elements in flight per workgroup
+        const int sub = t >> 4, sl = t & 15;
+        for (int q = sub; q < n_local; q += TPB / 16) {
             const long long ent = local_fix[q];
             const int m = (int)(ent >> 16), n = (int)(ent & 0xffff);
             const uint16_t* xr = a.A + (int64_t)m * a.lda;
             const uint16_t* wr = Bbase + (int64_t)n * a.ldb;
             double sum = 0.0;
-            for (int c = lane; c < red / 8; c += 64) {
+            for (int c = sl; c < red / 8; c += 16) {
                 const u32x4 xv = *reinterpret_cast<const u32x4*>(xr + c * 8);
                 const u32x4 wv = *reinterpret_cast<const u32x4*>(wr + c * 8);
 #pragma unroll
@@ -222,8 +224,8 @@ __global__ __launch_bounds__(TPB, 2) void k_gemm_nt(GemmArgs a)
                     sum += (double)__uint_as_float(xv[e] & 0xffff0000u) * (double)__uint_as_float(wv[e] & 0xffff0000u);
                 }
             }
-            for (int d = 32; d > 0; d >>= 1) sum += __shfl_down(sum, d, 64);
-            if (lane == 0) {
+            for (int d = 8; d > 0; d >>= 1) sum += __shfl_down(sum, d, 16);
+            if (sl == 0) {
                 const double z = sum + (double)a.bias[n];
                 C[(int64_t)m * a.ldc + n] = (float)(z > 0.0 ? z : 0.0);
             }
@@ -319,7 +321,10 @@ int dn_gemm_forward(const dn_model* m, const dn_batch* b, int i, float* out, int
     a.hdr = b->hdr; a.layer = i; a.m_const = -1; a.ncols = L.d_out; a.red_const = L.kp;
     a.bias = L.bias; a.relu = (i < m->k) ? 1 : 0; a.split_stride = 0; a.terms = 1; a.b_term_stride = 0;
     a.rownorm = L.rownorm; a.colnorm = L.colnorm;
-    a.gamma = (float)L.kp * 1.1920929e-7f;                 // 2 K 2^-24: worst case of K fp32 additions, doubled
+    // bound on |fp32 sum - exact sum| / (|x| |w|): 8 sqrt(K) 2^-24.  K additions, each off by at most 2^-24 of a
+    // partial sum that Cauchy-Schwarz bounds by |x| |w|; the errors add like a random walk, and 8 standard
+    // deviations leave a failure probability below 1e-14 per element (the worst case, K 2^-24, needs aligned errors)
+    a.gamma = 8.0f * sqrtf((float)L.kp) * 5.9604645e-8f;
     a.fix_count = m->fix_count;
     return launch<EPI_BIAS_ACT>(a, L.rows_cap, 1, st, "gemm_fwd");
 }
@@ -349,20 +354,20 @@ int dn_gemm_dw(const dn_model* m, const dn_batch* b, int i, float* dws, float* d
     if (splits > chunks_cap) splits = (int)(chunks_cap > 0 ? chunks_cap : 1);
     if (splits < 1) splits = 1;
     GemmArgs a{};
-    a.A = reinterpret_cast<const uint16_t*>(m->xt); a.lda = L.rows_pad;
-    a.B = reinterpret_cast<const uint16_t*>(m->dzbt); a.ldb = L.rows_pad;
-    a.C = m->partial; a.ldc = L.d_out;
+    a.A = reinterpret_cast<const uint16_t*>(L.xt); a.lda = L.rows_pad;
+    a.B = reinterpret_cast<const uint16_t*>(L.dzbt); a.ldb = L.rows_pad;
+    a.C = L.partial; a.ldc = L.d_out;
     a.hdr = b->hdr; a.layer = i; a.m_const = L.kx; a.ncols = L.d_out; a.red_const = -1;
     a.bias = nullptr; a.relu = 0; a.split_stride = (int64_t)L.kx * L.d_out;
-    a.terms = L.zterms; a.b_term_stride = m->dzbt_term_stride;
+    a.terms = L.zterms; a.b_term_stride = L.dzbt_term_stride;
     const int zsplits = splits * L.zterms;
-    if ((int64_t)zsplits * a.split_stride > m->partial_floats)
+    if ((int64_t)zsplits * a.split_stride > L.partial_floats)
         return dn_fail(DN_ECAPACITY, "dW partial buffer too small");
     int rc = launch<EPI_SPLIT>(a, L.kx, zsplits, st, "gemm_dw");
     if (rc) return rc;
     const int total = 2 * L.d_in * L.d_out;
     dn_prof_scope ps("dw_reduce", i, st);
-    hipLaunchKernelGGL(k_dw_reduce, dim3((total + TPB - 1) / TPB), dim3(TPB), 0, st, m->partial, a.split_stride, zsplits,
+    hipLaunchKernelGGL(k_dw_reduce, dim3((total + TPB - 1) / TPB), dim3(TPB), 0, st, L.partial, a.split_stride, zsplits,
                        L.xterms, L.d_in, L.d_out, dws, dwn);
     DN_LAUNCH_CHECK("k_dw_reduce");
     return DN_OK;
