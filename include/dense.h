@@ -158,9 +158,7 @@ DN_API int  sage_forward(dn_model* m, const dn_batch* b, const void* d_H0, float
  * (fp32 [dims[i]]) for every layer, and, when d_dH0 is not NULL, dL/dH^0 (fp32 [N x dims[0]],
  * capacity >= node capacity rows; needed for learnable base representations).  Uses the
  * activations saved by the last sage_forward on the same model and batch.  Neighbour-mean
- * gradients are summed per input row in ascending slot order (no floating-point atomics).
- * The weight-gradient kernels run on a second stream the model owns (forked from and joined back to
- * `stream` with events, so the call is still ordered on `stream` as a whole). */
+ * gradients are summed per input row in ascending slot order (no floating-point atomics). */
 DN_API int  sage_backward(dn_model* m, const dn_batch* b, const float* d_grad_out,
                    float* const* d_dw_self, float* const* d_dw_nbr, float* const* d_dbias,
                    float* d_dH0, void* stream);

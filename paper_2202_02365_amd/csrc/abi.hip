@@ -369,18 +369,6 @@ int dn_model_create(dn_model** out, const dn_batch* b, int32_t k, const int32_t*
     hipError_t e = hipMemsetAsync(d_workspace, 0, c.bytes(), static_cast<hipStream_t>(stream));
     if (e != hipSuccess) { delete m; return dn_fail(DN_EHIP, "hipMemsetAsync: %s", hipGetErrorString(e)); }
     m->fwd_serial = ~0ull;
-    // second stream for the weight-gradient chain (default priority); without it everything stays on the caller's stream
-    m->side = nullptr;
-    m->ev_fork = m->ev_join = nullptr;
-    for (int i = 0; i < DN_MAX_LAYERS; ++i) m->ev_dz[i] = nullptr;
-    bool ok = hipStreamCreateWithFlags(&m->side, hipStreamNonBlocking) == hipSuccess;
-    ok = ok && hipEventCreateWithFlags(&m->ev_fork, hipEventDisableTiming) == hipSuccess;
-    ok = ok && hipEventCreateWithFlags(&m->ev_join, hipEventDisableTiming) == hipSuccess;
-    for (int i = 0; ok && i < k; ++i) ok = hipEventCreateWithFlags(&m->ev_dz[i], hipEventDisableTiming) == hipSuccess;
-    if (!ok) {
-        (void)hipGetLastError();
-        if (m->side) { (void)hipStreamDestroy(m->side); m->side = nullptr; }
-    }
     *out = m;
     return DN_OK;
 }
@@ -396,15 +384,7 @@ int dn_model_set_weights(dn_model* m, const float* const* d_w_self, const float*
     return rc;
 }
 
-void dn_model_destroy(dn_model* m)
-{
-    if (!m) return;
-    if (m->side) (void)hipStreamDestroy(m->side);
-    if (m->ev_fork) (void)hipEventDestroy(m->ev_fork);
-    if (m->ev_join) (void)hipEventDestroy(m->ev_join);
-    for (int i = 0; i < DN_MAX_LAYERS; ++i) if (m->ev_dz[i]) (void)hipEventDestroy(m->ev_dz[i]);
-    delete m;
-}
+void dn_model_destroy(dn_model* m) { delete m; }
 
 int dn_model_status(const dn_model* m, int32_t* status, void* stream)
 {

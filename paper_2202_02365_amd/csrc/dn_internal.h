@@ -93,10 +93,7 @@ struct dn_model {
     dn_bf16* dzb;                  // bf16 terms of dZ, row-major (A operand of the dX GEMM)
     float *dx, *g[2];
     int32_t splits;
-    // weight gradients (X^T, dW GEMM, reductions) run on a second stream beside the chain that
-    // carries the gradient down the layers; host objects only, no device memory
-    hipStream_t side;
-    hipEvent_t ev_fork, ev_dz[DN_MAX_LAYERS], ev_join;
+
     // pre-activations too close to zero for the fp32 accumulation to settle their sign
     int32_t* fix_count;            // [0] exact recomputations in the last ReLU layer, [1] sticky overflow flag
     const void* h0;                // H^0 of the last forward
@@ -143,4 +140,5 @@ int dn_launch_backward(dn_model* m, dn_batch* b, const float* grad_out, float* c
 // GEMM entry points (gemm.hip), layer index i is 1-based
 int dn_gemm_forward(const dn_model* m, const dn_batch* b, int i, float* out, int64_t ldc, hipStream_t st);
 int dn_gemm_dx(const dn_model* m, const dn_batch* b, int i, hipStream_t st);
-int dn_gemm_dw(const dn_model* m, const dn_batch* b, int i, float* dws, float* dwn, hipStream_t st);
+int dn_gemm_dw_all(const dn_model* m, const dn_batch* b, float* const* dws, float* const* dwn, float* const* dbias,
+                   hipStream_t st);

@@ -6,6 +6,7 @@
 // reads input rows at (position - node_id_offsets[i-1]) and writes rows at
 // (position - node_id_offsets[i]); repr_map is kept relative to the full node_ids.
 #include "dn_internal.h"
+#include <algorithm>
 
 namespace {
 
@@ -138,40 +139,29 @@ __global__ __launch_bounds__(TPB) void k_dz(const int32_t* __restrict__ hdr, int
   }
 }
 
-// db[n] = sum over the row tiles of k_dz.  64 columns per workgroup; each of its 4 waves takes every
-// fourth tile (lanes = columns, coalesced), the four partial sums are combined in a fixed order.
-__global__ __launch_bounds__(TPB) void k_db_reduce(const int32_t* __restrict__ hdr, int layer,
-                                                   const float* __restrict__ db_partial, int d_out, float* __restrict__ db)
-{
-    __shared__ float part[4][64];
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    const int n = blockIdx.x * 64 + tx;
-    const int rows = hdr[HDR_N] - hdr[HDR_NODE_OFF + layer];
-    const int tiles = (rows + 63) / 64;
-    float s0 = 0.f, s1 = 0.f;
-    if (n < d_out) {
-        int t = ty;
-        for (; t + 4 < tiles; t += 8) {
-            s0 += db_partial[(int64_t)t * d_out + n];
-            s1 += db_partial[(int64_t)(t + 4) * d_out + n];
-        }
-        if (t < tiles) s0 += db_partial[(int64_t)t * d_out + n];
-    }
-    part[ty][tx] = s0 + s1;
-    __syncthreads();
-    if (ty == 0 && n < d_out) db[n] = (part[0][tx] + part[1][tx]) + (part[2][tx] + part[3][tx]);
-}
-
-// X [rows x kp] -> X^T [kp x rows_pad], zero for rows up to the next multiple of 64.
-__global__ __launch_bounds__(TPB) void k_transpose_x(const int32_t* __restrict__ hdr, int layer,
-                                                     const uint16_t* __restrict__ X, int kp, uint16_t* __restrict__ XT,
-                                                     int64_t rows_pad)
+// X [rows x kp] -> X^T [kp x rows_pad], zero for rows up to the next multiple of 64; all layers in one
+// launch: a 1-D grid, layer z owns workgroups [begin[z], begin[z+1]) = column tiles x row-tile slots.
+struct TransposeGroup {
+    const uint16_t* X[DN_MAX_LAYERS]; uint16_t* XT[DN_MAX_LAYERS];
+    int kp[DN_MAX_LAYERS]; int64_t rows_pad[DN_MAX_LAYERS];
+    int begin[DN_MAX_LAYERS + 1], row_slots[DN_MAX_LAYERS];
+    int n;
+};
+__global__ __launch_bounds__(TPB) void k_transpose_x_group(const int32_t* __restrict__ hdr, TransposeGroup T)
 {
     __shared__ uint16_t tile[64][66];
-    const int rows = hdr[HDR_N] - hdr[HDR_NODE_OFF + layer];
-    const int c0 = blockIdx.x * 64;
+    int z = 0;
+    while (z + 1 < T.n && (int)blockIdx.x >= T.begin[z + 1]) ++z;
+    const int local = (int)blockIdx.x - T.begin[z];
+    const int kp = T.kp[z];
+    const int c0 = (local / T.row_slots[z]) * 64;
+    const int rt0 = local % T.row_slots[z];
+    const uint16_t* __restrict__ X = T.X[z];
+    uint16_t* __restrict__ XT = T.XT[z];
+    const int64_t rows_pad = T.rows_pad[z];
+    const int rows = hdr[HDR_N] - hdr[HDR_NODE_OFF + z + 1];
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int rt = blockIdx.y; rt * 64 < rows; rt += gridDim.y) {
+    for (int rt = rt0; rt * 64 < rows; rt += T.row_slots[z]) {
         const int r0 = rt * 64;
         __syncthreads();
         for (int rr = ty; rr < 64; rr += 4) {
@@ -333,25 +323,9 @@ int dn_launch_backward(dn_model* m, dn_batch* b, const float* grad_out, float* c
     const int k = m->k;
     int rc = dn_launch_transpose_index(b, dh0 != nullptr, st);     // no-op when prepared for this sample
     if (rc) return rc;
-    // Two chains.  `st` carries the gradient down the layers: dZ^i -> dX^i -> transpose of the mean
-    // -> dZ^{i-1}.  `side` computes what nothing downstream waits for: X^T, the dW GEMM and the
-    // reductions of dW and db.  Fork and join with events; every layer has its own operands.
-    hipStream_t side = m->side ? m->side : st;
-    if (side != st) {
-        DN_HIP(hipEventRecord(m->ev_fork, st));
-        DN_HIP(hipStreamWaitEvent(side, m->ev_fork, 0));
-    }
-    for (int i = k; i >= 1; --i) {                                  // X^T needs only the forward pass
-        const dn_layer_bufs& L = m->layer[i - 1];
-        unsigned row_tiles = (unsigned)((L.rows_cap + 63) / 64);
-        if (row_tiles > 65535) row_tiles = 65535;
-        { dn_prof_scope ps("transpose_x", i, side);
-        hipLaunchKernelGGL(k_transpose_x, dim3((unsigned)(L.kp / 64), row_tiles ? row_tiles : 1), dim3(TPB), 0, side,
-                           b->hdr, i, reinterpret_cast<const uint16_t*>(L.x), L.kp, reinterpret_cast<uint16_t*>(L.xt),
-                           L.rows_pad);
-        }
-        DN_LAUNCH_CHECK("k_transpose_x");
-    }
+    // The chain that carries the gradient down the layers comes first: dZ^i -> dX^i -> transpose of
+    // the mean -> dZ^{i-1}.  What nothing downstream waits for (X^T, the dW GEMMs, the reductions of dW
+    // and db) follows in three launches that cover all layers; every layer has its own operands.
     const float* g = grad_out;
     for (int i = k; i >= 1; --i) {
         const dn_layer_bufs& L = m->layer[i - 1];
@@ -368,17 +342,6 @@ int dn_launch_backward(dn_model* m, dn_batch* b, const float* grad_out, float* c
                                reinterpret_cast<uint16_t*>(L.dzbt), L.rows_pad, L.dzbt_term_stride, L.db_partial);
         }
         DN_LAUNCH_CHECK("k_dz");
-        if (side != st) {
-            DN_HIP(hipEventRecord(m->ev_dz[i - 1], st));
-            DN_HIP(hipStreamWaitEvent(side, m->ev_dz[i - 1], 0));
-        }
-        { dn_prof_scope ps("db_reduce", i, side);
-        hipLaunchKernelGGL(k_db_reduce, dim3((L.d_out + 63) / 64), dim3(TPB), 0, side, b->hdr, i, L.db_partial,
-                           L.d_out, dbias[i - 1]);
-        }
-        DN_LAUNCH_CHECK("k_db_reduce");
-        rc = dn_gemm_dw(m, b, i, dws[i - 1], dwn[i - 1], side);
-        if (rc) return rc;
         if (i == 1 && dh0 == nullptr) break;            // nothing consumes the input gradient of layer 1
         rc = dn_gemm_dx(m, b, i, st);
         if (rc) return rc;
@@ -387,9 +350,24 @@ int dn_launch_backward(dn_model* m, dn_batch* b, const float* grad_out, float* c
         if (rc) return rc;
         g = gin;
     }
-    if (side != st) {
-        DN_HIP(hipEventRecord(m->ev_join, side));
-        DN_HIP(hipStreamWaitEvent(st, m->ev_join, 0));
+    TransposeGroup T{};
+    T.n = k;
+    int blocks = 0;
+    for (int i = 1; i <= k; ++i) {
+        const dn_layer_bufs& L = m->layer[i - 1];
+        T.X[i - 1] = reinterpret_cast<const uint16_t*>(L.x);
+        T.XT[i - 1] = reinterpret_cast<uint16_t*>(L.xt);
+        T.kp[i - 1] = L.kp;
+        T.rows_pad[i - 1] = L.rows_pad;
+        int64_t row_tiles = (L.rows_cap + 63) / 64;
+        T.row_slots[i - 1] = (int)(row_tiles < 1 ? 1 : (row_tiles > 4096 ? 4096 : row_tiles));
+        T.begin[i - 1] = blocks;
+        blocks += (L.kp / 64) * T.row_slots[i - 1];
     }
-    return DN_OK;
+    T.begin[k] = blocks;
+    { dn_prof_scope ps("transpose_x_all", 0, st);
+    hipLaunchKernelGGL(k_transpose_x_group, dim3((unsigned)blocks), dim3(TPB), 0, st, b->hdr, T);
+    }
+    DN_LAUNCH_CHECK("k_transpose_x_group");
+    return dn_gemm_dw_all(m, b, dws, dwn, dbias, st);
 }

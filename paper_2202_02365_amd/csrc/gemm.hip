@@ -23,6 +23,7 @@
 // so that the stored activation and the mask [Z > 0] used by the backward pass are those of the
 // exact sum.
 #include "dn_internal.h"
+#include <algorithm>
 
 namespace {
 
@@ -59,8 +60,9 @@ __device__ __forceinline__ int slot(int row, int c) { return row * 8 + (c ^ ((ro
 
 struct TileRegs { u32x4 a[4], b[4]; };
 
+// One 128 x 128 output tile (one reduction split for EPI_SPLIT): block coordinates (bx, by, bz of nz).
 template <int EPI>
-__global__ __launch_bounds__(TPB, 2) void k_gemm_nt(GemmArgs a)
+__device__ __forceinline__ void gemm_tile(const GemmArgs& a, const int bx, const int by, const int bz, const int nz)
 {
     __shared__ u32x4 As[2][BM * BK / 8];
     __shared__ u32x4 Bs[2][BN * BK / 8];
@@ -68,14 +70,14 @@ __global__ __launch_bounds__(TPB, 2) void k_gemm_nt(GemmArgs a)
     const int rows_layer = a.hdr[HDR_N] - a.hdr[HDR_NODE_OFF + a.layer];
     const int M = a.m_const >= 0 ? a.m_const : rows_layer;
     const int red = a.red_const >= 0 ? a.red_const : ((rows_layer + BK - 1) / BK) * BK;
-    const int row0 = blockIdx.y * BM, col0 = blockIdx.x * BN;
-    if (row0 >= M) return;
+    const int row0 = by * BM, col0 = bx * BN;
+    if (row0 >= M || col0 >= a.ncols) return;
 
     // reduction range of this split (dW: the splits of every term cover the whole range)
     const int chunks = red / BK;
-    const int groups = (EPI == EPI_SPLIT) ? (int)gridDim.z / a.terms : 1;
-    const int term = (EPI == EPI_SPLIT) ? (int)blockIdx.z / groups : 0;
-    const int grp = (EPI == EPI_SPLIT) ? (int)blockIdx.z % groups : 0;
+    const int groups = (EPI == EPI_SPLIT) ? nz / a.terms : 1;
+    const int term = (EPI == EPI_SPLIT) ? bz / groups : 0;
+    const int grp = (EPI == EPI_SPLIT) ? bz % groups : 0;
     const int per = (chunks + groups - 1) / groups;
     const int kc_begin = grp * per;
     const int kc_end = min(chunks, kc_begin + per);
@@ -157,7 +159,7 @@ __global__ __launch_bounds__(TPB, 2) void k_gemm_nt(GemmArgs a)
 
     // epilogue: lane holds column (lane & 31); register e holds row 8*(e/4) + 4*(lane/32) + e%4
     float* C = a.C;
-    if (EPI == EPI_SPLIT) C += (int64_t)blockIdx.z * a.split_stride;
+    if (EPI == EPI_SPLIT) C += (int64_t)bz * a.split_stride;
     __shared__ int s_fix_n;
     __shared__ long long local_fix[LOCAL_FIX_CAP];
     __shared__ float s_rownorm[BM];
@@ -233,13 +235,36 @@ __global__ __launch_bounds__(TPB, 2) void k_gemm_nt(GemmArgs a)
     }
 }
 
+template <int EPI>
+__global__ __launch_bounds__(TPB, 2) void k_gemm_nt(GemmArgs a)
+{
+    gemm_tile<EPI>(a, blockIdx.x, blockIdx.y, blockIdx.z, gridDim.z);
+}
+
+// The dW GEMMs of all layers in one launch: a 1-D grid, each layer owns the workgroups
+// [begin[i], begin[i+1]) = column tiles x row tiles x reduction splits of its own problem.
+struct GemmGroup {
+    GemmArgs g[DN_MAX_LAYERS];
+    int begin[DN_MAX_LAYERS + 1];
+    int gx[DN_MAX_LAYERS], gy[DN_MAX_LAYERS], gz[DN_MAX_LAYERS];
+    int n;
+};
+__global__ __launch_bounds__(TPB, 2) void k_gemm_dw_group(GemmGroup G)
+{
+    int gi = 0;
+    while (gi + 1 < G.n && (int)blockIdx.x >= G.begin[gi + 1]) ++gi;
+    const int local = (int)blockIdx.x - G.begin[gi];
+    const int bx = local % G.gx[gi], by = (local / G.gx[gi]) % G.gy[gi], bz = local / (G.gx[gi] * G.gy[gi]);
+    gemm_tile<EPI_SPLIT>(G.g[gi], bx, by, bz, G.gz[gi]);
+}
+
 // dW[kk][n] = sum over the X terms (rows kk + t*2d) and over the splits, in a fixed order;
 // rows kk < d go to dW_self, d <= kk < 2d to dW_nbr.
-__global__ __launch_bounds__(TPB) void k_dw_reduce(const float* __restrict__ partial, int64_t split_stride, int splits,
-                                                   int xterms, int d_in, int d_out, float* __restrict__ dws,
-                                                   float* __restrict__ dwn)
+__device__ __forceinline__ void dw_reduce_block(const int block, const float* __restrict__ partial, int64_t split_stride,
+                                                int splits, int xterms, int d_in, int d_out, float* __restrict__ dws,
+                                                float* __restrict__ dwn)
 {
-    const int idx = blockIdx.x * TPB + threadIdx.x;
+    const int idx = block * TPB + threadIdx.x;
     if (idx >= 2 * d_in * d_out) return;
     const int kk = idx / d_out, n = idx - kk * d_out;
     float s = 0.f;
@@ -258,6 +283,53 @@ __global__ __launch_bounds__(TPB) void k_dw_reduce(const float* __restrict__ par
     }
     if (kk < d_in) dws[(int64_t)kk * d_out + n] = s;
     else dwn[(int64_t)(kk - d_in) * d_out + n] = s;
+}
+
+// db[n] = sum over the row tiles of the dZ kernel.  64 columns per workgroup; each of its 4 waves takes
+// every fourth tile (lanes = columns, coalesced), the four partial sums are combined in a fixed order.
+__device__ __forceinline__ void db_reduce_block(const int block, int rows, const float* __restrict__ db_partial, int d_out,
+                                                float* __restrict__ db)
+{
+    __shared__ float part[4][64];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int n = block * 64 + tx;
+    const int tiles = (rows + 63) / 64;
+    float s0 = 0.f, s1 = 0.f;
+    if (n < d_out) {
+        int t = ty;
+        for (; t + 4 < tiles; t += 8) {
+            s0 += db_partial[(int64_t)t * d_out + n];
+            s1 += db_partial[(int64_t)(t + 4) * d_out + n];
+        }
+        if (t < tiles) s0 += db_partial[(int64_t)t * d_out + n];
+    }
+    part[ty][tx] = s0 + s1;
+    __syncthreads();
+    if (ty == 0 && n < d_out) db[n] = (part[0][tx] + part[1][tx]) + (part[2][tx] + part[3][tx]);
+}
+
+// All reductions of the backward pass in one launch: each layer owns workgroups [begin[y], begin[y+1]); the
+// first dw_blocks of them reduce the split-K partials of dW, the rest reduce the column sums for db.
+struct ReduceGroup {
+    const float* partial[DN_MAX_LAYERS]; int64_t split_stride[DN_MAX_LAYERS]; int splits[DN_MAX_LAYERS];
+    int xterms[DN_MAX_LAYERS], d_in[DN_MAX_LAYERS], d_out[DN_MAX_LAYERS], layer[DN_MAX_LAYERS];
+    float *dws[DN_MAX_LAYERS], *dwn[DN_MAX_LAYERS], *db[DN_MAX_LAYERS];
+    const float* db_partial[DN_MAX_LAYERS];
+    int dw_blocks[DN_MAX_LAYERS], db_blocks[DN_MAX_LAYERS];
+    int begin[DN_MAX_LAYERS + 1];
+    int n;
+};
+__global__ __launch_bounds__(TPB) void k_bwd_reduce_group(ReduceGroup R, const int32_t* __restrict__ hdr)
+{
+    int y = 0;
+    while (y + 1 < R.n && (int)blockIdx.x >= R.begin[y + 1]) ++y;
+    const int x = (int)blockIdx.x - R.begin[y];
+    if (x < R.dw_blocks[y]) {
+        dw_reduce_block(x, R.partial[y], R.split_stride[y], R.splits[y], R.xterms[y], R.d_in[y], R.d_out[y], R.dws[y], R.dwn[y]);
+    } else if (x < R.dw_blocks[y] + R.db_blocks[y]) {
+        const int rows = hdr[HDR_N] - hdr[HDR_NODE_OFF + R.layer[y]];
+        db_reduce_block(x - R.dw_blocks[y], rows, R.db_partial[y], R.d_out[y], R.db[y]);
+    }
 }
 
 // fp32 weights -> the two zero-padded bf16 layouts (round to nearest even).
@@ -342,34 +414,58 @@ int dn_gemm_dx(const dn_model* m, const dn_batch* b, int i, hipStream_t st)
     return launch<EPI_PLAIN>(a, L.rows_cap, 1, st, "gemm_dx");
 }
 
-// dWcat = X^T * bf16(dZ), reduction over the layer's rows split `splits` ways, then reduced in order.
-int dn_gemm_dw(const dn_model* m, const dn_batch* b, int i, float* dws, float* dwn, hipStream_t st)
+// dWcat^i = X^i^T * bf16(dZ^i) for every layer in one launch (reduction over the layer's rows split several
+// ways), then one launch that reduces the partials in a fixed order and finishes db.
+int dn_gemm_dw_all(const dn_model* m, const dn_batch* b, float* const* dws, float* const* dwn, float* const* dbias,
+                   hipStream_t st)
 {
-    const dn_layer_bufs& L = m->layer[i - 1];
-    int64_t chunks_cap = (L.rows_cap + BK - 1) / BK;
-    // enough workgroups to fill the chip, no more: every split costs a partial tile to write and re-read
-    const int tiles = ((L.kx + BM - 1) / BM) * ((L.d_out + BN - 1) / BN) * L.zterms;
-    int splits = (512 + tiles - 1) / tiles;
-    if (splits > m->splits) splits = m->splits;
-    if (splits > chunks_cap) splits = (int)(chunks_cap > 0 ? chunks_cap : 1);
-    if (splits < 1) splits = 1;
-    GemmArgs a{};
-    a.A = reinterpret_cast<const uint16_t*>(L.xt); a.lda = L.rows_pad;
-    a.B = reinterpret_cast<const uint16_t*>(L.dzbt); a.ldb = L.rows_pad;
-    a.C = L.partial; a.ldc = L.d_out;
-    a.hdr = b->hdr; a.layer = i; a.m_const = L.kx; a.ncols = L.d_out; a.red_const = -1;
-    a.bias = nullptr; a.relu = 0; a.split_stride = (int64_t)L.kx * L.d_out;
-    a.terms = L.zterms; a.b_term_stride = L.dzbt_term_stride;
-    const int zsplits = splits * L.zterms;
-    if ((int64_t)zsplits * a.split_stride > L.partial_floats)
-        return dn_fail(DN_ECAPACITY, "dW partial buffer too small");
-    int rc = launch<EPI_SPLIT>(a, L.kx, zsplits, st, "gemm_dw");
-    if (rc) return rc;
-    const int total = 2 * L.d_in * L.d_out;
-    dn_prof_scope ps("dw_reduce", i, st);
-    hipLaunchKernelGGL(k_dw_reduce, dim3((total + TPB - 1) / TPB), dim3(TPB), 0, st, L.partial, a.split_stride, zsplits,
-                       L.xterms, L.d_in, L.d_out, dws, dwn);
-    DN_LAUNCH_CHECK("k_dw_reduce");
+    GemmGroup G{};
+    ReduceGroup R{};
+    G.n = m->k;
+    R.n = m->k;
+    int blocks = 0, red_blocks = 0;
+    for (int i = 1; i <= m->k; ++i) {
+        const dn_layer_bufs& L = m->layer[i - 1];
+        int64_t chunks_cap = (L.rows_cap + BK - 1) / BK;
+        // enough workgroups to fill the chip, no more: every split costs a partial tile to write and re-read
+        const int tiles = ((L.kx + BM - 1) / BM) * ((L.d_out + BN - 1) / BN) * L.zterms;
+        int splits = (512 + tiles - 1) / tiles;
+        if (splits > m->splits) splits = m->splits;
+        if (splits > chunks_cap) splits = (int)(chunks_cap > 0 ? chunks_cap : 1);
+        if (splits < 1) splits = 1;
+        GemmArgs& a = G.g[i - 1];
+        a.A = reinterpret_cast<const uint16_t*>(L.xt); a.lda = L.rows_pad;
+        a.B = reinterpret_cast<const uint16_t*>(L.dzbt); a.ldb = L.rows_pad;
+        a.C = L.partial; a.ldc = L.d_out;
+        a.hdr = b->hdr; a.layer = i; a.m_const = L.kx; a.ncols = L.d_out; a.red_const = -1;
+        a.bias = nullptr; a.relu = 0; a.split_stride = (int64_t)L.kx * L.d_out;
+        a.terms = L.zterms; a.b_term_stride = L.dzbt_term_stride;
+        const int zsplits = splits * L.zterms;
+        if ((int64_t)zsplits * a.split_stride > L.partial_floats) return dn_fail(DN_ECAPACITY, "dW partial buffer too small");
+        const int y = i - 1;
+        G.gx[y] = (L.d_out + BN - 1) / BN;
+        G.gy[y] = (L.kx + BM - 1) / BM;
+        G.gz[y] = zsplits;
+        G.begin[y] = blocks;
+        blocks += G.gx[y] * G.gy[y] * G.gz[y];
+        R.partial[y] = L.partial; R.split_stride[y] = a.split_stride; R.splits[y] = zsplits; R.xterms[y] = L.xterms;
+        R.d_in[y] = L.d_in; R.d_out[y] = L.d_out; R.layer[y] = i;
+        R.dws[y] = dws[y]; R.dwn[y] = dwn[y]; R.db[y] = dbias[y]; R.db_partial[y] = L.db_partial;
+        R.dw_blocks[y] = (2 * L.d_in * L.d_out + TPB - 1) / TPB;
+        R.db_blocks[y] = (L.d_out + 63) / 64;
+        R.begin[y] = red_blocks;
+        red_blocks += R.dw_blocks[y] + R.db_blocks[y];
+    }
+    G.begin[m->k] = blocks;
+    R.begin[m->k] = red_blocks;
+    { dn_prof_scope ps("gemm_dw_all", 0, st);
+    hipLaunchKernelGGL(k_gemm_dw_group, dim3((unsigned)blocks), dim3(TPB), 0, st, G);
+    }
+    DN_LAUNCH_CHECK("k_gemm_dw_group");
+    { dn_prof_scope ps("bwd_reduce_all", 0, st);
+    hipLaunchKernelGGL(k_bwd_reduce_group, dim3((unsigned)red_blocks), dim3(TPB), 0, st, R, b->hdr);
+    }
+    DN_LAUNCH_CHECK("k_bwd_reduce_group");
     return DN_OK;
 }
 
