@@ -52,18 +52,33 @@ def algorithmic_work(tag, sizes, cfg, dims):
         rows = N - off[:, i]
         terms = 1 if i == 1 else 2
         return "mfma", float(np.mean(2 * rows * (2 * dims[i - 1] * terms) * dims[i]))
-    if tag.startswith("gemm_dw_L"):
-        i = int(tag.split("_L")[1])
-        rows = N - off[:, i]
-        xt = 1 if i == 1 else 2
-        zt = 1 if i == k else 2
-        return "mfma", float(np.mean(2 * rows * (2 * dims[i - 1] * xt) * dims[i] * zt))
+    if tag == "gemm_dw_all":               # the dW GEMMs of all layers share one launch
+        total = 0.0
+        for i in range(1, k + 1):
+            rows = N - off[:, i]
+            xt = 1 if i == 1 else 2
+            zt = 1 if i == k else 2
+            total = total + 2 * rows * (2 * dims[i - 1] * xt) * dims[i] * zt
+        return "mfma", float(np.mean(total))
     if tag.startswith("gemm_dx_L"):
         i = int(tag.split("_L")[1])
         rows = N - off[:, i]
         zt = 1 if i == k else 2
         return "mfma", float(np.mean(2 * rows * (2 * dims[i - 1]) * dims[i] * zt))
     return "hbm", None
+
+
+def measured_traffic(workload, tag):
+    """HBM bytes per launch of kernel `tag` from the committed rocprofv3 counter summary (FETCH_SIZE +
+    WRITE_SIZE, each scaled by a plain copy of known size), or None if there is none for this workload."""
+    path = os.path.join(ROOT, "profiles", "%s_hbm_traffic.txt" % workload)
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = line.split()
+        if len(parts) >= 2 and parts[0] == tag:
+            return float(parts[1])
+    return None
 
 
 def cpu_baseline(cfg, inputs, sizes, budget_s=20.0):
@@ -116,6 +131,8 @@ def main():
     ap.add_argument("--workload", default="rmat111m")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-times", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy a few times (reference for hardware byte counters)")
     ap.add_argument("--no-graphs", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -289,11 +306,24 @@ def main():
     # per-kernel durations: the same K steps again, every launch bracketed by HIP events on its stream
     roofline, kernels = None, {}
     if not args.no_kernel_times:
+        # The event pairs time what the GPU does only if the host is ahead of it: every step is preceded by
+        # a ~1 ms streaming copy (not bracketed) during which the host queues the whole step.
+        delay_src = torch.empty(256 << 20, dtype=torch.float32, device=dev)
+        delay_dst = torch.empty_like(delay_src)
         dn.profile_enable(True)
-        timed(args.steps)
+        torch.cuda.synchronize()
+        for s in range(args.steps):
+            dn.profile_calibration_copy(delay_dst, delay_src)
+            dn.profile_empty_bracket()
+            step(s % N_BATCHES)
         prof = dn.profile_collect()
         dn.profile_enable(False)
-        kernels = {tag: {"avg_us": 1e3 * ms / n, "launches_per_step": n / args.steps} for tag, (ms, n) in prof.items()}
+        del delay_src, delay_dst
+        # an event pair around nothing already reads a few microseconds: subtract that from every bracket
+        empty_ms, empty_n = prof.pop("empty_bracket", (0.0, 1))
+        bracket_us = 1e3 * empty_ms / max(empty_n, 1)
+        kernels = {tag: {"avg_us": max(1e3 * ms / n - bracket_us, 0.0), "launches_per_step": n / args.steps}
+                   for tag, (ms, n) in prof.items()}
         step_sum_us = sum(v["avg_us"] * v["launches_per_step"] for v in kernels.values())
         used = [sizes[s % N_BATCHES] for s in range(args.steps)]
         best = None
@@ -311,8 +341,16 @@ def main():
             else:
                 achieved, peak, unit = work / (avg_us * 1e-6) / 1e12, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s"
             roofline = {"kernel": tag, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
-                        "frac": achieved / peak, "traffic": None, "avg_us": avg_us,
-                        "algorithmic_per_launch": work, "kernel_time_share_of_step": best[0] / step_sum_us}
+                        "frac": achieved / peak, "traffic": measured_traffic(cfg.name, tag), "avg_us": avg_us,
+                        "algorithmic_per_launch": work, "kernel_time_share_of_step": best[0] / step_sum_us,
+                        "event_bracket_overhead_us_subtracted": bracket_us}
+
+    if args.copy_calibration:
+        src = torch.empty(64 << 20, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dn.profile_calibration_copy(dst, src)          # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
 
     baseline = None
     if not args.no_cpu_baseline:

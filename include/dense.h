@@ -174,6 +174,12 @@ typedef struct dn_kernel_time {
     int64_t launches;
 } dn_kernel_time;
 DN_API int  dn_profile_enable(int32_t enable);
+/* A plain device-to-device streaming copy (kernel k_calibration_copy) of `bytes` bytes (multiple of 16,
+ * 16-byte aligned pointers): the known-size reference that hardware byte counters are scaled by. */
+DN_API int  dn_profile_calibration_copy(void* d_dst, const void* d_src, size_t bytes, void* stream);
+/* Records an event pair with nothing in between under the tag "empty_bracket": what a bracket costs by
+ * itself, to be subtracted from the per-kernel averages. */
+DN_API int  dn_profile_empty_bracket(void* stream);
 DN_API int  dn_profile_collect(dn_kernel_time* out, int32_t max_entries, int32_t* n_entries);
 
 #ifdef __cplusplus

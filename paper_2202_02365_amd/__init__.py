@@ -6,8 +6,9 @@ and streams.  There is no CPU fallback: if the library is missing, loading raise
 """
 from .binding import (DN_F32, DN_BF16, DN_DIR_OUT, DN_DIR_IN, DN_DIR_BOTH, DenseError, Graph, Batch, Model,
                       dense_sample, dense_gather, sage_forward, sage_backward, library_path, load_library,
-                      declared_symbols, profile_enable, profile_collect)
+                      declared_symbols, profile_enable, profile_collect,
+                      profile_calibration_copy, profile_empty_bracket)
 
 __all__ = ["DN_F32", "DN_BF16", "DN_DIR_OUT", "DN_DIR_IN", "DN_DIR_BOTH", "DenseError", "Graph", "Batch", "Model",
            "dense_sample", "dense_gather", "sage_forward", "sage_backward", "library_path", "load_library",
-           "declared_symbols", "profile_enable", "profile_collect"]
+           "declared_symbols", "profile_enable", "profile_collect", "profile_calibration_copy", "profile_empty_bracket"]

@@ -70,6 +70,8 @@ def load_library():
         "dn_model_destroy": (None, [vp]),
         "dn_model_status": (ctypes.c_int, [vp, ctypes.POINTER(i32), vp]),
         "dn_profile_enable": (ctypes.c_int, [i32]),
+        "dn_profile_calibration_copy": (ctypes.c_int, [vp, vp, sz, vp]),
+        "dn_profile_empty_bracket": (ctypes.c_int, [vp]),
         "dn_profile_collect": (ctypes.c_int, [ctypes.POINTER(_KernelTime), i32, ctypes.POINTER(i32)]),
         "sage_forward": (ctypes.c_int, [vp, vp, vp, vp, vp]),
         "sage_backward": (ctypes.c_int, [vp, vp, vp, pp, pp, pp, vp, vp]),
@@ -229,6 +231,18 @@ class Model:
 def profile_enable(on: bool) -> None:
     """Bracket every kernel launch of the library with HIP events (benchmark use)."""
     _check(load_library().dn_profile_enable(1 if on else 0))
+
+
+def profile_calibration_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
+    """Plain streaming copy of src into dst with the library's reference copy kernel."""
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    _check(load_library().dn_profile_calibration_copy(_dev_ptr(dst), _dev_ptr(src), nbytes, _stream()))
+
+
+def profile_empty_bracket() -> None:
+    """One event pair around nothing (tag "empty_bracket"): the cost of a bracket itself."""
+    _check(load_library().dn_profile_empty_bracket(_stream()))
 
 
 def profile_collect():

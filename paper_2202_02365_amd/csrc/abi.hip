@@ -425,6 +425,19 @@ int sage_backward(dn_model* m, const dn_batch* b, const float* d_grad_out, float
                               static_cast<hipStream_t>(stream));
 }
 
+int dn_profile_calibration_copy(void* d_dst, const void* d_src, size_t bytes, void* stream)
+{
+    if (!d_dst || !d_src || ((uintptr_t)d_dst & 15) || ((uintptr_t)d_src & 15) || (bytes & 15))
+        return dn_fail(DN_EINVAL, "calibration copy needs 16-byte aligned pointers and size");
+    return dn_launch_calibration_copy(d_dst, d_src, bytes, static_cast<hipStream_t>(stream));
+}
+
+int dn_profile_empty_bracket(void* stream)
+{
+    dn_prof_scope ps("empty_bracket", 0, static_cast<hipStream_t>(stream));
+    return DN_OK;
+}
+
 int dn_profile_enable(int32_t enable)
 {
     std::lock_guard<std::mutex> lock(g_prof_mutex);

@@ -130,6 +130,7 @@ int dn_launch_sample(dn_batch* b, const dn_graph* g, const int32_t* d_targets, i
                      uint64_t seed, hipStream_t st);
 int dn_launch_gather(const dn_batch* b, const void* table, int32_t dtype, int32_t dim, int64_t ld,
                      void* h0, hipStream_t st);
+int dn_launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 int dn_launch_transpose_index(dn_batch* b, int need_all, hipStream_t st);
 int dn_launch_set_weights(dn_model* m, const float* const* ws, const float* const* wn,
                           const float* const* bias, hipStream_t st);

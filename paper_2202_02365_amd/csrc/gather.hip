@@ -42,7 +42,26 @@ __global__ __launch_bounds__(TPB) void k_gather_elem(const int32_t* __restrict__
     }
 }
 
+// Plain streaming copy of known size: the reference a profiler's byte counters are scaled by.
+__global__ __launch_bounds__(TPB) void k_calibration_copy(const u32x4* __restrict__ src, u32x4* __restrict__ dst, int64_t n16)
+{
+    const int64_t stride = (int64_t)gridDim.x * TPB;
+    for (int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
 }  // namespace
+
+int dn_launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t st)
+{
+    const int64_t n16 = (int64_t)(bytes / 16);
+    int64_t grid = (n16 + TPB - 1) / TPB;
+    if (grid > 16384) grid = 16384;
+    if (grid < 1) grid = 1;
+    hipLaunchKernelGGL(k_calibration_copy, dim3((int)grid), dim3(TPB), 0, st, static_cast<const u32x4*>(src),
+                       static_cast<u32x4*>(dst), n16);
+    DN_LAUNCH_CHECK("k_calibration_copy");
+    return DN_OK;
+}
 
 int dn_launch_gather(const dn_batch* b, const void* table, int32_t dtype, int32_t dim, int64_t ld,
                      void* h0, hipStream_t st)

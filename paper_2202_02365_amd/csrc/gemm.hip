@@ -235,7 +235,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const int bx, const
     }
 }
 
-template <int EPI>
+// LAYER_TAG only gives every layer's launch its own kernel symbol, so that a profiler's per-kernel
+// statistics do not mix the layers (tag 4 stands for "layer 4 and above").
+template <int EPI, int LAYER_TAG>
 __global__ __launch_bounds__(TPB, 2) void k_gemm_nt(GemmArgs a)
 {
     gemm_tile<EPI>(a, blockIdx.x, blockIdx.y, blockIdx.z, gridDim.z);
@@ -375,7 +377,12 @@ int launch(const GemmArgs& a, int64_t m_cap, int splits, hipStream_t st, const c
     dn_prof_scope ps(tag, a.layer, st);
     dim3 grid((unsigned)((a.ncols + BN - 1) / BN), (unsigned)((m_cap + BM - 1) / BM), (unsigned)splits);
     if (grid.y == 0) grid.y = 1;
-    hipLaunchKernelGGL((k_gemm_nt<EPI>), grid, dim3(TPB), 0, st, a);
+    switch (a.layer) {
+        case 1: hipLaunchKernelGGL((k_gemm_nt<EPI, 1>), grid, dim3(TPB), 0, st, a); break;
+        case 2: hipLaunchKernelGGL((k_gemm_nt<EPI, 2>), grid, dim3(TPB), 0, st, a); break;
+        case 3: hipLaunchKernelGGL((k_gemm_nt<EPI, 3>), grid, dim3(TPB), 0, st, a); break;
+        default: hipLaunchKernelGGL((k_gemm_nt<EPI, 4>), grid, dim3(TPB), 0, st, a); break;
+    }
     DN_LAUNCH_CHECK("k_gemm_nt");
     return DN_OK;
 }
