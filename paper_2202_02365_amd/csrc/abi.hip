@@ -69,6 +69,9 @@ void carve_batch(dn_batch* b, Carver& c)
     b->seen = c.take<uint32_t>(b->words0);
     b->fresh = c.take<uint32_t>(b->words0);
     b->summary = c.take<uint32_t>(b->words1);
+    b->tr_hist_words = dn_transpose_index_hist_words(b);
+    b->tr_hist = c.take<int32_t>(b->tr_hist_words);          // starts at zero like the bitmaps
+    b->tr_hist_next = 0;
     b->lvlpos = c.take<int32_t>(b->V);
     b->lvl_ids = c.take<int32_t>(b->cap_nodes);
     b->lvl_nbr_offsets = c.take<int32_t>(b->cap_nodes + 1);
@@ -86,9 +89,6 @@ void carve_batch(dn_batch* b, Carver& c)
         b->tr_val[i] = c.take<int32_t>(b->cap_slots);
     }
     b->tr_ptr = c.take<int32_t>(b->cap_nodes + 2);
-    const int64_t tiles = (b->cap_slots + 2047) / 2048;
-    b->tr_hist_words = 256 * tiles + (256 * tiles + 2047) / 2048 + 16;
-    b->tr_hist = c.take<int32_t>(b->tr_hist_words);
 }
 
 int fill_model(dn_model* m, const dn_batch* b, int32_t k, const int32_t* dims, int32_t in_dtype)
@@ -260,7 +260,7 @@ int dn_batch_create(dn_batch** out, int64_t num_nodes, int32_t max_targets, int3
     }
     b->workspace_bytes = c.bytes();
     hipStream_t st = static_cast<hipStream_t>(stream);
-    // header and the three bitmaps are contiguous at the front: they must start at zero
+    // header, the three bitmaps and the sort histograms are contiguous at the front: they must start at zero
     const size_t zero_bytes = (size_t)(reinterpret_cast<char*>(b->lvlpos) - reinterpret_cast<char*>(b->hdr));
     hipError_t e = hipMemsetAsync(b->hdr, 0, zero_bytes, st);
     if (e != hipSuccess) { delete b; return dn_fail(DN_EHIP, "hipMemsetAsync: %s", hipGetErrorString(e)); }

@@ -52,6 +52,7 @@ struct dn_batch {
     // transpose index for the backward pass (slots grouped by the input row they read)
     int32_t *tr_key[2], *tr_val[2], *tr_ptr, *tr_hist;
     int64_t tr_hist_words;
+    int32_t tr_hist_next;                   // which of the three rotating histograms is known to be zero
     int32_t n_targets;
     uint64_t sample_serial;                 // bumped by every dense_sample
     uint64_t tr_serial;                     // sample the transpose index was built for
@@ -132,6 +133,7 @@ int dn_launch_gather(const dn_batch* b, const void* table, int32_t dtype, int32_
                      void* h0, hipStream_t st);
 int dn_launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 int dn_launch_transpose_index(dn_batch* b, int need_all, hipStream_t st);
+int64_t dn_transpose_index_hist_words(const dn_batch* b);
 int dn_launch_set_weights(dn_model* m, const float* const* ws, const float* const* wn,
                           const float* const* bias, hipStream_t st);
 int dn_launch_forward(dn_model* m, const dn_batch* b, const void* h0, float* out, hipStream_t st);

@@ -60,6 +60,13 @@ __device__ __forceinline__ int slot(int row, int c) { return row * 8 + (c ^ ((ro
 
 struct TileRegs { u32x4 a[4], b[4]; };
 
+constexpr int MIN_CHUNKS = 8;
+__device__ __forceinline__ int effective_splits(int groups, int chunks)
+{
+    const int want = chunks / MIN_CHUNKS;
+    return want < 1 ? 1 : (want < groups ? want : groups);
+}
+
 // One 128 x 128 output tile (one reduction split for EPI_SPLIT): block coordinates (bx, by, bz of nz).
 template <int EPI>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const int bx, const int by, const int bz, const int nz)
@@ -78,7 +85,11 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const int bx, const
     const int groups = (EPI == EPI_SPLIT) ? nz / a.terms : 1;
     const int term = (EPI == EPI_SPLIT) ? bz / groups : 0;
     const int grp = (EPI == EPI_SPLIT) ? bz % groups : 0;
-    const int per = (chunks + groups - 1) / groups;
+    // dW: the grid has `groups` splits by capacity; only as many are used as leave at least MIN_CHUNKS k-steps
+    // per split for the rows that exist (the others leave at once and the reduction skips them)
+    const int eff_groups = (EPI == EPI_SPLIT) ? effective_splits(groups, chunks) : 1;
+    if (grp >= eff_groups) return;
+    const int per = (chunks + eff_groups - 1) / eff_groups;
     const int kc_begin = grp * per;
     const int kc_end = min(chunks, kc_begin + per);
     const uint16_t* Bbase = a.B + (int64_t)term * a.b_term_stride;
@@ -263,26 +274,28 @@ __global__ __launch_bounds__(TPB, 2) void k_gemm_dw_group(GemmGroup G)
 // dW[kk][n] = sum over the X terms (rows kk + t*2d) and over the splits, in a fixed order;
 // rows kk < d go to dW_self, d <= kk < 2d to dW_nbr.
 __device__ __forceinline__ void dw_reduce_block(const int block, const float* __restrict__ partial, int64_t split_stride,
-                                                int splits, int xterms, int d_in, int d_out, float* __restrict__ dws,
-                                                float* __restrict__ dwn)
+                                                int groups, int zterms, int rows, int xterms, int d_in, int d_out,
+                                                float* __restrict__ dws, float* __restrict__ dwn)
 {
     const int idx = block * TPB + threadIdx.x;
     if (idx >= 2 * d_in * d_out) return;
     const int kk = idx / d_out, n = idx - kk * d_out;
+    const int eff = effective_splits(groups, (rows + BK - 1) / BK);   // the splits the GEMM actually wrote
     float s = 0.f;
-    for (int t = 0; t < xterms; ++t) {
-        const float* src = partial + (int64_t)(kk + t * 2 * d_in) * d_out + n;
-        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;       // four chains: loads overlap, order stays fixed
-        int z = 0;
-        for (; z + 4 <= splits; z += 4) {
-            s0 += src[(int64_t)(z + 0) * split_stride];
-            s1 += src[(int64_t)(z + 1) * split_stride];
-            s2 += src[(int64_t)(z + 2) * split_stride];
-            s3 += src[(int64_t)(z + 3) * split_stride];
+    for (int t = 0; t < xterms; ++t)
+        for (int zt = 0; zt < zterms; ++zt) {
+            const float* src = partial + (int64_t)zt * groups * split_stride + (int64_t)(kk + t * 2 * d_in) * d_out + n;
+            float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;   // four chains: loads overlap, order stays fixed
+            int z = 0;
+            for (; z + 4 <= eff; z += 4) {
+                s0 += src[(int64_t)(z + 0) * split_stride];
+                s1 += src[(int64_t)(z + 1) * split_stride];
+                s2 += src[(int64_t)(z + 2) * split_stride];
+                s3 += src[(int64_t)(z + 3) * split_stride];
+            }
+            for (; z < eff; ++z) s0 += src[(int64_t)z * split_stride];
+            s += (s0 + s1) + (s2 + s3);
         }
-        for (; z < splits; ++z) s0 += src[(int64_t)z * split_stride];
-        s += (s0 + s1) + (s2 + s3);
-    }
     if (kk < d_in) dws[(int64_t)kk * d_out + n] = s;
     else dwn[(int64_t)(kk - d_in) * d_out + n] = s;
 }
@@ -313,7 +326,7 @@ __device__ __forceinline__ void db_reduce_block(const int block, int rows, const
 // All reductions of the backward pass in one launch: each layer owns workgroups [begin[y], begin[y+1]); the
 // first dw_blocks of them reduce the split-K partials of dW, the rest reduce the column sums for db.
 struct ReduceGroup {
-    const float* partial[DN_MAX_LAYERS]; int64_t split_stride[DN_MAX_LAYERS]; int splits[DN_MAX_LAYERS];
+    const float* partial[DN_MAX_LAYERS]; int64_t split_stride[DN_MAX_LAYERS]; int groups[DN_MAX_LAYERS], zterms[DN_MAX_LAYERS];
     int xterms[DN_MAX_LAYERS], d_in[DN_MAX_LAYERS], d_out[DN_MAX_LAYERS], layer[DN_MAX_LAYERS];
     float *dws[DN_MAX_LAYERS], *dwn[DN_MAX_LAYERS], *db[DN_MAX_LAYERS];
     const float* db_partial[DN_MAX_LAYERS];
@@ -326,10 +339,11 @@ __global__ __launch_bounds__(TPB) void k_bwd_reduce_group(ReduceGroup R, const i
     int y = 0;
     while (y + 1 < R.n && (int)blockIdx.x >= R.begin[y + 1]) ++y;
     const int x = (int)blockIdx.x - R.begin[y];
+    const int rows = hdr[HDR_N] - hdr[HDR_NODE_OFF + R.layer[y]];
     if (x < R.dw_blocks[y]) {
-        dw_reduce_block(x, R.partial[y], R.split_stride[y], R.splits[y], R.xterms[y], R.d_in[y], R.d_out[y], R.dws[y], R.dwn[y]);
+        dw_reduce_block(x, R.partial[y], R.split_stride[y], R.groups[y], R.zterms[y], rows, R.xterms[y], R.d_in[y], R.d_out[y],
+                        R.dws[y], R.dwn[y]);
     } else if (x < R.dw_blocks[y] + R.db_blocks[y]) {
-        const int rows = hdr[HDR_N] - hdr[HDR_NODE_OFF + R.layer[y]];
         db_reduce_block(x - R.dw_blocks[y], rows, R.db_partial[y], R.d_out[y], R.db[y]);
     }
 }
@@ -455,7 +469,8 @@ int dn_gemm_dw_all(const dn_model* m, const dn_batch* b, float* const* dws, floa
         G.gz[y] = zsplits;
         G.begin[y] = blocks;
         blocks += G.gx[y] * G.gy[y] * G.gz[y];
-        R.partial[y] = L.partial; R.split_stride[y] = a.split_stride; R.splits[y] = zsplits; R.xterms[y] = L.xterms;
+        R.partial[y] = L.partial; R.split_stride[y] = a.split_stride; R.groups[y] = splits; R.zterms[y] = L.zterms;
+        R.xterms[y] = L.xterms;
         R.d_in[y] = L.d_in; R.d_out[y] = L.d_out; R.layer[y] = i;
         R.dws[y] = dws[y]; R.dwn[y] = dwn[y]; R.db[y] = dbias[y]; R.db_partial[y] = L.db_partial;
         R.dw_blocks[y] = (2 * L.d_in * L.d_out + TPB - 1) / TPB;

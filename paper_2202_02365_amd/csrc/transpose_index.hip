@@ -1,9 +1,15 @@
 // Transpose index of repr_map for the backward pass: neighbour slots grouped by the node_ids
 // position they read, ascending slot number inside a group, so that the gradient of the
 // neighbour mean is a gather with a fixed summation order (no floating-point atomics).
-// Built by a stable least-significant-digit radix sort of (repr_map[j], j) pairs, 8 bits per
-// pass; group boundaries by binary search.  The number of pairs lives in device memory; grids
-// are sized by capacity.
+// Built by a stable least-significant-digit radix sort of (repr_map[j], j) pairs with up to
+// 11 bits per pass (two passes for up to 4M positions); group boundaries by binary search.
+// The number of pairs lives in device memory; grids are sized by capacity.
+//
+// Launches: k_tr_init (copy + histogram of the first digit), then per pass two scan kernels and
+// one scatter that also histograms the next digit at the element's new position, then k_tr_ptr.
+// Histograms are integer atomics (order-independent).  Three histogram buffers rotate: the scan
+// of a pass clears the buffer the next accumulation goes into, and the buffer the last scan
+// cleared is the one the next build starts with.
 #include "dn_internal.h"
 
 namespace {
@@ -11,10 +17,12 @@ namespace {
 constexpr int TPB = 256;
 constexpr int ITEMS = 8;                   // elements per thread
 constexpr int TILE = TPB * ITEMS;          // elements per workgroup
-constexpr int RADIX = 256;
+constexpr int MAX_BITS = 11;
+constexpr int MAX_RADIX = 1 << MAX_BITS;
 
 __global__ void k_tr_init(int32_t* __restrict__ hdr, int need_all, int k, const int32_t* __restrict__ nbr_offsets,
-                          const int32_t* __restrict__ repr_map, int32_t* __restrict__ key, int32_t* __restrict__ val)
+                          const int32_t* __restrict__ repr_map, int32_t* __restrict__ key, int32_t* __restrict__ val,
+                          int radix_mask, int nblocks, int32_t* __restrict__ hist)
 {
     const int E = hdr[HDR_E];
     int first = 0;
@@ -25,30 +33,15 @@ __global__ void k_tr_init(int32_t* __restrict__ hdr, int need_all, int k, const 
     const int cnt = E - first;
     const int stride = gridDim.x * blockDim.x;
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < cnt; i += stride) {
-        key[i] = repr_map[first + i];
+        const int kv = repr_map[first + i];
+        key[i] = kv;
         val[i] = first + i;
+        atomicAdd(&hist[(kv & radix_mask) * nblocks + i / TILE], 1);
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         hdr[HDR_TR_FIRST] = first;
         hdr[HDR_TR_COUNT] = cnt;
     }
-}
-
-// digit histogram of each tile, stored digit-major: hist[d * nblocks + block]
-__global__ __launch_bounds__(TPB) void k_radix_hist(const int32_t* __restrict__ hdr, const int32_t* __restrict__ key,
-                                                    int shift, int nblocks, int32_t* __restrict__ hist)
-{
-    __shared__ int lh[RADIX];
-    const int n = hdr[HDR_TR_COUNT];
-    lh[threadIdx.x] = 0;
-    __syncthreads();
-    const int base = blockIdx.x * TILE;
-    for (int it = 0; it < ITEMS; ++it) {
-        const int idx = base + it * TPB + threadIdx.x;
-        if (idx < n) atomicAdd(&lh[(key[idx] >> shift) & (RADIX - 1)], 1);
-    }
-    __syncthreads();
-    hist[threadIdx.x * nblocks + blockIdx.x] = lh[threadIdx.x];
 }
 
 // two-kernel exclusive scan of `total` ints in place (block partial sums, then look-behind)
@@ -64,7 +57,9 @@ __global__ __launch_bounds__(TPB) void k_scan_partial(const int32_t* __restrict_
     if (threadIdx.x == 0) part[blockIdx.x] = sm[0] + sm[1] + sm[2] + sm[3];
 }
 
-__global__ __launch_bounds__(TPB) void k_scan_apply(int32_t* __restrict__ data, int total, const int32_t* __restrict__ part)
+// second half of the scan; also zeroes `clear` (same extent), the buffer of the next accumulation
+__global__ __launch_bounds__(TPB) void k_scan_apply(int32_t* __restrict__ data, int total, const int32_t* __restrict__ part,
+                                                    int32_t* __restrict__ clear)
 {
     __shared__ int sm[TPB / 64];
     __shared__ int s_before;
@@ -91,37 +86,44 @@ __global__ __launch_bounds__(TPB) void k_scan_apply(int32_t* __restrict__ data, 
     for (int w = 0; w < wave; ++w) wbase += sm[w];
     int run = before + wbase + incl - s;
     for (int e = 0; e < ITEMS; ++e) {
-        if (base + e < total) data[base + e] = run;
+        if (base + e < total) { data[base + e] = run; clear[base + e] = 0; }
         run += v[e];
     }
 }
 
 // stable scatter: element order inside a tile is (wave, round, lane); a lane's rank among equal
-// digits of its round comes from 8 ballots, rounds and waves are chained through counters in LDS.
+// digits of its round comes from one ballot per digit bit, rounds and waves are chained through
+// counters in LDS.  Also counts the next pass's digit at the element's new position.
 __global__ __launch_bounds__(TPB) void k_radix_scatter(const int32_t* __restrict__ hdr, const int32_t* __restrict__ key_in,
-                                                       const int32_t* __restrict__ val_in, int shift, int nblocks,
+                                                       const int32_t* __restrict__ val_in, int shift, int bits, int nblocks,
                                                        const int32_t* __restrict__ hist, int32_t* __restrict__ key_out,
-                                                       int32_t* __restrict__ val_out)
+                                                       int32_t* __restrict__ val_out, int next_bits,
+                                                       int32_t* __restrict__ next_hist)
 {
-    __shared__ int cnt[TPB / 64][RADIX];
+    __shared__ int cnt[TPB / 64][MAX_RADIX];
+    const int radix = 1 << bits;
     const int n = hdr[HDR_TR_COUNT];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (blockIdx.x * TILE >= n) return;
-    for (int w = 0; w < TPB / 64; ++w) cnt[w][threadIdx.x] = 0;
+    for (int w = 0; w < TPB / 64; ++w)
+        for (int d = threadIdx.x; d < radix; d += TPB) cnt[w][d] = 0;
     __syncthreads();
     const int wbase = blockIdx.x * TILE + wave * (TILE / (TPB / 64));
     int keys[ITEMS], vals[ITEMS];
     uint64_t peers[ITEMS];
 #pragma unroll
+    for (int r = 0; r < ITEMS; ++r) {              // all loads first: one memory latency, not one per round
+        const int idx = wbase + r * 64 + lane;
+        keys[r] = idx < n ? key_in[idx] : 0;
+        vals[r] = idx < n ? val_in[idx] : 0;
+    }
+#pragma unroll
     for (int r = 0; r < ITEMS; ++r) {
         const int idx = wbase + r * 64 + lane;
         const bool ok = idx < n;
-        keys[r] = ok ? key_in[idx] : 0;
-        vals[r] = ok ? val_in[idx] : 0;
-        const int d = (keys[r] >> shift) & (RADIX - 1);
+        const int d = (keys[r] >> shift) & (radix - 1);
         uint64_t mask = __ballot(ok);
-#pragma unroll
-        for (int bit = 0; bit < 8; ++bit) {
+        for (int bit = 0; bit < bits; ++bit) {
             const uint64_t bal = __ballot((d >> bit) & 1);
             mask &= ((d >> bit) & 1) ? bal : ~bal;
         }
@@ -129,11 +131,12 @@ __global__ __launch_bounds__(TPB) void k_radix_scatter(const int32_t* __restrict
         if (ok && (mask & ((1ull << lane) - 1ull)) == 0) cnt[wave][d] += __popcll(mask);   // lowest lane of each digit
         __syncthreads();                       // the next round's leader may be another lane
     }
-    {   // thread t owns digit t: turn per-wave counts into per-wave start positions
-        int g = hist[threadIdx.x * nblocks + blockIdx.x];
+    // thread t owns digits t, t+TPB, ...: turn per-wave counts into per-wave start positions
+    for (int d = threadIdx.x; d < radix; d += TPB) {
+        int g = hist[d * nblocks + blockIdx.x];
         for (int w = 0; w < TPB / 64; ++w) {
-            const int c = cnt[w][threadIdx.x];
-            cnt[w][threadIdx.x] = g;
+            const int c = cnt[w][d];
+            cnt[w][d] = g;
             g += c;
         }
     }
@@ -142,12 +145,15 @@ __global__ __launch_bounds__(TPB) void k_radix_scatter(const int32_t* __restrict
     for (int r = 0; r < ITEMS; ++r) {
         const uint64_t mask = peers[r];
         if (mask) {
-            const int d = (keys[r] >> shift) & (RADIX - 1);
+            const int d = (keys[r] >> shift) & (radix - 1);
             const int start = cnt[wave][d];
             __builtin_amdgcn_wave_barrier();   // all lanes have read the counter before its owner advances it
             const int rank = __popcll(mask & ((1ull << lane) - 1ull));
-            key_out[start + rank] = keys[r];
-            val_out[start + rank] = vals[r];
+            const int pos = start + rank;
+            key_out[pos] = keys[r];
+            val_out[pos] = vals[r];
+            if (next_bits > 0)
+                atomicAdd(&next_hist[((keys[r] >> (shift + bits)) & ((1 << next_bits) - 1)) * nblocks + pos / TILE], 1);
             if (rank == 0) cnt[wave][d] = start + __popcll(mask);
         }
         __syncthreads();                       // counters are read by every lane of the next round
@@ -170,45 +176,62 @@ __global__ __launch_bounds__(TPB) void k_tr_ptr(const int32_t* __restrict__ hdr,
     }
 }
 
+void sort_plan(const dn_batch* b, int* passes, int* bits, int* nblocks)
+{
+    int key_bits = 1;
+    while (((int64_t)1 << key_bits) < b->cap_nodes) ++key_bits;
+    *passes = (key_bits + MAX_BITS - 1) / MAX_BITS;
+    *bits = (key_bits + *passes - 1) / *passes;            // bits per pass, <= MAX_BITS
+    const int64_t nb = (b->cap_slots + TILE - 1) / TILE;   // always planned for every slot, so the extent is fixed
+    *nblocks = (int)(nb > 0 ? nb : 1);
+}
+
 }  // namespace
+
+// ints of histogram space (three rotating histograms + scan partials); they must start at zero
+int64_t dn_transpose_index_hist_words(const dn_batch* b)
+{
+    int passes, bits, nblocks;
+    sort_plan(b, &passes, &bits, &nblocks);
+    const int64_t total = ((int64_t)1 << bits) * nblocks;
+    return 3 * total + (total + TILE - 1) / TILE + 64;
+}
 
 int dn_launch_transpose_index(dn_batch* b, int need_all, hipStream_t st)
 {
     if (b->tr_serial == b->sample_serial && (b->tr_covers_all || !need_all)) return DN_OK;
-    int64_t cap = b->cap_slots;
-    if (!need_all) cap -= b->cap_slots_hop[b->k - 1];      // the last hop's slots belong to layer 1 only
-    int bits = 1;
-    while (((int64_t)1 << bits) < b->cap_nodes) ++bits;
-    const int passes = (bits + 7) / 8;
+    int passes, bits, nblocks;
+    sort_plan(b, &passes, &bits, &nblocks);
+    const int radix = 1 << bits;
+    const int total = radix * nblocks;
+    const int sblocks = (total + TILE - 1) / TILE;
+    if (3 * (int64_t)total + sblocks > b->tr_hist_words) return dn_fail(DN_ECAPACITY, "transpose index: histogram space");
+    int32_t* hist[3] = { b->tr_hist, b->tr_hist + total, b->tr_hist + 2 * (int64_t)total };
+    int32_t* part = b->tr_hist + 3 * (int64_t)total;
     int src = passes & 1;                                   // so that the last pass lands in buffer 0
-    int64_t g = (cap + TPB - 1) / TPB;
+    int h = b->tr_hist_next;                                // the buffer that is known to be zero
+    dn_prof_scope ps("transpose_index", 0, st);             // the whole sort counts as one step
+    int64_t g = (b->cap_slots + TPB - 1) / TPB;
     if (g > 2048) g = 2048;
     if (g < 1) g = 1;
-    dn_prof_scope ps("transpose_index", 0, st);       // the whole sort counts as one step
     hipLaunchKernelGGL(k_tr_init, dim3((int)g), dim3(TPB), 0, st, b->hdr, need_all, b->k, b->nbr_offsets, b->repr_map,
-                       b->tr_key[src], b->tr_val[src]);
+                       b->tr_key[src], b->tr_val[src], radix - 1, nblocks, hist[h]);
     DN_LAUNCH_CHECK("k_tr_init");
-    if (cap > 0) {
-        const int nblocks = (int)((cap + TILE - 1) / TILE);
-        const int total = RADIX * nblocks;
-        const int sblocks = (total + TILE - 1) / TILE;
-        if ((int64_t)total + sblocks > b->tr_hist_words) return dn_fail(DN_ECAPACITY, "transpose index: histogram space");
-        int32_t* part = b->tr_hist + total;
-        for (int p = 0; p < passes; ++p) {
-            const int shift = 8 * p;
-            hipLaunchKernelGGL(k_radix_hist, dim3(nblocks), dim3(TPB), 0, st, b->hdr, b->tr_key[src], shift, nblocks,
-                               b->tr_hist);
-            DN_LAUNCH_CHECK("k_radix_hist");
-            hipLaunchKernelGGL(k_scan_partial, dim3(sblocks), dim3(TPB), 0, st, b->tr_hist, total, part);
-            DN_LAUNCH_CHECK("k_scan_partial");
-            hipLaunchKernelGGL(k_scan_apply, dim3(sblocks), dim3(TPB), 0, st, b->tr_hist, total, part);
-            DN_LAUNCH_CHECK("k_scan_apply");
-            hipLaunchKernelGGL(k_radix_scatter, dim3(nblocks), dim3(TPB), 0, st, b->hdr, b->tr_key[src], b->tr_val[src],
-                               shift, nblocks, b->tr_hist, b->tr_key[src ^ 1], b->tr_val[src ^ 1]);
-            DN_LAUNCH_CHECK("k_radix_scatter");
-            src ^= 1;
-        }
+    for (int p = 0; p < passes; ++p) {
+        const int shift = bits * p;
+        const int hn = (h + 1) % 3;
+        hipLaunchKernelGGL(k_scan_partial, dim3(sblocks), dim3(TPB), 0, st, hist[h], total, part);
+        DN_LAUNCH_CHECK("k_scan_partial");
+        hipLaunchKernelGGL(k_scan_apply, dim3(sblocks), dim3(TPB), 0, st, hist[h], total, part, hist[hn]);
+        DN_LAUNCH_CHECK("k_scan_apply");
+        const int next_bits = (p + 1 < passes) ? bits : 0;
+        hipLaunchKernelGGL(k_radix_scatter, dim3(nblocks), dim3(TPB), 0, st, b->hdr, b->tr_key[src], b->tr_val[src],
+                           shift, bits, nblocks, hist[h], b->tr_key[src ^ 1], b->tr_val[src ^ 1], next_bits, hist[hn]);
+        DN_LAUNCH_CHECK("k_radix_scatter");
+        src ^= 1;
+        h = hn;
     }
+    b->tr_hist_next = h;                                    // cleared by the last scan, untouched since
     int64_t gp = (b->cap_nodes + 1 + TPB - 1) / TPB;
     if (gp > 2048) gp = 2048;
     hipLaunchKernelGGL(k_tr_ptr, dim3((int)gp), dim3(TPB), 0, st, b->hdr, b->tr_key[0], b->tr_ptr);
