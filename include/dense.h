@@ -106,6 +106,24 @@ DN_API int  dn_batch_capacity(const dn_batch* b, int64_t* node_capacity, int64_t
 DN_API int  dense_sample(dn_batch* b, const dn_graph* g, const int32_t* d_targets, int32_t n_targets,
                   uint64_t seed, void* stream);
 
+/* ---- dense_sample_edges: the link-prediction front end (Section 2: a training example is a pair of target
+ *      nodes; Section 7.1: neighbours over incoming and outgoing edges).  The targets are the distinct ids
+ *      among d_src[0..n_edges), d_dst[0..n_edges) and d_neg[0..n_neg), in ASCENDING id (they form Delta_k);
+ *      sampling then proceeds exactly as dense_sample.  d_*_local (int32, same lengths as the inputs) receive,
+ *      for every endpoint and negative, its index in that target list = the row of sage_forward's output.
+ *      Requires 2 * n_edges + n_neg <= max_targets of the batch.  Out-of-range ids are reported by
+ *      dn_batch_counts as DN_ESAMPLE. */
+DN_API int  dense_sample_edges(dn_batch* b, const dn_graph* g, const int32_t* d_src, const int32_t* d_dst, int32_t n_edges,
+                               const int32_t* d_neg, int32_t n_neg, uint64_t seed,
+                               int32_t* d_src_local, int32_t* d_dst_local, int32_t* d_neg_local, void* stream);
+
+/* ---- dn_embedding_sgd: update of learnable base representations (Section 2: "updates for learned base
+ *      representations" applied to the lookup table): d_table[node_ids[r], :] -= lr * d_dH0[r, :] for r < N, fp32,
+ *      multiply and subtract rounded separately.  node_ids holds every node once, so no two rows collide.
+ *      The paper does not name the optimiser; plain SGD is the reading taken here. */
+DN_API int  dn_embedding_sgd(const dn_batch* b, float* d_table, int32_t dim, int64_t ld_elems, const float* d_dH0,
+                             float lr, void* stream);
+
 /* Optional: builds, on `stream`, the index sage_backward needs for the transpose of the neighbour mean
  * (neighbour slots grouped by the row of H they read; with need_input_grad = 0 only the slots of layers
  * 2..k).  sage_backward builds it itself when this was not called for the current sample; calling it

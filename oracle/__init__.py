@@ -167,6 +167,27 @@ def dense_sample(g: Graph, targets, fanouts, seed: int, direction: int = 0) -> D
                  nbrs[:e].copy(), repr_map[:e].copy())
 
 
+def dense_sample_edges(g: Graph, src, dst, neg, fanouts, seed: int, direction: int = 0):
+    """Link-prediction front end (Section 2: a training example is a pair of target nodes; Algorithm 1
+    takes "unique node IDs"): the targets are the distinct ids among the edge endpoints and the negative
+    nodes, in ascending id (a reading: the paper does not order them); returns the DENSE sample of those
+    targets and, for src / dst / neg, the index of each id in the target list."""
+    src, dst, neg = _i32(src), _i32(dst), _i32(neg)
+    targets = np.unique(np.concatenate([src, dst, neg]))              # sorted, distinct
+    d = dense_sample(g, targets, fanouts, seed, direction)
+    return d, np.searchsorted(targets, src), np.searchsorted(targets, dst), np.searchsorted(targets, neg)
+
+
+def embedding_sgd(table: np.ndarray, node_ids: np.ndarray, d_h0: np.ndarray, lr: float) -> np.ndarray:
+    """Learnable base representations (Section 2: their updates are applied to the lookup table):
+    table[node_ids[r]] -= lr * d_h0[r] in fp32, product and difference rounded separately.  Plain SGD is
+    a reading; the paper does not name the optimiser.  Returns the updated copy."""
+    out = np.array(table, dtype=np.float32, copy=True)
+    step = np.float32(lr) * np.asarray(d_h0, dtype=np.float32)
+    out[node_ids] = out[node_ids] - step
+    return out
+
+
 def dense_gather(table: np.ndarray, node_ids: np.ndarray) -> np.ndarray:
     """H^0[r] = table[node_ids[r]] (Section 4.2), any fixed-size row dtype."""
     assert table.ndim == 2 and table.flags.c_contiguous
@@ -182,5 +203,6 @@ from .sage import (round_bf16, dense_layer_view, sage_forward, sage_backward, Sa
                    ForwardState)
 
 __all__ = ["build", "philox4x32_10", "floyd_positions", "Graph", "Dense", "onehop", "dense_sample",
+           "dense_sample_edges", "embedding_sgd",
            "dense_gather", "round_bf16", "dense_layer_view", "sage_forward", "sage_backward",
            "SageParams", "ForwardState"]

@@ -60,6 +60,8 @@ def load_library():
         "dn_batch_destroy": (None, [vp]),
         "dn_batch_capacity": (ctypes.c_int, [vp, ctypes.POINTER(i64), ctypes.POINTER(i64)]),
         "dense_sample": (ctypes.c_int, [vp, vp, vp, i32, u64, vp]),
+        "dense_sample_edges": (ctypes.c_int, [vp, vp, vp, vp, i32, vp, i32, u64, vp, vp, vp, vp]),
+        "dn_embedding_sgd": (ctypes.c_int, [vp, vp, i32, i64, vp, ctypes.c_float, vp]),
         "dn_batch_view": (ctypes.c_int, [vp, ctypes.POINTER(_View)]),
         "dn_batch_prepare_backward": (ctypes.c_int, [vp, i32, vp]),
         "dn_batch_counts": (ctypes.c_int, [vp, ctypes.POINTER(i64), vp]),
@@ -259,6 +261,28 @@ def dense_sample(batch: Batch, graph: Graph, targets: torch.Tensor, seed: int) -
     batch._targets = targets
     _check(load_library().dense_sample(batch.handle, graph.handle, _dev_ptr(targets, torch.int32) if n else None,
                                        n, seed & 0xFFFFFFFFFFFFFFFF, _stream()))
+
+
+def dense_sample_edges(batch: Batch, graph: Graph, src: torch.Tensor, dst: torch.Tensor, neg: torch.Tensor, seed: int):
+    """Targets = ascending distinct ids of src, dst, neg; returns their indices in the target list."""
+    ne, nn = src.numel(), neg.numel()
+    assert dst.numel() == ne
+    batch._targets = (src, dst, neg)
+    out = [torch.empty_like(src), torch.empty_like(dst), torch.empty_like(neg)]
+    _check(load_library().dense_sample_edges(batch.handle, graph.handle,
+                                             _dev_ptr(src, torch.int32) if ne else None,
+                                             _dev_ptr(dst, torch.int32) if ne else None, ne,
+                                             _dev_ptr(neg, torch.int32) if nn else None, nn, seed & 0xFFFFFFFFFFFFFFFF,
+                                             _dev_ptr(out[0]) if ne else None, _dev_ptr(out[1]) if ne else None,
+                                             _dev_ptr(out[2]) if nn else None, _stream()))
+    return out
+
+
+def embedding_sgd(batch: Batch, table: torch.Tensor, d_h0: torch.Tensor, lr: float) -> None:
+    """table[node_ids[r]] -= lr * d_h0[r] for the batch's N nodes (fp32 table, rows may be strided)."""
+    assert table.dtype == torch.float32 and table.stride(1) == 1 and d_h0.shape[1] == table.shape[1]
+    _check(load_library().dn_embedding_sgd(batch.handle, table.data_ptr(), table.shape[1], table.stride(0),
+                                           _dev_ptr(d_h0, torch.float32), lr, _stream()))
 
 
 def dense_gather(batch: Batch, table: torch.Tensor, out: torch.Tensor) -> torch.Tensor:

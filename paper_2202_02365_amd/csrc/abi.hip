@@ -294,6 +294,34 @@ int dense_sample(dn_batch* b, const dn_graph* g, const int32_t* d_targets, int32
     return dn_launch_sample(b, g, d_targets, n_targets, seed, static_cast<hipStream_t>(stream));
 }
 
+int dense_sample_edges(dn_batch* b, const dn_graph* g, const int32_t* d_src, const int32_t* d_dst, int32_t n_edges,
+                       const int32_t* d_neg, int32_t n_neg, uint64_t seed, int32_t* d_src_local, int32_t* d_dst_local,
+                       int32_t* d_neg_local, void* stream)
+{
+    if (!b || !g) return dn_fail(DN_EINVAL, "batch or graph is null");
+    if (g->V != b->V) return dn_fail(DN_EINVAL, "graph has %lld nodes, the batch was created for %lld", (long long)g->V, (long long)b->V);
+    if (n_edges < 0 || n_neg < 0) return dn_fail(DN_EINVAL, "negative count");
+    if ((n_edges > 0 && (!d_src || !d_dst || !d_src_local || !d_dst_local)) || (n_neg > 0 && (!d_neg || !d_neg_local)))
+        return dn_fail(DN_EINVAL, "null id or output array");
+    const int64_t bound = 2 * (int64_t)n_edges + n_neg;
+    if (bound > b->max_targets)
+        return dn_fail(DN_ECAPACITY, "2 * n_edges + n_neg = %lld exceeds the batch's %d targets", (long long)bound, b->max_targets);
+    if (b->direction != DN_DIR_IN && !g->rowptr[0]) return dn_fail(DN_EINVAL, "the graph has no out-edge adjacency");
+    if (b->direction != DN_DIR_OUT && !g->rowptr[1]) return dn_fail(DN_EINVAL, "the graph has no in-edge adjacency");
+    b->n_targets = (int32_t)bound;
+    b->sample_serial += 1;
+    return dn_launch_sample_edges(b, g, d_src, d_dst, n_edges, d_neg, n_neg, seed, d_src_local, d_dst_local, d_neg_local,
+                                  static_cast<hipStream_t>(stream));
+}
+
+int dn_embedding_sgd(const dn_batch* b, float* d_table, int32_t dim, int64_t ld_elems, const float* d_dH0, float lr, void* stream)
+{
+    if (!b || !d_table || !d_dH0) return dn_fail(DN_EINVAL, "null argument");
+    if (dim < 1 || ld_elems < dim) return dn_fail(DN_EINVAL, "dim = %d, ld_elems = %lld", dim, (long long)ld_elems);
+    if (b->sample_serial == 0) return dn_fail(DN_ESTATE, "dense_sample has not run on this batch");
+    return dn_launch_embedding_sgd(b, d_table, dim, ld_elems, d_dH0, lr, static_cast<hipStream_t>(stream));
+}
+
 int dn_batch_prepare_backward(dn_batch* b, int32_t need_input_grad, void* stream)
 {
     if (!b) return dn_fail(DN_EINVAL, "batch is null");

@@ -129,6 +129,11 @@ static inline int64_t dn_round_up(int64_t x, int64_t m) { return (x + m - 1) / m
 // launchers (one per step of the hot path)
 int dn_launch_sample(dn_batch* b, const dn_graph* g, const int32_t* d_targets, int32_t n_targets,
                      uint64_t seed, hipStream_t st);
+int dn_launch_sample_edges(dn_batch* b, const dn_graph* g, const int32_t* d_src, const int32_t* d_dst, int32_t n_edges,
+                           const int32_t* d_neg, int32_t n_neg, uint64_t seed, int32_t* d_src_local,
+                           int32_t* d_dst_local, int32_t* d_neg_local, hipStream_t st);
+int dn_launch_embedding_sgd(const dn_batch* b, float* table, int32_t dim, int64_t ld, const float* dh0, float lr,
+                            hipStream_t st);
 int dn_launch_gather(const dn_batch* b, const void* table, int32_t dtype, int32_t dim, int64_t ld,
                      void* h0, hipStream_t st);
 int dn_launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t st);

@@ -42,6 +42,26 @@ __global__ __launch_bounds__(TPB) void k_gather_elem(const int32_t* __restrict__
     }
 }
 
+// table[node_ids[r], :] -= lr * g[r, :] for r < N.  node_ids holds every node once, so rows never collide.
+// Multiply and subtract are rounded separately (no fused multiply-add), as the plain formula is.
+__global__ __launch_bounds__(TPB) void k_embedding_sgd(const int32_t* __restrict__ hdr, const int32_t* __restrict__ node_ids,
+                                                       float* __restrict__ table, int64_t ld, int dim,
+                                                       const float* __restrict__ g, float lr)
+{
+#pragma clang fp contract(off)             // lr * g is rounded before the subtraction: no fused multiply-add
+    const int N = hdr[HDR_N];
+    const int lane = threadIdx.x & 63;
+    constexpr int ROWS_PER_BLOCK = TPB / 64;
+    for (int r = blockIdx.x * ROWS_PER_BLOCK + (threadIdx.x >> 6); r < N; r += gridDim.x * ROWS_PER_BLOCK) {
+        float* row = table + (int64_t)node_ids[r] * ld;
+        const float* gr = g + (int64_t)r * dim;
+        for (int c = lane; c < dim; c += 64) {
+            const float step = lr * gr[c];
+            row[c] = row[c] - step;
+        }
+    }
+}
+
 // Plain streaming copy of known size: the reference a profiler's byte counters are scaled by.
 __global__ __launch_bounds__(TPB) void k_calibration_copy(const u32x4* __restrict__ src, u32x4* __restrict__ dst, int64_t n16)
 {
@@ -50,6 +70,18 @@ __global__ __launch_bounds__(TPB) void k_calibration_copy(const u32x4* __restric
 }
 
 }  // namespace
+
+int dn_launch_embedding_sgd(const dn_batch* b, float* table, int32_t dim, int64_t ld, const float* dh0, float lr,
+                            hipStream_t st)
+{
+    int64_t grid = (b->cap_nodes + 3) / 4;
+    if (grid > 4096) grid = 4096;
+    if (grid < 1) grid = 1;
+    dn_prof_scope ps("embedding_sgd", 0, st);
+    hipLaunchKernelGGL(k_embedding_sgd, dim3((int)grid), dim3(TPB), 0, st, b->hdr, b->node_ids, table, ld, dim, dh0, lr);
+    DN_LAUNCH_CHECK("k_embedding_sgd");
+    return DN_OK;
+}
 
 int dn_launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t st)
 {

@@ -152,6 +152,45 @@ __global__ __launch_bounds__(TPB) void k_init_offsets(int n, int32_t* __restrict
     }
 }
 
+// ---------------------------------------------------------------- level 0 from training edges
+// Link prediction (Section 2: a training example is a pair of target nodes): the targets are the
+// distinct endpoints of the batch's edges plus the negative nodes.  Their ids are marked in the
+// `fresh` bitmap; the ordered walk that builds every other level then yields them in ascending id.
+__global__ __launch_bounds__(TPB) void k_mark_ids(int64_t V, const int32_t* __restrict__ a, int na,
+                                                  const int32_t* __restrict__ b, int nb, const int32_t* __restrict__ c, int nc,
+                                                  int32_t* __restrict__ hdr, uint32_t* __restrict__ fresh,
+                                                  uint32_t* __restrict__ summary)
+{
+    const int total = na + nb + nc;
+    const int stride = gridDim.x * TPB;
+    for (int i = blockIdx.x * TPB + threadIdx.x; i < total; i += stride) {
+        const int u = i < na ? a[i] : (i < na + nb ? b[i - na] : c[i - na - nb]);
+        if (u < 0 || (int64_t)u >= V) { atomicOr(&hdr[HDR_STATUS_ACC], ST_BAD_TARGET); continue; }
+        const uint32_t w = (uint32_t)u >> 5, bit = 1u << (u & 31);
+        if (!(__hip_atomic_load(&fresh[w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & bit)) {
+            const uint32_t old_word = atomicOr(&fresh[w], bit);
+            if (old_word == 0) atomicOr(&summary[w >> 5], 1u << (w & 31));
+        }
+    }
+}
+
+// position of every endpoint / negative in the target list (= row of the encoder's output)
+__global__ __launch_bounds__(TPB) void k_local_ids(int64_t V, const int32_t* __restrict__ a, int na,
+                                                   const int32_t* __restrict__ b, int nb, const int32_t* __restrict__ c, int nc,
+                                                   const int32_t* __restrict__ lvlpos, int32_t* __restrict__ la,
+                                                   int32_t* __restrict__ lb, int32_t* __restrict__ lc)
+{
+    const int total = na + nb + nc;
+    const int stride = gridDim.x * TPB;
+    for (int i = blockIdx.x * TPB + threadIdx.x; i < total; i += stride) {
+        const int u = i < na ? a[i] : (i < na + nb ? b[i - na] : c[i - na - nb]);
+        const int pos = (u < 0 || (int64_t)u >= V) ? 0 : lvlpos[u];
+        if (i < na) la[i] = pos;
+        else if (i < na + nb) lb[i - na] = pos;
+        else lc[i - na - nb] = pos;
+    }
+}
+
 // ---------------------------------------------------------------- one-hop sample of a level
 // G lanes cooperate on one node (G = power of two >= fanout).  Lane s owns Floyd step s: it draws
 // t_s in [0, deg-f+s]; the picks are then settled in step order with a G-wide ballot, which is the
@@ -253,7 +292,8 @@ __global__ __launch_bounds__(TPB) void k_fresh_emit(GraphDev g, int64_t words1, 
                                                     int32_t* __restrict__ hdr, uint32_t* __restrict__ fresh,
                                                     uint32_t* __restrict__ summary, const uint64_t* __restrict__ blk,
                                                     int32_t* __restrict__ lvlpos, int32_t* __restrict__ lvl_ids,
-                                                    int32_t* __restrict__ lvl_nbr_offsets, int64_t cap_nodes)
+                                                    int32_t* __restrict__ lvl_nbr_offsets, int64_t cap_nodes,
+                                                    uint32_t* __restrict__ seen_or_null)
 {
     __shared__ uint64_t sm[TPB / 64];
     const uint64_t before = block_sum_prefix(blk, blockIdx.x, sm);
@@ -292,6 +332,7 @@ __global__ __launch_bounds__(TPB) void k_fresh_emit(GraphDev g, int64_t words1, 
         const int64_t w = i * 32 + b;
         uint32_t fw = fresh[w];
         fresh[w] = 0;
+        if (seen_or_null) seen_or_null[w] = fw;          // level 0 from an id set: these nodes are the targets
         while (fw) {
             const int bit = __ffs(fw) - 1;
             fw &= fw - 1;
@@ -317,6 +358,7 @@ __global__ __launch_bounds__(TPB) void k_fresh_emit(GraphDev g, int64_t words1, 
         }
         hdr[HDR_LVL_OFF + next_level + 1] = node_base + n_new;
         if (f_next > 0) hdr[HDR_LVL_NBR_OFF + next_level + 1] = slot_base + (int)(uint32_t)(all >> 32);
+        if (seen_or_null) hdr[HDR_NTARGETS] = n_new;
     }
 }
 
@@ -385,15 +427,53 @@ void launch_sample_g(int grid, hipStream_t st, GraphDev gd, int hop, int f, int 
 
 }  // namespace
 
+static int launch_hops_and_assemble(dn_batch* b, const GraphDev& gd, int64_t level0_bound, uint64_t seed, hipStream_t st);
+
+int dn_launch_sample_edges(dn_batch* b, const dn_graph* g, const int32_t* d_src, const int32_t* d_dst, int32_t n_edges,
+                           const int32_t* d_neg, int32_t n_neg, uint64_t seed, int32_t* d_src_local,
+                           int32_t* d_dst_local, int32_t* d_neg_local, hipStream_t st)
+{
+    GraphDev gd;
+    gd.rp[0] = g->rowptr[0]; gd.rp[1] = g->rowptr[1];
+    gd.col[0] = g->col[0];   gd.col[1] = g->col[1];
+    const int dir = b->direction;
+    uint64_t* blk = reinterpret_cast<uint64_t*>(b->blk_a);
+    const int total = 2 * n_edges + n_neg;
+    int grid = (total + TPB - 1) / TPB;
+    if (grid > 2048) grid = 2048;
+    if (grid < 1) grid = 1;
+    { dn_prof_scope ps("mark_ids", 0, st);
+    hipLaunchKernelGGL(k_mark_ids, dim3(grid), dim3(TPB), 0, st, b->V, d_src, n_edges, d_dst, n_edges, d_neg, n_neg, b->hdr,
+                       b->fresh, b->summary);
+    }
+    DN_LAUNCH_CHECK("k_mark_ids");
+    const int grid_words = (int)((b->words1 + TPB - 1) / TPB);
+    { dn_prof_scope ps("fresh_count_hop", 0, st);
+    hipLaunchKernelGGL(k_fresh_count, dim3(grid_words), dim3(TPB), 0, st, gd, b->words1, b->fanouts[0], dir, b->fresh,
+                       b->summary, blk);
+    }
+    DN_LAUNCH_CHECK("k_fresh_count");
+    { dn_prof_scope ps("fresh_emit_hop", 0, st);
+    hipLaunchKernelGGL(k_fresh_emit, dim3(grid_words), dim3(TPB), 0, st, gd, b->words1, 0, b->fanouts[0], dir, b->hdr,
+                       b->fresh, b->summary, blk, b->lvlpos, b->lvl_ids, b->lvl_nbr_offsets, b->cap_nodes, b->seen);
+    }
+    DN_LAUNCH_CHECK("k_fresh_emit");
+    { dn_prof_scope ps("local_ids", 0, st);
+    hipLaunchKernelGGL(k_local_ids, dim3(grid), dim3(TPB), 0, st, b->V, d_src, n_edges, d_dst, n_edges, d_neg, n_neg,
+                       b->lvlpos, d_src_local, d_dst_local, d_neg_local);
+    }
+    DN_LAUNCH_CHECK("k_local_ids");
+    return launch_hops_and_assemble(b, gd, total, seed, st);
+}
+
 int dn_launch_sample(dn_batch* b, const dn_graph* g, const int32_t* d_targets, int32_t n_targets,
                      uint64_t seed, hipStream_t st)
 {
     GraphDev gd;
     gd.rp[0] = g->rowptr[0]; gd.rp[1] = g->rowptr[1];
     gd.col[0] = g->col[0];   gd.col[1] = g->col[1];
-    const int k = b->k, dir = b->direction;
+    const int dir = b->direction;
     uint64_t* blk = reinterpret_cast<uint64_t*>(b->blk_a);
-    const uint32_t key0 = (uint32_t)(seed & 0xffffffffu), key1 = (uint32_t)(seed >> 32);
 
     const int grid0 = n_targets > 0 ? (n_targets + TPB - 1) / TPB : 1;
     if (grid0 > b->max_blocks) return dn_fail(DN_ECAPACITY, "dense_sample: %d targets exceed the batch capacity", n_targets);
@@ -406,9 +486,17 @@ int dn_launch_sample(dn_batch* b, const dn_graph* g, const int32_t* d_targets, i
     hipLaunchKernelGGL(k_init_offsets, dim3(grid0), dim3(TPB), 0, st, n_targets, b->hdr, b->lvl_nbr_offsets, blk);
     }
     DN_LAUNCH_CHECK("k_init_offsets");
+    return launch_hops_and_assemble(b, gd, n_targets, seed, st);
+}
 
+// the k hops (sample, next Delta) and the final layout, common to both front ends
+static int launch_hops_and_assemble(dn_batch* b, const GraphDev& gd, int64_t level0_bound, uint64_t seed, hipStream_t st)
+{
+    const int k = b->k, dir = b->direction;
+    uint64_t* blk = reinterpret_cast<uint64_t*>(b->blk_a);
+    const uint32_t key0 = (uint32_t)(seed & 0xffffffffu), key1 = (uint32_t)(seed >> 32);
     const int grid_words = (int)((b->words1 + TPB - 1) / TPB);
-    int64_t level_bound = n_targets;                        // upper bound of the level size, known on the host
+    int64_t level_bound = level0_bound;                     // upper bound of the level size, known on the host
     for (int h = 0; h < k; ++h) {
         const int f = b->fanouts[h];
         int G = 4;
@@ -434,7 +522,8 @@ int dn_launch_sample(dn_batch* b, const dn_graph* g, const int32_t* d_targets, i
         DN_LAUNCH_CHECK("k_fresh_count");
         { dn_prof_scope ps("fresh_emit_hop", h + 1, st);
         hipLaunchKernelGGL(k_fresh_emit, dim3(grid_words), dim3(TPB), 0, st, gd, b->words1, h + 1, f_next, dir, b->hdr,
-                           b->fresh, b->summary, blk, b->lvlpos, b->lvl_ids, b->lvl_nbr_offsets, b->cap_nodes);
+                           b->fresh, b->summary, blk, b->lvlpos, b->lvl_ids, b->lvl_nbr_offsets, b->cap_nodes,
+                           (uint32_t*)nullptr);
         }
         DN_LAUNCH_CHECK("k_fresh_emit");
         const int mult = dir == DN_DIR_BOTH ? 2 : 1;

@@ -18,7 +18,7 @@ pytestmark = pytest.mark.gpu
 TOL = 1e-4
 
 
-def run_full(cfg, batches, n_targets=None, want_dh0=False):
+def run_full(cfg, batches, n_targets=None, want_dh0=False, edge_batch=None):
     dev = torch.device("cuda:0")
     inputs = make_inputs(cfg, dev, n_batches=max(batches) + 1)
     og = oracle.Graph(cfg.num_nodes, inputs["rowptr"].cpu().numpy(), inputs["col"].cpu().numpy(),
@@ -35,10 +35,25 @@ def run_full(cfg, batches, n_targets=None, want_dh0=False):
     h0 = torch.empty((batch.node_capacity, cfg.dims[0]), dtype=table.dtype, device=dev)
     report = []
     for bi in batches:
-        targets = inputs["targets"][bi] if n_targets is None else inputs["targets"][bi][:n_targets]
-        dn.dense_sample(batch, graph, torch.from_numpy(targets).to(dev), bi)
+        if edge_batch is None:
+            targets = inputs["targets"][bi] if n_targets is None else inputs["targets"][bi][:n_targets]
+            dn.dense_sample(batch, graph, torch.from_numpy(targets).to(dev), bi)
+            d = oracle.dense_sample(og, targets, cfg.fanouts, seed=bi, direction=cfg.direction)
+        else:
+            # link-prediction batch: uniform positive edges of the graph, shared uniform negatives per chunk
+            n_edges, chunk, n_neg = edge_batch
+            rng = np.random.default_rng([17, bi])
+            e = torch.from_numpy(rng.integers(0, inputs["col"].numel(), n_edges)).to(dev)
+            dst_t = inputs["col"][e]
+            src_t = (torch.searchsorted(inputs["rowptr"], e, right=True) - 1).to(torch.int32)
+            neg_t = torch.from_numpy(rng.integers(0, cfg.num_nodes, (n_edges // chunk) * n_neg).astype(np.int32)).to(dev)
+            ls, ld, ln = dn.dense_sample_edges(batch, graph, src_t, dst_t, neg_t, bi)
+            src, dst, neg = src_t.cpu().numpy(), dst_t.cpu().numpy(), neg_t.cpu().numpy()
+            d, ols, old, oln = oracle.dense_sample_edges(og, src, dst, neg, cfg.fanouts, seed=bi, direction=cfg.direction)
+            assert np.array_equal(ls.cpu().numpy(), ols) and np.array_equal(ld.cpu().numpy(), old)
+            assert np.array_equal(ln.cpu().numpy(), oln)
+            targets = d.node_ids[d.node_id_offsets[-2]:]
         view = {k: v.cpu().numpy() for k, v in batch.view().items()}
-        d = oracle.dense_sample(og, targets, cfg.fanouts, seed=bi, direction=cfg.direction)
         assert_dense_equal(view, d)
         n = len(d.node_ids)
         dn.dense_gather(batch, table, h0)
@@ -63,6 +78,12 @@ def run_full(cfg, batches, n_targets=None, want_dh0=False):
             errs["db%d" % (i + 1)] = row_rel_err(dbs[i].cpu().numpy(), grads.d_bias[i])
         if want_dh0:
             errs["dh0"] = row_rel_err(dh0[:n].cpu().numpy(), grads.d_h0)
+            # learnable inputs: apply the update to a small stand-in table indexed by position, row by row
+            probe = torch.from_numpy(d.node_ids[:2000].astype(np.int64)).to(dev)
+            before = table[probe].clone()
+            dn.embedding_sgd(batch, table, dh0, 0.01)
+            want = before.cpu().numpy() - np.float32(0.01) * dh0[:2000].cpu().numpy()
+            assert np.array_equal(table[probe].cpu().numpy().view(np.uint32), want.astype(np.float32).view(np.uint32))
         print(cfg.name, "batch", bi, "N=%d E=%d" % (n, len(d.nbrs)), {k: float("%.2e" % v) for k, v in errs.items()})
         bad = {k: v for k, v in errs.items() if not v <= TOL}
         assert not bad, bad
@@ -83,6 +104,7 @@ def test_rmat122m_bf16_features():
 
 
 def test_rmat86m_both_directions_with_input_gradient():
-    """150,000 target nodes (the size of the unique endpoints + negatives of a 50,000-edge batch),
-    20 in- plus 20 out-neighbours, one layer, gradient with respect to the learnable inputs."""
-    run_full(CONFIGS[4], batches=[0], want_dh0=True)
+    """50,000 positive edges with 1,000 shared negatives per chunk of 1,000 edges (at most 150,000 target
+    nodes), 20 in- plus 20 out-neighbours, one layer, gradient with respect to the learnable inputs and
+    their SGD update."""
+    run_full(CONFIGS[4], batches=[0], want_dh0=True, edge_batch=(50_000, 1_000, 1_000))

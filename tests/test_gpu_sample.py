@@ -178,3 +178,67 @@ def test_gather_strided_table(g16k):
     dn.dense_gather(batch, table, out)
     n = len(view["node_ids"])
     assert torch.equal(out[:n].cpu(), table.cpu()[torch.from_numpy(view["node_ids"]).long()])
+
+
+def _edge_batch(dg, n_edges, n_neg, seed):
+    rng = np.random.default_rng(seed)
+    rp, col = dg.oracle.rowptr_out, dg.oracle.col_out
+    e = rng.integers(0, len(col), n_edges)
+    src = (np.searchsorted(rp, e, side="right") - 1).astype(np.int32)
+    dst = col[e].astype(np.int32)
+    neg = rng.integers(0, dg.num_nodes, n_neg).astype(np.int32)
+    return src, dst, neg
+
+
+@pytest.mark.parametrize("direction,fanouts", [(dn.DN_DIR_BOTH, [20]), (dn.DN_DIR_OUT, [5, 3]), (dn.DN_DIR_IN, [4])])
+def test_edge_front_end_bit_exact(g16k, direction, fanouts):
+    src, dst, neg = _edge_batch(g16k, 500, 200, seed=1)
+    batch = dn.Batch(g16k.num_nodes, 2 * len(src) + len(neg), fanouts, direction)
+    t = lambda a: torch.from_numpy(a).to("cuda:0")
+    for seed in (3, 4):                                   # twice on the same batch object: bitmaps are left clean
+        ls, ld, ln = dn.dense_sample_edges(batch, g16k.graph, t(src), t(dst), t(neg), seed)
+        view = {k: v.cpu().numpy() for k, v in batch.view().items()}
+        d, ols, old, oln = oracle.dense_sample_edges(g16k.oracle, src, dst, neg, fanouts, seed, direction)
+        assert_dense_equal(view, d)
+        assert np.array_equal(ls.cpu().numpy(), ols) and np.array_equal(ld.cpu().numpy(), old)
+        assert np.array_equal(ln.cpu().numpy(), oln)
+    # a node-target batch on the same object afterwards still matches
+    targets = target_batch(g16k.num_nodes, 64, 0)
+    view = gpu_sample(g16k, batch, targets, seed=9)
+    assert_dense_equal(view, oracle.dense_sample(g16k.oracle, targets, fanouts, 9, direction))
+
+
+def test_edge_front_end_degenerate_and_errors(g16k):
+    batch = dn.Batch(g16k.num_nodes, 64, [3], dn.DN_DIR_OUT)
+    e32 = torch.zeros(0, dtype=torch.int32, device="cuda:0")
+    dn.dense_sample_edges(batch, g16k.graph, e32, e32, e32, 0)           # nothing at all
+    assert batch.counts() == [0, 0, 0, 0]
+    one = torch.tensor([5], dtype=torch.int32, device="cuda:0")
+    ls, ld, ln = dn.dense_sample_edges(batch, g16k.graph, one, one, one, 0)   # a self loop that is also a negative
+    d, ols, old, oln = oracle.dense_sample_edges(g16k.oracle, [5], [5], [5], [3], 0)
+    assert_dense_equal({k: v.cpu().numpy() for k, v in batch.view().items()}, d)
+    assert ls.item() == 0 and ld.item() == 0 and ln.item() == 0
+    big = torch.arange(40, dtype=torch.int32, device="cuda:0")
+    with pytest.raises(dn.DenseError) as err:                            # 2*40 + 0 > 64 targets
+        dn.dense_sample_edges(batch, g16k.graph, big, big, e32, 0)
+    assert err.value.code == -2
+    bad = torch.tensor([1, g16k.num_nodes], dtype=torch.int32, device="cuda:0")
+    dn.dense_sample_edges(batch, g16k.graph, bad, bad, e32, 0)
+    with pytest.raises(dn.DenseError) as err:
+        batch.counts()
+    assert err.value.code == -5
+
+
+def test_embedding_sgd_bit_exact(g16k):
+    cfg = CONFIGS[0]
+    batch = dn.Batch(cfg.num_nodes, cfg.batch, cfg.fanouts)
+    targets = target_batch(cfg.num_nodes, cfg.batch, 2)
+    view = gpu_sample(g16k, batch, targets, seed=6)
+    n = len(view["node_ids"])
+    rng = np.random.default_rng(1)
+    table = rng.standard_normal((cfg.num_nodes, 100)).astype(np.float32)
+    grad = rng.standard_normal((batch.node_capacity, 100)).astype(np.float32)
+    t_dev = torch.from_numpy(table).to("cuda:0")
+    dn.embedding_sgd(batch, t_dev, torch.from_numpy(grad).to("cuda:0"), 0.05)
+    want = oracle.embedding_sgd(table, view["node_ids"], grad[:n], 0.05)
+    assert np.array_equal(t_dev.cpu().numpy().view(np.uint32), want.view(np.uint32))

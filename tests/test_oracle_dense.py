@@ -242,3 +242,37 @@ def test_gather_is_row_selection():
     assert np.array_equal(oracle.dense_gather(table, ids), table[ids])
     t16 = rng.integers(0, 2**16, size=(50, 6)).astype(np.uint16)   # 2-byte rows (bf16 bit patterns)
     assert np.array_equal(oracle.dense_gather(t16, ids), t16[ids])
+
+
+def test_edge_front_end_targets_and_maps(rmat16k):
+    """Targets of a link-prediction batch are the distinct endpoints and negatives; the returned
+    indices point back at them, and the sample is the node-target sample of that list."""
+    rp, col = rmat16k["out"]
+    rpi, coli = rmat16k["in"]
+    g = oracle.Graph(len(rp) - 1, rp, col, rpi, coli)
+    rng = np.random.default_rng(8)
+    e = rng.integers(0, len(col), 300)
+    src = np.searchsorted(rp, e, side="right").astype(np.int32) - 1       # real edges of the graph
+    dst = col[e]
+    neg = rng.integers(0, g.num_nodes, 100).astype(np.int32)
+    neg[:5] = src[:5]                                                    # negatives may coincide with endpoints
+    d, ls, ld, ln = oracle.dense_sample_edges(g, src, dst, neg, [4], seed=2, direction=2)
+    targets = d.node_ids[d.node_id_offsets[1]:]
+    assert np.all(np.diff(targets) > 0)
+    assert set(targets.tolist()) == set(src.tolist()) | set(dst.tolist()) | set(neg.tolist())
+    assert np.array_equal(targets[ls], src) and np.array_equal(targets[ld], dst) and np.array_equal(targets[ln], neg)
+    d2 = oracle.dense_sample(g, targets, [4], seed=2, direction=2)
+    assert np.array_equal(d.nbrs, d2.nbrs) and np.array_equal(d.node_ids, d2.node_ids)
+    check_dense_invariants(d, g, targets, [4], direction=2)
+
+
+def test_embedding_sgd_touches_only_sampled_rows():
+    rng = np.random.default_rng(0)
+    table = rng.standard_normal((40, 6)).astype(np.float32)
+    ids = np.array([7, 3, 31], dtype=np.int32)
+    grad = rng.standard_normal((3, 6)).astype(np.float32)
+    out = oracle.embedding_sgd(table, ids, grad, 0.25)
+    untouched = np.setdiff1d(np.arange(40), ids)
+    assert np.array_equal(out[untouched], table[untouched])
+    np.testing.assert_allclose(out[ids], table[ids].astype(np.float64) - 0.25 * grad.astype(np.float64), rtol=0, atol=1e-6)
+    assert np.array_equal(oracle.embedding_sgd(table, ids, np.zeros_like(grad), 0.25), table)
