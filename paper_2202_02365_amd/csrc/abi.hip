@@ -71,7 +71,6 @@ void carve_batch(dn_batch* b, Carver& c)
     b->summary = c.take<uint32_t>(b->words1);
     b->tr_hist_words = dn_transpose_index_hist_words(b);
     b->tr_hist = c.take<int32_t>(b->tr_hist_words);          // starts at zero like the bitmaps
-    b->tr_hist_next = 0;
     b->lvlpos = c.take<int32_t>(b->V);
     b->lvl_ids = c.take<int32_t>(b->cap_nodes);
     b->lvl_nbr_offsets = c.take<int32_t>(b->cap_nodes + 1);

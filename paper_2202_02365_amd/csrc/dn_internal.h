@@ -52,7 +52,6 @@ struct dn_batch {
     // transpose index for the backward pass (slots grouped by the input row they read)
     int32_t *tr_key[2], *tr_val[2], *tr_ptr, *tr_hist;
     int64_t tr_hist_words;
-    int32_t tr_hist_next;                   // which of the three rotating histograms is known to be zero
     int32_t n_targets;
     uint64_t sample_serial;                 // bumped by every dense_sample
     uint64_t tr_serial;                     // sample the transpose index was built for

@@ -7,9 +7,11 @@
 //
 // Launches: k_tr_init (copy + histogram of the first digit), then per pass two scan kernels and
 // one scatter that also histograms the next digit at the element's new position, then k_tr_ptr.
-// Histograms are integer atomics (order-independent).  Three histogram buffers rotate: the scan
-// of a pass clears the buffer the next accumulation goes into, and the buffer the last scan
-// cleared is the one the next build starts with.
+// Histograms are integer atomics (order-independent).  Two histogram buffers alternate: pass p scans
+// buffer p % 2 and its scan clears the other one, into which the scatter then counts the next
+// digit.  Buffer 0 is zero on entry and zero again on exit (k_tr_ptr clears it when the number of
+// passes is odd), so a build depends on no host-side state and can be replayed from a HIP graph
+// in any order.
 #include "dn_internal.h"
 
 namespace {
@@ -160,12 +162,13 @@ __global__ __launch_bounds__(TPB) void k_radix_scatter(const int32_t* __restrict
     }
 }
 
-// tr_ptr[p] = first index of sorted keys >= p, for p = 0..N
+// tr_ptr[p] = first index of sorted keys >= p, for p = 0..N; also leaves histogram buffer 0 zeroed
 __global__ __launch_bounds__(TPB) void k_tr_ptr(const int32_t* __restrict__ hdr, const int32_t* __restrict__ key,
-                                                int32_t* __restrict__ tr_ptr)
+                                                int32_t* __restrict__ tr_ptr, int32_t* __restrict__ clear, int clear_words)
 {
     const int N = hdr[HDR_N], n = hdr[HDR_TR_COUNT];
     const int stride = gridDim.x * TPB;
+    for (int i = blockIdx.x * TPB + threadIdx.x; i < clear_words; i += stride) clear[i] = 0;
     for (int p = blockIdx.x * TPB + threadIdx.x; p <= N; p += stride) {
         int lo = 0, hi = n;
         while (lo < hi) {
@@ -188,13 +191,13 @@ void sort_plan(const dn_batch* b, int* passes, int* bits, int* nblocks)
 
 }  // namespace
 
-// ints of histogram space (three rotating histograms + scan partials); they must start at zero
+// ints of histogram space (two alternating histograms + scan partials); they must start at zero
 int64_t dn_transpose_index_hist_words(const dn_batch* b)
 {
     int passes, bits, nblocks;
     sort_plan(b, &passes, &bits, &nblocks);
     const int64_t total = ((int64_t)1 << bits) * nblocks;
-    return 3 * total + (total + TILE - 1) / TILE + 64;
+    return 2 * total + (total + TILE - 1) / TILE + 64;
 }
 
 int dn_launch_transpose_index(dn_batch* b, int need_all, hipStream_t st)
@@ -205,11 +208,11 @@ int dn_launch_transpose_index(dn_batch* b, int need_all, hipStream_t st)
     const int radix = 1 << bits;
     const int total = radix * nblocks;
     const int sblocks = (total + TILE - 1) / TILE;
-    if (3 * (int64_t)total + sblocks > b->tr_hist_words) return dn_fail(DN_ECAPACITY, "transpose index: histogram space");
-    int32_t* hist[3] = { b->tr_hist, b->tr_hist + total, b->tr_hist + 2 * (int64_t)total };
-    int32_t* part = b->tr_hist + 3 * (int64_t)total;
+    if (2 * (int64_t)total + sblocks > b->tr_hist_words) return dn_fail(DN_ECAPACITY, "transpose index: histogram space");
+    int32_t* hist[2] = { b->tr_hist, b->tr_hist + total };
+    int32_t* part = b->tr_hist + 2 * (int64_t)total;
     int src = passes & 1;                                   // so that the last pass lands in buffer 0
-    int h = b->tr_hist_next;                                // the buffer that is known to be zero
+    int h = 0;                                              // histogram buffer 0 is zero on entry
     dn_prof_scope ps("transpose_index", 0, st);             // the whole sort counts as one step
     int64_t g = (b->cap_slots + TPB - 1) / TPB;
     if (g > 2048) g = 2048;
@@ -219,7 +222,7 @@ int dn_launch_transpose_index(dn_batch* b, int need_all, hipStream_t st)
     DN_LAUNCH_CHECK("k_tr_init");
     for (int p = 0; p < passes; ++p) {
         const int shift = bits * p;
-        const int hn = (h + 1) % 3;
+        const int hn = h ^ 1;
         hipLaunchKernelGGL(k_scan_partial, dim3(sblocks), dim3(TPB), 0, st, hist[h], total, part);
         DN_LAUNCH_CHECK("k_scan_partial");
         hipLaunchKernelGGL(k_scan_apply, dim3(sblocks), dim3(TPB), 0, st, hist[h], total, part, hist[hn]);
@@ -231,10 +234,12 @@ int dn_launch_transpose_index(dn_batch* b, int need_all, hipStream_t st)
         src ^= 1;
         h = hn;
     }
-    b->tr_hist_next = h;                                    // cleared by the last scan, untouched since
+    // after the last pass the buffer it scanned holds offsets and the other one is zero: buffer 0 needs clearing
+    // exactly when the number of passes is odd
     int64_t gp = (b->cap_nodes + 1 + TPB - 1) / TPB;
     if (gp > 2048) gp = 2048;
-    hipLaunchKernelGGL(k_tr_ptr, dim3((int)gp), dim3(TPB), 0, st, b->hdr, b->tr_key[0], b->tr_ptr);
+    hipLaunchKernelGGL(k_tr_ptr, dim3((int)gp), dim3(TPB), 0, st, b->hdr, b->tr_key[0], b->tr_ptr, hist[0],
+                       (passes & 1) ? total : 0);
     DN_LAUNCH_CHECK("k_tr_ptr");
     b->tr_serial = b->sample_serial;
     b->tr_covers_all = need_all ? 1 : 0;
