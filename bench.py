@@ -134,6 +134,9 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (reference for hardware byte counters)")
     ap.add_argument("--no-graphs", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
+    ap.add_argument("--replicas", type=int, default=4,
+                    help="data-parallel replicas on one GPU: that many mini-batches run the whole path concurrently, "
+                         "each on a HIP stream of its own (0 = skip this measurement)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -273,20 +276,66 @@ def main():
         torch.cuda.synchronize()
         return time.perf_counter() - t0
 
+    # Data-parallel replicas on one GPU: R mini-batches run the whole path at once, each on its own stream
+    # with its own batch and model workspaces, against the same weights; their gradients are what R
+    # data-parallel workers would sum.  The step is a chain of ~40 short kernels, most of them far too
+    # small to fill 256 compute units, so concurrent chains fill the gaps.
+    def timed_replicas(n_steps, n_rep, backward=True):
+        reps = []
+        for r in range(n_rep):
+            b = dn.Batch(cfg.num_nodes, cfg.batch, cfg.fanouts, cfg.direction)
+            m = dn.Model(b, dims, in_dtype)
+            m.set_weights(w_self, w_nbr, bias)
+            reps.append(dict(batch=b, model=m, h0=torch.empty_like(h0), out=torch.empty_like(out),
+                             dws=[torch.empty_like(w) for w in w_self], dwn=[torch.empty_like(w) for w in w_nbr],
+                             dbs=[torch.empty_like(x) for x in bias],
+                             dh0=None if dh0 is None else torch.empty_like(dh0), stream=torch.cuda.Stream()))
+
+        def run(n):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for s in range(n):
+                o = reps[s % n_rep]
+                bi = s % N_BATCHES
+                with torch.cuda.stream(o["stream"]):
+                    dn.dense_sample(o["batch"], graph, targets[bi], bi)
+                    dn.dense_gather(o["batch"], table, o["h0"])
+                    dn.sage_forward(o["model"], o["batch"], o["h0"], o["out"])
+                    if backward:
+                        dn.sage_backward(o["model"], o["batch"], grad_out, o["dws"], o["dwn"], o["dbs"], o["dh0"])
+            torch.cuda.synchronize()
+            return time.perf_counter() - t0
+        run(max(args.warmup, n_rep))
+        spent = run(n_steps)
+        if backward:
+            # with every replica busy, the one that runs batch 5 must give the gradients of the one-at-a-time step
+            for r, o in enumerate(reps):
+                bi = 5 if r == 0 else 6 + r
+                with torch.cuda.stream(o["stream"]):
+                    dn.dense_sample(o["batch"], graph, targets[bi], bi)
+                    dn.dense_gather(o["batch"], table, o["h0"])
+                    dn.sage_forward(o["model"], o["batch"], o["h0"], o["out"])
+                    dn.sage_backward(o["model"], o["batch"], grad_out, o["dws"], o["dwn"], o["dbs"], o["dh0"])
+            torch.cuda.synchronize()
+            o = reps[0]
+            if not all(torch.equal(a, b) for a, b in zip(eager, o["dws"] + o["dwn"] + o["dbs"] + [o["out"]])):
+                raise RuntimeError("a replica's step differs from the one-at-a-time step")
+        return spent
+
     edges = sum(sizes[s % N_BATCHES][k + 2] for s in range(args.steps))
     timed(args.warmup)
     serial_s = timed(args.steps)
     serial_fwd_s = timed(args.steps, backward=False)
+    # one-at-a-time reference for batch 5, to compare a graph replay and a replica's step with
+    step(5)
+    torch.cuda.synchronize()
+    eager = [t.clone() for t in dws + dwn + dbs + [out]]
     if args.no_graphs:
         timed_pipelined(args.warmup)
         total_s = timed_pipelined(args.steps)
         fwd_only_s = timed_pipelined(args.steps, backward=False)
     else:
         assert N_BATCHES % 2 == 0
-        # eager reference for batch 5, to compare one replay with
-        step(5)
-        torch.cuda.synchronize()
-        eager = [t.clone() for t in dws + dwn + dbs + [out]]
         capture_graphs(True)
         capture_graphs(False)
         timed_graphs(args.warmup)
@@ -302,6 +351,22 @@ def main():
         "one in flight: %.3f ms/step (%.3f ms)" %
         (args.steps, 1e3 * total_s / args.steps, 1e3 * fwd_only_s / args.steps,
          1e3 * serial_s / args.steps, 1e3 * serial_fwd_s / args.steps))
+    pipelined = {"ms_per_step": 1e3 * total_s / args.steps, "mini_batches_per_s": args.steps / total_s,
+                 "sampled_edges_per_s": edges / total_s,
+                 "sample_gather_fwd_ms_per_step": 1e3 * fwd_only_s / args.steps,
+                 "launch": "eager" if args.no_graphs else
+                           "hipGraph replay (1 graph per step, construction forked onto a second stream)"}
+    in_flight = "2 mini-batches: sample+gather of batch t+1 on one stream, forward+backward of batch t on another"
+    if args.replicas > 1:
+        rep_s = timed_replicas(args.steps, args.replicas)
+        rep_fwd_s = timed_replicas(args.steps, args.replicas, backward=False)
+        log("%d replicas on %d streams: %.3f ms/step (sample+gather+fwd only: %.3f ms)" %
+            (args.replicas, args.replicas, 1e3 * rep_s / args.steps, 1e3 * rep_fwd_s / args.steps))
+        if rep_s < total_s:
+            total_s, fwd_only_s = rep_s, rep_fwd_s
+            in_flight = ("%d mini-batches, each running sample+gather+forward+backward on a stream of its own "
+                         "(data-parallel replicas on one GPU, same weights, gradients per replica), launched eagerly"
+                         % args.replicas)
 
     # per-kernel durations: the same K steps again, every launch bracketed by HIP events on its stream
     roofline, kernels = None, {}
@@ -374,8 +439,8 @@ def main():
                    "dims": dims, "fanouts": list(cfg.fanouts), "batch": cfg.batch,
                    "mean_nodes_per_batch": mean_n, "mean_sampled_edges_per_batch": mean_e},
         "mini_batches_per_s": args.steps / total_s,
-        "in_flight": "2 mini-batches: sample+gather of batch t+1 on one stream, forward+backward of batch t on another",
-        "launch": "eager" if args.no_graphs else "hipGraph replay (1 graph per step, construction forked onto a second stream)",
+        "in_flight": in_flight,
+        "two_in_flight": pipelined,
         "sample_gather_fwd": {"ms_per_step": 1e3 * fwd_only_s / args.steps,
                               "mini_batches_per_s": args.steps / fwd_only_s,
                               "sampled_edges_per_s": edges / fwd_only_s},
