@@ -181,6 +181,48 @@ DN_API int  sage_backward(dn_model* m, const dn_batch* b, const float* d_grad_ou
                    float* const* d_dw_self, float* const* d_dw_nbr, float* const* d_dbias,
                    float* d_dH0, void* stream);
 
+/* ---- DistMult decoder with shared negatives (link prediction).  The paper names the DistMult score function
+ *      (Section 7.1, link prediction: datasets, models and metrics) and the number of negatives (Section 7.3) only;
+ *      score, loss and negative scheme are the textbook ones:
+ *        f(s, r, d) = sum_j h_s[j] r[j] h_d[j];
+ *        edges are cut into chunks of `chunk` consecutive edges, chunk q shares the negatives d_neg[q, 0..num_neg);
+ *        side 0 corrupts the destination, f(s, r, neg), side 1 the source, f(neg, r, d);
+ *        loss[e] = sum over both sides of logsumexp([pos, that side's negatives]) - pos.
+ *      The negatives' scores are a bf16 MFMA contraction (operands bf16(h * r), formed in fp32, and bf16(h_neg),
+ *      fp32 accumulation); the positive's score uses the fp32 inputs.
+ *
+ *      dn_decoder_create carves the caller's 256-byte aligned device workspace (size from
+ *      dn_decoder_workspace_size) for at most max_edges edges per call, rows of H below max_rows and num_rel
+ *      relations, and clears it on `stream`.  The library allocates no device memory.
+ *
+ *      distmult_forward: d_H [n_rows x dim] fp32 with row stride ldh (the encoder's output for the batch's targets),
+ *      d_R [num_rel x dim] fp32 with row stride ldr, d_src / d_rel / d_dst int32[n_edges] (rows of H, relation ids),
+ *      d_neg int32[ceil(n_edges / chunk) x num_neg] rows of H.  Outputs d_pos, d_loss: fp32[n_edges].
+ *      An index outside its range makes that edge (negative) count as a zero row and raises a flag that
+ *      dn_decoder_status returns (1 = node index, 2 = relation); no access leaves its array.
+ *      The decoder keeps the input pointers: they must stay valid and unchanged until distmult_backward ran.
+ *
+ *      distmult_backward: gradients of sum_e loss[e] of the last distmult_forward: d_dH [n_rows x dim] (row stride
+ *      ld_dh) and d_dR [num_rel x dim] (row stride ld_dr), every row written (zero where nothing contributes),
+ *      summed in a fixed order (bit-identical from run to run).  Rounding to bf16 is differentiated as the identity.
+ *
+ *      dn_decoder_scores: device pointer and strides (in floats) of the negatives' scores of the last forward,
+ *      score of edge e against negative n = d_scores[(e / chunk) * chunk_stride + (e % chunk) * row_stride + n].
+ *      dn_decoder_status WAITS for `stream`.  All other calls are asynchronous on `stream`. */
+typedef struct dn_decoder dn_decoder;
+DN_API int  dn_decoder_workspace_size(int64_t max_edges, int32_t chunk, int32_t num_neg, int32_t dim, int64_t max_rows,
+                                      int64_t num_rel, size_t* bytes);
+DN_API int  dn_decoder_create(dn_decoder** out, int64_t max_edges, int32_t chunk, int32_t num_neg, int32_t dim,
+                              int64_t max_rows, int64_t num_rel, void* d_workspace, size_t workspace_bytes, void* stream);
+DN_API void dn_decoder_destroy(dn_decoder* d);
+DN_API int  distmult_forward(dn_decoder* d, const float* d_H, int64_t ldh, int64_t n_rows, const float* d_R, int64_t ldr,
+                             const int32_t* d_src, const int32_t* d_rel, const int32_t* d_dst, int64_t n_edges,
+                             const int32_t* d_neg, float* d_pos, float* d_loss, void* stream);
+DN_API int  distmult_backward(dn_decoder* d, float* d_dH, int64_t ld_dh, float* d_dR, int64_t ld_dr, void* stream);
+DN_API int  dn_decoder_scores(const dn_decoder* d, int32_t side, const float** d_scores, int64_t* chunk_stride,
+                              int64_t* row_stride);
+DN_API int  dn_decoder_status(const dn_decoder* d, int32_t* flags, void* stream);
+
 /* ---- per-kernel timing for benchmarks (off by default; not a step of the path).
  *      dn_profile_enable(1): from now on every kernel launch of this library is bracketed by a pair of
  *      HIP events on the stream it is launched on; dn_profile_enable(0) stops that.  Enabling also

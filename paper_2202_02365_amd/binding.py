@@ -75,6 +75,13 @@ def load_library():
         "dn_profile_calibration_copy": (ctypes.c_int, [vp, vp, sz, vp]),
         "dn_profile_empty_bracket": (ctypes.c_int, [vp]),
         "dn_profile_collect": (ctypes.c_int, [ctypes.POINTER(_KernelTime), i32, ctypes.POINTER(i32)]),
+        "dn_decoder_workspace_size": (ctypes.c_int, [i64, i32, i32, i32, i64, i64, ctypes.POINTER(sz)]),
+        "dn_decoder_create": (ctypes.c_int, [pp, i64, i32, i32, i32, i64, i64, vp, sz, vp]),
+        "dn_decoder_destroy": (None, [vp]),
+        "distmult_forward": (ctypes.c_int, [vp, vp, i64, i64, vp, i64, vp, vp, vp, i64, vp, vp, vp, vp]),
+        "distmult_backward": (ctypes.c_int, [vp, vp, i64, vp, i64, vp]),
+        "dn_decoder_scores": (ctypes.c_int, [vp, i32, pp, ctypes.POINTER(i64), ctypes.POINTER(i64)]),
+        "dn_decoder_status": (ctypes.c_int, [vp, ctypes.POINTER(i32), vp]),
         "sage_forward": (ctypes.c_int, [vp, vp, vp, vp, vp]),
         "sage_backward": (ctypes.c_int, [vp, vp, vp, pp, pp, pp, vp, vp]),
     }
@@ -228,6 +235,69 @@ class Model:
             assert tuple(bias[i].shape) == (self.dims[i + 1],)
         _check(load_library().dn_model_set_weights(self.handle, _ptr_array(w_self), _ptr_array(w_nbr),
                                                    _ptr_array(bias), _stream()))
+
+
+class Decoder:
+    """DistMult decoder with shared negatives: workspace for at most max_edges edges per call."""
+
+    def __init__(self, max_edges: int, chunk: int, num_neg: int, dim: int, max_rows: int, num_rel: int, device="cuda"):
+        lib = load_library()
+        self.max_edges, self.chunk, self.num_neg, self.dim = max_edges, chunk, num_neg, dim
+        self.max_rows, self.num_rel = max_rows, num_rel
+        nbytes = ctypes.c_size_t()
+        _check(lib.dn_decoder_workspace_size(max_edges, chunk, num_neg, dim, max_rows, num_rel, ctypes.byref(nbytes)))
+        self.workspace = _alloc_workspace(nbytes.value, device)
+        h = ctypes.c_void_p()
+        _check(lib.dn_decoder_create(ctypes.byref(h), max_edges, chunk, num_neg, dim, max_rows, num_rel,
+                                     self.workspace.data_ptr(), nbytes.value, _stream()))
+        self.handle = h
+        self._keep = None
+        self._n_edges = 0
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.dn_decoder_destroy(self.handle)
+            self.handle = None
+
+    def status(self) -> int:
+        """Flags of the last forward (1 = node index out of range, 2 = relation out of range); waits for the stream."""
+        f = ctypes.c_int32()
+        _check(load_library().dn_decoder_status(self.handle, ctypes.byref(f), _stream()))
+        return int(f.value)
+
+    def scores(self, side: int) -> torch.Tensor:
+        """Negatives' scores of the last forward as a [n_edges x num_neg] view-copy (side 0: corrupted destination)."""
+        ptr, cs, rs = ctypes.c_void_p(), ctypes.c_int64(), ctypes.c_int64()
+        _check(load_library().dn_decoder_scores(self.handle, side, ctypes.byref(ptr), ctypes.byref(cs), ctypes.byref(rs)))
+        n_chunks = (self._n_edges + self.chunk - 1) // self.chunk
+        off = ptr.value - self.workspace.data_ptr()
+        flat = self.workspace[off:off + 4 * n_chunks * cs.value].view(torch.float32)
+        full = flat.view(n_chunks, cs.value // rs.value, rs.value)[:, :self.chunk, :self.num_neg]
+        return full.reshape(n_chunks * self.chunk, self.num_neg)[:self._n_edges]
+
+
+def distmult_forward(dec: Decoder, h: torch.Tensor, r: torch.Tensor, src: torch.Tensor, rel: torch.Tensor,
+                     dst: torch.Tensor, neg: torch.Tensor, pos: torch.Tensor, loss: torch.Tensor) -> None:
+    """pos[e], loss[e] of the edges (src, rel, dst) with per-chunk shared negatives neg [chunks x num_neg]."""
+    ne = src.numel()
+    assert rel.numel() == ne and dst.numel() == ne and pos.numel() >= ne and loss.numel() >= ne
+    assert h.dtype == torch.float32 and r.dtype == torch.float32 and h.stride(1) == 1 and r.stride(1) == 1
+    assert h.shape[1] == dec.dim and r.shape[1] == dec.dim and r.shape[0] == dec.num_rel
+    assert neg.numel() == ((ne + dec.chunk - 1) // dec.chunk) * dec.num_neg
+    dec._keep = (h, r, src, rel, dst, neg)
+    dec._n_edges = ne
+    _check(load_library().distmult_forward(dec.handle, h.data_ptr(), h.stride(0), h.shape[0], r.data_ptr(), r.stride(0),
+                                           _dev_ptr(src, torch.int32), _dev_ptr(rel, torch.int32),
+                                           _dev_ptr(dst, torch.int32), ne, _dev_ptr(neg, torch.int32),
+                                           _dev_ptr(pos, torch.float32), _dev_ptr(loss, torch.float32), _stream()))
+
+
+def distmult_backward(dec: Decoder, d_h: torch.Tensor, d_r: torch.Tensor) -> None:
+    """Gradients of sum(loss) of the last distmult_forward with respect to h and r."""
+    assert d_h.dtype == torch.float32 and d_r.dtype == torch.float32 and d_h.stride(1) == 1 and d_r.stride(1) == 1
+    assert d_h.shape == dec._keep[0].shape and tuple(d_r.shape) == (dec.num_rel, dec.dim)
+    _check(load_library().distmult_backward(dec.handle, d_h.data_ptr(), d_h.stride(0), d_r.data_ptr(), d_r.stride(0),
+                                            _stream()))
 
 
 def profile_enable(on: bool) -> None:

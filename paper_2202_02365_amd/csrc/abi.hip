@@ -16,20 +16,7 @@ namespace {
 
 thread_local char g_err[512] = "";
 
-struct Carver {          // hands out 256-byte aligned pieces of one workspace; counts when base == nullptr
-    char* base;
-    size_t off = 0;
-    explicit Carver(void* b) : base(static_cast<char*>(b)) {}
-    template <typename T>
-    T* take(int64_t count)
-    {
-        off = (off + 255) & ~size_t(255);
-        T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
-        off += sizeof(T) * (size_t)(count > 0 ? count : 0);
-        return p;
-    }
-    size_t bytes() const { return (off + 255) & ~size_t(255); }
-};
+using Carver = dn_carver;
 
 int fill_batch_caps(dn_batch* b, int64_t V, int32_t max_targets, int32_t k, const int32_t* fanouts, int32_t direction)
 {

@@ -125,6 +125,21 @@ struct dn_prof_scope {
 
 static inline int64_t dn_round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
+struct dn_carver {       // hands out 256-byte aligned pieces of one workspace; counts when base == nullptr
+    char* base;
+    size_t off = 0;
+    explicit dn_carver(void* b) : base(static_cast<char*>(b)) {}
+    template <typename T>
+    T* take(int64_t count)
+    {
+        off = (off + 255) & ~size_t(255);
+        T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+        off += sizeof(T) * (size_t)(count > 0 ? count : 0);
+        return p;
+    }
+    size_t bytes() const { return (off + 255) & ~size_t(255); }
+};
+
 // launchers (one per step of the hot path)
 int dn_launch_sample(dn_batch* b, const dn_graph* g, const int32_t* d_targets, int32_t n_targets,
                      uint64_t seed, hipStream_t st);
@@ -138,6 +153,16 @@ int dn_launch_gather(const dn_batch* b, const void* table, int32_t dtype, int32_
 int dn_launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 int dn_launch_transpose_index(dn_batch* b, int need_all, hipStream_t st);
 int64_t dn_transpose_index_hist_words(const dn_batch* b);
+
+// Stable radix sort of (key, value) pairs whose count lives in device memory (transpose_index.hip).
+// The caller's own kernel writes the pairs into key[passes & 1] / val[passes & 1] and counts, per
+// tile of DN_SORT_TILE consecutive pairs, the first digit: hist[(key & ((1 << bits) - 1)) * nblocks + i / DN_SORT_TILE]++.
+constexpr int DN_SORT_TILE = 2048;
+struct dn_sort_plan { int passes, bits, nblocks, total, sblocks; };
+dn_sort_plan dn_sort_make_plan(int64_t key_range, int64_t cap_items);
+int64_t dn_sort_hist_words(const dn_sort_plan& p);
+int dn_sort_pairs_run(const dn_sort_plan& pl, const int32_t* count_ptr, int32_t* const key[2], int32_t* const val[2],
+                      int32_t* hist_space, const int32_t* nkeys_ptr, int64_t nkeys_cap, int32_t* ptr_out, hipStream_t st);
 int dn_launch_set_weights(dn_model* m, const float* const* ws, const float* const* wn,
                           const float* const* bias, hipStream_t st);
 int dn_launch_forward(dn_model* m, const dn_batch* b, const void* h0, float* out, hipStream_t st);

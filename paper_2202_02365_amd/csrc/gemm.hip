@@ -23,15 +23,13 @@
 // so that the stored activation and the mask [Z > 0] used by the backward pass are those of the
 // exact sum.
 #include "dn_internal.h"
+#include "mfma_tile.h"
 #include <algorithm>
 
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+using namespace dn_mma;
 
-constexpr int BM = 128, BN = 128, BK = 64, TPB = 256;
 constexpr int LOCAL_FIX_CAP = 1024;     // sign fix-ups one workgroup can queue (of its 16384 outputs)
 enum { EPI_BIAS_ACT = 0, EPI_PLAIN = 1, EPI_SPLIT = 2 };
 
@@ -54,12 +52,6 @@ struct GemmArgs {
     int* fix_count;         // [0] number of exact recomputations, [1] sticky overflow flag
 };
 
-// 16-byte slot of chunk c of tile row `row`: 16 consecutive rows of one chunk column land in 16 different
-// 16-byte bank groups (row parity picks the half, (row >> 1) & 7 permutes the chunks within it)
-__device__ __forceinline__ int slot(int row, int c) { return row * 8 + (c ^ ((row >> 1) & 7)); }
-
-struct TileRegs { u32x4 a[4], b[4]; };
-
 constexpr int MIN_CHUNKS = 8;
 __device__ __forceinline__ int effective_splits(int groups, int chunks)
 {
@@ -71,9 +63,6 @@ __device__ __forceinline__ int effective_splits(int groups, int chunks)
 template <int EPI>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const int bx, const int by, const int bz, const int nz)
 {
-    __shared__ u32x4 As[2][BM * BK / 8];
-    __shared__ u32x4 Bs[2][BN * BK / 8];
-
     const int rows_layer = a.hdr[HDR_N] - a.hdr[HDR_NODE_OFF + a.layer];
     const int M = a.m_const >= 0 ? a.m_const : rows_layer;
     const int red = a.red_const >= 0 ? a.red_const : ((rows_layer + BK - 1) / BK) * BK;
@@ -98,75 +87,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const int bx, const
     const int wm = wave >> 1, wn = wave & 1;
 
     f32x16 acc[2][2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-    // Two register stages: while tile kc is multiplied out of LDS, tiles kc+1 and kc+2 are in
-    // flight, so a chain of dependent k-steps exposes half of the memory latency per step.  Two
-    // LDS buffers allow a single barrier per step.
-    const uint16_t* a_ptr[4];
-    const uint16_t* b_ptr[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int id = t + TPB * i, row = id >> 3, c = id & 7;
-        a_ptr[i] = a.A + (int64_t)(row0 + row) * a.lda + c * 8;
-        b_ptr[i] = Bbase + (int64_t)(col0 + row) * a.ldb + c * 8;
-    }
-    auto load_tiles = [&](TileRegs& r, int kc) {
-        const int64_t k0 = (int64_t)kc * BK;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            r.a[i] = *reinterpret_cast<const u32x4*>(a_ptr[i] + k0);
-            r.b[i] = *reinterpret_cast<const u32x4*>(b_ptr[i] + k0);
-        }
-    };
-    auto store_tiles = [&](const TileRegs& r, int buf) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int id = t + TPB * i, row = id >> 3, c = id & 7;
-            As[buf][slot(row, c)] = r.a[i];
-            Bs[buf][slot(row, c)] = r.b[i];
-        }
-    };
-    auto multiply = [&](int buf) {
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            const int c = 2 * ks + (lane >> 5);
-            bf16x8 fa[2], fb[2];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                fa[i] = __builtin_bit_cast(bf16x8, As[buf][slot(wm * 64 + i * 32 + (lane & 31), c)]);
-                fb[i] = __builtin_bit_cast(bf16x8, Bs[buf][slot(wn * 64 + i * 32 + (lane & 31), c)]);
-            }
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-        }
-    };
-
-    TileRegs r0, r1;
-    if (kc_begin + 0 < kc_end) load_tiles(r0, kc_begin + 0);
-    if (kc_begin + 1 < kc_end) load_tiles(r1, kc_begin + 1);
-    int kc = kc_begin, buf = 0;
-#define DN_GEMM_STEP(R)                                       \
-    if (kc >= kc_end) break;                                  \
-    store_tiles(R, buf);                                      \
-    __syncthreads();                                          \
-    if (kc + 2 < kc_end) load_tiles(R, kc + 2);               \
-    multiply(buf);                                            \
-    buf ^= 1;                                                 \
-    ++kc;
-    for (;;) {
-        DN_GEMM_STEP(r0)
-        DN_GEMM_STEP(r1)
-    }
-#undef DN_GEMM_STEP
+    mainloop<false>(a.A + (int64_t)row0 * a.lda, a.lda, Bbase + (int64_t)col0 * a.ldb, a.ldb, kc_begin, kc_end, 0, acc);
 
     // epilogue: lane holds column (lane & 31); register e holds row 8*(e/4) + 4*(lane/32) + e%4
     float* C = a.C;

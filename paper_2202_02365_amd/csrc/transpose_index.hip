@@ -19,6 +19,7 @@ namespace {
 constexpr int TPB = 256;
 constexpr int ITEMS = 8;                   // elements per thread
 constexpr int TILE = TPB * ITEMS;          // elements per workgroup
+static_assert(TILE == DN_SORT_TILE, "the kernels that count the first digit use DN_SORT_TILE");
 constexpr int MAX_BITS = 11;
 constexpr int MAX_RADIX = 1 << MAX_BITS;
 
@@ -96,7 +97,7 @@ __global__ __launch_bounds__(TPB) void k_scan_apply(int32_t* __restrict__ data, 
 // stable scatter: element order inside a tile is (wave, round, lane); a lane's rank among equal
 // digits of its round comes from one ballot per digit bit, rounds and waves are chained through
 // counters in LDS.  Also counts the next pass's digit at the element's new position.
-__global__ __launch_bounds__(TPB) void k_radix_scatter(const int32_t* __restrict__ hdr, const int32_t* __restrict__ key_in,
+__global__ __launch_bounds__(TPB) void k_radix_scatter(const int32_t* __restrict__ count_ptr, const int32_t* __restrict__ key_in,
                                                        const int32_t* __restrict__ val_in, int shift, int bits, int nblocks,
                                                        const int32_t* __restrict__ hist, int32_t* __restrict__ key_out,
                                                        int32_t* __restrict__ val_out, int next_bits,
@@ -104,7 +105,7 @@ __global__ __launch_bounds__(TPB) void k_radix_scatter(const int32_t* __restrict
 {
     __shared__ int cnt[TPB / 64][MAX_RADIX];
     const int radix = 1 << bits;
-    const int n = hdr[HDR_TR_COUNT];
+    const int n = *count_ptr;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (blockIdx.x * TILE >= n) return;
     for (int w = 0; w < TPB / 64; ++w)
@@ -163,10 +164,11 @@ __global__ __launch_bounds__(TPB) void k_radix_scatter(const int32_t* __restrict
 }
 
 // tr_ptr[p] = first index of sorted keys >= p, for p = 0..N; also leaves histogram buffer 0 zeroed
-__global__ __launch_bounds__(TPB) void k_tr_ptr(const int32_t* __restrict__ hdr, const int32_t* __restrict__ key,
+__global__ __launch_bounds__(TPB) void k_tr_ptr(const int32_t* __restrict__ count_ptr, const int32_t* __restrict__ nkeys_ptr,
+                                                int nkeys_const, const int32_t* __restrict__ key,
                                                 int32_t* __restrict__ tr_ptr, int32_t* __restrict__ clear, int clear_words)
 {
-    const int N = hdr[HDR_N], n = hdr[HDR_TR_COUNT];
+    const int N = nkeys_ptr ? *nkeys_ptr : nkeys_const, n = *count_ptr;
     const int stride = gridDim.x * TPB;
     for (int i = blockIdx.x * TPB + threadIdx.x; i < clear_words; i += stride) clear[i] = 0;
     for (int p = blockIdx.x * TPB + threadIdx.x; p <= N; p += stride) {
@@ -179,68 +181,80 @@ __global__ __launch_bounds__(TPB) void k_tr_ptr(const int32_t* __restrict__ hdr,
     }
 }
 
-void sort_plan(const dn_batch* b, int* passes, int* bits, int* nblocks)
-{
-    int key_bits = 1;
-    while (((int64_t)1 << key_bits) < b->cap_nodes) ++key_bits;
-    *passes = (key_bits + MAX_BITS - 1) / MAX_BITS;
-    *bits = (key_bits + *passes - 1) / *passes;            // bits per pass, <= MAX_BITS
-    const int64_t nb = (b->cap_slots + TILE - 1) / TILE;   // always planned for every slot, so the extent is fixed
-    *nblocks = (int)(nb > 0 ? nb : 1);
-}
-
 }  // namespace
 
-// ints of histogram space (two alternating histograms + scan partials); they must start at zero
-int64_t dn_transpose_index_hist_words(const dn_batch* b)
+dn_sort_plan dn_sort_make_plan(int64_t key_range, int64_t cap_items)
 {
-    int passes, bits, nblocks;
-    sort_plan(b, &passes, &bits, &nblocks);
-    const int64_t total = ((int64_t)1 << bits) * nblocks;
-    return 2 * total + (total + TILE - 1) / TILE + 64;
+    dn_sort_plan p;
+    int key_bits = 1;
+    while (((int64_t)1 << key_bits) < key_range) ++key_bits;
+    p.passes = (key_bits + MAX_BITS - 1) / MAX_BITS;
+    p.bits = (key_bits + p.passes - 1) / p.passes;           // bits per pass, <= MAX_BITS
+    const int64_t nb = (cap_items + TILE - 1) / TILE;        // always planned for the capacity, so the extent is fixed
+    p.nblocks = (int)(nb > 0 ? nb : 1);
+    p.total = (1 << p.bits) * p.nblocks;
+    p.sblocks = (p.total + TILE - 1) / TILE;
+    return p;
 }
 
-int dn_launch_transpose_index(dn_batch* b, int need_all, hipStream_t st)
+// ints of histogram space (two alternating histograms + scan partials); they must start at zero
+int64_t dn_sort_hist_words(const dn_sort_plan& p) { return 2 * (int64_t)p.total + p.sblocks + 64; }
+
+// Sorts the pairs that the caller's first kernel left in key[plan.passes & 1] / val[plan.passes & 1]
+// (with the first digit's per-tile counts in hist[0 .. total)) by key, stably; the result is in
+// key[0] / val[0], and ptr_out[p] = first sorted index with key >= p for p = 0 .. number of keys.
+int dn_sort_pairs_run(const dn_sort_plan& pl, const int32_t* count_ptr, int32_t* const key[2], int32_t* const val[2],
+                      int32_t* hist_space, const int32_t* nkeys_ptr, int64_t nkeys_cap, int32_t* ptr_out, hipStream_t st)
 {
-    if (b->tr_serial == b->sample_serial && (b->tr_covers_all || !need_all)) return DN_OK;
-    int passes, bits, nblocks;
-    sort_plan(b, &passes, &bits, &nblocks);
-    const int radix = 1 << bits;
-    const int total = radix * nblocks;
-    const int sblocks = (total + TILE - 1) / TILE;
-    if (2 * (int64_t)total + sblocks > b->tr_hist_words) return dn_fail(DN_ECAPACITY, "transpose index: histogram space");
-    int32_t* hist[2] = { b->tr_hist, b->tr_hist + total };
-    int32_t* part = b->tr_hist + 2 * (int64_t)total;
-    int src = passes & 1;                                   // so that the last pass lands in buffer 0
+    int32_t* hist[2] = { hist_space, hist_space + pl.total };
+    int32_t* part = hist_space + 2 * (int64_t)pl.total;
+    int src = pl.passes & 1;                                // so that the last pass lands in buffer 0
     int h = 0;                                              // histogram buffer 0 is zero on entry
-    dn_prof_scope ps("transpose_index", 0, st);             // the whole sort counts as one step
-    int64_t g = (b->cap_slots + TPB - 1) / TPB;
-    if (g > 2048) g = 2048;
-    if (g < 1) g = 1;
-    hipLaunchKernelGGL(k_tr_init, dim3((int)g), dim3(TPB), 0, st, b->hdr, need_all, b->k, b->nbr_offsets, b->repr_map,
-                       b->tr_key[src], b->tr_val[src], radix - 1, nblocks, hist[h]);
-    DN_LAUNCH_CHECK("k_tr_init");
-    for (int p = 0; p < passes; ++p) {
-        const int shift = bits * p;
+    for (int p = 0; p < pl.passes; ++p) {
+        const int shift = pl.bits * p;
         const int hn = h ^ 1;
-        hipLaunchKernelGGL(k_scan_partial, dim3(sblocks), dim3(TPB), 0, st, hist[h], total, part);
+        hipLaunchKernelGGL(k_scan_partial, dim3(pl.sblocks), dim3(TPB), 0, st, hist[h], pl.total, part);
         DN_LAUNCH_CHECK("k_scan_partial");
-        hipLaunchKernelGGL(k_scan_apply, dim3(sblocks), dim3(TPB), 0, st, hist[h], total, part, hist[hn]);
+        hipLaunchKernelGGL(k_scan_apply, dim3(pl.sblocks), dim3(TPB), 0, st, hist[h], pl.total, part, hist[hn]);
         DN_LAUNCH_CHECK("k_scan_apply");
-        const int next_bits = (p + 1 < passes) ? bits : 0;
-        hipLaunchKernelGGL(k_radix_scatter, dim3(nblocks), dim3(TPB), 0, st, b->hdr, b->tr_key[src], b->tr_val[src],
-                           shift, bits, nblocks, hist[h], b->tr_key[src ^ 1], b->tr_val[src ^ 1], next_bits, hist[hn]);
+        const int next_bits = (p + 1 < pl.passes) ? pl.bits : 0;
+        hipLaunchKernelGGL(k_radix_scatter, dim3(pl.nblocks), dim3(TPB), 0, st, count_ptr, key[src], val[src],
+                           shift, pl.bits, pl.nblocks, hist[h], key[src ^ 1], val[src ^ 1], next_bits, hist[hn]);
         DN_LAUNCH_CHECK("k_radix_scatter");
         src ^= 1;
         h = hn;
     }
     // after the last pass the buffer it scanned holds offsets and the other one is zero: buffer 0 needs clearing
     // exactly when the number of passes is odd
-    int64_t gp = (b->cap_nodes + 1 + TPB - 1) / TPB;
+    int64_t gp = (nkeys_cap + 1 + TPB - 1) / TPB;
     if (gp > 2048) gp = 2048;
-    hipLaunchKernelGGL(k_tr_ptr, dim3((int)gp), dim3(TPB), 0, st, b->hdr, b->tr_key[0], b->tr_ptr, hist[0],
-                       (passes & 1) ? total : 0);
+    hipLaunchKernelGGL(k_tr_ptr, dim3((int)gp), dim3(TPB), 0, st, count_ptr, nkeys_ptr, (int)nkeys_cap, key[0], ptr_out,
+                       hist[0], (pl.passes & 1) ? pl.total : 0);
     DN_LAUNCH_CHECK("k_tr_ptr");
+    return DN_OK;
+}
+
+int64_t dn_transpose_index_hist_words(const dn_batch* b)
+{
+    return dn_sort_hist_words(dn_sort_make_plan(b->cap_nodes, b->cap_slots));
+}
+
+int dn_launch_transpose_index(dn_batch* b, int need_all, hipStream_t st)
+{
+    if (b->tr_serial == b->sample_serial && (b->tr_covers_all || !need_all)) return DN_OK;
+    const dn_sort_plan pl = dn_sort_make_plan(b->cap_nodes, b->cap_slots);
+    if (dn_sort_hist_words(pl) > b->tr_hist_words) return dn_fail(DN_ECAPACITY, "transpose index: histogram space");
+    dn_prof_scope ps("transpose_index", 0, st);             // the whole sort counts as one step
+    int64_t g = (b->cap_slots + TPB - 1) / TPB;
+    if (g > 2048) g = 2048;
+    if (g < 1) g = 1;
+    const int src = pl.passes & 1;
+    hipLaunchKernelGGL(k_tr_init, dim3((int)g), dim3(TPB), 0, st, b->hdr, need_all, b->k, b->nbr_offsets, b->repr_map,
+                       b->tr_key[src], b->tr_val[src], (1 << pl.bits) - 1, pl.nblocks, b->tr_hist);
+    DN_LAUNCH_CHECK("k_tr_init");
+    const int rc = dn_sort_pairs_run(pl, b->hdr + HDR_TR_COUNT, b->tr_key, b->tr_val, b->tr_hist, b->hdr + HDR_N,
+                                     b->cap_nodes, b->tr_ptr, st);
+    if (rc != DN_OK) return rc;
     b->tr_serial = b->sample_serial;
     b->tr_covers_all = need_all ? 1 : 0;
     return DN_OK;

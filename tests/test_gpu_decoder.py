@@ -1,0 +1,132 @@
+"""GPU parity of the DistMult decoder (distmult_forward / distmult_backward through the C ABI) against
+oracle/distmult.py in its bf16 mode: positives, negatives' scores, per-edge loss, dH and dR within 1e-4 of
+the oracle row's L2 norm; gradients bit-identical from run to run."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2202_02365_amd as dn
+from workloads import decoder_inputs
+from gpu_harness import row_rel_err
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-4
+
+
+def run_decoder(n_rows, num_rel, dim, n_edges, chunk, num_neg, seed=6, inputs=None, max_edges=None, dec=None):
+    dev = torch.device("cuda:0")
+    H, R, src, rel, dst, neg = inputs if inputs is not None else decoder_inputs(n_rows, num_rel, dim, n_edges, chunk,
+                                                                              num_neg, seed)
+    if dec is None:
+        dec = dn.Decoder(max_edges or n_edges, chunk, num_neg, dim, n_rows, num_rel)
+    t = [torch.from_numpy(np.ascontiguousarray(a)).to(dev) for a in (H, R, src, rel, dst, neg)]
+    pos = torch.empty(n_edges, device=dev)
+    loss = torch.empty(n_edges, device=dev)
+    dn.distmult_forward(dec, *t, pos, loss)
+    dH = torch.full((n_rows, dim), float("nan"), device=dev)
+    dR = torch.full((num_rel, dim), float("nan"), device=dev)
+    dn.distmult_backward(dec, dH, dR)
+    torch.cuda.synchronize()
+    got = dict(pos=pos.cpu().numpy(), loss=loss.cpu().numpy(), dH=dH.cpu().numpy(), dR=dR.cpu().numpy(),
+               neg_dst=dec.scores(0).cpu().numpy(), neg_src=dec.scores(1).cpu().numpy(), status=dec.status())
+    return got, (H, R, src, rel, dst, neg), dec
+
+
+def check(got, inputs, chunk, label=""):
+    H, R, src, rel, dst, neg = inputs
+    st = oracle.distmult_forward(H, R, src, rel, dst, neg, chunk, mode="bf16")
+    odH, odR = oracle.distmult_backward(st)
+    assert got["status"] == 0
+    errs = {
+        # one-element "rows": the positive and the loss are compared against the scale of the edge's score row
+        "pos": float(np.max(np.abs(got["pos"] - st.pos) / np.sqrt(st.pos ** 2 + (st.neg_dst ** 2).sum(axis=1)))),
+        "loss": float(np.max(np.abs(got["loss"] - st.loss) / np.maximum(np.abs(st.loss), 1.0))),
+        "neg_dst": row_rel_err(got["neg_dst"], st.neg_dst),
+        "neg_src": row_rel_err(got["neg_src"], st.neg_src),
+        "dH": row_rel_err(got["dH"], odH),
+        "dR": row_rel_err(got["dR"], odR),
+    }
+    print(label, {k: float("%.2e" % v) for k, v in errs.items()})
+    bad = {k: v for k, v in errs.items() if not v <= TOL}
+    assert not bad, bad
+    # rows nothing contributes to are exactly zero
+    used = np.zeros(H.shape[0], bool)
+    used[src] = used[dst] = True
+    used[neg.ravel()] = True
+    assert np.all(got["dH"][~used] == 0)
+    used_r = np.zeros(R.shape[0], bool)
+    used_r[rel] = True
+    assert np.all(got["dR"][~used_r] == 0)
+
+
+@pytest.mark.parametrize("n_rows,num_rel,dim,n_edges,chunk,num_neg", [
+    (700, 11, 100, 530, 200, 150),        # three chunks, ragged last one, padded tiles in every dimension
+    (300, 5, 64, 128, 128, 128),          # everything a whole tile
+    (900, 40, 130, 1000, 333, 70),        # dim above one 128 block, few negatives
+    (50, 3, 8, 7, 3, 2),                  # tiny
+    (4000, 1000, 100, 2500, 1000, 1000),  # the workload's chunk shape
+])
+def test_decoder_parity(n_rows, num_rel, dim, n_edges, chunk, num_neg):
+    got, inputs, _ = run_decoder(n_rows, num_rel, dim, n_edges, chunk, num_neg)
+    check(got, inputs, chunk, "decoder %s" % ((n_rows, num_rel, dim, n_edges, chunk, num_neg),))
+
+
+def test_decoder_hub_node_and_single_relation():
+    # every edge leaves one node and carries one relation: the long-segment reduction path
+    H, R, src, rel, dst, neg = decoder_inputs(600, 4, 100, 1500, 500, 300, seed=8)
+    src[:] = 17
+    rel[:] = 2
+    neg[:, ::3] = 17
+    got, inputs, _ = run_decoder(600, 4, 100, 1500, 500, 300, inputs=(H, R, src, rel, dst, neg))
+    check(got, inputs, 500, "hub")
+
+
+def test_decoder_reuse_with_smaller_batch_and_determinism():
+    a, inputs, dec = run_decoder(2000, 50, 100, 1800, 600, 400, seed=9)
+    check(a, inputs, 600, "first")
+    # a smaller batch through the same decoder: nothing of the larger one may leak into it
+    small = decoder_inputs(2000, 50, 100, 650, 600, 400, seed=10)
+    b, _, _ = run_decoder(2000, 50, 100, 650, 600, 400, inputs=small, dec=dec)
+    check(b, small, 600, "second, smaller")
+    # and the first batch again: bit-identical gradients
+    c, _, _ = run_decoder(2000, 50, 100, 1800, 600, 400, inputs=inputs, dec=dec)
+    for k in ("pos", "loss", "dH", "dR", "neg_dst", "neg_src"):
+        assert np.array_equal(a[k].view(np.uint32), c[k].view(np.uint32)), k
+
+
+def test_decoder_flags_bad_indices_without_leaving_bounds():
+    H, R, src, rel, dst, neg = decoder_inputs(300, 6, 32, 200, 64, 50, seed=11)
+    src[3] = 300          # one past the last row
+    dst[10] = -1
+    rel[20] = 6
+    neg[1, 4] = 1 << 30
+    got, _, dec = run_decoder(300, 6, 32, 200, 64, 50, inputs=(H, R, src, rel, dst, neg))
+    assert got["status"] == 3
+    assert np.all(np.isfinite(got["dH"])) and np.all(np.isfinite(got["dR"])) and np.all(np.isfinite(got["loss"]))
+    # the edges with valid indices only: same result as a batch in which the bad ones are replaced by zero rows
+    # is not claimed; what is claimed is that valid input afterwards is handled normally and the flag clears
+    good = decoder_inputs(300, 6, 32, 200, 64, 50, seed=12)
+    again, _, _ = run_decoder(300, 6, 32, 200, 64, 50, inputs=good, dec=dec)
+    check(again, good, 64, "after bad indices")
+
+
+def test_decoder_capacity_errors():
+    dec = dn.Decoder(100, 50, 20, 16, 64, 3)
+    dev = torch.device("cuda:0")
+    H, R, src, rel, dst, neg = [torch.from_numpy(a).to(dev) for a in decoder_inputs(64, 3, 16, 150, 50, 20)]
+    pos, loss = torch.empty(150, device=dev), torch.empty(150, device=dev)
+    with pytest.raises(dn.DenseError):
+        dn.distmult_forward(dec, H, R, src, rel, dst, neg, pos, loss)         # 150 edges > 100
+    fresh = dn.Decoder(10, 5, 4, 16, 64, 3)
+    fresh._keep = (torch.empty((64, 16), device=dev),)
+    with pytest.raises(dn.DenseError) as err:
+        dn.distmult_backward(fresh, torch.empty((64, 16), device=dev), torch.empty((3, 16), device=dev))
+    assert err.value.code == -4                                               # no forward yet
+
+
+def test_decoder_full_size_workload_shape():
+    """The link-prediction workload's decoder shape: 50,000 edges in 50 chunks of 1,000 with 1,000 shared negatives
+    each, 100-dim representations of 150,000 target rows, 1,000 Zipf(1.1) relation types."""
+    got, inputs, _ = run_decoder(150_000, 1000, 100, 50_000, 1000, 1000, seed=13)
+    check(got, inputs, 1000, "full size")

@@ -83,3 +83,21 @@ def softmax_xent_grad(logits: np.ndarray, labels: np.ndarray) -> np.ndarray:
     p /= p.sum(axis=1, keepdims=True)
     p[np.arange(len(labels)), labels] -= 1.0
     return (p / len(labels)).astype(np.float32)
+
+
+def decoder_inputs(n_rows: int, num_rel: int, dim: int, n_edges: int, chunk: int, num_neg: int, seed: int = 6,
+                   zipf_exponent: float = 1.1, scale: float = 0.5):
+    """Inputs of a link-prediction decoder in the shape of the Freebase86M-like workload: node representations
+    H [n_rows x dim] (N(0, scale^2)), relation embeddings R [num_rel x dim] (N(0,1)), edges as (row of H, relation,
+    row of H) with uniform endpoints and relation ids drawn from a Zipf(zipf_exponent) law over num_rel types,
+    and per chunk of `chunk` edges one list of num_neg uniform negative rows."""
+    rng = np.random.default_rng([seed, n_rows, n_edges])
+    H = (scale * rng.standard_normal((n_rows, dim))).astype(np.float32)
+    R = rng.standard_normal((num_rel, dim)).astype(np.float32)
+    src = rng.integers(0, n_rows, n_edges).astype(np.int32)
+    dst = rng.integers(0, n_rows, n_edges).astype(np.int32)
+    w = 1.0 / np.arange(1, num_rel + 1, dtype=np.float64) ** zipf_exponent
+    rel = rng.choice(num_rel, size=n_edges, p=w / w.sum()).astype(np.int32)
+    n_chunks = (n_edges + chunk - 1) // chunk
+    neg = rng.integers(0, n_rows, (n_chunks, num_neg)).astype(np.int32)
+    return H, R, src, rel, dst, neg
