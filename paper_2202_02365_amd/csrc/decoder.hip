@@ -41,9 +41,10 @@ struct dn_decoder {
     // workspace
     int32_t* hdr;
     dn_bf16 *Q, *Qt, *En, *Ent, *P, *Pt;
-    float *S, *lse, *dpos, *dQ, *dEn, *rows;
+    float *S, *lse, *dpos, *dQ, *dEn, *rows, *long_partial, *pmax, *psum;
     int32_t *nkey[2], *nval[2], *nptr, *nhist;
     int32_t *rkey[2], *rval[2], *rptr, *rhist;
+    int32_t* long_seg;                // per 64-row block of a sorted index: long segment starting there + 1, or 0
     dn_sort_plan nplan, rplan;
     // inputs of the last forward (borrowed)
     const float *H, *R;
@@ -150,9 +151,11 @@ struct DmGemm {
     int b_wrap_chunks;      // B repeats after this many units (WRAP only)
     float* C; int64_t ldc, stride_c;
     int ncols;              // columns stored (rows: every row of the tile; C is padded to whole tiles)
+    // LSE epilogue: per row and column tile, max and sum of exp(x - max) over the tile's columns below lse_cols
+    float* pmax; float* psum; int lse_cols;
 };
 
-template <bool WRAP>
+template <bool WRAP, bool LSE>
 __global__ __launch_bounds__(TPB, 2) void k_dm_gemm(DmGemm g)
 {
     const int z = blockIdx.z;
@@ -176,17 +179,78 @@ __global__ __launch_bounds__(TPB, 2) void k_dm_gemm(DmGemm g)
                 C[(int64_t)m * g.ldc + n] = acc[i][j][e];
             }
         }
+    if (LSE) {
+        // per row: max and sum of exp(x - max) over this tile's valid columns.  A row's 128 columns sit in the 32
+        // lanes of one half-wave (two registers each) of the two waves wn = 0, 1.  The 16 rows a lane holds
+        // (for one i) are reduced over the half-wave by a butterfly that halves the number of rows a lane
+        // carries at every step, so that 32 lane exchanges serve 16 rows; a (max, sum) pair merges as
+        // max = larger max, sum = sum_of_larger + sum_of_smaller * exp(smaller max - larger max).
+        __shared__ float s_max[2][BM], s_sum[2][BM];
+        const int n0 = col0 + wn * 64 + (lane & 31), n1 = n0 + 32;
+        const bool ok0 = n0 < g.lse_cols, ok1 = n1 < g.lse_cols;
+        auto merge = [](float& m, float& sm, const float m2, const float s2) {
+            const float big = fmaxf(m, m2), small = fminf(m, m2);
+            const float s_big = m >= m2 ? sm : s2, s_small = m >= m2 ? s2 : sm;
+            sm = s_big + (small > -INFINITY ? s_small * __expf(small - big) : 0.f);   // hardware exp2: error ~1e-7 |x|, far below the sums' own
+            m = big;
+        };
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            float pm[16], ps[16];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const float v0 = ok0 ? acc[i][0][e] : -INFINITY, v1 = ok1 ? acc[i][1][e] : -INFINITY;
+                pm[e] = v0;
+                ps[e] = ok0 ? 1.f : 0.f;
+                merge(pm[e], ps[e], v1, ok1 ? 1.f : 0.f);
+            }
+#pragma unroll
+            for (int half = 8; half >= 1; half >>= 1) {
+                const int sft = half * 2;                       // lane bit that decides which half this lane keeps
+                const bool upper = (lane & sft) != 0;
+#pragma unroll
+                for (int k = 0; k < half; ++k) {
+                    const float send_m = upper ? pm[k] : pm[k + half], send_s = upper ? ps[k] : ps[k + half];
+                    float keep_m = upper ? pm[k + half] : pm[k], keep_s = upper ? ps[k + half] : ps[k];
+                    const float rm = __shfl_xor(send_m, sft, 64), rs = __shfl_xor(send_s, sft, 64);
+                    merge(keep_m, keep_s, rm, rs);
+                    pm[k] = keep_m;
+                    ps[k] = keep_s;
+                }
+            }
+            {   // last lane bit: both partners end with the full result
+                const float rm = __shfl_xor(pm[0], 1, 64), rs = __shfl_xor(ps[0], 1, 64);
+                merge(pm[0], ps[0], rm, rs);
+            }
+            if ((lane & 1) == 0) {
+                const int e = (lane & 31) >> 1;                 // the register index whose row this lane ended up with
+                const int ml = wm * 64 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                s_max[wn][ml] = pm[0];
+                s_sum[wn][ml] = ps[0];
+            }
+        }
+        __syncthreads();
+        if (t < BM) {
+            const float m0 = s_max[0][t], m1 = s_max[1][t];
+            const float mx = fmaxf(m0, m1);
+            float sm = 0.f;
+            if (mx > -INFINITY) sm = (m0 > -INFINITY ? s_sum[0][t] * expf(m0 - mx) : 0.f) + (m1 > -INFINITY ? s_sum[1][t] * expf(m1 - mx) : 0.f);
+            const int64_t idx = ((int64_t)z * (gridDim.y * BM) + row0 + t) * gridDim.x + blockIdx.x;
+            g.pmax[idx] = mx;
+            g.psum[idx] = sm;
+        }
+    }
 }
 
 // ------------------------------------------------------------------ softmax over [pos, negatives]
-// One wave per edge, both sides: lse[side][e], loss[e] = (lse0 - pos) + (lse1 - pos),
-// dpos[e] = (exp(pos - lse0) - 1) + (exp(pos - lse1) - 1).
-__global__ __launch_bounds__(TPB_) void k_dm_lse(const float* __restrict__ S, const float* __restrict__ pos, int B, int C,
-                                                 int chunk, int Nn, int cpad, int npad, float* __restrict__ lse,
-                                                 float* __restrict__ loss, float* __restrict__ dpos, int32_t* __restrict__ hdr)
+// One thread per edge, both sides: combines the score contraction's per-tile (max, sum) pairs with the
+// positive: lse[side][e], loss[e] = (lse0 - pos) + (lse1 - pos), dpos[e] = (exp(pos - lse0) - 1) + (exp(pos - lse1) - 1).
+__global__ __launch_bounds__(TPB_) void k_dm_lse(const float* __restrict__ pmax, const float* __restrict__ psum,
+                                                 const float* __restrict__ pos, int B, int C, int chunk, int cpad, int ntn,
+                                                 float* __restrict__ lse, float* __restrict__ loss, float* __restrict__ dpos,
+                                                 int32_t* __restrict__ hdr)
 {
-    const int e = blockIdx.x * (TPB_ / 64) + (threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63;
+    const int e = blockIdx.x * TPB_ + threadIdx.x;
     if (blockIdx.x == 0 && threadIdx.x == 0) {      // flags raised by the operand kernel of this call become the status
         hdr[DM_HDR_STATUS] = hdr[DM_HDR_STATUS_ACC];
         hdr[DM_HDR_STATUS_ACC] = 0;
@@ -196,20 +260,19 @@ __global__ __launch_bounds__(TPB_) void k_dm_lse(const float* __restrict__ S, co
     const float p = pos[e];
     float l[2];
     for (int side = 0; side < 2; ++side) {
-        const float* row = S + (((int64_t)side * C + q) * cpad + i) * npad;
+        const int64_t base = (((int64_t)side * C + q) * cpad + i) * ntn;
         float m = p;
-        for (int n = lane; n < Nn; n += 64) m = fmaxf(m, row[n]);
-        for (int s = 32; s > 0; s >>= 1) m = fmaxf(m, __shfl_xor(m, s, 64));
-        float sum = 0.f;
-        for (int n = lane; n < Nn; n += 64) sum += expf(row[n] - m);
-        for (int s = 32; s > 0; s >>= 1) sum += __shfl_xor(sum, s, 64);
-        l[side] = m + logf(sum + expf(p - m));
-        if (lane == 0) lse[(int64_t)side * B + e] = l[side];
+        for (int tn = 0; tn < ntn; ++tn) m = fmaxf(m, pmax[base + tn]);
+        float sum = expf(p - m);
+        for (int tn = 0; tn < ntn; ++tn) {
+            const float pm = pmax[base + tn];
+            if (pm > -INFINITY) sum += psum[base + tn] * expf(pm - m);
+        }
+        l[side] = m + logf(sum);
+        lse[(int64_t)side * B + e] = l[side];
     }
-    if (lane == 0) {
-        loss[e] = (l[0] - p) + (l[1] - p);
-        dpos[e] = (expf(p - l[0]) - 1.f) + (expf(p - l[1]) - 1.f);
-    }
+    loss[e] = (l[0] - p) + (l[1] - p);
+    dpos[e] = (expf(p - l[0]) - 1.f) + (expf(p - l[1]) - 1.f);
 }
 
 // P = exp(S - lse) for valid (edge, negative) pairs, 0 elsewhere, as two bf16 terms; row-major
@@ -245,15 +308,29 @@ __global__ __launch_bounds__(TPB_) void k_dm_probs(const float* __restrict__ S, 
     }
 }
 
+// One atomic per distinct digit among a wave's active lanes (all of a wave's elements lie in one tile):
+// frequent keys (a popular relation, a hub node) would otherwise serialise on a few counters.
+__device__ __forceinline__ void hist_add_wave(int32_t* __restrict__ hist, int digit, int bits, int nblocks, int tile)
+{
+    const int lane = threadIdx.x & 63;
+    uint64_t mask = __ballot(1);
+    for (int bit = 0; bit < bits; ++bit) {
+        const uint64_t bal = __ballot((digit >> bit) & 1);
+        mask &= ((digit >> bit) & 1) ? bal : ~bal;
+    }
+    if ((mask & ((1ull << lane) - 1ull)) == 0) atomicAdd(&hist[digit * nblocks + tile], __popcll(mask));
+}
+
 // ------------------------------------------------------------------ gradient collection
 // Index entries: [0, B) edge e as a source, [B, 2B) edge e as a destination, [2B, 2B + C*Nn) negative
 // slot (q, n); key = the row of H the entry's gradient goes to (out-of-range ids go to the extra key n_rows).
 __global__ __launch_bounds__(TPB_) void k_dm_node_index_init(const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
                                                              const int32_t* __restrict__ neg, int B, int n_neg, int n_rows,
                                                              int32_t* __restrict__ key, int32_t* __restrict__ val,
-                                                             int radix_mask, int nblocks, int32_t* __restrict__ hist,
+                                                             int radix_bits, int nblocks, int32_t* __restrict__ hist,
                                                              int32_t* __restrict__ hdr)
 {
+    const int radix_mask = (1 << radix_bits) - 1;
     const int total = 2 * B + n_neg;
     const int stride = gridDim.x * blockDim.x;
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
@@ -261,23 +338,24 @@ __global__ __launch_bounds__(TPB_) void k_dm_node_index_init(const int32_t* __re
         if ((unsigned)kv >= (unsigned)n_rows) kv = n_rows;
         key[i] = kv;
         val[i] = i;
-        atomicAdd(&hist[(kv & radix_mask) * nblocks + i / DN_SORT_TILE], 1);
+        hist_add_wave(hist, kv & radix_mask, radix_bits, nblocks, i / DN_SORT_TILE);
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) hdr[DM_HDR_NODE_COUNT] = total;
 }
 
 __global__ __launch_bounds__(TPB_) void k_dm_rel_index_init(const int32_t* __restrict__ rel, int B, int num_rel,
                                                             int32_t* __restrict__ key, int32_t* __restrict__ val,
-                                                            int radix_mask, int nblocks, int32_t* __restrict__ hist,
+                                                            int radix_bits, int nblocks, int32_t* __restrict__ hist,
                                                             int32_t* __restrict__ hdr)
 {
+    const int radix_mask = (1 << radix_bits) - 1;
     const int stride = gridDim.x * blockDim.x;
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < B; i += stride) {
         int kv = rel[i];
         if ((unsigned)kv >= (unsigned)num_rel) kv = num_rel;
         key[i] = kv;
         val[i] = i;
-        atomicAdd(&hist[(kv & radix_mask) * nblocks + i / DN_SORT_TILE], 1);
+        hist_add_wave(hist, kv & radix_mask, radix_bits, nblocks, i / DN_SORT_TILE);
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) hdr[DM_HDR_REL_COUNT] = B;
 }
@@ -345,45 +423,100 @@ __global__ __launch_bounds__(TPB_) void k_dm_rel_rows(DmGrad g, const int32_t* _
     for (int j = sl; j < g.d; j += 32) out[j] = ok ? dp * (hs[j] * hd[j]) + dq0[j] * hs[j] + dq1[j] * hd[j] : 0.f;
 }
 
-// out[s][:] = sum of rows[ptr[s] .. ptr[s+1]) in ascending order.  Short segments: 32 lanes per
-// segment.  Segments longer than LONG_SEG are left to k_dm_segment_sum_long (one workgroup each:
-// 8 lane groups take the rows i = g, g+8, ... in order, their partial sums are added in order of g).
+// out[s][:] = sum of rows[ptr[s] .. ptr[s+1]) in a fixed order.  Segments of at most LONG_SEG rows: 32 lanes
+// per segment, ascending order.  Longer segments (a hub node, a frequent relation) are cut into LONG_PARTS
+// slices, one workgroup each: the workgroup's 8 lane groups take the slice's rows g, g+8, ... in order and
+// their sums are added in order of g; a second kernel adds the slices' sums in order.  A long segment is
+// registered under the 64-row block its first row lies in (no two long segments start in one block):
+// long_seg[block] = segment + 1, written by the short-segment kernel, reset to 0 by the last one, and the
+// slices' partial sums are kept under the same block number.
 constexpr int LONG_SEG = 64;
+constexpr int LONG_PARTS = 64;
 __global__ __launch_bounds__(TPB_) void k_dm_segment_sum(const float* __restrict__ rows, const int32_t* __restrict__ ptr,
-                                                         int nseg, int d, float* __restrict__ out, int64_t ldo)
+                                                         int nseg, int d, float* __restrict__ out, int64_t ldo,
+                                                         int32_t* __restrict__ long_seg)
 {
     const int s = (blockIdx.x * TPB_ + threadIdx.x) >> 5, sl = threadIdx.x & 31;
     if (s >= nseg) return;
     const int lo = ptr[s], hi = ptr[s + 1];
-    if (hi - lo > LONG_SEG) return;
+    if (hi - lo > LONG_SEG) {
+        if (sl == 0) long_seg[lo / LONG_SEG] = s + 1;
+        return;
+    }
     for (int j = sl; j < d; j += 32) {
         float acc = 0.f;
         for (int i = lo; i < hi; ++i) acc += rows[(int64_t)i * d + j];
         out[(int64_t)s * ldo + j] = acc;
     }
 }
-__global__ __launch_bounds__(TPB_) void k_dm_segment_sum_long(const float* __restrict__ rows, const int32_t* __restrict__ ptr,
-                                                              int d, float* __restrict__ out, int64_t ldo)
+
+__global__ __launch_bounds__(TPB_) void k_dm_long_partial(const float* __restrict__ rows, const int32_t* __restrict__ ptr,
+                                                          const int32_t* __restrict__ long_seg, int d,
+                                                          float* __restrict__ partial)
 {
     __shared__ float part[TPB_ / 32][32];
-    const int s = blockIdx.x;
+    constexpr int G = TPB_ / 32;
+    const int c = blockIdx.x, p = blockIdx.y;
+    const int s = long_seg[c] - 1;
+    if (s < 0) return;
     const int lo = ptr[s], hi = ptr[s + 1];
-    if (hi - lo <= LONG_SEG) return;
+    const int per = (hi - lo + LONG_PARTS - 1) / LONG_PARTS;
+    const int begin = lo + p * per, end = min(hi, begin + per);
     const int grp = threadIdx.x >> 5, sl = threadIdx.x & 31;
+    float* dst = partial + ((int64_t)c * LONG_PARTS + p) * d;
     for (int j0 = 0; j0 < d; j0 += 32) {
         const int j = j0 + sl;
         float acc = 0.f;
-        if (j < d)
-            for (int i = lo + grp; i < hi; i += TPB_ / 32) acc += rows[(int64_t)i * d + j];
+        if (j < d) {
+            int i = begin + grp;
+            for (; i + 3 * G < end; i += 4 * G) {          // four rows in flight, added in order
+                const float a0 = rows[(int64_t)i * d + j], a1 = rows[(int64_t)(i + G) * d + j];
+                const float a2 = rows[(int64_t)(i + 2 * G) * d + j], a3 = rows[(int64_t)(i + 3 * G) * d + j];
+                acc += a0; acc += a1; acc += a2; acc += a3;
+            }
+            for (; i < end; i += G) acc += rows[(int64_t)i * d + j];
+        }
         part[grp][sl] = acc;
         __syncthreads();
         if (grp == 0 && j < d) {
             float tot = part[0][sl];
-            for (int w = 1; w < TPB_ / 32; ++w) tot += part[w][sl];
-            out[(int64_t)s * ldo + j] = tot;
+            for (int w = 1; w < G; ++w) tot += part[w][sl];
+            dst[j] = tot;
         }
         __syncthreads();
     }
+}
+
+__global__ __launch_bounds__(64) void k_dm_long_final(int32_t* __restrict__ long_seg, int d, const float* __restrict__ partial,
+                                                      float* __restrict__ out, int64_t ldo)
+{
+    const int c = blockIdx.x;
+    const int s = long_seg[c] - 1;
+    if (s < 0) return;
+    const float* src = partial + (int64_t)c * LONG_PARTS * d;
+    for (int j = threadIdx.x; j < d; j += 64) {
+        float tot = src[j];
+        for (int p = 1; p < LONG_PARTS; ++p) tot += src[(int64_t)p * d + j];
+        out[(int64_t)s * ldo + j] = tot;
+    }
+    __syncthreads();                              // every lane has read the entry before it is reset for the next call
+    if (threadIdx.x == 0) long_seg[c] = 0;
+}
+
+int launch_segment_sums(const float* rows, const int32_t* ptr, int nseg, int total_rows, int d, float* partial,
+                        int32_t* long_seg, float* out, int64_t ldo, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_dm_segment_sum, dim3((int)(((int64_t)nseg * 32 + TPB_ - 1) / TPB_)), dim3(TPB_), 0, st, rows, ptr, nseg, d,
+                       out, ldo, long_seg);
+    DN_LAUNCH_CHECK("k_dm_segment_sum");
+    const int cand = (total_rows + LONG_SEG - 1) / LONG_SEG;
+    if (cand > 0) {
+        hipLaunchKernelGGL(k_dm_long_partial, dim3(cand, LONG_PARTS), dim3(TPB_), 0, st, rows, ptr, long_seg, d, partial);
+        DN_LAUNCH_CHECK("k_dm_long_partial");
+        hipLaunchKernelGGL(k_dm_long_final, dim3(cand), dim3(64), 0, st, long_seg, d, partial, out, ldo);
+        DN_LAUNCH_CHECK("k_dm_long_final");
+    }
+    return DN_OK;
 }
 
 int fill_decoder(dn_decoder* d, int64_t max_edges, int32_t chunk, int32_t num_neg, int32_t dim, int64_t max_rows,
@@ -417,11 +550,14 @@ void carve_decoder(dn_decoder* d, dn_carver& c)
     d->hdr = c.take<int32_t>(DM_HDR_WORDS);
     d->nhist = c.take<int32_t>(dn_sort_hist_words(d->nplan));
     d->rhist = c.take<int32_t>(dn_sort_hist_words(d->rplan));
+    d->long_seg = c.take<int32_t>(d->max_entries / LONG_SEG + 2);
     d->Q = c.take<dn_bf16>(2 * C * d->cpad * d->kp);
     d->Qt = c.take<dn_bf16>(2 * C * (int64_t)d->np * d->cpad);
     d->En = c.take<dn_bf16>(C * d->npad * d->kp);
     d->Ent = c.take<dn_bf16>(C * (int64_t)d->np * d->npad);
     d->S = c.take<float>(2 * C * (int64_t)d->cpad * d->npad);
+    d->pmax = c.take<float>(2 * C * (int64_t)d->cpad * (d->npad / BN));
+    d->psum = c.take<float>(2 * C * (int64_t)d->cpad * (d->npad / BN));
     d->lse = c.take<float>(2 * d->max_edges);
     d->dpos = c.take<float>(d->max_edges);
     d->P = c.take<dn_bf16>(2 * C * (int64_t)d->cpad * 2 * d->npad);
@@ -429,6 +565,7 @@ void carve_decoder(dn_decoder* d, dn_carver& c)
     d->dQ = c.take<float>(2 * C * (int64_t)d->cpad * d->np);
     d->dEn = c.take<float>(2 * C * (int64_t)d->npad * d->np);
     d->rows = c.take<float>(d->max_entries * d->dim);
+    d->long_partial = c.take<float>((d->max_entries / LONG_SEG + 2) * LONG_PARTS * d->dim);
     for (int i = 0; i < 2; ++i) {
         d->nkey[i] = c.take<int32_t>(d->max_entries);
         d->nval[i] = c.take<int32_t>(d->max_entries);
@@ -443,8 +580,9 @@ int launch_gemm(const DmGemm& g, bool wrap, int mtiles, int ntiles, int batch, h
 {
     dn_prof_scope ps(tag, 0, st);
     const dim3 grid(ntiles, mtiles, batch);
-    if (wrap) hipLaunchKernelGGL(k_dm_gemm<true>, grid, dim3(TPB), 0, st, g);
-    else hipLaunchKernelGGL(k_dm_gemm<false>, grid, dim3(TPB), 0, st, g);
+    if (wrap) hipLaunchKernelGGL((k_dm_gemm<true, false>), grid, dim3(TPB), 0, st, g);
+    else if (g.pmax) hipLaunchKernelGGL((k_dm_gemm<false, true>), grid, dim3(TPB), 0, st, g);
+    else hipLaunchKernelGGL((k_dm_gemm<false, false>), grid, dim3(TPB), 0, st, g);
     DN_LAUNCH_CHECK(tag);
     return DN_OK;
 }
@@ -525,12 +663,13 @@ int distmult_forward(dn_decoder* d, const float* d_H, int64_t ldh, int64_t n_row
     g.B = d->En; g.ldb = d->kp; g.stride_b = (int64_t)d->npad * d->kp; g.b_mod = C;
     g.kchunks = d->kp / BK; g.b_wrap_chunks = 1;
     g.C = d->S; g.ldc = d->npad; g.stride_c = (int64_t)d->cpad * d->npad; g.ncols = d->npad;
+    g.pmax = d->pmax; g.psum = d->psum; g.lse_cols = d->num_neg;
     int rc = launch_gemm(g, false, d->cpad / BM, d->npad / BN, 2 * C, st, "dm_gemm_scores");
     if (rc) return rc;
     {
         dn_prof_scope ps("dm_lse", 0, st);
-        hipLaunchKernelGGL(k_dm_lse, dim3(blocks_for(B, TPB_ / 64)), dim3(TPB_), 0, st, d->S, d_pos, B, C, d->chunk,
-                           d->num_neg, d->cpad, d->npad, d->lse, d_loss, d->dpos, d->hdr);
+        hipLaunchKernelGGL(k_dm_lse, dim3(blocks_for(B, TPB_)), dim3(TPB_), 0, st, d->pmax, d->psum, d_pos, B, C, d->chunk,
+                           d->cpad, d->npad / BN, d->lse, d_loss, d->dpos, d->hdr);
         DN_LAUNCH_CHECK("k_dm_lse");
     }
     return DN_OK;
@@ -561,6 +700,7 @@ int distmult_backward(dn_decoder* d, float* d_dH, int64_t ld_dh, float* d_dR, in
             DN_LAUNCH_CHECK("k_dm_transpose(E)");
         }
         DmGemm g;
+        g.pmax = nullptr; g.psum = nullptr; g.lse_cols = 0;
         // dQ[z] = P[z] (two terms along the reduction) * E[q] : B operand = E^T [np x npad], repeated per term
         g.A = d->P; g.lda = 2 * d->npad; g.stride_a = (int64_t)d->cpad * 2 * d->npad;
         g.B = d->Ent; g.ldb = d->npad; g.stride_b = (int64_t)d->np * d->npad; g.b_mod = C;
@@ -588,7 +728,7 @@ int distmult_backward(dn_decoder* d, float* d_dH, int64_t ld_dh, float* d_dR, in
         if (gb < 1) gb = 1;
         const int srcbuf = d->nplan.passes & 1;
         hipLaunchKernelGGL(k_dm_node_index_init, dim3(gb), dim3(TPB_), 0, st, d->src, d->dst, d->neg, B, n_neg, n_rows,
-                           d->nkey[srcbuf], d->nval[srcbuf], (1 << d->nplan.bits) - 1, d->nplan.nblocks, d->nhist, d->hdr);
+                           d->nkey[srcbuf], d->nval[srcbuf], d->nplan.bits, d->nplan.nblocks, d->nhist, d->hdr);
         DN_LAUNCH_CHECK("k_dm_node_index_init");
         const int rc = dn_sort_pairs_run(d->nplan, d->hdr + DM_HDR_NODE_COUNT, d->nkey, d->nval, d->nhist, nullptr, n_rows,
                                          d->nptr, st);
@@ -601,11 +741,8 @@ int distmult_backward(dn_decoder* d, float* d_dH, int64_t ld_dh, float* d_dR, in
                                d->rows);
             DN_LAUNCH_CHECK("k_dm_node_rows");
         }
-        hipLaunchKernelGGL(k_dm_segment_sum, dim3(blocks_for((int64_t)n_rows * 32, TPB_)), dim3(TPB_), 0, st, d->rows, d->nptr,
-                           n_rows, d->dim, d_dH, ld_dh);
-        DN_LAUNCH_CHECK("k_dm_segment_sum(dH)");
-        hipLaunchKernelGGL(k_dm_segment_sum_long, dim3(n_rows), dim3(TPB_), 0, st, d->rows, d->nptr, d->dim, d_dH, ld_dh);
-        DN_LAUNCH_CHECK("k_dm_segment_sum_long(dH)");
+        const int rc = launch_segment_sums(d->rows, d->nptr, n_rows, total, d->dim, d->long_partial, d->long_seg, d_dH, ld_dh, st);
+        if (rc) return rc;
     }
     // ---- dR: edges sorted by relation
     {
@@ -615,7 +752,7 @@ int distmult_backward(dn_decoder* d, float* d_dH, int64_t ld_dh, float* d_dR, in
         if (gb < 1) gb = 1;
         const int srcbuf = d->rplan.passes & 1;
         hipLaunchKernelGGL(k_dm_rel_index_init, dim3(gb), dim3(TPB_), 0, st, d->rel, B, (int)d->num_rel, d->rkey[srcbuf],
-                           d->rval[srcbuf], (1 << d->rplan.bits) - 1, d->rplan.nblocks, d->rhist, d->hdr);
+                           d->rval[srcbuf], d->rplan.bits, d->rplan.nblocks, d->rhist, d->hdr);
         DN_LAUNCH_CHECK("k_dm_rel_index_init");
         const int rc = dn_sort_pairs_run(d->rplan, d->hdr + DM_HDR_REL_COUNT, d->rkey, d->rval, d->rhist, nullptr, d->num_rel,
                                          d->rptr, st);
@@ -628,11 +765,8 @@ int distmult_backward(dn_decoder* d, float* d_dH, int64_t ld_dh, float* d_dR, in
             hipLaunchKernelGGL(k_dm_rel_rows, dim3(blocks_for((int64_t)B * 32, TPB_)), dim3(TPB_), 0, st, a, d->rval[0], d->rows);
             DN_LAUNCH_CHECK("k_dm_rel_rows");
         }
-        hipLaunchKernelGGL(k_dm_segment_sum, dim3(blocks_for((int64_t)nr * 32, TPB_)), dim3(TPB_), 0, st, d->rows, d->rptr, nr,
-                           d->dim, d_dR, ld_dr);
-        DN_LAUNCH_CHECK("k_dm_segment_sum(dR)");
-        hipLaunchKernelGGL(k_dm_segment_sum_long, dim3(nr), dim3(TPB_), 0, st, d->rows, d->rptr, d->dim, d_dR, ld_dr);
-        DN_LAUNCH_CHECK("k_dm_segment_sum_long(dR)");
+        const int rc = launch_segment_sums(d->rows, d->rptr, nr, B, d->dim, d->long_partial, d->long_seg, d_dR, ld_dr, st);
+        if (rc) return rc;
     }
     return DN_OK;
 }
