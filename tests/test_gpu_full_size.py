@@ -16,6 +16,16 @@ from gpu_harness import assert_dense_equal, row_rel_err, to_dev
 
 pytestmark = pytest.mark.gpu
 TOL = 1e-4
+# Decoder run on the device encoder's output versus oracle decoder run on the oracle encoder's output: the two
+# inputs differ in the last bits (fp32 accumulation order), and where such a difference straddles a bfloat16
+# rounding boundary one operand element of the score contraction moves by a whole bf16 step, 2^-8 = 4e-3
+# relative.  Every score of that edge moves with it, the softmax turns a score change of delta into a relative
+# change of up to delta in the probabilities, and a gradient row is a probability-weighted sum, so single rows
+# can be off by a few bf16 steps of their own scale (measured: 5e-3 on the worst of 150,000 rows, 1.4e-3 on the
+# worst edge's loss).  The bound checked here is four steps, 2^-6.  It is a check that the pieces fit together
+# (index maps, strides, chunking); the decoder's own parity, on identical inputs, is held to 1e-4 in
+# test_gpu_decoder.py, the encoder's here.
+DECODER_CHAIN_TOL = 2.0 ** -6
 
 
 def run_full(cfg, batches, n_targets=None, want_dh0=False, edge_batch=None):
@@ -63,7 +73,35 @@ def run_full(cfg, batches, n_targets=None, want_dh0=False, edge_batch=None):
         dn.sage_forward(model, batch, h0, out)
         st = oracle.sage_forward(d, table[ids].float().cpu().numpy(), params, mode="bf16")
         errs = {"fwd": row_rel_err(out.cpu().numpy(), st.out)}
-        gout = softmax_xent_grad(st.out, class_labels(len(targets), cfg.dims[-1]))
+        if edge_batch is None:
+            gout = softmax_xent_grad(st.out, class_labels(len(targets), cfg.dims[-1]))
+        else:
+            # link prediction: the DistMult decoder scores the encoder's output rows of the edge endpoints and the
+            # shared negatives; its gradient with respect to those rows is the encoder's upstream gradient.
+            # The oracle's decoder gradient feeds both encoders' backward passes (same input on both sides);
+            # the device decoder runs on the device encoder's output and is compared with a tolerance for a
+            # chain of two operators (see the comment at DECODER_CHAIN_TOL).
+            n_edges, chunk, n_neg = edge_batch
+            num_rel = 1000
+            w = 1.0 / np.arange(1, num_rel + 1) ** 1.1
+            rel = rng.choice(num_rel, size=n_edges, p=w / w.sum()).astype(np.int32)
+            R = np.random.default_rng([19, bi]).standard_normal((num_rel, cfg.dims[-1])).astype(np.float32)
+            ost = oracle.distmult_forward(st.out.astype(np.float32), R, ols, rel, old, oln.reshape(-1, n_neg), chunk, mode="bf16")
+            o_dh, o_dr = oracle.distmult_backward(ost)
+            gout = o_dh.astype(np.float32)
+            dec = dn.Decoder(n_edges, chunk, n_neg, cfg.dims[-1], len(targets), num_rel)
+            pos_t, loss_t = torch.empty(n_edges, device=dev), torch.empty(n_edges, device=dev)
+            dn.distmult_forward(dec, out, torch.from_numpy(R).to(dev), ls, torch.from_numpy(rel).to(dev), ld,
+                                ln.view(-1, n_neg), pos_t, loss_t)
+            g_dh = torch.empty_like(out)
+            g_dr = torch.empty((num_rel, cfg.dims[-1]), device=dev)
+            dn.distmult_backward(dec, g_dh, g_dr)
+            assert dec.status() == 0
+            chain = {"dec_loss": float(np.max(np.abs(loss_t.cpu().numpy() - ost.loss) / np.maximum(ost.loss, 1.0))),
+                     "dec_dH": row_rel_err(g_dh.cpu().numpy(), o_dh), "dec_dR": row_rel_err(g_dr.cpu().numpy(), o_dr)}
+            print(cfg.name, "decoder on the encoder's output:", {k: float("%.2e" % v) for k, v in chain.items()})
+            assert all(v <= DECODER_CHAIN_TOL for v in chain.values()), chain
+            del dec
         grads = oracle.sage_backward(st, params, gout, mode="bf16")
         dws = [torch.empty_like(t) for t in to_dev(w_self)]
         dwn = [torch.empty_like(t) for t in to_dev(w_nbr)]
