@@ -75,6 +75,10 @@ void carve_batch(dn_batch* b, Carver& c)
         b->tr_val[i] = c.take<int32_t>(b->cap_slots);
     }
     b->tr_ptr = c.take<int32_t>(b->cap_nodes + 2);
+    b->tr_own = c.take<int32_t>(b->cap_slots);
+    b->tr_inv = c.take<float>(b->cap_slots);
+    b->tr_long_words = b->cap_slots / DN_LONG_GROUP + 2;
+    b->tr_long = c.take<int32_t>(b->tr_long_words);
 }
 
 int fill_model(dn_model* m, const dn_batch* b, int32_t k, const int32_t* dims, int32_t in_dtype)

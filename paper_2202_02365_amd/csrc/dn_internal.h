@@ -51,6 +51,10 @@ struct dn_batch {
     int32_t *node_ids, *nbr_offsets, *nbrs, *repr_map, *slot_owner;
     // transpose index for the backward pass (slots grouped by the input row they read)
     int32_t *tr_key[2], *tr_val[2], *tr_ptr, *tr_hist;
+    int32_t* tr_own;                        // owner (output row) of slot tr_val[0][t]
+    float* tr_inv;                          // 1 / (number of slots of that owner)
+    int32_t* tr_long;                       // [cap_slots / DN_LONG_GROUP + 2] rows read by more than DN_LONG_GROUP slots
+    int64_t tr_long_words;
     int64_t tr_hist_words;
     int32_t n_targets;
     uint64_t sample_serial;                 // bumped by every dense_sample
@@ -161,8 +165,17 @@ constexpr int DN_SORT_TILE = 2048;
 struct dn_sort_plan { int passes, bits, nblocks, total, sblocks; };
 dn_sort_plan dn_sort_make_plan(int64_t key_range, int64_t cap_items);
 int64_t dn_sort_hist_words(const dn_sort_plan& p);
+// Optional by-products of the last kernel, for values that are slot numbers of a DENSE sample (null otherwise):
+// own_out[t] = slot_owner[val[t]], inv_out[t] = 1 / (number of slots of that owner), and
+// long_out[first / DN_LONG_GROUP] = key + 1 for every key whose group of more than DN_LONG_GROUP sorted pairs
+// starts at index `first` (no two such groups start in one block of DN_LONG_GROUP indices; the caller clears
+// long_out beforehand).
+constexpr int DN_LONG_GROUP = 64;
+struct dn_sort_slot_info { const int32_t* slot_owner; const int32_t* nbr_offsets; int32_t* own_out; float* inv_out;
+                           int32_t* long_out; };
 int dn_sort_pairs_run(const dn_sort_plan& pl, const int32_t* count_ptr, int32_t* const key[2], int32_t* const val[2],
-                      int32_t* hist_space, const int32_t* nkeys_ptr, int64_t nkeys_cap, int32_t* ptr_out, hipStream_t st);
+                      int32_t* hist_space, const int32_t* nkeys_ptr, int64_t nkeys_cap, int32_t* ptr_out, hipStream_t st,
+                      const dn_sort_slot_info* info = nullptr);
 int dn_launch_set_weights(dn_model* m, const float* const* ws, const float* const* wn,
                           const float* const* bias, hipStream_t st);
 int dn_launch_forward(dn_model* m, const dn_batch* b, const void* h0, float* out, hipStream_t st);

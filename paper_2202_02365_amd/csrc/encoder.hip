@@ -179,11 +179,12 @@ __global__ __launch_bounds__(TPB) void k_transpose_x_group(const int32_t* __rest
 // row) + sum over the slots that read r, in ascending slot order, of dX_mean[owner] / count[owner].
 // tr_ptr / tr_val: slots grouped by the node_ids position they read, ascending within a group;
 // a layer's slots are those >= its first slot, i.e. a suffix of every group.
-template <int V, int LANES>
+template <int V, int LANES, int ITERS>
 __global__ __launch_bounds__(TPB) void k_aggregate_bwd(const int32_t* __restrict__ hdr, int layer,
                                                        const int32_t* __restrict__ nbr_offsets,
-                                                       const int32_t* __restrict__ slot_owner,
                                                        const int32_t* __restrict__ tr_ptr, const int32_t* __restrict__ tr_val,
+                                                       const int32_t* __restrict__ tr_own, const float* __restrict__ tr_inv,
+                                                       const int32_t* __restrict__ tr_long, int row_blocks,
                                                        const float* __restrict__ dX, int ldx, int d,
                                                        float* __restrict__ Gin)
 {
@@ -195,24 +196,103 @@ __global__ __launch_bounds__(TPB) void k_aggregate_bwd(const int32_t* __restrict
     const int first_slot = nbr_offsets[off_out - off1];      // first slot owned by this layer's output rows
     const int lane = threadIdx.x % LANES;
     constexpr int GROUPS = TPB / LANES;
-    for (int r = blockIdx.x * GROUPS + threadIdx.x / LANES; r < rows_in; r += gridDim.x * GROUPS) {
+    const float* dXm = dX + (int64_t)(off1 - off_out) * ldx + d;     // row q of this: dX_mean of owner q
+
+    if ((int)blockIdx.x >= row_blocks) {
+        // A row read by more than DN_LONG_GROUP slots (a hub): the whole workgroup sums it.  Lane group g takes
+        // the slots g, g + GROUPS, ... in ascending order, four in flight; the groups' sums are added in order of g.
+        __shared__ float part[GROUPS][LANES * V * ITERS];
+        const int p = tr_long[blockIdx.x - row_blocks] - 1;
+        if (p < off_in) return;
+        const int r = p - off_in, g = threadIdx.x / LANES;
+        const int beg = tr_ptr[p], end = tr_ptr[p + 1];
+        float acc[ITERS][V];
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it)
+#pragma unroll
+            for (int e = 0; e < V; ++e) acc[it][e] = 0.f;
+        for (int t0 = beg + g; t0 < end; t0 += 4 * GROUPS) {
+            int q[4];
+            float inv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int t = t0 + u * GROUPS;
+                const bool valid = t < end && tr_val[t] >= first_slot;
+                q[u] = valid ? tr_own[t] : -1;
+                inv[u] = valid ? tr_inv[t] : 0.f;
+            }
+            float v[4][ITERS][V];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int it = 0; it < ITERS; ++it) {
+                    const int c0 = (it * LANES + lane) * V;
+#pragma unroll
+                    for (int e = 0; e < V; ++e) v[u][it][e] = (q[u] >= 0 && c0 < d) ? dXm[(int64_t)q[u] * ldx + c0 + e] : 0.f;
+                }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int it = 0; it < ITERS; ++it)
+#pragma unroll
+                    for (int e = 0; e < V; ++e) acc[it][e] += v[u][it][e] * inv[u];
+        }
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it)
+#pragma unroll
+            for (int e = 0; e < V; ++e) part[g][(it * LANES + lane) * V + e] = acc[it][e];
+        __syncthreads();
+        for (int c = threadIdx.x; c < d; c += TPB) {
+            float tot = (p >= off_out) ? dX[(int64_t)(p - off_out) * ldx + c] : 0.f;
+            for (int w = 0; w < GROUPS; ++w) tot += part[w][c];
+            Gin[(int64_t)r * d + c] = tot;
+        }
+        return;
+    }
+
+    // A small lane group per row (each lane carries up to ITERS pieces of V columns) keeps many rows in flight per
+    // wave: the row's chain of dependent loads (tr_ptr -> slot info -> dX rows) is what bounds this kernel.
+    for (int r = blockIdx.x * GROUPS + threadIdx.x / LANES; r < rows_in; r += row_blocks * GROUPS) {
         const int p = off_in + r;
         const int beg = tr_ptr[p], end = tr_ptr[p + 1];
-        for (int c0 = lane * V; c0 < d; c0 += LANES * V) {
-            float acc[V];
+        if (end - beg > DN_LONG_GROUP) continue;             // left to a workgroup of its own (above)
+        float acc[ITERS][V];
 #pragma unroll
-            for (int e = 0; e < V; ++e) acc[e] = (p >= off_out) ? dX[(int64_t)(p - off_out) * ldx + c0 + e] : 0.f;
-            for (int t = beg; t < end; ++t) {
-                const int j = tr_val[t];
-                if (j < first_slot) continue;
-                const int q = slot_owner[j];
-                const float inv = 1.0f / (float)(nbr_offsets[q + 1] - nbr_offsets[q]);
-                const float* src = dX + (int64_t)(q + off1 - off_out) * ldx + d + c0;
+        for (int it = 0; it < ITERS; ++it) {
+            const int c0 = (it * LANES + lane) * V;
 #pragma unroll
-                for (int e = 0; e < V; ++e) acc[e] += src[e] * inv;
+            for (int e = 0; e < V; ++e) acc[it][e] = (c0 < d && p >= off_out) ? dX[(int64_t)(p - off_out) * ldx + c0 + e] : 0.f;
+        }
+        // the lanes fetch the slots' owner and 1/count side by side and hand them around by shuffles; the sums run
+        // in ascending slot order
+        for (int base = beg; base < end; base += LANES) {
+            const int t = base + lane;
+            const bool valid = t < end && tr_val[t] >= first_slot;
+            const int q = valid ? tr_own[t] : -1;
+            const float inv = valid ? tr_inv[t] : 0.f;
+            const int cnt = min(LANES, end - base);
+            for (int l = 0; l < cnt; ++l) {
+                const int ql = __shfl(q, l, LANES);
+                const float il = __shfl(inv, l, LANES);
+                if (ql < 0) continue;
+                const float* src = dXm + (int64_t)ql * ldx;
+#pragma unroll
+                for (int it = 0; it < ITERS; ++it) {
+                    const int c0 = (it * LANES + lane) * V;
+                    if (c0 < d) {
+#pragma unroll
+                        for (int e = 0; e < V; ++e) acc[it][e] += src[c0 + e] * il;
+                    }
+                }
             }
+        }
 #pragma unroll
-            for (int e = 0; e < V; ++e) Gin[(int64_t)r * d + c0 + e] = acc[e];
+        for (int it = 0; it < ITERS; ++it) {
+            const int c0 = (it * LANES + lane) * V;
+            if (c0 < d) {
+#pragma unroll
+                for (int e = 0; e < V; ++e) Gin[(int64_t)r * d + c0 + e] = acc[it][e];
+            }
         }
     }
 }
@@ -262,34 +342,35 @@ int launch_aggregate_bwd(const dn_model* m, const dn_batch* b, int i, float* gin
     const dn_layer_bufs& L = m->layer[i - 1];
     const int d = L.d_in;
     const bool vec4 = (d % 4 == 0);
-    const int per = vec4 ? 4 : 1;
-    int lanes = 4;
-    while (lanes * per < d && lanes < 64) lanes <<= 1;
+    if (d > 1024) return dn_fail(DN_EINVAL, "aggregate_bwd: input width %d above 1024", d);
+    // vec4: lanes x 4 columns cover the row (4 pieces per lane above 256 columns); otherwise 64 lanes x 1 column x 4 or 16 pieces
+    int lanes = vec4 ? 4 : 64;
+    if (vec4) while (lanes * 4 < d && lanes < 64) lanes <<= 1;
     const int groups = TPB / lanes;
     const int64_t rows_in_cap = i >= 2 ? m->layer[i - 2].rows_cap : b->cap_nodes;
-    int64_t grid = (rows_in_cap + groups - 1) / groups;
-    if (grid > 8192) grid = 8192;
-    if (grid < 1) grid = 1;
+    int64_t row_blocks = (rows_in_cap + groups - 1) / groups;
+    if (row_blocks > 65536) row_blocks = 65536;
+    if (row_blocks < 1) row_blocks = 1;
+    // one more workgroup per block of DN_LONG_GROUP transposed slots: it sums the hub row registered there, if any
+    const int64_t grid = row_blocks + b->cap_slots / DN_LONG_GROUP + 1;
     dn_prof_scope ps("aggregate_bwd", i, st);
-#define DN_AGGB(VV, LL)                                                                                               \
-    hipLaunchKernelGGL((k_aggregate_bwd<VV, LL>), dim3((int)grid), dim3(TPB), 0, st, b->hdr, i, b->nbr_offsets,       \
-                       b->slot_owner, b->tr_ptr, b->tr_val[0], m->dx, 2 * d, d, gin)
-    if (vec4) {
+#define DN_AGGB(VV, LL, II)                                                                                           \
+    hipLaunchKernelGGL((k_aggregate_bwd<VV, LL, II>), dim3((int)grid), dim3(TPB), 0, st, b->hdr, i, b->nbr_offsets,   \
+                       b->tr_ptr, b->tr_val[0], b->tr_own, b->tr_inv, b->tr_long, (int)row_blocks, m->dx, 2 * d, d, gin)
+    if (vec4 && d <= 256) {
         switch (lanes) {
-            case 4: DN_AGGB(4, 4); break;
-            case 8: DN_AGGB(4, 8); break;
-            case 16: DN_AGGB(4, 16); break;
-            case 32: DN_AGGB(4, 32); break;
-            default: DN_AGGB(4, 64); break;
+            case 4: DN_AGGB(4, 4, 1); break;
+            case 8: DN_AGGB(4, 8, 1); break;
+            case 16: DN_AGGB(4, 16, 1); break;
+            case 32: DN_AGGB(4, 32, 1); break;
+            default: DN_AGGB(4, 64, 1); break;
         }
+    } else if (vec4) {
+        DN_AGGB(4, 64, 4);
+    } else if (d <= 256) {
+        DN_AGGB(1, 64, 4);
     } else {
-        switch (lanes) {
-            case 4: DN_AGGB(1, 4); break;
-            case 8: DN_AGGB(1, 8); break;
-            case 16: DN_AGGB(1, 16); break;
-            case 32: DN_AGGB(1, 32); break;
-            default: DN_AGGB(1, 64); break;
-        }
+        DN_AGGB(1, 64, 16);
     }
 #undef DN_AGGB
     DN_LAUNCH_CHECK("k_aggregate_bwd");

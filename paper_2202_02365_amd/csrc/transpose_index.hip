@@ -25,8 +25,10 @@ constexpr int MAX_RADIX = 1 << MAX_BITS;
 
 __global__ void k_tr_init(int32_t* __restrict__ hdr, int need_all, int k, const int32_t* __restrict__ nbr_offsets,
                           const int32_t* __restrict__ repr_map, int32_t* __restrict__ key, int32_t* __restrict__ val,
-                          int radix_mask, int nblocks, int32_t* __restrict__ hist)
+                          int radix_mask, int nblocks, int32_t* __restrict__ hist, int32_t* __restrict__ tr_long,
+                          int long_words)
 {
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < long_words; i += gridDim.x * blockDim.x) tr_long[i] = 0;
     const int E = hdr[HDR_E];
     int first = 0;
     if (!need_all) {
@@ -166,11 +168,19 @@ __global__ __launch_bounds__(TPB) void k_radix_scatter(const int32_t* __restrict
 // tr_ptr[p] = first index of sorted keys >= p, for p = 0..N; also leaves histogram buffer 0 zeroed
 __global__ __launch_bounds__(TPB) void k_tr_ptr(const int32_t* __restrict__ count_ptr, const int32_t* __restrict__ nkeys_ptr,
                                                 int nkeys_const, const int32_t* __restrict__ key,
-                                                int32_t* __restrict__ tr_ptr, int32_t* __restrict__ clear, int clear_words)
+                                                int32_t* __restrict__ tr_ptr, int32_t* __restrict__ clear, int clear_words,
+                                                const int32_t* __restrict__ val, dn_sort_slot_info info)
 {
     const int N = nkeys_ptr ? *nkeys_ptr : nkeys_const, n = *count_ptr;
     const int stride = gridDim.x * TPB;
     for (int i = blockIdx.x * TPB + threadIdx.x; i < clear_words; i += stride) clear[i] = 0;
+    if (info.own_out) {
+        for (int t = blockIdx.x * TPB + threadIdx.x; t < n; t += stride) {
+            const int q = info.slot_owner[val[t]];
+            info.own_out[t] = q;
+            info.inv_out[t] = 1.0f / (float)(info.nbr_offsets[q + 1] - info.nbr_offsets[q]);
+        }
+    }
     for (int p = blockIdx.x * TPB + threadIdx.x; p <= N; p += stride) {
         int lo = 0, hi = n;
         while (lo < hi) {
@@ -178,6 +188,7 @@ __global__ __launch_bounds__(TPB) void k_tr_ptr(const int32_t* __restrict__ coun
             if (key[mid] < p) lo = mid + 1; else hi = mid;
         }
         tr_ptr[p] = lo;
+        if (info.long_out && lo + DN_LONG_GROUP < n && key[lo + DN_LONG_GROUP] == p) info.long_out[lo / DN_LONG_GROUP] = p + 1;
     }
 }
 
@@ -204,7 +215,8 @@ int64_t dn_sort_hist_words(const dn_sort_plan& p) { return 2 * (int64_t)p.total 
 // (with the first digit's per-tile counts in hist[0 .. total)) by key, stably; the result is in
 // key[0] / val[0], and ptr_out[p] = first sorted index with key >= p for p = 0 .. number of keys.
 int dn_sort_pairs_run(const dn_sort_plan& pl, const int32_t* count_ptr, int32_t* const key[2], int32_t* const val[2],
-                      int32_t* hist_space, const int32_t* nkeys_ptr, int64_t nkeys_cap, int32_t* ptr_out, hipStream_t st)
+                      int32_t* hist_space, const int32_t* nkeys_ptr, int64_t nkeys_cap, int32_t* ptr_out, hipStream_t st,
+                      const dn_sort_slot_info* info)
 {
     int32_t* hist[2] = { hist_space, hist_space + pl.total };
     int32_t* part = hist_space + 2 * (int64_t)pl.total;
@@ -228,8 +240,10 @@ int dn_sort_pairs_run(const dn_sort_plan& pl, const int32_t* count_ptr, int32_t*
     // exactly when the number of passes is odd
     int64_t gp = (nkeys_cap + 1 + TPB - 1) / TPB;
     if (gp > 2048) gp = 2048;
+    dn_sort_slot_info si = { nullptr, nullptr, nullptr, nullptr, nullptr };
+    if (info) si = *info;
     hipLaunchKernelGGL(k_tr_ptr, dim3((int)gp), dim3(TPB), 0, st, count_ptr, nkeys_ptr, (int)nkeys_cap, key[0], ptr_out,
-                       hist[0], (pl.passes & 1) ? pl.total : 0);
+                       hist[0], (pl.passes & 1) ? pl.total : 0, val[0], si);
     DN_LAUNCH_CHECK("k_tr_ptr");
     return DN_OK;
 }
@@ -250,10 +264,12 @@ int dn_launch_transpose_index(dn_batch* b, int need_all, hipStream_t st)
     if (g < 1) g = 1;
     const int src = pl.passes & 1;
     hipLaunchKernelGGL(k_tr_init, dim3((int)g), dim3(TPB), 0, st, b->hdr, need_all, b->k, b->nbr_offsets, b->repr_map,
-                       b->tr_key[src], b->tr_val[src], (1 << pl.bits) - 1, pl.nblocks, b->tr_hist);
+                       b->tr_key[src], b->tr_val[src], (1 << pl.bits) - 1, pl.nblocks, b->tr_hist, b->tr_long,
+                       (int)b->tr_long_words);
     DN_LAUNCH_CHECK("k_tr_init");
+    const dn_sort_slot_info info = { b->slot_owner, b->nbr_offsets, b->tr_own, b->tr_inv, b->tr_long };
     const int rc = dn_sort_pairs_run(pl, b->hdr + HDR_TR_COUNT, b->tr_key, b->tr_val, b->tr_hist, b->hdr + HDR_N,
-                                     b->cap_nodes, b->tr_ptr, st);
+                                     b->cap_nodes, b->tr_ptr, st, &info);
     if (rc != DN_OK) return rc;
     b->tr_serial = b->sample_serial;
     b->tr_covers_all = need_all ? 1 : 0;

@@ -11,7 +11,7 @@ import torch
 
 import oracle
 import paper_2202_02365_amd as dn
-from workloads import CONFIGS, make_inputs, class_labels, softmax_xent_grad
+from workloads import CONFIGS, make_inputs, class_labels, softmax_xent_grad, edge_batch, relation_embeddings
 from gpu_harness import assert_dense_equal, row_rel_err, to_dev
 
 pytestmark = pytest.mark.gpu
@@ -28,7 +28,7 @@ TOL = 1e-4
 DECODER_CHAIN_TOL = 2.0 ** -6
 
 
-def run_full(cfg, batches, n_targets=None, want_dh0=False, edge_batch=None):
+def run_full(cfg, batches, n_targets=None, want_dh0=False, link_prediction=False):
     dev = torch.device("cuda:0")
     inputs = make_inputs(cfg, dev, n_batches=max(batches) + 1)
     og = oracle.Graph(cfg.num_nodes, inputs["rowptr"].cpu().numpy(), inputs["col"].cpu().numpy(),
@@ -45,18 +45,16 @@ def run_full(cfg, batches, n_targets=None, want_dh0=False, edge_batch=None):
     h0 = torch.empty((batch.node_capacity, cfg.dims[0]), dtype=table.dtype, device=dev)
     report = []
     for bi in batches:
-        if edge_batch is None:
+        if not link_prediction:
             targets = inputs["targets"][bi] if n_targets is None else inputs["targets"][bi][:n_targets]
             dn.dense_sample(batch, graph, torch.from_numpy(targets).to(dev), bi)
             d = oracle.dense_sample(og, targets, cfg.fanouts, seed=bi, direction=cfg.direction)
         else:
             # link-prediction batch: uniform positive edges of the graph, shared uniform negatives per chunk
-            n_edges, chunk, n_neg = edge_batch
-            rng = np.random.default_rng([17, bi])
-            e = torch.from_numpy(rng.integers(0, inputs["col"].numel(), n_edges)).to(dev)
-            dst_t = inputs["col"][e]
-            src_t = (torch.searchsorted(inputs["rowptr"], e, right=True) - 1).to(torch.int32)
-            neg_t = torch.from_numpy(rng.integers(0, cfg.num_nodes, (n_edges // chunk) * n_neg).astype(np.int32)).to(dev)
+            n_edges, chunk, n_neg = cfg.lp_edges, cfg.lp_chunk, cfg.lp_negatives
+            src_t, rel_t, dst_t, neg2d = edge_batch(inputs["rowptr"], inputs["col"], cfg.num_nodes, n_edges, chunk, n_neg,
+                                                    cfg.num_relations, bi)
+            neg_t = neg2d.reshape(-1)
             ls, ld, ln = dn.dense_sample_edges(batch, graph, src_t, dst_t, neg_t, bi)
             src, dst, neg = src_t.cpu().numpy(), dst_t.cpu().numpy(), neg_t.cpu().numpy()
             d, ols, old, oln = oracle.dense_sample_edges(og, src, dst, neg, cfg.fanouts, seed=bi, direction=cfg.direction)
@@ -73,7 +71,7 @@ def run_full(cfg, batches, n_targets=None, want_dh0=False, edge_batch=None):
         dn.sage_forward(model, batch, h0, out)
         st = oracle.sage_forward(d, table[ids].float().cpu().numpy(), params, mode="bf16")
         errs = {"fwd": row_rel_err(out.cpu().numpy(), st.out)}
-        if edge_batch is None:
+        if not link_prediction:
             gout = softmax_xent_grad(st.out, class_labels(len(targets), cfg.dims[-1]))
         else:
             # link prediction: the DistMult decoder scores the encoder's output rows of the edge endpoints and the
@@ -81,17 +79,15 @@ def run_full(cfg, batches, n_targets=None, want_dh0=False, edge_batch=None):
             # The oracle's decoder gradient feeds both encoders' backward passes (same input on both sides);
             # the device decoder runs on the device encoder's output and is compared with a tolerance for a
             # chain of two operators (see the comment at DECODER_CHAIN_TOL).
-            n_edges, chunk, n_neg = edge_batch
-            num_rel = 1000
-            w = 1.0 / np.arange(1, num_rel + 1) ** 1.1
-            rel = rng.choice(num_rel, size=n_edges, p=w / w.sum()).astype(np.int32)
-            R = np.random.default_rng([19, bi]).standard_normal((num_rel, cfg.dims[-1])).astype(np.float32)
+            num_rel = cfg.num_relations
+            rel = rel_t.cpu().numpy()
+            R = relation_embeddings(num_rel, cfg.dims[-1])
             ost = oracle.distmult_forward(st.out.astype(np.float32), R, ols, rel, old, oln.reshape(-1, n_neg), chunk, mode="bf16")
             o_dh, o_dr = oracle.distmult_backward(ost)
             gout = o_dh.astype(np.float32)
             dec = dn.Decoder(n_edges, chunk, n_neg, cfg.dims[-1], len(targets), num_rel)
             pos_t, loss_t = torch.empty(n_edges, device=dev), torch.empty(n_edges, device=dev)
-            dn.distmult_forward(dec, out, torch.from_numpy(R).to(dev), ls, torch.from_numpy(rel).to(dev), ld,
+            dn.distmult_forward(dec, out, torch.from_numpy(R).to(dev), ls, rel_t, ld,
                                 ln.view(-1, n_neg), pos_t, loss_t)
             g_dh = torch.empty_like(out)
             g_dr = torch.empty((num_rel, cfg.dims[-1]), device=dev)
@@ -145,4 +141,4 @@ def test_rmat86m_both_directions_with_input_gradient():
     """50,000 positive edges with 1,000 shared negatives per chunk of 1,000 edges (at most 150,000 target
     nodes), 20 in- plus 20 out-neighbours, one layer, gradient with respect to the learnable inputs and
     their SGD update."""
-    run_full(CONFIGS[4], batches=[0], want_dh0=True, edge_batch=(50_000, 1_000, 1_000))
+    run_full(CONFIGS[4], batches=[0], want_dh0=True, link_prediction=True)

@@ -26,6 +26,12 @@ class WorkloadConfig:
     feat_seed: int = 2
     weight_seed: int = 3
     target_seed: int = 4
+    # link prediction (0 = node-classification workload): positive edges per batch, edges per chunk that
+    # share one list of negatives, negatives per chunk, relation types (Zipf(1.1)-distributed)
+    lp_edges: int = 0
+    lp_chunk: int = 0
+    lp_negatives: int = 0
+    num_relations: int = 0
 
     @property
     def num_layers(self) -> int:
@@ -55,7 +61,7 @@ CONFIGS = [
                    train_fraction=0.011),
     WorkloadConfig("rmat122m", 122_000_000, 1_300_000_000, 768, "bf16", 256, 153, (15, 10, 5), 1000),
     WorkloadConfig("rmat86m_lp", 86_000_000, 338_000_000, 100, "f32", 100, 100, (20,), 150_000,
-                   direction=2),
+                   direction=2, lp_edges=50_000, lp_chunk=1000, lp_negatives=1000, num_relations=1000),
 ]
 
 

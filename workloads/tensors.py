@@ -101,3 +101,25 @@ def decoder_inputs(n_rows: int, num_rel: int, dim: int, n_edges: int, chunk: int
     n_chunks = (n_edges + chunk - 1) // chunk
     neg = rng.integers(0, n_rows, (n_chunks, num_neg)).astype(np.int32)
     return H, R, src, rel, dst, neg
+
+
+def edge_batch(rowptr: torch.Tensor, col: torch.Tensor, num_nodes: int, n_edges: int, chunk: int, num_neg: int,
+               num_rel: int, batch_index: int, seed: int = 17, zipf_exponent: float = 1.1):
+    """One link-prediction batch over a CSR graph: n_edges positive edges drawn uniformly from the graph's edges,
+    a Zipf(zipf_exponent) relation type per edge, and per chunk of `chunk` edges num_neg uniform negative nodes.
+    Returns (src, rel, dst, neg) as int32 tensors on the graph's device (neg is [chunks x num_neg])."""
+    rng = np.random.default_rng([seed, batch_index])
+    dev = col.device
+    e = torch.from_numpy(rng.integers(0, col.numel(), n_edges)).to(dev)
+    dst = col[e].to(torch.int32)
+    src = (torch.searchsorted(rowptr, e, right=True) - 1).to(torch.int32)
+    n_chunks = (n_edges + chunk - 1) // chunk
+    neg = torch.from_numpy(rng.integers(0, num_nodes, (n_chunks, num_neg)).astype(np.int32)).to(dev)
+    w = 1.0 / np.arange(1, num_rel + 1, dtype=np.float64) ** zipf_exponent
+    rel = torch.from_numpy(rng.choice(num_rel, size=n_edges, p=w / w.sum()).astype(np.int32)).to(dev)
+    return src, rel, dst, neg
+
+
+def relation_embeddings(num_rel: int, dim: int, seed: int = 19) -> np.ndarray:
+    """N(0,1) relation embeddings [num_rel x dim], fp32."""
+    return np.random.default_rng([seed, num_rel, dim]).standard_normal((num_rel, dim)).astype(np.float32)
