@@ -171,6 +171,20 @@ DN_API int  dn_model_status(const dn_model* m, int32_t* status, void* stream);
  * row t = embedding of target t (caller order). */
 DN_API int  sage_forward(dn_model* m, const dn_batch* b, const void* d_H0, float* d_out, void* stream);
 
+/* sage_forward_table: sage_forward without the H^0 round trip: layer 1 reads the rows of the lookup table
+ * (Section 4.2: base representations are looked up by node_ids) directly, d_table[node_ids[p], :] for a node's own
+ * row and d_table[nbrs[j], :] for neighbour slot j, so dense_gather and its buffer are not needed.  d_table:
+ * [V x dims[0]] of the model's in_dtype with row stride ld_elems elements.  Same values, same arithmetic, same
+ * results as dense_gather followed by sage_forward; sage_backward follows it in the same way. */
+DN_API int  sage_forward_table(dn_model* m, const dn_batch* b, const void* d_table, int64_t ld_elems, float* d_out,
+                               void* stream);
+
+/* dn_model_set_aggregation: DN_AGG_MEAN (default; the GraphSage-mean layer above) or DN_AGG_SUM, the additive
+ * aggregation of Algorithm 3 as printed (segment sum of the neighbours' rows, no division); applies to
+ * sage_forward / sage_forward_table / sage_backward calls that follow. */
+enum { DN_AGG_MEAN = 0, DN_AGG_SUM = 1 };
+DN_API int  dn_model_set_aggregation(dn_model* m, int32_t aggregation);
+
 /* sage_backward (Section 2: "loss and gradients"): given d_grad_out = dL/dH^k, fp32
  * [n_targets x dims[k]], writes dL/dW_self^i, dL/dW_nbr^i (fp32 [dims[i-1] x dims[i]]) and dL/db^i
  * (fp32 [dims[i]]) for every layer, and, when d_dH0 is not NULL, dL/dH^0 (fp32 [N x dims[0]],

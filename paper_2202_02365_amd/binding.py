@@ -9,6 +9,7 @@ import torch
 DN_F32, DN_BF16 = 0, 1
 DN_DIR_OUT, DN_DIR_IN, DN_DIR_BOTH = 0, 1, 2
 DN_MAX_LAYERS = 6
+DN_AGG_MEAN, DN_AGG_SUM = 0, 1
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _HEADER = os.path.join(os.path.dirname(_PKG), "include", "dense.h")
@@ -83,6 +84,8 @@ def load_library():
         "dn_decoder_scores": (ctypes.c_int, [vp, i32, pp, ctypes.POINTER(i64), ctypes.POINTER(i64)]),
         "dn_decoder_status": (ctypes.c_int, [vp, ctypes.POINTER(i32), vp]),
         "sage_forward": (ctypes.c_int, [vp, vp, vp, vp, vp]),
+        "sage_forward_table": (ctypes.c_int, [vp, vp, vp, i64, vp, vp]),
+        "dn_model_set_aggregation": (ctypes.c_int, [vp, i32]),
         "sage_backward": (ctypes.c_int, [vp, vp, vp, pp, pp, pp, vp, vp]),
     }
     for name, (res, args) in sig.items():
@@ -222,6 +225,10 @@ class Model:
         if getattr(self, "handle", None) and _lib is not None:
             _lib.dn_model_destroy(self.handle)
             self.handle = None
+
+    def set_aggregation(self, aggregation: int) -> None:
+        """DN_AGG_MEAN (default) or DN_AGG_SUM (Algorithm 3 as printed)."""
+        _check(load_library().dn_model_set_aggregation(self.handle, aggregation))
 
     def status(self):
         """(sign fix-ups of the last ReLU layer, queue-overflow flag); waits for the stream."""
@@ -371,6 +378,16 @@ def sage_forward(model: Model, batch: Batch, h0: torch.Tensor, out: torch.Tensor
     assert h0.dtype == want and h0.shape[1] == model.dims[0] and h0.shape[0] >= batch.node_capacity
     assert out.shape[1] == model.dims[-1]
     _check(load_library().sage_forward(model.handle, batch.handle, _dev_ptr(h0), _dev_ptr(out, torch.float32), _stream()))
+    return out
+
+
+def sage_forward_table(model: Model, batch: Batch, table: torch.Tensor, out: torch.Tensor) -> torch.Tensor:
+    """sage_forward reading the feature table's rows directly (no dense_gather, no H^0 buffer)."""
+    want = torch.float32 if model.in_dtype == DN_F32 else torch.bfloat16
+    assert table.dtype == want and table.shape[1] == model.dims[0] and table.stride(1) == 1
+    assert out.shape[1] == model.dims[-1]
+    _check(load_library().sage_forward_table(model.handle, batch.handle, table.data_ptr(), table.stride(0),
+                                             _dev_ptr(out, torch.float32), _stream()))
     return out
 
 

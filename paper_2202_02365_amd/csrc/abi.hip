@@ -387,6 +387,7 @@ int dn_model_create(dn_model** out, const dn_batch* b, int32_t k, const int32_t*
     hipError_t e = hipMemsetAsync(d_workspace, 0, c.bytes(), static_cast<hipStream_t>(stream));
     if (e != hipSuccess) { delete m; return dn_fail(DN_EHIP, "hipMemsetAsync: %s", hipGetErrorString(e)); }
     m->fwd_serial = ~0ull;
+    m->mean_agg = 1;
     *out = m;
     return DN_OK;
 }
@@ -425,9 +426,36 @@ int sage_forward(dn_model* m, const dn_batch* b, const void* d_H0, float* d_out,
         if (rows > b->V) rows = b->V;
         if (rows > m->layer[i - 1].rows_cap) return dn_fail(DN_ECAPACITY, "the model was created for a smaller batch capacity");
     }
-    int rc = dn_launch_forward(m, b, d_H0, d_out, static_cast<hipStream_t>(stream));
+    int rc = dn_launch_forward(m, b, d_H0, m->dims[0], 0, d_out, static_cast<hipStream_t>(stream));
     if (rc == DN_OK) { m->fwd_serial = b->sample_serial; m->h0 = d_H0; }
     return rc;
+}
+
+int sage_forward_table(dn_model* m, const dn_batch* b, const void* d_table, int64_t ld_elems, float* d_out, void* stream)
+{
+    if (!m || !b || !d_table || !d_out) return dn_fail(DN_EINVAL, "null argument");
+    if (!m->weights_set) return dn_fail(DN_ESTATE, "dn_model_set_weights has not been called");
+    if (b->sample_serial == 0) return dn_fail(DN_ESTATE, "dense_sample has not run on this batch");
+    if (m->k != b->k) return dn_fail(DN_EINVAL, "model and batch disagree on the number of layers");
+    if (ld_elems < m->dims[0]) return dn_fail(DN_EINVAL, "row stride below the input width");
+    for (int i = 1; i <= m->k; ++i) {
+        int64_t rows = 0;
+        for (int h = 0; h <= b->k - i; ++h) rows += b->cap_level[h];
+        if (rows > b->V) rows = b->V;
+        if (rows > m->layer[i - 1].rows_cap) return dn_fail(DN_ECAPACITY, "the model was created for a smaller batch capacity");
+    }
+    int rc = dn_launch_forward(m, b, d_table, ld_elems, 1, d_out, static_cast<hipStream_t>(stream));
+    if (rc == DN_OK) { m->fwd_serial = b->sample_serial; m->h0 = nullptr; }
+    return rc;
+}
+
+int dn_model_set_aggregation(dn_model* m, int32_t aggregation)
+{
+    if (!m) return dn_fail(DN_EINVAL, "model is null");
+    if (aggregation != DN_AGG_MEAN && aggregation != DN_AGG_SUM) return dn_fail(DN_EINVAL, "aggregation must be DN_AGG_MEAN or DN_AGG_SUM");
+    m->mean_agg = aggregation == DN_AGG_MEAN ? 1 : 0;
+    m->fwd_serial = ~0ull;            // activations saved under the other rule no longer fit
+    return DN_OK;
 }
 
 int sage_backward(dn_model* m, const dn_batch* b, const float* d_grad_out, float* const* d_dw_self,

@@ -103,6 +103,7 @@ struct dn_model {
     const void* h0;                // H^0 of the last forward
     uint64_t fwd_serial;           // sample the saved activations belong to
     int32_t weights_set;
+    int32_t mean_agg;              // 1: neighbour mean (default), 0: neighbour sum (Algorithm 3 as printed)
     size_t workspace_bytes;
 };
 
@@ -178,7 +179,8 @@ int dn_sort_pairs_run(const dn_sort_plan& pl, const int32_t* count_ptr, int32_t*
                       const dn_sort_slot_info* info = nullptr);
 int dn_launch_set_weights(dn_model* m, const float* const* ws, const float* const* wn,
                           const float* const* bias, hipStream_t st);
-int dn_launch_forward(dn_model* m, const dn_batch* b, const void* h0, float* out, hipStream_t st);
+int dn_launch_forward(dn_model* m, const dn_batch* b, const void* h0, int64_t ldh, int from_table, float* out,
+                      hipStream_t st);
 int dn_launch_backward(dn_model* m, dn_batch* b, const float* grad_out, float* const* dws,
                        float* const* dwn, float* const* dbias, float* dh0, hipStream_t st);
 

@@ -31,10 +31,15 @@ __device__ __forceinline__ float load_elem(const uint16_t* p) { return bf16_to_f
 // Writes the A operand of the layer's GEMM, X[row] = [ self | mean ] as bf16, followed for
 // TERMS == 2 by the bf16 of what the first rounding left over, [ self_lo | mean_lo ]; and the
 // L2 norm of the row (bound of the accumulation error of its dot products).
-template <typename TIN, int V, int LANES, int TERMS>
+// TABLE: H is the feature table itself (row stride ldh) and rows are addressed by node id, node_ids[p] for
+// the row's own representation and nbrs[j] for slot j, instead of by position in a gathered H^0; the values
+// read, and so every result, are the same.  mean = 0 gives the additive aggregation of Algorithm 3 as printed.
+template <typename TIN, int V, int LANES, int TERMS, bool TABLE>
 __global__ __launch_bounds__(TPB) void k_aggregate(const int32_t* __restrict__ hdr, int layer,
                                                    const int32_t* __restrict__ nbr_offsets,
                                                    const int32_t* __restrict__ repr_map, const TIN* __restrict__ H,
+                                                   int64_t ldh, const int32_t* __restrict__ node_ids,
+                                                   const int32_t* __restrict__ nbrs, int mean_agg,
                                                    int d, uint16_t* __restrict__ X, int kp, float* __restrict__ rownorm,
                                                    int32_t* __restrict__ fix_count)
 {
@@ -51,7 +56,7 @@ __global__ __launch_bounds__(TPB) void k_aggregate(const int32_t* __restrict__ h
         const int q = p - off1;
         const int beg = nbr_offsets[q], end = nbr_offsets[q + 1];
         const float cnt = (float)(end - beg);
-        const TIN* self = H + (int64_t)(p - off_in) * d;
+        const TIN* self = TABLE ? H + (int64_t)node_ids[p] * ldh : H + (int64_t)(p - off_in) * ldh;
         uint16_t* xrow = X + (int64_t)ro * kp;
         float sq = 0.f;
         for (int c0 = lane * V; c0 < d; c0 += LANES * V) {
@@ -59,7 +64,7 @@ __global__ __launch_bounds__(TPB) void k_aggregate(const int32_t* __restrict__ h
 #pragma unroll
             for (int e = 0; e < V; ++e) acc[e] = 0.f;
             for (int j = beg; j < end; ++j) {
-                const TIN* nb = H + (int64_t)(repr_map[j] - off_in) * d + c0;
+                const TIN* nb = (TABLE ? H + (int64_t)nbrs[j] * ldh : H + (int64_t)(repr_map[j] - off_in) * ldh) + c0;
                 float v[V];
 #pragma unroll
                 for (int e = 0; e < V; ++e) v[e] = load_elem(nb + e);
@@ -68,7 +73,7 @@ __global__ __launch_bounds__(TPB) void k_aggregate(const int32_t* __restrict__ h
             }
 #pragma unroll
             for (int e = 0; e < V; ++e) {
-                const float mean = end > beg ? acc[e] / cnt : 0.f;
+                const float mean = end > beg ? (mean_agg ? acc[e] / cnt : acc[e]) : 0.f;
                 const float sv = load_elem(self + c0 + e);
                 const uint16_t s_hi = f32_to_bf16(sv), m_hi = f32_to_bf16(mean);
                 xrow[c0 + e] = s_hi;
@@ -184,7 +189,7 @@ __global__ __launch_bounds__(TPB) void k_aggregate_bwd(const int32_t* __restrict
                                                        const int32_t* __restrict__ nbr_offsets,
                                                        const int32_t* __restrict__ tr_ptr, const int32_t* __restrict__ tr_val,
                                                        const int32_t* __restrict__ tr_own, const float* __restrict__ tr_inv,
-                                                       const int32_t* __restrict__ tr_long, int row_blocks,
+                                                       const int32_t* __restrict__ tr_long, int row_blocks, int mean_agg,
                                                        const float* __restrict__ dX, int ldx, int d,
                                                        float* __restrict__ Gin)
 {
@@ -219,7 +224,7 @@ __global__ __launch_bounds__(TPB) void k_aggregate_bwd(const int32_t* __restrict
                 const int t = t0 + u * GROUPS;
                 const bool valid = t < end && tr_val[t] >= first_slot;
                 q[u] = valid ? tr_own[t] : -1;
-                inv[u] = valid ? tr_inv[t] : 0.f;
+                inv[u] = valid ? (mean_agg ? tr_inv[t] : 1.f) : 0.f;
             }
             float v[4][ITERS][V];
 #pragma unroll
@@ -269,7 +274,7 @@ __global__ __launch_bounds__(TPB) void k_aggregate_bwd(const int32_t* __restrict
             const int t = base + lane;
             const bool valid = t < end && tr_val[t] >= first_slot;
             const int q = valid ? tr_own[t] : -1;
-            const float inv = valid ? tr_inv[t] : 0.f;
+            const float inv = valid ? (mean_agg ? tr_inv[t] : 1.f) : 0.f;
             const int cnt = min(LANES, end - base);
             for (int l = 0; l < cnt; ++l) {
                 const int ql = __shfl(q, l, LANES);
@@ -297,8 +302,8 @@ __global__ __launch_bounds__(TPB) void k_aggregate_bwd(const int32_t* __restrict
     }
 }
 
-template <typename TIN, int TERMS>
-int launch_aggregate_t(const dn_model* m, const dn_batch* b, int i, const TIN* H, hipStream_t st)
+template <typename TIN, int TERMS, bool TABLE>
+int launch_aggregate_t(const dn_model* m, const dn_batch* b, int i, const TIN* H, int64_t ldh, hipStream_t st)
 {
     const dn_layer_bufs& L = m->layer[i - 1];
     const int d = L.d_in;
@@ -313,8 +318,9 @@ int launch_aggregate_t(const dn_model* m, const dn_batch* b, int i, const TIN* H
     if (grid < 1) grid = 1;
     dn_prof_scope ps("aggregate", i, st);
 #define DN_AGG(VV, LL)                                                                                                 \
-    hipLaunchKernelGGL((k_aggregate<TIN, VV, LL, TERMS>), dim3((int)grid), dim3(TPB), 0, st, b->hdr, i, b->nbr_offsets, \
-                       b->repr_map, H, d, X, L.kp, L.rownorm, m->fix_count)
+    hipLaunchKernelGGL((k_aggregate<TIN, VV, LL, TERMS, TABLE>), dim3((int)grid), dim3(TPB), 0, st, b->hdr, i,         \
+                       b->nbr_offsets, b->repr_map, H, ldh, b->node_ids, b->nbrs, m->mean_agg, d, X, L.kp, L.rownorm, \
+                       m->fix_count)
     if (vec4) {
         switch (lanes) {
             case 4: DN_AGG(4, 4); break;
@@ -356,7 +362,8 @@ int launch_aggregate_bwd(const dn_model* m, const dn_batch* b, int i, float* gin
     dn_prof_scope ps("aggregate_bwd", i, st);
 #define DN_AGGB(VV, LL, II)                                                                                           \
     hipLaunchKernelGGL((k_aggregate_bwd<VV, LL, II>), dim3((int)grid), dim3(TPB), 0, st, b->hdr, i, b->nbr_offsets,   \
-                       b->tr_ptr, b->tr_val[0], b->tr_own, b->tr_inv, b->tr_long, (int)row_blocks, m->dx, 2 * d, d, gin)
+                       b->tr_ptr, b->tr_val[0], b->tr_own, b->tr_inv, b->tr_long, (int)row_blocks, m->mean_agg, m->dx, 2 * d, d,   \
+                       gin)
     if (vec4 && d <= 256) {
         switch (lanes) {
             case 4: DN_AGGB(4, 4, 1); break;
@@ -379,17 +386,19 @@ int launch_aggregate_bwd(const dn_model* m, const dn_batch* b, int i, float* gin
 
 }  // namespace
 
-int dn_launch_forward(dn_model* m, const dn_batch* b, const void* h0, float* out, hipStream_t st)
+int dn_launch_forward(dn_model* m, const dn_batch* b, const void* h0, int64_t ldh, int from_table, float* out, hipStream_t st)
 {
     const int k = m->k;
     for (int i = 1; i <= k; ++i) {
         int rc;
         if (i == 1 && m->in_dtype == DN_BF16)
-            rc = launch_aggregate_t<uint16_t, 1>(m, b, 1, static_cast<const uint16_t*>(h0), st);
+            rc = from_table ? launch_aggregate_t<uint16_t, 1, true>(m, b, 1, static_cast<const uint16_t*>(h0), ldh, st)
+                            : launch_aggregate_t<uint16_t, 1, false>(m, b, 1, static_cast<const uint16_t*>(h0), ldh, st);
         else if (i == 1)
-            rc = launch_aggregate_t<float, 1>(m, b, 1, static_cast<const float*>(h0), st);
+            rc = from_table ? launch_aggregate_t<float, 1, true>(m, b, 1, static_cast<const float*>(h0), ldh, st)
+                            : launch_aggregate_t<float, 1, false>(m, b, 1, static_cast<const float*>(h0), ldh, st);
         else
-            rc = launch_aggregate_t<float, 2>(m, b, i, m->layer[i - 2].h, st);
+            rc = launch_aggregate_t<float, 2, false>(m, b, i, m->layer[i - 2].h, m->layer[i - 1].d_in, st);
         if (rc) return rc;
         const dn_layer_bufs& L = m->layer[i - 1];
         rc = dn_gemm_forward(m, b, i, i == k ? out : L.h, L.d_out, st);

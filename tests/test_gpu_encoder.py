@@ -27,7 +27,7 @@ def g1m(rmat1m):
 
 
 def run_case(dg, fanouts, dims, n_targets, seed, batch_index=0, direction=0, feat_dtype="f32", bias_scale=0.1,
-             want_dh0=False, targets=None):
+             want_dh0=False, targets=None, aggregation="mean", from_table=False):
     V = dg.num_nodes
     if targets is None:
         targets = target_batch(V, n_targets, batch_index)
@@ -41,12 +41,21 @@ def run_case(dg, fanouts, dims, n_targets, seed, batch_index=0, direction=0, fea
     in_dtype = dn.DN_F32 if feat_dtype == "f32" else dn.DN_BF16
     model = dn.Model(batch, dims, in_dtype)
     model.set_weights(to_dev(w_self), to_dev(w_nbr), to_dev(bias))
+    if aggregation == "sum":
+        model.set_aggregation(dn.DN_AGG_SUM)
     h0 = torch.empty((batch.node_capacity, dims[0]), dtype=table.dtype, device="cuda:0")
-    dn.dense_gather(batch, table.to("cuda:0"), h0)
+    table_dev = table.to("cuda:0")
+    dn.dense_gather(batch, table_dev, h0)
     out = torch.empty((len(targets), dims[-1]), dtype=torch.float32, device="cuda:0")
     dn.sage_forward(model, batch, h0, out)
+    if from_table:
+        # layer 1 reads the table's rows itself: same values, same arithmetic, so the same bits; backward follows it
+        out_gathered = out.clone()
+        out.fill_(7.0)
+        dn.sage_forward_table(model, batch, table_dev, out)
+        assert torch.equal(out, out_gathered)
 
-    params = oracle.SageParams(w_self, w_nbr, bias)
+    params = oracle.SageParams(w_self, w_nbr, bias, aggregation=aggregation)
     h0_o = table.float().numpy()[d.node_ids]
     st = oracle.sage_forward(d, h0_o, params, mode="bf16")
     fwd_err = row_rel_err(out.cpu().numpy(), st.out)
@@ -96,6 +105,19 @@ def test_config1_forward_backward(g1m):
 def test_shapes_with_bias_and_input_gradient(g16k, fanouts, dims):
     """Ragged widths (padding paths of the GEMMs), scalar and vector aggregation paths, dH^0."""
     errs, _ = run_case(g16k, fanouts, dims, 200, seed=5, want_dh0=True)
+    check(errs)
+
+
+@pytest.mark.parametrize("feat_dtype", ["f32", "bf16"])
+def test_forward_from_the_table_equals_gather_then_forward(g16k, feat_dtype):
+    errs, _ = run_case(g16k, [7, 4], [36, 64, 12], 200, seed=11, feat_dtype=feat_dtype, want_dh0=True, from_table=True)
+    check(errs)
+
+
+def test_additive_aggregation_of_algorithm_3(g16k):
+    errs, _ = run_case(g16k, [6, 5], [32, 48, 10], 150, seed=12, want_dh0=True, aggregation="sum")
+    check(errs)
+    errs, _ = run_case(g16k, [5], [24, 16], 90, seed=13, direction=2, want_dh0=True, aggregation="sum", from_table=True)
     check(errs)
 
 
