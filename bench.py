@@ -315,6 +315,9 @@ def main():
     ap.add_argument("--no-kernel-times", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (reference for hardware byte counters)")
+    ap.add_argument("--separate-gather", action="store_true",
+                    help="dense_gather into an H^0 buffer, then sage_forward (default: sage_forward_table, whose layer-1 "
+                         "aggregation reads the table's rows itself)")
     ap.add_argument("--no-graphs", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
     ap.add_argument("--replicas", type=int, default=4,
                     help="data-parallel replicas on one GPU: that many mini-batches run the whole path concurrently, "
@@ -359,10 +362,25 @@ def main():
     need_dh0 = cfg.name.endswith("_lp")            # learnable base representations need dL/dH^0
     dh0 = torch.empty((batch.node_capacity, dims[0]), dtype=torch.float32, device=dev) if need_dh0 else None
 
-    def step(bi, backward=True):
+    fused = not args.separate_gather
+
+    def gather(b, h0_buf):
+        if not fused:
+            dn.dense_gather(b, table, h0_buf)
+
+    def forward(m, b, h0_buf, out_buf):
+        if fused:
+            dn.sage_forward_table(m, b, table, out_buf)
+        else:
+            dn.sage_forward(m, b, h0_buf, out_buf)
+
+    def step(bi, backward=True, separate=False):
         dn.dense_sample(batch, graph, targets[bi], bi)
-        dn.dense_gather(batch, table, h0)
-        dn.sage_forward(model, batch, h0, out)
+        if separate or not fused:
+            dn.dense_gather(batch, table, h0)
+            dn.sage_forward(model, batch, h0, out)
+        else:
+            dn.sage_forward_table(model, batch, table, out)
         if backward:
             dn.sage_backward(model, batch, grad_out, dws, dwn, dbs, dh0)
 
@@ -386,13 +404,13 @@ def main():
             with torch.cuda.stream(s_build):
                 s_build.wait_event(ev_free[s & 1])
                 dn.dense_sample(b_s, graph, targets[bi], bi)
-                dn.dense_gather(b_s, table, h0_s)
+                gather(b_s, h0_s)
                 if backward:
                     b_s.prepare_backward(need_dh0)
                 ev_built[s & 1].record(s_build)
             with torch.cuda.stream(s_compute):
                 s_compute.wait_event(ev_built[s & 1])
-                dn.sage_forward(model, b_s, h0_s, out)
+                forward(model, b_s, h0_s, out)
                 if backward:
                     dn.sage_backward(model, b_s, grad_out, dws, dwn, dbs, dh0)
                 ev_free[s & 1].record(s_compute)
@@ -438,10 +456,10 @@ def main():
                 s_build.wait_stream(s_compute)
                 with torch.cuda.stream(s_build):
                     dn.dense_sample(b_nxt, graph, targets[nxt], nxt)
-                    dn.dense_gather(b_nxt, table, h0_nxt)
+                    gather(b_nxt, h0_nxt)
                     if backward:
                         b_nxt.prepare_backward(need_dh0)
-                dn.sage_forward(model, b_cur, h0_cur, out)
+                forward(model, b_cur, h0_cur, out)
                 if backward:
                     dn.sage_backward(model, b_cur, grad_out, dws, dwn, dbs, dh0)
                 s_compute.wait_stream(s_build)
@@ -452,7 +470,7 @@ def main():
         # prologue (untimed): construct batch 0 so that the first graph finds its inputs
         with torch.cuda.stream(s_compute):
             dn.dense_sample(slots[0][0], graph, targets[0], 0)
-            dn.dense_gather(slots[0][0], table, slots[0][1])
+            gather(slots[0][0], slots[0][1])
             if backward:
                 slots[0][0].prepare_backward(need_dh0)
         torch.cuda.synchronize()
@@ -486,8 +504,8 @@ def main():
                 bi = s % N_BATCHES
                 with torch.cuda.stream(o["stream"]):
                     dn.dense_sample(o["batch"], graph, targets[bi], bi)
-                    dn.dense_gather(o["batch"], table, o["h0"])
-                    dn.sage_forward(o["model"], o["batch"], o["h0"], o["out"])
+                    gather(o["batch"], o["h0"])
+                    forward(o["model"], o["batch"], o["h0"], o["out"])
                     if backward:
                         dn.sage_backward(o["model"], o["batch"], grad_out, o["dws"], o["dwn"], o["dbs"], o["dh0"])
             torch.cuda.synchronize()
@@ -500,8 +518,8 @@ def main():
                 bi = 5 if r == 0 else 6 + r
                 with torch.cuda.stream(o["stream"]):
                     dn.dense_sample(o["batch"], graph, targets[bi], bi)
-                    dn.dense_gather(o["batch"], table, o["h0"])
-                    dn.sage_forward(o["model"], o["batch"], o["h0"], o["out"])
+                    gather(o["batch"], o["h0"])
+                    forward(o["model"], o["batch"], o["h0"], o["out"])
                     dn.sage_backward(o["model"], o["batch"], grad_out, o["dws"], o["dwn"], o["dbs"], o["dh0"])
             torch.cuda.synchronize()
             o = reps[0]
@@ -567,7 +585,7 @@ def main():
         for s in range(args.steps):
             dn.profile_calibration_copy(delay_dst, delay_src)
             dn.profile_empty_bracket()
-            step(s % N_BATCHES)
+            step(s % N_BATCHES, separate=True)        # gather as a kernel of its own, so that every step of the path is timed
         prof = dn.profile_collect()
         dn.profile_enable(False)
         del delay_src, delay_dst
@@ -627,6 +645,8 @@ def main():
                    "mean_nodes_per_batch": mean_n, "mean_sampled_edges_per_batch": mean_e},
         "mini_batches_per_s": args.steps / total_s,
         "in_flight": in_flight,
+        "forward": "sage_forward_table: the layer-1 aggregation reads the table's rows itself, no H^0 buffer" if fused
+                   else "dense_gather into H^0, then sage_forward",
         "two_in_flight": pipelined,
         "sample_gather_fwd": {"ms_per_step": 1e3 * fwd_only_s / args.steps,
                               "mini_batches_per_s": args.steps / fwd_only_s,
