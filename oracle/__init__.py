@@ -8,6 +8,7 @@ package.  It shares no code with the HIP path and never imports it.
   sage.py         NumPy fp64: GraphSage-mean forward / backward over DENSE
                   (Algorithms 2 and 3 of the paper with mean aggregation).
   distmult.py     NumPy fp64: DistMult decoder with shared negatives, forward / backward.
+  heads.py        NumPy: softmax cross-entropy head (fp64), Adagrad update of learnable rows (fp32).
 """
 import ctypes
 import os
@@ -203,8 +204,10 @@ def dense_gather(table: np.ndarray, node_ids: np.ndarray) -> np.ndarray:
 from .sage import (round_bf16, dense_layer_view, sage_forward, sage_backward, SageParams,  # noqa: E402
                    ForwardState)
 from .distmult import distmult_forward, distmult_backward, DistMultState  # noqa: E402
+from .heads import softmax_xent, embedding_adagrad  # noqa: E402
 
 __all__ = ["build", "philox4x32_10", "floyd_positions", "Graph", "Dense", "onehop", "dense_sample",
            "dense_sample_edges", "embedding_sgd",
            "dense_gather", "round_bf16", "dense_layer_view", "sage_forward", "sage_backward",
-           "SageParams", "ForwardState", "distmult_forward", "distmult_backward", "DistMultState"]
+           "SageParams", "ForwardState", "distmult_forward", "distmult_backward", "DistMultState",
+           "softmax_xent", "embedding_adagrad"]
