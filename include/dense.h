@@ -124,6 +124,21 @@ DN_API int  dense_sample_edges(dn_batch* b, const dn_graph* g, const int32_t* d_
 DN_API int  dn_embedding_sgd(const dn_batch* b, float* d_table, int32_t dim, int64_t ld_elems, const float* d_dH0,
                              float lr, void* stream);
 
+/* ---- dn_embedding_adagrad: the same update with Adagrad per element (another reading of the unnamed optimiser):
+ *      d_state[v, :] += g * g;  d_table[v, :] -= (lr * g) / (sqrt(d_state[v, :]) + eps)   for v = node_ids[r], g = d_dH0[r, :],
+ *      fp32, every operation rounded on its own.  d_state: fp32 accumulators laid out like d_table (same ld_elems). */
+DN_API int  dn_embedding_adagrad(const dn_batch* b, float* d_table, float* d_state, int32_t dim, int64_t ld_elems,
+                                 const float* d_dH0, float lr, float eps, void* stream);
+
+/* ---- dn_softmax_xent: node-classification loss head (Section 2: the forward pass ends in a loss whose gradients
+ *      flow back; the paper does not name the loss, softmax cross-entropy is the reading taken).  For row i < n:
+ *      d_loss[i] = logsumexp(d_logits[i, :]) - d_logits[i, d_labels[i]],
+ *      d_grad[i, :] = grad_scale * (softmax(d_logits[i, :]) - onehot(d_labels[i]))   (what sage_backward takes as dL/dH^k).
+ *      Row strides ld_logits, ld_grad in floats.  A label outside [0, num_classes) gives d_loss[i] = NaN and no
+ *      onehot term; no access leaves the arrays. */
+DN_API int  dn_softmax_xent(const float* d_logits, int64_t ld_logits, const int32_t* d_labels, int64_t n, int32_t num_classes,
+                            float grad_scale, float* d_loss, float* d_grad, int64_t ld_grad, void* stream);
+
 /* Optional: builds, on `stream`, the index sage_backward needs for the transpose of the neighbour mean
  * (neighbour slots grouped by the row of H they read; with need_input_grad = 0 only the slots of layers
  * 2..k).  sage_backward builds it itself when this was not called for the current sample; calling it

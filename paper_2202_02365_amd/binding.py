@@ -63,6 +63,8 @@ def load_library():
         "dense_sample": (ctypes.c_int, [vp, vp, vp, i32, u64, vp]),
         "dense_sample_edges": (ctypes.c_int, [vp, vp, vp, vp, i32, vp, i32, u64, vp, vp, vp, vp]),
         "dn_embedding_sgd": (ctypes.c_int, [vp, vp, i32, i64, vp, ctypes.c_float, vp]),
+        "dn_embedding_adagrad": (ctypes.c_int, [vp, vp, vp, i32, i64, vp, ctypes.c_float, ctypes.c_float, vp]),
+        "dn_softmax_xent": (ctypes.c_int, [vp, i64, vp, i64, i32, ctypes.c_float, vp, vp, i64, vp]),
         "dn_batch_view": (ctypes.c_int, [vp, ctypes.POINTER(_View)]),
         "dn_batch_prepare_backward": (ctypes.c_int, [vp, i32, vp]),
         "dn_batch_counts": (ctypes.c_int, [vp, ctypes.POINTER(i64), vp]),
@@ -360,6 +362,26 @@ def embedding_sgd(batch: Batch, table: torch.Tensor, d_h0: torch.Tensor, lr: flo
     assert table.dtype == torch.float32 and table.stride(1) == 1 and d_h0.shape[1] == table.shape[1]
     _check(load_library().dn_embedding_sgd(batch.handle, table.data_ptr(), table.shape[1], table.stride(0),
                                            _dev_ptr(d_h0, torch.float32), lr, _stream()))
+
+
+def embedding_adagrad(batch: Batch, table: torch.Tensor, state: torch.Tensor, d_h0: torch.Tensor, lr: float,
+                      eps: float) -> None:
+    """Adagrad step on the rows of `table` that the batch touched; `state` has the table's shape and strides."""
+    assert table.dtype == torch.float32 and state.dtype == torch.float32 and table.stride(1) == 1
+    assert state.shape == table.shape and state.stride() == table.stride() and d_h0.shape[1] == table.shape[1]
+    _check(load_library().dn_embedding_adagrad(batch.handle, table.data_ptr(), state.data_ptr(), table.shape[1],
+                                               table.stride(0), _dev_ptr(d_h0, torch.float32), lr, eps, _stream()))
+
+
+def softmax_xent(logits: torch.Tensor, labels: torch.Tensor, loss: torch.Tensor, grad: torch.Tensor,
+                 grad_scale: float = 1.0) -> None:
+    """loss[i], grad[i, :] of the softmax cross-entropy of logits[i, :] against labels[i]."""
+    n, c = logits.shape
+    assert logits.dtype == torch.float32 and grad.dtype == torch.float32 and logits.stride(1) == 1 and grad.stride(1) == 1
+    assert grad.shape == logits.shape and labels.numel() == n and loss.numel() >= n
+    _check(load_library().dn_softmax_xent(logits.data_ptr(), logits.stride(0), _dev_ptr(labels, torch.int32), n, c,
+                                          grad_scale, _dev_ptr(loss, torch.float32), grad.data_ptr(), grad.stride(0),
+                                          _stream()))
 
 
 def dense_gather(batch: Batch, table: torch.Tensor, out: torch.Tensor) -> torch.Tensor:

@@ -312,6 +312,25 @@ int dn_embedding_sgd(const dn_batch* b, float* d_table, int32_t dim, int64_t ld_
     return dn_launch_embedding_sgd(b, d_table, dim, ld_elems, d_dH0, lr, static_cast<hipStream_t>(stream));
 }
 
+int dn_embedding_adagrad(const dn_batch* b, float* d_table, float* d_state, int32_t dim, int64_t ld_elems,
+                         const float* d_dH0, float lr, float eps, void* stream)
+{
+    if (!b || !d_table || !d_state || !d_dH0) return dn_fail(DN_EINVAL, "null argument");
+    if (dim < 1 || ld_elems < dim) return dn_fail(DN_EINVAL, "dim = %d, ld_elems = %lld", dim, (long long)ld_elems);
+    if (b->sample_serial == 0) return dn_fail(DN_ESTATE, "dense_sample has not run on this batch");
+    return dn_launch_embedding_adagrad(b, d_table, d_state, dim, ld_elems, d_dH0, lr, eps, static_cast<hipStream_t>(stream));
+}
+
+int dn_softmax_xent(const float* d_logits, int64_t ld_logits, const int32_t* d_labels, int64_t n, int32_t num_classes,
+                    float grad_scale, float* d_loss, float* d_grad, int64_t ld_grad, void* stream)
+{
+    if (n < 0 || num_classes < 1) return dn_fail(DN_EINVAL, "n = %lld, num_classes = %d", (long long)n, num_classes);
+    if (n > 0 && (!d_logits || !d_labels || !d_loss || !d_grad)) return dn_fail(DN_EINVAL, "null argument");
+    if (ld_logits < num_classes || ld_grad < num_classes) return dn_fail(DN_EINVAL, "row stride below num_classes");
+    return dn_launch_softmax_xent(d_logits, ld_logits, d_labels, n, num_classes, grad_scale, d_loss, d_grad, ld_grad,
+                                  static_cast<hipStream_t>(stream));
+}
+
 int dn_batch_prepare_backward(dn_batch* b, int32_t need_input_grad, void* stream)
 {
     if (!b) return dn_fail(DN_EINVAL, "batch is null");

@@ -153,6 +153,10 @@ int dn_launch_sample_edges(dn_batch* b, const dn_graph* g, const int32_t* d_src,
                            int32_t* d_dst_local, int32_t* d_neg_local, hipStream_t st);
 int dn_launch_embedding_sgd(const dn_batch* b, float* table, int32_t dim, int64_t ld, const float* dh0, float lr,
                             hipStream_t st);
+int dn_launch_embedding_adagrad(const dn_batch* b, float* table, float* state, int32_t dim, int64_t ld, const float* dh0,
+                                float lr, float eps, hipStream_t st);
+int dn_launch_softmax_xent(const float* logits, int64_t ld, const int32_t* labels, int64_t n, int32_t num_classes, float scale,
+                           float* loss, float* grad, int64_t ldg, hipStream_t st);
 int dn_launch_gather(const dn_batch* b, const void* table, int32_t dtype, int32_t dim, int64_t ld,
                      void* h0, hipStream_t st);
 int dn_launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t st);

@@ -62,6 +62,60 @@ __global__ __launch_bounds__(TPB) void k_embedding_sgd(const int32_t* __restrict
     }
 }
 
+// Adagrad on the touched rows, per element and in fp32 with every operation rounded on its own:
+//   state += g * g;  table -= (lr * g) / (sqrt(state) + eps).     (square root and division are correctly rounded)
+__global__ __launch_bounds__(TPB) void k_embedding_adagrad(const int32_t* __restrict__ hdr, const int32_t* __restrict__ node_ids,
+                                                           float* __restrict__ table, float* __restrict__ state, int64_t ld,
+                                                           int dim, const float* __restrict__ g, float lr, float eps)
+{
+#pragma clang fp contract(off)
+    const int N = hdr[HDR_N];
+    const int lane = threadIdx.x & 63;
+    constexpr int ROWS_PER_BLOCK = TPB / 64;
+    for (int r = blockIdx.x * ROWS_PER_BLOCK + (threadIdx.x >> 6); r < N; r += gridDim.x * ROWS_PER_BLOCK) {
+        const int64_t base = (int64_t)node_ids[r] * ld;
+        const float* gr = g + (int64_t)r * dim;
+        for (int c = lane; c < dim; c += 64) {
+            const float gv = gr[c];
+            const float sq = gv * gv;
+            const float acc = state[base + c] + sq;
+            state[base + c] = acc;
+            const float num = lr * gv;
+            const float den = sqrtf(acc) + eps;          // sqrtf and '/' are correctly rounded in device code by default
+            const float step = num / den;
+            table[base + c] = table[base + c] - step;
+        }
+    }
+}
+
+// Softmax cross-entropy head, one wave per row: loss = logsumexp(z) - z[label], grad = scale * (softmax(z) - onehot).
+// A label outside [0, C) leaves loss = NaN and grad = scale * softmax(z).
+__global__ __launch_bounds__(TPB) void k_softmax_xent(const float* __restrict__ logits, int64_t ld, const int32_t* __restrict__ labels,
+                                                      int64_t n, int C, float scale, float* __restrict__ loss,
+                                                      float* __restrict__ grad, int64_t ldg)
+{
+    const int64_t r = (int64_t)blockIdx.x * (TPB / 64) + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (r >= n) return;
+    const float* z = logits + r * ld;
+    float m = -INFINITY;
+    for (int c = lane; c < C; c += 64) m = fmaxf(m, z[c]);
+    for (int s = 32; s > 0; s >>= 1) m = fmaxf(m, __shfl_xor(m, s, 64));
+    float sum = 0.f;
+    for (int c = lane; c < C; c += 64) sum += expf(z[c] - m);
+    for (int s = 32; s > 0; s >>= 1) sum += __shfl_xor(sum, s, 64);
+    const int lab = labels[r];
+    const bool ok = (unsigned)lab < (unsigned)C;
+    const float lse = m + logf(sum);
+    if (lane == 0) loss[r] = ok ? lse - z[lab] : __int_as_float(0x7fc00000);
+    const float inv = 1.f / sum;
+    for (int c = lane; c < C; c += 64) {
+        float p = expf(z[c] - m) * inv;
+        if (ok && c == lab) p -= 1.f;
+        grad[r * ldg + c] = scale * p;
+    }
+}
+
 // Plain streaming copy of known size: the reference a profiler's byte counters are scaled by.
 __global__ __launch_bounds__(TPB) void k_calibration_copy(const u32x4* __restrict__ src, u32x4* __restrict__ dst, int64_t n16)
 {
@@ -80,6 +134,31 @@ int dn_launch_embedding_sgd(const dn_batch* b, float* table, int32_t dim, int64_
     dn_prof_scope ps("embedding_sgd", 0, st);
     hipLaunchKernelGGL(k_embedding_sgd, dim3((int)grid), dim3(TPB), 0, st, b->hdr, b->node_ids, table, ld, dim, dh0, lr);
     DN_LAUNCH_CHECK("k_embedding_sgd");
+    return DN_OK;
+}
+
+int dn_launch_embedding_adagrad(const dn_batch* b, float* table, float* state, int32_t dim, int64_t ld, const float* dh0,
+                                float lr, float eps, hipStream_t st)
+{
+    int64_t grid = (b->cap_nodes + 3) / 4;
+    if (grid > 4096) grid = 4096;
+    if (grid < 1) grid = 1;
+    dn_prof_scope ps("embedding_adagrad", 0, st);
+    hipLaunchKernelGGL(k_embedding_adagrad, dim3((int)grid), dim3(TPB), 0, st, b->hdr, b->node_ids, table, state, ld, dim, dh0,
+                       lr, eps);
+    DN_LAUNCH_CHECK("k_embedding_adagrad");
+    return DN_OK;
+}
+
+int dn_launch_softmax_xent(const float* logits, int64_t ld, const int32_t* labels, int64_t n, int32_t num_classes, float scale,
+                           float* loss, float* grad, int64_t ldg, hipStream_t st)
+{
+    if (n == 0) return DN_OK;
+    dn_prof_scope ps("softmax_xent", 0, st);
+    const int64_t grid = (n + TPB / 64 - 1) / (TPB / 64);
+    hipLaunchKernelGGL(k_softmax_xent, dim3((int)grid), dim3(TPB), 0, st, logits, ld, labels, n, num_classes, scale, loss,
+                       grad, ldg);
+    DN_LAUNCH_CHECK("k_softmax_xent");
     return DN_OK;
 }
 

@@ -242,3 +242,52 @@ def test_embedding_sgd_bit_exact(g16k):
     dn.embedding_sgd(batch, t_dev, torch.from_numpy(grad).to("cuda:0"), 0.05)
     want = oracle.embedding_sgd(table, view["node_ids"], grad[:n], 0.05)
     assert np.array_equal(t_dev.cpu().numpy().view(np.uint32), want.view(np.uint32))
+
+
+def test_embedding_adagrad_bit_exact(g16k):
+    cfg = CONFIGS[0]
+    batch = dn.Batch(cfg.num_nodes, cfg.batch, cfg.fanouts)
+    targets = target_batch(cfg.num_nodes, cfg.batch, 3)
+    view = gpu_sample(g16k, batch, targets, seed=7)
+    n = len(view["node_ids"])
+    rng = np.random.default_rng(2)
+    table = rng.standard_normal((cfg.num_nodes, 100)).astype(np.float32)
+    state = (rng.random((cfg.num_nodes, 100)) * 0.3).astype(np.float32)
+    state[::3] = 0.0                                                   # fresh rows: accumulator starts at zero
+    grad = rng.standard_normal((batch.node_capacity, 100)).astype(np.float32)
+    grad[:, 5] = 0.0                                                   # zero gradient on a zero accumulator: 0 / eps
+    t_dev, s_dev, g_dev = (torch.from_numpy(a).to("cuda:0") for a in (table, state, grad))
+    for step in range(2):                                              # two steps: the accumulator carries over
+        dn.embedding_adagrad(batch, t_dev, s_dev, g_dev, 0.05, 1e-8)
+        table, state = oracle.embedding_adagrad(table, state, view["node_ids"], grad[:n], 0.05, 1e-8)
+        assert np.array_equal(s_dev.cpu().numpy().view(np.uint32), state.view(np.uint32)), step
+        assert np.array_equal(t_dev.cpu().numpy().view(np.uint32), table.view(np.uint32)), step
+
+
+@pytest.mark.parametrize("n,c", [(1000, 172), (3, 1), (257, 64), (50, 1000)])
+def test_softmax_xent_head(n, c):
+    rng = np.random.default_rng([3, n, c])
+    logits = (4.0 * rng.standard_normal((n, c))).astype(np.float32)
+    logits[0, :] += 200.0                                              # large logits: no overflow
+    labels = rng.integers(0, c, n).astype(np.int32)
+    z, lab = torch.from_numpy(logits).to("cuda:0"), torch.from_numpy(labels).to("cuda:0")
+    loss, grad = torch.empty(n, device="cuda:0"), torch.empty((n, c), device="cuda:0")
+    dn.softmax_xent(z, lab, loss, grad, grad_scale=1.0 / n)
+    want_loss, want_grad = oracle.softmax_xent(logits, labels, grad_scale=1.0 / n)
+    # loss against the scale of the logits that enter it; gradient rows against their L2 norm (1e-4 bar)
+    scale = np.maximum(np.abs(logits).max(axis=1), 1.0)
+    assert np.max(np.abs(loss.cpu().numpy() - want_loss) / scale) <= 1e-5
+    g = grad.cpu().numpy().astype(np.float64)
+    err = np.abs(g - want_grad).max(axis=1) / np.maximum(np.linalg.norm(want_grad, axis=1), 1e-300)
+    assert err.max() <= 1e-4, err.max()
+
+
+def test_softmax_xent_bad_label_and_empty():
+    z = torch.zeros((2, 4), device="cuda:0")
+    lab = torch.tensor([1, 9], dtype=torch.int32, device="cuda:0")
+    loss, grad = torch.empty(2, device="cuda:0"), torch.empty((2, 4), device="cuda:0")
+    dn.softmax_xent(z, lab, loss, grad)
+    l = loss.cpu().numpy()
+    assert l[0] == pytest.approx(np.log(4.0), rel=1e-6) and np.isnan(l[1])
+    assert np.allclose(grad.cpu().numpy()[1], 0.25)
+    dn.softmax_xent(torch.empty((0, 4), device="cuda:0"), lab[:0], loss[:0], torch.empty((0, 4), device="cuda:0"))
