@@ -163,7 +163,7 @@ __global__ __launch_bounds__(TPB, 2) void k_dm_gemm(DmGemm g)
     const uint16_t* A = g.A + (int64_t)z * g.stride_a + (int64_t)row0 * g.lda;
     const uint16_t* B = g.B + (int64_t)(z % g.b_mod) * g.stride_b + (int64_t)col0 * g.ldb;
     f32x16 acc[2][2];
-    mainloop<WRAP>(A, g.lda, B, g.ldb, 0, g.kchunks, g.b_wrap_chunks, acc);
+    mainloop<BM, BN, WRAP>(A, g.lda, B, g.ldb, 0, g.kchunks, g.b_wrap_chunks, acc);
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     float* C = g.C + (int64_t)z * g.stride_c;
