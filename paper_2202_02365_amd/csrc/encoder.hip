@@ -184,12 +184,14 @@ __global__ __launch_bounds__(TPB) void k_transpose_x_group(const int32_t* __rest
 // row) + sum over the slots that read r, in ascending slot order, of dX_mean[owner] / count[owner].
 // tr_ptr / tr_val: slots grouped by the node_ids position they read, ascending within a group;
 // a layer's slots are those >= its first slot, i.e. a suffix of every group.
+constexpr int HUB_ENTRIES_PER_BLOCK = 4;
 template <int V, int LANES, int ITERS>
 __global__ __launch_bounds__(TPB) void k_aggregate_bwd(const int32_t* __restrict__ hdr, int layer,
                                                        const int32_t* __restrict__ nbr_offsets,
                                                        const int32_t* __restrict__ tr_ptr, const int32_t* __restrict__ tr_val,
                                                        const int32_t* __restrict__ tr_own, const float* __restrict__ tr_inv,
-                                                       const int32_t* __restrict__ tr_long, int row_blocks, int mean_agg,
+                                                       const int32_t* __restrict__ tr_long, int n_long, int row_blocks,
+                                                       int mean_agg,
                                                        const float* __restrict__ dX, int ldx, int d,
                                                        float* __restrict__ Gin)
 {
@@ -204,53 +206,63 @@ __global__ __launch_bounds__(TPB) void k_aggregate_bwd(const int32_t* __restrict
     const float* dXm = dX + (int64_t)(off1 - off_out) * ldx + d;     // row q of this: dX_mean of owner q
 
     if ((int)blockIdx.x >= row_blocks) {
-        // A row read by more than DN_LONG_GROUP slots (a hub): the whole workgroup sums it.  Lane group g takes
-        // the slots g, g + GROUPS, ... in ascending order, four in flight; the groups' sums are added in order of g.
+        // Rows read by more than DN_LONG_GROUP slots (hubs): each workgroup after the row blocks looks at a few
+        // entries of the register of such rows and sums the rows it finds there with all of its lanes.
+        // Lane group g takes the slots g, g + GROUPS, ... in ascending order, four in flight; the groups' sums are
+        // added in order of g.
         __shared__ float part[GROUPS][LANES * V * ITERS];
-        const int p = tr_long[blockIdx.x - row_blocks] - 1;
-        if (p < off_in) return;
-        const int r = p - off_in, g = threadIdx.x / LANES;
-        const int beg = tr_ptr[p], end = tr_ptr[p + 1];
-        float acc[ITERS][V];
-#pragma unroll
-        for (int it = 0; it < ITERS; ++it)
-#pragma unroll
-            for (int e = 0; e < V; ++e) acc[it][e] = 0.f;
-        for (int t0 = beg + g; t0 < end; t0 += 4 * GROUPS) {
-            int q[4];
-            float inv[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int t = t0 + u * GROUPS;
-                const bool valid = t < end && tr_val[t] >= first_slot;
-                q[u] = valid ? tr_own[t] : -1;
-                inv[u] = valid ? (mean_agg ? tr_inv[t] : 1.f) : 0.f;
-            }
-            float v[4][ITERS][V];
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-#pragma unroll
-                for (int it = 0; it < ITERS; ++it) {
-                    const int c0 = (it * LANES + lane) * V;
-#pragma unroll
-                    for (int e = 0; e < V; ++e) v[u][it][e] = (q[u] >= 0 && c0 < d) ? dXm[(int64_t)q[u] * ldx + c0 + e] : 0.f;
-                }
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
+        const int g = threadIdx.x / LANES;
+        {
+            const int c0 = ((int)blockIdx.x - row_blocks) * HUB_ENTRIES_PER_BLOCK;
+            for (int f = 0; f < HUB_ENTRIES_PER_BLOCK; ++f) {
+                const int entry = c0 + f < n_long ? tr_long[c0 + f] : 0;
+                if (entry <= off_in) continue;                 // none, or a row that is no input of this layer
+                const int p = entry - 1;
+                const int r = p - off_in;
+                const int beg = tr_ptr[p], end = tr_ptr[p + 1];
+                float acc[ITERS][V];
 #pragma unroll
                 for (int it = 0; it < ITERS; ++it)
 #pragma unroll
-                    for (int e = 0; e < V; ++e) acc[it][e] += v[u][it][e] * inv[u];
-        }
+                    for (int e = 0; e < V; ++e) acc[it][e] = 0.f;
+                for (int t0 = beg + g; t0 < end; t0 += 4 * GROUPS) {
+                    int q[4];
+                    float inv[4];
 #pragma unroll
-        for (int it = 0; it < ITERS; ++it)
+                    for (int u = 0; u < 4; ++u) {
+                        const int t = t0 + u * GROUPS;
+                        const bool valid = t < end && tr_val[t] >= first_slot;
+                        q[u] = valid ? tr_own[t] : -1;
+                        inv[u] = valid ? (mean_agg ? tr_inv[t] : 1.f) : 0.f;
+                    }
+                    float v[4][ITERS][V];
 #pragma unroll
-            for (int e = 0; e < V; ++e) part[g][(it * LANES + lane) * V + e] = acc[it][e];
-        __syncthreads();
-        for (int c = threadIdx.x; c < d; c += TPB) {
-            float tot = (p >= off_out) ? dX[(int64_t)(p - off_out) * ldx + c] : 0.f;
-            for (int w = 0; w < GROUPS; ++w) tot += part[w][c];
-            Gin[(int64_t)r * d + c] = tot;
+                    for (int u = 0; u < 4; ++u)
+#pragma unroll
+                        for (int it = 0; it < ITERS; ++it) {
+                            const int c0v = (it * LANES + lane) * V;
+#pragma unroll
+                            for (int e = 0; e < V; ++e) v[u][it][e] = (q[u] >= 0 && c0v < d) ? dXm[(int64_t)q[u] * ldx + c0v + e] : 0.f;
+                        }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+#pragma unroll
+                        for (int it = 0; it < ITERS; ++it)
+#pragma unroll
+                            for (int e = 0; e < V; ++e) acc[it][e] += v[u][it][e] * inv[u];
+                }
+#pragma unroll
+                for (int it = 0; it < ITERS; ++it)
+#pragma unroll
+                    for (int e = 0; e < V; ++e) part[g][(it * LANES + lane) * V + e] = acc[it][e];
+                __syncthreads();
+                for (int c = threadIdx.x; c < d; c += TPB) {
+                    float tot = (p >= off_out) ? dX[(int64_t)(p - off_out) * ldx + c] : 0.f;
+                    for (int w = 0; w < GROUPS; ++w) tot += part[w][c];
+                    Gin[(int64_t)r * d + c] = tot;
+                }
+                __syncthreads();
+            }
         }
         return;
     }
@@ -355,15 +367,21 @@ int launch_aggregate_bwd(const dn_model* m, const dn_batch* b, int i, float* gin
     const int groups = TPB / lanes;
     const int64_t rows_in_cap = i >= 2 ? m->layer[i - 2].rows_cap : b->cap_nodes;
     int64_t row_blocks = (rows_in_cap + groups - 1) / groups;
-    if (row_blocks > 65536) row_blocks = 65536;
+    // capacity is an upper bound that real batches stay far below: a block per eight capacity row groups, within [8192, 65536]
+    int64_t want = row_blocks / 8;
+    if (want < 8192) want = 8192;
+    if (want > 65536) want = 65536;
+    if (row_blocks > want) row_blocks = want;
     if (row_blocks < 1) row_blocks = 1;
-    // one more workgroup per block of DN_LONG_GROUP transposed slots: it sums the hub row registered there, if any
-    const int64_t grid = row_blocks + b->cap_slots / DN_LONG_GROUP + 1;
+    // a few more workgroups scan the register of hub rows (one entry per DN_LONG_GROUP transposed slots) and sum those
+    const int n_long = (int)(b->cap_slots / DN_LONG_GROUP + 1);
+    const int hub_blocks = (n_long + HUB_ENTRIES_PER_BLOCK - 1) / HUB_ENTRIES_PER_BLOCK;
+    const int64_t grid = row_blocks + hub_blocks;
     dn_prof_scope ps("aggregate_bwd", i, st);
 #define DN_AGGB(VV, LL, II)                                                                                           \
     hipLaunchKernelGGL((k_aggregate_bwd<VV, LL, II>), dim3((int)grid), dim3(TPB), 0, st, b->hdr, i, b->nbr_offsets,   \
-                       b->tr_ptr, b->tr_val[0], b->tr_own, b->tr_inv, b->tr_long, (int)row_blocks, m->mean_agg, m->dx, 2 * d, d,   \
-                       gin)
+                       b->tr_ptr, b->tr_val[0], b->tr_own, b->tr_inv, b->tr_long, n_long, (int)row_blocks, m->mean_agg, m->dx,  \
+                       2 * d, d, gin)
     if (vec4 && d <= 256) {
         switch (lanes) {
             case 4: DN_AGGB(4, 4, 1); break;
