@@ -133,8 +133,9 @@ def cpu_baseline(cfg, inputs, sizes, budget_s=20.0):
 
 
 def run_link_prediction(args, cfg):
-    """Link-prediction step: dense_sample_edges -> dense_gather -> sage_forward -> distmult_forward ->
-    distmult_backward -> sage_backward (with dL/dH^0) -> dn_embedding_sgd, one batch of positive edges per step."""
+    """Link-prediction step: dense_sample_edges -> sage_forward_table (or dense_gather + sage_forward) ->
+    distmult_forward -> distmult_backward -> sage_backward (with dL/dH^0) -> dn_embedding_sgd, one batch of positive
+    edges per step."""
     import numpy as np
     import torch
     import paper_2202_02365_amd as dn
@@ -158,7 +159,8 @@ def run_link_prediction(args, cfg):
         m = dn.Model(b, dims, dn.DN_F32)
         m.set_weights(w_self, w_nbr, bias)
         return dict(batch=b, model=m, dec=dn.Decoder(B, chunk, Nn, dims[-1], cfg.batch, num_rel),
-                    h0=torch.empty((b.node_capacity, dims[0]), device=dev), out=torch.empty((cfg.batch, dims[-1]), device=dev),
+                    h0=torch.empty((b.node_capacity, dims[0]), device=dev) if args.separate_gather else None,
+                    out=torch.empty((cfg.batch, dims[-1]), device=dev),
                     pos=torch.empty(B, device=dev), loss=torch.empty(B, device=dev),
                     g_out=torch.empty((cfg.batch, dims[-1]), device=dev), g_rel=torch.empty((num_rel, dims[-1]), device=dev),
                     dws=[torch.empty_like(w) for w in w_self], dwn=[torch.empty_like(w) for w in w_nbr],
@@ -168,8 +170,11 @@ def run_link_prediction(args, cfg):
     def step(o, bi, update=True):
         src, rel, dst, neg = batches[bi % n_batches]
         ls, ld, ln = dn.dense_sample_edges(o["batch"], graph, src, dst, neg.reshape(-1), bi)
-        dn.dense_gather(o["batch"], table, o["h0"])
-        dn.sage_forward(o["model"], o["batch"], o["h0"], o["out"])
+        if args.separate_gather:
+            dn.dense_gather(o["batch"], table, o["h0"])
+            dn.sage_forward(o["model"], o["batch"], o["h0"], o["out"])
+        else:
+            dn.sage_forward_table(o["model"], o["batch"], table, o["out"])
         dn.distmult_forward(o["dec"], o["out"], R, ls, rel, ld, ln.view(-1, Nn), o["pos"], o["loss"])
         dn.distmult_backward(o["dec"], o["g_out"], o["g_rel"])
         dn.sage_backward(o["model"], o["batch"], o["g_out"], o["dws"], o["dwn"], o["dbs"], o["dh0"])
