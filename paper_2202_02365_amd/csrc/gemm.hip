@@ -173,10 +173,17 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const int bx, const
 
 // LAYER_TAG only gives every layer's launch its own kernel symbol, so that a profiler's per-kernel
 // statistics do not mix the layers (tag 4 stands for "layer 4 and above").
+// Workgroups are handed to the 8 XCDs (each with an L2 of its own) round-robin in launch order.  The column
+// tiles of one row tile read the same rows of A: the launch order is therefore re-read as chunks of 8 x (column
+// tiles), in which the workgroups j, j + 8, j + 16, ... (same XCD) are the column tiles of one row tile.
+// gridDim.y is a multiple of 8.
 template <int EPI, int LAYER_TAG, int BM_, int BN_>
 __global__ __launch_bounds__(TPB, (BM_ == 64 && BN_ == 64) ? 4 : 2) void k_gemm_nt(GemmArgs a)
 {
-    gemm_tile<EPI, BM_, BN_>(a, blockIdx.x, blockIdx.y, blockIdx.z, gridDim.z);
+    const int nx = gridDim.x;
+    const int id = blockIdx.x + nx * blockIdx.y;
+    const int chunk = id / (8 * nx), j = id - chunk * 8 * nx;
+    gemm_tile<EPI, BM_, BN_>(a, j >> 3, chunk * 8 + (j & 7), blockIdx.z, gridDim.z);
 }
 
 // The dW GEMMs of all layers in one launch: a 1-D grid, each layer owns the workgroups
@@ -192,6 +199,8 @@ __global__ __launch_bounds__(TPB, (BM_ == 64 && BN_ == 64) ? 4 : 2) void k_gemm_
 {
     int gi = 0;
     while (gi + 1 < G.n && (int)blockIdx.x >= G.begin[gi + 1]) ++gi;
+    // (placing the tiles of one reduction split on one XCD, so that its L2 serves their shared operand rows, was
+    // measured slower: 34 vs 27 us)
     const int local = (int)blockIdx.x - G.begin[gi];
     const int bx = local % G.gx[gi], by = (local / G.gx[gi]) % G.gy[gi], bz = local / (G.gx[gi] * G.gy[gi]);
     gemm_tile<EPI_SPLIT, BM_, BN_>(G.g[gi], bx, by, bz, G.gz[gi]);
@@ -336,8 +345,8 @@ int gemm_tile_edge_dw()
 template <int EPI, int T>
 int launch_t(const GemmArgs& a, int64_t m_cap, int splits, hipStream_t st)
 {
-    dim3 grid((unsigned)((a.ncols + T - 1) / T), (unsigned)((m_cap + T - 1) / T), (unsigned)splits);
-    if (grid.y == 0) grid.y = 1;
+    dim3 grid((unsigned)((a.ncols + T - 1) / T), (unsigned)dn_round_up((m_cap + T - 1) / T, 8), (unsigned)splits);
+    if (grid.y == 0) grid.y = 8;
     switch (a.layer) {
         case 1: hipLaunchKernelGGL((k_gemm_nt<EPI, 1, T, T>), grid, dim3(TPB), 0, st, a); break;
         case 2: hipLaunchKernelGGL((k_gemm_nt<EPI, 2, T, T>), grid, dim3(TPB), 0, st, a); break;
