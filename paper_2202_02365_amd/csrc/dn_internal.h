@@ -170,6 +170,7 @@ constexpr int DN_SORT_TILE = 2048;
 struct dn_sort_plan { int passes, bits, nblocks, total, sblocks; };
 dn_sort_plan dn_sort_make_plan(int64_t key_range, int64_t cap_items);
 int64_t dn_sort_hist_words(const dn_sort_plan& p);
+bool dn_sort_counts_separately(const dn_sort_plan& p);   // true: the caller's first kernel must NOT count the first digit
 // Optional by-products of the last kernel, for values that are slot numbers of a DENSE sample (null otherwise):
 // own_out[t] = slot_owner[val[t]], inv_out[t] = 1 / (number of slots of that owner), and
 // long_out[first / DN_LONG_GROUP] = key + 1 for every key whose group of more than DN_LONG_GROUP sorted pairs

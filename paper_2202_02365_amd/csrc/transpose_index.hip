@@ -41,11 +41,32 @@ __global__ void k_tr_init(int32_t* __restrict__ hdr, int need_all, int k, const 
         const int kv = repr_map[first + i];
         key[i] = kv;
         val[i] = first + i;
-        atomicAdd(&hist[(kv & radix_mask) * nblocks + i / TILE], 1);
+        if (hist) atomicAdd(&hist[(kv & radix_mask) * nblocks + i / TILE], 1);
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         hdr[HDR_TR_FIRST] = first;
         hdr[HDR_TR_COUNT] = cnt;
+    }
+}
+
+// Digit histogram per tile without global atomics, for sorts of millions of pairs (there the atomics of the
+// fused counting, one per pair at scattered addresses, cost more than a pass over the keys): a workgroup counts a
+// tile's digits in LDS and stores the tile's column of the histogram.
+__global__ __launch_bounds__(TPB) void k_radix_hist(const int32_t* __restrict__ count_ptr, const int32_t* __restrict__ key,
+                                                    int shift, int bits, int nblocks, int32_t* __restrict__ hist)
+{
+    __shared__ int cnt[MAX_RADIX];
+    const int radix = 1 << bits;
+    const int n = *count_ptr;
+    for (int tile = blockIdx.x; tile * TILE < n; tile += gridDim.x) {
+        for (int d = threadIdx.x; d < radix; d += TPB) cnt[d] = 0;
+        __syncthreads();
+        const int base = tile * TILE;
+        for (int e = threadIdx.x; e < TILE; e += TPB)
+            if (base + e < n) atomicAdd(&cnt[(key[base + e] >> shift) & (radix - 1)], 1);
+        __syncthreads();
+        for (int d = threadIdx.x; d < radix; d += TPB) hist[d * nblocks + tile] = cnt[d];
+        __syncthreads();
     }
 }
 
@@ -208,6 +229,10 @@ dn_sort_plan dn_sort_make_plan(int64_t key_range, int64_t cap_items)
     return p;
 }
 
+// Sorts planned for more than two million pairs count digits in a pass of their own (k_radix_hist); the caller's
+// first kernel then leaves the histogram alone.
+bool dn_sort_counts_separately(const dn_sort_plan& p) { return p.nblocks > 1024; }
+
 // ints of histogram space (two alternating histograms + scan partials); they must start at zero
 int64_t dn_sort_hist_words(const dn_sort_plan& p) { return 2 * (int64_t)p.total + p.sblocks + 64; }
 
@@ -222,6 +247,13 @@ int dn_sort_pairs_run(const dn_sort_plan& pl, const int32_t* count_ptr, int32_t*
     int32_t* part = hist_space + 2 * (int64_t)pl.total;
     int src = pl.passes & 1;                                // so that the last pass lands in buffer 0
     int h = 0;                                              // histogram buffer 0 is zero on entry
+    const bool big = dn_sort_counts_separately(pl);
+    int hist_grid = pl.nblocks < 4096 ? pl.nblocks : 4096;
+    if (big) {
+        // the caller's kernel left the first digit uncounted
+        hipLaunchKernelGGL(k_radix_hist, dim3(hist_grid), dim3(TPB), 0, st, count_ptr, key[src], 0, pl.bits, pl.nblocks, hist[0]);
+        DN_LAUNCH_CHECK("k_radix_hist");
+    }
     for (int p = 0; p < pl.passes; ++p) {
         const int shift = pl.bits * p;
         const int hn = h ^ 1;
@@ -231,8 +263,13 @@ int dn_sort_pairs_run(const dn_sort_plan& pl, const int32_t* count_ptr, int32_t*
         DN_LAUNCH_CHECK("k_scan_apply");
         const int next_bits = (p + 1 < pl.passes) ? pl.bits : 0;
         hipLaunchKernelGGL(k_radix_scatter, dim3(pl.nblocks), dim3(TPB), 0, st, count_ptr, key[src], val[src],
-                           shift, pl.bits, pl.nblocks, hist[h], key[src ^ 1], val[src ^ 1], next_bits, hist[hn]);
+                           shift, pl.bits, pl.nblocks, hist[h], key[src ^ 1], val[src ^ 1], big ? 0 : next_bits, hist[hn]);
         DN_LAUNCH_CHECK("k_radix_scatter");
+        if (big && next_bits > 0) {
+            hipLaunchKernelGGL(k_radix_hist, dim3(hist_grid), dim3(TPB), 0, st, count_ptr, key[src ^ 1], shift + pl.bits, pl.bits,
+                               pl.nblocks, hist[hn]);
+            DN_LAUNCH_CHECK("k_radix_hist");
+        }
         src ^= 1;
         h = hn;
     }
@@ -264,7 +301,8 @@ int dn_launch_transpose_index(dn_batch* b, int need_all, hipStream_t st)
     if (g < 1) g = 1;
     const int src = pl.passes & 1;
     hipLaunchKernelGGL(k_tr_init, dim3((int)g), dim3(TPB), 0, st, b->hdr, need_all, b->k, b->nbr_offsets, b->repr_map,
-                       b->tr_key[src], b->tr_val[src], (1 << pl.bits) - 1, pl.nblocks, b->tr_hist, b->tr_long,
+                       b->tr_key[src], b->tr_val[src], (1 << pl.bits) - 1, pl.nblocks,
+                       dn_sort_counts_separately(pl) ? nullptr : b->tr_hist, b->tr_long,
                        (int)b->tr_long_words);
     DN_LAUNCH_CHECK("k_tr_init");
     const dn_sort_slot_info info = { b->slot_owner, b->nbr_offsets, b->tr_own, b->tr_inv, b->tr_long };
