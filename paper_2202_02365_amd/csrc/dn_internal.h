@@ -189,6 +189,9 @@ int dn_launch_forward(dn_model* m, const dn_batch* b, const void* h0, int64_t ld
 int dn_launch_backward(dn_model* m, dn_batch* b, const float* grad_out, float* const* dws,
                        float* const* dwn, float* const* dbias, float* dh0, hipStream_t st);
 
+// row-tile workgroups of the dZ kernel = partial column sums the bias-gradient reduction adds up
+constexpr unsigned DN_DZ_MAX_ROW_BLOCKS = 512;
+
 // GEMM entry points (gemm.hip), layer index i is 1-based
 int dn_gemm_forward(const dn_model* m, const dn_batch* b, int i, float* out, int64_t ldc, hipStream_t st);
 int dn_gemm_dx(const dn_model* m, const dn_batch* b, int i, hipStream_t st);

@@ -113,10 +113,10 @@ __global__ __launch_bounds__(TPB) void k_dz(const int32_t* __restrict__ hdr, int
     const int c0 = blockIdx.x * 64;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;    // ty: 0..3
     const int nz = TERMS * np;
+    float csum = 0.f;                    // this thread's column sum over all row tiles of this workgroup, in order
   for (int rt = blockIdx.y; rt * 64 < rows; rt += gridDim.y) {
     const int r0 = rt * 64;
     __syncthreads();
-    float csum = 0.f;
     for (int rr = ty; rr < 64; rr += 4) {
         const int r = r0 + rr, n = c0 + tx;
         float v = 0.f;
@@ -134,14 +134,18 @@ __global__ __launch_bounds__(TPB) void k_dz(const int32_t* __restrict__ hdr, int
             if (r < rows) dzb[(int64_t)r * nz + np + n] = lo;
         }
     }
-    colsum[ty][tx] = csum;
     __syncthreads();
-    if (ty == 0 && c0 + tx < d_out)
-        db_partial[(int64_t)rt * d_out + c0 + tx] = (colsum[0][tx] + colsum[1][tx]) + (colsum[2][tx] + colsum[3][tx]);
     for (int t = 0; t < TERMS; ++t)
         for (int cc = ty; cc < 64; cc += 4)
             dzbt[t * term_stride + (int64_t)(c0 + cc) * rows_pad + r0 + tx] = tile[t][tx][cc];
   }
+    // one partial column sum per workgroup that had row tiles (the reduction reads min(gridDim.y, tiles) of them)
+    if ((int)blockIdx.y * 64 < rows) {
+        colsum[ty][tx] = csum;
+        __syncthreads();
+        if (ty == 0 && c0 + tx < d_out)
+            db_partial[(int64_t)blockIdx.y * d_out + c0 + tx] = (colsum[0][tx] + colsum[1][tx]) + (colsum[2][tx] + colsum[3][tx]);
+    }
 }
 
 // X [rows x kp] -> X^T [kp x rows_pad], zero for rows up to the next multiple of 64; all layers in one
@@ -438,7 +442,7 @@ int dn_launch_backward(dn_model* m, dn_batch* b, const float* grad_out, float* c
     for (int i = k; i >= 1; --i) {
         const dn_layer_bufs& L = m->layer[i - 1];
         unsigned row_tiles = (unsigned)((L.rows_cap + 63) / 64);
-        if (row_tiles > 65535) row_tiles = 65535;           // the kernels stride over the row tiles beyond the grid
+        if (row_tiles > DN_DZ_MAX_ROW_BLOCKS) row_tiles = DN_DZ_MAX_ROW_BLOCKS;   // the kernel strides over the row tiles beyond the grid
         { dn_prof_scope ps("dz", i, st);
         if (L.zterms == 2)
             hipLaunchKernelGGL((k_dz<2>), dim3((unsigned)(L.np / 64), row_tiles ? row_tiles : 1), dim3(TPB), 0, st, b->hdr,

@@ -235,7 +235,7 @@ __device__ __forceinline__ void dw_reduce_block(const int block, const float* __
     else dwn[(int64_t)(kk - d_in) * d_out + n] = s;
 }
 
-// db[n] = sum over the row tiles of the dZ kernel.  64 columns per workgroup; each of its 4 waves takes
+// db[n] = sum over the partial column sums of the dZ kernel's row-tile workgroups.  64 columns per workgroup; each of its 4 waves takes
 // every fourth tile (lanes = columns, coalesced), the four partial sums are combined in a fixed order.
 __device__ __forceinline__ void db_reduce_block(const int block, int rows, const float* __restrict__ db_partial, int d_out,
                                                 float* __restrict__ db)
@@ -243,7 +243,8 @@ __device__ __forceinline__ void db_reduce_block(const int block, int rows, const
     __shared__ float part[4][64];
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     const int n = block * 64 + tx;
-    const int tiles = (rows + 63) / 64;
+    const int all_tiles = (rows + 63) / 64;
+    const int tiles = all_tiles < (int)DN_DZ_MAX_ROW_BLOCKS ? all_tiles : (int)DN_DZ_MAX_ROW_BLOCKS;   // partial sums the dZ kernel wrote
     float s0 = 0.f, s1 = 0.f;
     if (n < d_out) {
         int t = ty;
