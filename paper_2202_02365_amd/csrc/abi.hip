@@ -115,7 +115,7 @@ int fill_model(dn_model* m, const dn_batch* b, int32_t k, const int32_t* dims, i
 void carve_model(dn_model* m, const dn_batch* b, Carver& c)
 {
     const int k = m->k;
-    int64_t max_dzb = 0, max_dx = 0, max_g = 0;
+    int64_t max_dx = 0, max_g = 0;
     m->splits = 32;
     for (int i = 1; i <= k; ++i) {
         dn_layer_bufs& L = m->layer[i - 1];
@@ -126,17 +126,13 @@ void carve_model(dn_model* m, const dn_batch* b, Carver& c)
         L.bias = c.take<float>(L.d_out);
         L.rownorm = c.take<float>(L.rows_pad);
         L.colnorm = c.take<float>(L.d_out);
-        L.xt = c.take<dn_bf16>(dn_round_up(L.kp, 128) * L.rows_pad);
-        L.dzbt_term_stride = dn_round_up(L.d_out, 128) * L.rows_pad;
-        L.dzbt = c.take<dn_bf16>(L.zterms * L.dzbt_term_stride);
+        L.dzb = c.take<dn_bf16>(L.rows_pad * L.nz);
         L.partial_floats = (int64_t)m->splits * L.kx * L.d_out * L.zterms;
         L.partial = c.take<float>(L.partial_floats);
         L.db_partial = c.take<float>(((L.rows_cap + 63) / 64 + 1) * L.d_out);
-        max_dzb = std::max<int64_t>(max_dzb, L.rows_pad * L.nz);
         max_dx = std::max<int64_t>(max_dx, L.rows_pad * 2 * L.d_in);
         if (i < k) max_g = std::max<int64_t>(max_g, L.rows_pad * L.d_out);   // gradient w.r.t. H^i
     }
-    m->dzb = c.take<dn_bf16>(max_dzb);
     m->dx = c.take<float>(max_dx);
     m->g[0] = c.take<float>(max_g);
     m->g[1] = c.take<float>(max_g);

@@ -80,10 +80,10 @@ struct dn_layer_bufs {
     float* bias;         // [d_out]
     float* rownorm;      // [rows_pad] L2 norm of each X row (bounds the accumulation error of Z)
     float* colnorm;      // [d_out]    L2 norm of each Wcat^T row
-    // backward operands of the weight-gradient chain, per layer so that the chains of different layers overlap
-    dn_bf16* xt;         // [round128(kp) x rows_pad]  X^T
-    dn_bf16* dzbt;       // zterms x [round128(d_out) x rows_pad]  bf16 terms of dZ^T
-    int64_t dzbt_term_stride;
+    // bf16 terms of dZ, row-major [rows_pad x nz] (term t in columns [t*np, (t+1)*np)): A operand of the dX GEMM and,
+    // with X, operand of the weight-gradient GEMM (both are read with the node index as the reduction index);
+    // per layer, because the weight gradients of all layers are computed in one launch after the chain
+    dn_bf16* dzb;
     float* partial;      // split-K partials of dWcat
     int64_t partial_floats;
     float* db_partial;   // per row-tile column sums of dZ
@@ -94,7 +94,6 @@ struct dn_model {
     int32_t dims[DN_MAX_LAYERS + 1];
     dn_layer_bufs layer[DN_MAX_LAYERS];
     // backward temporaries, sized for the largest layer
-    dn_bf16* dzb;                  // bf16 terms of dZ, row-major (A operand of the dX GEMM)
     float *dx, *g[2];
     int32_t splits;
 

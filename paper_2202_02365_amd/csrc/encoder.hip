@@ -95,91 +95,44 @@ __global__ __launch_bounds__(TPB) void k_aggregate(const int32_t* __restrict__ h
     }
 }
 
-// ---------------------------------------------------------------- backward: dZ, its transpose, db
-// Tile of 64 rows x 64 columns per workgroup.  dZ = G (.) [H > 0] (ReLU layers) or G.
-// Writes bf16 terms of dZ row-major [rows x TERMS*np] (hi block, then lo block; zero in the
-// padding columns), their transposes [np x rows_pad] per term (zero for rows up to the next
-// multiple of 64, which the dW reduction reads), and the tile's column sums of the unrounded dZ
-// for the bias gradient.
+// ---------------------------------------------------------------- backward: dZ and db
+// Tile of 64 rows x 64 columns per workgroup (striding over the row tiles beyond the grid).
+// dZ = G (.) [H > 0] (ReLU layers) or G.  Writes the bf16 terms of dZ row-major [rows x TERMS*np] (hi block, then
+// lo block; zero in the padding columns) and the workgroup's column sums of the unrounded dZ for the bias gradient.
 template <int TERMS>
 __global__ __launch_bounds__(TPB) void k_dz(const int32_t* __restrict__ hdr, int layer, const float* __restrict__ G, int ldg,
                                             const float* __restrict__ Hout, int d_out, int np, int relu,
-                                            uint16_t* __restrict__ dzb, uint16_t* __restrict__ dzbt, int64_t rows_pad,
-                                            int64_t term_stride, float* __restrict__ db_partial)
+                                            uint16_t* __restrict__ dzb, float* __restrict__ db_partial)
 {
-    __shared__ uint16_t tile[TERMS][64][66];
     __shared__ float colsum[4][64];
     const int rows = hdr[HDR_N] - hdr[HDR_NODE_OFF + layer];
     const int c0 = blockIdx.x * 64;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;    // ty: 0..3
     const int nz = TERMS * np;
+    const int n = c0 + tx;
     float csum = 0.f;                    // this thread's column sum over all row tiles of this workgroup, in order
-  for (int rt = blockIdx.y; rt * 64 < rows; rt += gridDim.y) {
-    const int r0 = rt * 64;
-    __syncthreads();
-    for (int rr = ty; rr < 64; rr += 4) {
-        const int r = r0 + rr, n = c0 + tx;
-        float v = 0.f;
-        if (r < rows && n < d_out) {
-            v = G[(int64_t)r * ldg + n];
-            if (relu && !(Hout[(int64_t)r * d_out + n] > 0.f)) v = 0.f;
-        }
-        csum += v;
-        const uint16_t hi = f32_to_bf16(v);
-        tile[0][rr][tx] = hi;
-        if (r < rows) dzb[(int64_t)r * nz + n] = hi;
-        if (TERMS == 2) {
-            const uint16_t lo = f32_to_bf16(v - bf16_to_f32(hi));
-            tile[TERMS - 1][rr][tx] = lo;
-            if (r < rows) dzb[(int64_t)r * nz + np + n] = lo;
+    for (int rt = blockIdx.y; rt * 64 < rows; rt += gridDim.y) {
+        const int r0 = rt * 64;
+        for (int rr = ty; rr < 64; rr += 4) {
+            const int r = r0 + rr;
+            if (r >= rows) break;
+            float v = 0.f;
+            if (n < d_out) {
+                v = G[(int64_t)r * ldg + n];
+                if (relu && !(Hout[(int64_t)r * d_out + n] > 0.f)) v = 0.f;
+            }
+            csum += v;
+            const uint16_t hi = f32_to_bf16(v);
+            dzb[(int64_t)r * nz + n] = hi;
+            if (TERMS == 2) dzb[(int64_t)r * nz + np + n] = f32_to_bf16(v - bf16_to_f32(hi));
         }
     }
-    __syncthreads();
-    for (int t = 0; t < TERMS; ++t)
-        for (int cc = ty; cc < 64; cc += 4)
-            dzbt[t * term_stride + (int64_t)(c0 + cc) * rows_pad + r0 + tx] = tile[t][tx][cc];
-  }
     // one partial column sum per workgroup that had row tiles (the reduction reads min(gridDim.y, tiles) of them)
     if ((int)blockIdx.y * 64 < rows) {
         colsum[ty][tx] = csum;
         __syncthreads();
-        if (ty == 0 && c0 + tx < d_out)
-            db_partial[(int64_t)blockIdx.y * d_out + c0 + tx] = (colsum[0][tx] + colsum[1][tx]) + (colsum[2][tx] + colsum[3][tx]);
-    }
-}
-
-// X [rows x kp] -> X^T [kp x rows_pad], zero for rows up to the next multiple of 64; all layers in one
-// launch: a 1-D grid, layer z owns workgroups [begin[z], begin[z+1]) = column tiles x row-tile slots.
-struct TransposeGroup {
-    const uint16_t* X[DN_MAX_LAYERS]; uint16_t* XT[DN_MAX_LAYERS];
-    int kp[DN_MAX_LAYERS]; int64_t rows_pad[DN_MAX_LAYERS];
-    int begin[DN_MAX_LAYERS + 1], row_slots[DN_MAX_LAYERS];
-    int n;
-};
-__global__ __launch_bounds__(TPB) void k_transpose_x_group(const int32_t* __restrict__ hdr, TransposeGroup T)
-{
-    __shared__ uint16_t tile[64][66];
-    int z = 0;
-    while (z + 1 < T.n && (int)blockIdx.x >= T.begin[z + 1]) ++z;
-    const int local = (int)blockIdx.x - T.begin[z];
-    const int kp = T.kp[z];
-    const int c0 = (local / T.row_slots[z]) * 64;
-    const int rt0 = local % T.row_slots[z];
-    const uint16_t* __restrict__ X = T.X[z];
-    uint16_t* __restrict__ XT = T.XT[z];
-    const int64_t rows_pad = T.rows_pad[z];
-    const int rows = hdr[HDR_N] - hdr[HDR_NODE_OFF + z + 1];
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int rt = rt0; rt * 64 < rows; rt += T.row_slots[z]) {
-        const int r0 = rt * 64;
-        __syncthreads();
-        for (int rr = ty; rr < 64; rr += 4) {
-            const int r = r0 + rr;
-            tile[rr][tx] = r < rows ? X[(int64_t)r * kp + c0 + tx] : (uint16_t)0;
-        }
-        __syncthreads();
-        for (int cc = ty; cc < 64; cc += 4)
-            XT[(int64_t)(c0 + cc) * rows_pad + r0 + tx] = tile[tx][cc];
+        if (ty == 0 && n < d_out)
+            db_partial[(int64_t)blockIdx.y * d_out + n] = (colsum[0][tx] + colsum[1][tx]) + (colsum[2][tx] + colsum[3][tx]);
     }
 }
 
@@ -436,8 +389,8 @@ int dn_launch_backward(dn_model* m, dn_batch* b, const float* grad_out, float* c
     int rc = dn_launch_transpose_index(b, dh0 != nullptr, st);     // no-op when prepared for this sample
     if (rc) return rc;
     // The chain that carries the gradient down the layers comes first: dZ^i -> dX^i -> transpose of
-    // the mean -> dZ^{i-1}.  What nothing downstream waits for (X^T, the dW GEMMs, the reductions of dW
-    // and db) follows in three launches that cover all layers; every layer has its own operands.
+    // the mean -> dZ^{i-1}.  What nothing downstream waits for (the dW GEMMs, the reductions of dW and db)
+    // follows in two launches that cover all layers; every layer has its own operands.
     const float* g = grad_out;
     for (int i = k; i >= 1; --i) {
         const dn_layer_bufs& L = m->layer[i - 1];
@@ -446,12 +399,10 @@ int dn_launch_backward(dn_model* m, dn_batch* b, const float* grad_out, float* c
         { dn_prof_scope ps("dz", i, st);
         if (L.zterms == 2)
             hipLaunchKernelGGL((k_dz<2>), dim3((unsigned)(L.np / 64), row_tiles ? row_tiles : 1), dim3(TPB), 0, st, b->hdr,
-                               i, g, L.d_out, L.h, L.d_out, L.np, 1, reinterpret_cast<uint16_t*>(m->dzb),
-                               reinterpret_cast<uint16_t*>(L.dzbt), L.rows_pad, L.dzbt_term_stride, L.db_partial);
+                               i, g, L.d_out, L.h, L.d_out, L.np, 1, reinterpret_cast<uint16_t*>(L.dzb), L.db_partial);
         else
             hipLaunchKernelGGL((k_dz<1>), dim3((unsigned)(L.np / 64), row_tiles ? row_tiles : 1), dim3(TPB), 0, st, b->hdr,
-                               i, g, L.d_out, nullptr, L.d_out, L.np, 0, reinterpret_cast<uint16_t*>(m->dzb),
-                               reinterpret_cast<uint16_t*>(L.dzbt), L.rows_pad, L.dzbt_term_stride, L.db_partial);
+                               i, g, L.d_out, nullptr, L.d_out, L.np, 0, reinterpret_cast<uint16_t*>(L.dzb), L.db_partial);
         }
         DN_LAUNCH_CHECK("k_dz");
         if (i == 1 && dh0 == nullptr) break;            // nothing consumes the input gradient of layer 1
@@ -462,24 +413,5 @@ int dn_launch_backward(dn_model* m, dn_batch* b, const float* grad_out, float* c
         if (rc) return rc;
         g = gin;
     }
-    TransposeGroup T{};
-    T.n = k;
-    int blocks = 0;
-    for (int i = 1; i <= k; ++i) {
-        const dn_layer_bufs& L = m->layer[i - 1];
-        T.X[i - 1] = reinterpret_cast<const uint16_t*>(L.x);
-        T.XT[i - 1] = reinterpret_cast<uint16_t*>(L.xt);
-        T.kp[i - 1] = L.kp;
-        T.rows_pad[i - 1] = L.rows_pad;
-        int64_t row_tiles = (L.rows_cap + 63) / 64;
-        T.row_slots[i - 1] = (int)(row_tiles < 1 ? 1 : (row_tiles > 4096 ? 4096 : row_tiles));
-        T.begin[i - 1] = blocks;
-        blocks += (L.kp / 64) * T.row_slots[i - 1];
-    }
-    T.begin[k] = blocks;
-    { dn_prof_scope ps("transpose_x_all", 0, st);
-    hipLaunchKernelGGL(k_transpose_x_group, dim3((unsigned)blocks), dim3(TPB), 0, st, b->hdr, T);
-    }
-    DN_LAUNCH_CHECK("k_transpose_x_group");
     return dn_gemm_dw_all(m, b, dws, dwn, dbias, st);
 }

@@ -49,6 +49,7 @@ struct GemmArgs {
     int64_t split_stride;   // floats between consecutive split partials
     int terms;              // dW: reduction terms (hi, lo) of B; split index z = term * (gridDim.z / terms) + chunk group
     int64_t b_term_stride;  // dW: elements between B's terms
+    int a_cols, b_cols;     // dW: allocated columns of A, of one term of B (loads beyond them read zero)
     // ReLU sign fix-up (EPI_BIAS_ACT with relu)
     const float* rownorm; const float* colnorm; float gamma;
     int* fix_count;         // [0] number of exact recomputations, [1] sticky overflow flag
@@ -91,7 +92,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const int bx, const
     const int wm = wave >> 1, wn = wave & 1;
 
     f32x16 acc[MI][NJ];
-    mainloop<BM_, BN_, false>(a.A + (int64_t)row0 * a.lda, a.lda, Bbase + (int64_t)col0 * a.ldb, a.ldb, kc_begin, kc_end, 0, acc);
+    if constexpr (EPI == EPI_SPLIT)     // weight gradient: both operands have the reduction index (the node) as their row index
+        mainloop_tn<BM_, BN_>(a.A, a.lda, a.a_cols, Bbase, a.ldb, a.b_cols, row0, col0, kc_begin, kc_end, rows_layer, acc);
+    else
+        mainloop<BM_, BN_, false>(a.A + (int64_t)row0 * a.lda, a.lda, Bbase + (int64_t)col0 * a.ldb, a.ldb, kc_begin, kc_end, 0, acc);
 
     // epilogue: lane holds column (lane & 31); register e holds row 8*(e/4) + 4*(lane/32) + e%4
     float* C = a.C;
@@ -391,7 +395,7 @@ int dn_gemm_dx(const dn_model* m, const dn_batch* b, int i, hipStream_t st)
 {
     const dn_layer_bufs& L = m->layer[i - 1];
     GemmArgs a{};
-    a.A = reinterpret_cast<const uint16_t*>(m->dzb); a.lda = L.nz;
+    a.A = reinterpret_cast<const uint16_t*>(L.dzb); a.lda = L.nz;
     a.B = reinterpret_cast<const uint16_t*>(L.w); a.ldb = L.nz;
     a.C = m->dx; a.ldc = 2 * L.d_in;
     a.hdr = b->hdr; a.layer = i; a.m_const = -1; a.ncols = 2 * L.d_in; a.red_const = L.nz;
@@ -420,12 +424,12 @@ int dn_gemm_dw_all(const dn_model* m, const dn_batch* b, float* const* dws, floa
         if (splits > chunks_cap) splits = (int)(chunks_cap > 0 ? chunks_cap : 1);
         if (splits < 1) splits = 1;
         GemmArgs& a = G.g[i - 1];
-        a.A = reinterpret_cast<const uint16_t*>(L.xt); a.lda = L.rows_pad;
-        a.B = reinterpret_cast<const uint16_t*>(L.dzbt); a.ldb = L.rows_pad;
+        a.A = reinterpret_cast<const uint16_t*>(L.x); a.lda = L.kp; a.a_cols = L.kp;
+        a.B = reinterpret_cast<const uint16_t*>(L.dzb); a.ldb = L.nz; a.b_cols = L.np;
         a.C = L.partial; a.ldc = L.d_out;
         a.hdr = b->hdr; a.layer = i; a.m_const = L.kx; a.ncols = L.d_out; a.red_const = -1;
         a.bias = nullptr; a.relu = 0; a.split_stride = (int64_t)L.kx * L.d_out;
-        a.terms = L.zterms; a.b_term_stride = L.dzbt_term_stride;
+        a.terms = L.zterms; a.b_term_stride = L.np;
         const int zsplits = splits * L.zterms;
         if ((int64_t)zsplits * a.split_stride > L.partial_floats) return dn_fail(DN_ECAPACITY, "dW partial buffer too small");
         const int y = i - 1;

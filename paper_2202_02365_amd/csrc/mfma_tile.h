@@ -122,4 +122,114 @@ __device__ __forceinline__ void mainloop(const uint16_t* __restrict__ A_tile, co
 #undef DN_GEMM_STEP
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// The same contraction for operands stored the other way round: the reduction index is the ROW index of both,
+//   acc += A[k][m0 .. m0 + BM_) ^T * B[k][n0 .. n0 + BN_)      A: [K x lda], B: [K x ldb] row-major bf16,
+// which is what a weight gradient is (dW = X^T dZ: both X and dZ have one row per node).  Tiles of 64 reduction
+// rows are copied to LDS as they are; the fragment v_mfma_f32_32x32x16_bf16 wants (8 values along the reduction
+// index per lane) comes out of LDS through ds_read_b64_tr_b16, the LDS transpose read of this architecture: in
+// every group of 16 lanes, lane r passes the address of 4 consecutive 16-bit values (row r of a 16 x 4 block) and
+// lane l receives column l % 4 of rows l / 4, l / 4 + 4, l / 4 + 8, l / 4 + 12 (layout established by a probe that
+// reads a known pattern).  With lane r = 4 e + q pointing at [reduction row k_e][4 q-th .. of 16 consecutive
+// columns], lane l of the group gets column l of those 16 at the reduction rows k_0 .. k_3: two such reads give a
+// lane its 8 reduction values.  LDS rows are padded by 32 bytes so that the 4 reduction rows a group touches fall
+// into disjoint banks.  Rows >= k_rows and columns >= a_cols / b_cols are read as zero (no padding assumed).
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+template <int BM_, int BN_>
+__device__ __forceinline__ void mainloop_tn(const uint16_t* __restrict__ A, const int64_t lda, const int a_cols,
+                                            const uint16_t* __restrict__ B, const int64_t ldb, const int b_cols,
+                                            const int m0, const int n0, const int kc_begin, const int kc_end,
+                                            const int k_rows, f32x16 (&acc)[BM_ / 64][BN_ / 64])
+{
+    constexpr int MI = BM_ / 64, NJ = BN_ / 64;
+    constexpr int CA = BM_ / 8, CB = BN_ / 8;            // 16-byte chunks per reduction row
+    constexpr int LA = BK * CA / TPB, LB = BK * CB / TPB;
+    constexpr int RSA = BM_ + 16, RSB = BN_ + 16;        // LDS row stride in elements (32 bytes of padding)
+    __shared__ __attribute__((aligned(16))) uint16_t As[2][BK * RSA];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BK * RSB];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    auto load_tiles = [&](TileRegs<LA, LB>& r, int kc) {
+        const int k0 = kc * BK;
+#pragma unroll
+        for (int i = 0; i < LA; ++i) {
+            const int id = t + TPB * i, kr = id / CA, c = id % CA;
+            const bool ok = k0 + kr < k_rows && m0 + c * 8 < a_cols;
+            r.a[i] = ok ? *reinterpret_cast<const u32x4*>(A + (int64_t)(k0 + kr) * lda + m0 + c * 8) : u32x4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int i = 0; i < LB; ++i) {
+            const int id = t + TPB * i, kr = id / CB, c = id % CB;
+            const bool ok = k0 + kr < k_rows && n0 + c * 8 < b_cols;
+            r.b[i] = ok ? *reinterpret_cast<const u32x4*>(B + (int64_t)(k0 + kr) * ldb + n0 + c * 8) : u32x4{0u, 0u, 0u, 0u};
+        }
+    };
+    auto store_tiles = [&](const TileRegs<LA, LB>& r, int buf) {
+#pragma unroll
+        for (int i = 0; i < LA; ++i) {
+            const int id = t + TPB * i, kr = id / CA, c = id % CA;
+            *reinterpret_cast<u32x4*>(&As[buf][kr * RSA + c * 8]) = r.a[i];
+        }
+#pragma unroll
+        for (int i = 0; i < LB; ++i) {
+            const int id = t + TPB * i, kr = id / CB, c = id % CB;
+            *reinterpret_cast<u32x4*>(&Bs[buf][kr * RSB + c * 8]) = r.b[i];
+        }
+    };
+    // this lane's part of the address pattern: reduction row offset and column offset inside a 32-column fragment
+    const int g = lane >> 4, r16 = lane & 15;
+    const int frag_k = 8 * (g >> 1) + (r16 >> 2);        // + 4 for the second read
+    const int frag_c = 16 * (g & 1) + 4 * (r16 & 3);
+    auto read_frag = [&](const uint16_t* tile, int rs, int kb, int col0) -> bf16x8 {
+        typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+        const uint16_t* p0 = tile + (kb + frag_k) * rs + col0 + frag_c;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)p0);
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p0 + 4 * rs));
+        const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        return __builtin_bit_cast(bf16x8, v);
+    };
+    auto multiply = [&](int buf) {
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8 fa[MI], fb[NJ];
+#pragma unroll
+            for (int i = 0; i < MI; ++i) fa[i] = read_frag(As[buf], RSA, ks * 16, wm * (BM_ / 2) + i * 32);
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) fb[j] = read_frag(Bs[buf], RSB, ks * 16, wn * (BN_ / 2) + j * 32);
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+    };
+
+    TileRegs<LA, LB> r0, r1;
+    if (kc_begin + 0 < kc_end) load_tiles(r0, kc_begin + 0);
+    if (kc_begin + 1 < kc_end) load_tiles(r1, kc_begin + 1);
+    int kc = kc_begin, buf = 0;
+#define DN_GEMM_STEP(R)                                       \
+    if (kc >= kc_end) break;                                  \
+    store_tiles(R, buf);                                      \
+    __syncthreads();                                          \
+    if (kc + 2 < kc_end) load_tiles(R, kc + 2);               \
+    multiply(buf);                                            \
+    buf ^= 1;                                                 \
+    ++kc;
+    for (;;) {
+        DN_GEMM_STEP(r0)
+        DN_GEMM_STEP(r1)
+    }
+#undef DN_GEMM_STEP
+}
+
 }  // namespace dn_mma
