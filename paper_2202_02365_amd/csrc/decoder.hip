@@ -12,8 +12,11 @@
 // on bf16 MFMA (reduction length padded to a multiple of 64), batched over sides and chunks in one
 // launch.  Backward has two more contractions per (side, chunk): dQ = P * E and dE = P^T * Q with
 // P = softmax probabilities of the negatives.  P is computed on the device (its last bits differ from
-// any other implementation's), so it enters as two bf16 terms hi + lo laid side by side along the
-// reduction index with the other operand repeated (wrap-around loads).  Row-wise sums that collect
+// any other implementation's), so it enters as two bf16 terms hi + lo, two column blocks of one row-major
+// matrix.  dQ contracts over the negatives (P's columns): the terms lie side by side along the reduction
+// index and E^T's tile loads wrap round.  dE contracts over the chunk's edges (the rows of P and of Q): both
+// are read as they lie in memory through the LDS transpose read, and the two terms come out as two row
+// blocks of the result.  Row-wise sums that collect
 // the per-edge / per-negative gradients into dH and dR run over an index sorted by node (relation)
 // in a fixed order: no floating-point atomics, bit-identical from run to run.
 //
@@ -40,7 +43,7 @@ struct dn_decoder {
     int64_t max_entries;              // 2 * max_edges + max_chunks * num_neg index entries
     // workspace
     int32_t* hdr;
-    dn_bf16 *Q, *Qt, *En, *Ent, *P, *Pt;
+    dn_bf16 *Q, *En, *Ent, *P;
     float *S, *lse, *dpos, *dQ, *dEn, *rows, *long_partial, *pmax, *psum;
     int32_t *nkey[2], *nval[2], *nptr, *nhist;
     int32_t *rkey[2], *rval[2], *rptr, *rhist;
@@ -275,19 +278,16 @@ __global__ __launch_bounds__(TPB_) void k_dm_lse(const float* __restrict__ pmax,
     dpos[e] = (expf(p - l[0]) - 1.f) + (expf(p - l[1]) - 1.f);
 }
 
-// P = exp(S - lse) for valid (edge, negative) pairs, 0 elsewhere, as two bf16 terms; row-major
-// P[z][i][term*npad + n] and transposed Pt[z][n][term*cpad + i]  (z = side*C + q), 64 x 64 tiles.
+// P = exp(S - lse) for valid (edge, negative) pairs, 0 elsewhere, as two bf16 terms, row-major:
+// P[z][i][term*npad + n]  (z = side*C + q).  One thread per element, 64 x 64 tiles.
 __global__ __launch_bounds__(TPB_) void k_dm_probs(const float* __restrict__ S, const float* __restrict__ lse, int B, int C,
-                                                   int chunk, int Nn, int cpad, int npad, uint16_t* __restrict__ P,
-                                                   uint16_t* __restrict__ Pt)
+                                                   int chunk, int Nn, int cpad, int npad, uint16_t* __restrict__ P)
 {
-    __shared__ uint16_t th[64][66], tl[64][66];
     const int z = blockIdx.z, side = z / C, q = z % C;
     const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     const float* Sz = S + (int64_t)z * cpad * npad;
     uint16_t* Pz = P + (int64_t)z * cpad * 2 * npad;
-    uint16_t* Ptz = Pt + (int64_t)z * npad * 2 * cpad;
     for (int rr = ty; rr < 64; rr += 4) {
         const int i = r0 + rr, n = c0 + tx;
         const int64_t e = (int64_t)q * chunk + i;
@@ -297,15 +297,41 @@ __global__ __launch_bounds__(TPB_) void k_dm_probs(const float* __restrict__ S, 
         const uint16_t lo = to_bf16(p - from_bf16(hi));
         Pz[(int64_t)i * 2 * npad + n] = hi;
         Pz[(int64_t)i * 2 * npad + npad + n] = lo;
-        th[rr][tx] = hi;
-        tl[rr][tx] = lo;
     }
-    __syncthreads();
-    for (int cc = ty; cc < 64; cc += 4) {
-        const int n = c0 + cc, i = r0 + tx;
-        Ptz[(int64_t)n * 2 * cpad + i] = th[tx][cc];
-        Ptz[(int64_t)n * 2 * cpad + cpad + i] = tl[tx][cc];
-    }
+}
+
+// dE[z] = P[z]^T * Q[z]: the contraction runs over the chunk's edges, the row index of both P and Q, so both are
+// read as they lie in memory through the LDS transpose read (mainloop_tn).  The two terms of P are two column
+// blocks of it, i.e. two row blocks of the result: C[z] is [2*npad x np], rows [0, npad) from the hi term and
+// [npad, 2*npad) from the lo term; whoever consumes dE adds the two.
+struct DmGemmTn {
+    const uint16_t* A; int64_t lda, stride_a; int a_cols;
+    const uint16_t* B; int64_t ldb, stride_b; int b_cols;
+    int k_rows;
+    float* C; int64_t ldc, stride_c; int ncols;
+};
+__global__ __launch_bounds__(TPB, 2) void k_dm_gemm_tn(DmGemmTn g)
+{
+    const int z = blockIdx.z;
+    const int row0 = blockIdx.y * BM, col0 = blockIdx.x * BN;
+    f32x16 acc[2][2];
+    mainloop_tn<BM, BN>(g.A + (int64_t)z * g.stride_a, g.lda, g.a_cols, g.B + (int64_t)z * g.stride_b, g.ldb, g.b_cols, row0, col0,
+                        0, (g.k_rows + BK - 1) / BK, g.k_rows, acc);
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    float* C = g.C + (int64_t)z * g.stride_c;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int n = col0 + wn * 64 + j * 32 + (lane & 31);
+            if (n >= g.ncols) continue;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int m = row0 + wm * 64 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                C[(int64_t)m * g.ldc + n] = acc[i][j][e];
+            }
+        }
 }
 
 // One atomic per distinct digit among a wave's active lanes (all of a wave's elements lie in one tile):
@@ -376,7 +402,7 @@ __device__ __forceinline__ bool dm_edge_ok(const DmGrad& g, int e, int& s, int& 
 // rows[i][:] = gradient row of the i-th entry of the node index (sorted order), 32 lanes per entry:
 //   edge e as a source:       dpos[e] * (r * h_dst) + dQ[0][e] * r
 //   edge e as a destination:  dpos[e] * (r * h_src) + dQ[1][e] * r
-//   negative slot (q, n):     dE[0][q][n] + dE[1][q][n]
+//   negative slot (q, n):     dE[0][q][n] + dE[1][q][n]   (each the sum of its hi-term and lo-term rows)
 __global__ __launch_bounds__(TPB_) void k_dm_node_rows(DmGrad g, const int32_t* __restrict__ val, int total,
                                                        float* __restrict__ rows)
 {
@@ -398,9 +424,11 @@ __global__ __launch_bounds__(TPB_) void k_dm_node_rows(DmGrad g, const int32_t* 
     } else {
         const int m = v - 2 * g.B;
         const int q = m / g.Nn, n = m % g.Nn;
-        const float* e0 = g.dEn + ((int64_t)q * g.npad + n) * g.np;
-        const float* e1 = g.dEn + (((int64_t)g.C + q) * g.npad + n) * g.np;
-        for (int j = sl; j < g.d; j += 32) out[j] = e0[j] + e1[j];
+        // per side z: rows [0, npad) hold the hi-term part, rows [npad, 2 npad) the lo-term part
+        const float* e0 = g.dEn + ((int64_t)q * 2 * g.npad + n) * g.np;
+        const float* e1 = g.dEn + (((int64_t)g.C + q) * 2 * g.npad + n) * g.np;
+        const int64_t lo = (int64_t)g.npad * g.np;
+        for (int j = sl; j < g.d; j += 32) out[j] = (e0[j] + e0[lo + j]) + (e1[j] + e1[lo + j]);
     }
 }
 
@@ -552,7 +580,6 @@ void carve_decoder(dn_decoder* d, dn_carver& c)
     d->rhist = c.take<int32_t>(dn_sort_hist_words(d->rplan));
     d->long_seg = c.take<int32_t>(d->max_entries / LONG_SEG + 2);
     d->Q = c.take<dn_bf16>(2 * C * d->cpad * d->kp);
-    d->Qt = c.take<dn_bf16>(2 * C * (int64_t)d->np * d->cpad);
     d->En = c.take<dn_bf16>(C * d->npad * d->kp);
     d->Ent = c.take<dn_bf16>(C * (int64_t)d->np * d->npad);
     d->S = c.take<float>(2 * C * (int64_t)d->cpad * d->npad);
@@ -561,9 +588,8 @@ void carve_decoder(dn_decoder* d, dn_carver& c)
     d->lse = c.take<float>(2 * d->max_edges);
     d->dpos = c.take<float>(d->max_edges);
     d->P = c.take<dn_bf16>(2 * C * (int64_t)d->cpad * 2 * d->npad);
-    d->Pt = c.take<dn_bf16>(2 * C * (int64_t)d->npad * 2 * d->cpad);
     d->dQ = c.take<float>(2 * C * (int64_t)d->cpad * d->np);
-    d->dEn = c.take<float>(2 * C * (int64_t)d->npad * d->np);
+    d->dEn = c.take<float>(2 * C * (int64_t)2 * d->npad * d->np);
     d->rows = c.take<float>(d->max_entries * d->dim);
     d->long_partial = c.take<float>((d->max_entries / LONG_SEG + 2) * LONG_PARTS * d->dim);
     for (int i = 0; i < 2; ++i) {
@@ -687,14 +713,11 @@ int distmult_backward(dn_decoder* d, float* d_dH, int64_t ld_dh, float* d_dR, in
         {
             dn_prof_scope ps("dm_probs", 0, st);
             hipLaunchKernelGGL(k_dm_probs, dim3(d->npad / 64, d->cpad / 64, 2 * C), dim3(TPB_), 0, st, d->S, d->lse, B, C,
-                               d->chunk, d->num_neg, d->cpad, d->npad, d->P, d->Pt);
+                               d->chunk, d->num_neg, d->cpad, d->npad, d->P);
             DN_LAUNCH_CHECK("k_dm_probs");
         }
         {
             dn_prof_scope ps("dm_transpose", 0, st);
-            hipLaunchKernelGGL(k_dm_transpose, dim3(d->kp / 64, d->cpad / 64, 2 * C), dim3(TPB_), 0, st, d->Q, d->cpad, d->kp,
-                               d->Qt, (int64_t)d->np * d->cpad);
-            DN_LAUNCH_CHECK("k_dm_transpose(Q)");
             hipLaunchKernelGGL(k_dm_transpose, dim3(d->kp / 64, d->npad / 64, C), dim3(TPB_), 0, st, d->En, d->npad, d->kp,
                                d->Ent, (int64_t)d->np * d->npad);
             DN_LAUNCH_CHECK("k_dm_transpose(E)");
@@ -708,13 +731,17 @@ int distmult_backward(dn_decoder* d, float* d_dH, int64_t ld_dh, float* d_dR, in
         g.C = d->dQ; g.ldc = d->np; g.stride_c = (int64_t)d->cpad * d->np; g.ncols = d->dim;
         int rc = launch_gemm(g, true, d->cpad / BM, d->np / BN, 2 * C, st, "dm_gemm_dq");
         if (rc) return rc;
-        // dE[z] = P[z]^T * Q[z] : B operand = Q^T [np x cpad], repeated per term
-        g.A = d->Pt; g.lda = 2 * d->cpad; g.stride_a = (int64_t)d->npad * 2 * d->cpad;
-        g.B = d->Qt; g.ldb = d->cpad; g.stride_b = (int64_t)d->np * d->cpad; g.b_mod = 2 * C;
-        g.kchunks = 2 * d->cpad / BK; g.b_wrap_chunks = d->cpad / BK;
-        g.C = d->dEn; g.ldc = d->np; g.stride_c = (int64_t)d->npad * d->np; g.ncols = d->dim;
-        rc = launch_gemm(g, true, d->npad / BM, d->np / BN, 2 * C, st, "dm_gemm_de");
-        if (rc) return rc;
+        // dE[z] = P[z]^T * Q[z], both operands read with the edge index as the reduction index
+        {
+            DmGemmTn t;
+            t.A = d->P; t.lda = 2 * d->npad; t.stride_a = (int64_t)d->cpad * 2 * d->npad; t.a_cols = 2 * d->npad;
+            t.B = d->Q; t.ldb = d->kp; t.stride_b = (int64_t)d->cpad * d->kp; t.b_cols = d->kp;
+            t.k_rows = d->cpad;
+            t.C = d->dEn; t.ldc = d->np; t.stride_c = (int64_t)2 * d->npad * d->np; t.ncols = d->dim;
+            dn_prof_scope ps("dm_gemm_de", 0, st);
+            hipLaunchKernelGGL(k_dm_gemm_tn, dim3(d->np / BN, 2 * d->npad / BM, 2 * C), dim3(TPB), 0, st, t);
+            DN_LAUNCH_CHECK("k_dm_gemm_tn");
+        }
     }
     DmGrad a;
     a.H = d->H; a.R = d->R; a.ldh = d->ldh; a.ldr = d->ldr; a.n_rows = n_rows; a.num_rel = (int)d->num_rel;
