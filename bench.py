@@ -38,7 +38,8 @@ def algorithmic_work(tag, sizes, cfg, dims):
     out = {}
     if tag == "gather":
         return "hbm", float(np.mean(2 * N * dims[0] * elt0))
-    if tag.startswith("aggregate_L"):
+    if tag.startswith("aggregate_L") or tag.startswith("aggregate_table_L"):
+        # aggregate_table_L1 reads the same rows from the feature table itself (plus 4 B of node id per row read)
         i = int(tag.split("_L")[1])
         rows = N - off[:, i]
         # slots owned by Delta_i..Delta_k: unknown per layer on the host without the arrays; bounded by E, exact for layer 1
@@ -46,7 +47,8 @@ def algorithmic_work(tag, sizes, cfg, dims):
         elt = elt0 if i == 1 else 4
         d = dims[i - 1]
         terms = 1 if i == 1 else 2
-        return "hbm", float(np.mean((slots + rows) * d * elt + slots * 4 + rows * 2 * d * terms * 2))
+        ids = 4 * rows if "table" in tag else 0
+        return "hbm", float(np.mean((slots + rows) * d * elt + slots * 4 + ids + rows * 2 * d * terms * 2))
     if tag.startswith("gemm_fwd_L"):
         i = int(tag.split("_L")[1])
         rows = N - off[:, i]
@@ -323,6 +325,9 @@ def main():
     ap.add_argument("--separate-gather", action="store_true",
                     help="dense_gather into an H^0 buffer, then sage_forward (default: sage_forward_table, whose layer-1 "
                          "aggregation reads the table's rows itself)")
+    ap.add_argument("--also-two-step", type=int, default=0,
+                    help="run that many untimed steps in the two-step form (dense_gather + sage_forward) first, so that a "
+                         "profiler sees those kernels too")
     ap.add_argument("--no-graphs", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
     ap.add_argument("--replicas", type=int, default=4,
                     help="data-parallel replicas on one GPU: that many mini-batches run the whole path concurrently, "
@@ -533,6 +538,8 @@ def main():
         return spent
 
     edges = sum(sizes[s % N_BATCHES][k + 2] for s in range(args.steps))
+    for s in range(args.also_two_step):
+        step(s % N_BATCHES, separate=True)
     timed(args.warmup)
     serial_s = timed(args.steps)
     serial_fwd_s = timed(args.steps, backward=False)
@@ -590,15 +597,29 @@ def main():
         for s in range(args.steps):
             dn.profile_calibration_copy(delay_dst, delay_src)
             dn.profile_empty_bracket()
-            step(s % N_BATCHES, separate=True)        # gather as a kernel of its own, so that every step of the path is timed
+            step(s % N_BATCHES)
         prof = dn.profile_collect()
         dn.profile_enable(False)
+        prof_two_step = {}
+        if fused:
+            # the two-step form too, so that dense_gather and the aggregation over H^0 have their own figures
+            dn.profile_enable(True)
+            for s in range(min(args.steps, 32)):
+                dn.profile_calibration_copy(delay_dst, delay_src)
+                step(s % N_BATCHES, separate=True)
+            prof_two_step = dn.profile_collect()
+            dn.profile_enable(False)
         del delay_src, delay_dst
         # an event pair around nothing already reads a few microseconds: subtract that from every bracket
         empty_ms, empty_n = prof.pop("empty_bracket", (0.0, 1))
         bracket_us = 1e3 * empty_ms / max(empty_n, 1)
         kernels = {tag: {"avg_us": max(1e3 * ms / n - bracket_us, 0.0), "launches_per_step": n / args.steps}
                    for tag, (ms, n) in prof.items()}
+        for tag in ("gather", "aggregate_L1"):
+            if tag in prof_two_step:
+                ms, n = prof_two_step[tag]
+                kernels[tag] = {"avg_us": max(1e3 * ms / n - bracket_us, 0.0), "launches_per_step": 0.0,
+                                "note": "two-step form (dense_gather + sage_forward) only"}
         step_sum_us = sum(v["avg_us"] * v["launches_per_step"] for v in kernels.values())
         used = [sizes[s % N_BATCHES] for s in range(args.steps)]
         best = None

@@ -285,7 +285,7 @@ int launch_aggregate_t(const dn_model* m, const dn_batch* b, int i, const TIN* H
     int64_t grid = (L.rows_cap + groups - 1) / groups;
     if (grid > 8192) grid = 8192;
     if (grid < 1) grid = 1;
-    dn_prof_scope ps("aggregate", i, st);
+    dn_prof_scope ps(TABLE ? "aggregate_table" : "aggregate", i, st);
 #define DN_AGG(VV, LL)                                                                                                 \
     hipLaunchKernelGGL((k_aggregate<TIN, VV, LL, TERMS, TABLE>), dim3((int)grid), dim3(TPB), 0, st, b->hdr, i,         \
                        b->nbr_offsets, b->repr_map, H, ldh, b->node_ids, b->nbrs, m->mean_agg, d, X, L.kp, L.rownorm, \
