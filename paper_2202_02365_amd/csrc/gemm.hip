@@ -1,24 +1,22 @@
-// bf16 MFMA GEMM for the GraphSage linear layers (the one dense contraction of the path).
+// bf16 MFMA GEMMs of the GraphSage linear layers (the one dense contraction of the path).
 //
-// One kernel form serves forward, dX and dW:   C[M x Nc] = A[M x R] * B[Nc x R]^T
-// with A and B row-major bf16 and the reduction index R contiguous in both, which is the layout
-// v_mfma_f32_32x32x16_bf16 wants (each lane supplies 8 consecutive reduction elements of one row).
-//   forward : A = X^i  = [bf16(H_self) | bf16(mean)]   B = Wcat^T        epilogue + bias, ReLU
-//   dX      : A = bf16(dZ)                              B = Wcat          plain store
-//   dW      : A = X^T (reduction over batch rows)       B = bf16(dZ)^T    split over the reduction,
-//             partial tiles reduced afterwards in a fixed order (deterministic).
-// Tile: 128 x 128 x 64 per workgroup of 4 waves (2 x 2), each wave 64 x 64 = 2 x 2 MFMA tiles of
-// 32 x 32.  Operand tiles go global -> registers -> LDS (16-byte slots, XOR-swizzled by row so the
-// fragment reads of 32 consecutive rows spread over all banks); the next tile's global loads
-// are in flight while the current one is multiplied.  M and the dW reduction length live in
-// device memory (they depend on the sample); the grid is sized by capacity and surplus
-// workgroups leave at once.
+//   forward : C = A * B^T   A = X^i = [bf16(H_self) | bf16(mean)]   B = Wcat^T     epilogue + bias, ReLU
+//   dX      : C = A * B^T   A = bf16 terms of dZ                     B = Wcat       plain store
+//     both operands row-major with the reduction index contiguous (mainloop of mfma_tile.h), 64 x 64 tiles:
+//     a layer has few output rows per mini-batch and a short reduction, so many small workgroups, several per
+//     compute unit, hide the memory latency of the few k-steps better than 128 x 128 tiles do;
+//   dW      : C = A^T * B   A = X^i, B = bf16 terms of dZ: the reduction runs over the nodes, the ROW index of both
+//     operands as they lie in memory, which mainloop_tn reads in place through the LDS transpose read; 128 x 128
+//     tiles, split over the reduction, partial tiles reduced afterwards in a fixed order (deterministic).
+// Four waves (2 x 2) per workgroup, v_mfma_f32_32x32x16_bf16, two register stages of global prefetch and two LDS
+// buffers.  M and the dW reduction length live in device memory (they depend on the sample); grids are sized by
+// capacity and surplus workgroups leave at once.
 //
 // Operand terms: an operand the device computed through an MFMA accumulation is carried as two
 // bf16 terms (hi + lo), laid side by side along the reduction index, with the other operand
 // repeated; an operand that derives from the caller's inputs is one term.
 //
-// ReLU sign: where |Z| is below a bound on the fp32 accumulation error (2 K 2^-24 |x| |w|), the
+// ReLU sign: where |Z| is below a probabilistic bound on the fp32 accumulation error (8 sqrt(K) 2^-24 |x| |w|), the
 // epilogue queues the element in LDS and the workgroup then recomputes that dot product in fp64,
 // so that the stored activation and the mask [Z > 0] used by the backward pass are those of the
 // exact sum.

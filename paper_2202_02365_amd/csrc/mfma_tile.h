@@ -1,12 +1,14 @@
-// 128 x 128 x 64 (or 64 x 64 x 64) bf16 MFMA tile shared by the GEMM kernels of this library (gfx950).
+// bf16 MFMA tile main loops shared by the GEMM kernels of this library (gfx950): T x T x 64 per k-step, T = 64 or 128.
 //
-//   acc += A_tile[128 x R] * B_tile[128 x R]^T     both row-major bf16, reduction index contiguous,
+//   mainloop     acc += A_tile[T x R] * B_tile[T x R]^T     both row-major bf16, reduction index contiguous,
 // which is the layout v_mfma_f32_32x32x16_bf16 wants (each lane supplies 8 consecutive reduction
-// elements of one row).  One workgroup of 4 waves (2 x 2), each wave 64 x 64 = 2 x 2 MFMA tiles of
+// elements of one row).  One workgroup of 4 waves (2 x 2), each wave (T/2) x (T/2) in MFMA tiles of
 // 32 x 32.  Operand tiles go global -> registers -> LDS (16-byte slots, XOR-swizzled by row so the
 // fragment reads of 32 consecutive rows spread over all banks); two register stages keep the next two
 // tiles' global loads in flight while the current one is multiplied, two LDS buffers allow a single
 // barrier per k-step.  Tile loads carry no bounds check: operands are padded to whole tiles.
+//
+//   mainloop_tn  the same contraction for operands whose ROW index is the reduction index (see there).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
