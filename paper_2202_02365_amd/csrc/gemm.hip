@@ -201,10 +201,15 @@ __global__ __launch_bounds__(TPB, (BM_ == 64 && BN_ == 64) ? 4 : 2) void k_gemm_
 {
     int gi = 0;
     while (gi + 1 < G.n && (int)blockIdx.x >= G.begin[gi + 1]) ++gi;
-    // (placing the tiles of one reduction split on one XCD, so that its L2 serves their shared operand rows, was
-    // measured slower: 34 vs 27 us)
+    // The column tiles of one (row tile, split) read the same rows of X: launch order is re-read as chunks of
+    // 8 x (column tiles) in which the workgroups j, j + 8, ... (same XCD, shared L2) are those column tiles.
+    // (Placing ALL tiles of a split on one XCD was measured slower: 34 vs 27 us.)
     const int local = (int)blockIdx.x - G.begin[gi];
-    const int bx = local % G.gx[gi], by = (local / G.gx[gi]) % G.gy[gi], bz = local / (G.gx[gi] * G.gy[gi]);
+    const int nx = G.gx[gi];
+    const int chunk = local / (8 * nx), j = local - chunk * 8 * nx;
+    const int bx = j >> 3, r = chunk * 8 + (j & 7);          // r = bz * gy + by
+    const int by = r % G.gy[gi], bz = r / G.gy[gi];
+    if (bz >= G.gz[gi]) return;
     gemm_tile<EPI_SPLIT, BM_, BN_>(G.g[gi], bx, by, bz, G.gz[gi]);
 }
 
@@ -435,7 +440,7 @@ int dn_gemm_dw_all(const dn_model* m, const dn_batch* b, float* const* dws, floa
         G.gy[y] = (L.kx + T - 1) / T;
         G.gz[y] = zsplits;
         G.begin[y] = blocks;
-        blocks += G.gx[y] * G.gy[y] * G.gz[y];
+        blocks += G.gx[y] * (int)dn_round_up((int64_t)G.gy[y] * G.gz[y], 8);     // a multiple of 8: every layer starts on XCD 0
         R.partial[y] = L.partial; R.split_stride[y] = a.split_stride; R.groups[y] = splits; R.zterms[y] = L.zterms;
         R.xterms[y] = L.xterms;
         R.d_in[y] = L.d_in; R.d_out[y] = L.d_out; R.layer[y] = i;
