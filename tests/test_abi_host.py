@@ -73,3 +73,42 @@ def test_no_cpu_fallback_exists():
     import paper_2202_02365_amd.binding as b
     src = open(b.__file__).read() + open(os.path.join(os.path.dirname(b.__file__), "__init__.py")).read()
     assert "oracle" not in src
+
+
+def _dec_ws(lib, max_edges, chunk, num_neg, dim, max_rows, num_rel):
+    n = ctypes.c_size_t()
+    rc = lib.dn_decoder_workspace_size(max_edges, chunk, num_neg, dim, max_rows, num_rel, ctypes.byref(n))
+    return rc, n.value
+
+
+def test_decoder_workspace_size_and_bad_arguments(lib):
+    rc, small = _dec_ws(lib, 1000, 100, 50, 32, 5000, 7)
+    assert rc == 0 and small > 0 and small % 256 == 0
+    # the link-prediction workload's shape: dominated by scores (fp32) and probabilities (two bf16 terms) per pair
+    rc, full = _dec_ws(lib, 50_000, 1000, 1000, 100, 150_000, 1000)
+    pairs_padded = 2 * 50 * 1024 * 1024
+    assert rc == 0 and 8 * pairs_padded < full < 16 * pairs_padded
+    for bad in [(0, 100, 50, 32, 5000, 7), (1000, 0, 50, 32, 5000, 7), (1000, 100, 0, 32, 5000, 7),
+                (1000, 100, 50, 0, 5000, 7), (1000, 100, 50, 2000, 5000, 7), (1000, 100, 50, 32, 0, 7),
+                (1000, 100, 50, 32, 5000, 0), (1 << 25, 100, 50, 32, 5000, 7)]:
+        assert _dec_ws(lib, *bad)[0] == -1, bad
+    assert lib.dn_decoder_workspace_size(1000, 100, 50, 32, 5000, 7, None) == -1
+    h = ctypes.c_void_p()
+    assert lib.dn_decoder_create(ctypes.byref(h), 1000, 100, 50, 32, 5000, 7, None, 0, None) == -1      # no workspace
+    assert lib.dn_decoder_create(ctypes.byref(h), 1000, 100, 50, 32, 5000, 7, ctypes.c_void_p(8), 1 << 30, None) == -1  # misaligned
+
+
+def test_new_entry_points_reject_null_and_bad_arguments(lib):
+    assert lib.distmult_forward(None, None, 0, 0, None, 0, None, None, None, 0, None, None, None, None) == -1
+    assert lib.distmult_backward(None, None, 0, None, 0, None) == -1
+    assert lib.dn_decoder_scores(None, 0, None, None, None) == -1
+    assert lib.dn_decoder_status(None, None, None) == -1
+    assert lib.sage_forward_table(None, None, None, 0, None, None) == -1
+    assert lib.dn_model_set_aggregation(None, 0) == -1
+    assert lib.dn_embedding_adagrad(None, None, None, 4, 4, None, 0.1, 1e-8, None) == -1
+    # the loss head validates sizes before it touches the device
+    assert lib.dn_softmax_xent(None, 4, None, 3, 4, 1.0, None, None, 4, None) == -1          # null with n > 0
+    assert lib.dn_softmax_xent(None, 4, None, -1, 4, 1.0, None, None, 4, None) == -1
+    assert lib.dn_softmax_xent(None, 4, None, 0, 0, 1.0, None, None, 4, None) == -1          # no classes
+    assert lib.dn_softmax_xent(None, 2, None, 0, 4, 1.0, None, None, 4, None) == -1          # row stride below width
+    assert lib.dn_softmax_xent(None, 4, None, 0, 4, 1.0, None, None, 4, None) == 0           # empty batch: nothing to do
