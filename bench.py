@@ -135,9 +135,9 @@ def cpu_baseline(cfg, inputs, sizes, budget_s=20.0):
 
 
 def run_link_prediction(args, cfg):
-    """Link-prediction step: dense_sample_edges -> sage_forward_table (or dense_gather + sage_forward) ->
-    distmult_forward -> distmult_backward -> sage_backward (with dL/dH^0) -> dn_embedding_sgd, one batch of positive
-    edges per step."""
+    """Link-prediction step: dense_sample_edges -> sage_forward_table -> distmult_forward -> distmult_backward ->
+    sage_backward_sgd, one batch of positive edges per step (--separate-gather: dense_gather + sage_forward and
+    sage_backward with dL/dH^0 + dn_embedding_sgd instead of the two fused calls)."""
     import numpy as np
     import torch
     import paper_2202_02365_amd as dn
@@ -166,7 +166,8 @@ def run_link_prediction(args, cfg):
                     pos=torch.empty(B, device=dev), loss=torch.empty(B, device=dev),
                     g_out=torch.empty((cfg.batch, dims[-1]), device=dev), g_rel=torch.empty((num_rel, dims[-1]), device=dev),
                     dws=[torch.empty_like(w) for w in w_self], dwn=[torch.empty_like(w) for w in w_nbr],
-                    dbs=[torch.empty_like(x) for x in bias], dh0=torch.empty((b.node_capacity, dims[0]), device=dev),
+                    dbs=[torch.empty_like(x) for x in bias],
+                    dh0=torch.empty((b.node_capacity, dims[0]), device=dev) if args.separate_gather else None,
                     stream=torch.cuda.Stream())
 
     def step(o, bi, update=True):
@@ -179,9 +180,13 @@ def run_link_prediction(args, cfg):
             dn.sage_forward_table(o["model"], o["batch"], table, o["out"])
         dn.distmult_forward(o["dec"], o["out"], R, ls, rel, ld, ln.view(-1, Nn), o["pos"], o["loss"])
         dn.distmult_backward(o["dec"], o["g_out"], o["g_rel"])
-        dn.sage_backward(o["model"], o["batch"], o["g_out"], o["dws"], o["dwn"], o["dbs"], o["dh0"])
-        if update:
-            dn.embedding_sgd(o["batch"], table, o["dh0"], lr)
+        if args.separate_gather:
+            dn.sage_backward(o["model"], o["batch"], o["g_out"], o["dws"], o["dwn"], o["dbs"], o["dh0"])
+            if update:
+                dn.embedding_sgd(o["batch"], table, o["dh0"], lr)
+        else:
+            # the layer-1 input gradient is applied to the table as it is formed: no dL/dH^0 buffer
+            dn.sage_backward_sgd(o["model"], o["batch"], o["g_out"], o["dws"], o["dwn"], o["dbs"], table, lr)
 
     slot = make_slot()
     sizes = []

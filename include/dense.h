@@ -210,6 +210,15 @@ DN_API int  sage_backward(dn_model* m, const dn_batch* b, const float* d_grad_ou
                    float* const* d_dw_self, float* const* d_dw_nbr, float* const* d_dbias,
                    float* d_dH0, void* stream);
 
+/* sage_backward_sgd: sage_backward for learnable base representations without the dL/dH^0 round trip: the layer-1
+ * input gradient of node_ids[r] is applied to the lookup table as it is formed,
+ *   d_table[node_ids[r], :] -= lr * dL/dH^0[r, :]      (fp32, product and difference rounded separately),
+ * which leaves the table exactly as sage_backward with d_dH0 followed by dn_embedding_sgd does.  The forward pass of
+ * the same sample must have read the table before (sage_forward_table, or dense_gather + sage_forward). */
+DN_API int  sage_backward_sgd(dn_model* m, const dn_batch* b, const float* d_grad_out,
+                              float* const* d_dw_self, float* const* d_dw_nbr, float* const* d_dbias,
+                              float* d_table, int64_t ld_elems, float lr, void* stream);
+
 /* ---- DistMult decoder with shared negatives (link prediction).  The paper names the DistMult score function
  *      (Section 7.1, link prediction: datasets, models and metrics) and the number of negatives (Section 7.3) only;
  *      score, loss and negative scheme are the textbook ones:

@@ -89,6 +89,7 @@ def load_library():
         "sage_forward_table": (ctypes.c_int, [vp, vp, vp, i64, vp, vp]),
         "dn_model_set_aggregation": (ctypes.c_int, [vp, i32]),
         "sage_backward": (ctypes.c_int, [vp, vp, vp, pp, pp, pp, vp, vp]),
+        "sage_backward_sgd": (ctypes.c_int, [vp, vp, vp, pp, pp, pp, vp, i64, ctypes.c_float, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -421,3 +422,13 @@ def sage_backward(model: Model, batch: Batch, grad_out: torch.Tensor, d_w_self: 
     _check(load_library().sage_backward(model.handle, batch.handle, _dev_ptr(grad_out, torch.float32),
                                         _ptr_array(d_w_self), _ptr_array(d_w_nbr), _ptr_array(d_bias),
                                         _dev_ptr(d_h0, torch.float32), _stream()))
+
+
+def sage_backward_sgd(model: Model, batch: Batch, grad_out: torch.Tensor, d_w_self: Sequence[torch.Tensor],
+                      d_w_nbr: Sequence[torch.Tensor], d_bias: Sequence[torch.Tensor], table: torch.Tensor,
+                      lr: float) -> None:
+    """sage_backward that applies the SGD step of the learnable input rows to `table` instead of writing dL/dH^0."""
+    assert table.dtype == torch.float32 and table.stride(1) == 1 and table.shape[1] == model.dims[0]
+    _check(load_library().sage_backward_sgd(model.handle, batch.handle, _dev_ptr(grad_out, torch.float32),
+                                            _ptr_array(d_w_self), _ptr_array(d_w_nbr), _ptr_array(d_bias),
+                                            table.data_ptr(), table.stride(0), lr, _stream()))

@@ -482,8 +482,22 @@ int sage_backward(dn_model* m, const dn_batch* b, const float* d_grad_out, float
     if (m->fwd_serial != b->sample_serial || b->sample_serial == 0)
         return dn_fail(DN_ESTATE, "sage_backward needs sage_forward on the same model and sample first");
     // the transpose index is cached in the batch object; building it is part of this call
-    return dn_launch_backward(m, const_cast<dn_batch*>(b), d_grad_out, d_dw_self, d_dw_nbr, d_dbias, d_dH0,
+    return dn_launch_backward(m, const_cast<dn_batch*>(b), d_grad_out, d_dw_self, d_dw_nbr, d_dbias, d_dH0, nullptr, 0, 0.f,
                               static_cast<hipStream_t>(stream));
+}
+
+int sage_backward_sgd(dn_model* m, const dn_batch* b, const float* d_grad_out, float* const* d_dw_self,
+                      float* const* d_dw_nbr, float* const* d_dbias, float* d_table, int64_t ld_elems, float lr, void* stream)
+{
+    if (!m || !b || !d_grad_out || !d_dw_self || !d_dw_nbr || !d_dbias || !d_table) return dn_fail(DN_EINVAL, "null argument");
+    for (int i = 0; i < m->k; ++i)
+        if (!d_dw_self[i] || !d_dw_nbr[i] || !d_dbias[i]) return dn_fail(DN_EINVAL, "gradient buffers of layer %d are null", i + 1);
+    if (m->in_dtype != DN_F32) return dn_fail(DN_EINVAL, "learnable base representations are fp32");
+    if (ld_elems < m->dims[0]) return dn_fail(DN_EINVAL, "row stride below the input width");
+    if (m->fwd_serial != b->sample_serial || b->sample_serial == 0)
+        return dn_fail(DN_ESTATE, "sage_backward_sgd needs sage_forward on the same model and sample first");
+    return dn_launch_backward(m, const_cast<dn_batch*>(b), d_grad_out, d_dw_self, d_dw_nbr, d_dbias, nullptr, d_table, ld_elems,
+                              lr, static_cast<hipStream_t>(stream));
 }
 
 int dn_profile_calibration_copy(void* d_dst, const void* d_src, size_t bytes, void* stream)

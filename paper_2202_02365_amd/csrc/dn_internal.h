@@ -186,7 +186,8 @@ int dn_launch_set_weights(dn_model* m, const float* const* ws, const float* cons
 int dn_launch_forward(dn_model* m, const dn_batch* b, const void* h0, int64_t ldh, int from_table, float* out,
                       hipStream_t st);
 int dn_launch_backward(dn_model* m, dn_batch* b, const float* grad_out, float* const* dws,
-                       float* const* dwn, float* const* dbias, float* dh0, hipStream_t st);
+                       float* const* dwn, float* const* dbias, float* dh0, float* sgd_table, int64_t sgd_ld, float sgd_lr,
+                       hipStream_t st);
 
 // row-tile workgroups of the dZ kernel = partial column sums the bias-gradient reduction adds up
 constexpr unsigned DN_DZ_MAX_ROW_BLOCKS = 512;

@@ -141,6 +141,42 @@ __global__ __launch_bounds__(TPB) void k_dz(const int32_t* __restrict__ hdr, int
 // row) + sum over the slots that read r, in ascending slot order, of dX_mean[owner] / count[owner].
 // tr_ptr / tr_val: slots grouped by the node_ids position they read, ascending within a group;
 // a layer's slots are those >= its first slot, i.e. a suffix of every group.
+// where the input gradient of a row goes: into G_in, or straight into the lookup table as a plain SGD step
+// (learnable base representations; product and difference rounded separately, as dn_embedding_sgd does)
+struct GradSink {
+    float* gin;                  // [rows_in x d], or null
+    float* table; int64_t ld;    // update mode: table[node_ids[p], :] -= lr * gradient
+    const int32_t* node_ids;
+    float lr;
+};
+__device__ __forceinline__ void sink_store(const GradSink& k, int r, int p, int d, int c, float v)
+{
+#pragma clang fp contract(off)
+    if (k.table) {
+        float* w = k.table + (int64_t)k.node_ids[p] * k.ld + c;
+        const float step = k.lr * v;
+        *w = *w - step;
+    } else {
+        k.gin[(int64_t)r * d + c] = v;
+    }
+}
+// V consecutive columns starting at c0 (V = 4: one 16-byte access when the table's rows allow it)
+template <int V>
+__device__ __forceinline__ void sink_store_vec(const GradSink& k, int r, int p, int d, int c0, const float (&v)[V])
+{
+#pragma clang fp contract(off)
+    if (V == 4 && k.table && (k.ld & 3) == 0) {
+        float4* w = reinterpret_cast<float4*>(k.table + (int64_t)k.node_ids[p] * k.ld + c0);
+        float4 o = *w;
+        const float s0 = k.lr * v[0], s1 = k.lr * v[1], s2 = k.lr * v[2], s3 = k.lr * v[3];
+        o.x = o.x - s0; o.y = o.y - s1; o.z = o.z - s2; o.w = o.w - s3;
+        *w = o;
+        return;
+    }
+#pragma unroll
+    for (int e = 0; e < V; ++e) sink_store(k, r, p, d, c0 + e, v[e]);
+}
+
 constexpr int HUB_ENTRIES_PER_BLOCK = 4;
 template <int V, int LANES, int ITERS>
 __global__ __launch_bounds__(TPB) void k_aggregate_bwd(const int32_t* __restrict__ hdr, int layer,
@@ -150,7 +186,7 @@ __global__ __launch_bounds__(TPB) void k_aggregate_bwd(const int32_t* __restrict
                                                        const int32_t* __restrict__ tr_long, int n_long, int row_blocks,
                                                        int mean_agg,
                                                        const float* __restrict__ dX, int ldx, int d,
-                                                       float* __restrict__ Gin)
+                                                       GradSink sink)
 {
     const int N = hdr[HDR_N];
     const int off_in = hdr[HDR_NODE_OFF + layer - 1];
@@ -216,7 +252,7 @@ __global__ __launch_bounds__(TPB) void k_aggregate_bwd(const int32_t* __restrict
                 for (int c = threadIdx.x; c < d; c += TPB) {
                     float tot = (p >= off_out) ? dX[(int64_t)(p - off_out) * ldx + c] : 0.f;
                     for (int w = 0; w < GROUPS; ++w) tot += part[w][c];
-                    Gin[(int64_t)r * d + c] = tot;
+                    sink_store(sink, r, p, d, c, tot);
                 }
                 __syncthreads();
             }
@@ -264,8 +300,7 @@ __global__ __launch_bounds__(TPB) void k_aggregate_bwd(const int32_t* __restrict
         for (int it = 0; it < ITERS; ++it) {
             const int c0 = (it * LANES + lane) * V;
             if (c0 < d) {
-#pragma unroll
-                for (int e = 0; e < V; ++e) Gin[(int64_t)r * d + c0 + e] = acc[it][e];
+                sink_store_vec<V>(sink, r, p, d, c0, acc[it]);
             }
         }
     }
@@ -312,7 +347,7 @@ int launch_aggregate_t(const dn_model* m, const dn_batch* b, int i, const TIN* H
     return DN_OK;
 }
 
-int launch_aggregate_bwd(const dn_model* m, const dn_batch* b, int i, float* gin, hipStream_t st)
+int launch_aggregate_bwd(const dn_model* m, const dn_batch* b, int i, const GradSink& sink, hipStream_t st)
 {
     const dn_layer_bufs& L = m->layer[i - 1];
     const int d = L.d_in;
@@ -338,7 +373,7 @@ int launch_aggregate_bwd(const dn_model* m, const dn_batch* b, int i, float* gin
 #define DN_AGGB(VV, LL, II)                                                                                           \
     hipLaunchKernelGGL((k_aggregate_bwd<VV, LL, II>), dim3((int)grid), dim3(TPB), 0, st, b->hdr, i, b->nbr_offsets,   \
                        b->tr_ptr, b->tr_val[0], b->tr_own, b->tr_inv, b->tr_long, n_long, (int)row_blocks, m->mean_agg, m->dx,  \
-                       2 * d, d, gin)
+                       2 * d, d, sink)
     if (vec4 && d <= 256) {
         switch (lanes) {
             case 4: DN_AGGB(4, 4, 1); break;
@@ -383,10 +418,12 @@ int dn_launch_forward(dn_model* m, const dn_batch* b, const void* h0, int64_t ld
 }
 
 int dn_launch_backward(dn_model* m, dn_batch* b, const float* grad_out, float* const* dws,
-                       float* const* dwn, float* const* dbias, float* dh0, hipStream_t st)
+                       float* const* dwn, float* const* dbias, float* dh0, float* sgd_table, int64_t sgd_ld, float sgd_lr,
+                       hipStream_t st)
 {
     const int k = m->k;
-    int rc = dn_launch_transpose_index(b, dh0 != nullptr, st);     // no-op when prepared for this sample
+    const bool need_input_grad = dh0 != nullptr || sgd_table != nullptr;
+    int rc = dn_launch_transpose_index(b, need_input_grad, st);     // no-op when prepared for this sample
     if (rc) return rc;
     // The chain that carries the gradient down the layers comes first: dZ^i -> dX^i -> transpose of
     // the mean -> dZ^{i-1}.  What nothing downstream waits for (the dW GEMMs, the reductions of dW and db)
@@ -405,13 +442,14 @@ int dn_launch_backward(dn_model* m, dn_batch* b, const float* grad_out, float* c
                                i, g, L.d_out, nullptr, L.d_out, L.np, 0, reinterpret_cast<uint16_t*>(L.dzb), L.db_partial);
         }
         DN_LAUNCH_CHECK("k_dz");
-        if (i == 1 && dh0 == nullptr) break;            // nothing consumes the input gradient of layer 1
+        if (i == 1 && !need_input_grad) break;          // nothing consumes the input gradient of layer 1
         rc = dn_gemm_dx(m, b, i, st);
         if (rc) return rc;
-        float* gin = (i == 1) ? dh0 : m->g[i & 1];
-        rc = launch_aggregate_bwd(m, b, i, gin, st);
+        GradSink sink = { (i == 1) ? dh0 : m->g[i & 1], nullptr, 0, b->node_ids, 0.f };
+        if (i == 1 && sgd_table) { sink.gin = nullptr; sink.table = sgd_table; sink.ld = sgd_ld; sink.lr = sgd_lr; }
+        rc = launch_aggregate_bwd(m, b, i, sink, st);
         if (rc) return rc;
-        g = gin;
+        g = sink.gin;
     }
     return dn_gemm_dw_all(m, b, dws, dwn, dbias, st);
 }

@@ -175,3 +175,34 @@ def test_backward_before_forward_is_an_error(g16k):
     with pytest.raises(dn.DenseError) as e:
         dn.sage_backward(model, batch, torch.zeros((8, 4), device="cuda:0"), w, w, b)
     assert e.value.code == -4
+
+
+@pytest.mark.parametrize("direction,fanouts,dims", [(0, [6, 4], [24, 32, 8]), (2, [5], [100, 100])])
+def test_backward_with_fused_sgd_update_equals_backward_then_embedding_sgd(g16k, direction, fanouts, dims):
+    V = g16k.num_nodes
+    targets = target_batch(V, 300, 4)
+    batch = dn.Batch(V, len(targets), fanouts, direction)
+    gpu_sample(g16k, batch, targets, seed=21)
+    table = feature_table(V, dims[0], "f32", seed=2).to("cuda:0")
+    w_self, w_nbr, bias = glorot_weights(dims, seed=3, bias_scale=0.1)
+    model = dn.Model(batch, dims)
+    model.set_weights(to_dev(w_self), to_dev(w_nbr), to_dev(bias))
+    out = torch.empty((len(targets), dims[-1]), device="cuda:0")
+    dn.sage_forward_table(model, batch, table, out)
+    gout = torch.randn(out.shape, generator=torch.Generator().manual_seed(5)).to("cuda:0")
+    grads_a = [[torch.empty_like(t) for t in to_dev(g)] for g in (w_self, w_nbr, bias)]
+    grads_b = [[torch.empty_like(t) for t in to_dev(g)] for g in (w_self, w_nbr, bias)]
+    dh0 = torch.empty((batch.node_capacity, dims[0]), device="cuda:0")
+    # two-step form on a copy of the table
+    dn.sage_backward(model, batch, gout, *grads_a, dh0)
+    two_step = table.clone()
+    dn.embedding_sgd(batch, two_step, dh0, 0.05)
+    # fused form on another copy
+    fused = table.clone()
+    dn.sage_backward_sgd(model, batch, gout, *grads_b, fused, 0.05)
+    torch.cuda.synchronize()
+    assert torch.equal(two_step, fused)
+    assert not torch.equal(fused, table)
+    for ga, gb in zip(grads_a, grads_b):
+        for a, b in zip(ga, gb):
+            assert torch.equal(a, b)
