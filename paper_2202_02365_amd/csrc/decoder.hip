@@ -61,13 +61,6 @@ namespace {
 
 constexpr int TPB_ = 256;
 
-__device__ __forceinline__ uint16_t to_bf16(float x)      // round to nearest even; inputs are finite
-{
-    const uint32_t u = __float_as_uint(x);
-    return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
-}
-__device__ __forceinline__ float from_bf16(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
-
 // ------------------------------------------------------------------ operands of the score contraction
 // One group of 16 lanes per operand row.  Rows [0, 2*C*cpad): Q[side][q][i] = bf16(h_a * r) for edge
 // e = q*chunk + i (a = source for side 0, destination for side 1), zero rows where there is no edge.
@@ -110,7 +103,7 @@ __global__ __launch_bounds__(TPB_) void k_dm_prepare(const float* __restrict__ H
                 qv = ha[j] * rv[j];
                 acc += qv * ho[j];
             }
-            out[j] = to_bf16(qv);
+            out[j] = f32_to_bf16(qv);
         }
         if (side == 0 && i < chunk && e < B) {
             for (int s = 8; s > 0; s >>= 1) acc += __shfl_down(acc, s, 16);
@@ -127,7 +120,7 @@ __global__ __launch_bounds__(TPB_) void k_dm_prepare(const float* __restrict__ H
             if ((unsigned)v >= (unsigned)n_rows) { ok = false; if (sl == 0) atomicOr(&hdr[DM_HDR_STATUS_ACC], DM_BAD_NODE); }
         }
         const float* hv = H + (int64_t)v * ldh;
-        for (int j = sl; j < kp; j += 16) out[j] = to_bf16(ok && j < d ? hv[j] : 0.f);
+        for (int j = sl; j < kp; j += 16) out[j] = f32_to_bf16(ok && j < d ? hv[j] : 0.f);
     }
 }
 
@@ -293,8 +286,8 @@ __global__ __launch_bounds__(TPB_) void k_dm_probs(const float* __restrict__ S, 
         const int64_t e = (int64_t)q * chunk + i;
         float p = 0.f;
         if (i < chunk && e < B && n < Nn) p = expf(Sz[(int64_t)i * npad + n] - lse[(int64_t)side * B + e]);
-        const uint16_t hi = to_bf16(p);
-        const uint16_t lo = to_bf16(p - from_bf16(hi));
+        const uint16_t hi = f32_to_bf16(p);
+        const uint16_t lo = f32_to_bf16(p - bf16_to_f32(hi));
         Pz[(int64_t)i * 2 * npad + n] = hi;
         Pz[(int64_t)i * 2 * npad + npad + n] = lo;
     }

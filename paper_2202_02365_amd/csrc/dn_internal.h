@@ -129,6 +129,16 @@ struct dn_prof_scope {
 
 static inline int64_t dn_round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
+// fp32 <-> bfloat16 bit patterns, round to nearest even (a NaN stays a quiet NaN)
+__device__ __forceinline__ uint16_t f32_to_bf16(float x)
+{
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
 struct dn_carver {       // hands out 256-byte aligned pieces of one workspace; counts when base == nullptr
     char* base;
     size_t off = 0;

@@ -292,14 +292,6 @@ __global__ __launch_bounds__(TPB) void k_bwd_reduce_group(ReduceGroup R, const i
 }
 
 // fp32 weights -> the two zero-padded bf16 layouts (round to nearest even).
-__device__ __forceinline__ uint16_t f32_to_bf16(float x)
-{
-    uint32_t u = __float_as_uint(x);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
-
 __global__ __launch_bounds__(TPB) void k_pack_weights(const float* __restrict__ ws, const float* __restrict__ wn,
                                                       const float* __restrict__ bias, int d_in, int d_out, int kp, int np,
                                                       int nz, int xterms, int zterms, uint16_t* __restrict__ wt,
