@@ -591,12 +591,20 @@ def main():
                          % args.replicas)
 
     # per-kernel durations: the same K steps again, every launch bracketed by HIP events on its stream
-    roofline, kernels = None, {}
+    roofline, kernels, copy_gbs = None, {}, None
     if not args.no_kernel_times:
         # The event pairs time what the GPU does only if the host is ahead of it: every step is preceded by
         # a ~1 ms streaming copy (not bracketed) during which the host queues the whole step.
         delay_src = torch.empty(256 << 20, dtype=torch.float32, device=dev)
         delay_dst = torch.empty_like(delay_src)
+        # what a plain streaming copy reaches on this machine (1 GiB read + 1 GiB written per call): context for the peak
+        dn.profile_calibration_copy(delay_dst, delay_src)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(10):
+            dn.profile_calibration_copy(delay_dst, delay_src)
+        torch.cuda.synchronize()
+        copy_gbs = 10 * 2 * delay_src.numel() * 4 / (time.perf_counter() - t0) / 1e9
         dn.profile_enable(True)
         torch.cuda.synchronize()
         for s in range(args.steps):
@@ -692,6 +700,7 @@ def main():
                           "sampled_edges_per_s": edges / serial_s,
                           "sample_gather_fwd_ms_per_step": 1e3 * serial_fwd_s / args.steps},
         "roofline": roofline,
+        "streaming_copy_GBs": copy_gbs,
         "kernels": kernels,
         "cpu_baseline": baseline,
     }
