@@ -2,7 +2,8 @@
 """Benchmark of the DENSE hot path on one MI355X.
 
 One step = one mini-batch through every step of the path: dense_sample (3-hop DENSE
-construction) -> dense_gather (H^0) -> sage_forward -> sage_backward, on synthetic inputs that
+construction) -> gather of H^0 (inside sage_forward_table, or dense_gather with --separate-gather)
+-> forward -> softmax cross-entropy head -> sage_backward, on synthetic inputs that
 are resident in HBM before the clock starts.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload rmat111m|rmat1m|rmat16k|...]
@@ -370,7 +371,15 @@ def main():
     h0 = torch.empty((batch.node_capacity, dims[0]), dtype=table.dtype, device=dev)
     out = torch.empty((cfg.batch, dims[-1]), dtype=torch.float32, device=dev)
     gen = torch.Generator(device="cpu").manual_seed(11)
-    grad_out = (torch.randn((cfg.batch, dims[-1]), generator=gen) / cfg.batch).to(dev)   # synthetic dL/dH^k
+    grad_out = torch.empty((cfg.batch, dims[-1]), dtype=torch.float32, device=dev)        # dL/dH^k from the loss head
+    loss_buf = torch.empty(cfg.batch, dtype=torch.float32, device=dev)
+    from workloads import class_labels
+    labels = torch.from_numpy(class_labels(cfg.batch, dims[-1]).astype(np.int32)).to(dev)  # synthetic class per target
+
+    def loss_and_backward(m, b, out_buf, gout_buf, lbuf, dws_, dwn_, dbs_, dh0_):
+        # softmax cross-entropy head on the device (mean over the batch), then the encoder's backward pass
+        dn.softmax_xent(out_buf, labels, lbuf, gout_buf, 1.0 / cfg.batch)
+        dn.sage_backward(m, b, gout_buf, dws_, dwn_, dbs_, dh0_)
     dws = [torch.empty_like(w) for w in w_self]
     dwn = [torch.empty_like(w) for w in w_nbr]
     dbs = [torch.empty_like(b) for b in bias]
@@ -397,7 +406,7 @@ def main():
         else:
             dn.sage_forward_table(model, batch, table, out)
         if backward:
-            dn.sage_backward(model, batch, grad_out, dws, dwn, dbs, dh0)
+            loss_and_backward(model, batch, out, grad_out, loss_buf, dws, dwn, dbs, dh0)
 
     # Two mini-batches in flight: batch t+1 is sampled and gathered on one stream while batch t runs
     # forward/backward on another (mini-batch construction does not read the weights; this is the
@@ -427,7 +436,7 @@ def main():
                 s_compute.wait_event(ev_built[s & 1])
                 forward(model, b_s, h0_s, out)
                 if backward:
-                    dn.sage_backward(model, b_s, grad_out, dws, dwn, dbs, dh0)
+                    loss_and_backward(model, b_s, out, grad_out, loss_buf, dws, dwn, dbs, dh0)
                 ev_free[s & 1].record(s_compute)
         torch.cuda.synchronize()
         return time.perf_counter() - t0
@@ -476,7 +485,7 @@ def main():
                         b_nxt.prepare_backward(need_dh0)
                 forward(model, b_cur, h0_cur, out)
                 if backward:
-                    dn.sage_backward(model, b_cur, grad_out, dws, dwn, dbs, dh0)
+                    loss_and_backward(model, b_cur, out, grad_out, loss_buf, dws, dwn, dbs, dh0)
                 s_compute.wait_stream(s_build)
             graphs[(bi, backward)] = g
         torch.cuda.synchronize()
@@ -507,6 +516,7 @@ def main():
             m = dn.Model(b, dims, in_dtype)
             m.set_weights(w_self, w_nbr, bias)
             reps.append(dict(batch=b, model=m, h0=torch.empty_like(h0), out=torch.empty_like(out),
+                             gout=torch.empty_like(grad_out), loss=torch.empty_like(loss_buf),
                              dws=[torch.empty_like(w) for w in w_self], dwn=[torch.empty_like(w) for w in w_nbr],
                              dbs=[torch.empty_like(x) for x in bias],
                              dh0=None if dh0 is None else torch.empty_like(dh0), stream=torch.cuda.Stream()))
@@ -522,7 +532,7 @@ def main():
                     gather(o["batch"], o["h0"])
                     forward(o["model"], o["batch"], o["h0"], o["out"])
                     if backward:
-                        dn.sage_backward(o["model"], o["batch"], grad_out, o["dws"], o["dwn"], o["dbs"], o["dh0"])
+                        loss_and_backward(o["model"], o["batch"], o["out"], o["gout"], o["loss"], o["dws"], o["dwn"], o["dbs"], o["dh0"])
             torch.cuda.synchronize()
             return time.perf_counter() - t0
         run(max(args.warmup, n_rep))
@@ -535,7 +545,7 @@ def main():
                     dn.dense_sample(o["batch"], graph, targets[bi], bi)
                     gather(o["batch"], o["h0"])
                     forward(o["model"], o["batch"], o["h0"], o["out"])
-                    dn.sage_backward(o["model"], o["batch"], grad_out, o["dws"], o["dwn"], o["dbs"], o["dh0"])
+                    loss_and_backward(o["model"], o["batch"], o["out"], o["gout"], o["loss"], o["dws"], o["dwn"], o["dbs"], o["dh0"])
             torch.cuda.synchronize()
             o = reps[0]
             if not all(torch.equal(a, b) for a, b in zip(eager, o["dws"] + o["dwn"] + o["dbs"] + [o["out"]])):
