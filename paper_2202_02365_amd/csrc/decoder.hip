@@ -655,7 +655,8 @@ int distmult_forward(dn_decoder* d, const float* d_H, int64_t ldh, int64_t n_row
                      const int32_t* d_src, const int32_t* d_rel, const int32_t* d_dst, int64_t n_edges,
                      const int32_t* d_neg, float* d_pos, float* d_loss, void* stream)
 {
-    if (!d || !d_H || !d_R || !d_src || !d_rel || !d_dst || !d_neg || !d_pos || !d_loss)
+    if (!d || !d_H || !d_R) return dn_fail(DN_EINVAL, "null argument");
+    if (n_edges > 0 && (!d_src || !d_rel || !d_dst || !d_neg || !d_pos || !d_loss))
         return dn_fail(DN_EINVAL, "null argument");
     if (n_edges < 0 || n_edges > d->max_edges) return dn_fail(DN_ECAPACITY, "n_edges %lld exceeds the decoder's %lld",
                                                              (long long)n_edges, (long long)d->max_edges);

@@ -130,3 +130,22 @@ def test_decoder_full_size_workload_shape():
     each, 100-dim representations of 150,000 target rows, 1,000 Zipf(1.1) relation types."""
     got, inputs, _ = run_decoder(150_000, 1000, 100, 50_000, 1000, 1000, seed=13)
     check(got, inputs, 1000, "full size")
+
+
+def test_decoder_empty_batch_gives_zero_gradients():
+    dev = torch.device("cuda:0")
+    dec = dn.Decoder(100, 50, 20, 16, 64, 3)
+    H = torch.randn((64, 16), device=dev)
+    R = torch.randn((3, 16), device=dev)
+    empty = torch.empty(0, dtype=torch.int32, device=dev)
+    pos, loss = torch.empty(0, device=dev), torch.empty(0, device=dev)
+    dn.distmult_forward(dec, H, R, empty, empty, empty, torch.empty((0, 20), dtype=torch.int32, device=dev), pos, loss)
+    dH = torch.full((64, 16), float("nan"), device=dev)
+    dR = torch.full((3, 16), float("nan"), device=dev)
+    dn.distmult_backward(dec, dH, dR)
+    torch.cuda.synchronize()
+    assert torch.all(dH == 0) and torch.all(dR == 0)
+    # and a normal batch afterwards through the same decoder
+    inputs = decoder_inputs(64, 3, 16, 90, 50, 20, seed=14)
+    got, _, _ = run_decoder(64, 3, 16, 90, 50, 20, inputs=inputs, dec=dec)
+    check(got, inputs, 50, "after an empty batch")
