@@ -46,25 +46,46 @@ __global__ __launch_bounds__(TPB) void k_aggregate(const int32_t* __restrict__ h
         const int p = off_out + ro;
         const int q = p - off1;
         const int beg = nbr_offsets[q], end = nbr_offsets[q + 1];
-        const float cnt = (float)(end - beg);
+        const float cnt_f = (float)(end - beg);
         const TIN* self = TABLE ? H + (int64_t)node_ids[p] * ldh : H + (int64_t)(p - off_in) * ldh;
         uint16_t* xrow = X + (int64_t)ro * kp;
         float sq = 0.f;
-        for (int c0 = lane * V; c0 < d; c0 += LANES * V) {
+        const int iters = (d + LANES * V - 1) / (LANES * V);      // the same for every lane: the shuffles below need the whole group
+        for (int it = 0; it < iters; ++it) {
+            const int c0 = (it * LANES + lane) * V;
+            const bool col_ok = c0 < d;
+            const int cc = col_ok ? c0 : 0;                        // lanes beyond the row read its first columns and drop them
             float acc[V];
 #pragma unroll
             for (int e = 0; e < V; ++e) acc[e] = 0.f;
-            for (int j = beg; j < end; ++j) {
-                const TIN* nb = (TABLE ? H + (int64_t)nbrs[j] * ldh : H + (int64_t)(repr_map[j] - off_in) * ldh) + c0;
-                float v[V];
+            // The group's lanes fetch the slots' row numbers side by side and hand them round by shuffles, so that the
+            // row loads of up to eight slots are in flight at once; the additions keep the ascending slot order.
+            for (int base = beg; base < end; base += LANES) {
+                const int t = base + lane;
+                int row = 0;
+                if (t < end) row = TABLE ? nbrs[t] : repr_map[t] - off_in;
+                const int cnt = min(LANES, end - base);
+                for (int l = 0; l < cnt; l += 8) {
+                    float v[8][V];
 #pragma unroll
-                for (int e = 0; e < V; ++e) v[e] = load_elem(nb + e);
+                    for (int u = 0; u < 8; ++u) {
+                        const int ru = __shfl(row, min(l + u, cnt - 1), LANES);
+                        const TIN* nb = H + (int64_t)ru * ldh + cc;
 #pragma unroll
-                for (int e = 0; e < V; ++e) acc[e] += v[e];
+                        for (int e = 0; e < V; ++e) v[u][e] = load_elem(nb + e);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (l + u < cnt) {
+#pragma unroll
+                            for (int e = 0; e < V; ++e) acc[e] += v[u][e];
+                        }
+                }
             }
+            if (!col_ok) continue;
 #pragma unroll
             for (int e = 0; e < V; ++e) {
-                const float mean = end > beg ? (mean_agg ? acc[e] / cnt : acc[e]) : 0.f;
+                const float mean = end > beg ? (mean_agg ? acc[e] / cnt_f : acc[e]) : 0.f;
                 const float sv = load_elem(self + c0 + e);
                 const uint16_t s_hi = f32_to_bf16(sv), m_hi = f32_to_bf16(mean);
                 xrow[c0 + e] = s_hi;
@@ -272,17 +293,50 @@ __global__ __launch_bounds__(TPB) void k_aggregate_bwd(const int32_t* __restrict
             const int q = valid ? tr_own[t] : -1;
             const float inv = valid ? (mean_agg ? tr_inv[t] : 1.f) : 0.f;
             const int cnt = min(LANES, end - base);
-            for (int l = 0; l < cnt; ++l) {
-                const int ql = __shfl(q, l, LANES);
-                const float il = __shfl(inv, l, LANES);
-                if (ql < 0) continue;
-                const float* src = dXm + (int64_t)ql * ldx;
+            if (ITERS == 1) {
+                // rows with many slots: four gradient rows in flight at a time (a slot that does not count reads the
+                // first row with weight 0); the rest one by one
+                const int c0 = lane * V;
+                const int cc = c0 < d ? c0 : 0;
+                int l = 0;
+                for (; l + 4 <= cnt; l += 4) {
+                    float v[4][V], w[4];
 #pragma unroll
-                for (int it = 0; it < ITERS; ++it) {
-                    const int c0 = (it * LANES + lane) * V;
-                    if (c0 < d) {
+                    for (int u = 0; u < 4; ++u) {
+                        const int ql = __shfl(q, l + u, LANES);
+                        w[u] = ql >= 0 ? __shfl(inv, l + u, LANES) : 0.f;
+                        const float* src = (ql >= 0 ? dXm + (int64_t)ql * ldx : dX + d) + cc;
 #pragma unroll
-                        for (int e = 0; e < V; ++e) acc[it][e] += src[c0 + e] * il;
+                        for (int e = 0; e < V; ++e) v[u][e] = src[e];
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (w[u] != 0.f) {
+#pragma unroll
+                            for (int e = 0; e < V; ++e) acc[0][e] += v[u][e] * w[u];
+                        }
+                }
+                for (; l < cnt; ++l) {
+                    const int ql = __shfl(q, l, LANES);
+                    const float il = __shfl(inv, l, LANES);
+                    if (ql < 0 || c0 >= d) continue;
+                    const float* src = dXm + (int64_t)ql * ldx + c0;
+#pragma unroll
+                    for (int e = 0; e < V; ++e) acc[0][e] += src[e] * il;
+                }
+            } else {
+                for (int l = 0; l < cnt; ++l) {
+                    const int ql = __shfl(q, l, LANES);
+                    const float il = __shfl(inv, l, LANES);
+                    if (ql < 0) continue;
+                    const float* src = dXm + (int64_t)ql * ldx;
+#pragma unroll
+                    for (int it = 0; it < ITERS; ++it) {
+                        const int c0 = (it * LANES + lane) * V;
+                        if (c0 < d) {
+#pragma unroll
+                            for (int e = 0; e < V; ++e) acc[it][e] += src[c0 + e] * il;
+                        }
                     }
                 }
             }
