@@ -173,16 +173,16 @@ __device__ __forceinline__ void sink_store(const GradSink& k, int r, int p, int 
     }
 }
 // V consecutive columns starting at c0 (V = 4: one 16-byte access when the table's rows allow it)
+// `w` / `old`: the table row's four values at c0, fetched by the caller before it walked the slots (null: not fetched)
 template <int V>
-__device__ __forceinline__ void sink_store_vec(const GradSink& k, int r, int p, int d, int c0, const float (&v)[V])
+__device__ __forceinline__ void sink_store_vec(const GradSink& k, int r, int p, int d, int c0, const float (&v)[V],
+                                               float4* w, float4 old)
 {
 #pragma clang fp contract(off)
-    if (V == 4 && k.table && (k.ld & 3) == 0) {
-        float4* w = reinterpret_cast<float4*>(k.table + (int64_t)k.node_ids[p] * k.ld + c0);
-        float4 o = *w;
+    if (w) {
         const float s0 = k.lr * v[0], s1 = k.lr * v[1], s2 = k.lr * v[2], s3 = k.lr * v[3];
-        o.x = o.x - s0; o.y = o.y - s1; o.z = o.z - s2; o.w = o.w - s3;
-        *w = o;
+        old.x = old.x - s0; old.y = old.y - s1; old.z = old.z - s2; old.w = old.w - s3;
+        *w = old;
         return;
     }
 #pragma unroll
@@ -278,6 +278,13 @@ __global__ __launch_bounds__(TPB) void k_aggregate_bwd(const int32_t* __restrict
         const int p = off_in + r;
         const int beg = tr_ptr[p], end = tr_ptr[p + 1];
         if (end - beg > DN_LONG_GROUP) continue;             // left to a workgroup of its own (above)
+        // update mode: the table row is fetched now, so that its latency overlaps the walk over the slots
+        float4* wrow = nullptr;
+        float4 wold = {0.f, 0.f, 0.f, 0.f};
+        if (V == 4 && ITERS == 1 && sink.table && (sink.ld & 3) == 0 && lane * V < d) {
+            wrow = reinterpret_cast<float4*>(sink.table + (int64_t)sink.node_ids[p] * sink.ld + lane * V);
+            wold = *wrow;
+        }
         float acc[ITERS][V];
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
@@ -345,7 +352,7 @@ __global__ __launch_bounds__(TPB) void k_aggregate_bwd(const int32_t* __restrict
         for (int it = 0; it < ITERS; ++it) {
             const int c0 = (it * LANES + lane) * V;
             if (c0 < d) {
-                sink_store_vec<V>(sink, r, p, d, c0, acc[it]);
+                sink_store_vec<V>(sink, r, p, d, c0, acc[it], wrow, wold);
             }
         }
     }
