@@ -80,6 +80,35 @@ def algorithmic_work(tag, sizes, cfg, dims):
     return "hbm", None
 
 
+def gemm_algorithmic_bytes(tag, sizes, cfg, dims):
+    """Operand + result bytes of one launch of a GEMM kernel (weights left out: a few hundred KB), for the
+    arithmetic intensity that tells whether the MFMA or the HBM roofline is the lower one at this shape."""
+    import numpy as np
+    k = cfg.num_layers
+    off = np.array([s[:k + 2] for s in sizes], dtype=np.float64)
+    N = off[:, k + 1]
+
+    def layer(i):
+        rows = N - off[:, i]
+        xt = 1 if i == 1 else 2                  # bf16 terms of the layer's input operand [self | mean]
+        zt = 1 if i == k else 2                  # bf16 terms of dZ
+        return rows, 2 * dims[i - 1], dims[i], xt, zt
+
+    if tag.startswith("gemm_fwd_L"):
+        rows, kk, n, xt, _ = layer(int(tag.split("_L")[1]))
+        return float(np.mean(rows * kk * xt * 2 + rows * n * 4))
+    if tag.startswith("gemm_dx_L"):
+        rows, kk, n, _, zt = layer(int(tag.split("_L")[1]))
+        return float(np.mean(rows * n * zt * 2 + rows * kk * 4))
+    if tag == "gemm_dw_all":
+        total = 0.0
+        for i in range(1, k + 1):
+            rows, kk, n, xt, zt = layer(i)
+            total = total + rows * kk * xt * 2 + rows * n * zt * 2
+        return float(np.mean(total))
+    return None
+
+
 def measured_traffic(workload, tag):
     """HBM bytes per launch of kernel `tag` from the committed rocprofv3 counter summary (FETCH_SIZE +
     WRITE_SIZE, each scaled by a plain copy of known size), or None if there is none for this workload."""
@@ -654,6 +683,15 @@ def main():
             rate = work / (v["avg_us"] * 1e-6)
             v["bound"] = bound
             v["frac_of_peak"] = rate / (HBM_PEAK_GBS * 1e9 if bound == "hbm" else MFMA_BF16_PEAK_TFLOPS * 1e12)
+            gemm_bytes = gemm_algorithmic_bytes(tag, used, cfg, dims) if bound == "mfma" else None
+            if gemm_bytes:
+                # at these shapes flops / byte sits below the ridge (peak flops / peak bytes), so the HBM roofline
+                # is the lower of the two: the fraction of min(MFMA peak, intensity x HBM peak) goes beside it
+                intensity = work / gemm_bytes
+                attainable = min(MFMA_BF16_PEAK_TFLOPS * 1e12, intensity * HBM_PEAK_GBS * 1e9)
+                v["flop_per_byte"] = intensity
+                v["attainable_TFLOPs"] = attainable / 1e12
+                v["frac_of_attainable"] = rate / attainable
             per_step_us = v["avg_us"] * v["launches_per_step"]
             if best is None or per_step_us > best[0]:
                 best = (per_step_us, tag, bound, work, v["avg_us"])

@@ -219,51 +219,71 @@ __device__ __forceinline__ void dw_reduce_block(const int block, const float* __
                                                 int groups, int zterms, int rows, int xterms, int d_in, int d_out,
                                                 float* __restrict__ dws, float* __restrict__ dwn)
 {
-    const int idx = block * TPB + threadIdx.x;
-    if (idx >= 2 * d_in * d_out) return;
-    const int kk = idx / d_out, n = idx - kk * d_out;
+    // 64 consecutive outputs per workgroup; each of its 4 waves sums a quarter of the list of partials
+    __shared__ float quarter[4][64];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int idx = block * 64 + tx;
+    const bool live = idx < 2 * d_in * d_out;
+    const int kk = live ? idx / d_out : 0, n = live ? idx - kk * d_out : 0;
     const int eff = effective_splits(groups, (rows + BK - 1) / BK);   // the splits the GEMM actually wrote
-    float s = 0.f;
-    for (int t = 0; t < xterms; ++t)
-        for (int zt = 0; zt < zterms; ++zt) {
-            const float* src = partial + (int64_t)zt * groups * split_stride + (int64_t)(kk + t * 2 * d_in) * d_out + n;
-            float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;   // four chains: loads overlap, order stays fixed
-            int z = 0;
-            for (; z + 4 <= eff; z += 4) {
-                s0 += src[(int64_t)(z + 0) * split_stride];
-                s1 += src[(int64_t)(z + 1) * split_stride];
-                s2 += src[(int64_t)(z + 2) * split_stride];
-                s3 += src[(int64_t)(z + 3) * split_stride];
+    // Wave ty takes the splits ty, ty + 4, ... of every (X term, dZ term) combination, eight loads in flight into
+    // eight running sums (a load past the last split re-reads the last one and counts as zero).  The order is
+    // fixed; the chain of dependent loads bounds this kernel, not the bytes.
+    const float* base = partial + (int64_t)kk * d_out + n;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (live) {
+        for (int t = 0; t < xterms; ++t)
+            for (int zt = 0; zt < zterms; ++zt) {
+                const float* src = base + (int64_t)zt * groups * split_stride + (int64_t)t * 2 * d_in * d_out;
+                for (int z = ty; z < eff; z += 32) {
+                    float v[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)min(z + 4 * u, eff - 1) * split_stride];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) acc[u] += (z + 4 * u < eff) ? v[u] : 0.f;
+                }
             }
-            for (; z < eff; ++z) s0 += src[(int64_t)z * split_stride];
-            s += (s0 + s1) + (s2 + s3);
-        }
-    if (kk < d_in) dws[(int64_t)kk * d_out + n] = s;
-    else dwn[(int64_t)(kk - d_in) * d_out + n] = s;
+    }
+    quarter[ty][tx] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
+    __syncthreads();
+    if (ty == 0 && live) {
+        const float s = (quarter[0][tx] + quarter[1][tx]) + (quarter[2][tx] + quarter[3][tx]);
+        if (kk < d_in) dws[(int64_t)kk * d_out + n] = s;
+        else dwn[(int64_t)(kk - d_in) * d_out + n] = s;
+    }
 }
 
-// db[n] = sum over the partial column sums of the dZ kernel's row-tile workgroups.  64 columns per workgroup; each of its 4 waves takes
-// every fourth tile (lanes = columns, coalesced), the four partial sums are combined in a fixed order.
+// db[n] = sum over the partial column sums of the dZ kernel's row-tile workgroups.  16 columns per workgroup; thread
+// group g of 16 takes the tiles g, g + 16, ..., eight loads in flight; the sixteen partial sums are combined in a
+// fixed order.
+constexpr int DB_COLS = 16;
 __device__ __forceinline__ void db_reduce_block(const int block, int rows, const float* __restrict__ db_partial, int d_out,
                                                 float* __restrict__ db)
 {
-    __shared__ float part[4][64];
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    const int n = block * 64 + tx;
+    __shared__ float part[TPB / DB_COLS][DB_COLS];
+    constexpr int G = TPB / DB_COLS;
+    const int tx = threadIdx.x % DB_COLS, g = threadIdx.x / DB_COLS;
+    const int n = block * DB_COLS + tx;
     const int all_tiles = (rows + 63) / 64;
     const int tiles = all_tiles < (int)DN_DZ_MAX_ROW_BLOCKS ? all_tiles : (int)DN_DZ_MAX_ROW_BLOCKS;   // partial sums the dZ kernel wrote
-    float s0 = 0.f, s1 = 0.f;
-    if (n < d_out) {
-        int t = ty;
-        for (; t + 4 < tiles; t += 8) {
-            s0 += db_partial[(int64_t)t * d_out + n];
-            s1 += db_partial[(int64_t)(t + 4) * d_out + n];
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (n < d_out && tiles > 0) {
+        for (int t = g; t < tiles; t += 8 * G) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = db_partial[(int64_t)min(t + G * u, tiles - 1) * d_out + n];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc[u] += (t + G * u < tiles) ? v[u] : 0.f;
         }
-        if (t < tiles) s0 += db_partial[(int64_t)t * d_out + n];
     }
-    part[ty][tx] = s0 + s1;
+    part[g][tx] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
     __syncthreads();
-    if (ty == 0 && n < d_out) db[n] = (part[0][tx] + part[1][tx]) + (part[2][tx] + part[3][tx]);
+    if (g == 0 && n < d_out) {
+        float s = 0.f;
+#pragma unroll
+        for (int j = 0; j < G; ++j) s += part[j][tx];
+        db[n] = s;
+    }
 }
 
 // All reductions of the backward pass in one launch: each layer owns workgroups [begin[y], begin[y+1]); the
@@ -437,8 +457,8 @@ int dn_gemm_dw_all(const dn_model* m, const dn_batch* b, float* const* dws, floa
         R.xterms[y] = L.xterms;
         R.d_in[y] = L.d_in; R.d_out[y] = L.d_out; R.layer[y] = i;
         R.dws[y] = dws[y]; R.dwn[y] = dwn[y]; R.db[y] = dbias[y]; R.db_partial[y] = L.db_partial;
-        R.dw_blocks[y] = (2 * L.d_in * L.d_out + TPB - 1) / TPB;
-        R.db_blocks[y] = (L.d_out + 63) / 64;
+        R.dw_blocks[y] = (2 * L.d_in * L.d_out + 63) / 64;
+        R.db_blocks[y] = (L.d_out + DB_COLS - 1) / DB_COLS;
         R.begin[y] = red_blocks;
         red_blocks += R.dw_blocks[y] + R.db_blocks[y];
     }
