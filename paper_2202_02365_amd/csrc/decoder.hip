@@ -346,7 +346,7 @@ __device__ __forceinline__ void hist_add_wave(int32_t* __restrict__ hist, int di
 __global__ __launch_bounds__(TPB_) void k_dm_node_index_init(const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
                                                              const int32_t* __restrict__ neg, int B, int n_neg, int n_rows,
                                                              int32_t* __restrict__ key, int32_t* __restrict__ val,
-                                                             int radix_bits, int nblocks, int32_t* __restrict__ hist,
+                                                             int radix_bits, int32_t* __restrict__ hist,
                                                              int32_t* __restrict__ hdr)
 {
     const int radix_mask = (1 << radix_bits) - 1;
@@ -357,14 +357,14 @@ __global__ __launch_bounds__(TPB_) void k_dm_node_index_init(const int32_t* __re
         if ((unsigned)kv >= (unsigned)n_rows) kv = n_rows;
         key[i] = kv;
         val[i] = i;
-        if (hist) hist_add_wave(hist, kv & radix_mask, radix_bits, nblocks, i / DN_SORT_TILE);
+        if (hist) hist_add_wave(hist, kv & radix_mask, radix_bits, dn_sort_tiles(total), i / DN_SORT_TILE);
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) hdr[DM_HDR_NODE_COUNT] = total;
 }
 
 __global__ __launch_bounds__(TPB_) void k_dm_rel_index_init(const int32_t* __restrict__ rel, int B, int num_rel,
                                                             int32_t* __restrict__ key, int32_t* __restrict__ val,
-                                                            int radix_bits, int nblocks, int32_t* __restrict__ hist,
+                                                            int radix_bits, int32_t* __restrict__ hist,
                                                             int32_t* __restrict__ hdr)
 {
     const int radix_mask = (1 << radix_bits) - 1;
@@ -374,7 +374,7 @@ __global__ __launch_bounds__(TPB_) void k_dm_rel_index_init(const int32_t* __res
         if ((unsigned)kv >= (unsigned)num_rel) kv = num_rel;
         key[i] = kv;
         val[i] = i;
-        if (hist) hist_add_wave(hist, kv & radix_mask, radix_bits, nblocks, i / DN_SORT_TILE);
+        if (hist) hist_add_wave(hist, kv & radix_mask, radix_bits, dn_sort_tiles(B), i / DN_SORT_TILE);
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) hdr[DM_HDR_REL_COUNT] = B;
 }
@@ -749,7 +749,7 @@ int distmult_backward(dn_decoder* d, float* d_dH, int64_t ld_dh, float* d_dR, in
         if (gb < 1) gb = 1;
         const int srcbuf = d->nplan.passes & 1;
         hipLaunchKernelGGL(k_dm_node_index_init, dim3(gb), dim3(TPB_), 0, st, d->src, d->dst, d->neg, B, n_neg, n_rows,
-                           d->nkey[srcbuf], d->nval[srcbuf], d->nplan.bits, d->nplan.nblocks,
+                           d->nkey[srcbuf], d->nval[srcbuf], d->nplan.bits,
                            dn_sort_counts_separately(d->nplan) ? nullptr : d->nhist, d->hdr);
         DN_LAUNCH_CHECK("k_dm_node_index_init");
         const int rc = dn_sort_pairs_run(d->nplan, d->hdr + DM_HDR_NODE_COUNT, d->nkey, d->nval, d->nhist, nullptr, n_rows,
@@ -774,7 +774,7 @@ int distmult_backward(dn_decoder* d, float* d_dH, int64_t ld_dh, float* d_dR, in
         if (gb < 1) gb = 1;
         const int srcbuf = d->rplan.passes & 1;
         hipLaunchKernelGGL(k_dm_rel_index_init, dim3(gb), dim3(TPB_), 0, st, d->rel, B, (int)d->num_rel, d->rkey[srcbuf],
-                           d->rval[srcbuf], d->rplan.bits, d->rplan.nblocks, dn_sort_counts_separately(d->rplan) ? nullptr : d->rhist,
+                           d->rval[srcbuf], d->rplan.bits, dn_sort_counts_separately(d->rplan) ? nullptr : d->rhist,
                            d->hdr);
         DN_LAUNCH_CHECK("k_dm_rel_index_init");
         const int rc = dn_sort_pairs_run(d->rplan, d->hdr + DM_HDR_REL_COUNT, d->rkey, d->rval, d->rhist, nullptr, d->num_rel,

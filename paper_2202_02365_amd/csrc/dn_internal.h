@@ -174,8 +174,12 @@ int64_t dn_transpose_index_hist_words(const dn_batch* b);
 
 // Stable radix sort of (key, value) pairs whose count lives in device memory (transpose_index.hip).
 // The caller's own kernel writes the pairs into key[passes & 1] / val[passes & 1] and counts, per
-// tile of DN_SORT_TILE consecutive pairs, the first digit: hist[(key & ((1 << bits) - 1)) * nblocks + i / DN_SORT_TILE]++.
+// tile of DN_SORT_TILE consecutive pairs, the first digit:
+//   hist[(key & ((1 << bits) - 1)) * dn_sort_tiles(count) + i / DN_SORT_TILE]++.
+// The histograms' rows are as long as the tiles in use, not as the capacity: scans and clears touch what a
+// mini-batch fills.
 constexpr int DN_SORT_TILE = 2048;
+__host__ __device__ inline int dn_sort_tiles(int count) { return count > 0 ? (count + DN_SORT_TILE - 1) / DN_SORT_TILE : 1; }
 struct dn_sort_plan { int passes, bits, nblocks, total, sblocks; };
 dn_sort_plan dn_sort_make_plan(int64_t key_range, int64_t cap_items);
 int64_t dn_sort_hist_words(const dn_sort_plan& p);

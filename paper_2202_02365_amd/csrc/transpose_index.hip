@@ -5,13 +5,13 @@
 // 11 bits per pass (two passes for up to 4M positions); group boundaries by binary search.
 // The number of pairs lives in device memory; grids are sized by capacity.
 //
-// Launches: k_tr_init (copy + histogram of the first digit), then per pass two scan kernels and
-// one scatter that also histograms the next digit at the element's new position, then k_tr_ptr.
-// Histograms are integer atomics (order-independent).  Two histogram buffers alternate: pass p scans
-// buffer p % 2 and its scan clears the other one, into which the scatter then counts the next
-// digit.  Buffer 0 is zero on entry and zero again on exit (k_tr_ptr clears it when the number of
-// passes is odd), so a build depends on no host-side state and can be replayed from a HIP graph
-// in any order.
+// Launches: k_tr_init (copy + histogram of the first digit), then per pass a scan of the histogram (one kernel
+// while the histogram is small, block sums + look-behind otherwise) and one scatter that also histograms the next
+// digit at the element's new position, then k_tr_ptr.  Histograms are integer atomics (order-independent); their
+// rows are as long as the tiles in use.  Two buffers of counts alternate: pass p scans buffer p % 2 into a
+// buffer of offsets, and its scatter counts the next digit into the other one and clears the one just scanned.
+// Both are zero on entry and zero again on exit, so a build depends on no host-side state and can be replayed
+// from a HIP graph in any order.
 #include "dn_internal.h"
 
 namespace {
@@ -25,8 +25,7 @@ constexpr int MAX_RADIX = 1 << MAX_BITS;
 
 __global__ void k_tr_init(int32_t* __restrict__ hdr, int need_all, int k, const int32_t* __restrict__ nbr_offsets,
                           const int32_t* __restrict__ repr_map, int32_t* __restrict__ key, int32_t* __restrict__ val,
-                          int radix_mask, int nblocks, int32_t* __restrict__ hist, int32_t* __restrict__ tr_long,
-                          int long_words)
+                          int radix_mask, int32_t* __restrict__ hist, int32_t* __restrict__ tr_long, int long_words)
 {
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < long_words; i += gridDim.x * blockDim.x) tr_long[i] = 0;
     const int E = hdr[HDR_E];
@@ -36,6 +35,7 @@ __global__ void k_tr_init(int32_t* __restrict__ hdr, int need_all, int k, const 
         first = k >= 2 ? nbr_offsets[hdr[HDR_NODE_OFF + 2] - hdr[HDR_NODE_OFF + 1]] : E;
     }
     const int cnt = E - first;
+    const int nblocks = dn_sort_tiles(cnt);
     const int stride = gridDim.x * blockDim.x;
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < cnt; i += stride) {
         const int kv = repr_map[first + i];
@@ -53,11 +53,12 @@ __global__ void k_tr_init(int32_t* __restrict__ hdr, int need_all, int k, const 
 // fused counting, one per pair at scattered addresses, cost more than a pass over the keys): a workgroup counts a
 // tile's digits in LDS and stores the tile's column of the histogram.
 __global__ __launch_bounds__(TPB) void k_radix_hist(const int32_t* __restrict__ count_ptr, const int32_t* __restrict__ key,
-                                                    int shift, int bits, int nblocks, int32_t* __restrict__ hist)
+                                                    int shift, int bits, int32_t* __restrict__ hist)
 {
     __shared__ int cnt[MAX_RADIX];
     const int radix = 1 << bits;
     const int n = *count_ptr;
+    const int nblocks = dn_sort_tiles(n);
     for (int tile = blockIdx.x; tile * TILE < n; tile += gridDim.x) {
         for (int d = threadIdx.x; d < radix; d += TPB) cnt[d] = 0;
         __syncthreads();
@@ -70,10 +71,14 @@ __global__ __launch_bounds__(TPB) void k_radix_hist(const int32_t* __restrict__ 
     }
 }
 
-// two-kernel exclusive scan of `total` ints in place (block partial sums, then look-behind)
-__global__ __launch_bounds__(TPB) void k_scan_partial(const int32_t* __restrict__ data, int total, int32_t* __restrict__ part)
+// two-kernel exclusive scan in place (block partial sums, then look-behind) of the histogram rows in use:
+// radix x dn_sort_tiles(count) ints; workgroups past them have nothing to do
+__global__ __launch_bounds__(TPB) void k_scan_partial(const int32_t* __restrict__ data, const int32_t* __restrict__ count_ptr,
+                                                      int radix, int32_t* __restrict__ part)
 {
     __shared__ int sm[TPB / 64];
+    const int total = radix * dn_sort_tiles(*count_ptr);
+    if ((int)blockIdx.x * TILE >= total) return;
     const int base = blockIdx.x * TILE + threadIdx.x * ITEMS;
     int s = 0;
     for (int e = 0; e < ITEMS; ++e) if (base + e < total) s += data[base + e];
@@ -83,22 +88,11 @@ __global__ __launch_bounds__(TPB) void k_scan_partial(const int32_t* __restrict_
     if (threadIdx.x == 0) part[blockIdx.x] = sm[0] + sm[1] + sm[2] + sm[3];
 }
 
-// second half of the scan; also zeroes `clear` (same extent), the buffer of the next accumulation
-__global__ __launch_bounds__(TPB) void k_scan_apply(int32_t* __restrict__ data, int total, const int32_t* __restrict__ part,
-                                                    int32_t* __restrict__ clear)
+// The exclusive scan of block `blockIdx.x`'s TILE ints, given the sum of everything before them; the offsets
+// go to `out` (the counts stay, for the scatter to clear).
+__device__ __forceinline__ void scan_tile(const int32_t* __restrict__ data, int total, int before, int32_t* __restrict__ out,
+                                          int* sm)
 {
-    __shared__ int sm[TPB / 64];
-    __shared__ int s_before;
-    // sum of the partials of all earlier blocks
-    int acc = 0;
-    for (int i = threadIdx.x; i < (int)blockIdx.x; i += TPB) acc += part[i];
-    for (int d = 32; d > 0; d >>= 1) acc += __shfl_down(acc, d, 64);
-    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = acc;
-    __syncthreads();
-    if (threadIdx.x == 0) s_before = sm[0] + sm[1] + sm[2] + sm[3];
-    __syncthreads();
-    const int before = s_before;
-    // exclusive scan inside the block: per-thread serial over ITEMS, then across threads
     const int base = blockIdx.x * TILE + threadIdx.x * ITEMS;
     int v[ITEMS], s = 0;
     for (int e = 0; e < ITEMS; ++e) { v[e] = (base + e < total) ? data[base + e] : 0; s += v[e]; }
@@ -112,25 +106,76 @@ __global__ __launch_bounds__(TPB) void k_scan_apply(int32_t* __restrict__ data, 
     for (int w = 0; w < wave; ++w) wbase += sm[w];
     int run = before + wbase + incl - s;
     for (int e = 0; e < ITEMS; ++e) {
-        if (base + e < total) { data[base + e] = run; clear[base + e] = 0; }
+        if (base + e < total) out[base + e] = run;
         run += v[e];
     }
 }
 
+// second half of the two-kernel scan
+__global__ __launch_bounds__(TPB) void k_scan_apply(const int32_t* __restrict__ data, const int32_t* __restrict__ count_ptr,
+                                                    int radix, const int32_t* __restrict__ part, int32_t* __restrict__ out)
+{
+    __shared__ int sm[TPB / 64];
+    __shared__ int s_before;
+    const int total = radix * dn_sort_tiles(*count_ptr);
+    if ((int)blockIdx.x * TILE >= total) return;
+    // sum of the partials of all earlier blocks
+    int acc = 0;
+    for (int i = threadIdx.x; i < (int)blockIdx.x; i += TPB) acc += part[i];
+    for (int d = 32; d > 0; d >>= 1) acc += __shfl_down(acc, d, 64);
+    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) s_before = sm[0] + sm[1] + sm[2] + sm[3];
+    __syncthreads();
+    scan_tile(data, total, s_before, out, sm);
+}
+
+// The scan in one kernel, for histograms of a few hundred tiles at most: every workgroup adds up all the counts
+// before its own tile itself (sixteen-byte loads, eight in flight) instead of waiting for a kernel of partial sums.
+__global__ __launch_bounds__(TPB) void k_scan_single(const int32_t* __restrict__ data, const int32_t* __restrict__ count_ptr,
+                                                     int radix, int32_t* __restrict__ out)
+{
+    __shared__ int sm[TPB / 64];
+    __shared__ int s_before;
+    const int total = radix * dn_sort_tiles(*count_ptr);
+    if ((int)blockIdx.x * TILE >= total) return;
+    const int4* d4 = reinterpret_cast<const int4*>(data);
+    const int quads = (int)blockIdx.x * (TILE / 4);
+    int part8[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int i = threadIdx.x; i < quads; i += 8 * TPB) {
+        int4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = d4[min(i + u * TPB, quads - 1)];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (i + u * TPB < quads) part8[u] += (v[u].x + v[u].y) + (v[u].z + v[u].w);
+    }
+    int acc = ((part8[0] + part8[1]) + (part8[2] + part8[3])) + ((part8[4] + part8[5]) + (part8[6] + part8[7]));
+    for (int d = 32; d > 0; d >>= 1) acc += __shfl_down(acc, d, 64);
+    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) s_before = sm[0] + sm[1] + sm[2] + sm[3];
+    __syncthreads();
+    scan_tile(data, total, s_before, out, sm);
+}
+
 // stable scatter: element order inside a tile is (wave, round, lane); a lane's rank among equal
 // digits of its round comes from one ballot per digit bit, rounds and waves are chained through
-// counters in LDS.  Also counts the next pass's digit at the element's new position.
+// counters in LDS.  Also counts the next pass's digit at the element's new position, and clears the counts
+// that this pass's offsets `hist` were scanned from.
 __global__ __launch_bounds__(TPB) void k_radix_scatter(const int32_t* __restrict__ count_ptr, const int32_t* __restrict__ key_in,
-                                                       const int32_t* __restrict__ val_in, int shift, int bits, int nblocks,
+                                                       const int32_t* __restrict__ val_in, int shift, int bits,
                                                        const int32_t* __restrict__ hist, int32_t* __restrict__ key_out,
                                                        int32_t* __restrict__ val_out, int next_bits,
-                                                       int32_t* __restrict__ next_hist)
+                                                       int32_t* __restrict__ next_hist, int32_t* __restrict__ counts)
 {
     __shared__ int cnt[TPB / 64][MAX_RADIX];
     const int radix = 1 << bits;
     const int n = *count_ptr;
+    const int nblocks = dn_sort_tiles(n);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (blockIdx.x * TILE >= n) return;
+    for (int i = blockIdx.x * TPB + threadIdx.x; i < radix * nblocks; i += nblocks * TPB) counts[i] = 0;   // nblocks workgroups get here
     for (int w = 0; w < TPB / 64; ++w)
         for (int d = threadIdx.x; d < radix; d += TPB) cnt[w][d] = 0;
     __syncthreads();
@@ -155,8 +200,9 @@ __global__ __launch_bounds__(TPB) void k_radix_scatter(const int32_t* __restrict
         }
         peers[r] = ok ? mask : 0ull;
         if (ok && (mask & ((1ull << lane) - 1ull)) == 0) cnt[wave][d] += __popcll(mask);   // lowest lane of each digit
-        __syncthreads();                       // the next round's leader may be another lane
+        __builtin_amdgcn_wave_barrier();       // the next round's leader may be another lane of this wave (the counters are the wave's own)
     }
+    __syncthreads();
     // thread t owns digits t, t+TPB, ...: turn per-wave counts into per-wave start positions
     for (int d = threadIdx.x; d < radix; d += TPB) {
         int g = hist[d * nblocks + blockIdx.x];
@@ -182,19 +228,18 @@ __global__ __launch_bounds__(TPB) void k_radix_scatter(const int32_t* __restrict
                 atomicAdd(&next_hist[((keys[r] >> (shift + bits)) & ((1 << next_bits) - 1)) * nblocks + pos / TILE], 1);
             if (rank == 0) cnt[wave][d] = start + __popcll(mask);
         }
-        __syncthreads();                       // counters are read by every lane of the next round
+        __builtin_amdgcn_wave_barrier();       // counters are read by every lane of the wave's next round
     }
 }
 
-// tr_ptr[p] = first index of sorted keys >= p, for p = 0..N; also leaves histogram buffer 0 zeroed
+// tr_ptr[p] = first index of sorted keys >= p, for p = 0..N
 __global__ __launch_bounds__(TPB) void k_tr_ptr(const int32_t* __restrict__ count_ptr, const int32_t* __restrict__ nkeys_ptr,
                                                 int nkeys_const, const int32_t* __restrict__ key,
-                                                int32_t* __restrict__ tr_ptr, int32_t* __restrict__ clear, int clear_words,
-                                                const int32_t* __restrict__ val, dn_sort_slot_info info)
+                                                int32_t* __restrict__ tr_ptr, const int32_t* __restrict__ val,
+                                                dn_sort_slot_info info)
 {
     const int N = nkeys_ptr ? *nkeys_ptr : nkeys_const, n = *count_ptr;
     const int stride = gridDim.x * TPB;
-    for (int i = blockIdx.x * TPB + threadIdx.x; i < clear_words; i += stride) clear[i] = 0;
     if (info.own_out) {
         for (int t = blockIdx.x * TPB + threadIdx.x; t < n; t += stride) {
             const int q = info.slot_owner[val[t]];
@@ -233,8 +278,13 @@ dn_sort_plan dn_sort_make_plan(int64_t key_range, int64_t cap_items)
 // first kernel then leaves the histogram alone.
 bool dn_sort_counts_separately(const dn_sort_plan& p) { return p.nblocks > 1024; }
 
-// ints of histogram space (two alternating histograms + scan partials); they must start at zero
-int64_t dn_sort_hist_words(const dn_sort_plan& p) { return 2 * (int64_t)p.total + p.sblocks + 64; }
+// ints of histogram space (two alternating histograms of counts, the scanned offsets, scan partials); they must
+// start at zero
+static int64_t hist_stride(const dn_sort_plan& p) { return ((int64_t)p.total + 3) & ~(int64_t)3; }   // 16-byte loads
+int64_t dn_sort_hist_words(const dn_sort_plan& p) { return 3 * hist_stride(p) + p.sblocks + 64; }
+
+// histograms up to this many ints (by capacity) are scanned by one kernel (k_scan_single)
+constexpr int64_t SINGLE_SCAN_MAX = 1 << 19;
 
 // Sorts the pairs that the caller's first kernel left in key[plan.passes & 1] / val[plan.passes & 1]
 // (with the first digit's per-tile counts in hist[0 .. total)) by key, stably; the result is in
@@ -243,44 +293,49 @@ int dn_sort_pairs_run(const dn_sort_plan& pl, const int32_t* count_ptr, int32_t*
                       int32_t* hist_space, const int32_t* nkeys_ptr, int64_t nkeys_cap, int32_t* ptr_out, hipStream_t st,
                       const dn_sort_slot_info* info)
 {
-    int32_t* hist[2] = { hist_space, hist_space + pl.total };
-    int32_t* part = hist_space + 2 * (int64_t)pl.total;
+    int32_t* hist[2] = { hist_space, hist_space + hist_stride(pl) };
+    int32_t* offs = hist_space + 2 * hist_stride(pl);
+    int32_t* part = hist_space + 3 * hist_stride(pl);
+    const bool single = pl.total <= SINGLE_SCAN_MAX;
     int src = pl.passes & 1;                                // so that the last pass lands in buffer 0
     int h = 0;                                              // histogram buffer 0 is zero on entry
     const bool big = dn_sort_counts_separately(pl);
     int hist_grid = pl.nblocks < 4096 ? pl.nblocks : 4096;
     if (big) {
         // the caller's kernel left the first digit uncounted
-        hipLaunchKernelGGL(k_radix_hist, dim3(hist_grid), dim3(TPB), 0, st, count_ptr, key[src], 0, pl.bits, pl.nblocks, hist[0]);
+        hipLaunchKernelGGL(k_radix_hist, dim3(hist_grid), dim3(TPB), 0, st, count_ptr, key[src], 0, pl.bits, hist[0]);
         DN_LAUNCH_CHECK("k_radix_hist");
     }
     for (int p = 0; p < pl.passes; ++p) {
         const int shift = pl.bits * p;
         const int hn = h ^ 1;
-        hipLaunchKernelGGL(k_scan_partial, dim3(pl.sblocks), dim3(TPB), 0, st, hist[h], pl.total, part);
-        DN_LAUNCH_CHECK("k_scan_partial");
-        hipLaunchKernelGGL(k_scan_apply, dim3(pl.sblocks), dim3(TPB), 0, st, hist[h], pl.total, part, hist[hn]);
-        DN_LAUNCH_CHECK("k_scan_apply");
+        if (single) {
+            hipLaunchKernelGGL(k_scan_single, dim3(pl.sblocks), dim3(TPB), 0, st, hist[h], count_ptr, 1 << pl.bits, offs);
+            DN_LAUNCH_CHECK("k_scan_single");
+        } else {
+            hipLaunchKernelGGL(k_scan_partial, dim3(pl.sblocks), dim3(TPB), 0, st, hist[h], count_ptr, 1 << pl.bits, part);
+            DN_LAUNCH_CHECK("k_scan_partial");
+            hipLaunchKernelGGL(k_scan_apply, dim3(pl.sblocks), dim3(TPB), 0, st, hist[h], count_ptr, 1 << pl.bits, part, offs);
+            DN_LAUNCH_CHECK("k_scan_apply");
+        }
         const int next_bits = (p + 1 < pl.passes) ? pl.bits : 0;
         hipLaunchKernelGGL(k_radix_scatter, dim3(pl.nblocks), dim3(TPB), 0, st, count_ptr, key[src], val[src],
-                           shift, pl.bits, pl.nblocks, hist[h], key[src ^ 1], val[src ^ 1], big ? 0 : next_bits, hist[hn]);
+                           shift, pl.bits, offs, key[src ^ 1], val[src ^ 1], big ? 0 : next_bits, hist[hn], hist[h]);
         DN_LAUNCH_CHECK("k_radix_scatter");
         if (big && next_bits > 0) {
             hipLaunchKernelGGL(k_radix_hist, dim3(hist_grid), dim3(TPB), 0, st, count_ptr, key[src ^ 1], shift + pl.bits, pl.bits,
-                               pl.nblocks, hist[hn]);
+                               hist[hn]);
             DN_LAUNCH_CHECK("k_radix_hist");
         }
         src ^= 1;
         h = hn;
     }
-    // after the last pass the buffer it scanned holds offsets and the other one is zero: buffer 0 needs clearing
-    // exactly when the number of passes is odd
     int64_t gp = (nkeys_cap + 1 + TPB - 1) / TPB;
     if (gp > 2048) gp = 2048;
     dn_sort_slot_info si = { nullptr, nullptr, nullptr, nullptr, nullptr };
     if (info) si = *info;
     hipLaunchKernelGGL(k_tr_ptr, dim3((int)gp), dim3(TPB), 0, st, count_ptr, nkeys_ptr, (int)nkeys_cap, key[0], ptr_out,
-                       hist[0], (pl.passes & 1) ? pl.total : 0, val[0], si);
+                       val[0], si);
     DN_LAUNCH_CHECK("k_tr_ptr");
     return DN_OK;
 }
@@ -301,7 +356,7 @@ int dn_launch_transpose_index(dn_batch* b, int need_all, hipStream_t st)
     if (g < 1) g = 1;
     const int src = pl.passes & 1;
     hipLaunchKernelGGL(k_tr_init, dim3((int)g), dim3(TPB), 0, st, b->hdr, need_all, b->k, b->nbr_offsets, b->repr_map,
-                       b->tr_key[src], b->tr_val[src], (1 << pl.bits) - 1, pl.nblocks,
+                       b->tr_key[src], b->tr_val[src], (1 << pl.bits) - 1,
                        dn_sort_counts_separately(pl) ? nullptr : b->tr_hist, b->tr_long,
                        (int)b->tr_long_words);
     DN_LAUNCH_CHECK("k_tr_init");
