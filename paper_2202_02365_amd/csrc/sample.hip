@@ -241,13 +241,14 @@ __global__ __launch_bounds__(TPB) void k_sample(GraphDev g, int hop, int f, int 
                 lvl_nbrs[o + s] = u;
                 lvl_owner[o + s] = p;
                 const uint32_t w = (uint32_t)u >> 5, bit = 1u << (u & 31);
-                // relaxed device-scope load first: hubs are claimed once and then only read
+                // relaxed device-scope load first: hubs are claimed once and then only read.  A clear bit means the
+                // node is in no earlier level (those kernels are complete), so it is new at this hop whichever lane
+                // marks it first: every lane that sees it clear marks `seen` and `fresh` without waiting for the
+                // former's result (the bitmaps end the same, one dependent round trip less).
                 if (!(__hip_atomic_load(&seen[w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & bit)) {
-                    const uint32_t old = atomicOr(&seen[w], bit);
-                    if (!(old & bit)) {
-                        const uint32_t old_word = atomicOr(&fresh[w], bit);
-                        if (old_word == 0) atomicOr(&summary[w >> 5], 1u << (w & 31));
-                    }
+                    atomicOr(&seen[w], bit);
+                    const uint32_t old_word = atomicOr(&fresh[w], bit);
+                    if (old_word == 0) atomicOr(&summary[w >> 5], 1u << (w & 31));
                 }
             }
             o += c;
