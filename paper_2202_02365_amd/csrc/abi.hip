@@ -53,8 +53,8 @@ int fill_batch_caps(dn_batch* b, int64_t V, int32_t max_targets, int32_t k, cons
 void carve_batch(dn_batch* b, Carver& c)
 {
     b->hdr = c.take<int32_t>(DN_HDR_WORDS);
-    b->seen = c.take<uint32_t>(b->words0);
-    b->fresh = c.take<uint32_t>(b->words0);
+    b->seen = c.take<uint32_t>(2 * b->words0);     // word pairs (seen, fresh), see sample.hip
+    b->fresh = b->seen + 1;
     b->summary = c.take<uint32_t>(b->words1);
     b->tr_hist_words = dn_transpose_index_hist_words(b);
     b->tr_hist = c.take<int32_t>(b->tr_hist_words);          // starts at zero like the bitmaps

@@ -18,6 +18,9 @@
 #include "dn_internal.h"
 
 namespace {
+// `seen` and `fresh` are interleaved: word w of `seen` and word w of `fresh` are the two halves of one aligned
+// 8-byte pair (fresh = seen + 1), so that the sampling kernel marks a node in both with one atomic.
+#define BM(w) (2 * (int64_t)(w))
 
 constexpr int TPB = 256;
 
@@ -119,7 +122,7 @@ __global__ __launch_bounds__(TPB) void k_init_targets(GraphDev g, int64_t V, con
             lvl_ids[i] = 0;
         } else {
             const uint32_t bit = 1u << (t & 31);
-            const uint32_t old = atomicOr(&seen[t >> 5], bit);
+            const uint32_t old = atomicOr(&seen[BM(t >> 5)], bit);
             if (old & bit) atomicOr(&hdr[HDR_STATUS_ACC], ST_DUP_TARGET);
             lvl_ids[i] = t;
             lvlpos[t] = i;
@@ -167,8 +170,8 @@ __global__ __launch_bounds__(TPB) void k_mark_ids(int64_t V, const int32_t* __re
         const int u = i < na ? a[i] : (i < na + nb ? b[i - na] : c[i - na - nb]);
         if (u < 0 || (int64_t)u >= V) { atomicOr(&hdr[HDR_STATUS_ACC], ST_BAD_TARGET); continue; }
         const uint32_t w = (uint32_t)u >> 5, bit = 1u << (u & 31);
-        if (!(__hip_atomic_load(&fresh[w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & bit)) {
-            const uint32_t old_word = atomicOr(&fresh[w], bit);
+        if (!(__hip_atomic_load(&fresh[BM(w)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & bit)) {
+            const uint32_t old_word = atomicOr(&fresh[BM(w)], bit);
             if (old_word == 0) atomicOr(&summary[w >> 5], 1u << (w & 31));
         }
     }
@@ -243,11 +246,12 @@ __global__ __launch_bounds__(TPB) void k_sample(GraphDev g, int hop, int f, int 
                 const uint32_t w = (uint32_t)u >> 5, bit = 1u << (u & 31);
                 // relaxed device-scope load first: hubs are claimed once and then only read.  A clear bit means the
                 // node is in no earlier level (those kernels are complete), so it is new at this hop whichever lane
-                // marks it first: every lane that sees it clear marks `seen` and `fresh` without waiting for the
-                // former's result (the bitmaps end the same, one dependent round trip less).
-                if (!(__hip_atomic_load(&seen[w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & bit)) {
-                    atomicOr(&seen[w], bit);
-                    const uint32_t old_word = atomicOr(&fresh[w], bit);
+                // marks it first: every lane that sees it clear marks it in `seen` and in `fresh` with one 64-bit
+                // atomic on the pair of words (the bitmaps end the same whoever comes first).
+                if (!(__hip_atomic_load(&seen[BM(w)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & bit)) {
+                    const unsigned long long both = (unsigned long long)bit | ((unsigned long long)bit << 32);
+                    const unsigned long long old_pair = atomicOr(reinterpret_cast<unsigned long long*>(&seen[BM(w)]), both);
+                    const uint32_t old_word = (uint32_t)(old_pair >> 32);
                     if (old_word == 0) atomicOr(&summary[w >> 5], 1u << (w & 31));
                 }
             }
@@ -273,7 +277,7 @@ __global__ __launch_bounds__(TPB) void k_fresh_count(GraphDev g, int64_t words1,
             const int b = __ffs(sw) - 1;
             sw &= sw - 1;
             const int64_t w = i * 32 + b;
-            uint32_t fw = fresh[w];
+            uint32_t fw = fresh[BM(w)];
             nodes += __popc(fw);
             if (f_next > 0) {
                 while (fw) {
@@ -309,7 +313,7 @@ __global__ __launch_bounds__(TPB) void k_fresh_emit(GraphDev g, int64_t words1, 
             const int b = __ffs(sw) - 1;
             sw &= sw - 1;
             const int64_t w = i * 32 + b;
-            uint32_t fw = fresh[w];
+            uint32_t fw = fresh[BM(w)];
             nodes += __popc(fw);
             if (f_next > 0) {
                 while (fw) {
@@ -331,9 +335,9 @@ __global__ __launch_bounds__(TPB) void k_fresh_emit(GraphDev g, int64_t words1, 
         const int b = __ffs(sw) - 1;
         sw &= sw - 1;
         const int64_t w = i * 32 + b;
-        uint32_t fw = fresh[w];
-        fresh[w] = 0;
-        if (seen_or_null) seen_or_null[w] = fw;          // level 0 from an id set: these nodes are the targets
+        uint32_t fw = fresh[BM(w)];
+        fresh[BM(w)] = 0;
+        if (seen_or_null) seen_or_null[BM(w)] = fw;          // level 0 from an id set: these nodes are the targets
         while (fw) {
             const int bit = __ffs(fw) - 1;
             fw &= fw - 1;
@@ -394,7 +398,7 @@ __global__ __launch_bounds__(TPB) void k_assemble(int k, int32_t* __restrict__ h
         const int fp = N - lvl_off[h + 1] + (p - lvl_off[h]);
         const int u = lvl_ids[p];
         node_ids[fp] = u;
-        seen[(uint32_t)u >> 5] = 0;                          // leave the bitmap clean for the next batch
+        seen[BM((uint32_t)u >> 5)] = 0;                          // leave the bitmap clean for the next batch
         if (h < k)
             nbr_offsets[fp - off1] = E - nbr_off[h + 1] + (lvl_nbr_offsets[p] - nbr_off[h]);
     }
