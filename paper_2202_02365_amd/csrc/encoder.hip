@@ -55,9 +55,12 @@ __global__ __launch_bounds__(TPB) void k_aggregate(const int32_t* __restrict__ h
             const int c0 = (it * LANES + lane) * V;
             const bool col_ok = c0 < d;
             const int cc = col_ok ? c0 : 0;                        // lanes beyond the row read its first columns and drop them
-            float acc[V];
+            float acc[V], sv[V];
 #pragma unroll
             for (int e = 0; e < V; ++e) acc[e] = 0.f;
+            // the row's own values are fetched now, so that their latency overlaps the walk over the slots
+#pragma unroll
+            for (int e = 0; e < V; ++e) sv[e] = load_elem(self + cc + e);
             // The group's lanes fetch the slots' row numbers side by side and hand them round by shuffles, so that the
             // row loads of up to eight slots are in flight at once; the additions keep the ascending slot order.
             for (int base = beg; base < end; base += LANES) {
@@ -86,14 +89,13 @@ __global__ __launch_bounds__(TPB) void k_aggregate(const int32_t* __restrict__ h
 #pragma unroll
             for (int e = 0; e < V; ++e) {
                 const float mean = end > beg ? (mean_agg ? acc[e] / cnt_f : acc[e]) : 0.f;
-                const float sv = load_elem(self + c0 + e);
-                const uint16_t s_hi = f32_to_bf16(sv), m_hi = f32_to_bf16(mean);
+                const uint16_t s_hi = f32_to_bf16(sv[e]), m_hi = f32_to_bf16(mean);
                 xrow[c0 + e] = s_hi;
                 xrow[d + c0 + e] = m_hi;
                 const float s_hf = bf16_to_f32(s_hi), m_hf = bf16_to_f32(m_hi);
                 sq += s_hf * s_hf + m_hf * m_hf;
                 if (TERMS == 2) {
-                    const uint16_t s_lo = f32_to_bf16(sv - s_hf), m_lo = f32_to_bf16(mean - m_hf);
+                    const uint16_t s_lo = f32_to_bf16(sv[e] - s_hf), m_lo = f32_to_bf16(mean - m_hf);
                     xrow[2 * d + c0 + e] = s_lo;
                     xrow[3 * d + c0 + e] = m_lo;
                     const float s_lf = bf16_to_f32(s_lo), m_lf = bf16_to_f32(m_lo);
