@@ -364,6 +364,8 @@ def main():
                     help="run that many untimed steps in the two-step form (dense_gather + sage_forward) first, so that a "
                          "profiler sees those kernels too")
     ap.add_argument("--no-graphs", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
+    ap.add_argument("--replica-graphs", action="store_true",
+                    help="replicas replay one HIP graph per step instead of launching every kernel from the host")
     ap.add_argument("--replicas", type=int, default=4,
                     help="data-parallel replicas on one GPU: that many mini-batches run the whole path concurrently, "
                          "each on a HIP stream of its own (0 = skip this measurement)")
@@ -550,6 +552,27 @@ def main():
                              dbs=[torch.empty_like(x) for x in bias],
                              dh0=None if dh0 is None else torch.empty_like(dh0), stream=torch.cuda.Stream()))
 
+        def one_step(o, bi):
+            dn.dense_sample(o["batch"], graph, targets[bi], bi)
+            gather(o["batch"], o["h0"])
+            forward(o["model"], o["batch"], o["h0"], o["out"])
+            if backward:
+                loss_and_backward(o["model"], o["batch"], o["out"], o["gout"], o["loss"], o["dws"], o["dwn"], o["dbs"], o["dh0"])
+
+        rep_graphs = {}
+        if args.replica_graphs:
+            # one HIP graph per (replica, batch it runs): the host then hands over a whole step with one call
+            assert N_BATCHES % n_rep == 0
+            for bi in range(N_BATCHES):
+                o = reps[bi % n_rep]
+                one_step(o, bi)                              # eager once (lazy initialisation stays out of the capture)
+                torch.cuda.synchronize()
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=o["stream"]):
+                    one_step(o, bi)
+                rep_graphs[bi] = g
+            torch.cuda.synchronize()
+
         def run(n):
             torch.cuda.synchronize()
             t0 = time.perf_counter()
@@ -557,13 +580,16 @@ def main():
                 o = reps[s % n_rep]
                 bi = s % N_BATCHES
                 with torch.cuda.stream(o["stream"]):
-                    dn.dense_sample(o["batch"], graph, targets[bi], bi)
-                    gather(o["batch"], o["h0"])
-                    forward(o["model"], o["batch"], o["h0"], o["out"])
-                    if backward:
-                        loss_and_backward(o["model"], o["batch"], o["out"], o["gout"], o["loss"], o["dws"], o["dwn"], o["dbs"], o["dh0"])
+                    if rep_graphs:
+                        rep_graphs[bi].replay()
+                    else:
+                        one_step(o, bi)
+            queued = time.perf_counter() - t0               # the host has handed over every launch
             torch.cuda.synchronize()
-            return time.perf_counter() - t0
+            spent = time.perf_counter() - t0
+            log("%d replicas, %s: host queued %d steps in %.3f ms/step, GPU finished them in %.3f ms/step" %
+                (n_rep, "whole step" if backward else "forward only", n, 1e3 * queued / n, 1e3 * spent / n))
+            return spent
         run(max(args.warmup, n_rep))
         spent = run(n_steps)
         if backward:
