@@ -269,6 +269,7 @@ def run_link_prediction(args, cfg):
         dn.profile_enable(False)
         del delay_src, delay_dst
         empty_ms, empty_n = prof.pop("empty_bracket", (0.0, 1))
+        noop_ms, noop_n = prof.pop("noop_kernel_bracket", (0.0, 1))
         bracket_us = 1e3 * empty_ms / max(empty_n, 1)
         kernels = {tag: {"avg_us": max(1e3 * ms / n - bracket_us, 0.0), "launches_per_step": n / steps}
                    for tag, (ms, n) in prof.items()}
@@ -291,7 +292,10 @@ def run_link_prediction(args, cfg):
             roofline = {"kernel": tag, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
                         "frac": achieved / peak, "traffic": measured_traffic(cfg.name, tag), "avg_us": avg_us,
                         "algorithmic_per_launch": work, "kernel_time_share_of_step": best[0] / step_sum_us,
-                        "event_bracket_overhead_us_subtracted": bracket_us}
+                        "event_bracket_overhead_us_subtracted": bracket_us,
+                        # a bracket around a kernel that does nothing reads this much more than an empty one: the latency
+                        # of a launch as such, still contained in avg_us (rocprofv3's own durations do not contain it)
+                        "launch_latency_us_not_subtracted": max(1e3 * noop_ms / max(noop_n, 1) - bracket_us, 0.0)}
 
     baseline = None
     if not args.no_cpu_baseline:
@@ -690,6 +694,7 @@ def main():
         del delay_src, delay_dst
         # an event pair around nothing already reads a few microseconds: subtract that from every bracket
         empty_ms, empty_n = prof.pop("empty_bracket", (0.0, 1))
+        noop_ms, noop_n = prof.pop("noop_kernel_bracket", (0.0, 1))
         bracket_us = 1e3 * empty_ms / max(empty_n, 1)
         kernels = {tag: {"avg_us": max(1e3 * ms / n - bracket_us, 0.0), "launches_per_step": n / args.steps}
                    for tag, (ms, n) in prof.items()}
@@ -730,7 +735,10 @@ def main():
             roofline = {"kernel": tag, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
                         "frac": achieved / peak, "traffic": measured_traffic(cfg.name, tag), "avg_us": avg_us,
                         "algorithmic_per_launch": work, "kernel_time_share_of_step": best[0] / step_sum_us,
-                        "event_bracket_overhead_us_subtracted": bracket_us}
+                        "event_bracket_overhead_us_subtracted": bracket_us,
+                        # a bracket around a kernel that does nothing reads this much more than an empty one: the latency
+                        # of a launch as such, still contained in avg_us (rocprofv3's own durations do not contain it)
+                        "launch_latency_us_not_subtracted": max(1e3 * noop_ms / max(noop_n, 1) - bracket_us, 0.0)}
 
     if args.copy_calibration:
         src = torch.empty(64 << 20, dtype=torch.float32, device=dev).normal_()

@@ -276,7 +276,9 @@ DN_API int  dn_profile_enable(int32_t enable);
  * 16-byte aligned pointers): the known-size reference that hardware byte counters are scaled by. */
 DN_API int  dn_profile_calibration_copy(void* d_dst, const void* d_src, size_t bytes, void* stream);
 /* Records an event pair with nothing in between under the tag "empty_bracket": what a bracket costs by
- * itself, to be subtracted from the per-kernel averages. */
+ * itself, to be subtracted from the per-kernel averages; then a pair around a one-wave kernel that does
+ * nothing under the tag "noop_kernel_bracket": the difference is the latency of a launch as such, which every
+ * bracketed kernel's figure still contains. */
 DN_API int  dn_profile_empty_bracket(void* stream);
 DN_API int  dn_profile_collect(dn_kernel_time* out, int32_t max_entries, int32_t* n_entries);
 

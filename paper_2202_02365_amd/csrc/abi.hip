@@ -507,9 +507,16 @@ int dn_profile_calibration_copy(void* d_dst, const void* d_src, size_t bytes, vo
     return dn_launch_calibration_copy(d_dst, d_src, bytes, static_cast<hipStream_t>(stream));
 }
 
+__global__ void k_noop() {}
+
 int dn_profile_empty_bracket(void* stream)
 {
-    dn_prof_scope ps("empty_bracket", 0, static_cast<hipStream_t>(stream));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    { dn_prof_scope ps("empty_bracket", 0, st); }
+    { dn_prof_scope ps("noop_kernel_bracket", 0, st);
+    hipLaunchKernelGGL(k_noop, dim3(1), dim3(64), 0, st);
+    }
+    DN_LAUNCH_CHECK("k_noop");
     return DN_OK;
 }
 
