@@ -232,13 +232,16 @@ __global__ __launch_bounds__(TPB) void k_radix_scatter(const int32_t* __restrict
     }
 }
 
-// tr_ptr[p] = first index of sorted keys >= p, for p = 0..N
+// tr_ptr[p] = first index of sorted keys >= p, for p = 0..N: a binary search inside the range of p's most
+// significant digit, whose bounds the last pass's offsets give (offs[d * tiles] = first sorted index of digit d)
 __global__ __launch_bounds__(TPB) void k_tr_ptr(const int32_t* __restrict__ count_ptr, const int32_t* __restrict__ nkeys_ptr,
                                                 int nkeys_const, const int32_t* __restrict__ key,
                                                 int32_t* __restrict__ tr_ptr, const int32_t* __restrict__ val,
+                                                const int32_t* __restrict__ offs, int top_shift, int top_radix,
                                                 dn_sort_slot_info info)
 {
     const int N = nkeys_ptr ? *nkeys_ptr : nkeys_const, n = *count_ptr;
+    const int tiles = dn_sort_tiles(n);
     const int stride = gridDim.x * TPB;
     if (info.own_out) {
         for (int t = blockIdx.x * TPB + threadIdx.x; t < n; t += stride) {
@@ -248,7 +251,12 @@ __global__ __launch_bounds__(TPB) void k_tr_ptr(const int32_t* __restrict__ coun
         }
     }
     for (int p = blockIdx.x * TPB + threadIdx.x; p <= N; p += stride) {
-        int lo = 0, hi = n;
+        const int d = p >> top_shift;
+        int lo = n, hi = n;
+        if (d < top_radix) {
+            lo = offs[(int64_t)d * tiles];
+            if (d + 1 < top_radix) hi = offs[(int64_t)(d + 1) * tiles];
+        }
         while (lo < hi) {
             const int mid = (lo + hi) >> 1;
             if (key[mid] < p) lo = mid + 1; else hi = mid;
@@ -335,7 +343,7 @@ int dn_sort_pairs_run(const dn_sort_plan& pl, const int32_t* count_ptr, int32_t*
     dn_sort_slot_info si = { nullptr, nullptr, nullptr, nullptr, nullptr };
     if (info) si = *info;
     hipLaunchKernelGGL(k_tr_ptr, dim3((int)gp), dim3(TPB), 0, st, count_ptr, nkeys_ptr, (int)nkeys_cap, key[0], ptr_out,
-                       val[0], si);
+                       val[0], offs, pl.bits * (pl.passes - 1), 1 << pl.bits, si);
     DN_LAUNCH_CHECK("k_tr_ptr");
     return DN_OK;
 }
