@@ -75,8 +75,8 @@ def algorithmic_work(tag, sizes, cfg, dims):
             return "mfma", 2.0 * pairs * d
         if tag in ("dm_gemm_dq", "dm_gemm_de"):                  # probabilities enter as two bf16 terms
             return "mfma", 2.0 * pairs * d * 2
-        if tag == "dm_probs":                                    # reads fp32 scores, writes two bf16 terms twice (P and P^T)
-            return "hbm", pairs * (4 + 2 * 2 * 2)
+        if tag == "dm_probs":                                    # the scores again; writes the probabilities as two bf16 terms
+            return "hbm", pairs * 2 * 2
     return "hbm", None
 
 

@@ -246,6 +246,8 @@ DN_API int  sage_backward_sgd(dn_model* m, const dn_batch* b, const float* d_gra
  *
  *      dn_decoder_scores: device pointer and strides (in floats) of the negatives' scores of the last forward,
  *      score of edge e against negative n = d_scores[(e / chunk) * chunk_stride + (e % chunk) * row_stride + n].
+ *      The forward pass does not keep the scores (only each row's log-sum-exp): this call computes them, for both
+ *      sides, asynchronously on `stream` from the operands of the last forward, into the decoder's workspace.
  *      dn_decoder_status WAITS for `stream`.  All other calls are asynchronous on `stream`. */
 typedef struct dn_decoder dn_decoder;
 DN_API int  dn_decoder_workspace_size(int64_t max_edges, int32_t chunk, int32_t num_neg, int32_t dim, int64_t max_rows,
@@ -258,7 +260,7 @@ DN_API int  distmult_forward(dn_decoder* d, const float* d_H, int64_t ldh, int64
                              const int32_t* d_neg, float* d_pos, float* d_loss, void* stream);
 DN_API int  distmult_backward(dn_decoder* d, float* d_dH, int64_t ld_dh, float* d_dR, int64_t ld_dr, void* stream);
 DN_API int  dn_decoder_scores(const dn_decoder* d, int32_t side, const float** d_scores, int64_t* chunk_stride,
-                              int64_t* row_stride);
+                              int64_t* row_stride, void* stream);
 DN_API int  dn_decoder_status(const dn_decoder* d, int32_t* flags, void* stream);
 
 /* ---- per-kernel timing for benchmarks (off by default; not a step of the path).

@@ -83,7 +83,7 @@ def load_library():
         "dn_decoder_destroy": (None, [vp]),
         "distmult_forward": (ctypes.c_int, [vp, vp, i64, i64, vp, i64, vp, vp, vp, i64, vp, vp, vp, vp]),
         "distmult_backward": (ctypes.c_int, [vp, vp, i64, vp, i64, vp]),
-        "dn_decoder_scores": (ctypes.c_int, [vp, i32, pp, ctypes.POINTER(i64), ctypes.POINTER(i64)]),
+        "dn_decoder_scores": (ctypes.c_int, [vp, i32, pp, ctypes.POINTER(i64), ctypes.POINTER(i64), vp]),
         "dn_decoder_status": (ctypes.c_int, [vp, ctypes.POINTER(i32), vp]),
         "sage_forward": (ctypes.c_int, [vp, vp, vp, vp, vp]),
         "sage_forward_table": (ctypes.c_int, [vp, vp, vp, i64, vp, vp]),
@@ -276,9 +276,11 @@ class Decoder:
         return int(f.value)
 
     def scores(self, side: int) -> torch.Tensor:
-        """Negatives' scores of the last forward as a [n_edges x num_neg] view-copy (side 0: corrupted destination)."""
+        """Negatives' scores of the last forward as a [n_edges x num_neg] view-copy (side 0: corrupted destination);
+        the library computes them on this call (the forward pass keeps only each row's log-sum-exp)."""
         ptr, cs, rs = ctypes.c_void_p(), ctypes.c_int64(), ctypes.c_int64()
-        _check(load_library().dn_decoder_scores(self.handle, side, ctypes.byref(ptr), ctypes.byref(cs), ctypes.byref(rs)))
+        _check(load_library().dn_decoder_scores(self.handle, side, ctypes.byref(ptr), ctypes.byref(cs), ctypes.byref(rs),
+                                                _stream()))
         n_chunks = (self._n_edges + self.chunk - 1) // self.chunk
         off = ptr.value - self.workspace.data_ptr()
         flat = self.workspace[off:off + 4 * n_chunks * cs.value].view(torch.float32)

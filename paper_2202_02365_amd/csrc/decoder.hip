@@ -149,9 +149,16 @@ struct DmGemm {
     int ncols;              // columns stored (rows: every row of the tile; C is padded to whole tiles)
     // LSE epilogue: per row and column tile, max and sum of exp(x - max) over the tile's columns below lse_cols
     float* pmax; float* psum; int lse_cols;
+    // probability epilogue: P = exp(x - lse) for valid (edge, negative) pairs, 0 elsewhere, as two bf16 terms
+    const float* lse; int n_edges, n_chunks, chunk, n_neg, npad; uint16_t* P;
 };
 
-template <bool WRAP, bool LSE>
+// What becomes of the tile: stored as it is; reduced to the (max, sum of exp) pairs of its rows (the scores
+// themselves are not kept: whoever needs them again computes them again, which costs less than 0.4 GB of
+// writes and as much of reads); or turned into probabilities with the rows' finished log-sum-exp.
+enum { DM_EPI_STORE = 0, DM_EPI_LSE = 1, DM_EPI_PROBS = 2 };
+
+template <bool WRAP, int EPI>
 __global__ __launch_bounds__(TPB, 2) void k_dm_gemm(DmGemm g)
 {
     const int z = blockIdx.z;
@@ -162,20 +169,45 @@ __global__ __launch_bounds__(TPB, 2) void k_dm_gemm(DmGemm g)
     mainloop<BM, BN, WRAP>(A, g.lda, B, g.ldb, 0, g.kchunks, g.b_wrap_chunks, acc);
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    float* C = g.C + (int64_t)z * g.stride_c;
+    if (EPI == DM_EPI_STORE) {
+        float* C = g.C + (int64_t)z * g.stride_c;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int n = col0 + wn * 64 + j * 32 + (lane & 31);
-            if (n >= g.ncols) continue;
+            for (int j = 0; j < 2; ++j) {
+                const int n = col0 + wn * 64 + j * 32 + (lane & 31);
+                if (n >= g.ncols) continue;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int m = row0 + wm * 64 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                    C[(int64_t)m * g.ldc + n] = acc[i][j][e];
+                }
+            }
+    }
+    if (EPI == DM_EPI_PROBS) {
+        // P[z][m][term * npad + n] (z = side * n_chunks + q), every element of the padded tile written
+        const int side = z / g.n_chunks, q = z % g.n_chunks;
+        uint16_t* Pz = g.P + (int64_t)z * ((int64_t)gridDim.y * BM) * 2 * g.npad;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int m = row0 + wm * 64 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-                C[(int64_t)m * g.ldc + n] = acc[i][j][e];
+                const int64_t edge = (int64_t)q * g.chunk + m;
+                const bool row_ok = m < g.chunk && edge < g.n_edges;
+                const float l = row_ok ? g.lse[(int64_t)side * g.n_edges + edge] : 0.f;
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const int n = col0 + wn * 64 + j * 32 + (lane & 31);
+                    const float pr = (row_ok && n < g.n_neg) ? expf(acc[i][j][e] - l) : 0.f;
+                    const uint16_t hi = f32_to_bf16(pr);
+                    const uint16_t lo = f32_to_bf16(pr - bf16_to_f32(hi));
+                    Pz[(int64_t)m * 2 * g.npad + n] = hi;
+                    Pz[(int64_t)m * 2 * g.npad + g.npad + n] = lo;
+                }
             }
-        }
-    if (LSE) {
+    }
+    if (EPI == DM_EPI_LSE) {
         // per row: max and sum of exp(x - max) over this tile's valid columns.  A row's 128 columns sit in the 32
         // lanes of one half-wave (two registers each) of the two waves wn = 0, 1.  The 16 rows a lane holds
         // (for one i) are reduced over the half-wave by a butterfly that halves the number of rows a lane
@@ -269,28 +301,6 @@ __global__ __launch_bounds__(TPB_) void k_dm_lse(const float* __restrict__ pmax,
     }
     loss[e] = (l[0] - p) + (l[1] - p);
     dpos[e] = (expf(p - l[0]) - 1.f) + (expf(p - l[1]) - 1.f);
-}
-
-// P = exp(S - lse) for valid (edge, negative) pairs, 0 elsewhere, as two bf16 terms, row-major:
-// P[z][i][term*npad + n]  (z = side*C + q).  One thread per element, 64 x 64 tiles.
-__global__ __launch_bounds__(TPB_) void k_dm_probs(const float* __restrict__ S, const float* __restrict__ lse, int B, int C,
-                                                   int chunk, int Nn, int cpad, int npad, uint16_t* __restrict__ P)
-{
-    const int z = blockIdx.z, side = z / C, q = z % C;
-    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    const float* Sz = S + (int64_t)z * cpad * npad;
-    uint16_t* Pz = P + (int64_t)z * cpad * 2 * npad;
-    for (int rr = ty; rr < 64; rr += 4) {
-        const int i = r0 + rr, n = c0 + tx;
-        const int64_t e = (int64_t)q * chunk + i;
-        float p = 0.f;
-        if (i < chunk && e < B && n < Nn) p = expf(Sz[(int64_t)i * npad + n] - lse[(int64_t)side * B + e]);
-        const uint16_t hi = f32_to_bf16(p);
-        const uint16_t lo = f32_to_bf16(p - bf16_to_f32(hi));
-        Pz[(int64_t)i * 2 * npad + n] = hi;
-        Pz[(int64_t)i * 2 * npad + npad + n] = lo;
-    }
 }
 
 // dE[z] = P[z]^T * Q[z]: the contraction runs over the chunk's edges, the row index of both P and Q, so both are
@@ -595,15 +605,31 @@ void carve_decoder(dn_decoder* d, dn_carver& c)
     d->rptr = c.take<int32_t>(d->num_rel + 2);
 }
 
-int launch_gemm(const DmGemm& g, bool wrap, int mtiles, int ntiles, int batch, hipStream_t st, const char* tag)
+int launch_gemm(const DmGemm& g, bool wrap, int epi, int mtiles, int ntiles, int batch, hipStream_t st, const char* tag)
 {
     dn_prof_scope ps(tag, 0, st);
     const dim3 grid(ntiles, mtiles, batch);
-    if (wrap) hipLaunchKernelGGL((k_dm_gemm<true, false>), grid, dim3(TPB), 0, st, g);
-    else if (g.pmax) hipLaunchKernelGGL((k_dm_gemm<false, true>), grid, dim3(TPB), 0, st, g);
-    else hipLaunchKernelGGL((k_dm_gemm<false, false>), grid, dim3(TPB), 0, st, g);
+    if (wrap) hipLaunchKernelGGL((k_dm_gemm<true, DM_EPI_STORE>), grid, dim3(TPB), 0, st, g);
+    else if (epi == DM_EPI_LSE) hipLaunchKernelGGL((k_dm_gemm<false, DM_EPI_LSE>), grid, dim3(TPB), 0, st, g);
+    else if (epi == DM_EPI_PROBS) hipLaunchKernelGGL((k_dm_gemm<false, DM_EPI_PROBS>), grid, dim3(TPB), 0, st, g);
+    else hipLaunchKernelGGL((k_dm_gemm<false, DM_EPI_STORE>), grid, dim3(TPB), 0, st, g);
     DN_LAUNCH_CHECK(tag);
     return DN_OK;
+}
+
+// the score contraction S[z] = Q[z] * E[q]^T of the last forward's operands (they stay until the next forward)
+DmGemm score_gemm(const dn_decoder* d)
+{
+    DmGemm g{};
+    const int C = (int)d->n_chunks;
+    g.A = d->Q; g.lda = d->kp; g.stride_a = (int64_t)d->cpad * d->kp;
+    g.B = d->En; g.ldb = d->kp; g.stride_b = (int64_t)d->npad * d->kp; g.b_mod = C;
+    g.kchunks = d->kp / BK; g.b_wrap_chunks = 1;
+    g.C = d->S; g.ldc = d->npad; g.stride_c = (int64_t)d->cpad * d->npad; g.ncols = d->npad;
+    g.pmax = d->pmax; g.psum = d->psum; g.lse_cols = d->num_neg;
+    g.lse = d->lse; g.n_edges = (int)d->n_edges; g.n_chunks = C; g.chunk = d->chunk; g.n_neg = d->num_neg; g.npad = d->npad;
+    g.P = d->P;
+    return g;
 }
 
 int blocks_for(int64_t items, int per_block) { return (int)((items + per_block - 1) / per_block); }
@@ -678,13 +704,7 @@ int distmult_forward(dn_decoder* d, const float* d_H, int64_t ldh, int64_t n_row
                            d->npad, d->Q, d->En, d_pos, d->hdr);
         DN_LAUNCH_CHECK("k_dm_prepare");
     }
-    DmGemm g;
-    g.A = d->Q; g.lda = d->kp; g.stride_a = (int64_t)d->cpad * d->kp;
-    g.B = d->En; g.ldb = d->kp; g.stride_b = (int64_t)d->npad * d->kp; g.b_mod = C;
-    g.kchunks = d->kp / BK; g.b_wrap_chunks = 1;
-    g.C = d->S; g.ldc = d->npad; g.stride_c = (int64_t)d->cpad * d->npad; g.ncols = d->npad;
-    g.pmax = d->pmax; g.psum = d->psum; g.lse_cols = d->num_neg;
-    int rc = launch_gemm(g, false, d->cpad / BM, d->npad / BN, 2 * C, st, "dm_gemm_scores");
+    int rc = launch_gemm(score_gemm(d), false, DM_EPI_LSE, d->cpad / BM, d->npad / BN, 2 * C, st, "dm_gemm_scores");
     if (rc) return rc;
     {
         dn_prof_scope ps("dm_lse", 0, st);
@@ -704,26 +724,23 @@ int distmult_backward(dn_decoder* d, float* d_dH, int64_t ld_dh, float* d_dR, in
     const int B = (int)d->n_edges, C = (int)d->n_chunks, n_rows = (int)d->n_rows;
     const int n_neg = C * d->num_neg, total = 2 * B + n_neg;
     if (B > 0) {
-        {
-            dn_prof_scope ps("dm_probs", 0, st);
-            hipLaunchKernelGGL(k_dm_probs, dim3(d->npad / 64, d->cpad / 64, 2 * C), dim3(TPB_), 0, st, d->S, d->lse, B, C,
-                               d->chunk, d->num_neg, d->cpad, d->npad, d->P);
-            DN_LAUNCH_CHECK("k_dm_probs");
-        }
+        // the scores again, this time turned into probabilities with the rows' log-sum-exp
+        int rc = launch_gemm(score_gemm(d), false, DM_EPI_PROBS, d->cpad / BM, d->npad / BN, 2 * C, st, "dm_probs");
+        if (rc) return rc;
         {
             dn_prof_scope ps("dm_transpose", 0, st);
             hipLaunchKernelGGL(k_dm_transpose, dim3(d->kp / 64, d->npad / 64, C), dim3(TPB_), 0, st, d->En, d->npad, d->kp,
                                d->Ent, (int64_t)d->np * d->npad);
             DN_LAUNCH_CHECK("k_dm_transpose(E)");
         }
-        DmGemm g;
+        DmGemm g{};
         g.pmax = nullptr; g.psum = nullptr; g.lse_cols = 0;
         // dQ[z] = P[z] (two terms along the reduction) * E[q] : B operand = E^T [np x npad], repeated per term
         g.A = d->P; g.lda = 2 * d->npad; g.stride_a = (int64_t)d->cpad * 2 * d->npad;
         g.B = d->Ent; g.ldb = d->npad; g.stride_b = (int64_t)d->np * d->npad; g.b_mod = C;
         g.kchunks = 2 * d->npad / BK; g.b_wrap_chunks = d->npad / BK;
         g.C = d->dQ; g.ldc = d->np; g.stride_c = (int64_t)d->cpad * d->np; g.ncols = d->dim;
-        int rc = launch_gemm(g, true, d->cpad / BM, d->np / BN, 2 * C, st, "dm_gemm_dq");
+        rc = launch_gemm(g, true, DM_EPI_STORE, d->cpad / BM, d->np / BN, 2 * C, st, "dm_gemm_dq");
         if (rc) return rc;
         // dE[z] = P[z]^T * Q[z], both operands read with the edge index as the reduction index
         {
@@ -794,11 +811,18 @@ int distmult_backward(dn_decoder* d, float* d_dH, int64_t ld_dh, float* d_dR, in
     return DN_OK;
 }
 
-int dn_decoder_scores(const dn_decoder* d, int32_t side, const float** d_scores, int64_t* chunk_stride, int64_t* row_stride)
+int dn_decoder_scores(const dn_decoder* d, int32_t side, const float** d_scores, int64_t* chunk_stride, int64_t* row_stride,
+                      void* stream)
 {
     if (!d || !d_scores || !chunk_stride || !row_stride) return dn_fail(DN_EINVAL, "null argument");
     if (side < 0 || side > 1) return dn_fail(DN_EINVAL, "side must be 0 or 1");
     if (!d->have_forward) return dn_fail(DN_ESTATE, "no distmult_forward yet");
+    if (d->n_edges > 0) {
+        // the forward pass keeps only the rows' log-sum-exp: the scores of both sides are computed here, on request
+        const int rc = launch_gemm(score_gemm(d), false, DM_EPI_STORE, d->cpad / BM, d->npad / BN, 2 * (int)d->n_chunks,
+                                   static_cast<hipStream_t>(stream), "dm_scores_on_request");
+        if (rc) return rc;
+    }
     *d_scores = d->S + (int64_t)side * d->n_chunks * d->cpad * d->npad;
     *chunk_stride = (int64_t)d->cpad * d->npad;
     *row_stride = d->npad;

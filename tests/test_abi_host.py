@@ -101,7 +101,7 @@ def test_decoder_workspace_size_and_bad_arguments(lib):
 def test_new_entry_points_reject_null_and_bad_arguments(lib):
     assert lib.distmult_forward(None, None, 0, 0, None, 0, None, None, None, 0, None, None, None, None) == -1
     assert lib.distmult_backward(None, None, 0, None, 0, None) == -1
-    assert lib.dn_decoder_scores(None, 0, None, None, None) == -1
+    assert lib.dn_decoder_scores(None, 0, None, None, None, None) == -1
     assert lib.dn_decoder_status(None, None, None) == -1
     assert lib.sage_forward_table(None, None, None, 0, None, None) == -1
     assert lib.dn_model_set_aggregation(None, 0) == -1
