@@ -10,8 +10,9 @@
 // The negatives' scores are the dense contraction: per (side, chunk) one
 //   S[chunk x Nn] = Q[chunk x d] * E[Nn x d]^T,   Q = bf16(h_a * r), E = bf16(h_neg)
 // on bf16 MFMA (reduction length padded to a multiple of 64), batched over sides and chunks in one
-// launch.  Backward has two more contractions per (side, chunk): dQ = P * E and dE = P^T * Q with
-// P = softmax probabilities of the negatives.  P is computed on the device (its last bits differ from
+// launch.  The forward pass keeps only each row's log-sum-exp of them.  Backward computes the scores again and
+// turns them into P = softmax probabilities of the negatives in the same kernel, then has two more
+// contractions per (side, chunk): dQ = P * E and dE = P^T * Q.  P is computed on the device (its last bits differ from
 // any other implementation's), so it enters as two bf16 terms hi + lo, two column blocks of one row-major
 // matrix.  dQ contracts over the negatives (P's columns): the terms lie side by side along the reduction
 // index and E^T's tile loads wrap round.  dE contracts over the chunk's edges (the rows of P and of Q): both
