@@ -291,6 +291,7 @@ def run_link_prediction(args, cfg):
                 achieved, peak, unit = work / (avg_us * 1e-6) / 1e12, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s"
             roofline = {"kernel": tag, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
                         "frac": achieved / peak, "traffic": measured_traffic(cfg.name, tag), "avg_us": avg_us,
+                        "p10_p50_p90_us": kernels[tag].get("p10_p50_p90_us"),
                         "algorithmic_per_launch": work, "kernel_time_share_of_step": best[0] / step_sum_us,
                         "event_bracket_overhead_us_subtracted": bracket_us,
                         # a bracket around a kernel that does nothing reads this much more than an empty one: the latency
@@ -680,7 +681,8 @@ def main():
             dn.profile_calibration_copy(delay_dst, delay_src)
             dn.profile_empty_bracket()
             step(s % N_BATCHES)
-        prof = dn.profile_collect()
+        prof_pct = dn.profile_collect_percentiles()
+        prof = {tag: (v[0], v[1]) for tag, v in prof_pct.items()}
         dn.profile_enable(False)
         prof_two_step = {}
         if fused:
@@ -698,6 +700,9 @@ def main():
         bracket_us = 1e3 * empty_ms / max(empty_n, 1)
         kernels = {tag: {"avg_us": max(1e3 * ms / n - bracket_us, 0.0), "launches_per_step": n / args.steps}
                    for tag, (ms, n) in prof.items()}
+        for tag, v in kernels.items():
+            # percentiles of the single brackets (the same bracket cost subtracted): the spread behind avg_us
+            v["p10_p50_p90_us"] = [max(1e3 * x - bracket_us, 0.0) for x in prof_pct[tag][2:5]]
         for tag in ("gather", "aggregate_L1"):
             if tag in prof_two_step:
                 ms, n = prof_two_step[tag]
@@ -734,6 +739,7 @@ def main():
                 achieved, peak, unit = work / (avg_us * 1e-6) / 1e12, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s"
             roofline = {"kernel": tag, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
                         "frac": achieved / peak, "traffic": measured_traffic(cfg.name, tag), "avg_us": avg_us,
+                        "p10_p50_p90_us": kernels[tag].get("p10_p50_p90_us"),
                         "algorithmic_per_launch": work, "kernel_time_share_of_step": best[0] / step_sum_us,
                         "event_bracket_overhead_us_subtracted": bracket_us,
                         # a bracket around a kernel that does nothing reads this much more than an empty one: the latency

@@ -267,11 +267,13 @@ DN_API int  dn_decoder_status(const dn_decoder* d, int32_t* flags, void* stream)
  *      dn_profile_enable(1): from now on every kernel launch of this library is bracketed by a pair of
  *      HIP events on the stream it is launched on; dn_profile_enable(0) stops that.  Enabling also
  *      discards earlier records.  dn_profile_collect WAITS for the device, adds up the elapsed time per
- *      kernel tag and writes up to `max_entries` entries; *n_entries = number of distinct tags. */
+ *      kernel tag (with three percentiles of the single brackets) and writes up to `max_entries` entries;
+ *      *n_entries = number of distinct tags. */
 typedef struct dn_kernel_time {
     char    tag[48];     /* e.g. "gather", "aggregate_L1", "gemm_fwd_L1" */
     double  total_ms;
     int64_t launches;
+    double  p10_ms, p50_ms, p90_ms;   /* 10th, 50th and 90th percentile of the launches' brackets */
 } dn_kernel_time;
 DN_API int  dn_profile_enable(int32_t enable);
 /* A plain device-to-device streaming copy (kernel k_calibration_copy) of `bytes` bytes (multiple of 16,

@@ -23,7 +23,8 @@ class DenseError(RuntimeError):
 
 
 class _KernelTime(ctypes.Structure):
-    _fields_ = [("tag", ctypes.c_char * 48), ("total_ms", ctypes.c_double), ("launches", ctypes.c_int64)]
+    _fields_ = [("tag", ctypes.c_char * 48), ("total_ms", ctypes.c_double), ("launches", ctypes.c_int64),
+                ("p10_ms", ctypes.c_double), ("p50_ms", ctypes.c_double), ("p90_ms", ctypes.c_double)]
 
 
 class _View(ctypes.Structure):
@@ -331,10 +332,16 @@ def profile_empty_bracket() -> None:
 
 def profile_collect():
     """{tag: (total_ms, launches)} since profile_enable(True); waits for the device."""
+    return {tag: (v[0], v[1]) for tag, v in profile_collect_percentiles().items()}
+
+
+def profile_collect_percentiles():
+    """{tag: (total_ms, launches, p10_ms, p50_ms, p90_ms)} since profile_enable(True); waits for the device."""
     buf = (_KernelTime * 128)()
     n = ctypes.c_int32()
     _check(load_library().dn_profile_collect(buf, 128, ctypes.byref(n)))
-    return {buf[i].tag.decode(): (buf[i].total_ms, int(buf[i].launches)) for i in range(min(n.value, 128))}
+    return {buf[i].tag.decode(): (buf[i].total_ms, int(buf[i].launches), buf[i].p10_ms, buf[i].p50_ms, buf[i].p90_ms)
+            for i in range(min(n.value, 128))}
 
 
 def dense_sample(batch: Batch, graph: Graph, targets: torch.Tensor, seed: int) -> None:

@@ -533,23 +533,30 @@ int dn_profile_collect(dn_kernel_time* out, int32_t max_entries, int32_t* n_entr
     if (!n_entries || (max_entries > 0 && !out)) return dn_fail(DN_EINVAL, "null argument");
     DN_HIP(hipDeviceSynchronize());
     std::lock_guard<std::mutex> lock(g_prof_mutex);
-    std::map<std::string, std::pair<double, int64_t>> acc;
+    std::map<std::string, std::vector<float>> acc;
     std::vector<std::string> order;
     for (auto& r : g_prof_records) {
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess) continue;
         auto it = acc.find(r.tag);
-        if (it == acc.end()) { acc[r.tag] = {0.0, 0}; order.push_back(r.tag); it = acc.find(r.tag); }
-        it->second.first += ms;
-        it->second.second += 1;
+        if (it == acc.end()) { order.push_back(r.tag); it = acc.emplace(r.tag, std::vector<float>()).first; }
+        it->second.push_back(ms);
     }
     int32_t n = 0;
     for (auto& tag : order) {
         if (n < max_entries) {
+            std::vector<float>& v = acc[tag];
+            std::sort(v.begin(), v.end());
+            double total = 0.0;
+            for (float ms : v) total += ms;
+            auto at = [&](double q) { return (double)v[(size_t)(q * (double)(v.size() - 1) + 0.5)]; };
             std::memset(&out[n], 0, sizeof(out[n]));
             std::strncpy(out[n].tag, tag.c_str(), sizeof(out[n].tag) - 1);
-            out[n].total_ms = acc[tag].first;
-            out[n].launches = acc[tag].second;
+            out[n].total_ms = total;
+            out[n].launches = (int64_t)v.size();
+            out[n].p10_ms = at(0.10);
+            out[n].p50_ms = at(0.50);
+            out[n].p90_ms = at(0.90);
         }
         ++n;
     }
