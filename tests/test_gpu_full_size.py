@@ -21,11 +21,11 @@ TOL = 1e-4
 # rounding boundary one operand element of the score contraction moves by a whole bf16 step, 2^-8 = 4e-3
 # relative.  Every score of that edge moves with it, the softmax turns a score change of delta into a relative
 # change of up to delta in the probabilities, and a gradient row is a probability-weighted sum, so single rows
-# can be off by a few bf16 steps of their own scale (measured: 5e-3 on the worst of 150,000 rows, 1.4e-3 on the
-# worst edge's loss).  The bound checked here is four steps, 2^-6.  It is a check that the pieces fit together
-# (index maps, strides, chunking); the decoder's own parity, on identical inputs, is held to 1e-4 in
-# test_gpu_decoder.py, the encoder's here.
-DECODER_CHAIN_TOL = 2.0 ** -6
+# can be off by a few bf16 steps of their own scale (measured: 1.4e-2 on the worst of 150,000 rows, 1.4e-3 on the
+# worst edge's loss).  The bound checked here is eight steps, 2^-5.  It is a check that the pieces fit together
+# (index maps, strides, chunking).  The decoder's own parity is held to 1e-4 on identical inputs: here with the
+# oracle's decoder run on the DEVICE encoder's output, and on synthetic inputs in test_gpu_decoder.py.
+DECODER_CHAIN_TOL = 2.0 ** -5
 
 
 def run_full(cfg, batches, n_targets=None, want_dh0=False, link_prediction=False):
@@ -71,6 +71,11 @@ def run_full(cfg, batches, n_targets=None, want_dh0=False, link_prediction=False
         dn.sage_forward(model, batch, h0, out)
         st = oracle.sage_forward(d, table[ids].float().cpu().numpy(), params, mode="bf16")
         errs = {"fwd": row_rel_err(out.cpu().numpy(), st.out)}
+        # the form bench.py times: the first layer reads the table itself; the backward pass below follows this forward
+        out_two_step = out.clone()
+        out.fill_(float("nan"))
+        dn.sage_forward_table(model, batch, table, out)
+        assert torch.equal(out, out_two_step)
         if not link_prediction:
             gout = softmax_xent_grad(st.out, class_labels(len(targets), cfg.dims[-1]))
         else:
@@ -93,6 +98,13 @@ def run_full(cfg, batches, n_targets=None, want_dh0=False, link_prediction=False
             g_dr = torch.empty((num_rel, cfg.dims[-1]), device=dev)
             dn.distmult_backward(dec, g_dh, g_dr)
             assert dec.status() == 0
+            # identical inputs: the oracle's decoder on the device encoder's output
+            ost_dev = oracle.distmult_forward(out.cpu().numpy(), R, ols, rel, old, oln.reshape(-1, n_neg), chunk, mode="bf16")
+            odh_dev, odr_dev = oracle.distmult_backward(ost_dev)
+            same = {"dec_loss": float(np.max(np.abs(loss_t.cpu().numpy() - ost_dev.loss) / np.maximum(ost_dev.loss, 1.0))),
+                    "dec_dH": row_rel_err(g_dh.cpu().numpy(), odh_dev), "dec_dR": row_rel_err(g_dr.cpu().numpy(), odr_dev)}
+            print(cfg.name, "decoder against the oracle's on the same input:", {k: float("%.2e" % v) for k, v in same.items()})
+            assert all(v <= TOL for v in same.values()), same
             chain = {"dec_loss": float(np.max(np.abs(loss_t.cpu().numpy() - ost.loss) / np.maximum(ost.loss, 1.0))),
                      "dec_dH": row_rel_err(g_dh.cpu().numpy(), o_dh), "dec_dR": row_rel_err(g_dr.cpu().numpy(), o_dr)}
             print(cfg.name, "decoder on the encoder's output:", {k: float("%.2e" % v) for k, v in chain.items()})
@@ -103,8 +115,20 @@ def run_full(cfg, batches, n_targets=None, want_dh0=False, link_prediction=False
         dwn = [torch.empty_like(t) for t in to_dev(w_nbr)]
         dbs = [torch.empty_like(t) for t in to_dev(bias)]
         dh0 = torch.empty((batch.node_capacity, cfg.dims[0]), device=dev) if want_dh0 else None
+        fused_rows = None
+        if want_dh0:
+            # the link-prediction step of bench.py: backward with the SGD update of the learnable rows fused in,
+            # on a copy of the table; compared below, bit for bit, with backward followed by embedding_sgd
+            fused_table = table.clone()
+            dws2, dwn2, dbs2 = ([torch.empty_like(t) for t in g] for g in (dws, dwn, dbs))
+            dn.sage_backward_sgd(model, batch, torch.from_numpy(gout).to(dev), dws2, dwn2, dbs2, fused_table, 0.01)
+            fused_rows = fused_table[ids].clone()
+            del fused_table
         dn.sage_backward(model, batch, torch.from_numpy(gout).to(dev), dws, dwn, dbs, dh0)
         torch.cuda.synchronize()
+        if want_dh0:
+            for a, b in zip(dws + dwn + dbs, dws2 + dwn2 + dbs2):
+                assert torch.equal(a, b)
         assert model.status()[1] == 0
         for i in range(cfg.num_layers):
             errs["dws%d" % (i + 1)] = row_rel_err(dws[i].cpu().numpy(), grads.d_w_self[i])
@@ -118,6 +142,7 @@ def run_full(cfg, batches, n_targets=None, want_dh0=False, link_prediction=False
             dn.embedding_sgd(batch, table, dh0, 0.01)
             want = before.cpu().numpy() - np.float32(0.01) * dh0[:2000].cpu().numpy()
             assert np.array_equal(table[probe].cpu().numpy().view(np.uint32), want.astype(np.float32).view(np.uint32))
+            assert torch.equal(table[ids], fused_rows)
         print(cfg.name, "batch", bi, "N=%d E=%d" % (n, len(d.nbrs)), {k: float("%.2e" % v) for k, v in errs.items()})
         bad = {k: v for k, v in errs.items() if not v <= TOL}
         assert not bad, bad
