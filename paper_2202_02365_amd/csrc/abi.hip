@@ -115,7 +115,7 @@ int fill_model(dn_model* m, const dn_batch* b, int32_t k, const int32_t* dims, i
 void carve_model(dn_model* m, const dn_batch* b, Carver& c)
 {
     const int k = m->k;
-    int64_t max_dx = 0, max_g = 0;
+    int64_t max_dx = 0;
     m->splits = 32;
     for (int i = 1; i <= k; ++i) {
         dn_layer_bufs& L = m->layer[i - 1];
@@ -129,13 +129,12 @@ void carve_model(dn_model* m, const dn_batch* b, Carver& c)
         L.dzb = c.take<dn_bf16>(L.rows_pad * L.nz);
         L.partial_floats = (int64_t)m->splits * L.kx * L.d_out * L.zterms;
         L.partial = c.take<float>(L.partial_floats);
-        L.db_partial = c.take<float>(((L.rows_cap + 63) / 64 + 1) * L.d_out);
+        // bias-gradient partials: one row per (dZ term, split) from the weight-gradient GEMM; the last layer's come from
+        // its dZ kernel, one row per row tile
+        L.db_partial = c.take<float>((i < k ? (int64_t)m->splits * L.zterms : (L.rows_cap + 63) / 64 + 1) * L.d_out);
         max_dx = std::max<int64_t>(max_dx, L.rows_pad * 2 * L.d_in);
-        if (i < k) max_g = std::max<int64_t>(max_g, L.rows_pad * L.d_out);   // gradient w.r.t. H^i
     }
     m->dx = c.take<float>(max_dx);
-    m->g[0] = c.take<float>(max_g);
-    m->g[1] = c.take<float>(max_g);
     m->fix_count = c.take<int32_t>(64);
     (void)b;
 }

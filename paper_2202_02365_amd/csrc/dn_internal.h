@@ -94,7 +94,7 @@ struct dn_model {
     int32_t dims[DN_MAX_LAYERS + 1];
     dn_layer_bufs layer[DN_MAX_LAYERS];
     // backward temporaries, sized for the largest layer
-    float *dx, *g[2];
+    float* dx;
     int32_t splits;
 
     // pre-activations too close to zero for the fp32 accumulation to settle their sign

@@ -109,10 +109,13 @@ __global__ __launch_bounds__(TPB) void k_aggregate(const int32_t* __restrict__ h
     }
 }
 
-// ---------------------------------------------------------------- backward: dZ and db
+// ---------------------------------------------------------------- backward: dZ and db of the last layer
 // Tile of 64 rows x 64 columns per workgroup (striding over the row tiles beyond the grid).
 // dZ = G (.) [H > 0] (ReLU layers) or G.  Writes the bf16 terms of dZ row-major [rows x TERMS*np] (hi block, then
 // lo block; zero in the padding columns) and the workgroup's column sums of the unrounded dZ for the bias gradient.
+// Only the layer that receives the caller's gradient runs this (its dZ is one bf16 term, so its bias gradient
+// cannot come from the terms); for the others the backward aggregation of the layer above writes dZ itself
+// (GradSink::dzb) and the weight-gradient GEMM sums the two terms' columns.
 template <int TERMS>
 __global__ __launch_bounds__(TPB) void k_dz(const int32_t* __restrict__ hdr, int layer, const float* __restrict__ G, int ldg,
                                             const float* __restrict__ Hout, int d_out, int np, int relu,
@@ -162,11 +165,20 @@ struct GradSink {
     float* table; int64_t ld;    // update mode: table[node_ids[p], :] -= lr * gradient
     const int32_t* node_ids;
     float lr;
+    // dZ mode (the layer below has a ReLU): the row is the gradient with respect to H of the layer below; masked
+    // by [H > 0] it IS that layer's dZ, which goes out as two bf16 terms [rows x 2*np] (hi block, lo block)
+    // without a pass of its own.  hmask = that layer's output H [rows x d].
+    uint16_t* dzb; int nz, np; const float* hmask;
 };
 __device__ __forceinline__ void sink_store(const GradSink& k, int r, int p, int d, int c, float v)
 {
 #pragma clang fp contract(off)
-    if (k.table) {
+    if (k.dzb) {
+        if (!(k.hmask[(int64_t)r * d + c] > 0.f)) v = 0.f;
+        const uint16_t hi = f32_to_bf16(v);
+        k.dzb[(int64_t)r * k.nz + c] = hi;
+        k.dzb[(int64_t)r * k.nz + k.np + c] = f32_to_bf16(v - bf16_to_f32(hi));
+    } else if (k.table) {
         float* w = k.table + (int64_t)k.node_ids[p] * k.ld + c;
         const float step = k.lr * v;
         *w = *w - step;
@@ -185,6 +197,22 @@ __device__ __forceinline__ void sink_store_vec(const GradSink& k, int r, int p, 
         const float s0 = k.lr * v[0], s1 = k.lr * v[1], s2 = k.lr * v[2], s3 = k.lr * v[3];
         old.x = old.x - s0; old.y = old.y - s1; old.z = old.z - s2; old.w = old.w - s3;
         *w = old;
+        return;
+    }
+    if constexpr (V == 4) if (k.dzb) {
+        // four columns at once: one 16-byte read of the mask row, two 8-byte stores (d and np are multiples of 4 here)
+        const float4 h = *reinterpret_cast<const float4*>(k.hmask + (int64_t)r * d + c0);
+        const float hv[4] = {h.x, h.y, h.z, h.w};
+        uint16_t hi[4], lo[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float z = hv[e] > 0.f ? v[e] : 0.f;
+            hi[e] = f32_to_bf16(z);
+            lo[e] = f32_to_bf16(z - bf16_to_f32(hi[e]));
+        }
+        uint16_t* row = k.dzb + (int64_t)r * k.nz + c0;
+        *reinterpret_cast<uint2*>(row) = make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
+        *reinterpret_cast<uint2*>(row + k.np) = make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
         return;
     }
 #pragma unroll
@@ -268,6 +296,11 @@ __global__ __launch_bounds__(TPB) void k_aggregate_bwd(const int32_t* __restrict
                     for (int w = 0; w < GROUPS; ++w) tot += part[w][c];
                     sink_store(sink, r, p, d, c, tot);
                 }
+                if (sink.dzb)                                  // the padding columns of both terms stay zero
+                    for (int c = d + threadIdx.x; c < sink.np; c += TPB) {
+                        sink.dzb[(int64_t)r * sink.nz + c] = 0;
+                        sink.dzb[(int64_t)r * sink.nz + sink.np + c] = 0;
+                    }
                 __syncthreads();
             }
         }
@@ -357,6 +390,11 @@ __global__ __launch_bounds__(TPB) void k_aggregate_bwd(const int32_t* __restrict
                 sink_store_vec<V>(sink, r, p, d, c0, acc[it], wrow, wold);
             }
         }
+        if (sink.dzb)                                          // the padding columns of both terms stay zero
+            for (int c = d + lane; c < sink.np; c += LANES) {
+                sink.dzb[(int64_t)r * sink.nz + c] = 0;
+                sink.dzb[(int64_t)r * sink.nz + sink.np + c] = 0;
+            }
     }
 }
 
@@ -482,28 +520,35 @@ int dn_launch_backward(dn_model* m, dn_batch* b, const float* grad_out, float* c
     // The chain that carries the gradient down the layers comes first: dZ^i -> dX^i -> transpose of
     // the mean -> dZ^{i-1}.  What nothing downstream waits for (the dW GEMMs, the reductions of dW and db)
     // follows in two launches that cover all layers; every layer has its own operands.
-    const float* g = grad_out;
-    for (int i = k; i >= 1; --i) {
-        const dn_layer_bufs& L = m->layer[i - 1];
+    {
+        // dZ of the last layer from the caller's gradient (no activation there)
+        const dn_layer_bufs& L = m->layer[k - 1];
         unsigned row_tiles = (unsigned)((L.rows_cap + 63) / 64);
         if (row_tiles > DN_DZ_MAX_ROW_BLOCKS) row_tiles = DN_DZ_MAX_ROW_BLOCKS;   // the kernel strides over the row tiles beyond the grid
-        { dn_prof_scope ps("dz", i, st);
+        dn_prof_scope ps("dz", k, st);
         if (L.zterms == 2)
             hipLaunchKernelGGL((k_dz<2>), dim3((unsigned)(L.np / 64), row_tiles ? row_tiles : 1), dim3(TPB), 0, st, b->hdr,
-                               i, g, L.d_out, L.h, L.d_out, L.np, 1, reinterpret_cast<uint16_t*>(L.dzb), L.db_partial);
+                               k, grad_out, L.d_out, nullptr, L.d_out, L.np, 0, reinterpret_cast<uint16_t*>(L.dzb), L.db_partial);
         else
             hipLaunchKernelGGL((k_dz<1>), dim3((unsigned)(L.np / 64), row_tiles ? row_tiles : 1), dim3(TPB), 0, st, b->hdr,
-                               i, g, L.d_out, nullptr, L.d_out, L.np, 0, reinterpret_cast<uint16_t*>(L.dzb), L.db_partial);
-        }
-        DN_LAUNCH_CHECK("k_dz");
+                               k, grad_out, L.d_out, nullptr, L.d_out, L.np, 0, reinterpret_cast<uint16_t*>(L.dzb), L.db_partial);
+    }
+    DN_LAUNCH_CHECK("k_dz");
+    for (int i = k; i >= 1; --i) {
         if (i == 1 && !need_input_grad) break;          // nothing consumes the input gradient of layer 1
         rc = dn_gemm_dx(m, b, i, st);
         if (rc) return rc;
-        GradSink sink = { (i == 1) ? dh0 : m->g[i & 1], nullptr, 0, b->node_ids, 0.f };
-        if (i == 1 && sgd_table) { sink.gin = nullptr; sink.table = sgd_table; sink.ld = sgd_ld; sink.lr = sgd_lr; }
+        GradSink sink = { dh0, nullptr, 0, b->node_ids, 0.f, nullptr, 0, 0, nullptr };
+        if (i == 1) {
+            if (sgd_table) { sink.gin = nullptr; sink.table = sgd_table; sink.ld = sgd_ld; sink.lr = sgd_lr; }
+        } else {
+            // the gradient with respect to H^{i-1}, masked by its ReLU, is dZ^{i-1}: written as that layer's bf16 terms
+            const dn_layer_bufs& Lb = m->layer[i - 2];
+            sink.gin = nullptr;
+            sink.dzb = reinterpret_cast<uint16_t*>(Lb.dzb); sink.nz = Lb.nz; sink.np = Lb.np; sink.hmask = Lb.h;
+        }
         rc = launch_aggregate_bwd(m, b, i, sink, st);
         if (rc) return rc;
-        g = sink.gin;
     }
     return dn_gemm_dw_all(m, b, dws, dwn, dbias, st);
 }

@@ -48,6 +48,7 @@ struct GemmArgs {
     int terms;              // dW: reduction terms (hi, lo) of B; split index z = term * (gridDim.z / terms) + chunk group
     int64_t b_term_stride;  // dW: elements between B's terms
     int a_cols, b_cols;     // dW: allocated columns of A, of one term of B (loads beyond them read zero)
+    float* db_partial;      // dW: [splits of all terms x ncols] column sums of this split's rows of B (the bias gradient's partials)
     // ReLU sign fix-up (EPI_BIAS_ACT with relu)
     const float* rownorm; const float* colnorm; float gamma;
     int* fix_count;         // [0] number of exact recomputations, [1] sticky overflow flag
@@ -90,9 +91,22 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const int bx, const
     const int wm = wave >> 1, wn = wave & 1;
 
     f32x16 acc[MI][NJ];
-    if constexpr (EPI == EPI_SPLIT)     // weight gradient: both operands have the reduction index (the node) as their row index
-        mainloop_tn<BM_, BN_>(a.A, a.lda, a.a_cols, Bbase, a.ldb, a.b_cols, row0, col0, kc_begin, kc_end, rows_layer, acc);
-    else
+    if constexpr (EPI == EPI_SPLIT) {
+        // weight gradient: both operands have the reduction index (the node) as their row index.  The first row
+        // tile's upper waves also multiply a row of ones with their fragments of dZ: the column sums of this
+        // split's rows of dZ, which are its share of the bias gradient.
+        f32x16 ones_acc[NJ];
+        const bool do_ones = by == 0 && wm == 0 && a.db_partial != nullptr;
+        mainloop_tn<BM_, BN_, true>(a.A, a.lda, a.a_cols, Bbase, a.ldb, a.b_cols, row0, col0, kc_begin, kc_end, rows_layer, acc,
+                                    ones_acc, do_ones);
+        if (do_ones && lane < 32) {                           // register 0 of lanes 0..31: row 0 of the 32 x 32 tile
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                const int n = col0 + wn * (BN_ / 2) + j * 32 + lane;
+                if (n < a.ncols) a.db_partial[(int64_t)bz * a.ncols + n] = ones_acc[j][0];
+            }
+        }
+    } else
         mainloop<BM_, BN_, false>(a.A + (int64_t)row0 * a.lda, a.lda, Bbase + (int64_t)col0 * a.ldb, a.ldb, kc_begin, kc_end, 0, acc);
 
     // epilogue: lane holds column (lane & 31); register e holds row 8*(e/4) + 4*(lane/32) + e%4
@@ -253,17 +267,38 @@ __device__ __forceinline__ void dw_reduce_block(const int block, const float* __
     }
 }
 
-// db[n] = sum over the partial column sums of the dZ kernel's row-tile workgroups.  16 columns per workgroup; thread
+// db[n] = sum over the bias-gradient partials that the dW workgroups of the first row tile wrote, one per (dZ
+// term, split), in a fixed order.  One thread per column.
+constexpr int DB_COLS = TPB;
+__device__ __forceinline__ void db_reduce_block(const int block, int rows, const float* __restrict__ db_partial, int groups,
+                                                int zterms, int d_out, float* __restrict__ db)
+{
+    const int n = block * DB_COLS + threadIdx.x;
+    if (n >= d_out) return;
+    const int eff = effective_splits(groups, (rows + BK - 1) / BK);   // the splits the GEMM actually wrote
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int zt = 0; zt < zterms; ++zt)
+        for (int z = 0; z < eff; z += 4) {
+            float v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = db_partial[(int64_t)(zt * groups + min(z + u, eff - 1)) * d_out + n];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc[u] += (z + u < eff) ? v[u] : 0.f;
+        }
+    db[n] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+}
+
+// Last layer: db[n] = sum over the partial column sums of the dZ kernel's row-tile workgroups.  16 columns per workgroup; thread
 // group g of 16 takes the tiles g, g + 16, ..., eight loads in flight; the sixteen partial sums are combined in a
 // fixed order.
-constexpr int DB_COLS = 16;
-__device__ __forceinline__ void db_reduce_block(const int block, int rows, const float* __restrict__ db_partial, int d_out,
+constexpr int DB_TILE_COLS = 16;
+__device__ __forceinline__ void db_reduce_tiles(const int block, int rows, const float* __restrict__ db_partial, int d_out,
                                                 float* __restrict__ db)
 {
-    __shared__ float part[TPB / DB_COLS][DB_COLS];
-    constexpr int G = TPB / DB_COLS;
-    const int tx = threadIdx.x % DB_COLS, g = threadIdx.x / DB_COLS;
-    const int n = block * DB_COLS + tx;
+    __shared__ float part[TPB / DB_TILE_COLS][DB_TILE_COLS];
+    constexpr int G = TPB / DB_TILE_COLS;
+    const int tx = threadIdx.x % DB_TILE_COLS, g = threadIdx.x / DB_TILE_COLS;
+    const int n = block * DB_TILE_COLS + tx;
     const int all_tiles = (rows + 63) / 64;
     const int tiles = all_tiles < (int)DN_DZ_MAX_ROW_BLOCKS ? all_tiles : (int)DN_DZ_MAX_ROW_BLOCKS;   // partial sums the dZ kernel wrote
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -294,6 +329,7 @@ struct ReduceGroup {
     float *dws[DN_MAX_LAYERS], *dwn[DN_MAX_LAYERS], *db[DN_MAX_LAYERS];
     const float* db_partial[DN_MAX_LAYERS];
     int dw_blocks[DN_MAX_LAYERS], db_blocks[DN_MAX_LAYERS];
+    int db_from_tiles[DN_MAX_LAYERS];    // last layer: the partials are the dZ kernel's, one per row tile
     int begin[DN_MAX_LAYERS + 1];
     int n;
 };
@@ -307,7 +343,8 @@ __global__ __launch_bounds__(TPB) void k_bwd_reduce_group(ReduceGroup R, const i
         dw_reduce_block(x, R.partial[y], R.split_stride[y], R.groups[y], R.zterms[y], rows, R.xterms[y], R.d_in[y], R.d_out[y],
                         R.dws[y], R.dwn[y]);
     } else if (x < R.dw_blocks[y] + R.db_blocks[y]) {
-        db_reduce_block(x - R.dw_blocks[y], rows, R.db_partial[y], R.d_out[y], R.db[y]);
+        if (R.db_from_tiles[y]) db_reduce_tiles(x - R.dw_blocks[y], rows, R.db_partial[y], R.d_out[y], R.db[y]);
+        else db_reduce_block(x - R.dw_blocks[y], rows, R.db_partial[y], R.groups[y], R.zterms[y], R.d_out[y], R.db[y]);
     }
 }
 
@@ -445,6 +482,7 @@ int dn_gemm_dw_all(const dn_model* m, const dn_batch* b, float* const* dws, floa
         a.hdr = b->hdr; a.layer = i; a.m_const = L.kx; a.ncols = L.d_out; a.red_const = -1;
         a.bias = nullptr; a.relu = 0; a.split_stride = (int64_t)L.kx * L.d_out;
         a.terms = L.zterms; a.b_term_stride = L.np;
+        a.db_partial = (i < m->k) ? L.db_partial : nullptr;          // the last layer's bias gradient comes from its dZ kernel
         const int zsplits = splits * L.zterms;
         if ((int64_t)zsplits * a.split_stride > L.partial_floats) return dn_fail(DN_ECAPACITY, "dW partial buffer too small");
         const int y = i - 1;
@@ -458,7 +496,8 @@ int dn_gemm_dw_all(const dn_model* m, const dn_batch* b, float* const* dws, floa
         R.d_in[y] = L.d_in; R.d_out[y] = L.d_out; R.layer[y] = i;
         R.dws[y] = dws[y]; R.dwn[y] = dwn[y]; R.db[y] = dbias[y]; R.db_partial[y] = L.db_partial;
         R.dw_blocks[y] = (2 * L.d_in * L.d_out + 63) / 64;
-        R.db_blocks[y] = (L.d_out + DB_COLS - 1) / DB_COLS;
+        R.db_from_tiles[y] = (i == m->k) ? 1 : 0;
+        R.db_blocks[y] = (i == m->k) ? (L.d_out + DB_TILE_COLS - 1) / DB_TILE_COLS : (L.d_out + DB_COLS - 1) / DB_COLS;
         R.begin[y] = red_blocks;
         red_blocks += R.dw_blocks[y] + R.db_blocks[y];
     }

@@ -139,11 +139,14 @@ __device__ __forceinline__ void mainloop(const uint16_t* __restrict__ A_tile, co
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-template <int BM_, int BN_>
+// ONES: where `do_ones` holds (the same for a whole wave), ones_acc[j] also accumulates a row of ones times B's
+// fragments: every row of that 32 x 32 tile is the sum of B over the reduction range, column by column.
+template <int BM_, int BN_, bool ONES = false>
 __device__ __forceinline__ void mainloop_tn(const uint16_t* __restrict__ A, const int64_t lda, const int a_cols,
                                             const uint16_t* __restrict__ B, const int64_t ldb, const int b_cols,
                                             const int m0, const int n0, const int kc_begin, const int kc_end,
-                                            const int k_rows, f32x16 (&acc)[BM_ / 64][BN_ / 64])
+                                            const int k_rows, f32x16 (&acc)[BM_ / 64][BN_ / 64],
+                                            f32x16* ones_acc = nullptr, const bool do_ones = false)
 {
     constexpr int MI = BM_ / 64, NJ = BN_ / 64;
     constexpr int CA = BM_ / 8, CB = BN_ / 8;            // 16-byte chunks per reduction row
@@ -159,6 +162,14 @@ __device__ __forceinline__ void mainloop_tn(const uint16_t* __restrict__ A, cons
         for (int j = 0; j < NJ; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    if (ONES) {
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) ones_acc[j][e] = 0.f;
+    }
+    const s16x8 one_bits = {0x3F80, 0x3F80, 0x3F80, 0x3F80, 0x3F80, 0x3F80, 0x3F80, 0x3F80};     // bf16 1.0
+    const bf16x8 one8 = __builtin_bit_cast(bf16x8, one_bits);
 
     auto load_tiles = [&](TileRegs<LA, LB>& r, int kc) {
         const int k0 = kc * BK;
@@ -212,6 +223,13 @@ __device__ __forceinline__ void mainloop_tn(const uint16_t* __restrict__ A, cons
 #pragma unroll
                 for (int j = 0; j < NJ; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+            if (ONES) {
+                if (do_ones) {
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j)
+                        ones_acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(one8, fb[j], ones_acc[j], 0, 0, 0);
+                }
+            }
         }
     };
 
