@@ -108,6 +108,32 @@ def test_shapes_with_bias_and_input_gradient(g16k, fanouts, dims):
     check(errs)
 
 
+@pytest.mark.parametrize("dims", [[32, 64, 48, 10], [20, 36, 33, 7]])
+def test_rows_read_by_hundreds_of_slots(dims):
+    """A star inside a ring: every node points at node 0 and at two ring neighbours, and the fanout takes all three.
+    Node 0 is then read by every target's and every first-hop node's segment: in the backward aggregation of
+    layers 2 and 3 its row has hundreds of transposed slots, far above the 64 that a lane group handles, and its
+    gradient is the dZ row of the layer below (ReLU mask and bf16 terms applied by the workgroup that sums it).
+    The second shape has widths that are no multiples of four and padding columns in every dZ."""
+    V = 3000
+    src = np.repeat(np.arange(V, dtype=np.int64), 3)
+    dst = np.stack([np.zeros(V, dtype=np.int64), (np.arange(V) + 1) % V, (np.arange(V) + 7) % V], axis=1).reshape(-1)
+    keep = src != dst                                      # node 0 does not point at itself
+    src, dst = src[keep], dst[keep]
+    order = np.lexsort((dst, src))
+    src, dst = src[order], dst[order]
+    rowptr = np.zeros(V + 1, dtype=np.int64)
+    np.add.at(rowptr, src + 1, 1)
+    rowptr = np.cumsum(rowptr)
+    dg = DeviceGraph(rowptr, dst.astype(np.int32))
+    targets = (np.arange(400, dtype=np.int32) * 5 + 11) % V           # 400 distinct nodes, none of them node 0
+    errs, (_, _, _, _, _, d) = run_case(dg, [3, 3, 3], dims, len(targets), seed=4, targets=targets, want_dh0=True)
+    pos0 = int(np.nonzero(np.asarray(d.node_ids) == 0)[0][0])
+    readers = int(np.sum(np.asarray(d.repr_map) == pos0))
+    assert readers > 500, readers                            # the hub row is what this test is about
+    check(errs)
+
+
 @pytest.mark.parametrize("feat_dtype", ["f32", "bf16"])
 def test_forward_from_the_table_equals_gather_then_forward(g16k, feat_dtype):
     errs, _ = run_case(g16k, [7, 4], [36, 64, 12], 200, seed=11, feat_dtype=feat_dtype, want_dh0=True, from_table=True)
