@@ -205,7 +205,9 @@ DN_API int  dn_model_set_aggregation(dn_model* m, int32_t aggregation);
  * (fp32 [dims[i]]) for every layer, and, when d_dH0 is not NULL, dL/dH^0 (fp32 [N x dims[0]],
  * capacity >= node capacity rows; needed for learnable base representations).  Uses the
  * activations saved by the last sage_forward on the same model and batch.  Neighbour-mean
- * gradients are summed per input row in ascending slot order (no floating-point atomics). */
+ * gradients are summed per input row in ascending slot order (no floating-point atomics).
+ * dL/db^k sums the fp32 rows of d_grad_out; below the last layer dL/db^i sums dZ^i as the two bf16 terms
+ * (16 mantissa bits per element) that the weight-gradient contraction multiplies, accumulated in fp32. */
 DN_API int  sage_backward(dn_model* m, const dn_batch* b, const float* d_grad_out,
                    float* const* d_dw_self, float* const* d_dw_nbr, float* const* d_dbias,
                    float* d_dH0, void* stream);
