@@ -178,7 +178,7 @@ int64_t dn_transpose_index_hist_words(const dn_batch* b);
 //   hist[(key & ((1 << bits) - 1)) * dn_sort_tiles(count) + i / DN_SORT_TILE]++.
 // The histograms' rows are as long as the tiles in use, not as the capacity: scans and clears touch what a
 // mini-batch fills.
-constexpr int DN_SORT_TILE = 2048;
+constexpr int DN_SORT_TILE = 1024;
 __host__ __device__ inline int dn_sort_tiles(int count) { return count > 0 ? (count + DN_SORT_TILE - 1) / DN_SORT_TILE : 1; }
 struct dn_sort_plan { int passes, bits, nblocks, total, sblocks; };
 dn_sort_plan dn_sort_make_plan(int64_t key_range, int64_t cap_items);
