@@ -294,7 +294,7 @@ static int64_t hist_stride(const dn_sort_plan& p) { return ((int64_t)p.total + 3
 int64_t dn_sort_hist_words(const dn_sort_plan& p) { return 3 * hist_stride(p) + p.sblocks + 64; }
 
 // histograms up to this many ints (by capacity) are scanned by one kernel (k_scan_single)
-constexpr int64_t SINGLE_SCAN_MAX = 1 << 19;
+constexpr int64_t SINGLE_SCAN_MAX = 1 << 20;
 
 // Sorts the pairs that the caller's first kernel left in key[plan.passes & 1] / val[plan.passes & 1]
 // (with the first digit's per-tile counts in hist[0 .. total)) by key, stably; the result is in
