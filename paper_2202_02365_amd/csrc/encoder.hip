@@ -188,9 +188,10 @@ __device__ __forceinline__ void sink_store(const GradSink& k, int r, int p, int 
 }
 // V consecutive columns starting at c0 (V = 4: one 16-byte access when the table's rows allow it)
 // `w` / `old`: the table row's four values at c0, fetched by the caller before it walked the slots (null: not fetched)
+// dZ mode: with `mask_fetched`, `old` holds the four values of the mask row at c0 instead
 template <int V>
 __device__ __forceinline__ void sink_store_vec(const GradSink& k, int r, int p, int d, int c0, const float (&v)[V],
-                                               float4* w, float4 old)
+                                               float4* w, float4 old, bool mask_fetched = false)
 {
 #pragma clang fp contract(off)
     if (w) {
@@ -201,7 +202,7 @@ __device__ __forceinline__ void sink_store_vec(const GradSink& k, int r, int p, 
     }
     if constexpr (V == 4) if (k.dzb) {
         // four columns at once: one 16-byte read of the mask row, two 8-byte stores (d and np are multiples of 4 here)
-        const float4 h = *reinterpret_cast<const float4*>(k.hmask + (int64_t)r * d + c0);
+        const float4 h = mask_fetched ? old : *reinterpret_cast<const float4*>(k.hmask + (int64_t)r * d + c0);
         const float hv[4] = {h.x, h.y, h.z, h.w};
         uint16_t hi[4], lo[4];
 #pragma unroll
@@ -320,6 +321,9 @@ __global__ __launch_bounds__(TPB) void k_aggregate_bwd(const int32_t* __restrict
             wrow = reinterpret_cast<float4*>(sink.table + (int64_t)sink.node_ids[p] * sink.ld + lane * V);
             wold = *wrow;
         }
+        // dZ mode: likewise the row of the ReLU mask
+        const bool mask_fetched = V == 4 && ITERS == 1 && sink.dzb != nullptr && lane * V < d;
+        if (mask_fetched) wold = *reinterpret_cast<const float4*>(sink.hmask + (int64_t)r * d + lane * V);
         float acc[ITERS][V];
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
@@ -387,7 +391,7 @@ __global__ __launch_bounds__(TPB) void k_aggregate_bwd(const int32_t* __restrict
         for (int it = 0; it < ITERS; ++it) {
             const int c0 = (it * LANES + lane) * V;
             if (c0 < d) {
-                sink_store_vec<V>(sink, r, p, d, c0, acc[it], wrow, wold);
+                sink_store_vec<V>(sink, r, p, d, c0, acc[it], wrow, wold, mask_fetched);
             }
         }
         if (sink.dzb)                                          // the padding columns of both terms stay zero
