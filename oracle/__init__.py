@@ -201,13 +201,13 @@ def dense_gather(table: np.ndarray, node_ids: np.ndarray) -> np.ndarray:
     return out
 
 
-from .sage import (round_bf16, dense_layer_view, sage_forward, sage_backward, SageParams,  # noqa: E402
+from .sage import (round_bf16, bf16_terms, dense_layer_view, sage_forward, sage_backward, SageParams,  # noqa: E402
                    ForwardState)
 from .distmult import distmult_forward, distmult_backward, DistMultState  # noqa: E402
-from .heads import softmax_xent, embedding_adagrad  # noqa: E402
+from .heads import softmax_xent, mean_xent_grad, embedding_adagrad  # noqa: E402
 
 __all__ = ["build", "philox4x32_10", "floyd_positions", "Graph", "Dense", "onehop", "dense_sample",
            "dense_sample_edges", "embedding_sgd",
            "dense_gather", "round_bf16", "dense_layer_view", "sage_forward", "sage_backward",
            "SageParams", "ForwardState", "distmult_forward", "distmult_backward", "DistMultState",
-           "softmax_xent", "embedding_adagrad"]
+           "softmax_xent", "mean_xent_grad", "embedding_adagrad", "bf16_terms"]

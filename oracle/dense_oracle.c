@@ -125,8 +125,8 @@ static int cmp_i32(const void* a, const void* b)
 static int32_t* cat_i32(const int32_t* front, int64_t nf, const int32_t* back, int64_t nb)
 {
     int32_t* r = (int32_t*)malloc(sizeof(int32_t) * (size_t)(nf + nb + 1));
-    memcpy(r, front, sizeof(int32_t) * (size_t)nf);
-    memcpy(r + nf, back, sizeof(int32_t) * (size_t)nb);
+    if (nf > 0) memcpy(r, front, sizeof(int32_t) * (size_t)nf);       /* an empty part may come as a null pointer */
+    if (nb > 0) memcpy(r + nf, back, sizeof(int32_t) * (size_t)nb);
     return r;
 }
 
@@ -134,7 +134,7 @@ static int32_t* cat_i32(const int32_t* front, int64_t nf, const int32_t* back, i
 static int64_t* cat_i64_shift(const int64_t* front, int64_t nf, const int64_t* back, int64_t nb, int64_t shift)
 {
     int64_t* r = (int64_t*)malloc(sizeof(int64_t) * (size_t)(nf + nb + 1));
-    memcpy(r, front, sizeof(int64_t) * (size_t)nf);
+    if (nf > 0) memcpy(r, front, sizeof(int64_t) * (size_t)nf);
     for (int64_t i = 0; i < nb; ++i) r[nf + i] = back[i] + shift;
     return r;
 }

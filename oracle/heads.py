@@ -38,3 +38,9 @@ def embedding_adagrad(table: np.ndarray, state: np.ndarray, node_ids: np.ndarray
     step = (np.float32(lr) * g) / (np.sqrt(acc) + np.float32(eps))
     t[node_ids] = t[node_ids] - step
     return t, s
+
+
+def mean_xent_grad(logits: np.ndarray, labels: np.ndarray) -> np.ndarray:
+    """d(mean over the rows of the softmax cross-entropy)/d(logits), stored as fp32: the upstream gradient dL/dH^k
+    that the tests, the smoke check and the benchmark's CPU leg hand to the backward pass of both sides."""
+    return softmax_xent(logits, labels, 1.0 / len(labels))[1].astype(np.float32)

@@ -181,12 +181,8 @@ class Gradients:
     d_z: List[np.ndarray]
 
 
-def sage_backward(st: ForwardState, params: SageParams, grad_out: np.ndarray, mode: str = "exact",
-                  relu_masks: Optional[List[Optional[np.ndarray]]] = None) -> Gradients:
-    """Gradients of <grad_out, H^k> with respect to every weight, bias and H^0.
-
-    relu_masks, if given, replaces [Z > 0] per layer (used by tests to settle pre-activations
-    that are zero to within the device's accumulation error)."""
+def sage_backward(st: ForwardState, params: SageParams, grad_out: np.ndarray, mode: str = "exact") -> Gradients:
+    """Gradients of <grad_out, H^k> with respect to every weight, bias and H^0."""
     k = len(params.w_self)
     rb = round_bf16 if mode == "bf16" else (lambda a: a)
     store = (lambda a: a.astype(np.float32).astype(np.float64)) if mode == "bf16" else (lambda a: a)
@@ -196,8 +192,7 @@ def sage_backward(st: ForwardState, params: SageParams, grad_out: np.ndarray, mo
         ls = st.layers[i - 1]
         view = ls.view
         if ls.relu:
-            mask = (ls.z > 0.0) if (relu_masks is None or relu_masks[i - 1] is None) else relu_masks[i - 1]
-            d_z = g * mask
+            d_z = g * (ls.z > 0.0)
         else:
             d_z = g
         d_zs[i - 1] = d_z

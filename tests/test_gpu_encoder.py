@@ -6,8 +6,8 @@ import torch
 
 import oracle
 import paper_2202_02365_amd as dn
-from workloads import CONFIGS, target_batch, feature_table, glorot_weights, class_labels, softmax_xent_grad
-from gpu_harness import DeviceGraph, gpu_sample, assert_dense_equal, row_rel_err, to_dev
+from workloads import CONFIGS, target_batch, feature_table, glorot_weights, class_labels
+from gpu_harness import DeviceGraph, gpu_sample, assert_dense_equal, row_rel_err, to_dev, exact_distance_report
 
 pytestmark = pytest.mark.gpu
 TOL = 1e-4
@@ -27,7 +27,7 @@ def g1m(rmat1m):
 
 
 def run_case(dg, fanouts, dims, n_targets, seed, batch_index=0, direction=0, feat_dtype="f32", bias_scale=0.1,
-             want_dh0=False, targets=None, aggregation="mean", from_table=False):
+             want_dh0=False, targets=None, aggregation="mean", from_table=False, versus_exact=False):
     V = dg.num_nodes
     if targets is None:
         targets = target_batch(V, n_targets, batch_index)
@@ -60,7 +60,7 @@ def run_case(dg, fanouts, dims, n_targets, seed, batch_index=0, direction=0, fea
     st = oracle.sage_forward(d, h0_o, params, mode="bf16")
     fwd_err = row_rel_err(out.cpu().numpy(), st.out)
 
-    gout = softmax_xent_grad(st.out, class_labels(len(targets), dims[-1]))
+    gout = oracle.mean_xent_grad(st.out, class_labels(len(targets), dims[-1]))
     grads = oracle.sage_backward(st, params, gout, mode="bf16")
     dws = [torch.full_like(t, 9.0) for t in to_dev(w_self)]
     dwn = [torch.full_like(t, 9.0) for t in to_dev(w_nbr)]
@@ -78,6 +78,20 @@ def run_case(dg, fanouts, dims, n_targets, seed, batch_index=0, direction=0, fea
     if want_dh0:
         n = len(d.node_ids)
         errs["dh0"] = row_rel_err(dh0[:n].cpu().numpy(), grads.d_h0)
+    if versus_exact:
+        # distance from the fp64 oracle without any operand rounding, same upstream gradient
+        st_e = oracle.sage_forward(d, h0_o, params, mode="exact")
+        gr_e = oracle.sage_backward(st_e, params, gout, mode="exact")
+        k = len(fanouts)
+        got = {"fwd": out.cpu().numpy()}
+        b16 = {"fwd": st.out}
+        exa = {"fwd": st_e.out}
+        for i in range(k):
+            for key, dev_t, gb, ge in (("dws%d" % (i + 1), dws[i], grads.d_w_self[i], gr_e.d_w_self[i]),
+                                       ("dwn%d" % (i + 1), dwn[i], grads.d_w_nbr[i], gr_e.d_w_nbr[i]),
+                                       ("db%d" % (i + 1), dbs[i], grads.d_bias[i], gr_e.d_bias[i])):
+                got[key], b16[key], exa[key] = dev_t.cpu().numpy(), gb, ge
+        exact_distance_report("run_case%s" % (dims,), got, b16, exa, d_out=dims[-1], layers=k, tol=TOL)
     return errs, (model, batch, h0, out, st, d)
 
 
@@ -90,13 +104,13 @@ def check(errs):
 def test_config0_forward_backward(g16k):
     cfg = CONFIGS[0]
     for bi in range(3):
-        errs, _ = run_case(g16k, cfg.fanouts, cfg.dims, cfg.batch, seed=bi, batch_index=bi, bias_scale=0.0)
+        errs, _ = run_case(g16k, cfg.fanouts, cfg.dims, cfg.batch, seed=bi, batch_index=bi, bias_scale=0.0, versus_exact=True)
         check(errs)
 
 
 def test_config1_forward_backward(g1m):
     cfg = CONFIGS[1]
-    errs, _ = run_case(g1m, cfg.fanouts, cfg.dims, cfg.batch, seed=0, batch_index=0, bias_scale=0.0)
+    errs, _ = run_case(g1m, cfg.fanouts, cfg.dims, cfg.batch, seed=0, batch_index=0, bias_scale=0.0, versus_exact=True)
     check(errs)
 
 
@@ -171,9 +185,9 @@ def test_degenerate_batches(g16k):
 def test_results_are_deterministic_run_to_run(g16k):
     cfg = CONFIGS[0]
     errs, (model, batch, h0, out, st, d) = run_case(g16k, cfg.fanouts, cfg.dims, cfg.batch, seed=3, want_dh0=True)
-    gout = torch.from_numpy(softmax_xent_grad(st.out, class_labels(cfg.batch, cfg.dims[-1]))).to("cuda:0")
+    gout = torch.from_numpy(oracle.mean_xent_grad(st.out, class_labels(cfg.batch, cfg.dims[-1]))).to("cuda:0")
     ref = None
-    for _ in range(5):
+    for _ in range(100):
         o = torch.empty_like(out)
         dn.sage_forward(model, batch, h0, o)
         dws = [torch.empty((a, b), device="cuda:0") for a, b in zip(cfg.dims[:-1], cfg.dims[1:])]

@@ -225,3 +225,142 @@ def test_bf16_backward_close_to_exact():
     for a, b in zip(ge.d_w_self + ge.d_w_nbr + ge.d_bias + [ge.d_h0], gb.d_w_self + gb.d_w_nbr + gb.d_bias + [gb.d_h0]):
         scale = np.abs(a).max() + 1e-12
         assert np.abs(a - b).max() / scale < 0.05
+
+
+def test_bf16_terms_error_bounds():
+    """One term is the nearest bfloat16 (8 significand bits: off by up to 2^-9 of the binade, so up to 2^-8 of the value);
+    two terms reproduce a bfloat16-representable value exactly and any other fp32 value to 2^-16 of it."""
+    rng = np.random.default_rng(5)
+    x = (rng.standard_normal(400000) * 10.0 ** rng.integers(-6, 6, 400000)).astype(np.float32)
+    x = x[np.abs(x) > 1e-30]
+    x64 = x.astype(np.float64)
+    e1 = np.abs(oracle.bf16_terms(x, 1) - x64) / np.abs(x64)
+    e2 = np.abs(oracle.bf16_terms(x, 2) - x64) / np.abs(x64)
+    assert e1.max() <= 2.0 ** -8 and e1.max() > 2.0 ** -9.5          # a single rounding is this coarse ...
+    assert e2.max() <= 2.0 ** -16 and e2.max() > 2.0 ** -18          # ... the second term buys eight more bits, not all 24
+    assert np.array_equal(oracle.bf16_terms(x, 1), oracle.round_bf16(x).astype(np.float64))
+    rep = oracle.round_bf16(x)                                         # representable: both forms are exact
+    assert np.array_equal(oracle.bf16_terms(rep, 1), rep.astype(np.float64))
+    assert np.array_equal(oracle.bf16_terms(rep, 2), rep.astype(np.float64))
+    # worked values: 1 + 2^-8 + 2^-12 -> hi = 1 + 2^-7 (above the tie), lo = -(2^-8 - 2^-12) = -15 * 2^-12, exact in bfloat16
+    v = np.array([1.0 + 2.0 ** -8 + 2.0 ** -12], dtype=np.float32)
+    assert oracle.bf16_terms(v, 1)[0] == 1.0 + 2.0 ** -7
+    assert oracle.bf16_terms(v, 2)[0] == float(v[0])
+    # 1 + 2^-9 + 2^-20: hi = 1, lo = bf16(2^-9 + 2^-20) = 2^-9 (the 2^-20 lies below lo's eight bits)
+    v = np.array([1.0 + 2.0 ** -9 + 2.0 ** -20], dtype=np.float32)
+    assert oracle.bf16_terms(v, 2)[0] == 1.0 + 2.0 ** -9
+
+
+def _rb1(x):
+    """nearest bfloat16 of one fp32 scalar, by torch's conversion (independent of the oracle's bit arithmetic)"""
+    return float(torch.tensor(float(np.float32(x)), dtype=torch.float32).to(torch.bfloat16).to(torch.float32))
+
+
+def _terms(x, n):
+    """scalar fp32 x as n bfloat16 terms, summed in fp64"""
+    x = np.float32(x)
+    hi = np.float32(_rb1(x))
+    if n == 1:
+        return float(hi)
+    return float(hi) + _rb1(np.float32(x - hi))
+
+
+def hand_two_layer_bf16(d, h0, params, gout, fwd_terms=(1, 2), dz_terms=(2, 1)):
+    """The bf16-operand reading of a TWO-layer encoder written out with scalar loops, forward and backward.
+    fwd_terms[i-1]: bfloat16 terms of layer i's [self | mean] operand; dz_terms[i-1]: terms of dZ^i in the gradient
+    contractions.  The reading under test is (1, 2) / (2, 1): what derives from the caller's inputs is one term, what
+    the device computed through an accumulation (H^1, its means, dZ^1) is two.  The neighbour mean is an fp32 sum in
+    ascending slot order and an fp32 division; H^1, dL/dH^1 are stored as fp32; weights are one term; everything
+    else is fp64."""
+    off = [int(v) for v in d.node_id_offsets]
+    N = off[-1]
+    nbr_off = [int(v) for v in d.nbr_offsets]
+    rmap = [int(v) for v in d.repr_map]
+    d0, d1, d2 = h0.shape[1], params.w_self[0].shape[1], params.w_self[1].shape[1]
+    W = [[np.vectorize(_rb1)(params.w_self[i]).astype(np.float64), np.vectorize(_rb1)(params.w_nbr[i]).astype(np.float64)]
+         for i in range(2)]
+    h0 = np.asarray(h0, dtype=np.float32)
+
+    def layer_forward(h_in, base_in, layer, d_in, d_out, terms):
+        """rows p >= off[layer]; h_in row r is node_ids position base_in + r"""
+        rows = N - off[layer]
+        a_self = np.zeros((rows, d_in)); a_mean = np.zeros((rows, d_in)); z = np.zeros((rows, d_out))
+        cnt = np.zeros(rows, dtype=np.int64)
+        for ro in range(rows):
+            p = off[layer] + ro
+            q = p - off[1]
+            seg = range(nbr_off[q], nbr_off[q + 1])
+            cnt[ro] = len(seg)
+            for c in range(d_in):
+                acc = np.float32(0.0)
+                for j in seg:
+                    acc = np.float32(acc + h_in[rmap[j] - base_in, c])
+                if len(seg):
+                    acc = np.float32(acc / np.float32(len(seg)))
+                a_mean[ro, c] = _terms(acc, terms)
+                a_self[ro, c] = _terms(h_in[p - base_in, c], terms)
+            for n in range(d_out):
+                s = float(params.bias[layer - 1][n])
+                for c in range(d_in):
+                    s += a_self[ro, c] * W[layer - 1][0][c, n] + a_mean[ro, c] * W[layer - 1][1][c, n]
+                z[ro, n] = s
+        return a_self, a_mean, z, cnt
+
+    s1, m1, z1, c1 = layer_forward(h0, 0, 1, d0, d1, fwd_terms[0])
+    h1 = np.maximum(z1, 0.0).astype(np.float32)
+    s2, m2, z2, c2 = layer_forward(h1, off[1], 2, d1, d2, fwd_terms[1])
+    out = z2.astype(np.float32)
+
+    def layer_backward(dz, a_self, a_mean, cnt, layer, base_in, rows_in, terms):
+        rows, d_out = dz.shape
+        d_in = a_self.shape[1]
+        dzb = np.array([[_terms(dz[r, n], terms) for n in range(d_out)] for r in range(rows)]).reshape(rows, d_out)
+        dws = np.zeros((d_in, d_out)); dwn = np.zeros((d_in, d_out)); db = np.zeros(d_out)
+        for r in range(rows):
+            for n in range(d_out):
+                db[n] += dz[r, n]                                  # the bias gradient sums the unrounded dZ
+                for c in range(d_in):
+                    dws[c, n] += a_self[r, c] * dzb[r, n]
+                    dwn[c, n] += a_mean[r, c] * dzb[r, n]
+        g_in = np.zeros((rows_in, d_in))
+        for r in range(rows):
+            p = off[layer] + r
+            q = p - off[1]
+            for c in range(d_in):
+                ds = sum(dzb[r, n] * W[layer - 1][0][c, n] for n in range(d_out))
+                dm = sum(dzb[r, n] * W[layer - 1][1][c, n] for n in range(d_out))
+                g_in[p - base_in, c] += ds
+                for j in range(nbr_off[q], nbr_off[q + 1]):
+                    g_in[rmap[j] - base_in, c] += dm / cnt[r]
+        return dws, dwn, db, g_in.astype(np.float32).astype(np.float64)
+
+    g2 = np.asarray(gout, dtype=np.float32).astype(np.float64)
+    dws2, dwn2, db2, g1 = layer_backward(g2, s2, m2, c2, 2, off[1], N - off[1], dz_terms[1])
+    dz1 = g1 * (z1 > 0.0)
+    dws1, dwn1, db1, g0 = layer_backward(dz1, s1, m1, c1, 1, 0, N, dz_terms[0])
+    return dict(out=out, h1=h1, dws=[dws1, dws2], dwn=[dwn1, dwn2], db=[db1, db2], dh0=g0)
+
+
+def test_two_layer_bf16_mode_equals_the_reading_written_out_with_loops():
+    """Pins mode="bf16" for more than one layer: one-term layer 1, two-term layer 2, one-term dZ^2, two-term dZ^1.
+    The same loops with the term counts swapped must NOT agree, so a swap in the oracle cannot pass."""
+    g, targets, d, table, params = small_case(61, n=40, avg_deg=3.0, fan=(3, 2), dims=(6, 5, 4), n_targets=5)
+    rng = np.random.default_rng(61)
+    h0 = oracle.dense_gather(table, d.node_ids).astype(np.float32)
+    gout = rng.standard_normal((len(targets), 4)).astype(np.float32)
+    st = oracle.sage_forward(d, h0, params, mode="bf16")
+    gr = oracle.sage_backward(st, params, gout, mode="bf16")
+    assert len(d.nbrs) > 20 and d.node_id_offsets[1] > 0             # both layers aggregate something
+
+    def distance(hand):
+        pairs = [(hand["out"], st.out), (hand["h1"], st.h[1]), (hand["dh0"], gr.d_h0)]
+        pairs += list(zip(hand["dws"], gr.d_w_self)) + list(zip(hand["dwn"], gr.d_w_nbr)) + list(zip(hand["db"], gr.d_bias))
+        return [float(np.abs(np.asarray(a, dtype=np.float64) - np.asarray(b, dtype=np.float64)).max()) for a, b in pairs]
+
+    same = distance(hand_two_layer_bf16(d, h0, params, gout))
+    assert max(same) < 1e-6, same
+    # the loops have the power to tell the readings apart: any other assignment of term counts is off by far more
+    for fwd_terms, dz_terms in (((2, 1), (2, 1)), ((1, 1), (2, 1)), ((1, 2), (1, 2)), ((1, 2), (1, 1)), ((2, 2), (2, 1)),
+                                ((1, 2), (2, 2))):
+        other = distance(hand_two_layer_bf16(d, h0, params, gout, fwd_terms, dz_terms))
+        assert max(other) > 2e-5, (fwd_terms, dz_terms, other)

@@ -11,7 +11,7 @@ wrapping int64 tensor ops, so the same graph is produced on the host and on the 
 from .configs import CONFIGS, WorkloadConfig, get_config
 from .rmat import rmat_csr, transpose_csr, mix64
 from .tensors import (feature_table, glorot_weights, target_batch, training_subset,
-                      class_labels, softmax_xent_grad, decoder_inputs, edge_batch, relation_embeddings)
+                      class_labels, decoder_inputs, edge_batch, relation_embeddings)
 
 
 
@@ -49,4 +49,4 @@ def make_inputs(cfg, device, n_batches: int = 64, log=None):
 
 __all__ = ["make_inputs", "CONFIGS", "WorkloadConfig", "get_config", "rmat_csr", "transpose_csr", "mix64",
            "feature_table", "glorot_weights", "target_batch", "training_subset",
-           "class_labels", "softmax_xent_grad", "decoder_inputs", "edge_batch", "relation_embeddings"]
+           "class_labels", "decoder_inputs", "edge_batch", "relation_embeddings"]

@@ -1,4 +1,4 @@
-"""Feature tables, Glorot weights, target batches and the harness's upstream gradient."""
+"""Feature tables, Glorot weights, target batches, class labels and link-prediction batches."""
 import math
 import numpy as np
 import torch
@@ -73,16 +73,6 @@ def target_batch(pool_size: int, batch: int, batch_index: int, seed: int = 4, po
 def class_labels(n: int, num_classes: int, seed: int = 5) -> np.ndarray:
     rng = np.random.Generator(np.random.PCG64(seed))
     return rng.integers(0, num_classes, size=n).astype(np.int64)
-
-
-def softmax_xent_grad(logits: np.ndarray, labels: np.ndarray) -> np.ndarray:
-    """Upstream gradient fed to the backward pass of both sides: d(mean cross-entropy)/d(logits)."""
-    z = logits.astype(np.float64)
-    z = z - z.max(axis=1, keepdims=True)
-    p = np.exp(z)
-    p /= p.sum(axis=1, keepdims=True)
-    p[np.arange(len(labels)), labels] -= 1.0
-    return (p / len(labels)).astype(np.float32)
 
 
 def decoder_inputs(n_rows: int, num_rel: int, dim: int, n_edges: int, chunk: int, num_neg: int, seed: int = 6,
