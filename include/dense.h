@@ -106,6 +106,29 @@ DN_API int  dn_batch_capacity(const dn_batch* b, int64_t* node_capacity, int64_t
 DN_API int  dense_sample(dn_batch* b, const dn_graph* g, const int32_t* d_targets, int32_t n_targets,
                   uint64_t seed, void* stream);
 
+/* ---- dense_sample_noalloc: dense_sample for callers that cannot allocate device memory or hold a workspace: code
+ *      under HIP-graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same sampling, same arrays,
+ *      bit for bit; the batch workspace is a static device array inside the library (64 MiB per GPU, held until
+ *      the process ends) and the five DENSE arrays are written straight into the caller's buffers.  The call
+ *      allocates nothing on the device (no hipMalloc / hipFree, no library that would), creates no handle, and
+ *      enqueues kernels only (no hipMemsetAsync).
+ *      k, fanouts (host array), direction: as in dn_batch_create.  Outputs (device, caller-owned):
+ *        d_node_id_offsets int32[k+2]; d_node_ids int32[node_capacity]; d_nbr_offsets int32[node_capacity + 1];
+ *        d_nbrs, d_repr_map int32[slot_capacity]; d_counts int32[3] = {N, E, status} with status != 0 for an invalid
+ *        target set (1 = id out of range, 2 = duplicate id, 4 = capacity), the arrays then unspecified but in bounds.
+ *      The capacities must cover the request's upper bound (DN_ECAPACITY otherwise, the message names the bound):
+ *        level_0 = max(n_targets, 1), level_{h+1} = min(V, level_h * fanouts[h] * m), m = 2 for DN_DIR_BOTH else 1;
+ *        slot_capacity >= sum_h level_h * fanouts[h] * m;  node_capacity >= min(V, sum of all levels).
+ *      Limit: graph and batch must fit the static array, about 4.3 bytes per node of the graph plus 8 bytes per
+ *      node and 12 bytes per slot of the bound (a 2^20-node graph with 1000 targets and fanouts 15/10/5 needs 23 MiB);
+ *      larger requests return DN_ECAPACITY and belong to dn_batch_create with a caller-supplied workspace.
+ *      Every call on one GPU uses that GPU's one array: calls that overlap in time on the same GPU (different streams
+ *      or threads) race and must be serialised by the caller; calls on different GPUs are independent. */
+DN_API int  dense_sample_noalloc(const dn_graph* g, const int32_t* d_targets, int32_t n_targets, int32_t k,
+                                 const int32_t* fanouts, int32_t direction, uint64_t seed,
+                                 int32_t* d_node_id_offsets, int32_t* d_node_ids, int32_t* d_nbr_offsets, int64_t node_capacity,
+                                 int32_t* d_nbrs, int32_t* d_repr_map, int64_t slot_capacity, int32_t* d_counts, void* stream);
+
 /* ---- dense_sample_edges: the link-prediction front end (Section 2: a training example is a pair of target
  *      nodes; Section 7.1: neighbours over incoming and outgoing edges).  The targets are the distinct ids
  *      among d_src[0..n_edges), d_dst[0..n_edges) and d_neg[0..n_neg), in ASCENDING id (they form Delta_k);

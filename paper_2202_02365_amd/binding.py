@@ -62,6 +62,7 @@ def load_library():
         "dn_batch_destroy": (None, [vp]),
         "dn_batch_capacity": (ctypes.c_int, [vp, ctypes.POINTER(i64), ctypes.POINTER(i64)]),
         "dense_sample": (ctypes.c_int, [vp, vp, vp, i32, u64, vp]),
+        "dense_sample_noalloc": (ctypes.c_int, [vp, vp, i32, i32, ctypes.POINTER(i32), i32, u64, vp, vp, vp, i64, vp, vp, i64, vp, vp]),
         "dense_sample_edges": (ctypes.c_int, [vp, vp, vp, vp, i32, vp, i32, u64, vp, vp, vp, vp]),
         "dn_embedding_sgd": (ctypes.c_int, [vp, vp, i32, i64, vp, ctypes.c_float, vp]),
         "dn_embedding_adagrad": (ctypes.c_int, [vp, vp, vp, i32, i64, vp, ctypes.c_float, ctypes.c_float, vp]),
@@ -350,6 +351,21 @@ def dense_sample(batch: Batch, graph: Graph, targets: torch.Tensor, seed: int) -
     batch._targets = targets
     _check(load_library().dense_sample(batch.handle, graph.handle, _dev_ptr(targets, torch.int32) if n else None,
                                        n, seed & 0xFFFFFFFFFFFFFFFF, _stream()))
+
+
+def dense_sample_noalloc(graph: Graph, targets: torch.Tensor, fanouts: Sequence[int], direction: int, seed: int,
+                         node_id_offsets: torch.Tensor, node_ids: torch.Tensor, nbr_offsets: torch.Tensor,
+                         nbrs: torch.Tensor, repr_map: torch.Tensor, counts: torch.Tensor) -> None:
+    """dense_sample into caller-provided int32 tensors, with the library's static scratch array as workspace."""
+    n = targets.numel()
+    assert node_id_offsets.numel() >= len(fanouts) + 2 and counts.numel() >= 3
+    assert nbr_offsets.numel() >= node_ids.numel() + 1 and repr_map.numel() >= nbrs.numel()
+    _check(load_library().dense_sample_noalloc(graph.handle, _dev_ptr(targets, torch.int32) if n else None, n, len(fanouts),
+                                               _i32_array(fanouts), direction, seed & 0xFFFFFFFFFFFFFFFF,
+                                               _dev_ptr(node_id_offsets, torch.int32), _dev_ptr(node_ids, torch.int32),
+                                               _dev_ptr(nbr_offsets, torch.int32), node_ids.numel(),
+                                               _dev_ptr(nbrs, torch.int32), _dev_ptr(repr_map, torch.int32), nbrs.numel(),
+                                               _dev_ptr(counts, torch.int32), _stream()))
 
 
 def dense_sample_edges(batch: Batch, graph: Graph, src: torch.Tensor, dst: torch.Tensor, neg: torch.Tensor, seed: int):

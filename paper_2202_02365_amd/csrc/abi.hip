@@ -50,13 +50,15 @@ int fill_batch_caps(dn_batch* b, int64_t V, int32_t max_targets, int32_t k, cons
     return DN_OK;
 }
 
-void carve_batch(dn_batch* b, Carver& c)
+// sample_only: no transpose index (the arrays of the backward pass stay null) and the four big DENSE arrays are
+// not carved: the caller of carve_batch points them at buffers of its own.
+void carve_batch(dn_batch* b, Carver& c, bool sample_only = false)
 {
     b->hdr = c.take<int32_t>(DN_HDR_WORDS);
     b->seen = c.take<uint32_t>(2 * b->words0);     // word pairs (seen, fresh), see sample.hip
     b->fresh = b->seen + 1;
     b->summary = c.take<uint32_t>(b->words1);
-    b->tr_hist_words = dn_transpose_index_hist_words(b);
+    b->tr_hist_words = sample_only ? 0 : dn_transpose_index_hist_words(b);
     b->tr_hist = c.take<int32_t>(b->tr_hist_words);          // starts at zero like the bitmaps
     b->lvlpos = c.take<int32_t>(b->V);
     b->lvl_ids = c.take<int32_t>(b->cap_nodes);
@@ -65,11 +67,12 @@ void carve_batch(dn_batch* b, Carver& c)
     b->lvl_owner = c.take<int32_t>(b->cap_slots);
     b->blk_a = c.take<int32_t>(2 * (int64_t)b->max_blocks + 2);    // used as uint64[max_blocks]
     b->blk_b = nullptr;
+    b->slot_owner = c.take<int32_t>(b->cap_slots);
+    if (sample_only) return;
     b->node_ids = c.take<int32_t>(b->cap_nodes);
     b->nbr_offsets = c.take<int32_t>(b->cap_nodes + 1);
     b->nbrs = c.take<int32_t>(b->cap_slots);
     b->repr_map = c.take<int32_t>(b->cap_slots);
-    b->slot_owner = c.take<int32_t>(b->cap_slots);
     for (int i = 0; i < 2; ++i) {
         b->tr_key[i] = c.take<int32_t>(b->cap_slots);
         b->tr_val[i] = c.take<int32_t>(b->cap_slots);
@@ -497,6 +500,92 @@ int sage_backward_sgd(dn_model* m, const dn_batch* b, const float* d_grad_out, f
         return dn_fail(DN_ESTATE, "sage_backward_sgd needs sage_forward on the same model and sample first");
     return dn_launch_backward(m, const_cast<dn_batch*>(b), d_grad_out, d_dw_self, d_dw_nbr, d_dbias, nullptr, d_table, ld_elems,
                               lr, static_cast<hipStream_t>(stream));
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// dense_sample for callers that cannot allocate: the batch workspace is a file-scope device array.
+// The array's name is a host-side stand-in in host code: its device address is looked up once per device with
+// hipGetSymbolAddress and only that address is handed to kernels.
+#define DN_NOALLOC_SCRATCH_BYTES ((size_t)64 << 20)
+static __device__ __align__(256) unsigned char scratch[DN_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int NOALLOC_MAX_DEVICES = 64;
+struct NoallocSlot {
+    void* ptr = nullptr;        // device address of this device's copy of `scratch`
+    dn_batch batch;             // host-side description of the carve-up of the last call
+};
+NoallocSlot g_noalloc[NOALLOC_MAX_DEVICES];
+std::mutex g_noalloc_mutex;
+
+__global__ void k_noalloc_clear(uint32_t* __restrict__ p, int64_t words)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < words; i += stride) p[i] = 0u;
+}
+
+// node_id_offsets (k + 2 entries) and {N, E, status flags} of the sample, from the header
+__global__ void k_noalloc_export(const int32_t* __restrict__ hdr, int k, int32_t* __restrict__ node_id_offsets,
+                                 int32_t* __restrict__ counts)
+{
+    const int t = threadIdx.x;
+    if (t <= k + 1) node_id_offsets[t] = hdr[HDR_NODE_OFF + t];
+    if (t == 0) { counts[0] = hdr[HDR_N]; counts[1] = hdr[HDR_E]; counts[2] = hdr[HDR_STATUS]; }
+}
+}  // namespace
+
+int dense_sample_noalloc(const dn_graph* g, const int32_t* d_targets, int32_t n_targets, int32_t k, const int32_t* fanouts,
+                         int32_t direction, uint64_t seed, int32_t* d_node_id_offsets, int32_t* d_node_ids,
+                         int32_t* d_nbr_offsets, int64_t node_capacity, int32_t* d_nbrs, int32_t* d_repr_map,
+                         int64_t slot_capacity, int32_t* d_counts, void* stream)
+{
+    if (!g) return dn_fail(DN_EINVAL, "graph is null");
+    if (!d_node_id_offsets || !d_node_ids || !d_nbr_offsets || !d_nbrs || !d_repr_map || !d_counts)
+        return dn_fail(DN_EINVAL, "null output array");
+    if (n_targets < 0) return dn_fail(DN_EINVAL, "n_targets is negative");
+    if (n_targets > 0 && !d_targets) return dn_fail(DN_EINVAL, "d_targets is null");
+    int dev = -1;
+    DN_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= NOALLOC_MAX_DEVICES) return dn_fail(DN_EINVAL, "device index %d is outside [0, %d)", dev, NOALLOC_MAX_DEVICES);
+    std::lock_guard<std::mutex> lock(g_noalloc_mutex);
+    NoallocSlot& slot = g_noalloc[dev];
+    if (!slot.ptr) {
+        // once per device, with that device current: every GPU holds its own copy of the array at its own address
+        void* p = nullptr;
+        DN_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return dn_fail(DN_EHIP, "hipGetSymbolAddress returned a null address");
+        slot.ptr = p;
+    }
+    dn_batch* b = &slot.batch;
+    int rc = fill_batch_caps(b, g->V, n_targets > 0 ? n_targets : 1, k, fanouts, direction);
+    if (rc) return rc;
+    if (b->direction != DN_DIR_IN && !g->rowptr[0]) return dn_fail(DN_EINVAL, "the graph has no out-edge adjacency");
+    if (b->direction != DN_DIR_OUT && !g->rowptr[1]) return dn_fail(DN_EINVAL, "the graph has no in-edge adjacency");
+    if (node_capacity < b->cap_nodes || slot_capacity < b->cap_slots)
+        return dn_fail(DN_ECAPACITY, "output arrays hold %lld nodes / %lld slots, the bound for this request is %lld / %lld",
+                       (long long)node_capacity, (long long)slot_capacity, (long long)b->cap_nodes, (long long)b->cap_slots);
+    Carver c(slot.ptr);
+    carve_batch(b, c, true);
+    if (c.bytes() > DN_NOALLOC_SCRATCH_BYTES)
+        return dn_fail(DN_ECAPACITY, "dense_sample_noalloc: this graph and batch need %zu bytes of scratch memory, the static "
+                       "array holds %zu (use dn_batch_create with a workspace of your own)", c.bytes(), (size_t)DN_NOALLOC_SCRATCH_BYTES);
+    b->workspace_bytes = c.bytes();
+    b->node_ids = d_node_ids; b->nbr_offsets = d_nbr_offsets; b->nbrs = d_nbrs; b->repr_map = d_repr_map;
+    b->n_targets = n_targets;
+    b->sample_serial = 1;
+    b->tr_serial = ~0ull;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // header and bitmaps must start at zero; the array keeps the last call's contents, carved for that call's sizes
+    const int64_t zero_words = (int64_t)((reinterpret_cast<char*>(b->lvlpos) - reinterpret_cast<char*>(b->hdr)) / 4);
+    int64_t grid = (zero_words + 255) / 256;
+    if (grid > 2048) grid = 2048;
+    hipLaunchKernelGGL(k_noalloc_clear, dim3((int)grid), dim3(256), 0, st, reinterpret_cast<uint32_t*>(b->hdr), zero_words);
+    DN_LAUNCH_CHECK("k_noalloc_clear");
+    rc = dn_launch_sample(b, g, d_targets, n_targets, seed, st);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_noalloc_export, dim3(1), dim3(64), 0, st, b->hdr, k, d_node_id_offsets, d_counts);
+    DN_LAUNCH_CHECK("k_noalloc_export");
+    return DN_OK;
 }
 
 int dn_profile_calibration_copy(void* d_dst, const void* d_src, size_t bytes, void* stream)
