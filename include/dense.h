@@ -166,7 +166,16 @@ DN_API int  dn_softmax_xent(const float* d_logits, int64_t ld_logits, const int3
  * (neighbour slots grouped by the row of H they read; with need_input_grad = 0 only the slots of layers
  * 2..k).  sage_backward builds it itself when this was not called for the current sample; calling it
  * right after dense_sample moves that work off the forward/backward chain, e.g. onto the stream
- * that constructs mini-batches. */
+ * that constructs mini-batches.
+ * HIP-graph capture: whether sage_backward enqueues the build is decided on the HOST when the call is made: it is
+ * skipped if a build for the batch's current sample was already issued, eager builds counting for eager calls and
+ * builds recorded into a graph for calls under capture.  So graphs captured from [dense_sample,
+ * dn_batch_prepare_backward] and then [sage_backward] hold one build between them, in the first graph, and the second
+ * graph is valid only behind a replay of the first; a sage_backward captured without a recorded
+ * dn_batch_prepare_backward for its sample holds its own build and can be replayed after any sample.  The device
+ * checks it: every sample carries a sequence number in the workspace, the build stamps the index with it, and a
+ * backward aggregation that finds another number computes nothing and raises a flag that dn_batch_counts returns as
+ * DN_ESTATE. */
 DN_API int  dn_batch_prepare_backward(dn_batch* b, int32_t need_input_grad, void* stream);
 
 /* Device pointers of the current sample. */

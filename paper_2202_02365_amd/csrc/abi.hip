@@ -254,6 +254,7 @@ int dn_batch_create(dn_batch** out, int64_t num_nodes, int32_t max_targets, int3
     if (e != hipSuccess) { delete b; return dn_fail(DN_EHIP, "hipMemsetAsync: %s", hipGetErrorString(e)); }
     b->sample_serial = 0;
     b->tr_serial = ~0ull;
+    b->tr_capture_serial = ~0ull;
     *out = b;
     return DN_OK;
 }
@@ -360,6 +361,9 @@ int dn_batch_counts(const dn_batch* b, int64_t* host_counts, void* stream)
     if (h[HDR_STATUS] & (ST_BAD_TARGET | ST_DUP_TARGET))
         return dn_fail(DN_ESAMPLE, "dense_sample: %s", (h[HDR_STATUS] & ST_BAD_TARGET) ? "target id out of range" : "duplicate target id");
     if (h[HDR_STATUS] & ST_CAPACITY) return dn_fail(DN_ECAPACITY, "dense_sample: node capacity exceeded");
+    if (h[HDR_STATUS] & ST_STALE_INDEX)
+        return dn_fail(DN_ESTATE, "sage_backward ran with a transpose index built for another sample of this batch (a captured "
+                       "graph replayed without the dn_batch_prepare_backward it was captured after); its gradients were not computed");
     return DN_OK;
 }
 
@@ -574,6 +578,7 @@ int dense_sample_noalloc(const dn_graph* g, const int32_t* d_targets, int32_t n_
     b->n_targets = n_targets;
     b->sample_serial = 1;
     b->tr_serial = ~0ull;
+    b->tr_capture_serial = ~0ull;
     hipStream_t st = static_cast<hipStream_t>(stream);
     // header and bitmaps must start at zero; the array keeps the last call's contents, carved for that call's sizes
     const int64_t zero_words = (int64_t)((reinterpret_cast<char*>(b->lvlpos) - reinterpret_cast<char*>(b->hdr)) / 4);

@@ -23,9 +23,12 @@ enum {
     HDR_NTARGETS = 28,
     HDR_TR_FIRST = 32,     // first slot covered by the transpose index
     HDR_TR_COUNT = 33,     // number of slots covered by it
+    HDR_SAMPLE_SEQ = 34,   // counts the samples built in this workspace (bumped on the device by the last sampling kernel)
+    HDR_TR_SEQ = 35,       // HDR_SAMPLE_SEQ of the sample the transpose index was built for
+    HDR_TR_ALL = 36,       // 1 if that index covers every slot (input gradient of layer 1), 0 if only layers 2..k
     DN_HDR_WORDS = 64
 };
-enum { ST_BAD_TARGET = 1, ST_DUP_TARGET = 2, ST_CAPACITY = 4 };
+enum { ST_BAD_TARGET = 1, ST_DUP_TARGET = 2, ST_CAPACITY = 4, ST_STALE_INDEX = 8 };
 
 struct dn_graph {
     int64_t V;
@@ -60,6 +63,8 @@ struct dn_batch {
     uint64_t sample_serial;                 // bumped by every dense_sample
     uint64_t tr_serial;                     // sample the transpose index was built for
     int32_t tr_covers_all;
+    uint64_t tr_capture_serial;             // the same pair for builds recorded into a HIP graph (not executed yet)
+    int32_t tr_capture_covers_all;
     size_t workspace_bytes;
 };
 
@@ -191,7 +196,8 @@ bool dn_sort_counts_separately(const dn_sort_plan& p);   // true: the caller's f
 // long_out beforehand).
 constexpr int DN_LONG_GROUP = 64;
 struct dn_sort_slot_info { const int32_t* slot_owner; const int32_t* nbr_offsets; int32_t* own_out; float* inv_out;
-                           int32_t* long_out; };
+                           int32_t* long_out;
+                           int32_t* hdr; int covers_all; };   // batch header: the last kernel stamps the index with the sample's sequence number
 int dn_sort_pairs_run(const dn_sort_plan& pl, const int32_t* count_ptr, int32_t* const key[2], int32_t* const val[2],
                       int32_t* hist_space, const int32_t* nkeys_ptr, int64_t nkeys_cap, int32_t* ptr_out, hipStream_t st,
                       const dn_sort_slot_info* info = nullptr);

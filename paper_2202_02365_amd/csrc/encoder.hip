@@ -222,7 +222,7 @@ __device__ __forceinline__ void sink_store_vec(const GradSink& k, int r, int p, 
 
 constexpr int HUB_ENTRIES_PER_BLOCK = 4;
 template <int V, int LANES, int ITERS>
-__global__ __launch_bounds__(TPB) void k_aggregate_bwd(const int32_t* __restrict__ hdr, int layer,
+__global__ __launch_bounds__(TPB) void k_aggregate_bwd(int32_t* __restrict__ hdr, int layer,
                                                        const int32_t* __restrict__ nbr_offsets,
                                                        const int32_t* __restrict__ tr_ptr, const int32_t* __restrict__ tr_val,
                                                        const int32_t* __restrict__ tr_own, const float* __restrict__ tr_inv,
@@ -231,6 +231,13 @@ __global__ __launch_bounds__(TPB) void k_aggregate_bwd(const int32_t* __restrict
                                                        const float* __restrict__ dX, int ldx, int d,
                                                        GradSink sink)
 {
+    // The transpose index must be the one built for the sample in the workspace (and cover layer 1's slots if this
+    // is layer 1).  The host checks that when it launches eagerly; a captured graph replayed after another sample has
+    // been drawn into the batch (without the build in the graph) is caught here: flag it and touch nothing.
+    if (hdr[HDR_TR_SEQ] != hdr[HDR_SAMPLE_SEQ] || (layer == 1 && hdr[HDR_TR_ALL] == 0)) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(&hdr[HDR_STATUS], ST_STALE_INDEX);
+        return;
+    }
     const int N = hdr[HDR_N];
     const int off_in = hdr[HDR_NODE_OFF + layer - 1];
     const int off_out = hdr[HDR_NODE_OFF + layer];

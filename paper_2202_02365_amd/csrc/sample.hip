@@ -419,6 +419,7 @@ __global__ __launch_bounds__(TPB) void k_assemble(int k, int32_t* __restrict__ h
         hdr[HDR_E] = E;
         hdr[HDR_STATUS] = hdr[HDR_STATUS_ACC];
         hdr[HDR_STATUS_ACC] = 0;
+        hdr[HDR_SAMPLE_SEQ] = hdr[HDR_SAMPLE_SEQ] + 1;           // a transpose index stamped with the old number is stale now
     }
 }
 

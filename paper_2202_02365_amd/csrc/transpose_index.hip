@@ -245,6 +245,11 @@ __global__ __launch_bounds__(TPB) void k_tr_ptr(const int32_t* __restrict__ coun
     const int N = nkeys_ptr ? *nkeys_ptr : nkeys_const, n = *count_ptr;
     const int tiles = dn_sort_tiles(n);
     const int stride = gridDim.x * TPB;
+    if (info.hdr && blockIdx.x == 0 && threadIdx.x == 0) {
+        // the index now belongs to the sample in the workspace: the backward aggregation checks this stamp on the device
+        info.hdr[HDR_TR_SEQ] = info.hdr[HDR_SAMPLE_SEQ];
+        info.hdr[HDR_TR_ALL] = info.covers_all;
+    }
     if (info.own_out) {
         for (int t = blockIdx.x * TPB + threadIdx.x; t < n; t += stride) {
             const int q = info.slot_owner[val[t]];
@@ -342,7 +347,7 @@ int dn_sort_pairs_run(const dn_sort_plan& pl, const int32_t* count_ptr, int32_t*
     }
     int64_t gp = (nkeys_cap + 1 + TPB - 1) / TPB;
     if (gp > 2048) gp = 2048;
-    dn_sort_slot_info si = { nullptr, nullptr, nullptr, nullptr, nullptr };
+    dn_sort_slot_info si = { nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0 };
     if (info) si = *info;
     hipLaunchKernelGGL(k_tr_ptr, dim3((int)gp), dim3(TPB), 0, st, count_ptr, nkeys_ptr, (int)nkeys_cap, key[0], ptr_out,
                        val[0], offs, pl.bits * (pl.passes - 1), 1 << pl.bits, si);
@@ -357,7 +362,14 @@ int64_t dn_transpose_index_hist_words(const dn_batch* b)
 
 int dn_launch_transpose_index(dn_batch* b, int need_all, hipStream_t st)
 {
-    if (b->tr_serial == b->sample_serial && (b->tr_covers_all || !need_all)) return DN_OK;
+    // Built already for this sample?  Work recorded into a HIP graph has not run: captured builds are tracked apart
+    // from executed ones, so that an eager call after a capture still builds, and a capture after an eager build too.
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cap) != hipSuccess) { (void)hipGetLastError(); cap = hipStreamCaptureStatusNone; }
+    const bool capturing = cap == hipStreamCaptureStatusActive;
+    uint64_t& serial = capturing ? b->tr_capture_serial : b->tr_serial;
+    int32_t& covers = capturing ? b->tr_capture_covers_all : b->tr_covers_all;
+    if (serial == b->sample_serial && (covers || !need_all)) return DN_OK;
     const dn_sort_plan pl = dn_sort_make_plan(b->cap_nodes, b->cap_slots);
     if (dn_sort_hist_words(pl) > b->tr_hist_words) return dn_fail(DN_ECAPACITY, "transpose index: histogram space");
     dn_prof_scope ps("transpose_index", 0, st);             // the whole sort counts as one step
@@ -370,11 +382,11 @@ int dn_launch_transpose_index(dn_batch* b, int need_all, hipStream_t st)
                        dn_sort_counts_separately(pl) ? nullptr : b->tr_hist, b->tr_long,
                        (int)b->tr_long_words);
     DN_LAUNCH_CHECK("k_tr_init");
-    const dn_sort_slot_info info = { b->slot_owner, b->nbr_offsets, b->tr_own, b->tr_inv, b->tr_long };
+    const dn_sort_slot_info info = { b->slot_owner, b->nbr_offsets, b->tr_own, b->tr_inv, b->tr_long, b->hdr, need_all ? 1 : 0 };
     const int rc = dn_sort_pairs_run(pl, b->hdr + HDR_TR_COUNT, b->tr_key, b->tr_val, b->tr_hist, b->hdr + HDR_N,
                                      b->cap_nodes, b->tr_ptr, st, &info);
     if (rc != DN_OK) return rc;
-    b->tr_serial = b->sample_serial;
-    b->tr_covers_all = need_all ? 1 : 0;
+    serial = b->sample_serial;
+    covers = need_all ? 1 : 0;
     return DN_OK;
 }
