@@ -109,7 +109,7 @@ def gemm_algorithmic_bytes(tag, sizes, cfg, dims):
     return None
 
 
-FORWARD_TAGS = ("targets", "init_", "hop_L", "last_delta", "assemble", "mark_ids", "local_ids", "gather", "aggregate_L",
+FORWARD_TAGS = ("init_", "sample_hop", "fresh_", "assemble", "mark_ids", "local_ids", "gather", "aggregate_L",
                 "aggregate_table_L", "gemm_fwd_L")
 
 

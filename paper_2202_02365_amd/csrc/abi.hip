@@ -43,14 +43,10 @@ int fill_batch_caps(dn_batch* b, int64_t V, int32_t max_targets, int32_t k, cons
     }
     if (b->cap_nodes > V) b->cap_nodes = V;
     if (b->cap_slots > 0x7fffff00LL) return dn_fail(DN_ECAPACITY, "more than 2^31 neighbour slots per batch");
-    // id ranges of the hop kernel: at most about two thousand of them, at least 1024 ids (one summary word) each
-    int shift = 10;
-    while (((V + ((int64_t)1 << shift) - 1) >> shift) > 2048) ++shift;
-    b->range_shift = shift;
-    b->n_ranges = (int32_t)((V + ((int64_t)1 << shift) - 1) >> shift);
-    b->words0 = (int64_t)b->n_ranges << (shift - 5);
-    b->words1 = b->words0 / 32;
-    b->max_blocks = (int32_t)((max_targets + 255) / 256);
+    b->words0 = (V + 31) / 32;
+    b->words1 = (b->words0 + 31) / 32;
+    const int64_t blocks_words = (b->words1 + 255) / 256, blocks_targets = (max_targets + 255) / 256;
+    b->max_blocks = (int32_t)(blocks_words > blocks_targets ? blocks_words : blocks_targets);
     return DN_OK;
 }
 
@@ -59,9 +55,9 @@ int fill_batch_caps(dn_batch* b, int64_t V, int32_t max_targets, int32_t k, cons
 void carve_batch(dn_batch* b, Carver& c, bool sample_only = false)
 {
     b->hdr = c.take<int32_t>(DN_HDR_WORDS);
-    b->bits = c.take<uint32_t>(4 * b->words0);     // [seen0, fresh0, seen1, fresh1] per 32 ids, see sample.hip
-    for (int p = 0; p < 2; ++p) b->summary2[p] = c.take<uint32_t>(b->words1);
-    for (int i = 0; i < 3; ++i) b->totals[i] = c.take<uint64_t>(b->n_ranges);
+    b->seen = c.take<uint32_t>(2 * b->words0);     // word pairs (seen, fresh), see sample.hip
+    b->fresh = b->seen + 1;
+    b->summary = c.take<uint32_t>(b->words1);
     b->tr_hist_words = sample_only ? 0 : dn_transpose_index_hist_words(b);
     b->tr_hist = c.take<int32_t>(b->tr_hist_words);          // starts at zero like the bitmaps
     b->lvlpos = c.take<int32_t>(b->V);
@@ -252,7 +248,7 @@ int dn_batch_create(dn_batch** out, int64_t num_nodes, int32_t max_targets, int3
     }
     b->workspace_bytes = c.bytes();
     hipStream_t st = static_cast<hipStream_t>(stream);
-    // header, bitmaps, per-range totals and the sort histograms are contiguous at the front: they must start at zero
+    // header, the three bitmaps and the sort histograms are contiguous at the front: they must start at zero
     const size_t zero_bytes = (size_t)(reinterpret_cast<char*>(b->lvlpos) - reinterpret_cast<char*>(b->hdr));
     hipError_t e = hipMemsetAsync(b->hdr, 0, zero_bytes, st);
     if (e != hipSuccess) { delete b; return dn_fail(DN_EHIP, "hipMemsetAsync: %s", hipGetErrorString(e)); }

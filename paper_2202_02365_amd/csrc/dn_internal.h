@@ -43,17 +43,11 @@ struct dn_batch {
     int64_t cap_level[DN_MAX_LAYERS + 1];   // node capacity per level
     int64_t cap_slots_hop[DN_MAX_LAYERS];   // slot capacity per hop
     int64_t cap_nodes, cap_slots;
-    // The node ids are cut into n_ranges ranges of 2^range_shift ids (one workgroup of the hop kernel each); the bitmaps
-    // cover whole ranges.  bits: four words per 32 ids [seen0, fresh0, seen1, fresh1]; summary2[p]: one bit per word of
-    // fresh_p; totals[3][n_ranges]: (nodes, slots) a level has in every range, rotating by level % 3.
-    int32_t range_shift, n_ranges;
-    int64_t words0, words1;                 // bitmap words: one bit per node / per bitmap word (padded to whole ranges)
-    int32_t max_blocks;                     // workgroups of the level-0 kernels at max_targets
+    int64_t words0, words1;                 // bitmap words: one bit per node / per bitmap word
+    int32_t max_blocks;
     // workspace carve-up (device pointers)
     int32_t* hdr;
-    uint32_t* bits;
-    uint32_t* summary2[2];
-    uint64_t* totals[3];
+    uint32_t *seen, *fresh, *summary;
     int32_t* lvlpos;                        // [V] node id -> staging position (valid for sampled nodes only)
     int32_t *lvl_ids, *lvl_nbr_offsets, *lvl_nbrs, *lvl_owner;
     int32_t *blk_a, *blk_b;
