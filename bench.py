@@ -27,34 +27,123 @@ def log(msg):
     print("[bench] " + msg, file=sys.stderr, flush=True)
 
 
+REPEATS = 5     # every timed block of K steps is run this often; the median block is reported
+
+
+def median_seconds(timed_block, repeats=REPEATS):
+    """Median of `repeats` runs of a block that times exactly K steps between two device synchronisations (a single
+    block of 20 steps is a 3 ms window; the median of five keeps one slow block from deciding the figure)."""
+    import numpy as np
+    times = sorted(timed_block() for _ in range(repeats))
+    return float(np.median(times)), times
+
+
+def dw_effective_splits(rows, kx, d_out, zterms, tile=128, max_splits=32, min_chunks=8):
+    """Reduction splits the weight-gradient GEMM of a layer actually uses for `rows` rows (the library chooses them on
+    the device: enough workgroups to fill the chip by capacity, then at least `min_chunks` k-steps of 64 rows per split)."""
+    tiles = -(-kx // tile) * -(-d_out // tile) * zterms
+    by_capacity = min(max_splits, -(-512 // tiles))
+    chunks = -(-int(rows) // 64)
+    return max(1, min(by_capacity, chunks // min_chunks))
+
+
 def algorithmic_work(tag, sizes, cfg, dims):
-    """Algorithmic bytes (HBM-bound kernels) or flops (GEMMs) of ONE launch of the kernel `tag`,
-    averaged over the batches; sizes = per-batch (node_id_offsets[0..k+1], E)."""
+    """Algorithmic bytes (HBM-bound kernels) or flops (GEMMs) of ONE launch of the kernel `tag`, averaged over the
+    batches.  sizes = per batch [node_id_offsets[0..k+1], E, S_1..S_k] with S_i = neighbour slots owned by
+    Delta_i..Delta_k (what layer i aggregates over).  Byte counts follow the data each step has to touch once:
+    16 B of row offsets per frontier node and direction, 4 B per adjacency entry read, 4 B per array entry written,
+    one 8-byte bitmap pair per claimed neighbour, a feature row per row read or written."""
     import numpy as np
     k = cfg.num_layers
     elt0 = 4 if cfg.feat_dtype == "f32" else 2
+    ndir = 2 if cfg.direction == 2 else 1
     off = np.array([s[:k + 2] for s in sizes], dtype=np.float64)      # [batches, k+2]
     E = np.array([s[k + 2] for s in sizes], dtype=np.float64)
+    S = np.array([list(s[k + 3:k + 3 + k]) + [0.0] for s in sizes], dtype=np.float64)   # S[:, i-1] = S_i, S_{k+1} = 0
     N = off[:, k + 1]
-    out = {}
+    mean = lambda x: float(np.mean(x))
+
+    def level_nodes(h):                    # level h = Delta_{k-h}
+        return off[:, k - h + 1] - off[:, k - h]
+
+    def hop_slots(h):                      # slots owned by level h
+        return S[:, k - h - 1] - S[:, k - h]
+
+    def layer_of(t):
+        return int(t.split("_L")[1])
+
     if tag == "gather":
-        return "hbm", float(np.mean(2 * N * dims[0] * elt0))
+        return "hbm", mean(2 * N * dims[0] * elt0)
+    if tag == "init_targets":
+        return "hbm", mean(level_nodes(0) * (4 + 16 * ndir + 8 + 12))
+    if tag == "init_offsets":
+        return "hbm", mean(level_nodes(0) * 8)
+    if tag in ("mark_ids", "local_ids") and cfg.lp_edges:
+        ids = 2.0 * cfg.lp_edges + cfg.lp_edges // cfg.lp_chunk * cfg.lp_negatives
+        return "hbm", ids * 12.0
+    if tag.startswith("sample_hop_L"):
+        h = layer_of(tag) - 1
+        return "hbm", mean(level_nodes(h) * (8 + 16 * ndir) + hop_slots(h) * (4 + 8 + 8))
+    if tag.startswith("fresh_count_hop") or tag.startswith("fresh_emit_hop"):
+        h = layer_of(tag) if "_L" in tag else 0      # forms level h (0: the link-prediction front end's targets)
+        new = level_nodes(h)
+        rowptr = 16 * ndir if h < k else 0
+        walk = cfg.num_nodes / 1024.0 * 4 + new * 8
+        if tag.startswith("fresh_count"):
+            return "hbm", mean(walk + new * rowptr)
+        return "hbm", mean(walk + new * (8 + 12 + rowptr))
+    if tag == "assemble":
+        return "hbm", mean(12 * N + 20 * E)
+    if tag == "transpose_index":
+        need_all = cfg.name.endswith("_lp")
+        pairs = E if need_all else (S[:, 1] if k >= 2 else 0 * E)
+        cap_nodes = cfg.capacity()[0]
+        passes = -(-max(1, int(np.ceil(np.log2(max(cap_nodes, 2))))) // 11)
+        return "hbm", mean(pairs * (8 + 16 * passes + 12) + (N + 1) * 4)
     if tag.startswith("aggregate_L") or tag.startswith("aggregate_table_L"):
         # aggregate_table_L1 reads the same rows from the feature table itself (plus 4 B of node id per row read)
-        i = int(tag.split("_L")[1])
+        i = layer_of(tag)
         rows = N - off[:, i]
-        # slots owned by Delta_i..Delta_k: unknown per layer on the host without the arrays; bounded by E, exact for layer 1
-        slots = np.array([s[k + 2 + i] for s in sizes], dtype=np.float64)
+        slots = S[:, i - 1]
         elt = elt0 if i == 1 else 4
         d = dims[i - 1]
         terms = 1 if i == 1 else 2
         ids = 4 * rows if "table" in tag else 0
-        return "hbm", float(np.mean((slots + rows) * d * elt + slots * 4 + ids + rows * 2 * d * terms * 2))
+        return "hbm", mean((slots + rows) * d * elt + slots * 4 + ids + rows * 2 * d * terms * 2)
+    if tag.startswith("aggregate_bwd_L"):
+        i = layer_of(tag)
+        d = dims[i - 1]
+        rows_in, rows_out, slots = N - off[:, i - 1], N - off[:, i], S[:, i - 1]
+        read = slots * (d * 4 + 12) + rows_out * d * 4 + rows_in * 8
+        if i >= 2:
+            np_pad = -(-dims[i - 1] // 64) * 64
+            write = rows_in * (d * 4 + 2 * np_pad * 2)           # ReLU mask row read, dZ of the layer below as two bf16 terms
+        elif cfg.name.endswith("_lp"):
+            write = rows_in * (2 * d * 4 + 4)                    # fused SGD: table row read and written, node id
+        else:
+            write = rows_in * d * 4
+        return "hbm", mean(read + write)
+    if tag.startswith("dz_L"):
+        i = layer_of(tag)
+        zt = 1 if i == k else 2
+        return "hbm", mean((N - off[:, i]) * dims[i] * (4 + 2 * zt))
+    if tag == "bwd_reduce_all":
+        total = 0.0
+        for i in range(1, k + 1):
+            xt, zt = (1 if i == 1 else 2), (1 if i == k else 2)
+            kx = 2 * dims[i - 1] * xt
+            eff = np.array([dw_effective_splits(r, kx, dims[i], zt) for r in (N - off[:, i])], dtype=np.float64)
+            total = total + eff * zt * kx * dims[i] * 4 + 2 * dims[i - 1] * dims[i] * 4
+        return "hbm", mean(total)
+    if tag == "softmax_xent":
+        return "hbm", float(cfg.batch * (dims[-1] * 8 + 8))
+    if tag in ("embedding_sgd", "embedding_adagrad"):
+        return "hbm", mean(N * dims[0] * 4 * (3 if tag.endswith("sgd") else 5))
     if tag.startswith("gemm_fwd_L"):
-        i = int(tag.split("_L")[1])
+        i = layer_of(tag)
         rows = N - off[:, i]
         terms = 1 if i == 1 else 2
-        return "mfma", float(np.mean(2 * rows * (2 * dims[i - 1] * terms) * dims[i]))
+        return "mfma", mean(2 * rows * (2 * dims[i - 1] * terms) * dims[i])
     if tag == "gemm_dw_all":               # the dW GEMMs of all layers share one launch
         total = 0.0
         for i in range(1, k + 1):
@@ -62,12 +151,12 @@ def algorithmic_work(tag, sizes, cfg, dims):
             xt = 1 if i == 1 else 2
             zt = 1 if i == k else 2
             total = total + 2 * rows * (2 * dims[i - 1] * xt) * dims[i] * zt
-        return "mfma", float(np.mean(total))
+        return "mfma", mean(total)
     if tag.startswith("gemm_dx_L"):
-        i = int(tag.split("_L")[1])
+        i = layer_of(tag)
         rows = N - off[:, i]
         zt = 1 if i == k else 2
-        return "mfma", float(np.mean(2 * rows * (2 * dims[i - 1]) * dims[i] * zt))
+        return "mfma", mean(2 * rows * (2 * dims[i - 1]) * dims[i] * zt)
     if tag.startswith("dm_") and cfg.lp_edges:
         pairs = 2.0 * cfg.lp_edges * cfg.lp_negatives            # (edge, negative) pairs of both corrupted sides
         d = dims[-1]
@@ -138,8 +227,37 @@ def measured_traffic(workload, tag):
     return None
 
 
-def cpu_baseline(cfg, inputs, sizes, budget_s=20.0):
-    """The oracle as it stands, timed on the host: sample + gather + forward + backward per batch."""
+def host_description():
+    """CPU model, usable cores and the C oracle's compiler flags, stated beside every oracle timing."""
+    import oracle
+    model = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count() or 1
+    return {"cpu_model": model, "nproc": os.cpu_count(), "usable_cores": usable,
+            "omp_num_threads_env": os.environ.get("OMP_NUM_THREADS"),
+            "c_oracle_build": "gcc " + " ".join(oracle.GCC_FLAGS) + " (OpenMP leg: the same plus -fopenmp)"}
+
+
+def blas_threads():
+    try:
+        from threadpoolctl import threadpool_info
+        return int(max([p.get("num_threads", 1) for p in threadpool_info()] + [1]))
+    except Exception:
+        return os.cpu_count() or 1
+
+
+def cpu_baseline(cfg, inputs, sizes, budget_s=16.0):
+    """The oracle as it stands, timed on the host: sample + gather + forward + backward per batch with the
+    single-threaded C sampler, then the sampler alone again from the OpenMP build of the same source."""
     import numpy as np
     import torch
     import oracle
@@ -154,30 +272,53 @@ def cpu_baseline(cfg, inputs, sizes, budget_s=20.0):
     table = inputs["table"]
     labels = class_labels(cfg.batch, cfg.dims[-1])
     done, edges, spent = 0, 0, 0.0
+    stage = {"sample": 0.0, "gather": 0.0, "forward": 0.0, "backward": 0.0}
     while done < N_BATCHES and (done < 2 or spent < budget_s):
         targets = inputs["targets"][done]
         t0 = time.time()
         d = oracle.dense_sample(g, targets, cfg.fanouts, seed=done, direction=cfg.direction)
-        t_fetch = time.time()
+        t1 = time.time()
         rows = table[torch.from_numpy(d.node_ids.astype(np.int64)).to(table.device)].float().cpu().numpy()
-        fetch = time.time() - t_fetch                    # device->host row fetch stands in for the host-side gather
+        t2 = time.time()                                 # device->host row fetch stands in for the host-side gather
         st = oracle.sage_forward(d, rows, params, mode="bf16")
+        t3 = time.time()
         gout = oracle.mean_xent_grad(st.out, labels[:len(targets)])
         oracle.sage_backward(st, params, gout, mode="bf16")
-        spent += time.time() - t0
+        t4 = time.time()
+        for name, dt in zip(("sample", "gather", "forward", "backward"), (t1 - t0, t2 - t1, t3 - t2, t4 - t3)):
+            stage[name] += dt
+        spent += t4 - t0
         edges += len(d.nbrs)
         done += 1
         log("cpu_baseline: batch %d, %.2fs so far" % (done, spent))
+    # the sampler alone on all cores (Section 4.1 runs the one-hop samples of a level on several threads)
+    host = host_description()
+    omp_threads = int(os.environ.get("OMP_NUM_THREADS") or host["usable_cores"])
+    omp_done, omp_edges, omp_spent = 0, 0, 0.0
+    oracle.use_openmp(True)
     try:
-        from threadpoolctl import threadpool_info
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    except Exception:
-        threads = os.cpu_count() or 1
+        while omp_done < N_BATCHES and (omp_done < 2 or omp_spent < 4.0):
+            t0 = time.time()
+            d = oracle.dense_sample(g, inputs["targets"][omp_done], cfg.fanouts, seed=omp_done, direction=cfg.direction)
+            omp_spent += time.time() - t0
+            omp_edges += len(d.nbrs)
+            omp_done += 1
+    finally:
+        oracle.use_openmp(False)
+    threads = blas_threads()
     return {"value": edges / spent, "unit": "sampled edges/s", "cores": int(threads), "kind": "oracle",
             "sample": "%d mini-batches of the same workload (sample+gather+forward+backward, %.1f s; C sampler is "
                       "single-threaded, NumPy GEMMs use the BLAS threads counted in cores; feature rows fetched "
                       "from the device table)" % (done, spent),
-            "mini_batches_per_s": done / spent}
+            "mini_batches_per_s": done / spent,
+            "seconds_per_batch_by_stage": {name: t / done for name, t in stage.items()},
+            "sampler_alone": {"single_thread_edges_per_s": edges / stage["sample"],
+                              "openmp_edges_per_s": omp_edges / omp_spent, "openmp_threads": omp_threads,
+                              "openmp_batches": omp_done,
+                              "note": "the OpenMP build parallelises the per-node one-hop samples of a level; computing "
+                                      "the next Delta and the concatenations stay serial"},
+            "host": host,
+            "note": "a plain oracle, not a tuned CPU baseline"}
 
 
 def run_link_prediction(args, cfg):
@@ -257,14 +398,14 @@ def run_link_prediction(args, cfg):
 
     steps, warmup = args.steps, args.warmup
     timed(warmup, [slot])
-    serial_s = timed(steps, [slot])
+    serial_s, _ = median_seconds(lambda: timed(steps, [slot]), 3)
     total_s, in_flight = serial_s, "1 mini-batch"
     if args.replicas > 1:
         # replicas update the shared embedding table without waiting for each other (rows of concurrent batches
         # rarely coincide; the paper's pipeline applies such updates with bounded staleness too, Section 3)
         slots = [slot] + [make_slot() for _ in range(args.replicas - 1)]
         timed(max(warmup, len(slots)), slots)
-        rep_s = timed(steps, slots)
+        rep_s, _ = median_seconds(lambda: timed(steps, slots), 3)
         log("%d replicas: %.3f ms/step; one at a time: %.3f ms/step" % (len(slots), 1e3 * rep_s / steps, 1e3 * serial_s / steps))
         if rep_s < total_s:
             total_s, in_flight = rep_s, "%d mini-batches, each on a stream of its own, launched eagerly" % len(slots)
@@ -357,15 +498,12 @@ def cpu_baseline_link_prediction(cfg, inputs, batches, R, budget_s=20.0):
         edges += len(d.nbrs)
         done += 1
         log("cpu_baseline: batch %d, %.2fs so far" % (done, spent))
-    try:
-        from threadpoolctl import threadpool_info
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    except Exception:
-        threads = os.cpu_count() or 1
+    threads = blas_threads()
     return {"value": edges / spent, "unit": "sampled edges/s", "cores": int(threads), "kind": "oracle",
             "sample": "%d mini-batches of the same workload (%.1f s; C sampler is single-threaded, NumPy contractions use "
                       "the BLAS threads counted in cores; feature rows fetched from the device table)" % (done, spent),
-            "training_edges_per_s": cfg.lp_edges * done / spent}
+            "training_edges_per_s": cfg.lp_edges * done / spent, "host": host_description(),
+            "note": "a plain oracle, not a tuned CPU baseline"}
 
 
 def main():
@@ -612,7 +750,7 @@ def main():
                 (n_rep, "whole step" if backward else "forward only", n, 1e3 * queued / n, 1e3 * spent / n))
             return spent
         run(max(args.warmup, n_rep))
-        spent = run(n_steps)
+        spent, _ = median_seconds(lambda: run(n_steps))
         if backward:
             # with every replica busy, the one that runs batch 5 must give the gradients of the one-at-a-time step
             for r, o in enumerate(reps):
@@ -632,23 +770,23 @@ def main():
     for s in range(args.also_two_step):
         step(s % N_BATCHES, separate=True)
     timed(args.warmup)
-    serial_s = timed(args.steps)
-    serial_fwd_s = timed(args.steps, backward=False)
+    serial_s, serial_all = median_seconds(lambda: timed(args.steps))
+    serial_fwd_s, _ = median_seconds(lambda: timed(args.steps, backward=False))
     # one-at-a-time reference for batch 5, to compare a graph replay and a replica's step with
     step(5)
     torch.cuda.synchronize()
     eager = [t.clone() for t in dws + dwn + dbs + [out]]
     if args.no_graphs:
         timed_pipelined(args.warmup)
-        total_s = timed_pipelined(args.steps)
-        fwd_only_s = timed_pipelined(args.steps, backward=False)
+        total_s, _ = median_seconds(lambda: timed_pipelined(args.steps))
+        fwd_only_s, _ = median_seconds(lambda: timed_pipelined(args.steps, backward=False))
     else:
         assert N_BATCHES % 2 == 0
         capture_graphs(True)
         capture_graphs(False)
         timed_graphs(args.warmup)
-        total_s = timed_graphs(args.steps)
-        fwd_only_s = timed_graphs(args.steps, backward=False)
+        total_s, _ = median_seconds(lambda: timed_graphs(args.steps))
+        fwd_only_s, _ = median_seconds(lambda: timed_graphs(args.steps, backward=False))
         with torch.cuda.stream(s_compute):
             graphs[(4, True)].replay()           # constructs batch 5
             graphs[(5, True)].replay()           # forward + backward of batch 5
@@ -677,7 +815,7 @@ def main():
                          % args.replicas)
 
     # per-kernel durations: the same K steps again, every launch bracketed by HIP events on its stream
-    roofline, kernels, copy_gbs = None, {}, None
+    roofline, kernels, copy_gbs, whole_step = None, {}, None, None
     if not args.no_kernel_times:
         # The event pairs time what the GPU does only if the host is ahead of it: every step is preceded by
         # a ~1 ms streaming copy (not bracketed) during which the host queues the whole step.
@@ -712,8 +850,11 @@ def main():
         del delay_src, delay_dst
         # an event pair around nothing already reads a few microseconds: subtract that from every bracket
         empty_ms, empty_n = prof.pop("empty_bracket", (0.0, 1))
-        noop_ms, noop_n = prof.pop("noop_kernel_bracket", (0.0, 1))
+        prof.pop("noop_kernel_bracket", None)
         bracket_us = 1e3 * empty_ms / max(empty_n, 1)
+        # launch latency as such: median bracket around a kernel that does nothing, less the median empty bracket (the
+        # first launch of that kernel loads its code object, which a mean would carry)
+        noop_us = 1e3 * (prof_pct["noop_kernel_bracket"][3] - prof_pct["empty_bracket"][3]) if "noop_kernel_bracket" in prof_pct else 0.0
         kernels = {tag: {"avg_us": max(1e3 * ms / n - bracket_us, 0.0), "launches_per_step": n / args.steps}
                    for tag, (ms, n) in prof.items()}
         for tag, v in kernels.items():
@@ -744,8 +885,28 @@ def main():
                 v["flop_per_byte"] = intensity
                 v["attainable_TFLOPs"] = attainable / 1e12
                 v["frac_of_attainable"] = rate / attainable
+            v["algorithmic_per_launch"] = work
+            traffic = measured_traffic(cfg.name, tag)
+            if traffic is not None:
+                v["traffic_bytes_per_launch"] = traffic
+                moved = work if bound == "hbm" else gemm_bytes
+                if moved:
+                    v["traffic_over_algorithmic"] = traffic / moved
             per_step_us = v["avg_us"] * v["launches_per_step"]
             candidates.append((per_step_us, tag, bound, work, v["avg_us"]))
+        # the whole step against the HBM roofline: algorithmic bytes of every launch of a step (a GEMM counts with its
+        # operand and result bytes) over the measured step time
+        step_bytes = 0.0
+        for tag, v in kernels.items():
+            if v["launches_per_step"] <= 0 or "bound" not in v:
+                continue
+            b = v["algorithmic_per_launch"] if v["bound"] == "hbm" else (gemm_algorithmic_bytes(tag, used, cfg, dims) or 0.0)
+            step_bytes += b * v["launches_per_step"]
+        whole_step = {"algorithmic_bytes_per_step": step_bytes,
+                      "hbm_frac_one_in_flight": step_bytes / (serial_s / args.steps) / (HBM_PEAK_GBS * 1e9),
+                      "hbm_frac_reported_mode": step_bytes / (total_s / args.steps) / (HBM_PEAK_GBS * 1e9),
+                      "kernel_time_sum_us": step_sum_us,
+                      "untagged_kernels": sorted(t for t, v in kernels.items() if "bound" not in v)}
         best = pick_dominant(candidates, True)
         if best is not None:
             _, tag, bound, work, avg_us = best
@@ -760,7 +921,7 @@ def main():
                         "event_bracket_overhead_us_subtracted": bracket_us,
                         # a bracket around a kernel that does nothing reads this much more than an empty one: the latency
                         # of a launch as such, still contained in avg_us (rocprofv3's own durations do not contain it)
-                        "launch_latency_us_not_subtracted": max(1e3 * noop_ms / max(noop_n, 1) - bracket_us, 0.0)}
+                        "launch_latency_us_not_subtracted": max(noop_us, 0.0)}
 
     if args.copy_calibration:
         src = torch.empty(64 << 20, dtype=torch.float32, device=dev).normal_()
@@ -803,7 +964,11 @@ def main():
         "one_in_flight": {"ms_per_step": 1e3 * serial_s / args.steps, "mini_batches_per_s": args.steps / serial_s,
                           "sampled_edges_per_s": edges / serial_s,
                           "sample_gather_fwd_ms_per_step": 1e3 * serial_fwd_s / args.steps},
+        "repeats": REPEATS,
+        "timing": "every figure is the median of %d timed blocks of `steps` steps" % REPEATS,
+        "one_in_flight_blocks_ms": [1e3 * t / args.steps for t in serial_all],
         "roofline": roofline,
+        "whole_step": whole_step,
         "streaming_copy_GBs": copy_gbs,
         "kernels": kernels,
         "cpu_baseline": baseline,

@@ -24,42 +24,63 @@ _LIB = os.path.join(_HERE, "libdense_oracle.so")
 _lib = None
 
 
+_LIB_OMP = os.path.join(_HERE, "libdense_oracle_omp.so")
+_lib_omp = None
+_use_openmp = False
+GCC_FLAGS = ["-O2", "-std=c11", "-Wall", "-Wextra", "-shared", "-fPIC"]
+
+
 def build(force: bool = False) -> str:
-    """Compile dense_oracle.c with gcc into libdense_oracle.so beside it."""
-    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
-    if force or stale:
-        tmp = _LIB + ".tmp.%d" % os.getpid()
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-shared", "-fPIC",
-                               _SRC, "-o", tmp])
-        os.replace(tmp, _LIB)
+    """Compile dense_oracle.c with gcc into libdense_oracle.so beside it (single-threaded) and, from the same file
+    with -fopenmp, libdense_oracle_omp.so, whose per-node sampling loop runs on all cores."""
+    for lib, extra in ((_LIB, []), (_LIB_OMP, ["-fopenmp"])):
+        stale = (not os.path.exists(lib)) or os.path.getmtime(lib) < os.path.getmtime(_SRC)
+        if force or stale:
+            tmp = lib + ".tmp.%d" % os.getpid()
+            subprocess.check_call(["gcc"] + GCC_FLAGS + extra + [_SRC, "-o", tmp])
+            os.replace(tmp, lib)
     return _LIB
 
 
+def use_openmp(on: bool) -> None:
+    """Route the C entry points to the OpenMP build (same source, same results; threads from OMP_NUM_THREADS)."""
+    global _use_openmp
+    _use_openmp = bool(on)
+
+
+def _bind(path):
+    lib = ctypes.CDLL(path)
+    i64p = ctypes.POINTER(ctypes.c_int64)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    u32p = ctypes.POINTER(ctypes.c_uint32)
+    lib.orc_philox4x32_10.argtypes = [u32p, u32p, u32p]
+    lib.orc_philox4x32_10.restype = None
+    lib.orc_floyd_positions.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64, ctypes.c_uint32,
+                                        ctypes.c_uint32, ctypes.c_uint32, i64p]
+    lib.orc_floyd_positions.restype = None
+    lib.orc_onehop.argtypes = [i64p, i32p, i64p, i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                               ctypes.c_uint64, ctypes.c_uint32, i32p]
+    lib.orc_onehop.restype = ctypes.c_int32
+    lib.orc_dense_sample.argtypes = [ctypes.c_int64, i64p, i32p, i64p, i32p, ctypes.c_int32,
+                                     i32p, ctypes.c_int32, ctypes.c_int32, i32p, ctypes.c_uint64,
+                                     ctypes.c_int64, ctypes.c_int64,
+                                     i64p, i32p, i64p, i32p, i32p, i64p]
+    lib.orc_dense_sample.restype = ctypes.c_int
+    lib.orc_dense_gather.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, i32p, ctypes.c_int64,
+                                     ctypes.c_void_p]
+    lib.orc_dense_gather.restype = None
+    return lib
+
+
 def _load():
-    global _lib
+    global _lib, _lib_omp
     if _lib is None:
         build()
-        lib = ctypes.CDLL(_LIB)
-        i64p = ctypes.POINTER(ctypes.c_int64)
-        i32p = ctypes.POINTER(ctypes.c_int32)
-        u32p = ctypes.POINTER(ctypes.c_uint32)
-        lib.orc_philox4x32_10.argtypes = [u32p, u32p, u32p]
-        lib.orc_philox4x32_10.restype = None
-        lib.orc_floyd_positions.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64, ctypes.c_uint32,
-                                            ctypes.c_uint32, ctypes.c_uint32, i64p]
-        lib.orc_floyd_positions.restype = None
-        lib.orc_onehop.argtypes = [i64p, i32p, i64p, i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
-                                   ctypes.c_uint64, ctypes.c_uint32, i32p]
-        lib.orc_onehop.restype = ctypes.c_int32
-        lib.orc_dense_sample.argtypes = [ctypes.c_int64, i64p, i32p, i64p, i32p, ctypes.c_int32,
-                                         i32p, ctypes.c_int32, ctypes.c_int32, i32p, ctypes.c_uint64,
-                                         ctypes.c_int64, ctypes.c_int64,
-                                         i64p, i32p, i64p, i32p, i32p, i64p]
-        lib.orc_dense_sample.restype = ctypes.c_int
-        lib.orc_dense_gather.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, i32p, ctypes.c_int64,
-                                         ctypes.c_void_p]
-        lib.orc_dense_gather.restype = None
-        _lib = lib
+        _lib = _bind(_LIB)
+    if _use_openmp:
+        if _lib_omp is None:
+            _lib_omp = _bind(_LIB_OMP)
+        return _lib_omp
     return _lib
 
 
@@ -206,7 +227,7 @@ from .sage import (round_bf16, bf16_terms, dense_layer_view, sage_forward, sage_
 from .distmult import distmult_forward, distmult_backward, DistMultState  # noqa: E402
 from .heads import softmax_xent, mean_xent_grad, embedding_adagrad  # noqa: E402
 
-__all__ = ["build", "philox4x32_10", "floyd_positions", "Graph", "Dense", "onehop", "dense_sample",
+__all__ = ["build", "use_openmp", "GCC_FLAGS", "philox4x32_10", "floyd_positions", "Graph", "Dense", "onehop", "dense_sample",
            "dense_sample_edges", "embedding_sgd",
            "dense_gather", "round_bf16", "dense_layer_view", "sage_forward", "sage_backward",
            "SageParams", "ForwardState", "distmult_forward", "distmult_backward", "DistMultState",

@@ -1,6 +1,6 @@
 /*
- * dense_oracle.c -- plain, slow, single-threaded CPU oracle for DENSE mini-batch
- * construction.  TEST INFRASTRUCTURE ONLY: it is called by the tests, by the smoke
+ * dense_oracle.c -- plain, slow CPU oracle for DENSE mini-batch construction (single-threaded; one loop, the
+ * per-node one-hop sample, carries an OpenMP pragma that a second build of the same file switches on).  TEST INFRASTRUCTURE ONLY: it is called by the tests, by the smoke
  * check and by the benchmark's cpu_baseline leg; the product path never links,
  * loads or calls it, and it shares no code with the HIP kernels.
  *
@@ -190,15 +190,28 @@ int orc_dense_sample(int64_t V,
         const int32_t hop = k - i;                 /* distance of Delta_i from the targets */
         const int32_t f = fanouts[hop];
 
-        /* Line 4: Delta_i_nbrs, Delta_i_offsets = oneHopSample(Delta_i, fanouts[i]) */
-        int32_t* d_nbrs = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n_delta * f * ndir + 1));
+        /* Line 4: Delta_i_nbrs, Delta_i_offsets = oneHopSample(Delta_i, fanouts[i]).
+         * The nodes' samples are independent of each other (Section 4.1 runs them on several threads): every node
+         * samples into a stretch of its own, long enough for the largest sample; the stretches are then packed in
+         * node order.  Built with -fopenmp the first loop runs on all cores; without it the pragma is ignored.
+         * The result is the same either way. */
+        const int64_t stretch = (int64_t)f * ndir;
+        int32_t* sampled = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n_delta * stretch + 1));
+        int32_t* sampled_count = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n_delta + 1));
+#pragma omp parallel for schedule(dynamic, 256)
+        for (int64_t q = 0; q < n_delta; ++q)
+            sampled_count[q] = orc_onehop(rowptr_out, col_out, rowptr_in, col_in, direction,
+                                          delta[q], f, seed, (uint32_t)hop, sampled + q * stretch);
+        int32_t* d_nbrs = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n_delta * stretch + 1));
         int64_t* d_offsets = (int64_t*)malloc(sizeof(int64_t) * (size_t)(n_delta + 1));
         int64_t n_d_nbrs = 0;
         for (int64_t q = 0; q < n_delta; ++q) {
             d_offsets[q] = n_d_nbrs;
-            n_d_nbrs += orc_onehop(rowptr_out, col_out, rowptr_in, col_in, direction,
-                                   delta[q], f, seed, (uint32_t)hop, d_nbrs + n_d_nbrs);
+            if (sampled_count[q] > 0)
+                memcpy(d_nbrs + n_d_nbrs, sampled + q * stretch, sizeof(int32_t) * (size_t)sampled_count[q]);
+            n_d_nbrs += sampled_count[q];
         }
+        free(sampled); free(sampled_count);
 
         /* Line 5: nbr_offsets = cat(Delta_i_offsets, nbr_offsets + len(Delta_i_nbrs)) */
         int64_t* new_nbr_offsets = cat_i64_shift(d_offsets, n_delta, nbr_offsets, n_nbr_off, n_d_nbrs);

@@ -138,7 +138,7 @@ void carve_model(dn_model* m, const dn_batch* b, Carver& c)
         max_dx = std::max<int64_t>(max_dx, L.rows_pad * 2 * L.d_in);
     }
     m->dx = c.take<float>(max_dx);
-    m->fix_count = c.take<int32_t>(64);
+    m->fix_count = c.take<int32_t>(DN_FIX_WORDS);
     (void)b;
 }
 
@@ -430,8 +430,13 @@ int dn_model_status(const dn_model* m, int32_t* status, void* stream)
 {
     if (!m || !status) return dn_fail(DN_EINVAL, "null argument");
     hipStream_t st = static_cast<hipStream_t>(stream);
-    DN_HIP(hipMemcpyAsync(status, m->fix_count, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    int32_t words[DN_FIX_WORDS];
+    DN_HIP(hipMemcpyAsync(words, m->fix_count, sizeof(words), hipMemcpyDeviceToHost, st));
     DN_HIP(hipStreamSynchronize(st));
+    int32_t total = 0;
+    for (int j = 0; j < DN_FIX_SLOTS; ++j) total += words[DN_FIX_FIRST + DN_FIX_STRIDE * j];
+    status[0] = total;
+    status[1] = words[1];
     return DN_OK;
 }
 

@@ -103,13 +103,19 @@ struct dn_model {
     int32_t splits;
 
     // pre-activations too close to zero for the fp32 accumulation to settle their sign
-    int32_t* fix_count;            // [0] exact recomputations in the last ReLU layer, [1] sticky overflow flag
+    // exact recomputations in the last ReLU layer: DN_FIX_SLOTS counters on cache lines of their own (a workgroup adds to
+    // slot (workgroup number % DN_FIX_SLOTS): one counter for all would queue a thousand atomics on one line), at
+    // fix_count[DN_FIX_FIRST + DN_FIX_STRIDE * j]; [1] sticky overflow flag
+    int32_t* fix_count;
     const void* h0;                // H^0 of the last forward
     uint64_t fwd_serial;           // sample the saved activations belong to
     int32_t weights_set;
     int32_t mean_agg;              // 1: neighbour mean (default), 0: neighbour sum (Algorithm 3 as printed)
     size_t workspace_bytes;
 };
+
+constexpr int DN_FIX_SLOTS = 32, DN_FIX_STRIDE = 16, DN_FIX_FIRST = 64;
+constexpr int DN_FIX_WORDS = DN_FIX_FIRST + DN_FIX_SLOTS * DN_FIX_STRIDE;
 
 // error plumbing (abi.cpp)
 int dn_fail(int code, const char* fmt, ...);

@@ -41,7 +41,7 @@ __global__ __launch_bounds__(TPB) void k_aggregate(const int32_t* __restrict__ h
     const int rows = N - off_out;
     const int lane = threadIdx.x % LANES;
     constexpr int GROUPS = TPB / LANES;
-    if (blockIdx.x == 0 && threadIdx.x == 0) fix_count[0] = 0;    // the GEMM that follows fills the queue
+    if (blockIdx.x == 0 && threadIdx.x < DN_FIX_SLOTS) fix_count[DN_FIX_FIRST + DN_FIX_STRIDE * threadIdx.x] = 0;    // the GEMM that follows counts its exact recomputations
     for (int ro = blockIdx.x * GROUPS + threadIdx.x / LANES; ro < rows; ro += gridDim.x * GROUPS) {
         const int p = off_out + ro;
         const int q = p - off1;

@@ -51,7 +51,7 @@ struct GemmArgs {
     float* db_partial;      // dW: [splits of all terms x ncols] column sums of this split's rows of B (the bias gradient's partials)
     // ReLU sign fix-up (EPI_BIAS_ACT with relu)
     const float* rownorm; const float* colnorm; float gamma;
-    int* fix_count;         // [0] number of exact recomputations, [1] sticky overflow flag
+    int* fix_count;         // counters of exact recomputations (see dn_model), [1] sticky overflow flag
 };
 
 constexpr int MIN_CHUNKS = 8;
@@ -158,7 +158,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const int bx, const
         const int queued = s_fix_n;
         const int n_local = min(queued, LOCAL_FIX_CAP);
         if (t == 0 && queued > 0) {
-            atomicAdd(&a.fix_count[0], n_local);
+            atomicAdd(&a.fix_count[DN_FIX_FIRST + DN_FIX_STRIDE * ((bx + 7 * by) % DN_FIX_SLOTS)], n_local);
             if (queued > LOCAL_FIX_CAP) a.fix_count[1] = 1;       // surplus keeps its fp32 sign
         }
         // 16 lanes per queued element, 16 elements in flight per workgroup

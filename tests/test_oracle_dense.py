@@ -276,3 +276,23 @@ def test_embedding_sgd_touches_only_sampled_rows():
     assert np.array_equal(out[untouched], table[untouched])
     np.testing.assert_allclose(out[ids], table[ids].astype(np.float64) - 0.25 * grad.astype(np.float64), rtol=0, atol=1e-6)
     assert np.array_equal(oracle.embedding_sgd(table, ids, np.zeros_like(grad), 0.25), table)
+
+
+def test_openmp_build_gives_the_same_arrays(rmat16k):
+    """The same source built with -fopenmp (the per-node sampling loop on all cores) must return identical arrays."""
+    import os
+    rp, col = rmat16k["out"]
+    rpi, coli = rmat16k["in"]
+    g = oracle.Graph(16384, rp, col, rpi, coli)
+    rng = np.random.default_rng(8)
+    os.environ.setdefault("OMP_NUM_THREADS", "4")
+    for direction, fanouts in ((0, [10, 5]), (2, [6, 3]), (1, [4, 4, 4])):
+        targets = rng.choice(16384, size=300, replace=False).astype(np.int32)
+        a = oracle.dense_sample(g, targets, fanouts, seed=31, direction=direction)
+        oracle.use_openmp(True)
+        try:
+            b = oracle.dense_sample(g, targets, fanouts, seed=31, direction=direction)
+        finally:
+            oracle.use_openmp(False)
+        for name in ("node_id_offsets", "node_ids", "nbr_offsets", "nbrs", "repr_map"):
+            assert np.array_equal(getattr(a, name), getattr(b, name)), name
