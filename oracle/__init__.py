@@ -27,7 +27,7 @@ _lib = None
 _LIB_OMP = os.path.join(_HERE, "libdense_oracle_omp.so")
 _lib_omp = None
 _use_openmp = False
-GCC_FLAGS = ["-O2", "-std=c11", "-Wall", "-Wextra", "-shared", "-fPIC"]
+GCC_FLAGS = ["-O2", "-std=c11", "-Wall", "-Wextra", "-Wno-unknown-pragmas", "-shared", "-fPIC"]
 
 
 def build(force: bool = False) -> str:

@@ -255,6 +255,7 @@ int dn_batch_create(dn_batch** out, int64_t num_nodes, int32_t max_targets, int3
     b->sample_serial = 0;
     b->tr_serial = ~0ull;
     b->tr_capture_serial = ~0ull;
+    b->seen_slots_all = b->seen_slots_upper = -1;
     *out = b;
     return DN_OK;
 }
@@ -358,6 +359,10 @@ int dn_batch_counts(const dn_batch* b, int64_t* host_counts, void* stream)
     DN_HIP(hipStreamSynchronize(st));
     for (int j = 0; j <= b->k + 1; ++j) host_counts[j] = h[HDR_NODE_OFF + j];
     host_counts[b->k + 2] = h[HDR_E];
+    // slots of the hops before the last = slots owned by Delta_2 .. Delta_k (what the layers above the first aggregate)
+    const int64_t upper = b->k >= 2 ? h[HDR_LVL_NBR_OFF + b->k - 1] : 0;
+    if (h[HDR_E] > b->seen_slots_all) b->seen_slots_all = h[HDR_E];
+    if (upper > b->seen_slots_upper) b->seen_slots_upper = upper;
     if (h[HDR_STATUS] & (ST_BAD_TARGET | ST_DUP_TARGET))
         return dn_fail(DN_ESAMPLE, "dense_sample: %s", (h[HDR_STATUS] & ST_BAD_TARGET) ? "target id out of range" : "duplicate target id");
     if (h[HDR_STATUS] & ST_CAPACITY) return dn_fail(DN_ECAPACITY, "dense_sample: node capacity exceeded");
@@ -584,6 +589,7 @@ int dense_sample_noalloc(const dn_graph* g, const int32_t* d_targets, int32_t n_
     b->sample_serial = 1;
     b->tr_serial = ~0ull;
     b->tr_capture_serial = ~0ull;
+    b->seen_slots_all = b->seen_slots_upper = -1;
     hipStream_t st = static_cast<hipStream_t>(stream);
     // header and bitmaps must start at zero; the array keeps the last call's contents, carved for that call's sizes
     const int64_t zero_words = (int64_t)((reinterpret_cast<char*>(b->lvlpos) - reinterpret_cast<char*>(b->hdr)) / 4);

@@ -60,6 +60,9 @@ struct dn_batch {
     int64_t tr_long_words;
     int64_t tr_hist_words;
     int32_t n_targets;
+    // largest slot counts that dn_batch_counts has read back so far (-1: none yet): all slots, and the slots of the
+    // layers above the first; they choose the form of the transpose-index build (a matter of speed only)
+    mutable int64_t seen_slots_all, seen_slots_upper;
     uint64_t sample_serial;                 // bumped by every dense_sample
     uint64_t tr_serial;                     // sample the transpose index was built for
     int32_t tr_covers_all;
@@ -201,6 +204,7 @@ bool dn_sort_counts_separately(const dn_sort_plan& p);   // true: the caller's f
 // starts at index `first` (no two such groups start in one block of DN_LONG_GROUP indices; the caller clears
 // long_out beforehand).
 constexpr int DN_LONG_GROUP = 64;
+constexpr int64_t DN_TR_SMALL_MAX_PAIRS = 40960;          // up to here the index is built by one kernel
 struct dn_sort_slot_info { const int32_t* slot_owner; const int32_t* nbr_offsets; int32_t* own_out; float* inv_out;
                            int32_t* long_out;
                            int32_t* hdr; int covers_all; };   // batch header: the last kernel stamps the index with the sample's sequence number

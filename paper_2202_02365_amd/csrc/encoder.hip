@@ -259,10 +259,13 @@ __global__ __launch_bounds__(TPB) void k_aggregate_bwd(int32_t* __restrict__ hdr
             const int c0 = ((int)blockIdx.x - row_blocks) * HUB_ENTRIES_PER_BLOCK;
             for (int f = 0; f < HUB_ENTRIES_PER_BLOCK; ++f) {
                 const int entry = c0 + f < n_long ? tr_long[c0 + f] : 0;
-                if (entry <= off_in) continue;                 // none, or a row that is no input of this layer
+                if (entry <= off_in || entry > N) continue;    // none, or a row that is no input of this layer
                 const int p = entry - 1;
                 const int r = p - off_in;
                 const int beg = tr_ptr[p], end = tr_ptr[p + 1];
+                // the register is not cleared between batches by every form of the index build: an entry counts only if
+                // row p is such a row in THIS index and its group starts in this entry's block of slots
+                if (end - beg <= DN_LONG_GROUP || beg / DN_LONG_GROUP != c0 + f) continue;
                 float acc[ITERS][V];
 #pragma unroll
                 for (int it = 0; it < ITERS; ++it)

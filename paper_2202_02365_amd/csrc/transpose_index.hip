@@ -273,6 +273,155 @@ __global__ __launch_bounds__(TPB) void k_tr_ptr(const int32_t* __restrict__ coun
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// The whole index in ONE kernel, for the few ten thousand pairs of a node-classification mini-batch (the general
+// path above is six launches, which cost more than the work).  Workgroup b owns the keys [b * SMALL_KEYS, (b + 1) *
+// SMALL_KEYS) and reads ALL pairs itself, twice, each of its waves a contiguous part of them, in order:
+//   pass 1  counts, per wave, the pairs of each of its keys (LDS atomics: counts do not depend on the order) and the
+//           pairs with smaller keys (they precede the workgroup's output);
+//   scan    turns the counts into tr_ptr of its keys and into one output cursor per (wave, key), waves in order;
+//   pass 2  hands every pair its place: cursor of (wave, key) plus its rank among the equal keys of its 64-pair step
+//           (ballots), steps in order.  Equal keys therefore keep their input order: the sort is stable.
+// No workgroup waits for another and nothing is sized by the number of pairs, so any count is handled (time grows with
+// count x workgroups in use: the caller chooses this path only for small counts).
+constexpr int SMALL_TPB = 1024, SMALL_WAVES = SMALL_TPB / 64, SMALL_KEYS = 512, SMALL_KEY_BITS = 9;
+constexpr int SMALL_BATCH = 8;     // 64-pair steps whose key loads a wave has in flight together (the loops stay short:
+                                   // a kernel this brief cannot afford long straight-line code, its instruction fetch is cold)
+
+// rank of a lane's pair among the pairs with the same key in its 64-pair step, and the number of those (one ballot
+// per key bit; taking the distinct keys of a step one after the other instead measured slower, 44 against 31 us)
+__device__ __forceinline__ void step_peers(int kl, bool mine, int lane, int& rank, int& count)
+{
+    uint64_t peers = __ballot(mine);
+#pragma unroll
+    for (int bit = 0; bit < SMALL_KEY_BITS; ++bit) {
+        const uint64_t bal = __ballot((kl >> bit) & 1);
+        peers &= ((kl >> bit) & 1) ? bal : ~bal;
+    }
+    rank = __popcll(peers & ((1ull << lane) - 1ull));
+    count = __popcll(peers);
+}
+
+__global__ __launch_bounds__(SMALL_TPB) void k_tr_small(int32_t* __restrict__ hdr, int need_all, int k,
+                                                        const int32_t* __restrict__ nbr_offsets,
+                                                        const int32_t* __restrict__ repr_map, const int32_t* __restrict__ slot_owner,
+                                                        int32_t* __restrict__ tr_ptr, int32_t* __restrict__ tr_val,
+                                                        int32_t* __restrict__ tr_own, float* __restrict__ tr_inv,
+                                                        int32_t* __restrict__ tr_long)
+{
+    __shared__ int cnt[SMALL_WAVES][SMALL_KEYS];
+    __shared__ int s_part[SMALL_WAVES];
+    const int N = hdr[HDR_N], E = hdr[HDR_E];
+    const int range_start = (int)blockIdx.x * SMALL_KEYS;
+    if (range_start > N) return;
+    int first = 0;
+    if (!need_all) first = k >= 2 ? nbr_offsets[hdr[HDR_NODE_OFF + 2] - hdr[HDR_NODE_OFF + 1]] : E;
+    const int n = E - first;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        hdr[HDR_TR_FIRST] = first;
+        hdr[HDR_TR_COUNT] = n;
+        hdr[HDR_TR_SEQ] = hdr[HDR_SAMPLE_SEQ];
+        hdr[HDR_TR_ALL] = need_all;
+    }
+    for (int i = threadIdx.x; i < SMALL_WAVES * SMALL_KEYS; i += SMALL_TPB) (&cnt[0][0])[i] = 0;
+    // this wave's part of the pairs: whole steps of 64
+    const int steps = (n + 63) / 64;
+    const int steps_per_wave = (steps + SMALL_WAVES - 1) / SMALL_WAVES;
+    const int s_begin = wave * steps_per_wave, s_end = min(steps, s_begin + steps_per_wave);
+    const int32_t* keys = repr_map + first;
+    constexpr int NONE = 0x7fffffff;
+
+    __syncthreads();                                           // the counts are zero
+
+    // ---- pass 1
+    int below = 0;
+    for (int st = s_begin; st < s_end; st += SMALL_BATCH) {
+        int kv[SMALL_BATCH];
+#pragma unroll
+        for (int u = 0; u < SMALL_BATCH; ++u) {
+            const int i = (st + u) * 64 + lane;
+            kv[u] = (st + u < s_end && i < n) ? keys[i] - range_start : NONE;
+        }
+#pragma unroll
+        for (int u = 0; u < SMALL_BATCH; ++u) {
+            below += kv[u] < 0;
+            if (kv[u] >= 0 && kv[u] < SMALL_KEYS) atomicAdd(&cnt[wave][kv[u]], 1);
+        }
+    }
+    for (int d = 32; d > 0; d >>= 1) below += __shfl_down(below, d, 64);
+    if (lane == 0) s_part[wave] = below;
+    __syncthreads();
+    int before = 0;
+#pragma unroll
+    for (int w = 0; w < SMALL_WAVES; ++w) before += s_part[w];
+    __syncthreads();
+
+    // ---- scan: the first SMALL_KEYS threads take a key each
+    int tot = 0;
+    if (threadIdx.x < SMALL_KEYS) {
+#pragma unroll
+        for (int w = 0; w < SMALL_WAVES; ++w) tot += cnt[w][threadIdx.x];
+    }
+    int incl = tot;
+    for (int d = 1; d < 64; d <<= 1) { const int t = __shfl_up(incl, d, 64); if (lane >= d) incl += t; }
+    if (lane == 63) s_part[wave] = incl;
+    __syncthreads();
+    int run = before + incl - tot;
+#pragma unroll
+    for (int w = 0; w < SMALL_WAVES; ++w) if (w < wave) run += s_part[w];
+    int mine_total = 0;                                        // pairs of this workgroup's keys
+#pragma unroll
+    for (int w = 0; w < SMALL_KEYS / 64; ++w) mine_total += s_part[w];
+    if (threadIdx.x < SMALL_KEYS) {
+        const int kl = threadIdx.x;
+        const int p = range_start + kl;
+        if (p <= N) {
+            tr_ptr[p] = run;
+            // a row read by more than DN_LONG_GROUP slots is registered for the workgroups that sum such rows
+            if (tot > DN_LONG_GROUP) tr_long[run / DN_LONG_GROUP] = p + 1;
+        }
+        int c = run;
+#pragma unroll
+        for (int w = 0; w < SMALL_WAVES; ++w) {
+            const int x = cnt[w][kl];
+            cnt[w][kl] = c;                                    // the cursor of (wave, key)
+            c += x;
+        }
+    }
+    __syncthreads();
+
+    // ---- pass 2: places (the keys again, a batch of loads at a time; the stores are not waited for)
+    for (int st = s_begin; st < s_end; st += SMALL_BATCH) {
+        int kv[SMALL_BATCH];
+#pragma unroll
+        for (int u = 0; u < SMALL_BATCH; ++u) {
+            const int i = (st + u) * 64 + lane;
+            kv[u] = (st + u < s_end && i < n) ? keys[i] - range_start : NONE;
+        }
+#pragma unroll
+        for (int u = 0; u < SMALL_BATCH; ++u) {
+            const int kl = kv[u];
+            const bool mine = kl >= 0 && kl < SMALL_KEYS;
+            int rank, count;
+            step_peers(kl, mine, lane, rank, count);
+            if (mine) tr_val[cnt[wave][kl] + rank] = first + (st + u) * 64 + lane;
+            __builtin_amdgcn_wave_barrier();                   // every lane has read the cursor before its leader moves it
+            if (mine && rank == 0) cnt[wave][kl] += count;
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+    __syncthreads();                                           // this workgroup's part of tr_val is written
+
+    // ---- owner and 1 / count of every slot placed by this workgroup (a thread per place: the loads run side by side)
+    for (int t = threadIdx.x; t < mine_total; t += SMALL_TPB) {
+        const int j = tr_val[before + t];
+        const int q = slot_owner[j];
+        tr_own[before + t] = q;
+        tr_inv[before + t] = 1.0f / (float)(nbr_offsets[q + 1] - nbr_offsets[q]);
+    }
+}
+
 }  // namespace
 
 dn_sort_plan dn_sort_make_plan(int64_t key_range, int64_t cap_items)
@@ -370,9 +519,22 @@ int dn_launch_transpose_index(dn_batch* b, int need_all, hipStream_t st)
     uint64_t& serial = capturing ? b->tr_capture_serial : b->tr_serial;
     int32_t& covers = capturing ? b->tr_capture_covers_all : b->tr_covers_all;
     if (serial == b->sample_serial && (covers || !need_all)) return DN_OK;
+    dn_prof_scope ps("transpose_index", 0, st);             // the whole build counts as one step
+    // A few ten thousand pairs: the one-kernel form.  The host does not know the count (it lives on the device); it
+    // goes by the largest counts that dn_batch_counts has read back for this batch object so far.  Both forms are
+    // correct for any count; the choice only decides the time.
+    const int64_t seen_pairs = need_all ? b->seen_slots_all : b->seen_slots_upper;
+    if (seen_pairs >= 0 && seen_pairs <= DN_TR_SMALL_MAX_PAIRS) {
+        const unsigned grid = (unsigned)((b->cap_nodes + 1 + SMALL_KEYS - 1) / SMALL_KEYS);
+        hipLaunchKernelGGL(k_tr_small, dim3(grid), dim3(SMALL_TPB), 0, st, b->hdr, need_all, b->k, b->nbr_offsets, b->repr_map,
+                           b->slot_owner, b->tr_ptr, b->tr_val[0], b->tr_own, b->tr_inv, b->tr_long);
+        DN_LAUNCH_CHECK("k_tr_small");
+        serial = b->sample_serial;
+        covers = need_all ? 1 : 0;
+        return DN_OK;
+    }
     const dn_sort_plan pl = dn_sort_make_plan(b->cap_nodes, b->cap_slots);
     if (dn_sort_hist_words(pl) > b->tr_hist_words) return dn_fail(DN_ECAPACITY, "transpose index: histogram space");
-    dn_prof_scope ps("transpose_index", 0, st);             // the whole sort counts as one step
     int64_t g = (b->cap_slots + TPB - 1) / TPB;
     if (g > 2048) g = 2048;
     if (g < 1) g = 1;
