@@ -45,7 +45,11 @@ int fill_batch_caps(dn_batch* b, int64_t V, int32_t max_targets, int32_t k, cons
     if (b->cap_slots > 0x7fffff00LL) return dn_fail(DN_ECAPACITY, "more than 2^31 neighbour slots per batch");
     b->words0 = (V + 31) / 32;
     b->words1 = (b->words0 + 31) / 32;
-    const int64_t blocks_words = (b->words1 + 255) / 256, blocks_targets = (max_targets + 255) / 256;
+    // a walker of the next-Delta kernels takes a whole summary word (32 bitmap words) unless that leaves fewer than 64k walkers
+    b->walk_shift = 5;
+    while (b->walk_shift > 0 && (b->words0 >> b->walk_shift) < 65536) --b->walk_shift;
+    const int64_t walkers = (b->words0 + ((int64_t)1 << b->walk_shift) - 1) >> b->walk_shift;
+    const int64_t blocks_words = (walkers + 255) / 256, blocks_targets = (max_targets + 255) / 256;
     b->max_blocks = (int32_t)(blocks_words > blocks_targets ? blocks_words : blocks_targets);
     return DN_OK;
 }

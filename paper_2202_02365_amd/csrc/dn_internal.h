@@ -44,6 +44,7 @@ struct dn_batch {
     int64_t cap_slots_hop[DN_MAX_LAYERS];   // slot capacity per hop
     int64_t cap_nodes, cap_slots;
     int64_t words0, words1;                 // bitmap words: one bit per node / per bitmap word
+    int32_t walk_shift;                     // log2 of the bitmap words one thread of the next-Delta kernels walks
     int32_t max_blocks;
     // workspace carve-up (device pointers)
     int32_t* hdr;
