@@ -411,6 +411,8 @@ def run_link_prediction(args, cfg):
             total_s, in_flight = rep_s, "%d mini-batches, each on a stream of its own, launched eagerly" % len(slots)
         del slots
     edges = sum(sizes[s % n_batches][k + 2] for s in range(steps))
+    if slot["model"].status()[1] != 0:
+        raise RuntimeError("the ReLU sign fix-up queue overflowed during the timed run")
 
     roofline, kernels = None, {}
     if not args.no_kernel_times:
@@ -422,13 +424,16 @@ def run_link_prediction(args, cfg):
             dn.profile_calibration_copy(delay_dst, delay_src)
             dn.profile_empty_bracket()
             step(slot, s)
-        prof = dn.profile_collect()
+        prof_pct = dn.profile_collect_percentiles()
+        prof = {tag: (v[0], v[1]) for tag, v in prof_pct.items()}
         dn.profile_enable(False)
         del delay_src, delay_dst
         empty_ms, empty_n = prof.pop("empty_bracket", (0.0, 1))
-        noop_ms, noop_n = prof.pop("noop_kernel_bracket", (0.0, 1))
+        prof.pop("noop_kernel_bracket", None)
         bracket_us = 1e3 * empty_ms / max(empty_n, 1)
-        kernels = {tag: {"avg_us": max(1e3 * ms / n - bracket_us, 0.0), "launches_per_step": n / steps}
+        noop_us = 1e3 * (prof_pct["noop_kernel_bracket"][3] - prof_pct["empty_bracket"][3]) if "noop_kernel_bracket" in prof_pct else 0.0
+        kernels = {tag: {"avg_us": max(1e3 * ms / n - bracket_us, 0.0), "launches_per_step": n / steps,
+                         "p10_p50_p90_us": [max(1e3 * x - bracket_us, 0.0) for x in prof_pct[tag][2:5]]}
                    for tag, (ms, n) in prof.items()}
         step_sum_us = sum(v["avg_us"] * v["launches_per_step"] for v in kernels.values())
         used = [sizes[s % n_batches] for s in range(steps)]
@@ -453,7 +458,7 @@ def run_link_prediction(args, cfg):
                         "event_bracket_overhead_us_subtracted": bracket_us,
                         # a bracket around a kernel that does nothing reads this much more than an empty one: the latency
                         # of a launch as such, still contained in avg_us (rocprofv3's own durations do not contain it)
-                        "launch_latency_us_not_subtracted": max(1e3 * noop_ms / max(noop_n, 1) - bracket_us, 0.0)}
+                        "launch_latency_us_not_subtracted": max(noop_us, 0.0)}
 
     baseline = None
     if not args.no_cpu_baseline:
@@ -469,6 +474,10 @@ def run_link_prediction(args, cfg):
                    "positive_edges_per_batch": B, "chunk": chunk, "negatives_per_chunk": Nn, "relations": num_rel,
                    "mean_nodes_per_batch": mean_n, "mean_sampled_edges_per_batch": mean_e},
         "mini_batches_per_s": steps / total_s, "training_edges_per_s": B * steps / total_s, "in_flight": in_flight,
+        "replica_note": "with more than one mini-batch in flight the replicas apply their SGD steps to ONE shared embedding table "
+                        "without waiting for each other (non-atomic read-modify-write per row): rows that concurrent batches share "
+                        "(hub nodes, negatives) can lose an update or be read half-updated, so that mode is not reproducible bit "
+                        "for bit; one_in_flight is the reproducible figure",
         "one_in_flight": {"ms_per_step": 1e3 * serial_s / steps, "training_edges_per_s": B * steps / serial_s},
         "roofline": roofline, "kernels": kernels, "cpu_baseline": baseline}))
 
@@ -525,6 +534,8 @@ def main():
     ap.add_argument("--no-graphs", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
     ap.add_argument("--replica-graphs", action="store_true",
                     help="replicas replay one HIP graph per step instead of launching every kernel from the host")
+    ap.add_argument("--python-replicas", action="store_true",
+                    help="drive the replicas' streams from Python instead of handing the steps to dn_train_steps")
     ap.add_argument("--replicas", type=int, default=4,
                     help="data-parallel replicas on one GPU: that many mini-batches run the whole path concurrently, "
                          "each on a HIP stream of its own (0 = skip this measurement)")
@@ -732,17 +743,33 @@ def main():
                 rep_graphs[bi] = g
             torch.cuda.synchronize()
 
+        lib_steps = None
+        if fused and not rep_graphs and not args.python_replicas:
+            # the library schedules the replicas itself (dn_train_steps): step s on its internal stream s % n_rep
+            assert N_BATCHES % n_rep == 0
+            lib_steps = dn.TrainSteps([dict(batch=reps[bi % n_rep]["batch"], model=reps[bi % n_rep]["model"], graph=graph,
+                                            targets=targets[bi], seed=bi, table=table, out=reps[bi % n_rep]["out"],
+                                            labels=labels, grad_scale=1.0 / cfg.batch, loss=reps[bi % n_rep]["loss"],
+                                            grad_out=reps[bi % n_rep]["gout"], dws=reps[bi % n_rep]["dws"],
+                                            dwn=reps[bi % n_rep]["dwn"], dbs=reps[bi % n_rep]["dbs"],
+                                            dh0=reps[bi % n_rep]["dh0"]) for bi in range(N_BATCHES)],
+                                      forward_only=not backward)
+
         def run(n):
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            for s in range(n):
-                o = reps[s % n_rep]
-                bi = s % N_BATCHES
-                with torch.cuda.stream(o["stream"]):
-                    if rep_graphs:
-                        rep_graphs[bi].replay()
-                    else:
-                        one_step(o, bi)
+            if lib_steps is not None:
+                for first in range(0, n, N_BATCHES):
+                    lib_steps.run(n_rep, 0, min(N_BATCHES, n - first))
+            else:
+                for s in range(n):
+                    o = reps[s % n_rep]
+                    bi = s % N_BATCHES
+                    with torch.cuda.stream(o["stream"]):
+                        if rep_graphs:
+                            rep_graphs[bi].replay()
+                        else:
+                            one_step(o, bi)
             queued = time.perf_counter() - t0               # the host has handed over every launch
             torch.cuda.synchronize()
             spent = time.perf_counter() - t0
@@ -811,8 +838,12 @@ def main():
         if rep_s < total_s:
             total_s, fwd_only_s = rep_s, rep_fwd_s
             in_flight = ("%d mini-batches, each running sample+gather+forward+backward on a stream of its own "
-                         "(data-parallel replicas on one GPU, same weights, gradients per replica), launched eagerly"
-                         % args.replicas)
+                         "(data-parallel replicas on one GPU, same weights, gradients per replica), %s"
+                         % (args.replicas, "scheduled by the library (dn_train_steps)"
+                            if fused and not args.replica_graphs and not args.python_replicas else "launched from Python"))
+
+    if model.status()[1] != 0:
+        raise RuntimeError("the ReLU sign fix-up queue overflowed during the timed run")
 
     # per-kernel durations: the same K steps again, every launch bracketed by HIP events on its stream
     roofline, kernels, copy_gbs, whole_step = None, {}, None, None

@@ -297,6 +297,40 @@ DN_API int  dn_decoder_scores(const dn_decoder* d, int32_t side, const float** d
                               int64_t* row_stride, void* stream);
 DN_API int  dn_decoder_status(const dn_decoder* d, int32_t* flags, void* stream);
 
+/* ---- dn_train_steps: several mini-batches in flight, scheduled by the library (Section 3: the mini-batch pipeline keeps
+ *      construction and compute of different mini-batches busy at once; here on one device).
+ *      A node-classification training step is the chain dense_sample -> sage_forward_table -> dn_softmax_xent ->
+ *      sage_backward on one (batch, model) pair; a mini-batch of a thousand targets is a chain of some thirty short
+ *      kernels, most of them too small to fill the device, so independent chains are run side by side.  steps[i] runs
+ *      on internal stream i % n_streams (1 <= n_streams <= 16; the library creates them once per device, default
+ *      priority): steps that share a dn_batch / dn_model must therefore be n_streams apart (they then follow each other
+ *      on one stream); steps on different streams must use different batch and model objects and output buffers.  The
+ *      internal streams first wait for everything enqueued on `stream`, and `stream` afterwards waits for all of them,
+ *      so the call behaves like one asynchronous operation on `stream` (it can also be captured into a HIP graph).
+ *      Fields as in the calls named above; d_dH0 may be NULL.  d_grad_out: fp32 [n_targets x dims[k]] scratch for
+ *      dL/dH^k.  Results are those of the same calls made one after the other (bit for bit). */
+typedef struct dn_train_step {
+    dn_batch* batch;
+    dn_model* model;
+    const dn_graph* graph;
+    const int32_t* d_targets;
+    int32_t n_targets;
+    uint64_t seed;
+    const void* d_table;          /* lookup table of the model's in_dtype, row stride ld_elems */
+    int64_t ld_elems;
+    float* d_out;                 /* [n_targets x dims[k]] logits */
+    const int32_t* d_labels;      /* [n_targets] */
+    float grad_scale;
+    float* d_loss;                /* [n_targets] */
+    float* d_grad_out;            /* [n_targets x dims[k]] */
+    float* const* d_dw_self;      /* host arrays of k device pointers, as for sage_backward */
+    float* const* d_dw_nbr;
+    float* const* d_dbias;
+    float* d_dH0;
+    int32_t forward_only;         /* 1: stop after sage_forward_table (sample + gather + forward) */
+} dn_train_step;
+DN_API int  dn_train_steps(const dn_train_step* steps, int32_t n_steps, int32_t n_streams, void* stream);
+
 /* ---- per-kernel timing for benchmarks (off by default; not a step of the path).
  *      dn_profile_enable(1): from now on every kernel launch of this library is bracketed by a pair of
  *      HIP events on the stream it is launched on; dn_profile_enable(0) stops that.  Enabling also

@@ -27,6 +27,16 @@ class _KernelTime(ctypes.Structure):
                 ("p10_ms", ctypes.c_double), ("p50_ms", ctypes.c_double), ("p90_ms", ctypes.c_double)]
 
 
+class _TrainStep(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_void_p), ("model", ctypes.c_void_p), ("graph", ctypes.c_void_p),
+                ("targets", ctypes.c_void_p), ("n_targets", ctypes.c_int32), ("seed", ctypes.c_uint64),
+                ("table", ctypes.c_void_p), ("ld_elems", ctypes.c_int64), ("out", ctypes.c_void_p),
+                ("labels", ctypes.c_void_p), ("grad_scale", ctypes.c_float), ("loss", ctypes.c_void_p),
+                ("grad_out", ctypes.c_void_p), ("dw_self", ctypes.POINTER(ctypes.c_void_p)),
+                ("dw_nbr", ctypes.POINTER(ctypes.c_void_p)), ("dbias", ctypes.POINTER(ctypes.c_void_p)),
+                ("dh0", ctypes.c_void_p), ("forward_only", ctypes.c_int32)]
+
+
 class _View(ctypes.Structure):
     _fields_ = [("node_id_offsets", ctypes.c_void_p), ("node_ids", ctypes.c_void_p),
                 ("nbr_offsets", ctypes.c_void_p), ("nbrs", ctypes.c_void_p), ("repr_map", ctypes.c_void_p)]
@@ -63,6 +73,7 @@ def load_library():
         "dn_batch_capacity": (ctypes.c_int, [vp, ctypes.POINTER(i64), ctypes.POINTER(i64)]),
         "dense_sample": (ctypes.c_int, [vp, vp, vp, i32, u64, vp]),
         "dense_sample_noalloc": (ctypes.c_int, [vp, vp, i32, i32, ctypes.POINTER(i32), i32, u64, vp, vp, vp, i64, vp, vp, i64, vp, vp]),
+        "dn_train_steps": (ctypes.c_int, [ctypes.POINTER(_TrainStep), i32, i32, vp]),
         "dense_sample_edges": (ctypes.c_int, [vp, vp, vp, vp, i32, vp, i32, u64, vp, vp, vp, vp]),
         "dn_embedding_sgd": (ctypes.c_int, [vp, vp, i32, i64, vp, ctypes.c_float, vp]),
         "dn_embedding_adagrad": (ctypes.c_int, [vp, vp, vp, i32, i64, vp, ctypes.c_float, ctypes.c_float, vp]),
@@ -366,6 +377,34 @@ def dense_sample_noalloc(graph: Graph, targets: torch.Tensor, fanouts: Sequence[
                                                _dev_ptr(nbr_offsets, torch.int32), node_ids.numel(),
                                                _dev_ptr(nbrs, torch.int32), _dev_ptr(repr_map, torch.int32), nbrs.numel(),
                                                _dev_ptr(counts, torch.int32), _stream()))
+
+
+class TrainSteps:
+    """A marshalled list of training steps for dn_train_steps (built once, run many times).  Each entry is a dict with
+    batch, model, graph, targets, seed, table, out, labels, grad_scale, loss, grad_out, dws, dwn, dbs, dh0 (optional)."""
+
+    def __init__(self, entries, forward_only: bool = False):
+        self._keep = []
+        self.array = (_TrainStep * len(entries))()
+        for a, e in zip(self.array, entries):
+            dws, dwn, dbs = _ptr_array(e["dws"]), _ptr_array(e["dwn"]), _ptr_array(e["dbs"])
+            self._keep.append((e, dws, dwn, dbs))
+            a.batch, a.model, a.graph = e["batch"].handle, e["model"].handle, e["graph"].handle
+            a.targets, a.n_targets, a.seed = _dev_ptr(e["targets"], torch.int32), e["targets"].numel(), e["seed"] & 0xFFFFFFFFFFFFFFFF
+            a.table, a.ld_elems = e["table"].data_ptr(), e["table"].stride(0)
+            a.out, a.labels = _dev_ptr(e["out"], torch.float32), _dev_ptr(e["labels"], torch.int32)
+            a.grad_scale, a.loss, a.grad_out = e["grad_scale"], _dev_ptr(e["loss"], torch.float32), _dev_ptr(e["grad_out"], torch.float32)
+            a.dw_self = ctypes.cast(dws, ctypes.POINTER(ctypes.c_void_p))
+            a.dw_nbr = ctypes.cast(dwn, ctypes.POINTER(ctypes.c_void_p))
+            a.dbias = ctypes.cast(dbs, ctypes.POINTER(ctypes.c_void_p))
+            a.dh0 = _dev_ptr(e.get("dh0"), torch.float32)
+            a.forward_only = 1 if forward_only else 0
+
+    def run(self, n_streams: int, first: int = 0, count: Optional[int] = None) -> None:
+        """Steps first .. first+count-1 on n_streams library-owned streams, ordered behind / before the current stream."""
+        count = len(self.array) - first if count is None else count
+        ptr = ctypes.cast(ctypes.byref(self.array, first * ctypes.sizeof(_TrainStep)), ctypes.POINTER(_TrainStep))
+        _check(load_library().dn_train_steps(ptr, count, n_streams, _stream()))
 
 
 def dense_sample_edges(batch: Batch, graph: Graph, src: torch.Tensor, dst: torch.Tensor, neg: torch.Tensor, seed: int):

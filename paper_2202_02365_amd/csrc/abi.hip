@@ -608,6 +608,61 @@ int dense_sample_noalloc(const dn_graph* g, const int32_t* d_targets, int32_t n_
     return DN_OK;
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// Several training steps in flight on streams the library owns.
+namespace {
+constexpr int STEP_MAX_STREAMS = 16, STEP_MAX_DEVICES = 64;
+struct StepStreams {
+    hipStream_t stream[STEP_MAX_STREAMS] = {};
+    hipEvent_t done[STEP_MAX_STREAMS] = {};
+    hipEvent_t start = nullptr;
+    int created = 0;
+};
+StepStreams g_step_streams[STEP_MAX_DEVICES];
+std::mutex g_step_mutex;
+}  // namespace
+
+int dn_train_steps(const dn_train_step* steps, int32_t n_steps, int32_t n_streams, void* stream)
+{
+    if (n_steps < 0 || (n_steps > 0 && !steps)) return dn_fail(DN_EINVAL, "steps is null");
+    if (n_streams < 1 || n_streams > STEP_MAX_STREAMS) return dn_fail(DN_EINVAL, "n_streams must be in [1, %d]", STEP_MAX_STREAMS);
+    if (n_steps == 0) return DN_OK;
+    int dev = -1;
+    DN_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= STEP_MAX_DEVICES) return dn_fail(DN_EINVAL, "device index %d is outside [0, %d)", dev, STEP_MAX_DEVICES);
+    std::lock_guard<std::mutex> lock(g_step_mutex);
+    StepStreams& ss = g_step_streams[dev];
+    if (!ss.start) DN_HIP(hipEventCreateWithFlags(&ss.start, hipEventDisableTiming));
+    while (ss.created < n_streams) {
+        DN_HIP(hipStreamCreateWithFlags(&ss.stream[ss.created], hipStreamNonBlocking));     // default priority
+        DN_HIP(hipEventCreateWithFlags(&ss.done[ss.created], hipEventDisableTiming));
+        ss.created += 1;
+    }
+    hipStream_t outer = static_cast<hipStream_t>(stream);
+    const int used = n_steps < n_streams ? n_steps : n_streams;
+    DN_HIP(hipEventRecord(ss.start, outer));
+    for (int j = 0; j < used; ++j) DN_HIP(hipStreamWaitEvent(ss.stream[j], ss.start, 0));
+    int rc = DN_OK;
+    for (int i = 0; i < n_steps && rc == DN_OK; ++i) {
+        const dn_train_step& t = steps[i];
+        hipStream_t st = ss.stream[i % n_streams];
+        rc = dense_sample(t.batch, t.graph, t.d_targets, t.n_targets, t.seed, st);
+        if (rc == DN_OK) rc = sage_forward_table(t.model, t.batch, t.d_table, t.ld_elems, t.d_out, st);
+        if (rc != DN_OK || t.forward_only) continue;
+        const int k = t.model->k;
+        rc = dn_softmax_xent(t.d_out, t.model->dims[k], t.d_labels, t.n_targets, t.model->dims[k], t.grad_scale, t.d_loss,
+                             t.d_grad_out, t.model->dims[k], st);
+        if (rc == DN_OK) rc = sage_backward(t.model, t.batch, t.d_grad_out, t.d_dw_self, t.d_dw_nbr, t.d_dbias, t.d_dH0, st);
+    }
+    // join: the caller's stream continues when every internal stream has drained (also after an error, so that no work
+    // of this call is left unordered behind the caller's stream)
+    for (int j = 0; j < used; ++j) {
+        DN_HIP(hipEventRecord(ss.done[j], ss.stream[j]));
+        DN_HIP(hipStreamWaitEvent(outer, ss.done[j], 0));
+    }
+    return rc;
+}
+
 int dn_profile_calibration_copy(void* d_dst, const void* d_src, size_t bytes, void* stream)
 {
     if (!d_dst || !d_src || ((uintptr_t)d_dst & 15) || ((uintptr_t)d_src & 15) || (bytes & 15))
