@@ -139,7 +139,8 @@ def algorithmic_work(tag, sizes, cfg, dims):
         return "hbm", float(cfg.batch * (dims[-1] * 8 + 8))
     if tag in ("embedding_sgd", "embedding_adagrad"):
         return "hbm", mean(N * dims[0] * 4 * (3 if tag.endswith("sgd") else 5))
-    if tag.startswith("gemm_fwd_L"):
+    if tag.startswith("gemm_fwd_L") or tag.startswith("sage_layer_L"):
+        # sage_layer_L*: aggregation and linear map of a layer above the first in one launch; the contraction is the same
         i = layer_of(tag)
         rows = N - off[:, i]
         terms = 1 if i == 1 else 2
@@ -186,6 +187,12 @@ def gemm_algorithmic_bytes(tag, sizes, cfg, dims):
     if tag.startswith("gemm_fwd_L"):
         rows, kk, n, xt, _ = layer(int(tag.split("_L")[1]))
         return float(np.mean(rows * kk * xt * 2 + rows * n * 4))
+    if tag.startswith("sage_layer_L"):
+        # input rows read per slot and per output row, slot list, X written for the backward pass, output rows, weights
+        i = int(tag.split("_L")[1])
+        rows, kk, n, xt, _ = layer(i)
+        slots = np.array([s[k + 2 + i] for s in sizes], dtype=np.float64)
+        return float(np.mean((slots + rows) * dims[i - 1] * 4 + slots * 4 + rows * kk * xt * 2 + rows * n * 4 + n * kk * 2))
     if tag.startswith("gemm_dx_L"):
         rows, kk, n, _, zt = layer(int(tag.split("_L")[1]))
         return float(np.mean(rows * n * zt * 2 + rows * kk * 4))
@@ -199,7 +206,7 @@ def gemm_algorithmic_bytes(tag, sizes, cfg, dims):
 
 
 FORWARD_TAGS = ("init_", "sample_hop", "fresh_", "assemble", "mark_ids", "local_ids", "gather", "aggregate_L",
-                "aggregate_table_L", "gemm_fwd_L")
+                "aggregate_table_L", "gemm_fwd_L", "sage_layer_L")
 
 
 def pick_dominant(candidates, forward_chain_timed):

@@ -209,8 +209,8 @@ DN_API int  dn_model_create(dn_model** out, const dn_batch* b, int32_t k, const 
 DN_API int  dn_model_set_weights(dn_model* m, const float* const* d_w_self, const float* const* d_w_nbr,
                           const float* const* d_bias, void* stream);
 DN_API void dn_model_destroy(dn_model* m);
-/* Diagnostics of the last sage_forward; WAITS for `stream`.  status[0] = pre-activations of the last
- * ReLU layer whose sign the fp32 accumulation could not settle and that were recomputed in fp64;
+/* Diagnostics of the last sage_forward; WAITS for `stream`.  status[0] = pre-activations, over all
+ * ReLU layers, whose sign the fp32 accumulation could not settle and that were recomputed in fp64;
  * status[1] = 1 if that queue ever overflowed since dn_model_create (the surplus kept its fp32 sign). */
 DN_API int  dn_model_status(const dn_model* m, int32_t* status, void* stream);
 

@@ -130,6 +130,7 @@ void carve_model(dn_model* m, const dn_batch* b, Carver& c)
         L.h = (i < k) ? c.take<float>(L.rows_pad * L.d_out) : nullptr;
         L.wt = c.take<dn_bf16>(dn_round_up(L.d_out, 128) * L.kp);
         L.w = c.take<dn_bf16>(dn_round_up(2 * (int64_t)L.d_in, 128) * L.nz);
+        L.wf = (L.xterms == 2 && L.d_in % 16 == 0) ? c.take<dn_bf16>((int64_t)L.np * 2 * L.d_in) : nullptr;
         L.bias = c.take<float>(L.d_out);
         L.rownorm = c.take<float>(L.rows_pad);
         L.colnorm = c.take<float>(L.d_out);
@@ -143,6 +144,7 @@ void carve_model(dn_model* m, const dn_batch* b, Carver& c)
     }
     m->dx = c.take<float>(max_dx);
     m->fix_count = c.take<int32_t>(DN_FIX_WORDS);
+    m->zero_row = c.take<float>(DN_ZERO_ROW_FLOATS);
     (void)b;
 }
 

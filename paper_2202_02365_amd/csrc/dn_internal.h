@@ -86,6 +86,10 @@ struct dn_layer_bufs {
     float* h;            // [rows_pad x d_out] layer output (not for the last layer)
     dn_bf16* wt;         // [round128(d_out) x kp]   Wcat^T repeated per X term, zero padded
     dn_bf16* w;          // [round128(2*d_in) x nz]  Wcat repeated per dZ term, zero padded
+    // layers above the first with d_in a multiple of 16: Wcat^T once more in the order v_mfma_f32_16x16x32_bf16 takes
+    // its B operand, [np/16 column tiles][2*d_in/32 reduction steps][64 lanes][8]: lane l of the fragment of tile T,
+    // step s holds Wcat^T[16 T + l % 16][32 s + 8 (l / 16) .. + 8]; rows >= d_out are zero.  Null otherwise.
+    dn_bf16* wf;
     float* bias;         // [d_out]
     float* rownorm;      // [rows_pad] L2 norm of each X row (bounds the accumulation error of Z)
     float* colnorm;      // [d_out]    L2 norm of each Wcat^T row
@@ -111,6 +115,7 @@ struct dn_model {
     // slot (workgroup number % DN_FIX_SLOTS): one counter for all would queue a thousand atomics on one line), at
     // fix_count[DN_FIX_FIRST + DN_FIX_STRIDE * j]; [1] sticky overflow flag
     int32_t* fix_count;
+    float* zero_row;               // DN_ZERO_ROW_FLOATS zeros that nothing writes (a place to read for a slot that does not exist)
     const void* h0;                // H^0 of the last forward
     uint64_t fwd_serial;           // sample the saved activations belong to
     int32_t weights_set;
@@ -118,6 +123,7 @@ struct dn_model {
     size_t workspace_bytes;
 };
 
+constexpr int DN_ZERO_ROW_FLOATS = 1024;
 constexpr int DN_FIX_SLOTS = 32, DN_FIX_STRIDE = 16, DN_FIX_FIRST = 64;
 constexpr int DN_FIX_WORDS = DN_FIX_FIRST + DN_FIX_SLOTS * DN_FIX_STRIDE;
 
@@ -225,6 +231,9 @@ constexpr unsigned DN_DZ_MAX_ROW_BLOCKS = 512;
 
 // GEMM entry points (gemm.hip), layer index i is 1-based
 int dn_gemm_forward(const dn_model* m, const dn_batch* b, int i, float* out, int64_t ldc, hipStream_t st);
+// a layer above the first as one launch (layer_fused.hip): aggregation + linear map + bias + ReLU
+bool dn_layer_is_fused(const dn_model* m, int i);
+int dn_launch_layer_fused(const dn_model* m, const dn_batch* b, int i, float* out, int64_t ldc, hipStream_t st);
 int dn_gemm_dx(const dn_model* m, const dn_batch* b, int i, hipStream_t st);
 int dn_gemm_dw_all(const dn_model* m, const dn_batch* b, float* const* dws, float* const* dwn, float* const* dbias,
                    hipStream_t st);

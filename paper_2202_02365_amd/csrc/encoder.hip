@@ -41,7 +41,8 @@ __global__ __launch_bounds__(TPB) void k_aggregate(const int32_t* __restrict__ h
     const int rows = N - off_out;
     const int lane = threadIdx.x % LANES;
     constexpr int GROUPS = TPB / LANES;
-    if (blockIdx.x == 0 && threadIdx.x < DN_FIX_SLOTS) fix_count[DN_FIX_FIRST + DN_FIX_STRIDE * threadIdx.x] = 0;    // the GEMM that follows counts its exact recomputations
+    // the first kernel of a forward pass clears the counters of exact recomputations that its ReLU layers add to
+    if (layer == 1 && blockIdx.x == 0 && threadIdx.x < DN_FIX_SLOTS) fix_count[DN_FIX_FIRST + DN_FIX_STRIDE * threadIdx.x] = 0;
     for (int ro = blockIdx.x * GROUPS + threadIdx.x / LANES; ro < rows; ro += gridDim.x * GROUPS) {
         const int p = off_out + ro;
         const int q = p - off1;
@@ -513,7 +514,13 @@ int dn_launch_forward(dn_model* m, const dn_batch* b, const void* h0, int64_t ld
         else if (i == 1)
             rc = from_table ? launch_aggregate_t<float, 1, true>(m, b, 1, static_cast<const float*>(h0), ldh, st)
                             : launch_aggregate_t<float, 1, false>(m, b, 1, static_cast<const float*>(h0), ldh, st);
-        else
+        else if (dn_layer_is_fused(m, i) && b->cap_slots > 0) {
+            // aggregation, linear map, bias and ReLU of the layer in one launch
+            const dn_layer_bufs& Lf = m->layer[i - 1];
+            rc = dn_launch_layer_fused(m, b, i, i == k ? out : Lf.h, Lf.d_out, st);
+            if (rc) return rc;
+            continue;
+        } else
             rc = launch_aggregate_t<float, 2, false>(m, b, i, m->layer[i - 2].h, m->layer[i - 1].d_in, st);
         if (rc) return rc;
         const dn_layer_bufs& L = m->layer[i - 1];

@@ -352,7 +352,8 @@ __global__ __launch_bounds__(TPB) void k_bwd_reduce_group(ReduceGroup R, const i
 __global__ __launch_bounds__(TPB) void k_pack_weights(const float* __restrict__ ws, const float* __restrict__ wn,
                                                       const float* __restrict__ bias, int d_in, int d_out, int kp, int np,
                                                       int nz, int xterms, int zterms, uint16_t* __restrict__ wt,
-                                                      uint16_t* __restrict__ w, float* __restrict__ bias_out)
+                                                      uint16_t* __restrict__ w, uint16_t* __restrict__ wf,
+                                                      float* __restrict__ bias_out)
 {
     const int idx = blockIdx.x * TPB + threadIdx.x;
     if (idx < d_out) bias_out[idx] = bias[idx];
@@ -362,6 +363,8 @@ __global__ __launch_bounds__(TPB) void k_pack_weights(const float* __restrict__ 
     const uint16_t h = f32_to_bf16(v);
     for (int t = 0; t < xterms; ++t) wt[(int64_t)n * kp + t * 2 * d_in + kk] = h;
     for (int t = 0; t < zterms; ++t) w[(int64_t)kk * nz + t * np + n] = h;
+    // fragment order (dn_layer_bufs::wf): tile n / 16, step kk / 32, lane 16 ((kk % 32) / 8) + n % 16, element kk % 8
+    if (wf) wf[((((int64_t)(n >> 4) * (2 * d_in / 32) + (kk >> 5)) * 64) + 16 * ((kk & 31) >> 3) + (n & 15)) * 8 + (kk & 7)] = h;
 }
 
 // colnorm[n] = L2 norm of row n of Wcat^T (all terms), one thread per row
@@ -524,7 +527,7 @@ int dn_launch_set_weights(dn_model* m, const float* const* ws, const float* cons
         const int n = total > L.d_out ? total : L.d_out;
         hipLaunchKernelGGL(k_pack_weights, dim3((n + TPB - 1) / TPB), dim3(TPB), 0, st, ws[i], wn[i], bias[i], L.d_in,
                            L.d_out, L.kp, L.np, L.nz, L.xterms, L.zterms, reinterpret_cast<uint16_t*>(L.wt),
-                           reinterpret_cast<uint16_t*>(L.w), L.bias);
+                           reinterpret_cast<uint16_t*>(L.w), reinterpret_cast<uint16_t*>(L.wf), L.bias);
         DN_LAUNCH_CHECK("k_pack_weights");
         hipLaunchKernelGGL(k_col_norms, dim3((L.d_out + TPB - 1) / TPB), dim3(TPB), 0, st,
                            reinterpret_cast<const uint16_t*>(L.wt), L.d_out, L.kp, L.colnorm);

@@ -148,6 +148,18 @@ def test_rows_read_by_hundreds_of_slots(dims):
     check(errs)
 
 
+def test_one_launch_layer_with_long_and_empty_segments(g16k):
+    """Layers above the first with 64, 128, 192 or 256 input columns run aggregation and linear map in one launch.
+    Fanout 48 over both edge directions (up to 96 slots a row) gives its rows segments beyond the 16 slots fetched at once and beyond one
+    chunk of 64, next to rows without any slot; 192 input columns and 40 output columns leave lanes and waves idle."""
+    errs, (_, _, _, _, _, d) = run_case(g16k, [48, 3], [24, 192, 40], 300, seed=21, direction=2, want_dh0=True)
+    seg = np.diff(np.asarray(d.nbr_offsets))[-300:]                 # the targets' segments: layer 2's rows
+    assert seg.max() > 64 and (seg > 16).sum() > 10 and (seg == 0).any(), (seg.max(), (seg > 16).sum(), (seg == 0).sum())
+    check(errs)
+    errs, _ = run_case(g16k, [40, 2], [16, 128, 256], 77, seed=22, direction=2, aggregation="sum")
+    check(errs)
+
+
 @pytest.mark.parametrize("feat_dtype", ["f32", "bf16"])
 def test_forward_from_the_table_equals_gather_then_forward(g16k, feat_dtype):
     errs, _ = run_case(g16k, [7, 4], [36, 64, 12], 200, seed=11, feat_dtype=feat_dtype, want_dh0=True, from_table=True)
