@@ -38,11 +38,12 @@ def median_seconds(timed_block, repeats=REPEATS):
     return float(np.median(times)), times
 
 
-def dw_effective_splits(rows, kx, d_out, zterms, tile=128, max_splits=32, min_chunks=8):
+def dw_effective_splits(rows, kx, d_out, zterms, tile=128, max_splits=64, min_chunks=8, target_blocks=256):
     """Reduction splits the weight-gradient GEMM of a layer actually uses for `rows` rows (the library chooses them on
-    the device: enough workgroups to fill the chip by capacity, then at least `min_chunks` k-steps of 64 rows per split)."""
+    the device: enough workgroups to fill the chip by capacity, then at least `min_chunks` k-steps of 64 rows per
+    split; every bf16 term of dZ has its own splits)."""
     tiles = -(-kx // tile) * -(-d_out // tile) * zterms
-    by_capacity = min(max_splits, -(-512 // tiles))
+    by_capacity = min(max_splits, -(-target_blocks // tiles))
     chunks = -(-int(rows) // 64)
     return max(1, min(by_capacity, chunks // min_chunks))
 

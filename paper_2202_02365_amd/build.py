@@ -10,7 +10,7 @@ LIB = os.path.join(PKG, "libdense_mi355x.so")
 SOURCES = ["abi.hip", "sample.hip", "gather.hip", "gemm.hip", "encoder.hip", "layer_fused.hip", "transpose_index.hip", "decoder.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wall", "-Wno-unused-function", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+         "-Wall", "-Wno-unused-function", "-I", os.path.join(ROOT, "include"), "-I", CSRC] + os.environ.get("DN_EXTRA_HIPCC_FLAGS", "").split()
 
 
 def build(verbose: bool = True) -> str:

@@ -123,7 +123,7 @@ void carve_model(dn_model* m, const dn_batch* b, Carver& c)
 {
     const int k = m->k;
     int64_t max_dx = 0;
-    m->splits = 32;
+    m->splits = 64;
     for (int i = 1; i <= k; ++i) {
         dn_layer_bufs& L = m->layer[i - 1];
         L.x = c.take<dn_bf16>(L.rows_pad * L.kp);
@@ -137,7 +137,7 @@ void carve_model(dn_model* m, const dn_batch* b, Carver& c)
         L.dzb = c.take<dn_bf16>(L.rows_pad * L.nz);
         L.partial_floats = (int64_t)m->splits * L.kx * L.d_out * L.zterms;
         L.partial = c.take<float>(L.partial_floats);
-        // bias-gradient partials: one row per (dZ term, split) from the weight-gradient GEMM; the last layer's come from
+        // bias-gradient partials: one row per split from the weight-gradient GEMM; the last layer's come from
         // its dZ kernel, one row per row tile
         L.db_partial = c.take<float>((i < k ? (int64_t)m->splits * L.zterms : (L.rows_cap + 63) / 64 + 1) * L.d_out);
         max_dx = std::max<int64_t>(max_dx, L.rows_pad * 2 * L.d_in);

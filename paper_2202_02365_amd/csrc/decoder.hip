@@ -319,7 +319,7 @@ __global__ __launch_bounds__(TPB, 2) void k_dm_gemm_tn(DmGemmTn g)
     const int z = blockIdx.z;
     const int row0 = blockIdx.y * BM, col0 = blockIdx.x * BN;
     f32x16 acc[2][2];
-    mainloop_tn<BM, BN>(g.A + (int64_t)z * g.stride_a, g.lda, g.a_cols, g.B + (int64_t)z * g.stride_b, g.ldb, g.b_cols, row0, col0,
+    mainloop_tn<BM, BN>(g.A + (int64_t)z * g.stride_a, g.lda, g.a_cols, g.B + (int64_t)z * g.stride_b, g.ldb, g.b_cols, 1, 0, row0, col0,
                         0, (g.k_rows + BK - 1) / BK, g.k_rows, acc);
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wm = wave >> 1, wn = wave & 1;

@@ -31,6 +31,14 @@ using namespace dn_mma;
 
 // sign fix-ups one workgroup can queue: one sixteenth of its outputs
 enum { EPI_BIAS_ACT = 0, EPI_PLAIN = 1, EPI_SPLIT = 2 };
+// Weight gradient with two bf16 terms of dZ: 0 = each term is a reduction split of its own (twice the workgroups, X is
+// read once per term), 1 = one workgroup reduces both terms (X read once, half the partial tiles, but LDS for two
+// terms leaves room for one workgroup per compute unit).  Measured at the 111M-node workload: 25 us and 131 MB through
+// HBM against 36 us and 66 MB; with four mini-batches in flight both give the same step rate.  0 is built.
+#ifndef DN_DW_FUSE_TERMS
+#define DN_DW_FUSE_TERMS 0
+#endif
+constexpr bool DW_FUSE = DN_DW_FUSE_TERMS != 0;
 
 
 struct GemmArgs {
@@ -45,19 +53,20 @@ struct GemmArgs {
     const float* bias;
     int relu;
     int64_t split_stride;   // floats between consecutive split partials
-    int terms;              // dW: reduction terms (hi, lo) of B; split index z = term * (gridDim.z / terms) + chunk group
+    int terms;              // dW: bf16 terms (hi, lo) of B, both reduced by every workgroup
     int64_t b_term_stride;  // dW: elements between B's terms
     int a_cols, b_cols;     // dW: allocated columns of A, of one term of B (loads beyond them read zero)
-    float* db_partial;      // dW: [splits of all terms x ncols] column sums of this split's rows of B (the bias gradient's partials)
+    int min_chunks;         // dW: see effective_splits
+    float* db_partial;      // dW: [splits x ncols] column sums of this split's rows of B, all terms (the bias gradient's partials)
     // ReLU sign fix-up (EPI_BIAS_ACT with relu)
     const float* rownorm; const float* colnorm; float gamma;
     int* fix_count;         // counters of exact recomputations (see dn_model), [1] sticky overflow flag
 };
 
-constexpr int MIN_CHUNKS = 8;
-__device__ __forceinline__ int effective_splits(int groups, int chunks)
+// fewest k-steps (of 64 rows) a split of the weight-gradient reduction is given
+__device__ __forceinline__ int effective_splits(int groups, int chunks, int min_chunks)
 {
-    const int want = chunks / MIN_CHUNKS;
+    const int want = chunks / min_chunks;
     return want < 1 ? 1 : (want < groups ? want : groups);
 }
 
@@ -75,12 +84,12 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const int bx, const
 
     // reduction range of this split (dW: the splits of every term cover the whole range)
     const int chunks = red / BK;
-    const int groups = (EPI == EPI_SPLIT) ? nz / a.terms : 1;
-    const int term = (EPI == EPI_SPLIT) ? bz / groups : 0;
+    const int groups = (EPI == EPI_SPLIT) ? (DW_FUSE ? nz : nz / a.terms) : 1;
+    const int term = (EPI == EPI_SPLIT && !DW_FUSE) ? bz / groups : 0;
     const int grp = (EPI == EPI_SPLIT) ? bz % groups : 0;
-    // dW: the grid has `groups` splits by capacity; only as many are used as leave at least MIN_CHUNKS k-steps
+    // dW: the grid has `groups` splits by capacity; only as many are used as leave at least min_chunks k-steps
     // per split for the rows that exist (the others leave at once and the reduction skips them)
-    const int eff_groups = (EPI == EPI_SPLIT) ? effective_splits(groups, chunks) : 1;
+    const int eff_groups = (EPI == EPI_SPLIT) ? effective_splits(groups, chunks, a.min_chunks) : 1;
     if (grp >= eff_groups) return;
     const int per = (chunks + eff_groups - 1) / eff_groups;
     const int kc_begin = grp * per;
@@ -97,8 +106,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const int bx, const
         // split's rows of dZ, which are its share of the bias gradient.
         f32x16 ones_acc[NJ];
         const bool do_ones = by == 0 && wm == 0 && a.db_partial != nullptr;
-        mainloop_tn<BM_, BN_, true>(a.A, a.lda, a.a_cols, Bbase, a.ldb, a.b_cols, row0, col0, kc_begin, kc_end, rows_layer, acc,
-                                    ones_acc, do_ones);
+        mainloop_tn<BM_, BN_, true, DW_FUSE>(a.A, a.lda, a.a_cols, Bbase, a.ldb, a.b_cols, DW_FUSE ? a.terms : 1, a.b_term_stride,
+                                             row0, col0, kc_begin, kc_end, rows_layer, acc, ones_acc, do_ones);
         if (do_ones && lane < 32) {                           // register 0 of lanes 0..31: row 0 of the 32 x 32 tile
 #pragma unroll
             for (int j = 0; j < NJ; ++j) {
@@ -208,21 +217,29 @@ struct GemmGroup {
     GemmArgs g[DN_MAX_LAYERS];
     int begin[DN_MAX_LAYERS + 1];
     int gx[DN_MAX_LAYERS], gy[DN_MAX_LAYERS], gz[DN_MAX_LAYERS];
-    int n;
+    int n, place;
 };
 template <int BM_, int BN_>
-__global__ __launch_bounds__(TPB, (BM_ == 64 && BN_ == 64) ? 4 : 2) void k_gemm_dw_group(GemmGroup G)
+__global__ __launch_bounds__(TPB, 2) void k_gemm_dw_group(GemmGroup G)
 {
     int gi = 0;
     while (gi + 1 < G.n && (int)blockIdx.x >= G.begin[gi + 1]) ++gi;
-    // The column tiles of one (row tile, split) read the same rows of X: launch order is re-read as chunks of
-    // 8 x (column tiles) in which the workgroups j, j + 8, ... (same XCD, shared L2) are those column tiles.
-    // (Placing ALL tiles of a split on one XCD was measured slower: 34 vs 27 us.)
+    // Workgroups go to the 8 XCDs round-robin in launch order.  place 0: the column tiles of one (row tile, split)
+    // read the same rows of X: launch order is re-read as chunks of 8 x (column tiles), in which the workgroups
+    // j, j + 8, ... (same XCD, shared L2) are those column tiles.  place 1: all tiles of one split share an XCD.
     const int local = (int)blockIdx.x - G.begin[gi];
     const int nx = G.gx[gi];
-    const int chunk = local / (8 * nx), j = local - chunk * 8 * nx;
-    const int bx = j >> 3, r = chunk * 8 + (j & 7);          // r = bz * gy + by
-    const int by = r % G.gy[gi], bz = r / G.gy[gi];
+    int bx, by, bz;
+    if (G.place == 0) {
+        const int chunk = local / (8 * nx), j = local - chunk * 8 * nx;
+        const int r = chunk * 8 + (j & 7);                       // r = bz * gy + by
+        bx = j >> 3; by = r % G.gy[gi]; bz = r / G.gy[gi];
+    } else {
+        const int tiles = nx * G.gy[gi];
+        const int chunk = local / (8 * tiles), j = local - chunk * 8 * tiles;
+        const int tile = j >> 3;
+        bz = chunk * 8 + (j & 7); bx = tile % nx; by = tile / nx;
+    }
     if (bz >= G.gz[gi]) return;
     gemm_tile<EPI_SPLIT, BM_, BN_>(G.g[gi], bx, by, bz, G.gz[gi]);
 }
@@ -231,7 +248,7 @@ __global__ __launch_bounds__(TPB, (BM_ == 64 && BN_ == 64) ? 4 : 2) void k_gemm_
 // rows kk < d go to dW_self, d <= kk < 2d to dW_nbr.
 __device__ __forceinline__ void dw_reduce_block(const int block, const float* __restrict__ partial, int64_t split_stride,
                                                 int groups, int zterms, int rows, int xterms, int d_in, int d_out,
-                                                float* __restrict__ dws, float* __restrict__ dwn)
+                                                int min_chunks, float* __restrict__ dws, float* __restrict__ dwn)
 {
     // 64 consecutive outputs per workgroup; each of its 4 waves sums a quarter of the list of partials
     __shared__ float quarter[4][64];
@@ -239,7 +256,7 @@ __device__ __forceinline__ void dw_reduce_block(const int block, const float* __
     const int idx = block * 64 + tx;
     const bool live = idx < 2 * d_in * d_out;
     const int kk = live ? idx / d_out : 0, n = live ? idx - kk * d_out : 0;
-    const int eff = effective_splits(groups, (rows + BK - 1) / BK);   // the splits the GEMM actually wrote
+    const int eff = effective_splits(groups, (rows + BK - 1) / BK, min_chunks);   // the splits the GEMM actually wrote
     // Wave ty takes the splits ty, ty + 4, ... of every (X term, dZ term) combination, eight loads in flight into
     // eight running sums (a load past the last split re-reads the last one and counts as zero).  The order is
     // fixed; the chain of dependent loads bounds this kernel, not the bytes.
@@ -271,11 +288,11 @@ __device__ __forceinline__ void dw_reduce_block(const int block, const float* __
 // term, split), in a fixed order.  One thread per column.
 constexpr int DB_COLS = TPB;
 __device__ __forceinline__ void db_reduce_block(const int block, int rows, const float* __restrict__ db_partial, int groups,
-                                                int zterms, int d_out, float* __restrict__ db)
+                                                int zterms, int d_out, int min_chunks, float* __restrict__ db)
 {
     const int n = block * DB_COLS + threadIdx.x;
     if (n >= d_out) return;
-    const int eff = effective_splits(groups, (rows + BK - 1) / BK);   // the splits the GEMM actually wrote
+    const int eff = effective_splits(groups, (rows + BK - 1) / BK, min_chunks);   // the splits the GEMM actually wrote
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
     for (int zt = 0; zt < zterms; ++zt)
         for (int z = 0; z < eff; z += 4) {
@@ -331,7 +348,7 @@ struct ReduceGroup {
     int dw_blocks[DN_MAX_LAYERS], db_blocks[DN_MAX_LAYERS];
     int db_from_tiles[DN_MAX_LAYERS];    // last layer: the partials are the dZ kernel's, one per row tile
     int begin[DN_MAX_LAYERS + 1];
-    int n;
+    int n, min_chunks;
 };
 __global__ __launch_bounds__(TPB) void k_bwd_reduce_group(ReduceGroup R, const int32_t* __restrict__ hdr)
 {
@@ -341,10 +358,10 @@ __global__ __launch_bounds__(TPB) void k_bwd_reduce_group(ReduceGroup R, const i
     const int rows = hdr[HDR_N] - hdr[HDR_NODE_OFF + R.layer[y]];
     if (x < R.dw_blocks[y]) {
         dw_reduce_block(x, R.partial[y], R.split_stride[y], R.groups[y], R.zterms[y], rows, R.xterms[y], R.d_in[y], R.d_out[y],
-                        R.dws[y], R.dwn[y]);
+                        R.min_chunks, R.dws[y], R.dwn[y]);
     } else if (x < R.dw_blocks[y] + R.db_blocks[y]) {
         if (R.db_from_tiles[y]) db_reduce_tiles(x - R.dw_blocks[y], rows, R.db_partial[y], R.d_out[y], R.db[y]);
-        else db_reduce_block(x - R.dw_blocks[y], rows, R.db_partial[y], R.groups[y], R.zterms[y], R.d_out[y], R.db[y]);
+        else db_reduce_block(x - R.dw_blocks[y], rows, R.db_partial[y], R.groups[y], R.zterms[y], R.d_out[y], R.min_chunks, R.db[y]);
     }
 }
 
@@ -395,6 +412,24 @@ int gemm_tile_edge()
 {
     static const int edge = tile_from_env("DN_GEMM_TILE", 64);
     return edge;
+}
+// workgroups the weight-gradient GEMM of one layer aims for when it splits the reduction (one per compute unit:
+// LDS for two dZ terms leaves room for one workgroup); DN_DW_BLOCKS in the environment overrides, read once
+int dw_target_blocks()
+{
+    static const int n = [] { const char* e = getenv("DN_DW_BLOCKS"); const int v = e ? atoi(e) : 0; return v > 0 ? v : 256; }();
+    return n;
+}
+// DN_DW_MIN_CHUNKS in the environment overrides the fewest k-steps per split (default 8), read once
+int dw_min_chunks()
+{
+    static const int n = [] { const char* e = getenv("DN_DW_MIN_CHUNKS"); const int v = e ? atoi(e) : 0; return v > 0 ? v : 8; }();
+    return n;
+}
+int dw_place()
+{
+    static const int n = [] { const char* e = getenv("DN_DW_PLACE"); return e ? atoi(e) : 0; }();
+    return n;
 }
 int gemm_tile_edge_dw()
 {
@@ -466,15 +501,17 @@ int dn_gemm_dw_all(const dn_model* m, const dn_batch* b, float* const* dws, floa
     GemmGroup G{};
     ReduceGroup R{};
     G.n = m->k;
+    G.place = dw_place();
     R.n = m->k;
+    R.min_chunks = dw_min_chunks();
     int blocks = 0, red_blocks = 0;
     const int T = gemm_tile_edge_dw();
     for (int i = 1; i <= m->k; ++i) {
         const dn_layer_bufs& L = m->layer[i - 1];
         int64_t chunks_cap = (L.rows_cap + BK - 1) / BK;
         // enough workgroups to fill the chip, no more: every split costs a partial tile to write and re-read
-        const int tiles = ((L.kx + T - 1) / T) * ((L.d_out + T - 1) / T) * L.zterms;
-        int splits = ((T == 64 ? 2048 : 512) + tiles - 1) / tiles;
+        const int tiles = ((L.kx + T - 1) / T) * ((L.d_out + T - 1) / T) * (DW_FUSE ? 1 : L.zterms);
+        int splits = ((T == 64 ? 2048 : dw_target_blocks()) + tiles - 1) / tiles;
         if (splits > m->splits) splits = m->splits;
         if (splits > chunks_cap) splits = (int)(chunks_cap > 0 ? chunks_cap : 1);
         if (splits < 1) splits = 1;
@@ -484,17 +521,18 @@ int dn_gemm_dw_all(const dn_model* m, const dn_batch* b, float* const* dws, floa
         a.C = L.partial; a.ldc = L.d_out;
         a.hdr = b->hdr; a.layer = i; a.m_const = L.kx; a.ncols = L.d_out; a.red_const = -1;
         a.bias = nullptr; a.relu = 0; a.split_stride = (int64_t)L.kx * L.d_out;
-        a.terms = L.zterms; a.b_term_stride = L.np;
+        a.terms = L.zterms; a.b_term_stride = L.np; a.min_chunks = dw_min_chunks();
         a.db_partial = (i < m->k) ? L.db_partial : nullptr;          // the last layer's bias gradient comes from its dZ kernel
-        const int zsplits = splits * L.zterms;
+        const int zsplits = splits * (DW_FUSE ? 1 : L.zterms);
         if ((int64_t)zsplits * a.split_stride > L.partial_floats) return dn_fail(DN_ECAPACITY, "dW partial buffer too small");
         const int y = i - 1;
         G.gx[y] = (L.d_out + T - 1) / T;
         G.gy[y] = (L.kx + T - 1) / T;
         G.gz[y] = zsplits;
         G.begin[y] = blocks;
-        blocks += G.gx[y] * (int)dn_round_up((int64_t)G.gy[y] * G.gz[y], 8);     // a multiple of 8: every layer starts on XCD 0
-        R.partial[y] = L.partial; R.split_stride[y] = a.split_stride; R.groups[y] = splits; R.zterms[y] = L.zterms;
+        blocks += G.place == 0 ? G.gx[y] * (int)dn_round_up((int64_t)G.gy[y] * G.gz[y], 8)   // a multiple of 8: every layer starts on XCD 0
+                               : G.gx[y] * G.gy[y] * (int)dn_round_up(G.gz[y], 8);
+        R.partial[y] = L.partial; R.split_stride[y] = a.split_stride; R.groups[y] = splits; R.zterms[y] = DW_FUSE ? 1 : L.zterms;   // fused: the GEMM reduced both dZ terms
         R.xterms[y] = L.xterms;
         R.d_in[y] = L.d_in; R.d_out[y] = L.d_out; R.layer[y] = i;
         R.dws[y] = dws[y]; R.dwn[y] = dwn[y]; R.db[y] = dbias[y]; R.db_partial[y] = L.db_partial;

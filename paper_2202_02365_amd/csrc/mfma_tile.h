@@ -105,16 +105,24 @@ __device__ __forceinline__ void mainloop(const uint16_t* __restrict__ A_tile, co
         }
     };
 
+    // The prefetch is issued without a condition (past the last k-step it fetches the last tile again and nobody
+    // uses it): behind a branch the compiler no longer knows how many loads are outstanding, and then waits for ALL of
+    // them before a tile goes to LDS, which leaves a single tile in flight.  The scheduling barriers keep the
+    // loads in front of the multiplication.
+    if (kc_begin >= kc_end) return;
     TileRegs<LA, LB> r0, r1;
-    if (kc_begin + 0 < kc_end) load_tiles(r0, kc_begin + 0);
-    if (kc_begin + 1 < kc_end) load_tiles(r1, kc_begin + 1);
+    load_tiles(r0, kc_begin);
+    load_tiles(r1, min(kc_begin + 1, kc_end - 1));
     int kc = kc_begin, buf = 0;
 #define DN_GEMM_STEP(R)                                       \
     if (kc >= kc_end) break;                                  \
     store_tiles(R, buf);                                      \
     __syncthreads();                                          \
-    if (kc + 2 < kc_end) load_tiles(R, kc + 2);               \
+    __builtin_amdgcn_sched_barrier(0);                        \
+    load_tiles(R, min(kc + 2, kc_end - 1));                   \
+    __builtin_amdgcn_sched_barrier(0);                        \
     multiply(buf);                                            \
+    __builtin_amdgcn_sched_barrier(0);                        \
     buf ^= 1;                                                 \
     ++kc;
     for (;;) {
@@ -141,9 +149,13 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 
 // ONES: where `do_ones` holds (the same for a whole wave), ones_acc[j] also accumulates a row of ones times B's
 // fragments: every row of that 32 x 32 tile is the sum of B over the reduction range, column by column.
-template <int BM_, int BN_, bool ONES = false>
+// B may come as two terms (b_terms = 2: the second BN_ columns start b_term_stride elements after the first): both
+// are multiplied with the same A fragments into the same accumulators, i.e. the reduction runs over both terms, and
+// A is read once for the two.  TERMS2 = false leaves out the second term's LDS (b_terms must be 1 then).
+template <int BM_, int BN_, bool ONES = false, bool TERMS2 = false>
 __device__ __forceinline__ void mainloop_tn(const uint16_t* __restrict__ A, const int64_t lda, const int a_cols,
                                             const uint16_t* __restrict__ B, const int64_t ldb, const int b_cols,
+                                            const int b_terms, const int64_t b_term_stride,
                                             const int m0, const int n0, const int kc_begin, const int kc_end,
                                             const int k_rows, f32x16 (&acc)[BM_ / 64][BN_ / 64],
                                             f32x16* ones_acc = nullptr, const bool do_ones = false)
@@ -153,9 +165,11 @@ __device__ __forceinline__ void mainloop_tn(const uint16_t* __restrict__ A, cons
     constexpr int LA = BK * CA / TPB, LB = BK * CB / TPB;
     constexpr int RSA = BM_ + 16, RSB = BN_ + 16;        // LDS row stride in elements (32 bytes of padding)
     __shared__ __attribute__((aligned(16))) uint16_t As[2][BK * RSA];
-    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BK * RSB];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][TERMS2 ? 2 : 1][BK * RSB];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wm = wave >> 1, wn = wave & 1;
+    const bool two = TERMS2 && b_terms == 2;
+    const int64_t term2_off = b_term_stride * (int64_t)(b_terms - 1);     // 0 with one term: the read repeats the first
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -171,31 +185,40 @@ __device__ __forceinline__ void mainloop_tn(const uint16_t* __restrict__ A, cons
     const s16x8 one_bits = {0x3F80, 0x3F80, 0x3F80, 0x3F80, 0x3F80, 0x3F80, 0x3F80, 0x3F80};     // bf16 1.0
     const bf16x8 one8 = __builtin_bit_cast(bf16x8, one_bits);
 
-    auto load_tiles = [&](TileRegs<LA, LB>& r, int kc) {
+    // Every load is issued without a branch (a chunk outside the operand reads its last row or last 8 columns
+    // instead; zeros replace it when the tile goes to LDS, one k-step later): only then does the compiler know how
+    // many loads are outstanding and lets the wait for one k-step's tiles pass while the next k-step's are in flight.
+    auto load_tiles = [&](TileRegs<LA, 2 * LB>& r, int kc) {
         const int k0 = kc * BK;
 #pragma unroll
         for (int i = 0; i < LA; ++i) {
             const int id = t + TPB * i, kr = id / CA, c = id % CA;
+            r.a[i] = *reinterpret_cast<const u32x4*>(A + (int64_t)min(k0 + kr, k_rows - 1) * lda + min(m0 + c * 8, a_cols - 8));
+        }
+#pragma unroll
+        for (int i = 0; i < LB; ++i) {
+            const int id = t + TPB * i, kr = id / CB, c = id % CB;
+            const uint16_t* src = B + (int64_t)min(k0 + kr, k_rows - 1) * ldb + min(n0 + c * 8, b_cols - 8);
+            r.b[i] = *reinterpret_cast<const u32x4*>(src);
+            // with one term the second read repeats the first and is not used
+            if (TERMS2) r.b[LB + i] = *reinterpret_cast<const u32x4*>(src + term2_off);
+        }
+    };
+    auto store_tiles = [&](const TileRegs<LA, 2 * LB>& r, int buf, int kc) {
+        const int k0 = kc * BK;
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int i = 0; i < LA; ++i) {
+            const int id = t + TPB * i, kr = id / CA, c = id % CA;
             const bool ok = k0 + kr < k_rows && m0 + c * 8 < a_cols;
-            r.a[i] = ok ? *reinterpret_cast<const u32x4*>(A + (int64_t)(k0 + kr) * lda + m0 + c * 8) : u32x4{0u, 0u, 0u, 0u};
+            *reinterpret_cast<u32x4*>(&As[buf][kr * RSA + c * 8]) = ok ? r.a[i] : zero;
         }
 #pragma unroll
         for (int i = 0; i < LB; ++i) {
             const int id = t + TPB * i, kr = id / CB, c = id % CB;
             const bool ok = k0 + kr < k_rows && n0 + c * 8 < b_cols;
-            r.b[i] = ok ? *reinterpret_cast<const u32x4*>(B + (int64_t)(k0 + kr) * ldb + n0 + c * 8) : u32x4{0u, 0u, 0u, 0u};
-        }
-    };
-    auto store_tiles = [&](const TileRegs<LA, LB>& r, int buf) {
-#pragma unroll
-        for (int i = 0; i < LA; ++i) {
-            const int id = t + TPB * i, kr = id / CA, c = id % CA;
-            *reinterpret_cast<u32x4*>(&As[buf][kr * RSA + c * 8]) = r.a[i];
-        }
-#pragma unroll
-        for (int i = 0; i < LB; ++i) {
-            const int id = t + TPB * i, kr = id / CB, c = id % CB;
-            *reinterpret_cast<u32x4*>(&Bs[buf][kr * RSB + c * 8]) = r.b[i];
+            *reinterpret_cast<u32x4*>(&Bs[buf][0][kr * RSB + c * 8]) = ok ? r.b[i] : zero;
+            if (two) *reinterpret_cast<u32x4*>(&Bs[buf][TERMS2 ? 1 : 0][kr * RSB + c * 8]) = ok ? r.b[LB + i] : zero;
         }
     };
     // this lane's part of the address pattern: reduction row offset and column offset inside a 32-column fragment
@@ -210,39 +233,49 @@ __device__ __forceinline__ void mainloop_tn(const uint16_t* __restrict__ A, cons
         const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         return __builtin_bit_cast(bf16x8, v);
     };
-    auto multiply = [&](int buf) {
+    auto multiply_term = [&](const bf16x8 (&fa)[MI], const uint16_t* btile, int ks) {
+        bf16x8 fb[NJ];
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 fa[MI], fb[NJ];
+        for (int j = 0; j < NJ; ++j) fb[j] = read_frag(btile, RSB, ks * 16, wn * (BN_ / 2) + j * 32);
 #pragma unroll
-            for (int i = 0; i < MI; ++i) fa[i] = read_frag(As[buf], RSA, ks * 16, wm * (BM_ / 2) + i * 32);
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) fb[j] = read_frag(Bs[buf], RSB, ks * 16, wn * (BN_ / 2) + j * 32);
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
+            for (int j = 0; j < NJ; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        if (ONES) {
+            if (do_ones) {
 #pragma unroll
                 for (int j = 0; j < NJ; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-            if (ONES) {
-                if (do_ones) {
-#pragma unroll
-                    for (int j = 0; j < NJ; ++j)
-                        ones_acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(one8, fb[j], ones_acc[j], 0, 0, 0);
-                }
+                    ones_acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(one8, fb[j], ones_acc[j], 0, 0, 0);
             }
         }
     };
+    auto multiply = [&](int buf) {
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8 fa[MI];
+#pragma unroll
+            for (int i = 0; i < MI; ++i) fa[i] = read_frag(As[buf], RSA, ks * 16, wm * (BM_ / 2) + i * 32);
+            multiply_term(fa, Bs[buf][0], ks);
+            if (two) multiply_term(fa, Bs[buf][TERMS2 ? 1 : 0], ks);
+        }
+    };
 
-    TileRegs<LA, LB> r0, r1;
-    if (kc_begin + 0 < kc_end) load_tiles(r0, kc_begin + 0);
-    if (kc_begin + 1 < kc_end) load_tiles(r1, kc_begin + 1);
+    // unconditional prefetch and scheduling barriers as in mainloop
+    if (kc_begin >= kc_end) return;
+    TileRegs<LA, 2 * LB> r0, r1;
+    load_tiles(r0, kc_begin);
+    load_tiles(r1, min(kc_begin + 1, kc_end - 1));
     int kc = kc_begin, buf = 0;
 #define DN_GEMM_STEP(R)                                       \
     if (kc >= kc_end) break;                                  \
-    store_tiles(R, buf);                                      \
+    store_tiles(R, buf, kc);                                  \
     __syncthreads();                                          \
-    if (kc + 2 < kc_end) load_tiles(R, kc + 2);               \
+    __builtin_amdgcn_sched_barrier(0);                        \
+    load_tiles(R, min(kc + 2, kc_end - 1));                   \
+    __builtin_amdgcn_sched_barrier(0);                        \
     multiply(buf);                                            \
+    __builtin_amdgcn_sched_barrier(0);                        \
     buf ^= 1;                                                 \
     ++kc;
     for (;;) {
