@@ -850,6 +850,12 @@ def main():
                          % (args.replicas, "scheduled by the library (dn_train_steps)"
                             if fused and not args.replica_graphs and not args.python_replicas else "launched from Python"))
 
+    # one mini-batch at a time, but scheduled by the library (dn_train_steps on one stream)
+    one_lib_s = None
+    if fused and not args.python_replicas:
+        one_lib_s = timed_replicas(args.steps, 1)
+        log("one mini-batch at a time through dn_train_steps: %.3f ms/step" % (1e3 * one_lib_s / args.steps))
+
     if model.status()[1] != 0:
         raise RuntimeError("the ReLU sign fix-up queue overflowed during the timed run")
 
@@ -1002,7 +1008,11 @@ def main():
                               "sampled_edges_per_s": edges / fwd_only_s},
         "one_in_flight": {"ms_per_step": 1e3 * serial_s / args.steps, "mini_batches_per_s": args.steps / serial_s,
                           "sampled_edges_per_s": edges / serial_s,
-                          "sample_gather_fwd_ms_per_step": 1e3 * serial_fwd_s / args.steps},
+                          "sample_gather_fwd_ms_per_step": 1e3 * serial_fwd_s / args.steps,
+                          "launch": "every call of the path made from Python on one stream"},
+        "one_in_flight_library": None if one_lib_s is None else
+                                 {"ms_per_step": 1e3 * one_lib_s / args.steps, "mini_batches_per_s": args.steps / one_lib_s,
+                                  "launch": "dn_train_steps with one stream"},
         "repeats": REPEATS,
         "timing": "every figure is the median of %d timed blocks of `steps` steps" % REPEATS,
         "one_in_flight_blocks_ms": [1e3 * t / args.steps for t in serial_all],

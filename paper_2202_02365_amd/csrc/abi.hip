@@ -647,8 +647,13 @@ int dn_train_steps(const dn_train_step* steps, int32_t n_steps, int32_t n_stream
     int rc = DN_OK;
     for (int i = 0; i < n_steps && rc == DN_OK; ++i) {
         const dn_train_step& t = steps[i];
-        hipStream_t st = ss.stream[i % n_streams];
+        const int j = i % n_streams;
+        hipStream_t st = ss.stream[j];
         rc = dense_sample(t.batch, t.graph, t.d_targets, t.n_targets, t.seed, st);
+        // (Building the backward pass's transpose index on a further stream beside the forward pass was tried: one step
+        // at a time went from 0.263 to 0.256 ms, but a process has four hardware queues which streams take in the order
+        // of their creation, and whenever a side stream shared a queue with a step stream the steps got slower, up to
+        // 0.19 from 0.165 ms with four in flight.)
         if (rc == DN_OK) rc = sage_forward_table(t.model, t.batch, t.d_table, t.ld_elems, t.d_out, st);
         if (rc != DN_OK || t.forward_only) continue;
         const int k = t.model->k;

@@ -201,14 +201,21 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const int bx, const
 // Workgroups are handed to the 8 XCDs (each with an L2 of its own) round-robin in launch order.  The column
 // tiles of one row tile read the same rows of A: the launch order is therefore re-read as chunks of 8 x (column
 // tiles), in which the workgroups j, j + 8, j + 16, ... (same XCD) are the column tiles of one row tile.
-// gridDim.y is a multiple of 8.
+// gridDim.y is a multiple of 8 and at most GEMM_MAX_ROW_BLOCKS: a workgroup takes the row tiles by, by + gridDim.y, ...
+// (the capacity of rows is several times what a mini-batch fills, and a grid sized by it consists mostly of workgroups
+// that find no rows and leave: at 1 us each they delayed the end of a 15 us kernel by a third).
+constexpr int GEMM_MAX_ROW_BLOCKS = 512;
 template <int EPI, int LAYER_TAG, int BM_, int BN_>
 __global__ __launch_bounds__(TPB, (BM_ == 64 && BN_ == 64) ? 4 : 2) void k_gemm_nt(GemmArgs a)
 {
     const int nx = gridDim.x;
     const int id = blockIdx.x + nx * blockIdx.y;
     const int chunk = id / (8 * nx), j = id - chunk * 8 * nx;
-    gemm_tile<EPI, BM_, BN_>(a, j >> 3, chunk * 8 + (j & 7), blockIdx.z, gridDim.z);
+    const int M = a.m_const >= 0 ? a.m_const : a.hdr[HDR_N] - a.hdr[HDR_NODE_OFF + a.layer];
+    for (int by = chunk * 8 + (j & 7); by * BM_ < M; by += gridDim.y) {
+        gemm_tile<EPI, BM_, BN_>(a, j >> 3, by, blockIdx.z, gridDim.z);
+        __syncthreads();                  // the tile's LDS buffers are free for the next one
+    }
 }
 
 // The dW GEMMs of all layers in one launch: a 1-D grid, each layer owns the workgroups
@@ -246,41 +253,51 @@ __global__ __launch_bounds__(TPB, 2) void k_gemm_dw_group(GemmGroup G)
 
 // dW[kk][n] = sum over the X terms (rows kk + t*2d) and over the splits, in a fixed order;
 // rows kk < d go to dW_self, d <= kk < 2d to dW_nbr.
+// W = outputs per thread: 4 (16-byte loads) where d_in * d_out is a multiple of 4, which keeps every partial tile
+// and the boundary between dW_self and dW_nbr 16-byte aligned; 1 otherwise.
+template <int W>
 __device__ __forceinline__ void dw_reduce_block(const int block, const float* __restrict__ partial, int64_t split_stride,
                                                 int groups, int zterms, int rows, int xterms, int d_in, int d_out,
                                                 int min_chunks, float* __restrict__ dws, float* __restrict__ dwn)
 {
-    // 64 consecutive outputs per workgroup; each of its 4 waves sums a quarter of the list of partials
-    __shared__ float quarter[4][64];
+    // 64 W consecutive outputs per workgroup; each of its 4 waves sums a quarter of the list of partials
+    __shared__ float quarter[4][64 * W];
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    const int idx = block * 64 + tx;
+    const int idx = (block * 64 + tx) * W;
     const bool live = idx < 2 * d_in * d_out;
-    const int kk = live ? idx / d_out : 0, n = live ? idx - kk * d_out : 0;
     const int eff = effective_splits(groups, (rows + BK - 1) / BK, min_chunks);   // the splits the GEMM actually wrote
     // Wave ty takes the splits ty, ty + 4, ... of every (X term, dZ term) combination, eight loads in flight into
-    // eight running sums (a load past the last split re-reads the last one and counts as zero).  The order is
-    // fixed; the chain of dependent loads bounds this kernel, not the bytes.
-    const float* base = partial + (int64_t)kk * d_out + n;
-    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    // eight running sums (a load past the last split re-reads the last one and counts as zero).  The order is fixed.
+    typedef float vecw __attribute__((ext_vector_type(W)));
+    const float* base = partial + (live ? idx : 0);
+    vecw acc[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc[u] = vecw(0.f);
     if (live) {
         for (int t = 0; t < xterms; ++t)
             for (int zt = 0; zt < zterms; ++zt) {
                 const float* src = base + (int64_t)zt * groups * split_stride + (int64_t)t * 2 * d_in * d_out;
                 for (int z = ty; z < eff; z += 32) {
-                    float v[8];
+                    vecw v[8];
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)min(z + 4 * u, eff - 1) * split_stride];
+                    for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const vecw*>(src + (int64_t)min(z + 4 * u, eff - 1) * split_stride);
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) acc[u] += (z + 4 * u < eff) ? v[u] : 0.f;
+                    for (int u = 0; u < 8; ++u) acc[u] += (z + 4 * u < eff) ? v[u] : vecw(0.f);
                 }
             }
     }
-    quarter[ty][tx] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
+    const vecw mine = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
+#pragma unroll
+    for (int e = 0; e < W; ++e) quarter[ty][tx * W + e] = mine[e];
     __syncthreads();
     if (ty == 0 && live) {
-        const float s = (quarter[0][tx] + quarter[1][tx]) + (quarter[2][tx] + quarter[3][tx]);
-        if (kk < d_in) dws[(int64_t)kk * d_out + n] = s;
-        else dwn[(int64_t)(kk - d_in) * d_out + n] = s;
+#pragma unroll
+        for (int e = 0; e < W; ++e) {
+            const float s = (quarter[0][tx * W + e] + quarter[1][tx * W + e]) + (quarter[2][tx * W + e] + quarter[3][tx * W + e]);
+            const int o = idx + e;                               // = kk * d_out + n over [self ; nbr]
+            if (o < d_in * d_out) dws[o] = s;
+            else dwn[o - d_in * d_out] = s;
+        }
     }
 }
 
@@ -345,7 +362,7 @@ struct ReduceGroup {
     int xterms[DN_MAX_LAYERS], d_in[DN_MAX_LAYERS], d_out[DN_MAX_LAYERS], layer[DN_MAX_LAYERS];
     float *dws[DN_MAX_LAYERS], *dwn[DN_MAX_LAYERS], *db[DN_MAX_LAYERS];
     const float* db_partial[DN_MAX_LAYERS];
-    int dw_blocks[DN_MAX_LAYERS], db_blocks[DN_MAX_LAYERS];
+    int dw_blocks[DN_MAX_LAYERS], db_blocks[DN_MAX_LAYERS], vec4[DN_MAX_LAYERS];
     int db_from_tiles[DN_MAX_LAYERS];    // last layer: the partials are the dZ kernel's, one per row tile
     int begin[DN_MAX_LAYERS + 1];
     int n, min_chunks;
@@ -357,8 +374,12 @@ __global__ __launch_bounds__(TPB) void k_bwd_reduce_group(ReduceGroup R, const i
     const int x = (int)blockIdx.x - R.begin[y];
     const int rows = hdr[HDR_N] - hdr[HDR_NODE_OFF + R.layer[y]];
     if (x < R.dw_blocks[y]) {
-        dw_reduce_block(x, R.partial[y], R.split_stride[y], R.groups[y], R.zterms[y], rows, R.xterms[y], R.d_in[y], R.d_out[y],
-                        R.min_chunks, R.dws[y], R.dwn[y]);
+        if (R.vec4[y])
+            dw_reduce_block<4>(x, R.partial[y], R.split_stride[y], R.groups[y], R.zterms[y], rows, R.xterms[y], R.d_in[y],
+                               R.d_out[y], R.min_chunks, R.dws[y], R.dwn[y]);
+        else
+            dw_reduce_block<1>(x, R.partial[y], R.split_stride[y], R.groups[y], R.zterms[y], rows, R.xterms[y], R.d_in[y],
+                               R.d_out[y], R.min_chunks, R.dws[y], R.dwn[y]);
     } else if (x < R.dw_blocks[y] + R.db_blocks[y]) {
         if (R.db_from_tiles[y]) db_reduce_tiles(x - R.dw_blocks[y], rows, R.db_partial[y], R.d_out[y], R.db[y]);
         else db_reduce_block(x - R.dw_blocks[y], rows, R.db_partial[y], R.groups[y], R.zterms[y], R.d_out[y], R.min_chunks, R.db[y]);
@@ -442,6 +463,7 @@ int launch_t(const GemmArgs& a, int64_t m_cap, int splits, hipStream_t st)
 {
     dim3 grid((unsigned)((a.ncols + T - 1) / T), (unsigned)dn_round_up((m_cap + T - 1) / T, 8), (unsigned)splits);
     if (grid.y == 0) grid.y = 8;
+    if (grid.y > (unsigned)GEMM_MAX_ROW_BLOCKS) grid.y = GEMM_MAX_ROW_BLOCKS;
     switch (a.layer) {
         case 1: hipLaunchKernelGGL((k_gemm_nt<EPI, 1, T, T>), grid, dim3(TPB), 0, st, a); break;
         case 2: hipLaunchKernelGGL((k_gemm_nt<EPI, 2, T, T>), grid, dim3(TPB), 0, st, a); break;
@@ -536,7 +558,8 @@ int dn_gemm_dw_all(const dn_model* m, const dn_batch* b, float* const* dws, floa
         R.xterms[y] = L.xterms;
         R.d_in[y] = L.d_in; R.d_out[y] = L.d_out; R.layer[y] = i;
         R.dws[y] = dws[y]; R.dwn[y] = dwn[y]; R.db[y] = dbias[y]; R.db_partial[y] = L.db_partial;
-        R.dw_blocks[y] = (2 * L.d_in * L.d_out + 63) / 64;
+        R.vec4[y] = ((int64_t)L.d_in * L.d_out) % 4 == 0 ? 1 : 0;
+        R.dw_blocks[y] = R.vec4[y] ? (2 * L.d_in * L.d_out + 255) / 256 : (2 * L.d_in * L.d_out + 63) / 64;
         R.db_from_tiles[y] = (i == m->k) ? 1 : 0;
         R.db_blocks[y] = (i == m->k) ? (L.d_out + DB_TILE_COLS - 1) / DB_TILE_COLS : (L.d_out + DB_COLS - 1) / DB_COLS;
         R.begin[y] = red_blocks;
