@@ -403,6 +403,9 @@ __global__ __launch_bounds__(SMALL_TPB) void k_tr_small(int32_t* __restrict__ hd
         for (int u = 0; u < SMALL_BATCH; ++u) {
             const int kl = kv[u];
             const bool mine = kl >= 0 && kl < SMALL_KEYS;
+            // a workgroup owns 512 of ~100k keys: three of four steps hold none of its pairs, and the kernel is bound
+            // by the instructions its 16 waves issue on one compute unit, so those steps end here
+            if (__ballot(mine) == 0) continue;
             int rank, count;
             step_peers(kl, mine, lane, rank, count);
             if (mine) tr_val[cnt[wave][kl] + rank] = first + (st + u) * 64 + lane;
