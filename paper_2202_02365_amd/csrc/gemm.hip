@@ -39,6 +39,16 @@ enum { EPI_BIAS_ACT = 0, EPI_PLAIN = 1, EPI_SPLIT = 2 };
 #define DN_DW_FUSE_TERMS 0
 #endif
 constexpr bool DW_FUSE = DN_DW_FUSE_TERMS != 0;
+#ifndef DN_NT_STAGES
+#define DN_NT_STAGES 2
+#endif
+#ifndef DN_TN_STAGES
+#define DN_TN_STAGES 2
+#endif
+// register stages of global prefetch (see mainloop).  More than two were measured slower: four stages on the 64 x 64
+// forward tiles (two workgroups per compute unit instead of four) 22.5 against 16.5 us at the 111M-node workload and
+// 59.5 against 46.9 at the 122M-node one; three stages on the weight gradient 26.3 against 24.8 and 79.7 against 77.6.
+constexpr int NT_STAGES = DN_NT_STAGES, TN_STAGES = DN_TN_STAGES;
 
 
 struct GemmArgs {
@@ -106,7 +116,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const int bx, const
         // split's rows of dZ, which are its share of the bias gradient.
         f32x16 ones_acc[NJ];
         const bool do_ones = by == 0 && wm == 0 && a.db_partial != nullptr;
-        mainloop_tn<BM_, BN_, true, DW_FUSE>(a.A, a.lda, a.a_cols, Bbase, a.ldb, a.b_cols, DW_FUSE ? a.terms : 1, a.b_term_stride,
+        mainloop_tn<BM_, BN_, true, DW_FUSE, TN_STAGES>(a.A, a.lda, a.a_cols, Bbase, a.ldb, a.b_cols, DW_FUSE ? a.terms : 1, a.b_term_stride,
                                              row0, col0, kc_begin, kc_end, rows_layer, acc, ones_acc, do_ones);
         if (do_ones && lane < 32) {                           // register 0 of lanes 0..31: row 0 of the 32 x 32 tile
 #pragma unroll
@@ -116,7 +126,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const int bx, const
             }
         }
     } else
-        mainloop<BM_, BN_, false>(a.A + (int64_t)row0 * a.lda, a.lda, Bbase + (int64_t)col0 * a.ldb, a.ldb, kc_begin, kc_end, 0, acc);
+        mainloop<BM_, BN_, false, NT_STAGES>(a.A + (int64_t)row0 * a.lda, a.lda, Bbase + (int64_t)col0 * a.ldb, a.ldb, kc_begin, kc_end, 0, acc);
 
     // epilogue: lane holds column (lane & 31); register e holds row 8*(e/4) + 4*(lane/32) + e%4
     float* C = a.C;

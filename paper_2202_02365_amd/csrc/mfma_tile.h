@@ -35,7 +35,9 @@ struct TileRegs { u32x4 a[LA], b[LB]; };
 // Register e of acc[i][j] holds row (BM_/2)*wm + 32*i + 8*(e/4) + 4*(lane/32) + e%4, column (BN_/2)*wn + 32*j + lane%32.
 // The small tile is for problems with few rows: four times as many workgroups, several of them per compute
 // unit, so that one workgroup's memory latency is covered by another's arithmetic.
-template <int BM_, int BN_, bool WRAP_B>
+// STAGES register stages of global prefetch: a k-step waits for a tile requested STAGES k-steps before.  More than
+// two were measured slower (figures in gemm.hip): they cost the registers that let four workgroups share a compute unit.
+template <int BM_, int BN_, bool WRAP_B, int STAGES = 2>
 __device__ __forceinline__ void mainloop(const uint16_t* __restrict__ A_tile, const int64_t lda,
                                          const uint16_t* __restrict__ B_tile, const int64_t ldb,
                                          const int kc_begin, const int kc_end, const int b_wrap_chunks,
@@ -110,26 +112,25 @@ __device__ __forceinline__ void mainloop(const uint16_t* __restrict__ A_tile, co
     // them before a tile goes to LDS, which leaves a single tile in flight.  The scheduling barriers keep the
     // loads in front of the multiplication.
     if (kc_begin >= kc_end) return;
-    TileRegs<LA, LB> r0, r1;
-    load_tiles(r0, kc_begin);
-    load_tiles(r1, min(kc_begin + 1, kc_end - 1));
+    TileRegs<LA, LB> r[STAGES];
+#pragma unroll
+    for (int s = 0; s < STAGES; ++s) load_tiles(r[s], min(kc_begin + s, kc_end - 1));
     int kc = kc_begin, buf = 0;
-#define DN_GEMM_STEP(R)                                       \
-    if (kc >= kc_end) break;                                  \
-    store_tiles(R, buf);                                      \
-    __syncthreads();                                          \
-    __builtin_amdgcn_sched_barrier(0);                        \
-    load_tiles(R, min(kc + 2, kc_end - 1));                   \
-    __builtin_amdgcn_sched_barrier(0);                        \
-    multiply(buf);                                            \
-    __builtin_amdgcn_sched_barrier(0);                        \
-    buf ^= 1;                                                 \
-    ++kc;
-    for (;;) {
-        DN_GEMM_STEP(r0)
-        DN_GEMM_STEP(r1)
+    for (bool more = true; more;) {
+#pragma unroll
+        for (int s = 0; s < STAGES; ++s) {
+            if (kc >= kc_end) { more = false; break; }
+            store_tiles(r[s], buf);
+            __syncthreads();
+            __builtin_amdgcn_sched_barrier(0);
+            load_tiles(r[s], min(kc + STAGES, kc_end - 1));
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(buf);
+            __builtin_amdgcn_sched_barrier(0);
+            buf ^= 1;
+            ++kc;
+        }
     }
-#undef DN_GEMM_STEP
 }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -152,7 +153,7 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 // B may come as two terms (b_terms = 2: the second BN_ columns start b_term_stride elements after the first): both
 // are multiplied with the same A fragments into the same accumulators, i.e. the reduction runs over both terms, and
 // A is read once for the two.  TERMS2 = false leaves out the second term's LDS (b_terms must be 1 then).
-template <int BM_, int BN_, bool ONES = false, bool TERMS2 = false>
+template <int BM_, int BN_, bool ONES = false, bool TERMS2 = false, int STAGES = 2>
 __device__ __forceinline__ void mainloop_tn(const uint16_t* __restrict__ A, const int64_t lda, const int a_cols,
                                             const uint16_t* __restrict__ B, const int64_t ldb, const int b_cols,
                                             const int b_terms, const int64_t b_term_stride,
@@ -261,28 +262,27 @@ __device__ __forceinline__ void mainloop_tn(const uint16_t* __restrict__ A, cons
         }
     };
 
-    // unconditional prefetch and scheduling barriers as in mainloop
+    // unconditional prefetch, STAGES register stages and scheduling barriers as in mainloop
     if (kc_begin >= kc_end) return;
-    TileRegs<LA, 2 * LB> r0, r1;
-    load_tiles(r0, kc_begin);
-    load_tiles(r1, min(kc_begin + 1, kc_end - 1));
+    TileRegs<LA, 2 * LB> r[STAGES];
+#pragma unroll
+    for (int s = 0; s < STAGES; ++s) load_tiles(r[s], min(kc_begin + s, kc_end - 1));
     int kc = kc_begin, buf = 0;
-#define DN_GEMM_STEP(R)                                       \
-    if (kc >= kc_end) break;                                  \
-    store_tiles(R, buf, kc);                                  \
-    __syncthreads();                                          \
-    __builtin_amdgcn_sched_barrier(0);                        \
-    load_tiles(R, min(kc + 2, kc_end - 1));                   \
-    __builtin_amdgcn_sched_barrier(0);                        \
-    multiply(buf);                                            \
-    __builtin_amdgcn_sched_barrier(0);                        \
-    buf ^= 1;                                                 \
-    ++kc;
-    for (;;) {
-        DN_GEMM_STEP(r0)
-        DN_GEMM_STEP(r1)
+    for (bool more = true; more;) {
+#pragma unroll
+        for (int s = 0; s < STAGES; ++s) {
+            if (kc >= kc_end) { more = false; break; }
+            store_tiles(r[s], buf, kc);
+            __syncthreads();
+            __builtin_amdgcn_sched_barrier(0);
+            load_tiles(r[s], min(kc + STAGES, kc_end - 1));
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(buf);
+            __builtin_amdgcn_sched_barrier(0);
+            buf ^= 1;
+            ++kc;
+        }
     }
-#undef DN_GEMM_STEP
 }
 
 }  // namespace dn_mma
