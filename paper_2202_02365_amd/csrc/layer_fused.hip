@@ -69,8 +69,10 @@ __device__ __forceinline__ void split4(const float (&v)[4], uint2& hi, uint2& lo
     for (int e = 0; e < 4; ++e) sq += h[e] * h[e] + l[e] * l[e];
 }
 
-// S = d_in / 64 (1..4): the reduction over [self | mean] has 2 d_in = 128 S elements per term
-template <int S>
+// S = d_in / 64 (1..4): the reduction over [self | mean] has 2 d_in = 128 S elements per term.  LAYER_TAG only gives
+// every layer's launch a kernel symbol of its own, so that a profiler's per-kernel statistics do not mix the layers
+// (2, 3, and 4 for "layer 4 and above").
+template <int S, int LAYER_TAG>
 __global__ __launch_bounds__(FT) void k_sage_layer(FusedArgs a)
 {
     constexpr int D = 64 * S;
@@ -359,12 +361,16 @@ int dn_launch_layer_fused(const dn_model* m, const dn_batch* b, int i, float* ou
     int64_t grid = (L.rows_cap + FR - 1) / FR;
     if (grid < 1) grid = 1;
     dn_prof_scope ps("sage_layer", i, st);
+#define FUSED_LAUNCH(SS, TAG) hipLaunchKernelGGL((k_sage_layer<SS, TAG>), dim3((unsigned)grid), dim3(FT), 0, st, a)
+#define FUSED_LAUNCH_S(SS) do { if (i == 2) FUSED_LAUNCH(SS, 2); else if (i == 3) FUSED_LAUNCH(SS, 3); else FUSED_LAUNCH(SS, 4); } while (0)
     switch (L.d_in / 64) {
-        case 1: hipLaunchKernelGGL(k_sage_layer<1>, dim3((unsigned)grid), dim3(FT), 0, st, a); break;
-        case 2: hipLaunchKernelGGL(k_sage_layer<2>, dim3((unsigned)grid), dim3(FT), 0, st, a); break;
-        case 3: hipLaunchKernelGGL(k_sage_layer<3>, dim3((unsigned)grid), dim3(FT), 0, st, a); break;
-        default: hipLaunchKernelGGL(k_sage_layer<4>, dim3((unsigned)grid), dim3(FT), 0, st, a); break;
+        case 1: FUSED_LAUNCH_S(1); break;
+        case 2: FUSED_LAUNCH_S(2); break;
+        case 3: FUSED_LAUNCH_S(3); break;
+        default: FUSED_LAUNCH_S(4); break;
     }
+#undef FUSED_LAUNCH_S
+#undef FUSED_LAUNCH
     DN_LAUNCH_CHECK("k_sage_layer");
     return DN_OK;
 }
