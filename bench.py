@@ -79,6 +79,8 @@ def algorithmic_work(tag, sizes, cfg, dims):
         return "hbm", mean(level_nodes(0) * (4 + 16 * ndir + 8 + 12))
     if tag == "init_offsets":
         return "hbm", mean(level_nodes(0) * 8)
+    if tag == "init_level0":                  # both steps in one launch (target lists of a few thousand ids)
+        return "hbm", mean(level_nodes(0) * (4 + 16 * ndir + 8 + 12 + 4))
     if tag in ("mark_ids", "local_ids") and cfg.lp_edges:
         ids = 2.0 * cfg.lp_edges + cfg.lp_edges // cfg.lp_chunk * cfg.lp_negatives
         return "hbm", ids * 12.0
@@ -785,6 +787,10 @@ def main():
                 (n_rep, "whole step" if backward else "forward only", n, 1e3 * queued / n, 1e3 * spent / n))
             return spent
         run(max(args.warmup, n_rep))
+        # one read-back of the sizes per batch object, as a training loop does when it logs them: the library picks the
+        # form of the transpose-index build from the largest counts read back so far (a matter of speed only)
+        for o in reps:
+            o["batch"].counts()
         spent, _ = median_seconds(lambda: run(n_steps))
         if backward:
             # with every replica busy, the one that runs batch 5 must give the gradients of the one-at-a-time step

@@ -182,7 +182,12 @@ DN_API int  dn_batch_prepare_backward(dn_batch* b, int32_t need_input_grad, void
 DN_API int  dn_batch_view(const dn_batch* b, dn_dense_view* view);
 
 /* Copies node_id_offsets[0..k+1] followed by E (k+3 values) to host_counts and WAITS for `stream`.
- * Returns DN_ESAMPLE if the last dense_sample saw an invalid target set. */
+ * Returns DN_ESAMPLE if the last dense_sample saw an invalid target set.
+ * The batch object remembers the largest slot counts read back so far: the transpose-index build of sage_backward /
+ * dn_batch_prepare_backward takes its one-kernel form for a batch object whose mini-batches have stayed below a few
+ * ten thousand slots and the multi-pass sort otherwise or when no size was ever read back (both forms are correct for
+ * any size; a training loop that reads the sizes once per batch object, e.g. to log them, gets the faster one).
+ * dn_train_steps hands the counts on between batch objects of one shape that take turns in its step list. */
 DN_API int  dn_batch_counts(const dn_batch* b, int64_t* host_counts, void* stream);
 
 /* ---- dense_gather: H^0[r, :] = table[node_ids[r], :] for r < N (Section 4.2).

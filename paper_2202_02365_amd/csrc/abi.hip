@@ -642,6 +642,19 @@ int dn_train_steps(const dn_train_step* steps, int32_t n_steps, int32_t n_stream
     }
     hipStream_t outer = static_cast<hipStream_t>(stream);
     const int used = n_steps < n_streams ? n_steps : n_streams;
+    // The form of the transpose-index build goes by the slot counts that dn_batch_counts has read back for a batch
+    // object (a matter of speed only).  Batch objects of one shape that take turns here see mini-batches of one
+    // workload: those that have never been read back go by the largest counts of those that have.
+    for (int i = 0; i < n_steps; ++i) {
+        dn_batch* bi = steps[i].batch;
+        if (!bi || (bi->seen_slots_all >= 0 && bi->seen_slots_upper >= 0)) continue;
+        for (int j = 0; j < n_steps; ++j) {
+            const dn_batch* bj = steps[j].batch;
+            if (!bj || bj == bi || bj->k != bi->k || bj->cap_slots != bi->cap_slots || bj->cap_nodes != bi->cap_nodes) continue;
+            if (bj->seen_slots_all > bi->seen_slots_all) bi->seen_slots_all = bj->seen_slots_all;
+            if (bj->seen_slots_upper > bi->seen_slots_upper) bi->seen_slots_upper = bj->seen_slots_upper;
+        }
+    }
     DN_HIP(hipEventRecord(ss.start, outer));
     for (int j = 0; j < used; ++j) DN_HIP(hipStreamWaitEvent(ss.stream[j], ss.start, 0));
     int rc = DN_OK;

@@ -155,6 +155,52 @@ __global__ __launch_bounds__(TPB) void k_init_offsets(int n, int32_t* __restrict
     }
 }
 
+// Both steps in one launch for target lists of a few thousand ids: a workgroup adds up the counts of the targets in
+// front of its own by itself (reading their row offsets once more: at most INIT_FUSED_MAX / TPB rounds per thread),
+// so no workgroup waits for another and the second launch is gone.  Results are those of the two kernels above.
+constexpr int INIT_FUSED_MAX = 4096;
+__global__ __launch_bounds__(TPB) void k_init_level0(GraphDev g, int64_t V, const int32_t* __restrict__ targets,
+                                                     int n, int f0, int direction, int32_t* __restrict__ hdr,
+                                                     uint32_t* __restrict__ seen, int32_t* __restrict__ lvlpos,
+                                                     int32_t* __restrict__ lvl_ids, int32_t* __restrict__ lvl_nbr_offsets)
+{
+    __shared__ uint64_t sm[TPB / 64];
+    const int first = blockIdx.x * TPB;
+    const int i = first + threadIdx.x;
+    int c = 0;
+    if (i < n) {
+        int t = targets[i];
+        if (t < 0 || (int64_t)t >= V) {
+            atomicOr(&hdr[HDR_STATUS_ACC], ST_BAD_TARGET);
+            lvl_ids[i] = 0;                              // keeps every later access in bounds
+        } else {
+            const uint32_t bit = 1u << (t & 31);
+            const uint32_t old = atomicOr(&seen[BM(t >> 5)], bit);
+            if (old & bit) atomicOr(&hdr[HDR_STATUS_ACC], ST_DUP_TARGET);
+            lvl_ids[i] = t;
+            lvlpos[t] = i;
+            c = node_sample_count(g, t, f0, direction);
+        }
+    }
+    uint64_t before = 0;
+    for (int j = threadIdx.x; j < first; j += TPB) {
+        const int t = targets[j];
+        if (t >= 0 && (int64_t)t < V) before += (uint64_t)node_sample_count(g, t, f0, direction);
+    }
+    uint64_t base;
+    block_exclusive_scan(before, base, sm);              // base = slots of all targets in front of this workgroup
+    uint64_t total;
+    const uint64_t ex = block_exclusive_scan((uint64_t)c, total, sm);
+    if (i < n) lvl_nbr_offsets[i] = (int)(base + ex);
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+        hdr[HDR_LVL_OFF + 0] = 0;
+        hdr[HDR_LVL_OFF + 1] = n;
+        hdr[HDR_LVL_NBR_OFF + 0] = 0;
+        hdr[HDR_LVL_NBR_OFF + 1] = (int)(base + total);
+        hdr[HDR_NTARGETS] = n;
+    }
+}
+
 // ---------------------------------------------------------------- level 0 from training edges
 // Link prediction (Section 2: a training example is a pair of target nodes): the targets are the
 // distinct endpoints of the batch's edges plus the negative nodes.  Their ids are marked in the
@@ -499,6 +545,13 @@ int dn_launch_sample(dn_batch* b, const dn_graph* g, const int32_t* d_targets, i
 
     const int grid0 = n_targets > 0 ? (n_targets + TPB - 1) / TPB : 1;
     if (grid0 > b->max_blocks) return dn_fail(DN_ECAPACITY, "dense_sample: %d targets exceed the batch capacity", n_targets);
+    if (n_targets <= INIT_FUSED_MAX) {
+        dn_prof_scope ps("init_level0", 0, st);
+        hipLaunchKernelGGL(k_init_level0, dim3(grid0), dim3(TPB), 0, st, gd, b->V, d_targets, n_targets, b->fanouts[0], dir,
+                           b->hdr, b->seen, b->lvlpos, b->lvl_ids, b->lvl_nbr_offsets);
+        DN_LAUNCH_CHECK("k_init_level0");
+        return launch_hops_and_assemble(b, gd, n_targets, seed, st);
+    }
     { dn_prof_scope ps("init_targets", 0, st);
     hipLaunchKernelGGL(k_init_targets, dim3(grid0), dim3(TPB), 0, st, gd, b->V, d_targets, n_targets, b->fanouts[0], dir,
                        b->hdr, b->seen, b->lvlpos, b->lvl_ids, b->lvl_nbr_offsets, blk);
