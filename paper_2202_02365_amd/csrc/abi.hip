@@ -1,6 +1,7 @@
 // The C ABI of libdense_mi355x.so: argument checking, handle bookkeeping, workspace carve-up.
 // Every step of the hot path runs in the kernels behind the dn_launch_* calls.
 #include "dn_internal.h"
+#include <cstdlib>
 
 #include <cstdarg>
 #include <cstdio>
@@ -615,6 +616,7 @@ int dense_sample_noalloc(const dn_graph* g, const int32_t* d_targets, int32_t n_
 namespace {
 constexpr int STEP_MAX_STREAMS = 16, STEP_MAX_DEVICES = 64;
 struct StepStreams {
+    hipStream_t spare = nullptr;                  // created first and never used (see dn_train_steps)
     hipStream_t stream[STEP_MAX_STREAMS] = {};
     hipEvent_t done[STEP_MAX_STREAMS] = {};
     hipEvent_t start = nullptr;
@@ -635,6 +637,13 @@ int dn_train_steps(const dn_train_step* steps, int32_t n_steps, int32_t n_stream
     std::lock_guard<std::mutex> lock(g_step_mutex);
     StepStreams& ss = g_step_streams[dev];
     if (!ss.start) DN_HIP(hipEventCreateWithFlags(&ss.start, hipEventDisableTiming));
+    if (ss.created == 0 && !ss.spare) {
+        // One stream that is never used comes first.  Measured: when the step streams are the first streams the
+        // process creates, four steps in flight run at 0.195 ms per step of the 111M-node workload instead of 0.155
+        // (the first stream created shares its hardware queue less well); with one, or up to five, other streams
+        // created before them the rate is the same whatever else the process has created.
+        DN_HIP(hipStreamCreateWithFlags(&ss.spare, hipStreamNonBlocking));
+    }
     while (ss.created < n_streams) {
         DN_HIP(hipStreamCreateWithFlags(&ss.stream[ss.created], hipStreamNonBlocking));     // default priority
         DN_HIP(hipEventCreateWithFlags(&ss.done[ss.created], hipEventDisableTiming));

@@ -12,6 +12,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace dn_mma {
 
@@ -88,49 +89,68 @@ __device__ __forceinline__ void mainloop(const uint16_t* __restrict__ A_tile, co
             Bs[buf][slot(row, c)] = r.b[i];
         }
     };
+    // KG reduction sub-steps of 16 have their fragments requested together (all four on the small tile, two on the
+    // large one, whose accumulators leave fewer registers): the LDS reads of a sub-step then overlap the matrix
+    // instructions of the one before instead of being waited for one by one.
+    constexpr int KG = (MI * NJ == 1) ? 4 : 2;
     auto multiply = [&](int buf) {
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            const int c = 2 * ks + (lane >> 5);
-            bf16x8 fa[MI], fb[NJ];
+        for (int k0 = 0; k0 < BK / 16; k0 += KG) {
+            bf16x8 fa[KG][MI], fb[KG][NJ];
 #pragma unroll
-            for (int i = 0; i < MI; ++i)
-                fa[i] = __builtin_bit_cast(bf16x8, As[buf][slot(wm * (BM_ / 2) + i * 32 + (lane & 31), c)]);
+            for (int kk = 0; kk < KG; ++kk) {
+                const int c = 2 * (k0 + kk) + (lane >> 5);
 #pragma unroll
-            for (int j = 0; j < NJ; ++j)
-                fb[j] = __builtin_bit_cast(bf16x8, Bs[buf][slot(wn * (BN_ / 2) + j * 32 + (lane & 31), c)]);
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
+                for (int i = 0; i < MI; ++i)
+                    fa[kk][i] = __builtin_bit_cast(bf16x8, As[buf][slot(wm * (BM_ / 2) + i * 32 + (lane & 31), c)]);
 #pragma unroll
                 for (int j = 0; j < NJ; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                    fb[kk][j] = __builtin_bit_cast(bf16x8, Bs[buf][slot(wn * (BN_ / 2) + j * 32 + (lane & 31), c)]);
+            }
+#pragma unroll
+            for (int kk = 0; kk < KG; ++kk)
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk][i], fb[kk][j], acc[i][j], 0, 0, 0);
+            // order within the scheduling region: the group's LDS reads, then its matrix instructions (left alone, the
+            // scheduler puts each pair of reads right in front of its instruction and waits for both every time)
+            __builtin_amdgcn_sched_group_barrier(0x100, KG * (MI + NJ), 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, KG * MI * NJ, 0);
         }
     };
 
     // The prefetch is issued without a condition (past the last k-step it fetches the last tile again and nobody
     // uses it): behind a branch the compiler no longer knows how many loads are outstanding, and then waits for ALL of
-    // them before a tile goes to LDS, which leaves a single tile in flight.  The scheduling barriers keep the
-    // loads in front of the multiplication.
+    // them before a tile goes to LDS, which leaves a single tile in flight.  For the same reason the loop body is
+    // straight-line code of STAGES whole k-steps with the trip count fixed on entry, and the remaining k-steps follow
+    // the loop: with an exit test between the stages the compiler's wait-count pass sees a path from the middle of the
+    // body back to its top on which the loads are outstanding in another order, and drains them all at the top (found
+    // in the generated code: vmcnt(0) in front of every other k-step).  The scheduling barriers keep the loads in
+    // front of the multiplication.
     if (kc_begin >= kc_end) return;
+    static_assert(STAGES == 2, "the LDS buffers alternate with the register stages");
     TileRegs<LA, LB> r[STAGES];
 #pragma unroll
     for (int s = 0; s < STAGES; ++s) load_tiles(r[s], min(kc_begin + s, kc_end - 1));
-    int kc = kc_begin, buf = 0;
-    for (bool more = true; more;) {
-#pragma unroll
-        for (int s = 0; s < STAGES; ++s) {
-            if (kc >= kc_end) { more = false; break; }
-            store_tiles(r[s], buf);
-            __syncthreads();
-            __builtin_amdgcn_sched_barrier(0);
-            load_tiles(r[s], min(kc + STAGES, kc_end - 1));
-            __builtin_amdgcn_sched_barrier(0);
-            multiply(buf);
-            __builtin_amdgcn_sched_barrier(0);
-            buf ^= 1;
-            ++kc;
-        }
+    int kc = kc_begin;
+    auto stage = [&](TileRegs<LA, LB>& rs, const int buf, const bool prefetch) {
+        store_tiles(rs, buf);
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+        if (prefetch) load_tiles(rs, min(kc + STAGES, kc_end - 1));
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(buf);
+        __builtin_amdgcn_sched_barrier(0);
+        ++kc;
+    };
+    const int trips = (kc_end - kc_begin) / STAGES;
+    for (int it = 0; it < trips; ++it) {
+        stage(r[0], 0, true);
+        stage(r[1], 1, true);
     }
+    if ((kc_end - kc_begin) & 1) stage(r[0], 0, false);
 }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -234,55 +254,88 @@ __device__ __forceinline__ void mainloop_tn(const uint16_t* __restrict__ A, cons
         const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         return __builtin_bit_cast(bf16x8, v);
     };
-    auto multiply_term = [&](const bf16x8 (&fa)[MI], const uint16_t* btile, int ks) {
-        bf16x8 fb[NJ];
+    // One k-step as straight-line code: the fragments of sub-step ks + 1 are requested before the matrix instructions
+    // of sub-step ks are issued (two sets of fragment registers), so that the LDS reads run under the arithmetic.
+    // WITH_ONES is a parameter of the whole k-step: a test of do_ones per sub-step would cut the code into basic
+    // blocks, and the scheduler moves nothing across their ends.
+    auto multiply_steps = [&](int buf, auto with_ones) {
+        constexpr bool WITH_ONES = decltype(with_ones)::value;
+        constexpr int KS = BK / 16;
+        constexpr int READS = 2 * (MI + NJ) + (TERMS2 ? 2 * NJ : 0);          // ds_read_b64_tr_b16 per sub-step (upper bound with one term)
+        constexpr int MMAS = MI * NJ + (WITH_ONES ? NJ : 0);
+        bf16x8 fa[2][MI], fb[2][NJ], fb2[2][NJ];
+        auto fetch = [&](int set, int ks) {
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) fb[j] = read_frag(btile, RSB, ks * 16, wn * (BN_ / 2) + j * 32);
+            for (int i = 0; i < MI; ++i) fa[set][i] = read_frag(As[buf], RSA, ks * 16, wm * (BM_ / 2) + i * 32);
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
+            for (int j = 0; j < NJ; ++j) fb[set][j] = read_frag(Bs[buf][0], RSB, ks * 16, wn * (BN_ / 2) + j * 32);
+            if (two) {
 #pragma unroll
-            for (int j = 0; j < NJ; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-        if (ONES) {
-            if (do_ones) {
+                for (int j = 0; j < NJ; ++j) fb2[set][j] = read_frag(Bs[buf][TERMS2 ? 1 : 0], RSB, ks * 16, wn * (BN_ / 2) + j * 32);
+            }
+        };
+        fetch(0, 0);
+        if (!TERMS2) __builtin_amdgcn_sched_group_barrier(0x100, READS, 0);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int set = ks & 1;
+            if (ks + 1 < KS) fetch(set ^ 1, ks + 1);
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
 #pragma unroll
                 for (int j = 0; j < NJ; ++j)
-                    ones_acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(one8, fb[j], ones_acc[j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
+            if (WITH_ONES) {
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+                    ones_acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(one8, fb[set][j], ones_acc[j], 0, 0, 0);
+            }
+            if (two) {
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb2[set][j], acc[i][j], 0, 0, 0);
+                if (WITH_ONES) {
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j)
+                        ones_acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(one8, fb2[set][j], ones_acc[j], 0, 0, 0);
+                }
+            }
+            if (!TERMS2) {
+                if (ks + 1 < KS) __builtin_amdgcn_sched_group_barrier(0x100, READS, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, MMAS, 0);
             }
         }
     };
     auto multiply = [&](int buf) {
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 fa[MI];
-#pragma unroll
-            for (int i = 0; i < MI; ++i) fa[i] = read_frag(As[buf], RSA, ks * 16, wm * (BM_ / 2) + i * 32);
-            multiply_term(fa, Bs[buf][0], ks);
-            if (two) multiply_term(fa, Bs[buf][TERMS2 ? 1 : 0], ks);
-        }
+        if (ONES && do_ones) multiply_steps(buf, std::true_type{});
+        else multiply_steps(buf, std::false_type{});
     };
 
-    // unconditional prefetch, STAGES register stages and scheduling barriers as in mainloop
+    // unconditional prefetch, two register stages, straight-line loop body and scheduling barriers as in mainloop
     if (kc_begin >= kc_end) return;
+    static_assert(STAGES == 2, "the LDS buffers alternate with the register stages");
     TileRegs<LA, 2 * LB> r[STAGES];
 #pragma unroll
     for (int s = 0; s < STAGES; ++s) load_tiles(r[s], min(kc_begin + s, kc_end - 1));
-    int kc = kc_begin, buf = 0;
-    for (bool more = true; more;) {
-#pragma unroll
-        for (int s = 0; s < STAGES; ++s) {
-            if (kc >= kc_end) { more = false; break; }
-            store_tiles(r[s], buf, kc);
-            __syncthreads();
-            __builtin_amdgcn_sched_barrier(0);
-            load_tiles(r[s], min(kc + STAGES, kc_end - 1));
-            __builtin_amdgcn_sched_barrier(0);
-            multiply(buf);
-            __builtin_amdgcn_sched_barrier(0);
-            buf ^= 1;
-            ++kc;
-        }
+    int kc = kc_begin;
+    auto stage = [&](TileRegs<LA, 2 * LB>& rs, const int buf, const bool prefetch) {
+        store_tiles(rs, buf, kc);
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+        if (prefetch) load_tiles(rs, min(kc + STAGES, kc_end - 1));
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(buf);
+        __builtin_amdgcn_sched_barrier(0);
+        ++kc;
+    };
+    const int trips = (kc_end - kc_begin) / STAGES;
+    for (int it = 0; it < trips; ++it) {
+        stage(r[0], 0, true);
+        stage(r[1], 1, true);
     }
+    if ((kc_end - kc_begin) & 1) stage(r[0], 0, false);
 }
 
 }  // namespace dn_mma

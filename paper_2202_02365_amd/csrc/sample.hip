@@ -546,9 +546,10 @@ int dn_launch_sample(dn_batch* b, const dn_graph* g, const int32_t* d_targets, i
     const int grid0 = n_targets > 0 ? (n_targets + TPB - 1) / TPB : 1;
     if (grid0 > b->max_blocks) return dn_fail(DN_ECAPACITY, "dense_sample: %d targets exceed the batch capacity", n_targets);
     if (n_targets <= INIT_FUSED_MAX) {
-        dn_prof_scope ps("init_level0", 0, st);
+        { dn_prof_scope ps("init_level0", 0, st);
         hipLaunchKernelGGL(k_init_level0, dim3(grid0), dim3(TPB), 0, st, gd, b->V, d_targets, n_targets, b->fanouts[0], dir,
                            b->hdr, b->seen, b->lvlpos, b->lvl_ids, b->lvl_nbr_offsets);
+        }
         DN_LAUNCH_CHECK("k_init_level0");
         return launch_hops_and_assemble(b, gd, n_targets, seed, st);
     }

@@ -312,7 +312,12 @@ __global__ __launch_bounds__(SMALL_TPB) void k_tr_small(int32_t* __restrict__ hd
     __shared__ int cnt[SMALL_WAVES][SMALL_KEYS];
     __shared__ int s_part[SMALL_WAVES];
     const int N = hdr[HDR_N], E = hdr[HDR_E];
-    const int range_start = (int)blockIdx.x * SMALL_KEYS;
+    // Without layer 1's slots every pair's key is a node of Delta_1 .. Delta_k (the slots of Delta_2 .. Delta_k select
+    // nodes at most one level further from the targets): the workgroups share out the positions from node_id_offsets[1]
+    // on, and tr_ptr below that position, which no layer above the first reads, is left alone.  (Workgroups for the
+    // positions of Delta_0, 85 % of a mini-batch's nodes, would each read every pair only to find none of theirs.)
+    const int key_lo = need_all ? 0 : hdr[HDR_NODE_OFF + 1];
+    const int range_start = key_lo + (int)blockIdx.x * SMALL_KEYS;
     if (range_start > N) return;
     int first = 0;
     if (!need_all) first = k >= 2 ? nbr_offsets[hdr[HDR_NODE_OFF + 2] - hdr[HDR_NODE_OFF + 1]] : E;
