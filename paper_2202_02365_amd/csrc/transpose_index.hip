@@ -275,8 +275,8 @@ __global__ __launch_bounds__(TPB) void k_tr_ptr(const int32_t* __restrict__ coun
 
 // ---------------------------------------------------------------------------------------------------------------
 // The whole index in ONE kernel, for the few ten thousand pairs of a node-classification mini-batch (the general
-// path above is six launches, which cost more than the work).  Workgroup b owns the keys [b * SMALL_KEYS, (b + 1) *
-// SMALL_KEYS) and reads ALL pairs itself, twice, each of its waves a contiguous part of them, in order:
+// path above is six launches, which cost more than the work).  Workgroup b owns SMALL_KEYS consecutive keys
+// and reads ALL pairs itself, twice, each of its waves a contiguous part of them, in order:
 //   pass 1  counts, per wave, the pairs of each of its keys (LDS atomics: counts do not depend on the order) and the
 //           pairs with smaller keys (they precede the workgroup's output);
 //   scan    turns the counts into tr_ptr of its keys and into one output cursor per (wave, key), waves in order;
@@ -284,7 +284,14 @@ __global__ __launch_bounds__(TPB) void k_tr_ptr(const int32_t* __restrict__ coun
 //           (ballots), steps in order.  Equal keys therefore keep their input order: the sort is stable.
 // No workgroup waits for another and nothing is sized by the number of pairs, so any count is handled (time grows with
 // count x workgroups in use: the caller chooses this path only for small counts).
-constexpr int SMALL_TPB = 1024, SMALL_WAVES = SMALL_TPB / 64, SMALL_KEYS = 512, SMALL_KEY_BITS = 9;
+// Keys per workgroup, as a power of two.  Measured at the 111M-node workload (about 40k pairs on 17k keys), index build /
+// step with four mini-batches in flight: 512 keys 27.8 us / 0.155 ms, 256 keys 23.3 / 0.155, 128 keys 20.7 / 0.159,
+// 64 keys 22.8 / 0.170, 32 keys 42 / 0.192: fewer keys shorten a workgroup's second pass, but every workgroup reads
+// all pairs, and hundreds of 1024-thread workgroups take the compute units from the kernels of the other mini-batches.
+#ifndef DN_TR_SMALL_KEY_BITS
+#define DN_TR_SMALL_KEY_BITS 8
+#endif
+constexpr int SMALL_TPB = 1024, SMALL_WAVES = SMALL_TPB / 64, SMALL_KEY_BITS = DN_TR_SMALL_KEY_BITS, SMALL_KEYS = 1 << SMALL_KEY_BITS;
 constexpr int SMALL_BATCH = 8;     // 64-pair steps whose key loads a wave has in flight together (the loops stay short:
                                    // a kernel this brief cannot afford long straight-line code, its instruction fetch is cold)
 
@@ -377,7 +384,7 @@ __global__ __launch_bounds__(SMALL_TPB) void k_tr_small(int32_t* __restrict__ hd
     for (int w = 0; w < SMALL_WAVES; ++w) if (w < wave) run += s_part[w];
     int mine_total = 0;                                        // pairs of this workgroup's keys
 #pragma unroll
-    for (int w = 0; w < SMALL_KEYS / 64; ++w) mine_total += s_part[w];
+    for (int w = 0; w < SMALL_WAVES; ++w) mine_total += s_part[w];  // threads without a key added nothing
     if (threadIdx.x < SMALL_KEYS) {
         const int kl = threadIdx.x;
         const int p = range_start + kl;
