@@ -87,7 +87,8 @@ def algorithmic_work(tag, sizes, cfg, dims):
     if tag.startswith("sample_hop_L"):
         h = layer_of(tag) - 1
         return "hbm", mean(level_nodes(h) * (8 + 16 * ndir) + hop_slots(h) * (4 + 8 + 8))
-    if tag.startswith("fresh_count_hop") or tag.startswith("fresh_emit_hop"):
+    if tag.startswith("fresh_count_hop") or tag.startswith("fresh_emit_hop") or tag.startswith("next_delta_hop"):
+        # next_delta_hop: count and emit in one launch (the walk's words are read once from memory)
         h = layer_of(tag) if "_L" in tag else 0      # forms level h (0: the link-prediction front end's targets)
         new = level_nodes(h)
         rowptr = 16 * ndir if h < k else 0
@@ -208,7 +209,7 @@ def gemm_algorithmic_bytes(tag, sizes, cfg, dims):
     return None
 
 
-FORWARD_TAGS = ("init_", "sample_hop", "fresh_", "assemble", "mark_ids", "local_ids", "gather", "aggregate_L",
+FORWARD_TAGS = ("init_", "sample_hop", "fresh_", "next_delta", "assemble", "mark_ids", "local_ids", "gather", "aggregate_L",
                 "aggregate_table_L", "gemm_fwd_L", "sage_layer_L")
 
 

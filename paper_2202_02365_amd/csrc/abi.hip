@@ -373,6 +373,9 @@ int dn_batch_counts(const dn_batch* b, int64_t* host_counts, void* stream)
     if (h[HDR_STATUS] & (ST_BAD_TARGET | ST_DUP_TARGET))
         return dn_fail(DN_ESAMPLE, "dense_sample: %s", (h[HDR_STATUS] & ST_BAD_TARGET) ? "target id out of range" : "duplicate target id");
     if (h[HDR_STATUS] & ST_CAPACITY) return dn_fail(DN_ECAPACITY, "dense_sample: node capacity exceeded");
+    if (h[HDR_STATUS] & ST_INTERNAL)
+        return dn_fail(DN_ESTATE, "dense_sample: a workgroup gave up waiting for the totals of the workgroups in front of it; "
+                       "the sample is incomplete");
     if (h[HDR_STATUS] & ST_STALE_INDEX)
         return dn_fail(DN_ESTATE, "sage_backward ran with a transpose index built for another sample of this batch (a captured "
                        "graph replayed without the dn_batch_prepare_backward it was captured after); its gradients were not computed");

@@ -28,7 +28,8 @@ enum {
     HDR_TR_ALL = 36,       // 1 if that index covers every slot (input gradient of layer 1), 0 if only layers 2..k
     DN_HDR_WORDS = 64
 };
-enum { ST_BAD_TARGET = 1, ST_DUP_TARGET = 2, ST_CAPACITY = 4, ST_STALE_INDEX = 8 };
+enum { ST_BAD_TARGET = 1, ST_DUP_TARGET = 2, ST_CAPACITY = 4, ST_STALE_INDEX = 8,
+       ST_INTERNAL = 16 };   // a bounded wait between workgroups of one kernel ran out (never seen; see k_next_delta)
 
 struct dn_graph {
     int64_t V;

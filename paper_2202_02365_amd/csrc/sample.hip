@@ -16,6 +16,7 @@
 // k_assemble lays the staging arrays (level order) out in the paper's order (Delta_0 first, last
 // hop's neighbours first) and translates every neighbour id to its position in node_ids.
 #include "dn_internal.h"
+#include <cstdlib>
 
 namespace {
 // `seen` and `fresh` are interleaved: word w of `seen` and word w of `fresh` are the two halves of one aligned
@@ -208,10 +209,11 @@ __global__ __launch_bounds__(TPB) void k_init_level0(GraphDev g, int64_t V, cons
 __global__ __launch_bounds__(TPB) void k_mark_ids(int64_t V, const int32_t* __restrict__ a, int na,
                                                   const int32_t* __restrict__ b, int nb, const int32_t* __restrict__ c, int nc,
                                                   int32_t* __restrict__ hdr, uint32_t* __restrict__ fresh,
-                                                  uint32_t* __restrict__ summary)
+                                                  uint32_t* __restrict__ summary, unsigned long long* __restrict__ blk, int n_blk)
 {
     const int total = na + nb + nc;
     const int stride = gridDim.x * TPB;
+    for (int i = blockIdx.x * TPB + threadIdx.x; i < n_blk; i += stride) blk[i] = 0ull;     // as in k_sample
     for (int i = blockIdx.x * TPB + threadIdx.x; i < total; i += stride) {
         const int u = i < na ? a[i] : (i < na + nb ? b[i - na] : c[i - na - nb]);
         if (u < 0 || (int64_t)u >= V) { atomicOr(&hdr[HDR_STATUS_ACC], ST_BAD_TARGET); continue; }
@@ -250,9 +252,12 @@ __global__ __launch_bounds__(TPB) void k_sample(GraphDev g, int hop, int f, int 
                                                 const int32_t* __restrict__ lvl_nbr_offsets,
                                                 int32_t* __restrict__ lvl_nbrs, int32_t* __restrict__ lvl_owner,
                                                 int64_t cap_slots, uint32_t* __restrict__ seen,
-                                                uint32_t* __restrict__ fresh, uint32_t* __restrict__ summary)
+                                                uint32_t* __restrict__ fresh, uint32_t* __restrict__ summary,
+                                                unsigned long long* __restrict__ blk, int n_blk)
 {
     constexpr int GROUPS = TPB / G;
+    // the totals that the workgroups of the next-Delta kernel publish to each other start at zero ("not yet there")
+    for (int i = blockIdx.x * TPB + threadIdx.x; i < n_blk; i += gridDim.x * TPB) blk[i] = 0ull;
     const int lane = threadIdx.x & 63;
     const int s = threadIdx.x % G;
     const uint64_t gmask = (G == 64) ? ~0ull : (((1ull << G) - 1ull) << ((lane / G) * G));
@@ -429,6 +434,122 @@ __global__ __launch_bounds__(TPB) void k_fresh_emit(GraphDev g, int64_t words0, 
     }
 }
 
+// computeNextDelta in ONE launch: count, hand the workgroup's totals to the workgroups behind it, emit.
+// Workgroup b publishes pack(nodes, slots) of its id range with bit 63 set in blk[b] (one 64-bit atomic exchange at
+// device scope: value and "it is there" in one word, so no fence is needed), then adds up blk[0 .. b), waiting for
+// the words that are still zero (the sampling kernel in front of this one cleared them).  Every workgroup publishes
+// BEFORE it waits and waits only for workgroups with a smaller number, which the dispatcher starts first: workgroup 0
+// waits for nobody, and by induction every wait ends.  As a second line of defence a wait gives up after ND_SPIN_MAX
+// looks (far beyond the few microseconds the kernel runs): the workgroup then raises ST_INTERNAL, which
+// dn_batch_counts reports, emits nothing and leaves, so the kernel ends whatever the hardware does.
+constexpr unsigned long long ND_VALID = 1ull << 63;
+constexpr int ND_SPIN_MAX = 1 << 20;
+__global__ __launch_bounds__(TPB) void k_next_delta(GraphDev g, int64_t words0, int walk_shift, int next_level, int f_next, int direction,
+                                                    int32_t* __restrict__ hdr, uint32_t* __restrict__ fresh,
+                                                    uint32_t* __restrict__ summary, unsigned long long* __restrict__ blk,
+                                                    int32_t* __restrict__ lvlpos, int32_t* __restrict__ lvl_ids,
+                                                    int32_t* __restrict__ lvl_nbr_offsets, int64_t cap_nodes,
+                                                    uint32_t* __restrict__ seen_or_null)
+{
+    __shared__ uint64_t sm[TPB / 64];
+    __shared__ int s_gave_up;
+    if (threadIdx.x == 0) s_gave_up = 0;
+    const int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    // ---- count
+    int nodes = 0, slots = 0;
+    uint32_t sw0 = 0, full = 0;
+    const int64_t w0 = i << walk_shift;
+    if (w0 < words0) {
+        sw0 = walker_bits(summary, w0, walk_shift, full);
+        uint32_t sw = sw0;
+        while (sw) {
+            const int b = __ffs(sw) - 1;
+            sw &= sw - 1;
+            const int64_t w = w0 + b;
+            uint32_t fw = fresh[BM(w)];
+            nodes += __popc(fw);
+            if (f_next > 0) {
+                while (fw) {
+                    const int bit = __ffs(fw) - 1;
+                    fw &= fw - 1;
+                    slots += node_sample_count(g, (int)(w * 32 + bit), f_next, direction);
+                }
+            }
+        }
+    }
+    uint64_t total;
+    const uint64_t ex_local = block_exclusive_scan(pack(nodes, slots), total, sm);     // (its barriers also publish s_gave_up = 0)
+    // ---- publish, then collect what lies in front
+    if (threadIdx.x == 0)
+        __hip_atomic_exchange(&blk[blockIdx.x], (unsigned long long)total | ND_VALID, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    uint64_t acc = 0;
+    for (int j = threadIdx.x; j < (int)blockIdx.x; j += TPB) {
+        unsigned long long v = 0;
+        int spins = 0;
+        while (!((v = __hip_atomic_load(&blk[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) & ND_VALID)) {
+            if (++spins >= ND_SPIN_MAX) { s_gave_up = 1; break; }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        acc += (uint64_t)(v & ~ND_VALID);
+    }
+    uint64_t before;
+    block_exclusive_scan(acc, before, sm);
+    if (s_gave_up) {                                         // read after the scan's barriers: the same for all threads
+        if (threadIdx.x == 0) atomicOr(&hdr[HDR_STATUS_ACC], ST_INTERNAL);
+        return;
+    }
+    // ---- emit (the words are in cache from the count)
+    const uint64_t ex = ex_local + before;
+    const int node_base = hdr[HDR_LVL_OFF + next_level];
+    const int slot_base = f_next > 0 ? hdr[HDR_LVL_NBR_OFF + next_level] : 0;
+    int p = node_base + (int)(uint32_t)(ex & 0xffffffffu);
+    int so = slot_base + (int)(uint32_t)(ex >> 32);
+    uint32_t sw = sw0;
+    while (sw) {
+        const int b = __ffs(sw) - 1;
+        sw &= sw - 1;
+        const int64_t w = w0 + b;
+        uint32_t fw = fresh[BM(w)];
+        fresh[BM(w)] = 0;
+        if (seen_or_null) seen_or_null[BM(w)] = fw;          // level 0 from an id set: these nodes are the targets
+        while (fw) {
+            const int bit = __ffs(fw) - 1;
+            fw &= fw - 1;
+            const int u = (int)(w * 32 + bit);
+            if (p < cap_nodes) {
+                lvl_ids[p] = u;
+                lvlpos[u] = p;
+                if (f_next > 0) {
+                    lvl_nbr_offsets[p] = so;
+                    so += node_sample_count(g, u, f_next, direction);
+                }
+            }
+            ++p;
+        }
+    }
+    // the walkers that share a summary word are neighbours in one wave and have all read it (first thing above):
+    // the one at its first bitmap word clears it
+    if (full && (w0 & 31) == 0) summary[w0 >> 5] = 0;
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+        const uint64_t all = before + total;
+        int n_new = (int)(uint32_t)(all & 0xffffffffu);
+        if ((int64_t)node_base + n_new > cap_nodes) {
+            atomicOr(&hdr[HDR_STATUS_ACC], ST_CAPACITY);
+            n_new = (int)(cap_nodes - node_base);
+        }
+        hdr[HDR_LVL_OFF + next_level + 1] = node_base + n_new;
+        if (f_next > 0) hdr[HDR_LVL_NBR_OFF + next_level + 1] = slot_base + (int)(uint32_t)(all >> 32);
+        if (seen_or_null) hdr[HDR_NTARGETS] = n_new;
+    }
+}
+
+// DN_NEXT_DELTA_TWO_PASS=1 in the environment (read once) keeps the two-kernel form (count, then emit)
+static bool next_delta_fused()
+{
+    static const bool on = [] { const char* e = getenv("DN_NEXT_DELTA_TWO_PASS"); return !(e && e[0] == '1'); }();
+    return on;
+}
+
 // ---------------------------------------------------------------- final layout + repr_map
 // staging position -> position in node_ids: level h occupies [N - LVL_OFF[h+1], N - LVL_OFF[h]).
 __device__ __forceinline__ int final_node_pos(int p, const int* lvl_off, int k, int N)
@@ -487,10 +608,11 @@ __global__ __launch_bounds__(TPB) void k_assemble(int k, int32_t* __restrict__ h
 
 template <int G>
 void launch_sample_g(int grid, hipStream_t st, GraphDev gd, int hop, int f, int direction, uint32_t k0, uint32_t k1,
-                     dn_batch* b)
+                     dn_batch* b, int n_blk)
 {
     hipLaunchKernelGGL((k_sample<G>), dim3(grid), dim3(TPB), 0, st, gd, hop, f, direction, k0, k1, b->hdr, b->lvl_ids,
-                       b->lvl_nbr_offsets, b->lvl_nbrs, b->lvl_owner, b->cap_slots, b->seen, b->fresh, b->summary);
+                       b->lvl_nbr_offsets, b->lvl_nbrs, b->lvl_owner, b->cap_slots, b->seen, b->fresh, b->summary,
+                       reinterpret_cast<unsigned long long*>(b->blk_a), n_blk);
 }
 
 }  // namespace
@@ -510,22 +632,32 @@ int dn_launch_sample_edges(dn_batch* b, const dn_graph* g, const int32_t* d_src,
     int grid = (total + TPB - 1) / TPB;
     if (grid > 2048) grid = 2048;
     if (grid < 1) grid = 1;
+    const int grid_words = (int)((((b->words0 + ((int64_t)1 << b->walk_shift) - 1) >> b->walk_shift) + TPB - 1) / TPB);
+    const bool fused_nd = next_delta_fused();
+    unsigned long long* blk_u = reinterpret_cast<unsigned long long*>(b->blk_a);
     { dn_prof_scope ps("mark_ids", 0, st);
     hipLaunchKernelGGL(k_mark_ids, dim3(grid), dim3(TPB), 0, st, b->V, d_src, n_edges, d_dst, n_edges, d_neg, n_neg, b->hdr,
-                       b->fresh, b->summary);
+                       b->fresh, b->summary, blk_u, fused_nd ? grid_words : 0);
     }
     DN_LAUNCH_CHECK("k_mark_ids");
-    const int grid_words = (int)((((b->words0 + ((int64_t)1 << b->walk_shift) - 1) >> b->walk_shift) + TPB - 1) / TPB);
-    { dn_prof_scope ps("fresh_count_hop", 0, st);
-    hipLaunchKernelGGL(k_fresh_count, dim3(grid_words), dim3(TPB), 0, st, gd, b->words0, b->walk_shift, b->fanouts[0], dir, b->fresh,
-                       b->summary, blk);
+    if (fused_nd) {
+        { dn_prof_scope ps("next_delta_hop", 0, st);
+        hipLaunchKernelGGL(k_next_delta, dim3(grid_words), dim3(TPB), 0, st, gd, b->words0, b->walk_shift, 0, b->fanouts[0], dir, b->hdr,
+                           b->fresh, b->summary, blk_u, b->lvlpos, b->lvl_ids, b->lvl_nbr_offsets, b->cap_nodes, b->seen);
+        }
+        DN_LAUNCH_CHECK("k_next_delta");
+    } else {
+        { dn_prof_scope ps("fresh_count_hop", 0, st);
+        hipLaunchKernelGGL(k_fresh_count, dim3(grid_words), dim3(TPB), 0, st, gd, b->words0, b->walk_shift, b->fanouts[0], dir, b->fresh,
+                           b->summary, blk);
+        }
+        DN_LAUNCH_CHECK("k_fresh_count");
+        { dn_prof_scope ps("fresh_emit_hop", 0, st);
+        hipLaunchKernelGGL(k_fresh_emit, dim3(grid_words), dim3(TPB), 0, st, gd, b->words0, b->walk_shift, 0, b->fanouts[0], dir, b->hdr,
+                           b->fresh, b->summary, blk, b->lvlpos, b->lvl_ids, b->lvl_nbr_offsets, b->cap_nodes, b->seen);
+        }
+        DN_LAUNCH_CHECK("k_fresh_emit");
     }
-    DN_LAUNCH_CHECK("k_fresh_count");
-    { dn_prof_scope ps("fresh_emit_hop", 0, st);
-    hipLaunchKernelGGL(k_fresh_emit, dim3(grid_words), dim3(TPB), 0, st, gd, b->words0, b->walk_shift, 0, b->fanouts[0], dir, b->hdr,
-                       b->fresh, b->summary, blk, b->lvlpos, b->lvl_ids, b->lvl_nbr_offsets, b->cap_nodes, b->seen);
-    }
-    DN_LAUNCH_CHECK("k_fresh_emit");
     { dn_prof_scope ps("local_ids", 0, st);
     hipLaunchKernelGGL(k_local_ids, dim3(grid), dim3(TPB), 0, st, b->V, d_src, n_edges, d_dst, n_edges, d_neg, n_neg,
                        b->lvlpos, d_src_local, d_dst_local, d_neg_local);
@@ -572,6 +704,7 @@ static int launch_hops_and_assemble(dn_batch* b, const GraphDev& gd, int64_t lev
     uint64_t* blk = reinterpret_cast<uint64_t*>(b->blk_a);
     const uint32_t key0 = (uint32_t)(seed & 0xffffffffu), key1 = (uint32_t)(seed >> 32);
     const int grid_words = (int)((((b->words0 + ((int64_t)1 << b->walk_shift) - 1) >> b->walk_shift) + TPB - 1) / TPB);
+    const bool fused_nd = next_delta_fused();
     int64_t level_bound = level0_bound;                     // upper bound of the level size, known on the host
     for (int h = 0; h < k; ++h) {
         const int f = b->fanouts[h];
@@ -582,26 +715,35 @@ static int launch_hops_and_assemble(dn_batch* b, const GraphDev& gd, int64_t lev
         if (grid > 8192) grid = 8192;                       // grid-stride beyond this
         { dn_prof_scope ps("sample_hop", h + 1, st);
         switch (G) {
-            case 4:  launch_sample_g<4>((int)grid, st, gd, h, f, dir, key0, key1, b); break;
-            case 8:  launch_sample_g<8>((int)grid, st, gd, h, f, dir, key0, key1, b); break;
-            case 16: launch_sample_g<16>((int)grid, st, gd, h, f, dir, key0, key1, b); break;
-            case 32: launch_sample_g<32>((int)grid, st, gd, h, f, dir, key0, key1, b); break;
-            default: launch_sample_g<64>((int)grid, st, gd, h, f, dir, key0, key1, b); break;
+            case 4:  launch_sample_g<4>((int)grid, st, gd, h, f, dir, key0, key1, b, fused_nd ? grid_words : 0); break;
+            case 8:  launch_sample_g<8>((int)grid, st, gd, h, f, dir, key0, key1, b, fused_nd ? grid_words : 0); break;
+            case 16: launch_sample_g<16>((int)grid, st, gd, h, f, dir, key0, key1, b, fused_nd ? grid_words : 0); break;
+            case 32: launch_sample_g<32>((int)grid, st, gd, h, f, dir, key0, key1, b, fused_nd ? grid_words : 0); break;
+            default: launch_sample_g<64>((int)grid, st, gd, h, f, dir, key0, key1, b, fused_nd ? grid_words : 0); break;
         }
         }
         DN_LAUNCH_CHECK("k_sample");
         const int f_next = (h + 1 < k) ? b->fanouts[h + 1] : 0;
-        { dn_prof_scope ps("fresh_count_hop", h + 1, st);
-        hipLaunchKernelGGL(k_fresh_count, dim3(grid_words), dim3(TPB), 0, st, gd, b->words0, b->walk_shift, f_next, dir, b->fresh,
-                           b->summary, blk);
+        if (fused_nd) {
+            { dn_prof_scope ps("next_delta_hop", h + 1, st);
+            hipLaunchKernelGGL(k_next_delta, dim3(grid_words), dim3(TPB), 0, st, gd, b->words0, b->walk_shift, h + 1, f_next, dir, b->hdr,
+                               b->fresh, b->summary, reinterpret_cast<unsigned long long*>(b->blk_a), b->lvlpos, b->lvl_ids,
+                               b->lvl_nbr_offsets, b->cap_nodes, (uint32_t*)nullptr);
+            }
+            DN_LAUNCH_CHECK("k_next_delta");
+        } else {
+            { dn_prof_scope ps("fresh_count_hop", h + 1, st);
+            hipLaunchKernelGGL(k_fresh_count, dim3(grid_words), dim3(TPB), 0, st, gd, b->words0, b->walk_shift, f_next, dir, b->fresh,
+                               b->summary, blk);
+            }
+            DN_LAUNCH_CHECK("k_fresh_count");
+            { dn_prof_scope ps("fresh_emit_hop", h + 1, st);
+            hipLaunchKernelGGL(k_fresh_emit, dim3(grid_words), dim3(TPB), 0, st, gd, b->words0, b->walk_shift, h + 1, f_next, dir, b->hdr,
+                               b->fresh, b->summary, blk, b->lvlpos, b->lvl_ids, b->lvl_nbr_offsets, b->cap_nodes,
+                               (uint32_t*)nullptr);
+            }
+            DN_LAUNCH_CHECK("k_fresh_emit");
         }
-        DN_LAUNCH_CHECK("k_fresh_count");
-        { dn_prof_scope ps("fresh_emit_hop", h + 1, st);
-        hipLaunchKernelGGL(k_fresh_emit, dim3(grid_words), dim3(TPB), 0, st, gd, b->words0, b->walk_shift, h + 1, f_next, dir, b->hdr,
-                           b->fresh, b->summary, blk, b->lvlpos, b->lvl_ids, b->lvl_nbr_offsets, b->cap_nodes,
-                           (uint32_t*)nullptr);
-        }
-        DN_LAUNCH_CHECK("k_fresh_emit");
         const int mult = dir == DN_DIR_BOTH ? 2 : 1;
         level_bound = level_bound * f * mult;
         if (level_bound > b->cap_level[h + 1]) level_bound = b->cap_level[h + 1];
