@@ -109,6 +109,21 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const int bx, const
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wm = wave >> 1, wn = wave & 1;
 
+    // what the epilogue needs from memory (bias, column norms, row norms) is requested before the main loop, so that
+    // its latency passes under the k-steps instead of after them
+    float pre_bias[NJ], pre_cn[NJ], pre_rn = 0.f;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) { pre_bias[j] = 0.f; pre_cn[j] = 0.f; }
+    if constexpr (EPI == EPI_BIAS_ACT) {
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            const int n = min(col0 + wn * (BN_ / 2) + j * 32 + (lane & 31), a.ncols - 1);
+            pre_bias[j] = a.bias[n];
+            if (a.relu) pre_cn[j] = a.colnorm[n];
+        }
+        if (a.relu && t < BM_) pre_rn = a.rownorm[min(row0 + t, M - 1)];
+    }
+
     f32x16 acc[MI][NJ];
     if constexpr (EPI == EPI_SPLIT) {
         // weight gradient: both operands have the reduction index (the node) as their row index.  The first row
@@ -136,7 +151,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const int bx, const
     __shared__ float s_rownorm[BM_];
     if (EPI == EPI_BIAS_ACT && a.relu) {
         if (t == 0) s_fix_n = 0;
-        if (t < BM_) s_rownorm[t] = row0 + t < M ? a.rownorm[row0 + t] : 0.f;
+        if (t < BM_) s_rownorm[t] = row0 + t < M ? pre_rn : 0.f;
         __syncthreads();
     }
 #pragma unroll
@@ -145,8 +160,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const int bx, const
         for (int j = 0; j < NJ; ++j) {
             const int n = col0 + wn * (BN_ / 2) + j * 32 + (lane & 31);
             if (n >= a.ncols) continue;
-            const float bv = (EPI == EPI_BIAS_ACT) ? a.bias[n] : 0.f;
-            const float cn = (EPI == EPI_BIAS_ACT && a.relu) ? a.gamma * a.colnorm[n] : 0.f;
+            const float bv = pre_bias[j];
+            const float cn = a.gamma * pre_cn[j];                  // both zero unless EPI_BIAS_ACT (with ReLU)
             const float bt = fabsf(bv) * 4.76837158e-7f;          // 2^-21 |b|: rounding of the bias add
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
