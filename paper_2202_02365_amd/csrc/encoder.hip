@@ -131,14 +131,21 @@ __global__ __launch_bounds__(TPB) void k_dz(const int32_t* __restrict__ hdr, int
     float csum = 0.f;                    // this thread's column sum over all row tiles of this workgroup, in order
     for (int rt = blockIdx.y; rt * 64 < rows; rt += gridDim.y) {
         const int r0 = rt * 64;
-        for (int rr = ty; rr < 64; rr += 4) {
-            const int r = r0 + rr;
+        // the thread's 16 rows are requested together (one after the other, each load waited for, they took most of
+        // the kernel's 5 us); the sums keep the order of the rows
+        float g[16], h[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int r = r0 + ty + 4 * u;
+            const bool ok = r < rows && n < d_out;
+            g[u] = ok ? G[(int64_t)r * ldg + n] : 0.f;
+            h[u] = (ok && relu) ? Hout[(int64_t)r * d_out + n] : 1.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int r = r0 + ty + 4 * u;
             if (r >= rows) break;
-            float v = 0.f;
-            if (n < d_out) {
-                v = G[(int64_t)r * ldg + n];
-                if (relu && !(Hout[(int64_t)r * d_out + n] > 0.f)) v = 0.f;
-            }
+            const float v = (h[u] > 0.f) ? g[u] : 0.f;
             csum += v;
             const uint16_t hi = f32_to_bf16(v);
             dzb[(int64_t)r * nz + n] = hi;

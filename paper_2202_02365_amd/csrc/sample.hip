@@ -168,25 +168,32 @@ __global__ __launch_bounds__(TPB) void k_init_level0(GraphDev g, int64_t V, cons
     __shared__ uint64_t sm[TPB / 64];
     const int first = blockIdx.x * TPB;
     const int i = first + threadIdx.x;
+    // the ids are requested first, the thread's own and those in front of the workgroup four at a time, then everything
+    // that depends on them: two chains of dependent loads side by side instead of one after the other
+    int t = i < n ? targets[i] : -1;
+    const bool valid = t >= 0 && (int64_t)t < V;
+    uint64_t before = 0;
+    for (int j0 = threadIdx.x; j0 < first; j0 += 4 * TPB) {
+        int tb[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) tb[u] = j0 + u * TPB < first ? targets[j0 + u * TPB] : -1;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (tb[u] >= 0 && (int64_t)tb[u] < V) before += (uint64_t)node_sample_count(g, tb[u], f0, direction);
+    }
     int c = 0;
     if (i < n) {
-        int t = targets[i];
-        if (t < 0 || (int64_t)t >= V) {
+        if (!valid) {
             atomicOr(&hdr[HDR_STATUS_ACC], ST_BAD_TARGET);
             lvl_ids[i] = 0;                              // keeps every later access in bounds
         } else {
             const uint32_t bit = 1u << (t & 31);
             const uint32_t old = atomicOr(&seen[BM(t >> 5)], bit);
-            if (old & bit) atomicOr(&hdr[HDR_STATUS_ACC], ST_DUP_TARGET);
             lvl_ids[i] = t;
             lvlpos[t] = i;
             c = node_sample_count(g, t, f0, direction);
+            if (old & bit) atomicOr(&hdr[HDR_STATUS_ACC], ST_DUP_TARGET);
         }
-    }
-    uint64_t before = 0;
-    for (int j = threadIdx.x; j < first; j += TPB) {
-        const int t = targets[j];
-        if (t >= 0 && (int64_t)t < V) before += (uint64_t)node_sample_count(g, t, f0, direction);
     }
     uint64_t base;
     block_exclusive_scan(before, base, sm);              // base = slots of all targets in front of this workgroup
