@@ -721,6 +721,8 @@ def main():
     # with its own batch and model workspaces, against the same weights; their gradients are what R
     # data-parallel workers would sum.  The step is a chain of ~40 short kernels, most of them far too
     # small to fill 256 compute units, so concurrent chains fill the gaps.
+    stream_overlap = {}
+
     def timed_replicas(n_steps, n_rep, backward=True):
         reps = []
         for r in range(n_rep):
@@ -756,8 +758,8 @@ def main():
 
         lib_steps = None
         if fused and not rep_graphs and not args.python_replicas:
-            # the library schedules the replicas itself (dn_train_steps): step s on its internal stream s % n_rep
-            assert N_BATCHES % n_rep == 0
+            # the library schedules the replicas itself (dn_train_steps): step s on its internal stream s % n_rep (every
+            # call starts at step 0 and the call joins its streams at the end, so a replica's steps stay in order)
             lib_steps = dn.TrainSteps([dict(batch=reps[bi % n_rep]["batch"], model=reps[bi % n_rep]["model"], graph=graph,
                                             targets=targets[bi], seed=bi, table=table, out=reps[bi % n_rep]["out"],
                                             labels=labels, grad_scale=1.0 / cfg.batch, loss=reps[bi % n_rep]["loss"],
@@ -788,6 +790,12 @@ def main():
                 (n_rep, "whole step" if backward else "forward only", n, 1e3 * queued / n, 1e3 * spent / n))
             return spent
         run(max(args.warmup, n_rep))
+        if lib_steps is not None and backward:
+            # do the library's step streams run side by side?  (a busy-wait kernel of 20 us on each of them at once)
+            overlap = {n: dn.profile_step_stream_overlap(n, 20) for n in range(1, n_rep + 1)}
+            log("step streams: 20 us busy-wait kernels on 1..%d streams at once take %s us per round" %
+                (n_rep, ", ".join("%.1f" % overlap[n] for n in sorted(overlap))))
+            stream_overlap.update(overlap)
         # one read-back of the sizes per batch object, as a training loop does when it logs them: the library picks the
         # form of the transpose-index build from the largest counts read back so far (a matter of speed only)
         for o in reps:
@@ -1007,6 +1015,10 @@ def main():
                    "mean_nodes_per_batch": mean_n, "mean_sampled_edges_per_batch": mean_e},
         "mini_batches_per_s": args.steps / total_s,
         "in_flight": in_flight,
+        "step_streams_busy_wait_us": {"note": "a 20 us single-wave busy-wait kernel on each of the library's first n step streams "
+                                              "at once, us per round (about 20 + 2.5 n if the streams run side by side; the 2.5 "
+                                              "is the host's launch call)",
+                                      **{str(n): v for n, v in sorted(stream_overlap.items())}},
         "forward": "sage_forward_table: the layer-1 aggregation reads the table's rows itself, no H^0 buffer" if fused
                    else "dense_gather into H^0, then sage_forward",
         "two_in_flight": pipelined,

@@ -357,6 +357,12 @@ DN_API int  dn_profile_calibration_copy(void* d_dst, const void* d_src, size_t b
  * nothing under the tag "noop_kernel_bracket": the difference is the latency of a launch as such, which every
  * bracketed kernel's figure still contains. */
 DN_API int  dn_profile_empty_bracket(void* stream);
+/* Diagnostic for dn_train_steps' streams (HIP does not tell which hardware queue a stream runs on, and two streams on
+ * one queue take turns): eight rounds of one single-wave kernel that busy-waits kernel_us microseconds on each of the
+ * first n_streams step streams; *elapsed_us = best time per round of five tries.  About kernel_us if the streams run
+ * side by side, a multiple of it if some share a queue.  WAITS for the device.  DN_ESTATE before dn_train_steps has
+ * created that many streams. */
+DN_API int  dn_profile_step_stream_overlap(int32_t n_streams, int32_t kernel_us, double* elapsed_us);
 DN_API int  dn_profile_collect(dn_kernel_time* out, int32_t max_entries, int32_t* n_entries);
 
 #ifdef __cplusplus

@@ -7,8 +7,8 @@ and streams.  There is no CPU fallback: if the library is missing, loading raise
 from .binding import (DN_F32, DN_BF16, DN_DIR_OUT, DN_DIR_IN, DN_DIR_BOTH, DenseError, Graph, Batch, Model, Decoder, distmult_forward, distmult_backward,
                       dense_sample, dense_sample_noalloc, TrainSteps, dense_sample_edges, embedding_sgd, embedding_adagrad, softmax_xent, dense_gather, sage_forward, sage_forward_table, sage_backward, sage_backward_sgd, DN_AGG_MEAN, DN_AGG_SUM, library_path, load_library,
                       declared_symbols, profile_enable, profile_collect, profile_collect_percentiles,
-                      profile_calibration_copy, profile_empty_bracket)
+                      profile_calibration_copy, profile_empty_bracket, profile_step_stream_overlap)
 
 __all__ = ["DN_F32", "DN_BF16", "DN_DIR_OUT", "DN_DIR_IN", "DN_DIR_BOTH", "DenseError", "Graph", "Batch", "Model", "Decoder", "distmult_forward", "distmult_backward",
            "dense_sample", "dense_sample_noalloc", "TrainSteps", "dense_sample_edges", "embedding_sgd", "embedding_adagrad", "softmax_xent", "dense_gather", "sage_forward", "sage_forward_table", "sage_backward", "sage_backward_sgd", "DN_AGG_MEAN", "DN_AGG_SUM", "library_path", "load_library",
-           "declared_symbols", "profile_enable", "profile_collect", "profile_collect_percentiles", "profile_calibration_copy", "profile_empty_bracket"]
+           "declared_symbols", "profile_enable", "profile_collect", "profile_collect_percentiles", "profile_calibration_copy", "profile_empty_bracket", "profile_step_stream_overlap"]

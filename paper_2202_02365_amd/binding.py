@@ -90,6 +90,7 @@ def load_library():
         "dn_profile_enable": (ctypes.c_int, [i32]),
         "dn_profile_calibration_copy": (ctypes.c_int, [vp, vp, sz, vp]),
         "dn_profile_empty_bracket": (ctypes.c_int, [vp]),
+        "dn_profile_step_stream_overlap": (ctypes.c_int, [ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(ctypes.c_double)]),
         "dn_profile_collect": (ctypes.c_int, [ctypes.POINTER(_KernelTime), i32, ctypes.POINTER(i32)]),
         "dn_decoder_workspace_size": (ctypes.c_int, [i64, i32, i32, i32, i64, i64, ctypes.POINTER(sz)]),
         "dn_decoder_create": (ctypes.c_int, [pp, i64, i32, i32, i32, i64, i64, vp, sz, vp]),
@@ -335,6 +336,13 @@ def profile_calibration_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
     nbytes = src.numel() * src.element_size()
     assert dst.numel() * dst.element_size() == nbytes
     _check(load_library().dn_profile_calibration_copy(_dev_ptr(dst), _dev_ptr(src), nbytes, _stream()))
+
+
+def profile_step_stream_overlap(n_streams: int, kernel_us: int = 20) -> float:
+    """Microseconds per round of one kernel_us-long single-wave kernel on each of dn_train_steps' first n_streams streams."""
+    out = ctypes.c_double(0.0)
+    _check(load_library().dn_profile_step_stream_overlap(n_streams, kernel_us, ctypes.byref(out)))
+    return out.value
 
 
 def profile_empty_bracket() -> None:

@@ -1,6 +1,7 @@
 // The C ABI of libdense_mi355x.so: argument checking, handle bookkeeping, workspace carve-up.
 // Every step of the hot path runs in the kernels behind the dn_launch_* calls.
 #include "dn_internal.h"
+#include <chrono>
 #include <cstdlib>
 
 #include <cstdarg>
@@ -693,6 +694,40 @@ int dn_train_steps(const dn_train_step* steps, int32_t n_steps, int32_t n_stream
         DN_HIP(hipStreamWaitEvent(outer, ss.done[j], 0));
     }
     return rc;
+}
+
+// busy-waits `ticks` of the 100 MHz realtime counter on one wave (bounded by a fixed number of loop trips)
+__global__ void k_probe_wait(int ticks, int* sink)
+{
+    const unsigned long long t0 = wall_clock64();
+    int n = 0;
+    while ((long long)(wall_clock64() - t0) < ticks && n < (1 << 20)) ++n;
+    if (n < 0) *sink = n;
+}
+
+int dn_profile_step_stream_overlap(int32_t n_streams, int32_t kernel_us, double* elapsed_us)
+{
+    if (n_streams < 1 || n_streams > STEP_MAX_STREAMS || kernel_us < 1 || kernel_us > 1000 || !elapsed_us)
+        return dn_fail(DN_EINVAL, "n_streams in [1, %d], kernel_us in [1, 1000]", STEP_MAX_STREAMS);
+    int dev = -1;
+    DN_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= STEP_MAX_DEVICES) return dn_fail(DN_EINVAL, "device index %d is outside [0, %d)", dev, STEP_MAX_DEVICES);
+    std::lock_guard<std::mutex> lock(g_step_mutex);
+    StepStreams& ss = g_step_streams[dev];
+    if (ss.created < n_streams) return dn_fail(DN_ESTATE, "dn_train_steps has not created %d streams yet", n_streams);
+    DN_HIP(hipDeviceSynchronize());
+    double best = 1e30;
+    for (int rep = 0; rep < 5; ++rep) {
+        const auto t0 = std::chrono::steady_clock::now();
+        for (int i = 0; i < 8; ++i)
+            for (int j = 0; j < n_streams; ++j)
+                hipLaunchKernelGGL(k_probe_wait, dim3(1), dim3(64), 0, ss.stream[j], kernel_us * 100, (int*)nullptr);
+        DN_HIP(hipDeviceSynchronize());
+        const double us = std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count() / 8.0;
+        if (us < best) best = us;
+    }
+    *elapsed_us = best;
+    return DN_OK;
 }
 
 int dn_profile_calibration_copy(void* d_dst, const void* d_src, size_t bytes, void* stream)
