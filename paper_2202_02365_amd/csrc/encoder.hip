@@ -87,21 +87,40 @@ __global__ __launch_bounds__(TPB) void k_aggregate(const int32_t* __restrict__ h
                 }
             }
             if (!col_ok) continue;
+            // the lane's V values of each block of the row leave in one store (V = 4 only with d a multiple of 4, and
+            // rows of X start on 128-byte boundaries: 8-byte aligned); as 2-byte stores they were 8 to 16 store
+            // instructions per lane
+            uint16_t o_sh[V], o_mh[V], o_sl[V], o_ml[V];
 #pragma unroll
             for (int e = 0; e < V; ++e) {
                 const float mean = end > beg ? (mean_agg ? acc[e] / cnt_f : acc[e]) : 0.f;
                 const uint16_t s_hi = f32_to_bf16(sv[e]), m_hi = f32_to_bf16(mean);
-                xrow[c0 + e] = s_hi;
-                xrow[d + c0 + e] = m_hi;
+                o_sh[e] = s_hi;
+                o_mh[e] = m_hi;
                 const float s_hf = bf16_to_f32(s_hi), m_hf = bf16_to_f32(m_hi);
                 sq += s_hf * s_hf + m_hf * m_hf;
+                o_sl[e] = 0; o_ml[e] = 0;
                 if (TERMS == 2) {
                     const uint16_t s_lo = f32_to_bf16(sv[e] - s_hf), m_lo = f32_to_bf16(mean - m_hf);
-                    xrow[2 * d + c0 + e] = s_lo;
-                    xrow[3 * d + c0 + e] = m_lo;
+                    o_sl[e] = s_lo;
+                    o_ml[e] = m_lo;
                     const float s_lf = bf16_to_f32(s_lo), m_lf = bf16_to_f32(m_lo);
                     sq += s_lf * s_lf + m_lf * m_lf;
                 }
+            }
+            auto put = [&](uint16_t* dst, const uint16_t (&o)[V]) {
+                if constexpr (V == 4) {
+                    *reinterpret_cast<uint2*>(dst) = make_uint2((uint32_t)o[0] | ((uint32_t)o[1] << 16), (uint32_t)o[2] | ((uint32_t)o[3] << 16));
+                } else {
+#pragma unroll
+                    for (int e = 0; e < V; ++e) dst[e] = o[e];
+                }
+            };
+            put(xrow + c0, o_sh);
+            put(xrow + d + c0, o_mh);
+            if (TERMS == 2) {
+                put(xrow + 2 * d + c0, o_sl);
+                put(xrow + 3 * d + c0, o_ml);
             }
         }
 #pragma unroll
