@@ -127,6 +127,67 @@ def test_whole_graph_as_targets(g16k):
     assert d.node_id_offsets.tolist() == [0, 0, 0, n]
 
 
+@pytest.mark.parametrize("n_targets", [255, 256, 257, 1023, 4095, 4096, 4097, 5000])
+def test_target_list_sizes_around_the_one_launch_limit(g16k, n_targets):
+    """Level 0 runs as one launch up to 4096 targets (each workgroup adds up the counts in front of it itself) and as
+    two launches beyond: sizes on both sides of the limit and of the 256-target workgroups."""
+    batch = dn.Batch(g16k.num_nodes, 5000, [4, 3])
+    targets = np.random.default_rng(n_targets).permutation(g16k.num_nodes)[:n_targets].astype(np.int32)
+    view = gpu_sample(g16k, batch, targets, seed=11)
+    assert_dense_equal(view, oracle.dense_sample(g16k.oracle, targets, [4, 3], seed=11))
+
+
+def test_two_launch_next_delta_form_gives_the_same_sample(g16k, tmp_path):
+    """DN_NEXT_DELTA_TWO_PASS=1 (read once per process) keeps computeNextDelta as two launches per hop (count, emit): a
+    child process samples with it, node classification and the edge front end, and this process (one launch per hop)
+    must see the same arrays, which the other tests compare with the oracle."""
+    import os, subprocess, sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = str(tmp_path / "two_pass.npz")
+    code = (
+        "import sys, numpy as np, torch\n"
+        "sys.path.insert(0, %r)\n"
+        "import paper_2202_02365_amd as dn\n"
+        "from workloads import rmat_csr, transpose_csr, target_batch\n"
+        "V = 16384\n"
+        "rp, col = rmat_csr(V, 262144, 1)\n"
+        "rpi, coli = transpose_csr(rp, col)\n"
+        "dev = torch.device('cuda:0')\n"
+        "g = dn.Graph(rp.to(dev), col.to(dev), rpi.to(dev), coli.to(dev))\n"
+        "b = dn.Batch(V, 300, [5, 4, 3], dn.DN_DIR_BOTH)\n"
+        "t = torch.from_numpy(target_batch(V, 300, 2)).to(dev)\n"
+        "dn.dense_sample(b, g, t, 21)\n"
+        "res = {'nc_' + k: v.cpu().numpy() for k, v in b.view().items()}\n"
+        "src = torch.arange(0, 600, 3, dtype=torch.int32, device=dev); dst = torch.arange(5, 1205, 6, dtype=torch.int32, device=dev)\n"
+        "neg = torch.arange(7, 707, 7, dtype=torch.int32, device=dev)\n"
+        "b2 = dn.Batch(V, 600, [6], dn.DN_DIR_BOTH)\n"
+        "loc = dn.dense_sample_edges(b2, g, src, dst, neg, 5)\n"
+        "res.update({'lp_' + k: v.cpu().numpy() for k, v in b2.view().items()})\n"
+        "res.update({'lp_local%%d' %% i: x.cpu().numpy() for i, x in enumerate(loc)})\n"
+        "np.savez(%r, **res)\n"
+    ) % (root, out)
+    env = dict(os.environ, DN_NEXT_DELTA_TWO_PASS="1")
+    subprocess.run([sys.executable, "-c", code], check=True, env=env, timeout=300)
+    child = np.load(out)
+    V = g16k.num_nodes
+    assert V == 16384
+    batch = dn.Batch(V, 300, [5, 4, 3], dn.DN_DIR_BOTH)
+    t = torch.from_numpy(target_batch(V, 300, 2)).to("cuda:0")
+    dn.dense_sample(batch, g16k.graph, t, 21)
+    for k, v in batch.view().items():
+        assert np.array_equal(v.cpu().numpy(), child["nc_" + k]), k
+    dev = torch.device("cuda:0")
+    src = torch.arange(0, 600, 3, dtype=torch.int32, device=dev)
+    dst = torch.arange(5, 1205, 6, dtype=torch.int32, device=dev)
+    neg = torch.arange(7, 707, 7, dtype=torch.int32, device=dev)
+    b2 = dn.Batch(V, 600, [6], dn.DN_DIR_BOTH)
+    loc = dn.dense_sample_edges(b2, g16k.graph, src, dst, neg, 5)
+    for k, v in b2.view().items():
+        assert np.array_equal(v.cpu().numpy(), child["lp_" + k]), k
+    for i, x in enumerate(loc):
+        assert np.array_equal(x.cpu().numpy(), child["lp_local%d" % i])
+
+
 def test_invalid_targets_are_reported_not_fatal(g16k):
     batch = dn.Batch(g16k.num_nodes, 16, [4, 2])
     t = torch.tensor([1, 2, 3, 2], dtype=torch.int32, device="cuda:0")

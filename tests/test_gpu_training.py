@@ -96,7 +96,10 @@ def test_library_scheduled_steps_equal_the_calls_made_one_after_the_other(rmat16
                 got = [r["out"], r["loss"]] + r["dws"] + r["dwn"] + r["dbs"]
                 for a, b in zip(want[bi], got):
                     assert torch.equal(a, b), (n_streams, bi)
-        # and all of them in one call (replicas reused along their streams): the last steps' results must be in place
+        # and all of them in one call (replicas reused along their streams): the last steps' results must be in place.
+        # One replica's sizes are read back first: the library hands them on to the other batch objects of the call, and
+        # all of them now build the transpose index in its one-kernel form, which must not change a bit
+        reps[0]["batch"].counts()
         steps.run(n_streams)
         torch.cuda.synchronize()
         for bi in range(n_steps - n_streams, n_steps):
@@ -105,3 +108,8 @@ def test_library_scheduled_steps_equal_the_calls_made_one_after_the_other(rmat16
                 assert torch.equal(a, b), (n_streams, bi)
     with pytest.raises(dn.DenseError):
         steps.run(17)
+    # the diagnostic of the step streams: three 20 us busy-wait kernels side by side take far less than three in a row
+    one, three = dn.profile_step_stream_overlap(1, 20), dn.profile_step_stream_overlap(3, 20)
+    assert 15.0 < one < 60.0 and three < 3 * one, (one, three)
+    with pytest.raises(dn.DenseError):
+        dn.profile_step_stream_overlap(16, 20)             # more streams than dn_train_steps has created
