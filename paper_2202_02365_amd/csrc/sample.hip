@@ -408,7 +408,10 @@ __global__ __launch_bounds__(TPB) void k_fresh_emit(GraphDev g, int64_t words0, 
         sw &= sw - 1;
         const int64_t w = w0 + b;
         uint32_t fw = fresh[BM(w)];
-        fresh[BM(w)] = 0;
+        // after the last hop nothing reads `seen` any more: the pair of words is cleared together, and the final pass
+        // need not come back to this level's nodes (most of a mini-batch) to clear their bits one random store each
+        if (f_next == 0 && !seen_or_null) *reinterpret_cast<uint2*>(&fresh[BM(w) - 1]) = make_uint2(0u, 0u);
+        else fresh[BM(w)] = 0;
         if (seen_or_null) seen_or_null[BM(w)] = fw;          // level 0 from an id set: these nodes are the targets
         while (fw) {
             const int bit = __ffs(fw) - 1;
@@ -517,7 +520,10 @@ __global__ __launch_bounds__(TPB) void k_next_delta(GraphDev g, int64_t words0, 
         sw &= sw - 1;
         const int64_t w = w0 + b;
         uint32_t fw = fresh[BM(w)];
-        fresh[BM(w)] = 0;
+        // after the last hop nothing reads `seen` any more: the pair of words is cleared together, and the final pass
+        // need not come back to this level's nodes (most of a mini-batch) to clear their bits one random store each
+        if (f_next == 0 && !seen_or_null) *reinterpret_cast<uint2*>(&fresh[BM(w) - 1]) = make_uint2(0u, 0u);
+        else fresh[BM(w)] = 0;
         if (seen_or_null) seen_or_null[BM(w)] = fw;          // level 0 from an id set: these nodes are the targets
         while (fw) {
             const int bit = __ffs(fw) - 1;
@@ -588,7 +594,8 @@ __global__ __launch_bounds__(TPB) void k_assemble(int k, int32_t* __restrict__ h
         const int fp = N - lvl_off[h + 1] + (p - lvl_off[h]);
         const int u = lvl_ids[p];
         node_ids[fp] = u;
-        seen[BM((uint32_t)u >> 5)] = 0;                          // leave the bitmap clean for the next batch
+        // leave the bitmap clean for the next batch (the words of the last level's nodes were cleared when it was formed)
+        if (h < k) seen[BM((uint32_t)u >> 5)] = 0;
         if (h < k)
             nbr_offsets[fp - off1] = E - nbr_off[h + 1] + (lvl_nbr_offsets[p] - nbr_off[h]);
     }
