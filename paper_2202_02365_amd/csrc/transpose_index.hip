@@ -292,6 +292,11 @@ __global__ __launch_bounds__(TPB) void k_tr_ptr(const int32_t* __restrict__ coun
 #define DN_TR_SMALL_KEY_BITS 8
 #endif
 constexpr int SMALL_TPB = 1024, SMALL_WAVES = SMALL_TPB / 64, SMALL_KEY_BITS = DN_TR_SMALL_KEY_BITS, SMALL_KEYS = 1 << SMALL_KEY_BITS;
+#ifndef DN_TR_SMALL_LIST_CAP
+#define DN_TR_SMALL_LIST_CAP 512
+#endif
+constexpr int SMALL_LIST_CAP = DN_TR_SMALL_LIST_CAP;     // entries per wave (a small value, for a test build, sends most waves the other way)
+static_assert(SMALL_KEYS <= 0x10000, "a key's offset in the workgroup's range must fit 16 bits");
 constexpr int SMALL_BATCH = 8;     // 64-pair steps whose key loads a wave has in flight together (the loops stay short:
                                    // a kernel this brief cannot afford long straight-line code, its instruction fetch is cold)
 
@@ -318,6 +323,11 @@ __global__ __launch_bounds__(SMALL_TPB) void k_tr_small(int32_t* __restrict__ hd
 {
     __shared__ int cnt[SMALL_WAVES][SMALL_KEYS];
     __shared__ int s_part[SMALL_WAVES];
+    // the pairs of this workgroup's keys that a wave met in pass 1, in their order: (key offset << 16) | (pair index
+    // relative to the wave's first pair).  Pass 2 then ranks and places a list of a few dozen entries instead of walking
+    // all of the wave's 64-pair steps again (a ballot per key bit and two LDS round trips per step: 11 of the kernel's
+    // 23 us).  A wave whose list would overflow (or whose part is too long for 16 bits) walks its steps as before.
+    __shared__ uint32_t s_list[SMALL_WAVES][SMALL_LIST_CAP];
     const int N = hdr[HDR_N], E = hdr[HDR_E];
     // Without layer 1's slots every pair's key is a node of Delta_1 .. Delta_k (the slots of Delta_2 .. Delta_k select
     // nodes at most one level further from the targets): the workgroups share out the positions from node_id_offsets[1]
@@ -348,6 +358,7 @@ __global__ __launch_bounds__(SMALL_TPB) void k_tr_small(int32_t* __restrict__ hd
 
     // ---- pass 1
     int below = 0;
+    int list_n = 0;                                            // entries of this wave's list (wave-uniform); above the capacity: not usable
     for (int st = s_begin; st < s_end; st += SMALL_BATCH) {
         int kv[SMALL_BATCH];
 #pragma unroll
@@ -358,7 +369,16 @@ __global__ __launch_bounds__(SMALL_TPB) void k_tr_small(int32_t* __restrict__ hd
 #pragma unroll
         for (int u = 0; u < SMALL_BATCH; ++u) {
             below += kv[u] < 0;
-            if (kv[u] >= 0 && kv[u] < SMALL_KEYS) atomicAdd(&cnt[wave][kv[u]], 1);
+            const bool mine = kv[u] >= 0 && kv[u] < SMALL_KEYS;
+            if (mine) atomicAdd(&cnt[wave][kv[u]], 1);
+            const uint64_t m = __ballot(mine);
+            if (m) {                                           // the same for the whole wave
+                const int rel = (st + u - s_begin) * 64 + lane;
+                const int pos = list_n + __popcll(m & ((1ull << lane) - 1ull));
+                if (mine && pos < SMALL_LIST_CAP && rel < 0x10000) s_list[wave][pos] = ((uint32_t)kv[u] << 16) | (uint32_t)rel;
+                list_n += __popcll(m);
+                if ((st + u - s_begin) * 64 + 63 >= 0x10000) list_n = SMALL_LIST_CAP + 1;      // index beyond 16 bits: this wave walks its steps
+            }
         }
     }
     for (int d = 32; d > 0; d >>= 1) below += __shfl_down(below, d, 64);
@@ -403,7 +423,21 @@ __global__ __launch_bounds__(SMALL_TPB) void k_tr_small(int32_t* __restrict__ hd
     }
     __syncthreads();
 
-    // ---- pass 2: places (the keys again, a batch of loads at a time; the stores are not waited for)
+    // ---- pass 2: places.  From the wave's list, 64 entries at a time in list order (= pair order)...
+    if (list_n <= SMALL_LIST_CAP) {
+        for (int base = 0; base < list_n; base += 64) {
+            const bool mine = base + lane < list_n;
+            const uint32_t ent = mine ? s_list[wave][base + lane] : 0u;
+            const int kl = (int)(ent >> 16);
+            int rank, count;
+            step_peers(kl, mine, lane, rank, count);
+            if (mine) tr_val[cnt[wave][kl] + rank] = first + s_begin * 64 + (int)(ent & 0xffffu);
+            __builtin_amdgcn_wave_barrier();                   // every lane has read the cursor before its leader moves it
+            if (mine && rank == 0) cnt[wave][kl] += count;
+            __builtin_amdgcn_wave_barrier();
+        }
+    } else
+    // ... or, for a wave whose list did not fit, from the keys again (a batch of loads at a time; the stores are not waited for)
     for (int st = s_begin; st < s_end; st += SMALL_BATCH) {
         int kv[SMALL_BATCH];
 #pragma unroll
