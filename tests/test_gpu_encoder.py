@@ -148,6 +148,30 @@ def test_rows_read_by_hundreds_of_slots(dims):
     check(errs)
 
 
+@pytest.mark.parametrize("fanouts,dims,want_dh0", [([10], [24, 20], True), ([10, 3], [24, 32, 12], False)])
+def test_twenty_thousand_slots_on_a_hundred_rows(fanouts, dims, want_dh0):
+    """Two thousand targets whose neighbours all lie among a hundred hub nodes: the 20,000 pairs of the transpose index
+    fall into one workgroup's range of keys, so in the one-kernel form of the build every wave meets more of that
+    workgroup's pairs than its list in LDS holds and places them by walking its steps instead; every hub row is read by
+    about two hundred slots.  With one layer the index covers all slots (input gradient), with two only the targets'."""
+    V, H = 6000, 100
+    rng = np.random.default_rng(5)
+    rows = []
+    for u in range(V):
+        if u < H:
+            rows.append(np.array([(u + 1) % H, (u + 7) % H], dtype=np.int64))             # hubs: a small ring
+        else:
+            rows.append(np.sort(rng.choice(H, size=12, replace=False)).astype(np.int64))
+    rowptr = np.zeros(V + 1, dtype=np.int64)
+    rowptr[1:] = np.cumsum([len(r) for r in rows])
+    dg = DeviceGraph(rowptr, np.concatenate(rows).astype(np.int32))
+    targets = (H + rng.permutation(V - H)[:2000]).astype(np.int32)
+    errs, (_, _, _, _, _, d) = run_case(dg, fanouts, dims, len(targets), seed=9, targets=targets, want_dh0=want_dh0)
+    first_hop = np.asarray(d.repr_map)[-2000 * fanouts[0]:]                              # the targets' slots come last
+    assert len(np.unique(first_hop)) <= H and len(first_hop) == 20000
+    check(errs)
+
+
 def test_one_launch_layer_with_long_and_empty_segments(g16k):
     """Layers above the first with 64, 128, 192 or 256 input columns run aggregation and linear map in one launch.
     Fanout 48 over both edge directions (up to 96 slots a row) gives its rows segments beyond the 16 slots fetched at once and beyond one
