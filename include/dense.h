@@ -183,6 +183,9 @@ DN_API int  dn_batch_view(const dn_batch* b, dn_dense_view* view);
 
 /* Copies node_id_offsets[0..k+1] followed by E (k+3 values) to host_counts and WAITS for `stream`.
  * Returns DN_ESAMPLE if the last dense_sample saw an invalid target set.
+ * DN_ESTATE is also returned if a workgroup of the next-Delta kernel ever gave up its (bounded) wait for the totals of the
+ * workgroups in front of it: the sample is then incomplete (never observed; the bound exists so that the kernel ends
+ * whatever happens).
  * The batch object remembers the largest slot counts read back so far: the transpose-index build of sage_backward /
  * dn_batch_prepare_backward takes its one-kernel form for a batch object whose mini-batches have stayed below a few
  * ten thousand slots and the multi-pass sort otherwise or when no size was ever read back (both forms are correct for
