@@ -7,10 +7,11 @@
 //     compute unit, hide the memory latency of the few k-steps better than 128 x 128 tiles do;
 //   dW      : C = A^T * B   A = X^i, B = bf16 terms of dZ: the reduction runs over the nodes, the ROW index of both
 //     operands as they lie in memory, which mainloop_tn reads in place through the LDS transpose read; 128 x 128
-//     tiles, split over the reduction, partial tiles reduced afterwards in a fixed order (deterministic).
+//     tiles, split over the reduction, partial tiles reduced afterwards in a fixed order (deterministic).  The
+//     128 x 128 tile loads its operand tiles from global memory straight into LDS (mainloop_tn_direct).
 // Four waves (2 x 2) per workgroup, v_mfma_f32_32x32x16_bf16, two register stages of global prefetch and two LDS
-// buffers.  M and the dW reduction length live in device memory (they depend on the sample); grids are sized by
-// capacity and surplus workgroups leave at once.
+// buffers (dW: two LDS buffers filled directly).  M and the dW reduction length live in device memory (they depend
+// on the sample); grids are sized by capacity and surplus workgroups leave at once.
 //
 // Operand terms: an operand the device computed through an MFMA accumulation is carried as two
 // bf16 terms (hi + lo), laid side by side along the reduction index, with the other operand
@@ -39,6 +40,17 @@ enum { EPI_BIAS_ACT = 0, EPI_PLAIN = 1, EPI_SPLIT = 2 };
 #define DN_DW_FUSE_TERMS 0
 #endif
 constexpr bool DW_FUSE = DN_DW_FUSE_TERMS != 0;
+// The 128 x 128 weight-gradient tile takes its operand tiles from global memory straight into LDS
+// (mainloop_tn_direct) with this many LDS buffers of DN_TN_DIRECT_ROWS reduction rows; 0: through registers
+// (mainloop_tn).  Measured per launch at the 111M- / 122M-node workloads, through registers 24.7 / 75.0 us:
+// 2 x 64 rows 21.8 / 63.0 (two workgroups per compute unit), 3 x 64 29.4 / 73.4 and 4 x 64 30.7 / 75.6 (one
+// workgroup per compute unit), 4 x 32 rows 23.8 / 67.6, 3 x 32 rows 26.1 / 64.7.
+#ifndef DN_TN_DIRECT_BUFFERS
+#define DN_TN_DIRECT_BUFFERS 2
+#endif
+#ifndef DN_TN_DIRECT_ROWS
+#define DN_TN_DIRECT_ROWS 64
+#endif
 #ifndef DN_NT_STAGES
 #define DN_NT_STAGES 2
 #endif
@@ -131,6 +143,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const int bx, const
         // split's rows of dZ, which are its share of the bias gradient.
         f32x16 ones_acc[NJ];
         const bool do_ones = by == 0 && wm == 0 && a.db_partial != nullptr;
+        if constexpr (BM_ == 128 && BN_ == 128 && !DW_FUSE && DN_TN_DIRECT_BUFFERS > 0)
+            mainloop_tn_direct<true, DN_TN_DIRECT_BUFFERS, DN_TN_DIRECT_ROWS>(a.A, a.lda, a.a_cols, Bbase, a.ldb, a.b_cols, row0, col0, kc_begin, kc_end,
+                                                           rows_layer, acc, ones_acc, do_ones);
+        else
         mainloop_tn<BM_, BN_, true, DW_FUSE, TN_STAGES>(a.A, a.lda, a.a_cols, Bbase, a.ldb, a.b_cols, DW_FUSE ? a.terms : 1, a.b_term_stride,
                                              row0, col0, kc_begin, kc_end, rows_layer, acc, ones_acc, do_ones);
         if (do_ones && lane < 32) {                           // register 0 of lanes 0..31: row 0 of the 32 x 32 tile
@@ -459,12 +475,16 @@ int gemm_tile_edge()
     static const int edge = tile_from_env("DN_GEMM_TILE", 64);
     return edge;
 }
-// workgroups the weight-gradient GEMM of one layer aims for when it splits the reduction (one per compute unit:
-// LDS for two dZ terms leaves room for one workgroup); DN_DW_BLOCKS in the environment overrides, read once
-int dw_target_blocks()
+// Workgroups the weight-gradient GEMM of one layer aims for when it splits the reduction.  A layer of few output
+// tiles (8 at 256 x 256 weights) gets one workgroup per compute unit: every further split is another 64 KB partial
+// tile per output tile to write and to read back, more than the shorter loops save (111M-node workload: 21.8 us at
+// 256, 29.8 at 384).  A layer of many output tiles (48 at 1536 x 256) has long reductions per split and gains from
+// a second workgroup on half of the compute units (122M-node workload: 63.0 us at 288 workgroups, 57.1 at 336,
+// 52.2 at 384, 58.9 at 432, 54.1 at 480).  DN_DW_BLOCKS in the environment overrides both, read once.
+int dw_target_blocks(int tiles)
 {
-    static const int n = [] { const char* e = getenv("DN_DW_BLOCKS"); const int v = e ? atoi(e) : 0; return v > 0 ? v : 256; }();
-    return n;
+    static const int n = [] { const char* e = getenv("DN_DW_BLOCKS"); const int v = e ? atoi(e) : 0; return v > 0 ? v : 0; }();
+    return n > 0 ? n : (tiles >= 32 ? 384 : 256);
 }
 // DN_DW_MIN_CHUNKS in the environment overrides the fewest k-steps per split (default 8), read once
 int dw_min_chunks()
@@ -558,7 +578,7 @@ int dn_gemm_dw_all(const dn_model* m, const dn_batch* b, float* const* dws, floa
         int64_t chunks_cap = (L.rows_cap + BK - 1) / BK;
         // enough workgroups to fill the chip, no more: every split costs a partial tile to write and re-read
         const int tiles = ((L.kx + T - 1) / T) * ((L.d_out + T - 1) / T) * (DW_FUSE ? 1 : L.zterms);
-        int splits = ((T == 64 ? 2048 : dw_target_blocks()) + tiles - 1) / tiles;
+        int splits = ((T == 64 ? 2048 : dw_target_blocks(tiles)) + tiles - 1) / tiles;
         if (splits > m->splits) splits = m->splits;
         if (splits > chunks_cap) splits = (int)(chunks_cap > 0 ? chunks_cap : 1);
         if (splits < 1) splits = 1;
@@ -594,7 +614,15 @@ int dn_gemm_dw_all(const dn_model* m, const dn_batch* b, float* const* dws, floa
     R.begin[m->k] = red_blocks;
     { dn_prof_scope ps("gemm_dw_all", 0, st);
     if (T == 64) hipLaunchKernelGGL((k_gemm_dw_group<64, 64>), dim3((unsigned)blocks), dim3(TPB), 0, st, G);
-    else hipLaunchKernelGGL((k_gemm_dw_group<128, 128>), dim3((unsigned)blocks), dim3(TPB), 0, st, G);
+    else {
+        constexpr unsigned direct_lds = (DN_TN_DIRECT_BUFFERS > 0 && !DW_FUSE) ? DN_TN_DIRECT_BUFFERS * 2u * DN_TN_DIRECT_ROWS * 128u * 2u : 0u;
+        if (direct_lds > 65536u) {                              // more dynamic LDS than a kernel gets without asking
+            static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_dw_group<128, 128>),
+                                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)direct_lds);
+            if (attr != hipSuccess) return dn_fail(DN_EHIP, "hipFuncSetAttribute(dynamic LDS of the weight-gradient GEMM)");
+        }
+        hipLaunchKernelGGL((k_gemm_dw_group<128, 128>), dim3((unsigned)blocks), dim3(TPB), direct_lds, st, G);
+    }
     }
     DN_LAUNCH_CHECK("k_gemm_dw_group");
     { dn_prof_scope ps("bwd_reduce_all", 0, st);

@@ -9,6 +9,7 @@
 // barrier per k-step.  Tile loads carry no bounds check: operands are padded to whole tiles.
 //
 //   mainloop_tn  the same contraction for operands whose ROW index is the reduction index (see there).
+//   mainloop_tn_direct  mainloop_tn for 128 x 128 tiles with the tiles loaded from global memory straight into LDS.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -336,6 +337,200 @@ __device__ __forceinline__ void mainloop_tn(const uint16_t* __restrict__ A, cons
         stage(r[1], 1, true);
     }
     if ((kc_end - kc_begin) & 1) stage(r[0], 0, false);
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// mainloop_tn for 128 x 128 tiles with the operand tiles sent from global memory straight into LDS
+// (global_load_lds_dwordx4: a wave's 64 lanes fill 1 KB of LDS in lane order, no registers and no LDS store
+// instruction in between; in mainloop_tn the stores of a tile and the wait for its registers are a third of the
+// k-step).  The loads are inline assembly on purpose: told about them, the compiler waits for ALL outstanding ones in
+// front of every LDS read; here the loop counts them (8 per wave and pair of 64-row tiles) and waits for its own tiles only.
+//
+// LDS image of a tile: BKD (64 or 32) reduction rows of 256 bytes, no padding; the 16-byte chunk c of row r sits at chunk
+// position c ^ 4 (r & 3), so that the four reduction rows a group of 16 lanes reads (64 bytes each) fall into four
+// different quarters of the 64 banks.  The permutation is applied on the global side: the lane that fills chunk
+// position p of row r fetches chunk p ^ 4 (r & 3) of that row.
+// NB buffers: the next NB - 1 tile pairs are in flight while one is multiplied; one barrier per tile pair.
+// The last tile of the reduction, if only part of its rows exist, goes through registers (rows past the end
+// become zeros).  Columns past a_cols / b_cols repeat the last 8 columns: they only reach output rows / columns
+// that the caller does not store.
+// (M0, which carries the LDS address, is no register the compiler allocates; it sets M0 itself right in front of
+// any instruction of its own that reads it.)
+__device__ __forceinline__ void load_to_lds16(const void* gsrc, const uint32_t lds_wave_base)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gsrc), "s"(lds_wave_base) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_direct_loads()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
+template <bool ONES, int NB, int BKD = BK>
+__device__ __forceinline__ void mainloop_tn_direct(const uint16_t* __restrict__ A, const int64_t lda, const int a_cols,
+                                                   const uint16_t* __restrict__ B, const int64_t ldb, const int b_cols,
+                                                   const int m0, const int n0, const int kc_begin, const int kc_end,
+                                                   const int k_rows, f32x16 (&acc)[2][2],
+                                                   f32x16* ones_acc = nullptr, const bool do_ones = false)
+{
+    constexpr int T = 128, MI = 2, NJ = 2;
+    constexpr int CH = T / 8;                            // 16-byte chunks per reduction row
+    constexpr int TILE_BYTES = BKD * T * 2;              // 16 KB with 64 reduction rows per tile, 8 KB with 32
+    constexpr int BUF_BYTES = 2 * TILE_BYTES;            // A tile, then B tile
+    constexpr int D = NB - 1;                            // k-steps of prefetch
+    constexpr int LJ = BKD / 16;                         // direct loads per wave, operand and tile (16 rows per round of the 4 waves)
+    constexpr int LOADS = 2 * LJ;                        // per wave and tile pair
+    constexpr int SUB = BK / BKD;                        // tiles per k-step of the caller's count
+    static_assert(BKD == 32 || BKD == 64, "rows per tile");
+    static_assert(NB >= 2 && NB <= 4 && D * LOADS < 64, "outstanding loads must fit the wait counter");
+    // The buffers are the kernel's dynamic LDS (NB * 32 KB, set at launch): with a static array of that size the
+    // compiler knows that one workgroup fills a compute unit, hands the wave all 512 registers and then moves the
+    // accumulators between the two register files in every k-step (seen in the generated code).
+    extern __shared__ __attribute__((aligned(1024))) uint8_t S[];
+    typedef __attribute__((address_space(3))) uint8_t* lds_bytes;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    if (ONES) {
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) ones_acc[j][e] = 0.f;
+    }
+    const s16x8 one_bits = {0x3F80, 0x3F80, 0x3F80, 0x3F80, 0x3F80, 0x3F80, 0x3F80, 0x3F80};     // bf16 1.0
+    const bf16x8 one8 = __builtin_bit_cast(bf16x8, one_bits);
+    if (kc_begin >= kc_end) return;
+
+    const uint32_t s_base = (uint32_t)(uintptr_t)(lds_bytes)S;
+    // direct loads: instruction j of wave w fills the rows 4 q .. 4 q + 3 of a tile, q = 4 j + w; lane L fills chunk
+    // position L & 15 of row 4 q + (L >> 4) and therefore fetches chunk (L & 15) ^ 4 (L >> 4) of it
+    const int rowl = lane >> 4, chunk = (lane & 15) ^ (4 * rowl);
+    const uint16_t* a_src = A + (int64_t)(4 * wave + rowl) * lda + min(m0 + chunk * 8, a_cols - 8);
+    const uint16_t* b_src = B + (int64_t)(4 * wave + rowl) * ldb + min(n0 + chunk * 8, b_cols - 8);
+    const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(s_base + 1024u * (uint32_t)wave);
+    const int h_begin = kc_begin * SUB, h_end = min(kc_end * SUB, (k_rows + BKD - 1) / BKD);   // tiles of BKD rows
+    const int h_full_end = min(h_end, k_rows / BKD);     // tiles whose rows all exist
+    auto issue = [&](int h, int buf) {                   // h: a tile with all rows (the caller clamps)
+        const uint16_t* pa = a_src + (int64_t)h * BKD * lda;
+        const uint16_t* pb = b_src + (int64_t)h * BKD * ldb;
+#pragma unroll
+        for (int j = 0; j < LJ; ++j) load_to_lds16(pa + (int64_t)(16 * j) * lda, wave_lds + buf * BUF_BYTES + 4096 * j);
+#pragma unroll
+        for (int j = 0; j < LJ; ++j) load_to_lds16(pb + (int64_t)(16 * j) * ldb, wave_lds + buf * BUF_BYTES + TILE_BYTES + 4096 * j);
+    };
+
+    // fragment reads (see mainloop_tn): this lane's reduction row and 8-byte piece inside a 32-column fragment
+    const int g = lane >> 4, r16 = lane & 15;
+    const int frag_k = 8 * (g >> 1) + (r16 >> 2);        // + 4 for the second read
+    const int frag_c = 16 * (g & 1) + 4 * (r16 & 3);     // column inside the fragment, a multiple of 4
+    const int x4 = 4 * (frag_k & 3);                     // this lane's rows all have the same r & 3
+    uint32_t a_off[MI], b_off[NJ];                       // byte offsets inside a buffer for reduction row frag_k
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+        const int col = wm * 64 + i * 32 + frag_c;
+        a_off[i] = frag_k * (T * 2) + (((col >> 3) ^ x4) << 4) + ((col & 7) << 1);
+    }
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        const int col = wn * 64 + j * 32 + frag_c;
+        b_off[j] = TILE_BYTES + frag_k * (T * 2) + (((col >> 3) ^ x4) << 4) + ((col & 7) << 1);
+    }
+    auto read_frag = [&](lds_bytes p, int ks) -> bf16x8 {
+        typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + ks * 16 * (T * 2)));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + ks * 16 * (T * 2) + 4 * (T * 2)));
+        const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        return __builtin_bit_cast(bf16x8, v);
+    };
+    auto multiply_steps = [&](int buf, auto with_ones) {
+        constexpr bool WITH_ONES = decltype(with_ones)::value;
+        constexpr int KS = BKD / 16;
+        constexpr int READS = 2 * (MI + NJ);
+        constexpr int MMAS = MI * NJ + (WITH_ONES ? NJ : 0);
+        lds_bytes pa[MI], pb[NJ];
+#pragma unroll
+        for (int i = 0; i < MI; ++i) pa[i] = (lds_bytes)S + buf * BUF_BYTES + a_off[i];
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) pb[j] = (lds_bytes)S + buf * BUF_BYTES + b_off[j];
+        bf16x8 fa[2][MI], fb[2][NJ];
+        auto fetch = [&](int set, int ks) {
+#pragma unroll
+            for (int i = 0; i < MI; ++i) fa[set][i] = read_frag(pa[i], ks);
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) fb[set][j] = read_frag(pb[j], ks);
+        };
+        fetch(0, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, READS, 0);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int set = ks & 1;
+            if (ks + 1 < KS) fetch(set ^ 1, ks + 1);
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
+            if (WITH_ONES) {
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+                    ones_acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(one8, fb[set][j], ones_acc[j], 0, 0, 0);
+            }
+            if (ks + 1 < KS) __builtin_amdgcn_sched_group_barrier(0x100, READS, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, MMAS, 0);
+        }
+    };
+    auto multiply = [&](int buf) {
+        if (ONES && do_ones) multiply_steps(buf, std::true_type{});
+        else multiply_steps(buf, std::false_type{});
+    };
+
+    const int n_full = h_full_end - h_begin;             // may be <= 0: the split is the partial tile alone
+    if (n_full > 0) {
+#pragma unroll
+        for (int s = 0; s < D; ++s) issue(min(h_begin + s, h_full_end - 1), s);
+        int buf = 0, pre = D;                            // buffer of this tile, buffer the prefetch goes to
+        for (int k = 0; k < n_full; ++k) {
+            wait_direct_loads<(D - 1) * LOADS>();        // this tile pair is in LDS (this wave's part)
+            __syncthreads();                             // everybody's part; and buffer `pre` has been read by all
+            __builtin_amdgcn_sched_barrier(0);
+            issue(min(h_begin + k + D, h_full_end - 1), pre);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(buf);
+            __builtin_amdgcn_sched_barrier(0);
+            buf = buf + 1 == NB ? 0 : buf + 1;
+            pre = pre + 1 == NB ? 0 : pre + 1;
+        }
+        wait_direct_loads<0>();                          // the surplus prefetches: nothing may land after this point
+    }
+    if (h_end > h_full_end) {
+        // the partial tile: through registers into buffer 0, rows past the end as zeros
+        const int k0 = h_full_end * BKD;
+        u32x4 ra[LJ], rb[LJ];
+#pragma unroll
+        for (int j = 0; j < LJ; ++j) {
+            const int row = 16 * j + 4 * wave + rowl;
+            ra[j] = *reinterpret_cast<const u32x4*>(a_src + ((int64_t)min(k0 + row, k_rows - 1) - (4 * wave + rowl)) * lda);
+            rb[j] = *reinterpret_cast<const u32x4*>(b_src + ((int64_t)min(k0 + row, k_rows - 1) - (4 * wave + rowl)) * ldb);
+        }
+        __syncthreads();                                 // all waves are done with buffer 0 and with their direct loads
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int j = 0; j < LJ; ++j) {
+            const int row = 16 * j + 4 * wave + rowl;
+            const bool ok = k0 + row < k_rows;
+            u32x4* dst_a = reinterpret_cast<u32x4*>(S + row * (T * 2) + (lane & 15) * 16);
+            u32x4* dst_b = reinterpret_cast<u32x4*>(S + TILE_BYTES + row * (T * 2) + (lane & 15) * 16);
+            *dst_a = ok ? ra[j] : zero;
+            *dst_b = ok ? rb[j] : zero;
+        }
+        __syncthreads();
+        multiply(0);
+    }
 }
 
 }  // namespace dn_mma

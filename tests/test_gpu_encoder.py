@@ -122,6 +122,15 @@ def test_shapes_with_bias_and_input_gradient(g16k, fanouts, dims):
     check(errs)
 
 
+@pytest.mark.parametrize("n_targets", [1, 63, 64, 65, 127, 128, 129, 1087, 1088, 1089])
+def test_weight_gradient_row_counts_around_the_reduction_tiles(g16k, n_targets):
+    """The weight gradient reduces over a layer's rows in tiles of 64 that go from memory straight into LDS; a last
+    tile with fewer rows takes another way (through registers, zeros past the end).  The last layer has exactly
+    n_targets rows: none, one or several whole tiles, with and without a partial one, in one and in two splits."""
+    errs, _ = run_case(g16k, [3], [40, 24], n_targets, seed=11)
+    check(errs)
+
+
 @pytest.mark.parametrize("dims", [[32, 64, 48, 10], [20, 36, 33, 7]])
 def test_rows_read_by_hundreds_of_slots(dims):
     """A star inside a ring: every node points at node 0 and at two ring neighbours, and the fanout takes all three.
