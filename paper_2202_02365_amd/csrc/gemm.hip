@@ -51,6 +51,13 @@ constexpr bool DW_FUSE = DN_DW_FUSE_TERMS != 0;
 #ifndef DN_TN_DIRECT_ROWS
 #define DN_TN_DIRECT_ROWS 64
 #endif
+// The forward GEMM of a layer with a long reduction (NT_DIRECT_MIN_K columns of X or more) runs on 128 x 128 tiles
+// whose operand tiles go from global memory straight into LDS (mainloop_direct), NT_DIRECT_BUFFERS LDS buffers.
+#ifndef DN_NT_DIRECT_BUFFERS
+#define DN_NT_DIRECT_BUFFERS 2
+#endif
+constexpr int NT_DIRECT_BUFFERS = DN_NT_DIRECT_BUFFERS;
+constexpr int NT_DIRECT_MIN_K = 1024;
 #ifndef DN_NT_STAGES
 #define DN_NT_STAGES 2
 #endif
@@ -93,7 +100,7 @@ __device__ __forceinline__ int effective_splits(int groups, int chunks, int min_
 }
 
 // One BM_ x BN_ output tile (one reduction split for EPI_SPLIT): block coordinates (bx, by, bz of nz).
-template <int EPI, int BM_, int BN_>
+template <int EPI, int BM_, int BN_, bool DIRECT = false>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const int bx, const int by, const int bz, const int nz)
 {
     constexpr int MI = BM_ / 64, NJ = BN_ / 64;
@@ -156,7 +163,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const int bx, const
                 if (n < a.ncols) a.db_partial[(int64_t)bz * a.ncols + n] = ones_acc[j][0];
             }
         }
-    } else
+    } else if constexpr (DIRECT)
+        mainloop_direct<BM_, BN_, NT_DIRECT_BUFFERS>(a.A + (int64_t)row0 * a.lda, a.lda, Bbase + (int64_t)col0 * a.ldb, a.ldb, kc_begin, kc_end, acc);
+    else
         mainloop<BM_, BN_, false, NT_STAGES>(a.A + (int64_t)row0 * a.lda, a.lda, Bbase + (int64_t)col0 * a.ldb, a.ldb, kc_begin, kc_end, 0, acc);
 
     // epilogue: lane holds column (lane & 31); register e holds row 8*(e/4) + 4*(lane/32) + e%4
@@ -246,7 +255,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, const int bx, const
 // (the capacity of rows is several times what a mini-batch fills, and a grid sized by it consists mostly of workgroups
 // that find no rows and leave: at 1 us each they delayed the end of a 15 us kernel by a third).
 constexpr int GEMM_MAX_ROW_BLOCKS = 512;
-template <int EPI, int LAYER_TAG, int BM_, int BN_>
+template <int EPI, int LAYER_TAG, int BM_, int BN_, bool DIRECT = false>
 __global__ __launch_bounds__(TPB, (BM_ == 64 && BN_ == 64) ? 4 : 2) void k_gemm_nt(GemmArgs a)
 {
     const int nx = gridDim.x;
@@ -254,7 +263,7 @@ __global__ __launch_bounds__(TPB, (BM_ == 64 && BN_ == 64) ? 4 : 2) void k_gemm_
     const int chunk = id / (8 * nx), j = id - chunk * 8 * nx;
     const int M = a.m_const >= 0 ? a.m_const : a.hdr[HDR_N] - a.hdr[HDR_NODE_OFF + a.layer];
     for (int by = chunk * 8 + (j & 7); by * BM_ < M; by += gridDim.y) {
-        gemm_tile<EPI, BM_, BN_>(a, j >> 3, by, blockIdx.z, gridDim.z);
+        gemm_tile<EPI, BM_, BN_, DIRECT>(a, j >> 3, by, blockIdx.z, gridDim.z);
         __syncthreads();                  // the tile's LDS buffers are free for the next one
     }
 }
@@ -519,10 +528,50 @@ int launch_t(const GemmArgs& a, int64_t m_cap, int splits, hipStream_t st)
     return DN_OK;
 }
 
+// forward GEMM, 128 x 128 tiles loaded straight into LDS
+int launch_direct(const GemmArgs& a, int64_t m_cap, hipStream_t st)
+{
+    constexpr int T = 128;
+    constexpr unsigned lds = NT_DIRECT_BUFFERS * 2u * T * BK * 2u;
+    dim3 grid((unsigned)((a.ncols + T - 1) / T), (unsigned)dn_round_up((m_cap + T - 1) / T, 8), 1u);
+    if (grid.y == 0) grid.y = 8;
+    if (grid.y > (unsigned)GEMM_MAX_ROW_BLOCKS) grid.y = GEMM_MAX_ROW_BLOCKS;
+    if (lds > 65536u) {                                         // more dynamic LDS than a kernel gets without asking
+        static const hipError_t attr = [] {
+            hipError_t e = hipSuccess;
+            const void* fns[4] = {reinterpret_cast<const void*>(&k_gemm_nt<EPI_BIAS_ACT, 1, T, T, true>),
+                                  reinterpret_cast<const void*>(&k_gemm_nt<EPI_BIAS_ACT, 2, T, T, true>),
+                                  reinterpret_cast<const void*>(&k_gemm_nt<EPI_BIAS_ACT, 3, T, T, true>),
+                                  reinterpret_cast<const void*>(&k_gemm_nt<EPI_BIAS_ACT, 4, T, T, true>)};
+            for (const void* f : fns) {
+                const hipError_t r = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                if (r != hipSuccess) e = r;
+            }
+            return e;
+        }();
+        if (attr != hipSuccess) return dn_fail(DN_EHIP, "hipFuncSetAttribute(dynamic LDS of the forward GEMM)");
+    }
+    switch (a.layer) {
+        case 1: hipLaunchKernelGGL((k_gemm_nt<EPI_BIAS_ACT, 1, T, T, true>), grid, dim3(TPB), lds, st, a); break;
+        case 2: hipLaunchKernelGGL((k_gemm_nt<EPI_BIAS_ACT, 2, T, T, true>), grid, dim3(TPB), lds, st, a); break;
+        case 3: hipLaunchKernelGGL((k_gemm_nt<EPI_BIAS_ACT, 3, T, T, true>), grid, dim3(TPB), lds, st, a); break;
+        default: hipLaunchKernelGGL((k_gemm_nt<EPI_BIAS_ACT, 4, T, T, true>), grid, dim3(TPB), lds, st, a); break;
+    }
+    DN_LAUNCH_CHECK("k_gemm_nt (direct)");
+    return DN_OK;
+}
+// DN_GEMM_DIRECT=0 in the environment keeps every forward GEMM on the register path, read once
+bool nt_direct_enabled()
+{
+    static const bool on = [] { const char* e = getenv("DN_GEMM_DIRECT"); return !(e && atoi(e) == 0); }();
+    return on;
+}
+
 template <int EPI>
 int launch(const GemmArgs& a, int64_t m_cap, int splits, hipStream_t st, const char* tag)
 {
     dn_prof_scope ps(tag, a.layer, st);
+    if (EPI == EPI_BIAS_ACT && a.red_const >= NT_DIRECT_MIN_K && splits == 1 && nt_direct_enabled()) return launch_direct(a, m_cap, st);
     return gemm_tile_edge() == 64 ? launch_t<EPI, 64>(a, m_cap, splits, st) : launch_t<EPI, 128>(a, m_cap, splits, st);
 }
 

@@ -533,4 +533,96 @@ __device__ __forceinline__ void mainloop_tn_direct(const uint16_t* __restrict__ 
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// mainloop with the operand tiles loaded from global memory straight into LDS (see mainloop_tn_direct for the
+// instruction and why it is inline assembly).  The LDS image is mainloop's: 16-byte chunk c of tile row r at
+// slot(r, c); a wave's load fills 8 consecutive rows, so the lane that fills chunk position p of row r fetches
+// chunk p ^ ((r >> 1) & 7) of that row.  NB buffers in the kernel's dynamic LDS (NB * (BM_ + BN_) * 128 bytes),
+// NB - 1 k-steps of tiles in flight, one barrier per k-step.  For long reductions: with few k-steps the two
+// register stages of mainloop, which start two tiles at once, are ahead.
+template <int BM_, int BN_, int NB>
+__device__ __forceinline__ void mainloop_direct(const uint16_t* __restrict__ A_tile, const int64_t lda,
+                                                const uint16_t* __restrict__ B_tile, const int64_t ldb,
+                                                const int kc_begin, const int kc_end, f32x16 (&acc)[BM_ / 64][BN_ / 64])
+{
+    constexpr int MI = BM_ / 64, NJ = BN_ / 64;
+    constexpr int A_BYTES = BM_ * BK * 2, B_BYTES = BN_ * BK * 2, BUF_BYTES = A_BYTES + B_BYTES;
+    constexpr int JA = BM_ / 32, JB = BN_ / 32;          // direct loads per wave and k-step: 32 tile rows per round of the 4 waves
+    constexpr int LOADS = JA + JB, D = NB - 1;
+    static_assert(NB >= 2 && NB <= 4 && D * LOADS < 64, "outstanding loads must fit the wait counter");
+    extern __shared__ __attribute__((aligned(1024))) uint8_t S[];
+    typedef __attribute__((address_space(3))) uint8_t* lds_bytes;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    if (kc_begin >= kc_end) return;
+
+    // this lane's row inside a round of 32 rows, and the chunk it fetches for chunk position lane & 7
+    // ((row >> 1) & 7 of row 32 j + 8 wave + (lane >> 3) does not depend on j)
+    const int r8 = lane >> 3;
+    const int swz = (4 * (wave & 1) + (r8 >> 1)) & 7;
+    const int chunk = (lane & 7) ^ swz;
+    const uint16_t* a_src = A_tile + (int64_t)(8 * wave + r8) * lda + chunk * 8;
+    const uint16_t* b_src = B_tile + (int64_t)(8 * wave + r8) * ldb + chunk * 8;
+    const uint32_t s_base = (uint32_t)(uintptr_t)(lds_bytes)S;
+    const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(s_base + 1024u * (uint32_t)wave);
+    auto issue = [&](int kc, int buf) {
+        const uint16_t* pa = a_src + (int64_t)kc * BK;
+        const uint16_t* pb = b_src + (int64_t)kc * BK;
+#pragma unroll
+        for (int j = 0; j < JA; ++j) load_to_lds16(pa + (int64_t)(32 * j) * lda, wave_lds + buf * BUF_BYTES + 4096 * j);
+#pragma unroll
+        for (int j = 0; j < JB; ++j) load_to_lds16(pb + (int64_t)(32 * j) * ldb, wave_lds + buf * BUF_BYTES + A_BYTES + 4096 * j);
+    };
+    constexpr int KG = (MI * NJ == 1) ? 4 : 2;
+    auto multiply = [&](int buf) {
+        const u32x4* As = reinterpret_cast<const u32x4*>(S + buf * BUF_BYTES);
+        const u32x4* Bs = reinterpret_cast<const u32x4*>(S + buf * BUF_BYTES + A_BYTES);
+#pragma unroll
+        for (int k0 = 0; k0 < BK / 16; k0 += KG) {
+            bf16x8 fa[KG][MI], fb[KG][NJ];
+#pragma unroll
+            for (int kk = 0; kk < KG; ++kk) {
+                const int c = 2 * (k0 + kk) + (lane >> 5);
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+                    fa[kk][i] = __builtin_bit_cast(bf16x8, As[slot(wm * (BM_ / 2) + i * 32 + (lane & 31), c)]);
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+                    fb[kk][j] = __builtin_bit_cast(bf16x8, Bs[slot(wn * (BN_ / 2) + j * 32 + (lane & 31), c)]);
+            }
+#pragma unroll
+            for (int kk = 0; kk < KG; ++kk)
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk][i], fb[kk][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, KG * (MI + NJ), 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, KG * MI * NJ, 0);
+        }
+    };
+    const int n_steps = kc_end - kc_begin;
+#pragma unroll
+    for (int s = 0; s < D; ++s) issue(min(kc_begin + s, kc_end - 1), s);
+    int buf = 0, pre = D;
+    for (int k = 0; k < n_steps; ++k) {
+        wait_direct_loads<(D - 1) * LOADS>();            // this k-step's tiles are in LDS (this wave's part)
+        __syncthreads();                                 // everybody's part; and buffer `pre` has been read by all
+        __builtin_amdgcn_sched_barrier(0);
+        issue(min(kc_begin + k + D, kc_end - 1), pre);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(buf);
+        __builtin_amdgcn_sched_barrier(0);
+        buf = buf + 1 == NB ? 0 : buf + 1;
+        pre = pre + 1 == NB ? 0 : pre + 1;
+    }
+    wait_direct_loads<0>();                              // the surplus prefetches: nothing may land after this point
+}
+
 }  // namespace dn_mma

@@ -131,6 +131,14 @@ def test_weight_gradient_row_counts_around_the_reduction_tiles(g16k, n_targets):
     check(errs)
 
 
+@pytest.mark.parametrize("fanouts,dims,n_targets", [([3], [512, 40], 200), ([2, 2], [640, 200, 24], 300), ([4], [768, 256], 1)])
+def test_forward_gemm_with_a_long_reduction(g16k, fanouts, dims, n_targets):
+    """Layers whose X has 1024 columns or more take the forward GEMM that loads 128 x 128 operand tiles from memory
+    straight into LDS: output widths below and above one tile, row counts that end inside a tile, a single row."""
+    errs, _ = run_case(g16k, fanouts, dims, n_targets, seed=13, want_dh0=True)
+    check(errs)
+
+
 @pytest.mark.parametrize("dims", [[32, 64, 48, 10], [20, 36, 33, 7]])
 def test_rows_read_by_hundreds_of_slots(dims):
     """A star inside a ring: every node points at node 0 and at two ring neighbours, and the fanout takes all three.
