@@ -448,8 +448,9 @@ __global__ __launch_bounds__(TPB) void k_fresh_emit(GraphDev g, int64_t words0, 
 // Workgroup b publishes pack(nodes, slots) of its id range with bit 63 set in blk[b] (one 64-bit atomic exchange at
 // device scope: value and "it is there" in one word, so no fence is needed), then adds up blk[0 .. b), waiting for
 // the words that are still zero (the sampling kernel in front of this one cleared them).  Every workgroup publishes
-// BEFORE it waits and waits only for workgroups with a smaller number, which the dispatcher starts first: workgroup 0
-// waits for nobody, and by induction every wait ends.  As a second line of defence a wait gives up after ND_SPIN_MAX
+// BEFORE it waits and waits only for workgroups with a smaller number; the host launches this kernel only where all
+// of them are running by then (next_delta_fused below): workgroup 0 waits for nobody, and by induction every wait
+// ends.  As a second line of defence a wait gives up after ND_SPIN_MAX
 // looks (far beyond the few microseconds the kernel runs): the workgroup then raises ST_INTERNAL, which
 // dn_batch_counts reports, emits nothing and leaves, so the kernel ends whatever the hardware does.
 constexpr unsigned long long ND_VALID = 1ull << 63;
@@ -556,11 +557,31 @@ __global__ __launch_bounds__(TPB) void k_next_delta(GraphDev g, int64_t words0, 
     }
 }
 
-// DN_NEXT_DELTA_TWO_PASS=1 in the environment (read once) keeps the two-kernel form (count, then emit)
-static bool next_delta_fused()
+// Which form computeNextDelta takes.  In the one-launch form a workgroup waits for the workgroups with smaller
+// numbers.  The eight XCDs work through their shares of a grid (every eighth workgroup) independently of each other,
+// so a workgroup can be running while one with a smaller number, in another XCD's share, still waits for a free slot;
+// if every slot it could get were held by waiting workgroups of several such kernels, none of them would ever leave
+// (the bounded wait would then end the kernel with ST_INTERNAL and an unfinished level).  That cannot happen while all
+// workgroups of all such kernels in flight fit the chip at once, XCD by XCD: each then holds a slot of its own and
+// waits only for workgroups that run.  A compute unit holds 8 workgroups of 256 threads; a process has as many
+// kernels in flight as it has hardware queues (GPU_MAX_HW_QUEUES in the environment, 4 if it is not set: the
+// runtime's default).  The one-launch form is therefore used only where
+//     queues x ceil(workgroups / 8)  <=  8 x compute units / 8,
+// which holds for graphs up to 134M nodes on 256 compute units with the default 4 queues (424 and 466 workgroups at
+// the 111M- and 122M-node workloads); otherwise, or with DN_NEXT_DELTA_TWO_PASS=1 in the environment, two kernels
+// (count, then emit), in which no workgroup waits for another.  All of it is read once per process.
+static bool next_delta_fused(int grid_words)
 {
-    static const bool on = [] { const char* e = getenv("DN_NEXT_DELTA_TWO_PASS"); return !(e && e[0] == '1'); }();
-    return on;
+    static const bool forced_two_pass = [] { const char* e = getenv("DN_NEXT_DELTA_TWO_PASS"); return e && e[0] == '1'; }();
+    static const int queues = [] { const char* e = getenv("GPU_MAX_HW_QUEUES"); const int v = e ? atoi(e) : 0; return v > 0 ? v : 4; }();
+    static const int slots_per_xcd = [] {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+        return cus;                                              // 8 workgroups per compute unit, 8 XCDs
+    }();
+    if (forced_two_pass) return false;
+    return (int64_t)queues * ((grid_words + 7) / 8) <= (int64_t)slots_per_xcd;
 }
 
 // ---------------------------------------------------------------- final layout + repr_map
@@ -647,7 +668,7 @@ int dn_launch_sample_edges(dn_batch* b, const dn_graph* g, const int32_t* d_src,
     if (grid > 2048) grid = 2048;
     if (grid < 1) grid = 1;
     const int grid_words = (int)((((b->words0 + ((int64_t)1 << b->walk_shift) - 1) >> b->walk_shift) + TPB - 1) / TPB);
-    const bool fused_nd = next_delta_fused();
+    const bool fused_nd = next_delta_fused(grid_words);
     unsigned long long* blk_u = reinterpret_cast<unsigned long long*>(b->blk_a);
     { dn_prof_scope ps("mark_ids", 0, st);
     hipLaunchKernelGGL(k_mark_ids, dim3(grid), dim3(TPB), 0, st, b->V, d_src, n_edges, d_dst, n_edges, d_neg, n_neg, b->hdr,
@@ -718,7 +739,7 @@ static int launch_hops_and_assemble(dn_batch* b, const GraphDev& gd, int64_t lev
     uint64_t* blk = reinterpret_cast<uint64_t*>(b->blk_a);
     const uint32_t key0 = (uint32_t)(seed & 0xffffffffu), key1 = (uint32_t)(seed >> 32);
     const int grid_words = (int)((((b->words0 + ((int64_t)1 << b->walk_shift) - 1) >> b->walk_shift) + TPB - 1) / TPB);
-    const bool fused_nd = next_delta_fused();
+    const bool fused_nd = next_delta_fused(grid_words);
     int64_t level_bound = level0_bound;                     // upper bound of the level size, known on the host
     for (int h = 0; h < k; ++h) {
         const int f = b->fanouts[h];
