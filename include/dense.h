@@ -184,8 +184,11 @@ DN_API int  dn_batch_view(const dn_batch* b, dn_dense_view* view);
 /* Copies node_id_offsets[0..k+1] followed by E (k+3 values) to host_counts and WAITS for `stream`.
  * Returns DN_ESAMPLE if the last dense_sample saw an invalid target set.
  * DN_ESTATE is also returned if a workgroup of the next-Delta kernel ever gave up its (bounded) wait for the totals of the
- * workgroups in front of it: the sample is then incomplete (never observed; the bound exists so that the kernel ends
- * whatever happens).
+ * workgroups in front of it: the sample is then incomplete, and the batch object must not be sampled into again (its
+ * bitmaps are no longer clean).  The library launches that kernel only where every workgroup of every such kernel the
+ * process can have in flight is resident at once (hardware queues of the process, GPU_MAX_HW_QUEUES or 4, times the
+ * workgroups per XCD within the chip's slots), where no wait can starve, and uses two kernels without waits
+ * otherwise; the bound exists so that the kernel ends whatever happens.
  * The batch object remembers the largest slot counts read back so far: the transpose-index build of sage_backward /
  * dn_batch_prepare_backward takes its one-kernel form for a batch object whose mini-batches have stayed below a few
  * ten thousand slots and the multi-pass sort otherwise or when no size was ever read back (both forms are correct for
