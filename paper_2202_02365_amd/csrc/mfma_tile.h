@@ -164,8 +164,10 @@ __device__ __forceinline__ void mainloop(const uint16_t* __restrict__ A_tile, co
 // lane l receives column l % 4 of rows l / 4, l / 4 + 4, l / 4 + 8, l / 4 + 12 (layout established by a probe that
 // reads a known pattern).  With lane r = 4 e + q pointing at [reduction row k_e][4 q-th .. of 16 consecutive
 // columns], lane l of the group gets column l of those 16 at the reduction rows k_0 .. k_3: two such reads give a
-// lane its 8 reduction values.  LDS rows are padded by 32 bytes so that the 4 reduction rows a group touches fall
-// into disjoint banks.  Rows >= k_rows and columns >= a_cols / b_cols are read as zero (no padding assumed).
+// lane its 8 reduction values.  LDS rows are padded by 32 bytes so that the 4 reduction rows a group touches start
+// in different banks (the pieces of neighbouring rows still overlap: the hardware counter reads a third of the LDS
+// cycles as bank conflicts; the chunk permutation of mainloop_tn_direct below has none).  Rows >= k_rows and
+// columns >= a_cols / b_cols are read as zero (no padding assumed).
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
