@@ -563,7 +563,8 @@ __global__ __launch_bounds__(TPB) void k_next_delta(GraphDev g, int64_t words0, 
 // if every slot it could get were held by waiting workgroups of several such kernels, none of them would ever leave
 // (the bounded wait would then end the kernel with ST_INTERNAL and an unfinished level).  That cannot happen while all
 // workgroups of all such kernels in flight fit the chip at once, XCD by XCD: each then holds a slot of its own and
-// waits only for workgroups that run.  A compute unit holds 8 workgroups of 256 threads; a process has as many
+// waits only for workgroups that run.  A compute unit holds 8 workgroups of 256 threads (the kernel needs 35 vector
+// registers and 40 bytes of LDS: eight waves per SIMD); a process has as many
 // kernels in flight as it has hardware queues (GPU_MAX_HW_QUEUES in the environment, 4 if it is not set: the
 // runtime's default).  The one-launch form is therefore used only where
 //     queues x ceil(workgroups / 8)  <=  8 x compute units / 8,
